@@ -1,0 +1,237 @@
+"""Pins for oracle/codes.py and oracle/coding.py: Def. 1 by brute force, Def. 2,
+Alg. 1's first layer, the fractional-repetition worked case, and the coding
+invariant decode == sum of partial gradients for every straggler set."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import codes, coding, gradients as og
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _masks(n, max_s):
+    for s in range(max_s + 1):
+        for out in itertools.combinations(range(n), s):
+            m = np.zeros(n, np.uint8)
+            m[list(out)] = 1
+            yield m
+
+
+@pytest.mark.parametrize("n,layers", [(6, [0, 1, 2, 3]), (8, [0, 1, 2, 3]), (8, [0, 1, 3, 7]),
+                                      (7, [0, 2, 5])])
+def test_cyclic_nested_code_satisfies_def1_and_def2(n, layers):
+    Bs = codes.nested_code(n, layers, "cyclic", seed=3, draws=4)
+    assert np.array_equal(Bs[0], np.eye(n))                       # Alg. 1: B_0 = I
+    prev = None
+    for B, sigma in zip(Bs, layers):
+        supp = [set(np.flatnonzero(B[i])) for i in range(n)]
+        for i in range(n):
+            assert supp[i] == set(codes.cyclic_support(n, sigma, i))   # Lemma 2, size sigma+1
+            assert len(supp[i]) == sigma + 1                           # load (k/n)(sigma+1)
+            if prev is not None:
+                assert prev[i] <= supp[i]                              # Def. 2 nesting
+        prev = supp
+        # Def. 1: any n-sigma rows span an (n-sigma)-dim space containing 1
+        for out in itertools.combinations(range(n), sigma):
+            S = [i for i in range(n) if i not in out]
+            assert np.linalg.matrix_rank(B[S]) == n - sigma
+            assert np.linalg.matrix_rank(np.vstack([B[S], np.ones(n)])) == n - sigma
+        # every straggler set of size <= sigma decodes: a B = 1, supp(a) in responders
+        for m in _masks(n, sigma):
+            a, resid = coding.decode_vector(B, m)
+            assert resid < 1e-9
+            assert np.all(a[m == 1] == 0.0)
+            assert np.allclose(a @ B, 1.0, atol=1e-9)
+
+
+def test_decoding_matrix_rows_times_B_is_all_ones():
+    B = codes.nested_code(7, [0, 2], seed=1, draws=2)[1]
+    A = codes.decoding_matrix(B, 2)
+    assert A.shape == (21, 7)
+    assert np.allclose(A @ B, 1.0, atol=1e-9)                       # Def. 1: A B = 1
+    assert np.all((A != 0).sum(axis=1) <= 5)
+
+
+def test_min_norm_equals_unique_solution_when_exactly_n_minus_sigma_respond():
+    n, sigma = 9, 3
+    B = codes.nested_code(n, [0, sigma], seed=5, draws=2)[1]
+    for out in itertools.combinations(range(n), sigma):
+        m = np.zeros(n, np.uint8)
+        m[list(out)] = 1
+        S = np.flatnonzero(m == 0)
+        a, _ = coding.decode_vector(B, m)
+        # independent route: normal equations of the consistent system B_S^T x = 1
+        x = np.linalg.solve(B[S] @ B[S].T, B[S] @ np.ones(n))
+        assert np.allclose(a[S], x, rtol=1e-6, atol=1e-8)
+        a1, r1 = coding.decode_vector_first(B, sigma, m)
+        assert np.allclose(a1, a, rtol=1e-6, atol=1e-8) and r1 < 1e-9
+
+
+def test_first_responders_rule_is_supported_on_lowest_indices():
+    n, sigma = 8, 3
+    B = codes.nested_code(n, [0, sigma], seed=2, draws=2)[1]
+    m = np.zeros(n, np.uint8)
+    m[2] = 1                                  # one straggler, tolerance 3: 7 respond, 5 are used
+    a, r = coding.decode_vector_first(B, sigma, m)
+    assert r < 1e-9
+    assert set(np.flatnonzero(a)) <= {0, 1, 3, 4, 5}
+
+
+def test_fracrep_worked_case_matches_golden():
+    Bs = codes.nested_code(4, [0, 1], "fracrep")
+    assert np.array_equal(Bs[1], np.array([[1, 1, 0, 0], [1, 1, 0, 0],
+                                           [0, 0, 1, 1], [0, 0, 1, 1.0]]))
+    seen = 0
+    with open(os.path.join(GOLD, "fracrep_n4.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            tok = line.split()
+            mask = np.array([int(c) for c in tok[0]], np.uint8)
+            u = coding.select_layer([0, 1], mask)
+            assert u == int(tok[1])
+            a, r = coding.decode_vector(Bs[u], mask)
+            assert np.allclose(a, [float(t) for t in tok[2:6]], atol=1e-12) and r < 1e-12
+            seen += 1
+    assert seen == 5
+
+
+def test_fracrep_weights_are_one_over_responders_in_block():
+    n, sigma = 12, 3
+    B = codes.fracrep_code(n, sigma)
+    rng = np.random.default_rng(0)
+    for _ in range(50):
+        m = np.zeros(n, np.uint8)
+        m[rng.choice(n, size=rng.integers(0, sigma + 1), replace=False)] = 1
+        a, r = coding.decode_vector(B, m)
+        for i in range(n):
+            blk = codes.fracrep_support(n, sigma, i)
+            alive = sum(1 for j in blk if m[j] == 0)
+            assert np.isclose(a[i], 0.0 if m[i] else 1.0 / alive, atol=1e-12)
+
+
+def test_fracrep_nesting_rule():
+    codes.nested_code(8, [0, 1, 3, 7], "fracrep")
+    with pytest.raises(ValueError):
+        codes.nested_code(20, [0, 1, 4], "fracrep")       # 2 does not divide 5
+
+
+def test_select_layer_table():
+    layers = [0, 1, 3, 7]
+    expect = {0: 0, 1: 1, 2: 2, 3: 2, 4: 3, 5: 3, 6: 3, 7: 3}
+    for s in range(17):
+        m = np.zeros(16, np.uint8)
+        m[:s] = 1
+        if s in expect:
+            assert coding.select_layer(layers, m) == expect[s]
+        else:
+            with pytest.raises(coding.Undecodable):
+                coding.select_layer(layers, m)
+
+
+def _c1_like(n=4, rows=16, d=5, seed=0):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((n, rows, d))
+    th_star = rng.standard_normal(d)
+    Y = X @ th_star + 0.01 * rng.standard_normal((n, rows))
+    return X, Y, rng.standard_normal(d)
+
+
+def test_decode_equals_sum_of_partial_gradients_for_all_16_subsets_of_n4():
+    X, Y, th = _c1_like()
+    G = og.partial_gradients(0, X, Y, th)
+    full = og.lsq_gradient(X.reshape(-1, 5), Y.reshape(-1), th)
+    layers = [0, 1]
+    for kind in ("fracrep", "cyclic"):
+        Bs = codes.nested_code(4, layers, kind, seed=0, draws=2)
+        ok = bad = 0
+        for bits in range(16):
+            m = np.array([(bits >> i) & 1 for i in range(4)], np.uint8)
+            try:
+                u, a, g = coding.coded_gradient(Bs, layers, G, m)
+            except coding.Undecodable:
+                bad += 1
+                continue
+            ok += 1
+            assert np.all(a[m == 1] == 0)
+            assert np.allclose(g, full, rtol=1e-10, atol=1e-10)
+        assert (ok, bad) == (5, 11)
+
+
+def test_layer_zero_without_stragglers_is_plain_row_sum():
+    G = np.random.default_rng(1).standard_normal((6, 11))
+    Bs = codes.nested_code(6, [0, 2], seed=0, draws=2)
+    u, a, g = coding.coded_gradient(Bs, [0, 2], G, np.zeros(6, np.uint8))
+    assert u == 0 and np.array_equal(a, np.ones(6))
+    assert np.allclose(g, G.sum(axis=0), rtol=1e-14)
+    assert np.array_equal(coding.encode(Bs[0], G), G)
+
+
+def test_decode_is_the_same_from_every_sufficient_layer():
+    n, layers = 8, [0, 1, 3]
+    G = np.random.default_rng(2).standard_normal((n, 13))
+    Bs = codes.nested_code(n, layers, seed=4, draws=2)
+    m = np.zeros(n, np.uint8)
+    m[5] = 1
+    outs = []
+    for u in (1, 2):
+        a, r = coding.decode_vector(Bs[u], m)
+        outs.append(coding.decode(a, coding.encode(Bs[u], G)))
+    assert np.allclose(outs[0], outs[1], rtol=1e-9, atol=1e-9)
+    assert np.allclose(outs[0], G.sum(axis=0), rtol=1e-9, atol=1e-9)
+
+
+def test_encode_row_is_the_sparse_combination_written_out():
+    n, sigma = 7, 2
+    B = codes.nested_code(n, [0, sigma], seed=9, draws=2)[1]
+    G = np.random.default_rng(3).standard_normal((n, 4))
+    C = coding.encode(B, G)
+    for i in range(n):
+        acc = np.zeros(4)
+        for j in codes.cyclic_support(n, sigma, i):
+            acc += B[i, j] * G[j]
+        assert np.allclose(C[i], acc, rtol=1e-13, atol=1e-13)
+    assert coding.encode_layers([np.eye(n), B], G).shape == (2, n, 4)
+
+
+def test_coded_descent_follows_uncoded_descent_whatever_the_stragglers():
+    """Exact recovery (Sec. I): the trajectory does not depend on who straggles,
+    and converges to the least-squares solution."""
+    n, layers = 4, [0, 1]
+    X, Y, _ = _c1_like(rows=32)
+    m_total = n * 32
+    Bs = codes.nested_code(n, layers, "cyclic", seed=0, draws=2)
+    rng = np.random.default_rng(11)
+    th_c = np.zeros(5)
+    th_u = np.zeros(5)
+    for it in range(300):
+        mask = np.zeros(n, np.uint8)
+        if rng.random() < 0.7:
+            mask[rng.integers(n)] = 1
+        G = og.partial_gradients(0, X, Y, th_c)
+        _, _, g = coding.coded_gradient(Bs, layers, G, mask)
+        th_c = og.gd_update(th_c, g, 0.5, m_total)
+        th_u = og.gd_update(th_u, og.lsq_gradient(X.reshape(-1, 5), Y.reshape(-1), th_u),
+                            0.5, m_total)
+    assert np.allclose(th_c, th_u, rtol=1e-9, atol=1e-10)
+    th_ls = np.linalg.lstsq(X.reshape(-1, 5), Y.reshape(-1), rcond=None)[0]
+    assert np.allclose(th_c, th_ls, rtol=1e-6, atol=1e-8)
+
+
+def test_fp32_messages_stay_within_the_forward_error_bound():
+    n, layers = 16, [0, 1, 3, 7]
+    G = np.random.default_rng(5).standard_normal((n, 64))
+    Bs = codes.nested_code(n, layers, seed=0, draws=4)
+    rng = np.random.default_rng(6)
+    for _ in range(30):
+        m = (rng.random(n) < 0.2).astype(np.uint8)
+        if m.sum() > 7:
+            continue
+        u, a, g32 = coding.coded_gradient(Bs, layers, G, m, np.float32)
+        full = G.sum(axis=0)
+        kap = coding.conditioning(a, coding.encode(Bs[u], G), full)
+        err = np.linalg.norm(g32 - full) / np.linalg.norm(full)
+        assert err <= 2.0 ** -24 * kap * 4
