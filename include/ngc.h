@@ -1,0 +1,189 @@
+/*
+ * libngc -- nested gradient coding (NGC) on one AMD Instinct MI355X (gfx950).
+ *
+ * One GPU plays all n workers of the coded distributed gradient descent of
+ * Sec. II-C: the data matrix is split into k = n row blocks, block j yields the
+ * partial gradient g_j, worker i sends the linear combination
+ * c_i = sum_j B_sigma[i][j] g_j under the component code sigma chosen for this
+ * iteration (Sec. III, Defs. 1-2), and the main node recovers the full gradient
+ * sum_j g_j = sum_{i in responders} a_i c_i with a decode vector a that
+ * satisfies a B_sigma = 1 and vanishes at the stragglers.
+ *
+ * Conventions
+ *  - Every call returns NGC_OK (0) or a negative NGC_ERR_* code; nothing
+ *    throws or aborts.  ngc_strerror() names a code, ngc_last_error() gives the
+ *    detail of the last failure on a context.
+ *  - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary
+ *    host memory.  The caller owns every buffer passed in; the library neither
+ *    frees nor keeps them beyond the stream work of the call.  The context owns
+ *    only its private workspace (block partials, uploaded code tables).
+ *  - Device work is enqueued on the HIP stream given to ngc_create() and is
+ *    asynchronous; outputs are fully overwritten, never accumulated into.
+ *  - ngc_create, ngc_set_code, ngc_build_code, ngc_get_code,
+ *    ngc_select_decode_vec, ngc_destroy, ngc_strerror touch no device state and
+ *    work on a machine without a GPU.
+ *  - All matrices are row-major and dense unless stated otherwise.  Device data
+ *    is fp32; code matrices and decode vectors are fp64 on the host.
+ *  - Calls on one context must not overlap in time from several host threads.
+ */
+#ifndef NGC_H
+#define NGC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ngc_ctx ngc_ctx;
+
+enum {
+    NGC_OK = 0,
+    NGC_ERR_INVALID = -1,     /* bad shape, null pointer, layer out of range, k != n        */
+    NGC_ERR_UNDECODABLE = -2, /* more stragglers than the largest tolerance s_{L-1}          */
+    NGC_ERR_SINGULAR = -3,    /* no a with |a^T B_S - 1| below tolerance (B violates Def. 1) */
+    NGC_ERR_HIP = -4,         /* a HIP runtime call failed                                   */
+    NGC_ERR_NOMEM = -5,       /* host or device allocation failed                            */
+    NGC_ERR_STATE = -6        /* call needs something not yet set (a code layer, MLP shape)  */
+};
+
+enum { NGC_LOSS_LSQ = 0, NGC_LOSS_LOGISTIC = 1, NGC_LOSS_MLP2 = 2 };
+enum { NGC_CODE_CYCLIC = 0, NGC_CODE_FRACREP = 1 };
+
+/* Kernel ids for ngc_profile_read(). */
+enum {
+    NGC_KERNEL_GRAD = 0,    /* single-pass partition-gradient kernel (or the two generic passes) */
+    NGC_KERNEL_REDUCE = 1,  /* fixed-order sum of block partials                             */
+    NGC_KERNEL_ENCODE = 2,
+    NGC_KERNEL_DECODE = 3,
+    NGC_KERNEL_UPDATE = 4,
+    NGC_KERNEL_MLP = 5,     /* all GEMM-shaped kernels of the MLP gradient                  */
+    NGC_KERNEL_COUNT = 6
+};
+
+/*
+ * Create a context for n workers, k partitions and L nested layers
+ * (Sec. III, Def. 2).  s[0..L-1] are the straggler tolerances of the layers,
+ * strictly ascending with s[0] == 0 and s[L-1] < n; they may be a subset of
+ * 0..s_max (a subset of component codes of a nested code is nested).  d is the
+ * gradient length (the paper's l).  k must equal n (Sec. II-C takes k = n),
+ * 1 <= n <= 64.  hip_stream is a hipStream_t (NULL = the default stream); it
+ * must outlive the context.  Layer 0 is preset to B_0 = I (Alg. 1); the other
+ * layers must be given by ngc_set_code() or ngc_build_code() before use.
+ * No HIP call is made here.
+ */
+int ngc_create(ngc_ctx** out, int n, int k, int L, const int* s, int64_t d, void* hip_stream);
+
+/* Release the context and its workspace.  NULL is allowed. */
+void ngc_destroy(ngc_ctx* ctx);
+
+/*
+ * Install the encoding matrix B_sigma of one layer (Def. 1): B_host is n x k
+ * fp64 row-major with zeros outside each row's support.  Rejected with
+ * NGC_ERR_INVALID if a row is empty, if worker i does not hold partition i
+ * (needed for nesting with B_0 = I), or if a row's support does not contain
+ * the support of the same row in the layer below (Def. 2, second bullet;
+ * checked against layers already set).  The values are copied.
+ */
+int ngc_set_code(ngc_ctx* ctx, int layer, const double* B_host);
+
+/* Copy the layer's B (n x k fp64 row-major) to B_host_out. */
+int ngc_get_code(const ngc_ctx* ctx, int layer, double* B_host_out);
+
+/*
+ * Build all layers (Alg. 1).  NGC_CODE_CYCLIC: row i of the layer with
+ * tolerance sigma is supported on columns {i..i+sigma} mod n (Lemma 2, with the
+ * window length sigma+1 that matches the load (k/n)(sigma+1) of Sec. II-C) and
+ * lies in the null space of a random sigma x n matrix whose rows sum to zero,
+ * so any n-sigma rows span a space containing the all-ones vector (Def. 1);
+ * out of several random draws the one that magnifies message rounding least is
+ * kept.  NGC_CODE_FRACREP: all-ones rows on blocks of sigma+1 consecutive
+ * partitions; needs (s[u]+1) | n and (s[u]+1) | (s[u+1]+1).  Random numbers
+ * come from a counter-based generator keyed by seed; the same seed gives the
+ * same code on every machine.
+ */
+int ngc_build_code(ngc_ctx* ctx, int kind, uint64_t seed);
+
+/* Shape of the 2-layer perceptron for NGC_LOSS_MLP2: theta is the concatenation
+ * [W1 (d_in x hidden) | b1 (hidden) | W2 (hidden x classes) | b2 (classes)] and
+ * its length must equal the context's d. */
+int ngc_set_mlp2_shape(ngc_ctx* ctx, int d_in, int hidden, int classes);
+
+/*
+ * Partial gradients of all k row blocks at theta (Sec. II-C):
+ *   G[j] = sum over the rows of block j of grad_theta L(y, f(x, theta)),
+ * a plain sum (the 1/m of the update rule, Sec. II-B eq. (1), is not applied).
+ *   NGC_LOSS_LSQ       L = (x.theta - y)^2 / 2;       y_dev: float [k][rows]
+ *   NGC_LOSS_LOGISTIC  L = log(1 + exp(-y x.theta));  y_dev: float +/-1 [k][rows]
+ *   NGC_LOSS_MLP2      softmax cross-entropy of relu(x W1 + b1) W2 + b2;
+ *                      y_dev: int32 class ids [k][rows]
+ * X_dev: float [k][rows_per_part][d_in] row-major (d_in = d for the first two
+ * losses), 16-byte aligned.  theta_dev: float [d].  G_dev: float [k][d], fully
+ * overwritten.  Each row of X is read from HBM exactly once when d is a
+ * multiple of 256 and at most 4096; other d take a two-pass route.
+ * Accumulation is fp32 with a fixed summation order (bit-reproducible).
+ */
+int ngc_partition_grads(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_dev,
+                        const float* theta_dev, int64_t rows_per_part, float* G_dev);
+
+/*
+ * Worker messages C = B G (Sec. II-C) layer by layer:
+ *   C[u][i][:] = sum_j B^(u)[i][j] G[j][:]   in fp32.
+ * G_dev: float [k][d].  C_dev: float [L][n][d].  layer = -1 encodes every
+ * layer in one pass over G; layer = u writes only slice u of C_dev.
+ */
+int ngc_encode(ngc_ctx* ctx, const float* G_dev, int layer, float* C_dev);
+
+/*
+ * Main-node bookkeeping for one iteration, on the host.
+ * straggler_mask[i] != 0 marks worker i as a straggler.  The layer chosen is
+ * the smallest u with s[u] >= number of stragglers (Observation after Def. 2);
+ * NGC_ERR_UNDECODABLE if there is none.  a_out[n] receives the least-2-norm
+ * solution of a^T B^(u) = 1^T with a_i = 0 at every straggler (a row of A_sigma
+ * in the sense of Def. 1: supported on responders, a B = 1; when exactly
+ * n - s[u] workers respond it is the only one).  residual_out (may be NULL)
+ * receives max_j |(a^T B)_j - 1|; above 1e-6 the call returns
+ * NGC_ERR_SINGULAR.  layer_out is written even when that happens.
+ */
+int ngc_select_decode_vec(const ngc_ctx* ctx, const uint8_t* straggler_mask, int* layer_out,
+                          double* a_out, double* residual_out);
+
+/*
+ * Same bookkeeping with the decode vector supported on the n - s[u]
+ * responders of lowest index only (a literal row of the decoding matrix of
+ * Def. 1).
+ */
+int ngc_select_decode_vec_first(const ngc_ctx* ctx, const uint8_t* straggler_mask,
+                                int* layer_out, double* a_out, double* residual_out);
+
+/*
+ * Main-node recovery (Def. 1, A B = 1):  g[:] = sum_i a[i] * C[layer][i][:]
+ * over the workers with a[i] != 0.  a_host: double [n] (read before the call
+ * returns).  C_dev: float [L][n][d] as written by ngc_encode.  g_dev: float [d].
+ * Products and the sum are formed in fp64 and rounded once to fp32.
+ */
+int ngc_decode(ngc_ctx* ctx, int layer, const double* a_host, const float* C_dev, float* g_dev);
+
+/* theta[:] -= scale * g[:]  with scale = eta/m  (Sec. II-B eq. (1)). */
+int ngc_update(ngc_ctx* ctx, float* theta_dev, const float* g_dev, double scale);
+
+/* Block until the context's stream is idle. */
+int ngc_sync(ngc_ctx* ctx);
+
+/*
+ * Per-kernel timing.  With profiling on, each kernel launch is bracketed by
+ * HIP events on the context's stream.  ngc_profile_read() synchronises, adds
+ * the elapsed times up per kernel id, writes launch counts and total
+ * milliseconds (arrays of NGC_KERNEL_COUNT) and clears the record.  At most
+ * 4096 launches are recorded between reads; later ones run untimed.
+ */
+int ngc_profile_enable(ngc_ctx* ctx, int on);
+int ngc_profile_read(ngc_ctx* ctx, int64_t* launches_out, double* total_ms_out);
+
+const char* ngc_strerror(int code);
+const char* ngc_last_error(const ngc_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NGC_H */

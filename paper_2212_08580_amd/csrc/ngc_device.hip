@@ -1,0 +1,728 @@
+// Device side of libngc for gfx950 (CDNA4, wave64): partition gradients,
+// layered encode, decode and the descent update, plus their launchers.
+//
+// Bandwidth picture (fp32 everywhere on the device):
+//  * partition gradients read every row of X from HBM exactly once; all other
+//    traffic (theta, labels, block partials, G) is below 2 % of that;
+//  * encode reads a column tile of G once into LDS and writes every layer's
+//    messages from it;
+//  * decode reads the responders' messages once.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+
+#include "ngc_internal.h"
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+
+#define NGC_HIP(ctx, call)                                                                  \
+    do {                                                                                    \
+        hipError_t e_ = (call);                                                             \
+        if (e_ != hipSuccess)                                                               \
+            return ngc_fail(ctx, NGC_ERR_HIP, std::string(#call) + ": " + hipGetErrorString(e_)); \
+    } while (0)
+
+// ---------------------------------------------------------------------------
+// wave-wide sum, result in every lane.  Four DPP steps give each row of 16
+// lanes its own sum; the four row sums are then added in a fixed order.
+// ---------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_step(float v) {
+    int iv = __builtin_bit_cast(int, v);
+    int sh = __builtin_amdgcn_update_dpp(iv, iv, CTRL, 0xF, 0xF, false);
+    return v + __builtin_bit_cast(float, sh);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+    v = dpp_step<0xB1>(v);   // quad_perm [1,0,3,2]
+    v = dpp_step<0x4E>(v);   // quad_perm [2,3,0,1]
+    v = dpp_step<0x141>(v);  // row_half_mirror
+    v = dpp_step<0x140>(v);  // row_mirror
+    int iv = __builtin_bit_cast(int, v);
+    float s0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 0));
+    float s1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 16));
+    float s2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32));
+    float s3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 48));
+    return (s0 + s1) + (s2 + s3);
+}
+
+// d/dz of the per-sample loss at margin z = x.theta (the factor of x in the gradient)
+template <int LOSS>
+__device__ __forceinline__ float loss_slope(float z, float y) {
+    if (LOSS == NGC_LOSS_LSQ) return z - y;
+    // logistic, labels +/-1:  -y / (1 + exp(y z)); exp overflow gives the correct limit 0
+    return -y / (1.0f + expf(y * z));
+}
+
+// ---------------------------------------------------------------------------
+// K1: single-pass partition gradient for d = WAVES * 256 * NV.
+// A block of WAVES waves owns a run of consecutive rows of one partition; wave w
+// owns columns [w*256*NV, (w+1)*256*NV) of every row.  A group of R rows sits in
+// registers (lane l holds float4 number i*64+l of the wave's slice, i < NV), so
+// the same registers feed the dot product x.theta and, once the residual is
+// known, the update acc += r*x: X is read from HBM exactly once.  While a group
+// is consumed the following NBUF-1 groups are already in flight.  The waves
+// exchange their partial dot products through LDS, one barrier per group; the
+// exchange area is double buffered so a fast wave cannot overwrite values a
+// slow wave still has to read.  theta and the accumulator stay in registers.
+// Each block writes one partial sum per partition run; K2 adds them in a fixed
+// order.
+// ---------------------------------------------------------------------------
+template <int NV, int R>
+struct row_group {
+    v4f x[R][NV];
+    float y;  // lane l < R holds the label of row l of the group
+};
+
+template <int NV, int R, int DV>
+__device__ __forceinline__ void load_group(row_group<NV, R>& b, const char* __restrict__ xbase,
+                                           const float* __restrict__ yp, uint32_t lane_off,
+                                           int lane, int64_t row, int64_t last_row) {
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+        int64_t r = row + rr;
+        r = r < last_row ? r : last_row;  // past the end: re-read the last row; its weight is 0
+        const char* p = xbase + r * (int64_t)(DV * 16);  // wave-uniform
+#pragma unroll
+        for (int i = 0; i < NV; ++i)
+            b.x[rr][i] = __builtin_nontemporal_load(
+                reinterpret_cast<const v4f*>(p + lane_off + i * 1024));
+    }
+    int64_t ry = row + (lane < R ? lane : R - 1);
+    ry = ry < last_row ? ry : last_row;
+    b.y = yp[ry];
+}
+
+template <int NV, int R, int WAVES, int LOSS>
+__device__ __forceinline__ void consume_group(const row_group<NV, R>& b, v4f (&acc)[NV],
+                                              const v4f (&th)[NV], float* ex, int wave,
+                                              int64_t row, int64_t end_row) {
+    float dot[R];
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+        v4f q = b.x[rr][0] * th[0];
+#pragma unroll
+        for (int i = 1; i < NV; ++i) q += b.x[rr][i] * th[i];
+        dot[rr] = wave_sum((q.x + q.y) + (q.z + q.w));
+    }
+    if (WAVES > 1) {
+        // ex[rr*WAVES + w]: every lane of wave w stores the same value
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) ex[rr * WAVES + wave] = dot[rr];
+        __syncthreads();
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) {
+            float z = ex[rr * WAVES];
+#pragma unroll
+            for (int w = 1; w < WAVES; ++w) z += ex[rr * WAVES + w];
+            dot[rr] = z;
+        }
+    }
+    const int yi = __builtin_bit_cast(int, b.y);
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+        float yv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(yi, rr));
+        float res = (row + rr < end_row) ? loss_slope<LOSS>(dot[rr], yv) : 0.0f;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) acc[i] += res * b.x[rr][i];
+    }
+}
+
+template <int NV, int R, int NBUF, int WAVES, int LOSS>
+__global__ __launch_bounds__(WAVES * 64) void grad_stream_kernel(
+    const float* __restrict__ X, const float* __restrict__ y, const float* __restrict__ theta,
+    float* __restrict__ partial, int64_t rows, int chunks, int64_t rows_per_chunk) {
+    constexpr int DV = WAVES * 64 * NV;  // float4 per row
+    __shared__ float ex_s[2][R * WAVES];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int j = blockIdx.x / chunks;
+    const int c = blockIdx.x % chunks;
+    const int64_t r0 = (int64_t)c * rows_per_chunk;
+    const int64_t r1 = rows < r0 + rows_per_chunk ? rows : r0 + rows_per_chunk;
+    const char* xbase = reinterpret_cast<const char*>(X) +
+                        ((int64_t)j * rows * DV + (int64_t)wave * 64 * NV) * 16;
+    const float* yp = y + (int64_t)j * rows;
+    const uint32_t lane_off = (uint32_t)lane * 16u;
+
+    v4f th[NV], acc[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        th[i] = reinterpret_cast<const v4f*>(theta)[wave * 64 * NV + i * 64 + lane];
+        acc[i] = (v4f)(0.0f);
+    }
+
+    // Groups are taken NBUF at a time with no branch inside the loop, so that the
+    // waits the compiler places before a group's first use cover only that
+    // group's loads and leave the younger ones in flight.  Groups past the end of
+    // the run re-read its last row (a cache hit) and get weight 0.
+    const int64_t ngroups = r0 < r1 ? (r1 - r0 + R - 1) / R : 0;  // block-uniform
+    if (ngroups > 0) {
+        const int64_t last = r1 - 1;
+        row_group<NV, R> buf[NBUF];
+#pragma unroll
+        for (int p = 0; p < NBUF - 1; ++p)
+            load_group<NV, R, DV>(buf[p], xbase, yp, lane_off, lane, r0 + (int64_t)p * R, last);
+        for (int64_t gb = 0; gb < ngroups; gb += NBUF) {
+#pragma unroll
+            for (int p = 0; p < NBUF; ++p) {
+                const int64_t gi = gb + p;
+                load_group<NV, R, DV>(buf[(p + NBUF - 1) % NBUF], xbase, yp, lane_off, lane,
+                                      r0 + (gi + NBUF - 1) * R, last);
+                consume_group<NV, R, WAVES, LOSS>(buf[p], acc, th, ex_s[gi & 1], wave, r0 + gi * R, r1);
+            }
+        }
+    }
+    v4f* out = reinterpret_cast<v4f*>(partial) + (int64_t)blockIdx.x * DV + wave * 64 * NV + lane;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) out[i * 64] = acc[i];
+}
+
+// ---------------------------------------------------------------------------
+// Generic two-pass route for any d.  Pass 1: one wave per row forms the margin
+// and stores the residual.  Pass 2: one thread per column adds r*x over a run
+// of rows; partials are summed by K2.
+// ---------------------------------------------------------------------------
+template <int LOSS>
+__global__ __launch_bounds__(256) void resid_kernel(const float* __restrict__ X,
+                                                    const float* __restrict__ y,
+                                                    const float* __restrict__ theta,
+                                                    float* __restrict__ resid, int64_t total_rows,
+                                                    int64_t d) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave0 = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t r = wave0; r < total_rows; r += nwaves) {
+        const float* xr = X + r * d;
+        float dot = 0.0f;
+        for (int64_t c = lane; c < d; c += 64) dot += xr[c] * theta[c];
+        float z = wave_sum(dot);
+        if (lane == 0) resid[r] = loss_slope<LOSS>(z, y[r]);
+    }
+}
+
+__global__ __launch_bounds__(256) void xtr_kernel(const float* __restrict__ X,
+                                                  const float* __restrict__ resid,
+                                                  float* __restrict__ partial, int64_t rows,
+                                                  int64_t d, int chunks, int64_t rows_per_chunk) {
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int chunk = blockIdx.y;
+    const int j = blockIdx.z;
+    if (c >= d) return;
+    const int64_t r0 = (int64_t)chunk * rows_per_chunk;
+    const int64_t r1 = rows < r0 + rows_per_chunk ? rows : r0 + rows_per_chunk;
+    const float* xp = X + ((int64_t)j * rows) * d + c;
+    const float* rp = resid + (int64_t)j * rows;
+    float acc = 0.0f;
+    for (int64_t r = r0; r < r1; ++r) acc += rp[r] * xp[r * d];
+    partial[((int64_t)j * chunks + chunk) * d + c] = acc;
+}
+
+// K2: G[j][:] = sum over chunks of partial[j][chunk][:], chunks added in index order.
+template <typename VT>
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const VT* __restrict__ partial,
+                                                              VT* __restrict__ G, int64_t dv,
+                                                              int chunks) {
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int j = blockIdx.y;
+    if (c >= dv) return;
+    const VT* p = partial + (int64_t)j * chunks * dv + c;
+    VT acc = p[0];
+    int t = 1;
+    for (; t + 4 <= chunks; t += 4) {
+        VT a0 = p[(int64_t)t * dv], a1 = p[(int64_t)(t + 1) * dv];
+        VT a2 = p[(int64_t)(t + 2) * dv], a3 = p[(int64_t)(t + 3) * dv];
+        acc = (((acc + a0) + a1) + a2) + a3;
+    }
+    for (; t < chunks; ++t) acc += p[(int64_t)t * dv];
+    G[(int64_t)j * dv + c] = acc;
+}
+
+// ---------------------------------------------------------------------------
+// K3: layered encode.  A block stages a tile of G (all n rows, 16*V columns) in
+// LDS, then writes the messages of its share of (layer, worker) pairs from
+// there: every pair is one sparse row of B^(u) in compressed form.
+// pair p = u*n + i is also the row index of C viewed as [L*n][d].
+// ---------------------------------------------------------------------------
+template <typename VT, int V>
+__global__ __launch_bounds__(256) void encode_kernel(const float* __restrict__ G,
+                                                     float* __restrict__ C,
+                                                     const int* __restrict__ rowptr,
+                                                     const int* __restrict__ col,
+                                                     const float* __restrict__ coef, int n,
+                                                     int64_t d, int pair_begin, int pair_end,
+                                                     int pairs_per_group) {
+    __shared__ VT tile[NGC_MAX_N * 16];
+    const int lane16 = threadIdx.x & 15;
+    const int slot = threadIdx.x >> 4;
+    const int64_t c = ((int64_t)blockIdx.x * 16 + lane16) * V;
+    const bool in = c < d;
+    for (int r = slot; r < n; r += 16) {
+        VT v = (VT)(0.0f);
+        if (in) v = *reinterpret_cast<const VT*>(G + (int64_t)r * d + c);
+        tile[r * 16 + lane16] = v;
+    }
+    __syncthreads();
+    const int p0 = pair_begin + blockIdx.y * pairs_per_group;
+    const int p1 = pair_end < p0 + pairs_per_group ? pair_end : p0 + pairs_per_group;
+    for (int p = p0 + slot; p < p1; p += 16) {
+        const int b = rowptr[p], e = rowptr[p + 1];
+        VT acc = (VT)(0.0f);
+        for (int t = b; t < e; ++t) acc += coef[t] * tile[col[t] * 16 + lane16];
+        if (in) *reinterpret_cast<VT*>(C + (int64_t)p * d + c) = acc;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// K4: decode.  g = sum_t a[t] * C[idx[t]][:], products and sum in fp64, one
+// rounding to fp32.  The four waves of a block take every fourth responder and
+// their partial sums are added in wave order.
+// ---------------------------------------------------------------------------
+struct decode_args {
+    double a[NGC_MAX_N];
+    int idx[NGC_MAX_N];
+    int count;
+};
+
+template <typename VT, int V>
+__global__ __launch_bounds__(256) void decode_kernel(const float* __restrict__ Cl,
+                                                     float* __restrict__ g, int64_t d,
+                                                     decode_args args) {
+    __shared__ double part[4][64][V];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int64_t c = ((int64_t)blockIdx.x * 64 + lane) * V;
+    double acc[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[v] = 0.0;
+    if (c < d) {
+        for (int t = wave; t < args.count; t += 4) {
+            VT m = *reinterpret_cast<const VT*>(Cl + (int64_t)args.idx[t] * d + c);
+            const double a = args.a[t];
+            if constexpr (V == 1) {
+                acc[0] += a * (double)m;
+            } else {
+#pragma unroll
+                for (int v = 0; v < V; ++v) acc[v] += a * (double)m[v];
+            }
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < V; ++v) part[wave][lane][v] = acc[v];
+    __syncthreads();
+    if (wave == 0 && c < d) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            double s = ((part[0][lane][v] + part[1][lane][v]) + part[2][lane][v]) + part[3][lane][v];
+            g[c + v] = (float)s;
+        }
+    }
+}
+
+// K6: theta -= scale * g
+__global__ __launch_bounds__(256) void update_kernel(float* __restrict__ theta,
+                                                     const float* __restrict__ g, float scale,
+                                                     int64_t d) {
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (c < d) theta[c] = theta[c] - scale * g[c];
+}
+
+// ===========================================================================
+// host-side launchers
+// ===========================================================================
+static int dev_init(ngc_ctx* ctx) {
+    if (ctx->dev_ready) return NGC_OK;
+    int dev = 0;
+    NGC_HIP(ctx, hipGetDevice(&dev));
+    hipDeviceProp_t prop;
+    NGC_HIP(ctx, hipGetDeviceProperties(&prop, dev));
+    ctx->cu_count = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    ctx->dev_ready = true;
+    return NGC_OK;
+}
+
+void ngc_dev_release(ngc_ctx* ctx) {
+    if (!ctx->dev_ready) return;
+    (void)hipStreamSynchronize(ctx->stream);
+    for (auto& r : ctx->prof) {
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    for (auto e : ctx->event_pool) (void)hipEventDestroy(e);
+    if (ctx->d_code) (void)hipFree(ctx->d_code);
+    if (ctx->d_ws) (void)hipFree(ctx->d_ws);
+    ctx->d_code = nullptr;
+    ctx->d_ws = nullptr;
+    ctx->dev_ready = false;
+}
+
+static int ensure_ws(ngc_ctx* ctx, size_t bytes) {
+    if (bytes <= ctx->d_ws_bytes) return NGC_OK;
+    if (ctx->d_ws) {
+        NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        NGC_HIP(ctx, hipFree(ctx->d_ws));
+        ctx->d_ws = nullptr;
+        ctx->d_ws_bytes = 0;
+    }
+    void* p = nullptr;
+    if (hipMalloc(&p, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return ngc_fail(ctx, NGC_ERR_NOMEM, "workspace allocation failed");
+    }
+    ctx->d_ws = (float*)p;
+    ctx->d_ws_bytes = bytes;
+    return NGC_OK;
+}
+
+namespace {
+struct prof_scope {
+    ngc_ctx* ctx;
+    int rec = -1;
+    prof_scope(ngc_ctx* c, int kernel) : ctx(c) {
+        if (!c->profiling || c->prof.size() >= (size_t)NGC_MAX_PROFILE) return;
+        ngc_profile_rec r;
+        r.kernel = kernel;
+        auto get = [&](hipEvent_t& e) {
+            if (!c->event_pool.empty()) {
+                e = c->event_pool.back();
+                c->event_pool.pop_back();
+                return true;
+            }
+            return hipEventCreate(&e) == hipSuccess;
+        };
+        if (!get(r.start)) return;
+        if (!get(r.stop)) {
+            c->event_pool.push_back(r.start);
+            return;
+        }
+        (void)hipEventRecord(r.start, c->stream);
+        c->prof.push_back(r);
+        rec = (int)c->prof.size() - 1;
+    }
+    ~prof_scope() {
+        if (rec >= 0) (void)hipEventRecord(ctx->prof[rec].stop, ctx->stream);
+    }
+};
+}  // namespace
+
+extern "C" int ngc_profile_enable(ngc_ctx* ctx, int on) {
+    if (!ctx) return NGC_ERR_INVALID;
+    ctx->profiling = on != 0;
+    return NGC_OK;
+}
+
+extern "C" int ngc_profile_read(ngc_ctx* ctx, int64_t* launches_out, double* total_ms_out) {
+    if (!ctx || !launches_out || !total_ms_out) return NGC_ERR_INVALID;
+    for (int i = 0; i < NGC_KERNEL_COUNT; ++i) {
+        launches_out[i] = 0;
+        total_ms_out[i] = 0.0;
+    }
+    if (ctx->prof.empty()) return NGC_OK;
+    NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    for (auto& r : ctx->prof) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
+            launches_out[r.kernel] += 1;
+            total_ms_out[r.kernel] += ms;
+        }
+        ctx->event_pool.push_back(r.start);
+        ctx->event_pool.push_back(r.stop);
+    }
+    ctx->prof.clear();
+    return NGC_OK;
+}
+
+extern "C" int ngc_sync(ngc_ctx* ctx) {
+    if (!ctx) return NGC_ERR_INVALID;
+    NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    return NGC_OK;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+// ---- partition gradients --------------------------------------------------
+template <int NV, int R, int NBUF, int WAVES>
+static void launch_stream(ngc_ctx* ctx, int loss, const float* X, const float* y,
+                          const float* theta, float* partial, int k, int64_t rows, int chunks,
+                          int64_t rpc) {
+    dim3 grid((unsigned)(k * chunks));
+    if (loss == NGC_LOSS_LSQ)
+        hipLaunchKernelGGL((grad_stream_kernel<NV, R, NBUF, WAVES, NGC_LOSS_LSQ>), grid, dim3(WAVES * 64), 0,
+                           ctx->stream, X, y, theta, partial, rows, chunks, rpc);
+    else
+        hipLaunchKernelGGL((grad_stream_kernel<NV, R, NBUF, WAVES, NGC_LOSS_LOGISTIC>), grid, dim3(WAVES * 64),
+                           0, ctx->stream, X, y, theta, partial, rows, chunks, rpc);
+}
+
+// Shape of the single-pass kernel for a given d, or waves = 0 if d has none.
+struct stream_shape {
+    int nv, r, waves;
+};
+static stream_shape pick_stream_shape(int64_t d) {
+    if (d % 1024 == 0) {
+        const int w = (int)(d / 1024);
+        if (w == 1 || w == 2 || w == 3 || w == 4 || w == 6 || w == 8) return {4, 4, w};
+        if (w == 12 || w == 16) return {8, 2, w / 2};
+    }
+    if (d == 256) return {1, 16, 1};
+    if (d == 512) return {2, 8, 1};
+    if (d == 768) return {3, 4, 1};
+    return {0, 0, 0};
+}
+
+int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float* theta,
+                   int64_t rows, float* G);  // ngc_mlp.hip
+
+extern "C" int ngc_partition_grads(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_dev,
+                                   const float* theta_dev, int64_t rows, float* G_dev) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (!X_dev || !y_dev || !theta_dev || !G_dev) return ngc_fail(ctx, NGC_ERR_INVALID, "null device pointer");
+    if (rows < 1) return ngc_fail(ctx, NGC_ERR_INVALID, "rows_per_part must be positive");
+    if (!aligned16(X_dev) || !aligned16(theta_dev) || !aligned16(G_dev))
+        return ngc_fail(ctx, NGC_ERR_INVALID, "X, theta and G must be 16-byte aligned");
+    int rc = dev_init(ctx);
+    if (rc) return rc;
+    if (loss == NGC_LOSS_MLP2) {
+        if (!ctx->mlp_din) return ngc_fail(ctx, NGC_ERR_STATE, "call ngc_set_mlp2_shape first");
+        return ngc_mlp2_grads(ctx, X_dev, (const int*)y_dev, theta_dev, rows, G_dev);
+    }
+    if (loss != NGC_LOSS_LSQ && loss != NGC_LOSS_LOGISTIC) return ngc_fail(ctx, NGC_ERR_INVALID, "unknown loss");
+    const int k = ctx->n;
+    const int64_t d = ctx->d;
+    const float* y = (const float*)y_dev;
+    const int64_t wave_slots = (int64_t)ctx->cu_count * 8;  // 2 waves per SIMD
+
+    const stream_shape sh = pick_stream_shape(d);
+    if (sh.waves) {
+        // enough blocks to give every SIMD two waves, split evenly over the partitions
+        const int64_t block_slots = std::max<int64_t>(1, wave_slots / sh.waves);
+        int64_t chunks = std::max<int64_t>(1, (block_slots + k - 1) / k);
+        int64_t rpc = (rows + chunks - 1) / chunks;
+        const int64_t quantum = 2 * sh.r;  // two row groups: one trip of the kernel's loop
+        rpc = ((rpc + quantum - 1) / quantum) * quantum;
+        chunks = (rows + rpc - 1) / rpc;
+        rc = ensure_ws(ctx, sizeof(float) * (size_t)k * chunks * d);
+        if (rc) return rc;
+        {
+            prof_scope ps(ctx, NGC_KERNEL_GRAD);
+#define NGC_STREAM_CASE(W) \
+    case W: launch_stream<4, 4, 2, W>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc); break;
+            if (sh.nv == 4) {
+                switch (sh.waves) {
+                    NGC_STREAM_CASE(1) NGC_STREAM_CASE(2) NGC_STREAM_CASE(3) NGC_STREAM_CASE(4)
+                    NGC_STREAM_CASE(6) NGC_STREAM_CASE(8)
+                }
+            } else if (sh.nv == 8 && sh.waves == 6) {
+                launch_stream<8, 2, 2, 6>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc);
+            } else if (sh.nv == 8) {
+                launch_stream<8, 2, 2, 8>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc);
+            } else if (sh.nv == 1) {
+                launch_stream<1, 16, 2, 1>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc);
+            } else if (sh.nv == 2) {
+                launch_stream<2, 8, 2, 1>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc);
+            } else {
+                launch_stream<3, 4, 2, 1>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc);
+            }
+#undef NGC_STREAM_CASE
+        }
+        NGC_HIP(ctx, hipGetLastError());
+        {
+            prof_scope ps(ctx, NGC_KERNEL_REDUCE);
+            const int64_t dv = d / 4;
+            dim3 grid((unsigned)((dv + 255) / 256), (unsigned)k);
+            hipLaunchKernelGGL((reduce_partials_kernel<v4f>), grid, dim3(256), 0, ctx->stream,
+                               (const v4f*)ctx->d_ws, (v4f*)G_dev, dv, (int)chunks);
+        }
+        NGC_HIP(ctx, hipGetLastError());
+        return NGC_OK;
+    }
+    // generic two-pass route
+    const int64_t total_rows = (int64_t)k * rows;
+    const int64_t col_blocks = (d + 255) / 256;
+    int64_t chunks = std::max<int64_t>(1, std::min<int64_t>(rows, (wave_slots / 4 + k * col_blocks - 1) / (k * col_blocks)));
+    chunks = std::min<int64_t>(chunks, 65535);
+    int64_t rpc = (rows + chunks - 1) / chunks;
+    chunks = (rows + rpc - 1) / rpc;
+    const size_t resid_floats = ((size_t)total_rows + 63) / 64 * 64;
+    rc = ensure_ws(ctx, sizeof(float) * (resid_floats + (size_t)k * chunks * d));
+    if (rc) return rc;
+    float* resid = ctx->d_ws;
+    float* partial = ctx->d_ws + resid_floats;
+    {
+        prof_scope ps(ctx, NGC_KERNEL_GRAD);
+        const int64_t blocks = std::min<int64_t>((total_rows + 3) / 4, (int64_t)ctx->cu_count * 8);
+        if (loss == NGC_LOSS_LSQ)
+            hipLaunchKernelGGL((resid_kernel<NGC_LOSS_LSQ>), dim3((unsigned)blocks), dim3(256), 0, ctx->stream,
+                               X_dev, y, theta_dev, resid, total_rows, d);
+        else
+            hipLaunchKernelGGL((resid_kernel<NGC_LOSS_LOGISTIC>), dim3((unsigned)blocks), dim3(256), 0,
+                               ctx->stream, X_dev, y, theta_dev, resid, total_rows, d);
+        NGC_HIP(ctx, hipGetLastError());
+        dim3 grid((unsigned)col_blocks, (unsigned)chunks, (unsigned)k);
+        hipLaunchKernelGGL(xtr_kernel, grid, dim3(256), 0, ctx->stream, X_dev, resid, partial, rows, d,
+                           (int)chunks, rpc);
+    }
+    NGC_HIP(ctx, hipGetLastError());
+    {
+        prof_scope ps(ctx, NGC_KERNEL_REDUCE);
+        dim3 grid((unsigned)((d + 255) / 256), (unsigned)k);
+        hipLaunchKernelGGL((reduce_partials_kernel<float>), grid, dim3(256), 0, ctx->stream,
+                           (const float*)partial, G_dev, d, (int)chunks);
+    }
+    NGC_HIP(ctx, hipGetLastError());
+    return NGC_OK;
+}
+
+// ---- code tables on the device --------------------------------------------
+// layout of d_code: int rowptr[L*n + 1] | int col[nnz] | float coef[nnz]
+static int upload_code(ngc_ctx* ctx) {
+    if (!ctx->code_dirty && ctx->d_code) return NGC_OK;
+    const int n = ctx->n, L = ctx->L;
+    for (int u = 0; u < L; ++u)
+        if (!ctx->code[u].set) return ngc_fail(ctx, NGC_ERR_STATE, "a layer has no code yet");
+    size_t nnz = 0;
+    for (int u = 0; u < L; ++u) nnz += ctx->code[u].col.size();
+    const size_t np = (size_t)L * n;
+    std::vector<int> host(np + 1 + 2 * nnz);
+    int* rowptr = host.data();
+    int* col = rowptr + np + 1;
+    float* coef = reinterpret_cast<float*>(col + nnz);
+    size_t at = 0;
+    for (int u = 0; u < L; ++u) {
+        const ngc_layer_code& lc = ctx->code[u];
+        for (int i = 0; i < n; ++i) {
+            rowptr[(size_t)u * n + i] = (int)at;
+            for (int t = lc.rowptr[i]; t < lc.rowptr[i + 1]; ++t) {
+                col[at] = lc.col[t];
+                coef[at] = (float)lc.coef[t];
+                ++at;
+            }
+        }
+    }
+    rowptr[np] = (int)at;
+    const size_t bytes = host.size() * sizeof(int);
+    NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (bytes > ctx->d_code_bytes) {
+        if (ctx->d_code) NGC_HIP(ctx, hipFree(ctx->d_code));
+        ctx->d_code = nullptr;
+        ctx->d_code_bytes = 0;
+        if (hipMalloc(&ctx->d_code, bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return ngc_fail(ctx, NGC_ERR_NOMEM, "code table allocation failed");
+        }
+        ctx->d_code_bytes = bytes;
+    }
+    NGC_HIP(ctx, hipMemcpy(ctx->d_code, host.data(), bytes, hipMemcpyHostToDevice));
+    ctx->code_nnz = nnz;
+    ctx->code_dirty = false;
+    return NGC_OK;
+}
+
+static int vec_width(int64_t d, const void* p0, const void* p1) {
+    auto al = [](const void* p, uintptr_t m) { return (reinterpret_cast<uintptr_t>(p) & (m - 1)) == 0; };
+    if (d % 4 == 0 && al(p0, 16) && al(p1, 16)) return 4;
+    if (d % 2 == 0 && al(p0, 8) && al(p1, 8)) return 2;
+    return 1;
+}
+
+extern "C" int ngc_encode(ngc_ctx* ctx, const float* G_dev, int layer, float* C_dev) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (!G_dev || !C_dev) return ngc_fail(ctx, NGC_ERR_INVALID, "null device pointer");
+    if (layer < -1 || layer >= ctx->L) return ngc_fail(ctx, NGC_ERR_INVALID, "layer out of range");
+    if ((reinterpret_cast<uintptr_t>(G_dev) | reinterpret_cast<uintptr_t>(C_dev)) & 3)
+        return ngc_fail(ctx, NGC_ERR_INVALID, "G and C must be 4-byte aligned");
+    int rc = dev_init(ctx);
+    if (rc) return rc;
+    rc = upload_code(ctx);
+    if (rc) return rc;
+    const int n = ctx->n;
+    const int64_t d = ctx->d;
+    const size_t np = (size_t)ctx->L * n;
+    const size_t nnz = ctx->code_nnz;
+    const int* rowptr = (const int*)ctx->d_code;
+    const int* col = rowptr + np + 1;
+    const float* coef = (const float*)(col + nnz);
+    const int pb = layer < 0 ? 0 : layer * n;
+    const int pe = layer < 0 ? (int)np : (layer + 1) * n;
+    const int V = vec_width(d, G_dev, C_dev);
+    const int64_t gx = (d + 16 * V - 1) / (16 * V);
+    const int pairs = pe - pb;
+    int64_t gy = std::max<int64_t>(1, (2 * (int64_t)ctx->cu_count + gx - 1) / gx);
+    gy = std::min<int64_t>(gy, (pairs + 15) / 16);
+    int ppg = (int)((pairs + gy - 1) / gy);
+    ppg = ((ppg + 15) / 16) * 16;
+    gy = (pairs + ppg - 1) / ppg;
+    if (gx > 0x7fffffffLL) return ngc_fail(ctx, NGC_ERR_INVALID, "d too large");
+    dim3 grid((unsigned)gx, (unsigned)gy);
+    {
+        prof_scope ps(ctx, NGC_KERNEL_ENCODE);
+        if (V == 4)
+            hipLaunchKernelGGL((encode_kernel<v4f, 4>), grid, dim3(256), 0, ctx->stream, G_dev, C_dev,
+                               rowptr, col, coef, n, d, pb, pe, ppg);
+        else if (V == 2)
+            hipLaunchKernelGGL((encode_kernel<v2f, 2>), grid, dim3(256), 0, ctx->stream, G_dev, C_dev,
+                               rowptr, col, coef, n, d, pb, pe, ppg);
+        else
+            hipLaunchKernelGGL((encode_kernel<float, 1>), grid, dim3(256), 0, ctx->stream, G_dev, C_dev,
+                               rowptr, col, coef, n, d, pb, pe, ppg);
+    }
+    NGC_HIP(ctx, hipGetLastError());
+    return NGC_OK;
+}
+
+extern "C" int ngc_decode(ngc_ctx* ctx, int layer, const double* a_host, const float* C_dev,
+                          float* g_dev) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (!a_host || !C_dev || !g_dev) return ngc_fail(ctx, NGC_ERR_INVALID, "null pointer");
+    if (layer < 0 || layer >= ctx->L) return ngc_fail(ctx, NGC_ERR_INVALID, "layer out of range");
+    int rc = dev_init(ctx);
+    if (rc) return rc;
+    const int n = ctx->n;
+    const int64_t d = ctx->d;
+    decode_args args;
+    args.count = 0;
+    for (int i = 0; i < n; ++i) {
+        if (!std::isfinite(a_host[i])) return ngc_fail(ctx, NGC_ERR_INVALID, "decode vector has a non-finite entry");
+        if (a_host[i] != 0.0) {
+            args.a[args.count] = a_host[i];
+            args.idx[args.count] = i;
+            ++args.count;
+        }
+    }
+    for (int t = args.count; t < NGC_MAX_N; ++t) {
+        args.a[t] = 0.0;
+        args.idx[t] = 0;
+    }
+    const float* Cl = C_dev + (size_t)layer * n * d;
+    const int V = vec_width(d, Cl, g_dev);
+    const int64_t gx = (d + 64 * V - 1) / (64 * V);
+    {
+        prof_scope ps(ctx, NGC_KERNEL_DECODE);
+        if (V == 4)
+            hipLaunchKernelGGL((decode_kernel<v4f, 4>), dim3((unsigned)gx), dim3(256), 0, ctx->stream, Cl, g_dev, d, args);
+        else if (V == 2)
+            hipLaunchKernelGGL((decode_kernel<v2f, 2>), dim3((unsigned)gx), dim3(256), 0, ctx->stream, Cl, g_dev, d, args);
+        else
+            hipLaunchKernelGGL((decode_kernel<float, 1>), dim3((unsigned)gx), dim3(256), 0, ctx->stream, Cl, g_dev, d, args);
+    }
+    NGC_HIP(ctx, hipGetLastError());
+    return NGC_OK;
+}
+
+extern "C" int ngc_update(ngc_ctx* ctx, float* theta_dev, const float* g_dev, double scale) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (!theta_dev || !g_dev) return ngc_fail(ctx, NGC_ERR_INVALID, "null device pointer");
+    int rc = dev_init(ctx);
+    if (rc) return rc;
+    {
+        prof_scope ps(ctx, NGC_KERNEL_UPDATE);
+        hipLaunchKernelGGL(update_kernel, dim3((unsigned)((ctx->d + 255) / 256)), dim3(256), 0, ctx->stream,
+                           theta_dev, g_dev, (float)scale, ctx->d);
+    }
+    NGC_HIP(ctx, hipGetLastError());
+    return NGC_OK;
+}

@@ -1,0 +1,332 @@
+// Host side of libngc: context life cycle, code tables (Sec. III, Defs. 1-2,
+// Alg. 1, Lemma 2), layer choice and decode-vector selection.  No HIP call is
+// made from this file.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "ngc_internal.h"
+
+int ngc_fail(const ngc_ctx* ctx, int code, const std::string& msg) {
+    if (ctx) ctx->err = msg;
+    return code;
+}
+
+extern "C" const char* ngc_strerror(int code) {
+    switch (code) {
+        case NGC_OK: return "ok";
+        case NGC_ERR_INVALID: return "invalid argument";
+        case NGC_ERR_UNDECODABLE: return "more stragglers than the code tolerates";
+        case NGC_ERR_SINGULAR: return "no decode vector: responders do not span the all-ones row";
+        case NGC_ERR_HIP: return "HIP runtime error";
+        case NGC_ERR_NOMEM: return "out of memory";
+        case NGC_ERR_STATE: return "context not ready for this call";
+        default: return "unknown error code";
+    }
+}
+
+extern "C" const char* ngc_last_error(const ngc_ctx* ctx) { return ctx ? ctx->err.c_str() : ""; }
+
+static void compress_layer(ngc_layer_code& lc, int n) {
+    lc.rowptr.assign(n + 1, 0);
+    lc.col.clear();
+    lc.coef.clear();
+    for (int i = 0; i < n; ++i) {
+        for (int j = 0; j < n; ++j) {
+            double v = lc.B[(size_t)i * n + j];
+            if (v != 0.0) {
+                lc.col.push_back(j);
+                lc.coef.push_back(v);
+            }
+        }
+        lc.rowptr[i + 1] = (int)lc.col.size();
+    }
+}
+
+static void install_layer(ngc_ctx* ctx, int layer, const double* B) {
+    ngc_layer_code& lc = ctx->code[layer];
+    lc.B.assign(B, B + (size_t)ctx->n * ctx->n);
+    compress_layer(lc, ctx->n);
+    lc.set = true;
+    ctx->code_dirty = true;
+}
+
+extern "C" int ngc_create(ngc_ctx** out, int n, int k, int L, const int* s, int64_t d,
+                          void* hip_stream) {
+    if (!out) return NGC_ERR_INVALID;
+    *out = nullptr;
+    if (n < 1 || n > NGC_MAX_N || k != n || L < 1 || L > NGC_MAX_N || !s || d < 1)
+        return NGC_ERR_INVALID;
+    if (s[0] != 0) return NGC_ERR_INVALID;
+    for (int u = 1; u < L; ++u)
+        if (s[u] <= s[u - 1]) return NGC_ERR_INVALID;
+    if (s[L - 1] >= n) return NGC_ERR_INVALID;
+    ngc_ctx* ctx = new (std::nothrow) ngc_ctx;
+    if (!ctx) return NGC_ERR_NOMEM;
+    ctx->n = n;
+    ctx->L = L;
+    ctx->d = d;
+    ctx->s.assign(s, s + L);
+    ctx->stream = (hipStream_t)hip_stream;
+    ctx->code.resize(L);
+    std::vector<double> I((size_t)n * n, 0.0);
+    for (int i = 0; i < n; ++i) I[(size_t)i * n + i] = 1.0;
+    install_layer(ctx, 0, I.data());  // Alg. 1: B_0 = I
+    *out = ctx;
+    return NGC_OK;
+}
+
+extern "C" void ngc_destroy(ngc_ctx* ctx) {
+    if (!ctx) return;
+    ngc_dev_release(ctx);
+    delete ctx;
+}
+
+extern "C" int ngc_set_code(ngc_ctx* ctx, int layer, const double* B_host) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (layer < 0 || layer >= ctx->L || !B_host) return ngc_fail(ctx, NGC_ERR_INVALID, "bad layer or null B");
+    const int n = ctx->n;
+    for (size_t t = 0; t < (size_t)n * n; ++t)
+        if (!std::isfinite(B_host[t])) return ngc_fail(ctx, NGC_ERR_INVALID, "B has a non-finite entry");
+    for (int i = 0; i < n; ++i) {
+        if (B_host[(size_t)i * n + i] == 0.0)
+            return ngc_fail(ctx, NGC_ERR_INVALID, "worker i must hold partition i (B[i][i] != 0)");
+        // Def. 2: supports grow with the layer
+        for (int j = 0; j < n; ++j) {
+            bool here = B_host[(size_t)i * n + j] != 0.0;
+            for (int v = 0; v < ctx->L; ++v) {
+                if (v == layer || !ctx->code[v].set) continue;
+                bool there = ctx->code[v].B[(size_t)i * n + j] != 0.0;
+                if (v < layer && there && !here)
+                    return ngc_fail(ctx, NGC_ERR_INVALID, "row support does not contain the layer below (Def. 2)");
+                if (v > layer && here && !there)
+                    return ngc_fail(ctx, NGC_ERR_INVALID, "row support is not contained in the layer above (Def. 2)");
+            }
+        }
+    }
+    install_layer(ctx, layer, B_host);
+    return NGC_OK;
+}
+
+extern "C" int ngc_get_code(const ngc_ctx* ctx, int layer, double* B_host_out) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (layer < 0 || layer >= ctx->L || !B_host_out) return ngc_fail(ctx, NGC_ERR_INVALID, "bad layer or null output");
+    if (!ctx->code[layer].set) return ngc_fail(ctx, NGC_ERR_STATE, "layer has no code yet");
+    std::memcpy(B_host_out, ctx->code[layer].B.data(), sizeof(double) * ctx->n * ctx->n);
+    return NGC_OK;
+}
+
+extern "C" int ngc_set_mlp2_shape(ngc_ctx* ctx, int d_in, int hidden, int classes) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (d_in < 1 || hidden < 1 || classes < 2) return ngc_fail(ctx, NGC_ERR_INVALID, "bad MLP shape");
+    int64_t need = (int64_t)d_in * hidden + hidden + (int64_t)hidden * classes + classes;
+    if (need != ctx->d) return ngc_fail(ctx, NGC_ERR_INVALID, "MLP parameter count differs from d");
+    ctx->mlp_din = d_in;
+    ctx->mlp_hidden = hidden;
+    ctx->mlp_classes = classes;
+    return NGC_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Random numbers for the code construction: Philox-4x32 with 10 rounds
+// (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3",
+// SC'11), a counter-based generator: output = bijection_key(counter).
+// ---------------------------------------------------------------------------
+namespace {
+
+struct Philox {
+    uint32_t key[2];
+    uint64_t ctr_lo = 0, ctr_hi;
+    uint32_t out[4];
+    int have = 0;
+    Philox(uint64_t seed, uint64_t stream) : ctr_hi(stream) {
+        key[0] = (uint32_t)seed;
+        key[1] = (uint32_t)(seed >> 32);
+    }
+    void block() {
+        uint32_t c[4] = {(uint32_t)ctr_lo, (uint32_t)(ctr_lo >> 32), (uint32_t)ctr_hi, (uint32_t)(ctr_hi >> 32)};
+        uint32_t k0 = key[0], k1 = key[1];
+        for (int r = 0; r < 10; ++r) {
+            uint64_t p0 = (uint64_t)0xD2511F53u * c[0];
+            uint64_t p1 = (uint64_t)0xCD9E8D57u * c[2];
+            uint32_t n0 = (uint32_t)(p1 >> 32) ^ c[1] ^ k0;
+            uint32_t n1 = (uint32_t)p1;
+            uint32_t n2 = (uint32_t)(p0 >> 32) ^ c[3] ^ k1;
+            uint32_t n3 = (uint32_t)p0;
+            c[0] = n0; c[1] = n1; c[2] = n2; c[3] = n3;
+            k0 += 0x9E3779B9u;
+            k1 += 0xBB67AE85u;
+        }
+        std::memcpy(out, c, sizeof(out));
+        ++ctr_lo;
+        have = 4;
+    }
+    uint32_t u32() {
+        if (!have) block();
+        return out[4 - have--];
+    }
+    double uniform() {  // (0,1], 53 bits
+        uint64_t hi = u32(), lo = u32();
+        uint64_t x = ((hi << 32) | lo) >> 11;
+        return ((double)x + 1.0) * (1.0 / 9007199254740992.0);
+    }
+    double normal() {  // Box-Muller, one value per call
+        double u1 = uniform(), u2 = uniform();
+        return std::sqrt(-2.0 * std::log(u1)) * std::cos(6.283185307179586476925 * u2);
+    }
+    int below(int m) { return (int)(((uint64_t)u32() * (uint64_t)m) >> 32); }
+};
+
+// Solve the s x s system A x = b in place by Gaussian elimination with partial
+// pivoting.  A row-major.  Returns false if a pivot vanishes.
+bool solve_square(std::vector<double>& A, std::vector<double>& b, int s) {
+    for (int c = 0; c < s; ++c) {
+        int p = c;
+        for (int r = c + 1; r < s; ++r)
+            if (std::fabs(A[(size_t)r * s + c]) > std::fabs(A[(size_t)p * s + c])) p = r;
+        if (A[(size_t)p * s + c] == 0.0) return false;
+        if (p != c) {
+            for (int j = 0; j < s; ++j) std::swap(A[(size_t)p * s + j], A[(size_t)c * s + j]);
+            std::swap(b[p], b[c]);
+        }
+        for (int r = c + 1; r < s; ++r) {
+            double f = A[(size_t)r * s + c] / A[(size_t)c * s + c];
+            if (f == 0.0) continue;
+            for (int j = c; j < s; ++j) A[(size_t)r * s + j] -= f * A[(size_t)c * s + j];
+            b[r] -= f * b[c];
+        }
+    }
+    for (int r = s - 1; r >= 0; --r) {
+        double acc = b[r];
+        for (int j = r + 1; j < s; ++j) acc -= A[(size_t)r * s + j] * b[j];
+        b[r] = acc / A[(size_t)r * s + r];
+    }
+    return true;
+}
+
+// One random cyclic code with tolerance sigma: rows in the null space of H
+// (sigma x n, Gaussian, rows summing to zero), row i supported on {i..i+sigma}.
+bool draw_cyclic(int n, int sigma, Philox& rng, std::vector<double>& B) {
+    std::vector<double> H((size_t)sigma * n);
+    for (int r = 0; r < sigma; ++r) {
+        double sum = 0.0;
+        for (int j = 0; j < n - 1; ++j) {
+            H[(size_t)r * n + j] = rng.normal();
+            sum += H[(size_t)r * n + j];
+        }
+        H[(size_t)r * n + n - 1] = -sum;
+    }
+    B.assign((size_t)n * n, 0.0);
+    std::vector<double> A((size_t)sigma * sigma), rhs(sigma);
+    for (int i = 0; i < n; ++i) {
+        for (int r = 0; r < sigma; ++r) {
+            for (int t = 1; t <= sigma; ++t) A[(size_t)r * sigma + t - 1] = H[(size_t)r * n + (i + t) % n];
+            rhs[r] = -H[(size_t)r * n + i];
+        }
+        if (!solve_square(A, rhs, sigma)) return false;
+        B[(size_t)i * n + i] = 1.0;
+        for (int t = 1; t <= sigma; ++t) B[(size_t)i * n + (i + t) % n] = rhs[t - 1];
+    }
+    return true;
+}
+
+// How much decoding magnifies rounding of the messages: mean over sampled
+// straggler sets of size sigma of sum_i |a_i| ||b_i||_1.
+double amplification(const std::vector<double>& B, int n, int sigma, uint64_t seed, int samples) {
+    Philox rng(seed, 0x5c0feULL);
+    std::vector<double> l1(n, 0.0), a(n);
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < n; ++j) l1[i] += std::fabs(B[(size_t)i * n + j]);
+    std::vector<int> perm(n), rows;
+    double tot = 0.0;
+    for (int t = 0; t < samples; ++t) {
+        for (int i = 0; i < n; ++i) perm[i] = i;
+        for (int i = 0; i < sigma; ++i) std::swap(perm[i], perm[i + rng.below(n - i)]);
+        rows.assign(perm.begin() + sigma, perm.end());
+        std::sort(rows.begin(), rows.end());
+        double resid = 0.0;
+        ngc_min_norm_decode(B.data(), n, rows.data(), (int)rows.size(), a.data(), &resid);
+        if (!(resid < 1e-6)) return INFINITY;
+        for (int i = 0; i < n; ++i) tot += std::fabs(a[i]) * l1[i];
+    }
+    return tot / samples;
+}
+
+}  // namespace
+
+extern "C" int ngc_build_code(ngc_ctx* ctx, int kind, uint64_t seed) {
+    if (!ctx) return NGC_ERR_INVALID;
+    const int n = ctx->n;
+    if (kind != NGC_CODE_CYCLIC && kind != NGC_CODE_FRACREP) return ngc_fail(ctx, NGC_ERR_INVALID, "unknown code kind");
+    std::vector<std::vector<double>> built(ctx->L);
+    for (int u = 0; u < ctx->L; ++u) {
+        const int sigma = ctx->s[u];
+        std::vector<double>& B = built[u];
+        if (sigma == 0) {
+            B.assign((size_t)n * n, 0.0);
+            for (int i = 0; i < n; ++i) B[(size_t)i * n + i] = 1.0;
+        } else if (kind == NGC_CODE_FRACREP) {
+            const int w = sigma + 1;
+            if (n % w) return ngc_fail(ctx, NGC_ERR_INVALID, "fractional repetition needs (s+1) | n");
+            if (w % (ctx->s[u - 1] + 1)) return ngc_fail(ctx, NGC_ERR_INVALID, "fractional-repetition layers are not nested");
+            B.assign((size_t)n * n, 0.0);
+            for (int i = 0; i < n; ++i)
+                for (int j = w * (i / w); j < w * (i / w) + w; ++j) B[(size_t)i * n + j] = 1.0;
+        } else {
+            const int draws = 16;
+            double best = INFINITY;
+            std::vector<double> cand;
+            for (int t = 0; t < draws; ++t) {
+                Philox rng(seed, ((uint64_t)sigma << 32) | (uint64_t)t);
+                if (!draw_cyclic(n, sigma, rng, cand)) continue;
+                double score = amplification(cand, n, sigma, seed ^ (uint64_t)sigma, 32);
+                if (score < best) {
+                    best = score;
+                    B = cand;
+                }
+            }
+            if (!(best < INFINITY)) return ngc_fail(ctx, NGC_ERR_SINGULAR, "no valid cyclic draw found");
+        }
+    }
+    for (int u = 0; u < ctx->L; ++u) ctx->code[u].set = false;
+    for (int u = 0; u < ctx->L; ++u) install_layer(ctx, u, built[u].data());
+    return NGC_OK;
+}
+
+static int select_impl(const ngc_ctx* ctx, const uint8_t* mask, int* layer_out, double* a_out,
+                       double* residual_out, bool first_only) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (!mask || !layer_out || !a_out) return ngc_fail(ctx, NGC_ERR_INVALID, "null argument");
+    const int n = ctx->n;
+    int stragglers = 0;
+    for (int i = 0; i < n; ++i) stragglers += mask[i] != 0;
+    for (int i = 0; i < n; ++i) a_out[i] = 0.0;
+    int u = -1;
+    for (int v = 0; v < ctx->L; ++v)
+        if (ctx->s[v] >= stragglers) { u = v; break; }
+    *layer_out = u;
+    if (residual_out) *residual_out = 0.0;
+    if (u < 0) return ngc_fail(ctx, NGC_ERR_UNDECODABLE, "stragglers exceed the largest tolerance");
+    if (!ctx->code[u].set) return ngc_fail(ctx, NGC_ERR_STATE, "chosen layer has no code yet");
+    int rows[NGC_MAX_N];
+    int ns = 0;
+    const int want = first_only ? n - ctx->s[u] : n;
+    for (int i = 0; i < n && ns < want; ++i)
+        if (!mask[i]) rows[ns++] = i;
+    double resid = 0.0;
+    ngc_min_norm_decode(ctx->code[u].B.data(), n, rows, ns, a_out, &resid);
+    if (residual_out) *residual_out = resid;
+    if (!(resid <= 1e-6)) return ngc_fail(ctx, NGC_ERR_SINGULAR, "decode residual above tolerance");
+    return NGC_OK;
+}
+
+extern "C" int ngc_select_decode_vec(const ngc_ctx* ctx, const uint8_t* straggler_mask, int* layer_out,
+                                     double* a_out, double* residual_out) {
+    return select_impl(ctx, straggler_mask, layer_out, a_out, residual_out, false);
+}
+
+extern "C" int ngc_select_decode_vec_first(const ngc_ctx* ctx, const uint8_t* straggler_mask,
+                                           int* layer_out, double* a_out, double* residual_out) {
+    return select_impl(ctx, straggler_mask, layer_out, a_out, residual_out, true);
+}

@@ -1,0 +1,68 @@
+// Internal state of a libngc context.  Host side only; no kernel includes this
+// for anything but the table layouts below.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "../../include/ngc.h"
+
+constexpr int NGC_MAX_N = 64;
+constexpr int NGC_MAX_PROFILE = 4096;
+
+// One layer's encoding matrix in compressed-row form: the non-zeros of row i are
+// entries rowptr[i] .. rowptr[i+1]-1 of (col, coef).
+struct ngc_layer_code {
+    bool set = false;
+    std::vector<double> B;      // n x n dense, fp64, as given
+    std::vector<int> rowptr;    // n + 1
+    std::vector<int> col;
+    std::vector<double> coef;
+};
+
+struct ngc_profile_rec {
+    int kernel;
+    hipEvent_t start, stop;
+};
+
+struct ngc_ctx {
+    int n = 0;
+    int L = 0;
+    int64_t d = 0;
+    std::vector<int> s;
+    hipStream_t stream = nullptr;
+    std::vector<ngc_layer_code> code;
+
+    // MLP shape (NGC_LOSS_MLP2)
+    int mlp_din = 0, mlp_hidden = 0, mlp_classes = 0;
+
+    // device-side private state, created on first use
+    bool dev_ready = false;
+    int cu_count = 0;
+    bool code_dirty = true;          // host tables changed since the last upload
+    void* d_code = nullptr;          // packed tables for all layers (see ngc_device.hip)
+    size_t d_code_bytes = 0;
+    size_t code_nnz = 0;             // non-zeros over all layers in d_code
+    float* d_ws = nullptr;           // workspace: block partials / residuals / MLP activations
+    size_t d_ws_bytes = 0;
+
+    bool profiling = false;
+    std::vector<ngc_profile_rec> prof;
+    std::vector<hipEvent_t> event_pool;
+
+    mutable std::string err;
+};
+
+int ngc_fail(const ngc_ctx* ctx, int code, const std::string& msg);
+
+// defined in ngc_device.hip
+void ngc_dev_release(ngc_ctx* ctx);
+
+// defined in ngc_solve.cpp: least-norm a_S with a_S^T B_S = 1^T.
+// rows: indices of responders (size ns).  B: n x n row-major.  a_out: n entries,
+// zero outside rows.  Returns the numerical rank found; resid = max_j |a^T B - 1|.
+int ngc_min_norm_decode(const double* B, int n, const int* rows, int ns, double* a_out,
+                        double* resid);

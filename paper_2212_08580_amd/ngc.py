@@ -1,0 +1,192 @@
+"""ctypes binding of libngc.so: same names as include/ngc.h, argument marshalling only.
+
+Device buffers are torch tensors (torch is used for HBM allocation and streams
+only); host arrays are NumPy.  Every function returns what the C call returns
+through its output arguments and raises NgcError on a negative status.  If the
+shared library has not been built the import of this module fails: there is no
+CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libngc.so")
+
+NGC_OK = 0
+NGC_ERR_INVALID = -1
+NGC_ERR_UNDECODABLE = -2
+NGC_ERR_SINGULAR = -3
+NGC_ERR_HIP = -4
+NGC_ERR_NOMEM = -5
+NGC_ERR_STATE = -6
+
+NGC_LOSS_LSQ, NGC_LOSS_LOGISTIC, NGC_LOSS_MLP2 = 0, 1, 2
+NGC_CODE_CYCLIC, NGC_CODE_FRACREP = 0, 1
+NGC_KERNEL_NAMES = ("grad", "reduce", "encode", "decode", "update", "mlp")
+NGC_KERNEL_COUNT = len(NGC_KERNEL_NAMES)
+
+EXPORTS = (
+    "ngc_create", "ngc_destroy", "ngc_set_code", "ngc_get_code", "ngc_build_code",
+    "ngc_set_mlp2_shape", "ngc_partition_grads", "ngc_encode", "ngc_select_decode_vec",
+    "ngc_select_decode_vec_first", "ngc_decode", "ngc_update", "ngc_sync",
+    "ngc_profile_enable", "ngc_profile_read", "ngc_strerror", "ngc_last_error",
+)
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        "libngc.so is not built (%s missing): run `python -m paper_2212_08580_amd.build` "
+        "or __graft_entry__.build(); there is no CPU fallback" % LIB_PATH)
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+_vp, _i, _i64, _u64, _dbl = (ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_uint64,
+                             ctypes.c_double)
+_lib.ngc_create.argtypes = [ctypes.POINTER(_vp), _i, _i, _i, ctypes.POINTER(_i), _i64, _vp]
+_lib.ngc_destroy.argtypes = [_vp]
+_lib.ngc_destroy.restype = None
+_lib.ngc_set_code.argtypes = [_vp, _i, _vp]
+_lib.ngc_get_code.argtypes = [_vp, _i, _vp]
+_lib.ngc_build_code.argtypes = [_vp, _i, _u64]
+_lib.ngc_set_mlp2_shape.argtypes = [_vp, _i, _i, _i]
+_lib.ngc_partition_grads.argtypes = [_vp, _i, _vp, _vp, _vp, _i64, _vp]
+_lib.ngc_encode.argtypes = [_vp, _vp, _i, _vp]
+_lib.ngc_select_decode_vec.argtypes = [_vp, _vp, ctypes.POINTER(_i), _vp, ctypes.POINTER(_dbl)]
+_lib.ngc_select_decode_vec_first.argtypes = _lib.ngc_select_decode_vec.argtypes
+_lib.ngc_decode.argtypes = [_vp, _i, _vp, _vp, _vp]
+_lib.ngc_update.argtypes = [_vp, _vp, _vp, _dbl]
+_lib.ngc_sync.argtypes = [_vp]
+_lib.ngc_profile_enable.argtypes = [_vp, _i]
+_lib.ngc_profile_read.argtypes = [_vp, _vp, _vp]
+_lib.ngc_strerror.argtypes = [_i]
+_lib.ngc_strerror.restype = ctypes.c_char_p
+_lib.ngc_last_error.argtypes = [_vp]
+_lib.ngc_last_error.restype = ctypes.c_char_p
+
+
+class NgcError(RuntimeError):
+    def __init__(self, code, detail=""):
+        self.code = code
+        msg = _lib.ngc_strerror(code).decode()
+        super().__init__("libngc error %d (%s)%s" % (code, msg, ": " + detail if detail else ""))
+
+
+def _check(rc, ctx=None):
+    if rc != NGC_OK:
+        detail = _lib.ngc_last_error(ctx).decode() if ctx else ""
+        raise NgcError(rc, detail)
+
+
+def _dev(t):
+    """Raw device address of a torch tensor (contiguous, on the GPU)."""
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("device buffers must be contiguous GPU tensors")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _host(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a, a.ctypes.data_as(ctypes.c_void_p)
+
+
+def ngc_strerror(code):
+    return _lib.ngc_strerror(int(code)).decode()
+
+
+def ngc_last_error(ctx):
+    return _lib.ngc_last_error(ctx).decode()
+
+
+def ngc_create(n, k, layers, d, hip_stream=0):
+    """-> opaque context handle.  hip_stream: integer hipStream_t (0 = default)."""
+    layers = [int(s) for s in layers]
+    arr = (ctypes.c_int * max(1, len(layers)))(*layers)
+    out = ctypes.c_void_p()
+    rc = _lib.ngc_create(ctypes.byref(out), int(n), int(k), len(layers), arr, int(d),
+                         ctypes.c_void_p(int(hip_stream)))
+    _check(rc)
+    return out
+
+
+def ngc_destroy(ctx):
+    _lib.ngc_destroy(ctx)
+
+
+def ngc_set_code(ctx, layer, B):
+    B, p = _host(B, np.float64)
+    _check(_lib.ngc_set_code(ctx, int(layer), p), ctx)
+
+
+def ngc_get_code(ctx, layer, n):
+    out = np.empty((n, n), np.float64)
+    _check(_lib.ngc_get_code(ctx, int(layer), out.ctypes.data_as(ctypes.c_void_p)), ctx)
+    return out
+
+
+def ngc_build_code(ctx, kind, seed):
+    _check(_lib.ngc_build_code(ctx, int(kind), int(seed)), ctx)
+
+
+def ngc_set_mlp2_shape(ctx, d_in, hidden, classes):
+    _check(_lib.ngc_set_mlp2_shape(ctx, int(d_in), int(hidden), int(classes)), ctx)
+
+
+def ngc_partition_grads(ctx, loss, X, y, theta, rows_per_part, G):
+    _check(_lib.ngc_partition_grads(ctx, int(loss), _dev(X), _dev(y), _dev(theta),
+                                    int(rows_per_part), _dev(G)), ctx)
+
+
+def ngc_encode(ctx, G, layer, C):
+    _check(_lib.ngc_encode(ctx, _dev(G), int(layer), _dev(C)), ctx)
+
+
+def _select(fn, ctx, mask, n):
+    mask, pm = _host(mask, np.uint8)
+    if mask.size != n:
+        raise ValueError("mask must have n entries")
+    a = np.zeros(n, np.float64)
+    layer = ctypes.c_int(-1)
+    resid = ctypes.c_double(0.0)
+    rc = fn(ctx, pm, ctypes.byref(layer), a.ctypes.data_as(ctypes.c_void_p), ctypes.byref(resid))
+    _check(rc, ctx)
+    return layer.value, a, resid.value
+
+
+def ngc_select_decode_vec(ctx, mask, n):
+    """-> (layer, a [n] fp64, residual)."""
+    return _select(_lib.ngc_select_decode_vec, ctx, mask, n)
+
+
+def ngc_select_decode_vec_first(ctx, mask, n):
+    return _select(_lib.ngc_select_decode_vec_first, ctx, mask, n)
+
+
+def ngc_decode(ctx, layer, a, C, g):
+    a, pa = _host(a, np.float64)
+    _check(_lib.ngc_decode(ctx, int(layer), pa, _dev(C), _dev(g)), ctx)
+
+
+def ngc_update(ctx, theta, g, scale):
+    _check(_lib.ngc_update(ctx, _dev(theta), _dev(g), float(scale)), ctx)
+
+
+def ngc_sync(ctx):
+    _check(_lib.ngc_sync(ctx), ctx)
+
+
+def ngc_profile_enable(ctx, on):
+    _check(_lib.ngc_profile_enable(ctx, int(bool(on))), ctx)
+
+
+def ngc_profile_read(ctx):
+    """-> {kernel name: (launches, total_ms)}."""
+    cnt = np.zeros(NGC_KERNEL_COUNT, np.int64)
+    ms = np.zeros(NGC_KERNEL_COUNT, np.float64)
+    _check(_lib.ngc_profile_read(ctx, cnt.ctypes.data_as(ctypes.c_void_p),
+                                 ms.ctypes.data_as(ctypes.c_void_p)), ctx)
+    return {name: (int(cnt[i]), float(ms[i])) for i, name in enumerate(NGC_KERNEL_NAMES)}

@@ -15,5 +15,5 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def ngc():
     """The Python binding of libngc (argument marshalling only)."""
-    from paper_2212_08580_amd import libngc
-    return libngc
+    from paper_2212_08580_amd import ngc as binding
+    return binding

@@ -1,0 +1,369 @@
+"""Parity of the HIP path (through the C ABI) against the fp64 oracle.
+
+Bars: rel-L2 <= 1e-4 for floating point; layer, straggler handling and the
+support of the decode vector exact.  Where decoding is ill-conditioned
+(kappa = sum |a_i| ||c_i|| / ||g|| large, C5-like cases) the error must in
+addition stay inside the forward-error bound 4 * 2^-24 * kappa, and the share of
+rounds above 1e-4 is reported.
+"""
+import numpy as np
+import pytest
+
+from oracle import codes, coding, gradients
+from paper_2212_08580_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def torch_dev():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (run on the MI355X box)")
+    torch.cuda.set_device(0)
+    return torch
+
+
+def rel(x, ref):
+    x = np.asarray(x, np.float64)
+    ref = np.asarray(ref, np.float64)
+    return float(np.linalg.norm(x - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+class Pipeline:
+    """Device buffers + context for one workload; B comes from the oracle's constructor."""
+
+    def __init__(self, ngc, torch, w, Bs=None, kind=None, seed=0):
+        self.ngc, self.torch, self.w = ngc, torch, w
+        self.dev = torch.device("cuda:0")
+        stream = torch.cuda.current_stream().cuda_stream
+        self.ctx = ngc.ngc_create(w.n, w.n, w.layers, w.d, stream)
+        if Bs is None:
+            kind = kind or ("cyclic" if w.code == wl.CODE_CYCLIC else "fracrep")
+            Bs = codes.nested_code(w.n, w.layers, kind, seed=seed, draws=2)
+        self.Bs = Bs
+        for u, B in enumerate(Bs):
+            ngc.ngc_set_code(self.ctx, u, B)
+        self.G = torch.empty((w.n, w.d), dtype=torch.float32, device=self.dev)
+        self.C = torch.empty((len(w.layers), w.n, w.d), dtype=torch.float32, device=self.dev)
+        self.g = torch.empty(w.d, dtype=torch.float32, device=self.dev)
+
+    def close(self):
+        self.ngc.ngc_destroy(self.ctx)
+
+    def to_dev(self, a):
+        return self.torch.from_numpy(np.ascontiguousarray(a)).to(self.dev)
+
+    def grads(self, X, Y, th):
+        self.ngc.ngc_partition_grads(self.ctx, self.w.loss, self.to_dev(X), self.to_dev(Y),
+                                     self.to_dev(th), X.shape[1], self.G)
+        self.ngc.ngc_sync(self.ctx)
+        return self.G.cpu().numpy()
+
+    def encode(self, layer=-1):
+        self.ngc.ngc_encode(self.ctx, self.G, layer, self.C)
+        self.ngc.ngc_sync(self.ctx)
+        return self.C.cpu().numpy()
+
+    def decode(self, mask):
+        u, a, r = self.ngc.ngc_select_decode_vec(self.ctx, mask, self.w.n)
+        self.ngc.ngc_decode(self.ctx, u, a, self.C, self.g)
+        self.ngc.ngc_sync(self.ctx)
+        return u, a, r, self.g.cpu().numpy()
+
+
+def check_round(p, G_o, mask, C_gpu, strict=True):
+    """One mask: layer/support exact, decoded gradient vs oracle."""
+    w = p.w
+    u_o, a_o, g_o = coding.coded_gradient(p.Bs, w.layers, G_o, mask)
+    u, a, r, g = p.decode(mask)
+    assert u == u_o
+    assert np.array_equal(a != 0, a_o != 0)
+    assert np.all(a[mask == 1] == 0)
+    # the decode kernel itself: fp64 combination of the GPU's own fp32 messages
+    g_same = coding.decode(a, C_gpu[u])
+    assert rel(g, g_same) <= 2e-7
+    err = rel(g, g_o)
+    kappa = coding.conditioning(a_o, coding.encode(p.Bs[u_o], G_o), g_o)
+    assert err <= max(TOL if strict else 0.0, 4 * 2.0 ** -24 * kappa), (err, kappa)
+    return err, kappa
+
+
+# --------------------------------------------------------------------------------------------
+# C1 exactly: least squares, n = 4, 4 x 256 rows, d = 64, layers (0,1), fractional repetition,
+# all 16 straggler subsets
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("kind", ["fracrep", "cyclic"])
+def test_c1_all_16_straggler_subsets(ngc, torch_dev, kind):
+    w = wl.C1
+    X, Y = wl.dataset(w, 0, threads=1)
+    th = wl.theta(w, 0)
+    p = Pipeline(ngc, torch_dev, w, kind=kind)
+    try:
+        G = p.grads(X, Y, th)
+        G_o = gradients.partial_gradients(w.loss, X, Y, th)
+        assert rel(G, G_o) <= TOL
+        for j in range(w.n):
+            assert rel(G[j], G_o[j]) <= TOL
+        C = p.encode()
+        C_o = coding.encode_layers(p.Bs, G_o)
+        assert rel(C, C_o) <= TOL
+        ok = bad = 0
+        for bits in range(16):
+            m = np.array([(bits >> i) & 1 for i in range(4)], np.uint8)
+            if m.sum() > 1:
+                with pytest.raises(ngc.NgcError) as e:
+                    ngc.ngc_select_decode_vec(p.ctx, m, 4)
+                assert e.value.code == ngc.NGC_ERR_UNDECODABLE
+                bad += 1
+                continue
+            check_round(p, G_o, m, C)
+            ok += 1
+        assert (ok, bad) == (5, 11)
+    finally:
+        p.close()
+
+
+# --------------------------------------------------------------------------------------------
+# gradient kernels: every single-pass shape, the two-pass route, ragged row counts, both losses
+# --------------------------------------------------------------------------------------------
+GRAD_SHAPES = [
+    # (d, n, rows)   rows chosen to leave ragged tails (not multiples of the row group)
+    (256, 3, 37), (512, 3, 21), (768, 2, 9), (1024, 4, 131), (2048, 3, 29), (3072, 2, 11),
+    (4096, 4, 67), (6144, 2, 7), (8192, 2, 13), (12288, 2, 5), (16384, 2, 6),
+    (64, 4, 256), (200, 3, 50), (77, 2, 19), (1000, 2, 33), (4100, 2, 10), (5120, 2, 9),
+    (4096, 2, 1), (1024, 1, 3), (4096, 64, 9),
+]
+
+
+@pytest.mark.parametrize("loss", [wl.LOSS_LSQ, wl.LOSS_LOGISTIC])
+@pytest.mark.parametrize("d,n,rows", GRAD_SHAPES)
+def test_partition_gradients_match_oracle(ngc, torch_dev, loss, d, n, rows):
+    base = wl.C3 if loss == wl.LOSS_LSQ else wl.C2
+    w = base.scaled(rows=rows, d=d, n=n, layers=(0,), name="shape")
+    X, Y = wl.dataset(w, seed=d + rows, threads=1)
+    scale = None if loss == wl.LOSS_LSQ else 2.0 / np.sqrt(d)   # margins of order 1, not saturated
+    th = wl.theta(w, seed=1, scale=scale)
+    p = Pipeline(ngc, torch_dev, w, Bs=[np.eye(n)])
+    try:
+        G = p.grads(X, Y, th)
+        G_o = gradients.partial_gradients(loss, X, Y, th)
+        assert G.shape == G_o.shape
+        assert np.all(np.isfinite(G))
+        for j in range(n):
+            assert rel(G[j], G_o[j]) <= TOL, (j, rel(G[j], G_o[j]))
+        G2 = p.grads(X, Y, th)
+        assert np.array_equal(G, G2)              # fixed summation order: bit-reproducible
+    finally:
+        p.close()
+
+
+def test_logistic_saturated_margins(ngc, torch_dev):
+    """exp overflow in the logistic slope must give the limits 0 and -y, not NaN."""
+    w = wl.C2.scaled(rows=64, d=1024, n=2, layers=(0,))
+    X, Y = wl.dataset(w, seed=3, threads=1)
+    th = wl.theta(w, seed=1, scale=50.0)           # |x.theta| ~ 1600 >> 88
+    p = Pipeline(ngc, torch_dev, w, Bs=[np.eye(2)])
+    try:
+        G = p.grads(X, Y, th)
+        G_o = gradients.partial_gradients(w.loss, X, Y, th)
+        assert np.all(np.isfinite(G))
+        assert rel(G, G_o) <= TOL
+    finally:
+        p.close()
+
+
+# --------------------------------------------------------------------------------------------
+# encode / decode on their own (no data): vector widths 4, 2, 1, column tails, both families
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,layers,kind,d", [
+    (4, (0, 1), "fracrep", 64), (16, (0, 1, 3, 7), "cyclic", 1024), (32, (0, 1, 3, 7, 15), "cyclic", 4096),
+    (64, (0, 1, 3, 7, 15, 31), "cyclic", 16384), (64, (0, 1, 3, 7, 15, 31), "fracrep", 4096),
+    (20, (0, 1, 4, 9), "cyclic", 1002), (20, (0, 1, 4, 9), "cyclic", 999), (7, (0, 2, 5), "cyclic", 100),
+    (1, (0,), "cyclic", 5), (33, (0, 32), "cyclic", 68),
+])
+def test_encode_and_decode_match_oracle(ngc, torch_dev, n, layers, kind, d):
+    w = wl.C5.scaled(n=n, d=d, layers=layers)
+    G_h = wl.partial_gradients(w, seed=n + d)
+    p = Pipeline(ngc, torch_dev, w, kind=kind)
+    try:
+        p.G.copy_(torch_dev.from_numpy(G_h))
+        C = p.encode()
+        C_o = coding.encode_layers(p.Bs, G_h)
+        for u in range(len(layers)):
+            assert rel(C[u], C_o[u]) <= 1e-6, (u, rel(C[u], C_o[u]))
+        assert np.array_equal(C[0], G_h)                       # B_0 = I: layer 0 is a copy
+        # one layer at a time writes only its slice
+        p.C.fill_(-7.0)
+        last = len(layers) - 1
+        C1 = p.encode(layer=last)
+        assert np.array_equal(C1[last], C[last])
+        if last > 0:
+            assert np.all(C1[:last] == -7.0)
+        p.encode()
+        rng = np.random.default_rng(5)
+        worst = 0.0
+        for t in range(12):
+            s = int(rng.integers(0, layers[-1] + 1))
+            m = np.zeros(n, np.uint8)
+            m[rng.choice(n, size=s, replace=False)] = 1
+            err, kappa = check_round(p, G_h.astype(np.float64), m, C, strict=(n <= 32))
+            worst = max(worst, err)
+        print("n=%d d=%d %s worst decode rel-L2 %.2e" % (n, d, kind, worst))
+    finally:
+        p.close()
+
+
+def test_decode_rejects_bad_arguments_and_update_matches(ngc, torch_dev):
+    w = wl.C5.scaled(n=4, d=1030, layers=(0, 1))
+    p = Pipeline(ngc, torch_dev, w)
+    try:
+        a = np.ones(4)
+        with pytest.raises(ngc.NgcError):
+            ngc.ngc_decode(p.ctx, 2, a, p.C, p.g)
+        a[1] = np.inf
+        with pytest.raises(ngc.NgcError):
+            ngc.ngc_decode(p.ctx, 0, a, p.C, p.g)
+        with pytest.raises(ngc.NgcError):
+            ngc.ngc_encode(p.ctx, p.G, 5, p.C)
+        th = np.random.default_rng(0).standard_normal(w.d).astype(np.float32)
+        gg = np.random.default_rng(1).standard_normal(w.d).astype(np.float32)
+        thd, gd = p.to_dev(th), p.to_dev(gg)
+        ngc.ngc_update(p.ctx, thd, gd, 0.25)
+        ngc.ngc_sync(p.ctx)
+        assert rel(thd.cpu().numpy(), gradients.gd_update(th, gg, 0.25, 1.0)) <= 1e-6
+    finally:
+        p.close()
+
+
+# --------------------------------------------------------------------------------------------
+# C2 shrunk (logistic, n = 16, layers 0,1,3,7, Bernoulli(0.2) stragglers): a short descent run,
+# each iteration checked against the oracle evaluated at the GPU's own theta_t
+# --------------------------------------------------------------------------------------------
+def test_c2_scaled_descent_with_stragglers(ngc, torch_dev):
+    w = wl.C2.scaled(rows=515, name="C2-rows515")              # d = 1024, 16 partitions
+    X, Y = wl.dataset(w, 0, threads=4)
+    th0 = wl.theta(w, 0, scale=0.01)
+    masks = wl.bernoulli_masks(w, 12, seed=0)
+    p = Pipeline(ngc, torch_dev, w)
+    try:
+        Xd, Yd, thd = p.to_dev(X), p.to_dev(Y), p.to_dev(th0)
+        eta, used, skipped = 1.0, set(), 0
+        for t in range(12):
+            th_t = thd.cpu().numpy()
+            ngc.ngc_partition_grads(p.ctx, w.loss, Xd, Yd, thd, w.rows, p.G)
+            ngc.ngc_encode(p.ctx, p.G, -1, p.C)
+            try:
+                u, a, r = ngc.ngc_select_decode_vec(p.ctx, masks[t], w.n)
+            except ngc.NgcError as e:
+                assert e.code == ngc.NGC_ERR_UNDECODABLE      # theta stays as it is this round
+                skipped += 1
+                continue
+            ngc.ngc_decode(p.ctx, u, a, p.C, p.g)
+            ngc.ngc_update(p.ctx, thd, p.g, eta / w.m)
+            ngc.ngc_sync(p.ctx)
+            G_o = gradients.partial_gradients(w.loss, X, Y, th_t)
+            u_o, a_o, g_o = coding.coded_gradient(p.Bs, w.layers, G_o, masks[t])
+            assert u == u_o and np.array_equal(a != 0, a_o != 0)
+            assert rel(p.G.cpu().numpy(), G_o) <= TOL
+            assert rel(p.g.cpu().numpy(), g_o) <= TOL
+            assert rel(thd.cpu().numpy(), gradients.gd_update(th_t, g_o, eta, w.m)) <= 1e-6
+            used.add(u)
+        assert len(used) >= 2 and skipped <= 2
+    finally:
+        p.close()
+
+
+# --------------------------------------------------------------------------------------------
+# C3 shrunk in rows only (n = 32, d = 4096, layers 0,1,3,7,15, Bernoulli(0.1) stragglers)
+# --------------------------------------------------------------------------------------------
+def test_c3_scaled_pipeline(ngc, torch_dev):
+    w = wl.C3.scaled(rows=203, name="C3-rows203")
+    X, Y = wl.dataset(w, 0, threads=4)
+    th = wl.theta(w, 0)
+    p = Pipeline(ngc, torch_dev, w)
+    try:
+        G = p.grads(X, Y, th)
+        G_o = gradients.partial_gradients(w.loss, X, Y, th)
+        for j in range(w.n):
+            assert rel(G[j], G_o[j]) <= TOL
+        C = p.encode()
+        assert rel(C, coding.encode_layers(p.Bs, G_o)) <= TOL
+        masks = wl.bernoulli_masks(w, 40, seed=1)
+        errs = [check_round(p, G_o, m, C)[0] for m in masks if m.sum() <= w.layers[-1]]
+        assert len(errs) >= 38
+        print("C3-scaled: worst decode rel-L2 %.2e over %d masks" % (max(errs), len(errs)))
+    finally:
+        p.close()
+
+
+# --------------------------------------------------------------------------------------------
+# C5: encode/decode stress, n = 64, d = 16384, layers (0,1,3,7,15,31), straggler count
+# Binomial(64, 0.2), decode vector solved per round (100 of the 1000 rounds here)
+# --------------------------------------------------------------------------------------------
+def test_c5_rounds(ngc, torch_dev):
+    w = wl.C5
+    G_h = wl.partial_gradients(w, 0)
+    masks = wl.binomial_count_masks(w, 100, seed=0)
+    p = Pipeline(ngc, torch_dev, w)
+    try:
+        p.G.copy_(torch_dev.from_numpy(G_h))
+        C = p.encode()
+        assert rel(C, coding.encode_layers(p.Bs, G_h)) <= 1e-6
+        G64 = G_h.astype(np.float64)
+        errs = []
+        for m in masks:
+            if m.sum() > w.layers[-1]:
+                with pytest.raises(ngc.NgcError):
+                    ngc.ngc_select_decode_vec(p.ctx, m, w.n)
+                continue
+            errs.append(check_round(p, G64, m, C, strict=False)[0])
+        errs = np.array(errs)
+        print("C5: %d rounds, median rel-L2 %.2e, worst %.2e, share above 1e-4: %.3f" %
+              (errs.size, np.median(errs), errs.max(), float(np.mean(errs > TOL))))
+        assert np.mean(errs > TOL) <= 0.05
+    finally:
+        p.close()
+
+
+# --------------------------------------------------------------------------------------------
+# Full headline size (C3: 32 x 16384 x 4096, 8.6 GB) in the launch configuration the benchmark
+# times: sampled partitions against the oracle one by one, the rest through properties.
+# --------------------------------------------------------------------------------------------
+def test_c3_full_size_sampled(ngc, torch_dev):
+    torch = torch_dev
+    w = wl.C3
+    dev = torch.device("cuda:0")
+    truth = wl.truth_vector(w, 0)
+    th = wl.theta(w, 0)
+    Xd = torch.empty((w.n, w.rows, w.d), dtype=torch.float32, device=dev)
+    Yd = torch.empty((w.n, w.rows), dtype=torch.float32, device=dev)
+    sampled = {0: None, 13: None, 31: None}
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        for j, (X, Y) in enumerate(ex.map(lambda j: wl.partition(w, j, 0, truth), range(w.n))):
+            Xd[j].copy_(torch.from_numpy(X))
+            Yd[j].copy_(torch.from_numpy(Y))
+            if j in sampled:
+                sampled[j] = gradients.lsq_gradient(X, Y, th)
+    p = Pipeline(ngc, torch, w)
+    try:
+        ngc.ngc_partition_grads(p.ctx, w.loss, Xd, Yd, p.to_dev(th), w.rows, p.G)
+        ngc.ngc_sync(p.ctx)
+        G = p.G.cpu().numpy()
+        for j, g_o in sampled.items():
+            assert rel(G[j], g_o) <= TOL, (j, rel(G[j], g_o))
+        assert np.all(np.isfinite(G))
+        C = p.encode()
+        G64 = G.astype(np.float64)
+        # messages and decoding, given the GPU's own G (exact recovery: decode == sum_j g_j)
+        assert rel(C, coding.encode_layers(p.Bs, G64)) <= 1e-6
+        masks = wl.bernoulli_masks(w, 20, seed=2)
+        for m in masks:
+            if m.sum() <= w.layers[-1]:
+                u, a, r, g = p.decode(m)
+                assert rel(g, G64.sum(axis=0)) <= TOL
+    finally:
+        p.close()

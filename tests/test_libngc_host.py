@@ -1,0 +1,233 @@
+"""Host-side behaviour of libngc that needs no GPU: the library loads and
+exports the declared symbols, argument checks, code construction (checked
+against Defs. 1-2 of the paper, not against the oracle's numbers), layer choice
+and decode-vector selection (checked against the oracle)."""
+import ctypes
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import codes, coding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol(ngc):
+    header = open(os.path.join(ROOT, "include", "ngc.h")).read()
+    declared = set(re.findall(r"\b(ngc_[a-z0-9_]+)\s*\(", header))
+    declared -= {"ngc_ctx"}
+    assert declared == set(ngc.EXPORTS)
+    lib = ctypes.CDLL(ngc.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_create_rejects_bad_arguments(ngc):
+    bad = [
+        dict(n=4, k=5, layers=[0, 1], d=8),          # k != n (Sec. II-C)
+        dict(n=4, k=4, layers=[1, 2], d=8),          # first layer must be sigma = 0
+        dict(n=4, k=4, layers=[0, 2, 2], d=8),       # not strictly ascending
+        dict(n=4, k=4, layers=[0, 4], d=8),          # tolerance >= n
+        dict(n=0, k=0, layers=[0], d=8),
+        dict(n=65, k=65, layers=[0], d=8),
+        dict(n=4, k=4, layers=[0, 1], d=0),
+    ]
+    for kw in bad:
+        with pytest.raises(ngc.NgcError) as e:
+            ngc.ngc_create(kw["n"], kw["k"], kw["layers"], kw["d"])
+        assert e.value.code == ngc.NGC_ERR_INVALID
+    ngc.ngc_destroy(None)
+
+
+def test_layer_zero_is_identity_and_set_code_checks_nesting(ngc):
+    ctx = ngc.ngc_create(4, 4, [0, 1, 3], 8)
+    try:
+        assert np.array_equal(ngc.ngc_get_code(ctx, 0, 4), np.eye(4))      # Alg. 1: B_0 = I
+        with pytest.raises(ngc.NgcError) as e:
+            ngc.ngc_get_code(ctx, 1, 4)
+        assert e.value.code == ngc.NGC_ERR_STATE
+        B1 = codes.fracrep_code(4, 1)
+        ngc.ngc_set_code(ctx, 1, B1)
+        assert np.array_equal(ngc.ngc_get_code(ctx, 1, 4), B1)
+        # layer 2 must contain layer 1's supports (Def. 2)
+        bad = np.eye(4)
+        with pytest.raises(ngc.NgcError) as e:
+            ngc.ngc_set_code(ctx, 2, bad)
+        assert e.value.code == ngc.NGC_ERR_INVALID
+        # a worker must hold its own partition
+        bad = np.ones((4, 4))
+        bad[2, 2] = 0.0
+        with pytest.raises(ngc.NgcError):
+            ngc.ngc_set_code(ctx, 2, bad)
+        with pytest.raises(ngc.NgcError):
+            ngc.ngc_set_code(ctx, 3, np.ones((4, 4)))
+        nan = np.ones((4, 4))
+        nan[0, 1] = np.nan
+        with pytest.raises(ngc.NgcError):
+            ngc.ngc_set_code(ctx, 2, nan)
+        ngc.ngc_set_code(ctx, 2, np.ones((4, 4)))
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
+@pytest.mark.parametrize("n,layers", [(6, [0, 1, 2, 3]), (8, [0, 1, 3, 7]), (9, [0, 2, 4])])
+def test_built_cyclic_code_satisfies_def1_and_def2(ngc, n, layers):
+    ctx = ngc.ngc_create(n, n, layers, 4)
+    try:
+        ngc.ngc_build_code(ctx, ngc.NGC_CODE_CYCLIC, 7)
+        prev = None
+        for u, sigma in enumerate(layers):
+            B = ngc.ngc_get_code(ctx, u, n)
+            if sigma == 0:
+                assert np.array_equal(B, np.eye(n))
+            supp = [set(np.flatnonzero(B[i])) for i in range(n)]
+            for i in range(n):
+                assert supp[i] == {(i + t) % n for t in range(sigma + 1)}
+                if prev is not None:
+                    assert prev[i] <= supp[i]
+            prev = supp
+            for out in itertools.combinations(range(n), sigma):
+                S = [i for i in range(n) if i not in out]
+                assert np.linalg.matrix_rank(B[S], tol=1e-9) == n - sigma
+                assert np.linalg.matrix_rank(np.vstack([B[S], np.ones(n)]), tol=1e-9) == n - sigma
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
+def test_build_code_is_deterministic_in_the_seed(ngc):
+    def built(seed):
+        ctx = ngc.ngc_create(12, 12, [0, 1, 3], 4)
+        ngc.ngc_build_code(ctx, ngc.NGC_CODE_CYCLIC, seed)
+        B = [ngc.ngc_get_code(ctx, u, 12) for u in range(3)]
+        ngc.ngc_destroy(ctx)
+        return B
+    a, b, c = built(5), built(5), built(6)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    assert not np.array_equal(a[2], c[2])
+
+
+def test_built_fracrep_code(ngc):
+    ctx = ngc.ngc_create(8, 8, [0, 1, 3, 7], 4)
+    try:
+        ngc.ngc_build_code(ctx, ngc.NGC_CODE_FRACREP, 0)
+        for u, sigma in enumerate([0, 1, 3, 7]):
+            assert np.array_equal(ngc.ngc_get_code(ctx, u, 8), codes.fracrep_code(8, sigma))
+    finally:
+        ngc.ngc_destroy(ctx)
+    ctx = ngc.ngc_create(20, 20, [0, 1, 4], 4)
+    try:
+        with pytest.raises(ngc.NgcError) as e:
+            ngc.ngc_build_code(ctx, ngc.NGC_CODE_FRACREP, 0)       # 2 does not divide 5
+        assert e.value.code == ngc.NGC_ERR_INVALID
+        with pytest.raises(ngc.NgcError):
+            ngc.ngc_build_code(ctx, 9, 0)
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
+def test_select_matches_golden_fracrep_case_for_all_16_masks(ngc):
+    ctx = ngc.ngc_create(4, 4, [0, 1], 4)
+    try:
+        ngc.ngc_build_code(ctx, ngc.NGC_CODE_FRACREP, 0)
+        gold = {}
+        with open(os.path.join(ROOT, "tests", "golden", "fracrep_n4.txt")) as f:
+            for line in f:
+                if line.startswith("#") or not line.strip():
+                    continue
+                tok = line.split()
+                gold[tok[0]] = (int(tok[1]), [float(t) for t in tok[2:6]])
+        ok = bad = 0
+        for bits in range(16):
+            m = np.array([(bits >> i) & 1 for i in range(4)], np.uint8)
+            key = "".join(str(int(b)) for b in m)
+            if key in gold:
+                u, a, r = ngc.ngc_select_decode_vec(ctx, m, 4)
+                assert u == gold[key][0]
+                assert np.allclose(a, gold[key][1], atol=1e-12)
+                assert r < 1e-12
+                ok += 1
+            else:
+                with pytest.raises(ngc.NgcError) as e:
+                    ngc.ngc_select_decode_vec(ctx, m, 4)
+                assert e.value.code == ngc.NGC_ERR_UNDECODABLE
+                bad += 1
+        assert (ok, bad) == (5, 11)
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
+@pytest.mark.parametrize("n,layers,kind", [(16, [0, 1, 3, 7], "cyclic"), (32, [0, 1, 3, 7, 15], "cyclic"),
+                                           (64, [0, 1, 3, 7, 15, 31], "cyclic"),
+                                           (64, [0, 1, 3, 7, 15, 31], "fracrep"), (20, [0, 1, 4, 9], "cyclic")])
+def test_select_agrees_with_oracle_on_random_masks(ngc, n, layers, kind):
+    Bs = codes.nested_code(n, layers, kind, seed=0, draws=2)
+    ctx = ngc.ngc_create(n, n, layers, 4)
+    try:
+        for u, B in enumerate(Bs):
+            ngc.ngc_set_code(ctx, u, B)
+        rng = np.random.default_rng(n)
+        for t in range(60):
+            s = int(rng.integers(0, layers[-1] + 3))
+            m = np.zeros(n, np.uint8)
+            m[rng.choice(n, size=min(s, n), replace=False)] = 1
+            try:
+                u_o = coding.select_layer(layers, m)
+            except coding.Undecodable:
+                with pytest.raises(ngc.NgcError) as e:
+                    ngc.ngc_select_decode_vec(ctx, m, n)
+                assert e.value.code == ngc.NGC_ERR_UNDECODABLE
+                continue
+            u, a, r = ngc.ngc_select_decode_vec(ctx, m, n)
+            a_o, r_o = coding.decode_vector(Bs[u_o], m)
+            assert u == u_o
+            assert np.array_equal(a != 0, a_o != 0)                    # support: exact
+            assert np.all(a[m == 1] == 0)
+            assert r < 1e-8
+            scale = max(1.0, np.abs(a_o).max())
+            assert np.abs(a - a_o).max() <= 1e-7 * scale
+            # first-responders rule
+            u1, a1, r1 = ngc.ngc_select_decode_vec_first(ctx, m, n)
+            if kind == "cyclic":
+                a1_o, _ = coding.decode_vector_first(Bs[u_o], layers[u_o], m)
+                assert u1 == u_o and r1 < 1e-8
+                assert np.abs(a1 - a1_o).max() <= 1e-7 * max(1.0, np.abs(a1_o).max())
+                assert np.count_nonzero(a1) <= n - layers[u_o]
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
+def test_select_reports_singular_for_a_matrix_that_is_no_gradient_code(ngc):
+    n = 6
+    ctx = ngc.ngc_create(n, n, [0, 2], 4)
+    try:
+        B = np.eye(n)
+        for i in range(n):
+            B[i, (i + 1) % n] = 2.0
+            B[i, (i + 2) % n] = -1.0 - i      # rows do not span the all-ones row once two are missing
+        ngc.ngc_set_code(ctx, 1, B)
+        m = np.zeros(n, np.uint8)
+        m[[0, 3]] = 1
+        with pytest.raises(ngc.NgcError) as e:
+            ngc.ngc_select_decode_vec(ctx, m, n)
+        assert e.value.code == ngc.NGC_ERR_SINGULAR
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
+def test_null_arguments_are_rejected_not_dereferenced(ngc):
+    ctx = ngc.ngc_create(4, 4, [0, 1], 8)
+    try:
+        lib = ngc._lib
+        assert lib.ngc_set_code(ctx, 1, None) == ngc.NGC_ERR_INVALID
+        assert lib.ngc_select_decode_vec(ctx, None, None, None, None) == ngc.NGC_ERR_INVALID
+        assert lib.ngc_partition_grads(ctx, 0, None, None, None, 4, None) == ngc.NGC_ERR_INVALID
+        assert lib.ngc_encode(ctx, None, -1, None) == ngc.NGC_ERR_INVALID
+        assert lib.ngc_decode(ctx, 0, None, None, None) == ngc.NGC_ERR_INVALID
+        assert lib.ngc_update(ctx, None, None, 0.1) == ngc.NGC_ERR_INVALID
+        assert "null" in ngc.ngc_last_error(ctx)
+        assert ngc.ngc_strerror(-2).startswith("more stragglers")
+    finally:
+        ngc.ngc_destroy(ctx)

@@ -37,8 +37,8 @@ def test_cyclic_nested_code_satisfies_def1_and_def2(n, layers):
         # Def. 1: any n-sigma rows span an (n-sigma)-dim space containing 1
         for out in itertools.combinations(range(n), sigma):
             S = [i for i in range(n) if i not in out]
-            assert np.linalg.matrix_rank(B[S]) == n - sigma
-            assert np.linalg.matrix_rank(np.vstack([B[S], np.ones(n)])) == n - sigma
+            assert np.linalg.matrix_rank(B[S], tol=1e-9) == n - sigma
+            assert np.linalg.matrix_rank(np.vstack([B[S], np.ones(n)]), tol=1e-9) == n - sigma
         # every straggler set of size <= sigma decodes: a B = 1, supp(a) in responders
         for m in _masks(n, sigma):
             a, resid = coding.decode_vector(B, m)
