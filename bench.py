@@ -26,6 +26,25 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def measured_traffic(workload_name):
+    """HBM bytes per launch of the gradient kernel from the committed rocprofv3 counter summary,
+    or None if the kernel source has changed since those counters were taken."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "grad_stream_%s.txt" % workload_name)
+    src = os.path.join(ROOT, "paper_2212_08580_amd", "csrc", "ngc_device.hip")
+    try:
+        sha = hashlib.sha256(open(src, "rb").read()).hexdigest()
+        text = open(path).read()
+    except OSError:
+        return None
+    if ("ngc_device.hip: " + sha) not in text:
+        return None
+    for line in text.splitlines():
+        if line.startswith("traffic-bytes-per-launch:"):
+            return float(line.split(":")[1])
+    return None
+
+
 def cpu_baseline(w, wl, parts_host, theta, masks, budget_parts):
     """The fp64 checker timed on the host cores over a bounded sample of the same
     workload: `budget_parts` partitions for the gradients, then encode of all
@@ -69,7 +88,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-parts", type=int, default=16)
+    ap.add_argument("--no-probe", action="store_true")
+    ap.add_argument("--cpu-parts", type=int, default=32)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: nested gradient coding here simulates all n workers on "
@@ -152,7 +172,8 @@ def main():
     grad_bytes = 4.0 * w.m * w.d + 4.0 * w.m + 4.0 * w.d + 4.0 * w.n * w.d
     achieved = grad_bytes / (grad_avg_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(w.name),
+                "algorithmic_bytes": grad_bytes,
                 "kernel": "grad_stream_kernel", "avg_ms": round(grad_avg_ms, 4),
                 "launches": grad_launches}
     enc_ms = prof["encode"][1] / max(1, prof["encode"][0])
@@ -167,6 +188,23 @@ def main():
         "update_ms": round(prof["update"][1] / max(1, prof["update"][0]), 4),
     }
 
+    # ---- context figures outside the timed region: what a trivial kernel reaches ---------------
+    ceiling = None
+    if not args.no_probe:
+        ngc.ngc_profile_enable(ctx, True)
+        for _ in range(3):
+            ngc.ngc_probe_read(ctx, Xd, Xd.numel() * 4)
+        n_read, ms_read = ngc.ngc_profile_read(ctx)["probe"]
+        scratch = torch.empty(1 << 28, dtype=torch.float32, device=dev)          # 1 GiB
+        nb = min(scratch.numel(), Xd[0].numel()) * 4
+        for _ in range(3):
+            ngc.ngc_probe_copy(ctx, Xd[0], scratch, nb)
+        n_copy, ms_copy = ngc.ngc_profile_read(ctx)["probe"]
+        ngc.ngc_profile_enable(ctx, False)
+        del scratch
+        ceiling = {"plain_read_GBps": round(Xd.numel() * 4 * n_read / (ms_read * 1e-3) / 1e9, 1),
+                   "plain_copy_GBps_read_plus_write": round(2 * nb * n_copy / (ms_copy * 1e-3) / 1e9, 1)}
+
     out = {
         "metric": "partition-gradient samples/s + encode/decode GB/s vs HBM peak, n=32 d=4096",
         "value": round(w.m * K / elapsed, 1), "unit": "samples/s", "n_gpus": 1, "steps": K,
@@ -175,7 +213,7 @@ def main():
         "config": {"workload": w.name, "loss": "lsq" if w.loss == 0 else "logistic", "n": w.n,
                    "rows_per_partition": w.rows, "d": w.d, "layers": list(w.layers),
                    "p_straggle": w.p_straggle},
-        "roofline": roofline, "stages": stages,
+        "roofline": roofline, "stages": stages, "hbm_probe": ceiling,
     }
     if not args.no_cpu_baseline:
         ngc.ngc_sync(ctx)

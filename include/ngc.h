@@ -58,7 +58,8 @@ enum {
     NGC_KERNEL_DECODE = 3,
     NGC_KERNEL_UPDATE = 4,
     NGC_KERNEL_MLP = 5,     /* all GEMM-shaped kernels of the MLP gradient                  */
-    NGC_KERNEL_COUNT = 6
+    NGC_KERNEL_PROBE = 6,   /* ngc_probe_copy / ngc_probe_read                              */
+    NGC_KERNEL_COUNT = 7
 };
 
 /*
@@ -119,8 +120,9 @@ int ngc_set_mlp2_shape(ngc_ctx* ctx, int d_in, int hidden, int classes);
  *                      y_dev: int32 class ids [k][rows]
  * X_dev: float [k][rows_per_part][d_in] row-major (d_in = d for the first two
  * losses), 16-byte aligned.  theta_dev: float [d].  G_dev: float [k][d], fully
- * overwritten.  Each row of X is read from HBM exactly once when d is a
- * multiple of 256 and at most 4096; other d take a two-pass route.
+ * overwritten.  Each row of X is read from HBM exactly once when d is 256, 512,
+ * 768 or 1024*w with w in {1,2,3,4,6,8,12,16}; other d take a two-pass route
+ * that reads X twice.
  * Accumulation is fp32 with a fixed summation order (bit-reproducible).
  */
 int ngc_partition_grads(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_dev,
@@ -179,6 +181,17 @@ int ngc_sync(ngc_ctx* ctx);
  */
 int ngc_profile_enable(ngc_ctx* ctx, int on);
 int ngc_profile_read(ngc_ctx* ctx, int64_t* launches_out, double* total_ms_out);
+
+/*
+ * Measurement aids, not part of the method.  ngc_probe_copy copies `bytes`
+ * (a multiple of 16, both pointers 16-byte aligned, buffers must not overlap)
+ * with a plain kernel: a dispatch of known HBM traffic against which byte
+ * counters can be calibrated.  ngc_probe_read streams `bytes` once through a
+ * plain read-and-add kernel: the read bandwidth a trivial kernel reaches.
+ * Both are recorded under NGC_KERNEL_PROBE when profiling is on.
+ */
+int ngc_probe_copy(ngc_ctx* ctx, const void* src_dev, void* dst_dev, int64_t bytes);
+int ngc_probe_read(ngc_ctx* ctx, const void* src_dev, int64_t bytes);
 
 const char* ngc_strerror(int code);
 const char* ngc_last_error(const ngc_ctx* ctx);

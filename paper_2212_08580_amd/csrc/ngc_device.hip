@@ -331,6 +331,39 @@ __global__ __launch_bounds__(256) void update_kernel(float* __restrict__ theta,
     if (c < d) theta[c] = theta[c] - scale * g[c];
 }
 
+// ---------------------------------------------------------------------------
+// Measurement probes (not part of the method): a plain copy and a plain read of
+// a known number of bytes, used to calibrate HBM byte counters and to find the
+// read bandwidth a trivial kernel reaches on the same buffers.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void probe_copy_kernel(const v4f* __restrict__ src,
+                                                         v4f* __restrict__ dst, int64_t nvec) {
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += stride)
+        dst[i] = __builtin_nontemporal_load(src + i);
+}
+
+__global__ __launch_bounds__(256) void probe_read_kernel(const v4f* __restrict__ src,
+                                                         float* __restrict__ sink, int64_t nvec) {
+    // every block reads a contiguous run, 8 independent 16-byte loads per thread in flight
+    const int64_t per_block = (nvec + gridDim.x - 1) / gridDim.x;
+    const int64_t b0 = (int64_t)blockIdx.x * per_block;
+    const int64_t b1 = b0 + per_block < nvec ? b0 + per_block : nvec;
+    v4f acc = (v4f)(0.0f);
+    int64_t i = b0 + threadIdx.x;
+    for (; i + 7 * 256 < b1; i += 8 * 256) {
+        v4f t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = __builtin_nontemporal_load(src + i + u * 256);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += t[u];
+    }
+    for (; i < b1; i += 256) acc += __builtin_nontemporal_load(src + i);
+    float s = wave_sum((acc.x + acc.y) + (acc.z + acc.w));
+    if ((threadIdx.x & 63) == 0) sink[blockIdx.x * 4 + (threadIdx.x >> 6)] = s;
+}
+
+
 // ===========================================================================
 // host-side launchers
 // ===========================================================================
@@ -722,6 +755,43 @@ extern "C" int ngc_update(ngc_ctx* ctx, float* theta_dev, const float* g_dev, do
         prof_scope ps(ctx, NGC_KERNEL_UPDATE);
         hipLaunchKernelGGL(update_kernel, dim3((unsigned)((ctx->d + 255) / 256)), dim3(256), 0, ctx->stream,
                            theta_dev, g_dev, (float)scale, ctx->d);
+    }
+    NGC_HIP(ctx, hipGetLastError());
+    return NGC_OK;
+}
+
+// ---- measurement probes -----------------------------------------------------
+extern "C" int ngc_probe_copy(ngc_ctx* ctx, const void* src_dev, void* dst_dev, int64_t bytes) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (!src_dev || !dst_dev || bytes < 16 || bytes % 16 || !aligned16(src_dev) || !aligned16(dst_dev))
+        return ngc_fail(ctx, NGC_ERR_INVALID, "probe buffers must be 16-byte aligned, size a multiple of 16");
+    int rc = dev_init(ctx);
+    if (rc) return rc;
+    const int64_t nvec = bytes / 16;
+    const int64_t blocks = std::min<int64_t>((nvec + 255) / 256, (int64_t)ctx->cu_count * 16);
+    {
+        prof_scope ps(ctx, NGC_KERNEL_PROBE);
+        hipLaunchKernelGGL(probe_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream,
+                           (const v4f*)src_dev, (v4f*)dst_dev, nvec);
+    }
+    NGC_HIP(ctx, hipGetLastError());
+    return NGC_OK;
+}
+
+extern "C" int ngc_probe_read(ngc_ctx* ctx, const void* src_dev, int64_t bytes) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (!src_dev || bytes < 16 || bytes % 16 || !aligned16(src_dev))
+        return ngc_fail(ctx, NGC_ERR_INVALID, "probe buffer must be 16-byte aligned, size a multiple of 16");
+    int rc = dev_init(ctx);
+    if (rc) return rc;
+    const int64_t nvec = bytes / 16;
+    const int64_t blocks = std::min<int64_t>((nvec + 255) / 256, (int64_t)ctx->cu_count * 8);
+    rc = ensure_ws(ctx, sizeof(float) * 4 * (size_t)blocks);
+    if (rc) return rc;
+    {
+        prof_scope ps(ctx, NGC_KERNEL_PROBE);
+        hipLaunchKernelGGL(probe_read_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream,
+                           (const v4f*)src_dev, ctx->d_ws, nvec);
     }
     NGC_HIP(ctx, hipGetLastError());
     return NGC_OK;

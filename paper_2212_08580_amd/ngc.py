@@ -26,14 +26,15 @@ NGC_ERR_STATE = -6
 
 NGC_LOSS_LSQ, NGC_LOSS_LOGISTIC, NGC_LOSS_MLP2 = 0, 1, 2
 NGC_CODE_CYCLIC, NGC_CODE_FRACREP = 0, 1
-NGC_KERNEL_NAMES = ("grad", "reduce", "encode", "decode", "update", "mlp")
+NGC_KERNEL_NAMES = ("grad", "reduce", "encode", "decode", "update", "mlp", "probe")
 NGC_KERNEL_COUNT = len(NGC_KERNEL_NAMES)
 
 EXPORTS = (
     "ngc_create", "ngc_destroy", "ngc_set_code", "ngc_get_code", "ngc_build_code",
     "ngc_set_mlp2_shape", "ngc_partition_grads", "ngc_encode", "ngc_select_decode_vec",
     "ngc_select_decode_vec_first", "ngc_decode", "ngc_update", "ngc_sync",
-    "ngc_profile_enable", "ngc_profile_read", "ngc_strerror", "ngc_last_error",
+    "ngc_profile_enable", "ngc_profile_read", "ngc_probe_copy", "ngc_probe_read",
+    "ngc_strerror", "ngc_last_error",
 )
 
 if not os.path.exists(LIB_PATH):
@@ -61,6 +62,8 @@ _lib.ngc_update.argtypes = [_vp, _vp, _vp, _dbl]
 _lib.ngc_sync.argtypes = [_vp]
 _lib.ngc_profile_enable.argtypes = [_vp, _i]
 _lib.ngc_profile_read.argtypes = [_vp, _vp, _vp]
+_lib.ngc_probe_copy.argtypes = [_vp, _vp, _vp, _i64]
+_lib.ngc_probe_read.argtypes = [_vp, _vp, _i64]
 _lib.ngc_strerror.argtypes = [_i]
 _lib.ngc_strerror.restype = ctypes.c_char_p
 _lib.ngc_last_error.argtypes = [_vp]
@@ -177,6 +180,14 @@ def ngc_update(ctx, theta, g, scale):
 
 def ngc_sync(ctx):
     _check(_lib.ngc_sync(ctx), ctx)
+
+
+def ngc_probe_copy(ctx, src, dst, nbytes):
+    _check(_lib.ngc_probe_copy(ctx, _dev(src), _dev(dst), int(nbytes)), ctx)
+
+
+def ngc_probe_read(ctx, src, nbytes):
+    _check(_lib.ngc_probe_read(ctx, _dev(src), int(nbytes)), ctx)
 
 
 def ngc_profile_enable(ctx, on):
