@@ -61,7 +61,7 @@ def cpu_baseline(w, wl, parts_host, theta, masks, budget_parts):
     t0 = time.perf_counter()
     rows = []
     for X, Y in parts_host[:budget_parts]:
-        rows.append(gradients.partial_gradients(w.loss, X[None], Y[None], theta)[0])
+        rows.append(gradients.partial_gradients(w.loss, X[None], Y[None], theta, w.hidden, w.classes)[0])
     t_grad = time.perf_counter() - t0
     G = np.stack(rows + [rows[-1]] * (w.n - len(rows)))      # pad to n rows for the coding steps
     t1 = time.perf_counter()
@@ -106,17 +106,18 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     w = wl.CONFIGS[args.workload]
-    if w.loss not in (wl.LOSS_LSQ, wl.LOSS_LOGISTIC):
-        print("bench.py times the regression workloads (C1, C2, C3)", file=sys.stderr)
+    if w.loss not in (wl.LOSS_LSQ, wl.LOSS_LOGISTIC, wl.LOSS_MLP2):
+        print("bench.py times the gradient workloads (C1, C2, C3, C4)", file=sys.stderr)
         sys.exit(2)
+    is_mlp = w.loss == wl.LOSS_MLP2
     K, W = args.steps, args.warmup
     L = len(w.layers)
 
     # ---- inputs: generated per partition on the host, uploaded once -------------------------
     t0 = time.perf_counter()
     Xd = torch.empty((w.n, w.rows, w.d_in), dtype=torch.float32, device=dev)
-    Yd = torch.empty((w.n, w.rows), dtype=torch.float32, device=dev)
-    truth = wl.truth_vector(w, 0)
+    Yd = torch.empty((w.n, w.rows), dtype=torch.int32 if is_mlp else torch.float32, device=dev)
+    truth = None if is_mlp else wl.truth_vector(w, 0)
     keep = []
     from concurrent.futures import ThreadPoolExecutor
     with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
@@ -137,6 +138,8 @@ def main():
     stream = torch.cuda.current_stream().cuda_stream
     ctx = ngc.ngc_create(w.n, w.n, w.layers, w.d, stream)
     ngc.ngc_build_code(ctx, ngc.NGC_CODE_CYCLIC if w.code == wl.CODE_CYCLIC else ngc.NGC_CODE_FRACREP, 0)
+    if is_mlp:
+        ngc.ngc_set_mlp2_shape(ctx, w.d_in, w.hidden, w.classes)
     G = torch.empty((w.n, w.d), dtype=torch.float32, device=dev)
     C = torch.empty((L, w.n, w.d), dtype=torch.float32, device=dev)
     g = torch.empty(w.d, dtype=torch.float32, device=dev)
@@ -153,7 +156,7 @@ def main():
     for t in range(W):
         step(t)
     torch.cuda.synchronize()
-    ngc.ngc_profile_enable(ctx, True)
+    ngc.ngc_profile_enable(ctx, ["mlp" if is_mlp else "grad"])   # events around the dominant part only
     resp = 0
     t0 = time.perf_counter()
     for t in range(W, W + K):
@@ -162,24 +165,45 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     prof = ngc.ngc_profile_read(ctx)
-    ngc.ngc_profile_enable(ctx, False)
     ms_per_step = elapsed / K * 1e3
+    # the small kernels are timed in a pass of their own, after the timed region
+    ngc.ngc_profile_enable(ctx, True)
+    for t in range(W, W + min(K, 10)):
+        step(t)
+    prof_small = ngc.ngc_profile_read(ctx)
+    ngc.ngc_profile_enable(ctx, False)
+    for name in ("grad", "mlp", "reduce", "encode", "decode", "update"):
+        if prof[name][0] == 0:
+            prof[name] = prof_small[name]
+    resp_per_step = resp / K
 
-    # ---- roofline of the dominant kernel (the single-pass gradient kernel) -------------------
-    grad_launches, grad_ms = prof["grad"]
-    grad_avg_ms = grad_ms / max(1, grad_launches)
-    # algorithmic bytes per launch: X once + labels + theta + G  (4*d bytes per sample)
-    grad_bytes = 4.0 * w.m * w.d + 4.0 * w.m + 4.0 * w.d + 4.0 * w.n * w.d
-    achieved = grad_bytes / (grad_avg_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(w.name),
-                "algorithmic_bytes": grad_bytes,
-                "kernel": "grad_stream_kernel", "avg_ms": round(grad_avg_ms, 4),
-                "launches": grad_launches}
+    # ---- roofline of the dominant kernel -------------------------------------------------------
+    if is_mlp:
+        # the two fp32 MFMA GEMMs (forward layer 1 and dW1) carry 98 % of the flops; timed here is
+        # the whole gradient call (GEMM, head pass, tail reduce, GEMM)
+        grad_launches, grad_ms = prof["mlp"]
+        grad_avg_ms = grad_ms / max(1, grad_launches)
+        flops = w.m * (2.0 * w.d_in * w.hidden * 2 + 2.0 * w.hidden * w.classes * 3)
+        achieved = flops / (grad_avg_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": 157.3, "unit": "TFLOP/s",
+                    "frac": round(achieved / 157.3, 4), "traffic": None, "algorithmic_flops": flops,
+                    "kernel": "mlp_gemm_kernel (whole MLP gradient call)", "avg_ms": round(grad_avg_ms, 4),
+                    "launches": grad_launches}
+    else:
+        grad_launches, grad_ms = prof["grad"]
+        grad_avg_ms = grad_ms / max(1, grad_launches)
+        # algorithmic bytes per launch: X once + labels + theta + G  (4*d bytes per sample)
+        grad_bytes = 4.0 * w.m * w.d + 4.0 * w.m + 4.0 * w.d + 4.0 * w.n * w.d
+        achieved = grad_bytes / (grad_avg_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(w.name),
+                    "algorithmic_bytes": grad_bytes,
+                    "kernel": "grad_stream_kernel", "avg_ms": round(grad_avg_ms, 4),
+                    "launches": grad_launches}
     enc_ms = prof["encode"][1] / max(1, prof["encode"][0])
     dec_ms = prof["decode"][1] / max(1, prof["decode"][0])
     enc_bytes = 4.0 * w.n * w.d * (1 + L)
-    dec_bytes = 4.0 * w.d * (resp / K + 1)
+    dec_bytes = 4.0 * w.d * (resp_per_step + 1)
     stages = {
         "grad_samples_per_s": round(w.m / (grad_avg_ms * 1e-3), 1),
         "reduce_ms": round(prof["reduce"][1] / max(1, prof["reduce"][0]), 4),
@@ -210,7 +234,7 @@ def main():
         "value": round(w.m * K / elapsed, 1), "unit": "samples/s", "n_gpus": 1, "steps": K,
         "warmup": W, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w.name, "loss": "lsq" if w.loss == 0 else "logistic", "n": w.n,
+        "config": {"workload": w.name, "loss": ("lsq", "logistic", "mlp2")[w.loss], "n": w.n,
                    "rows_per_partition": w.rows, "d": w.d, "layers": list(w.layers),
                    "p_straggle": w.p_straggle},
         "roofline": roofline, "stages": stages, "hbm_probe": ceiling,

@@ -173,13 +173,14 @@ int ngc_update(ngc_ctx* ctx, float* theta_dev, const float* g_dev, double scale)
 int ngc_sync(ngc_ctx* ctx);
 
 /*
- * Per-kernel timing.  With profiling on, each kernel launch is bracketed by
- * HIP events on the context's stream.  ngc_profile_read() synchronises, adds
- * the elapsed times up per kernel id, writes launch counts and total
- * milliseconds (arrays of NGC_KERNEL_COUNT) and clears the record.  At most
- * 4096 launches are recorded between reads; later ones run untimed.
+ * Per-kernel timing.  kernel_mask selects the kernel ids to time (bit k =
+ * NGC_KERNEL_k, -1 = all, 0 = off); each launch of a selected kernel is
+ * bracketed by HIP events on the context's stream.  ngc_profile_read()
+ * synchronises, adds the elapsed times up per kernel id, writes launch counts
+ * and total milliseconds (arrays of NGC_KERNEL_COUNT) and clears the record.
+ * At most 4096 launches are recorded between reads; later ones run untimed.
  */
-int ngc_profile_enable(ngc_ctx* ctx, int on);
+int ngc_profile_enable(ngc_ctx* ctx, int kernel_mask);
 int ngc_profile_read(ngc_ctx* ctx, int64_t* launches_out, double* total_ms_out);
 
 /*

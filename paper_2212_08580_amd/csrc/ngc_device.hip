@@ -416,7 +416,7 @@ struct prof_scope {
     ngc_ctx* ctx;
     int rec = -1;
     prof_scope(ngc_ctx* c, int kernel) : ctx(c) {
-        if (!c->profiling || c->prof.size() >= (size_t)NGC_MAX_PROFILE) return;
+        if (!((c->profile_mask >> kernel) & 1u) || c->prof.size() >= (size_t)NGC_MAX_PROFILE) return;
         ngc_profile_rec r;
         r.kernel = kernel;
         auto get = [&](hipEvent_t& e) {
@@ -442,9 +442,9 @@ struct prof_scope {
 };
 }  // namespace
 
-extern "C" int ngc_profile_enable(ngc_ctx* ctx, int on) {
+extern "C" int ngc_profile_enable(ngc_ctx* ctx, int kernel_mask) {
     if (!ctx) return NGC_ERR_INVALID;
-    ctx->profiling = on != 0;
+    ctx->profile_mask = (unsigned)kernel_mask;
     return NGC_OK;
 }
 

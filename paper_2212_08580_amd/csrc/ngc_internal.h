@@ -49,7 +49,7 @@ struct ngc_ctx {
     float* d_ws = nullptr;           // workspace: block partials / residuals / MLP activations
     size_t d_ws_bytes = 0;
 
-    bool profiling = false;
+    unsigned profile_mask = 0;       // bit k: time launches of kernel id k
     std::vector<ngc_profile_rec> prof;
     std::vector<hipEvent_t> event_pool;
 

@@ -1,7 +1,431 @@
-// Partition gradients of the 2-layer perceptron (placeholder until the MFMA
-// route is in place: reports that the loss is not available).
+// Partition gradients of the 2-layer perceptron (softmax cross-entropy of
+// relu(x W1 + b1) W2 + b2), the third loss of ngc_partition_grads: the partial
+// gradient g_j of Sec. II-C for each row block j, a plain sum over its rows.
+//
+// Three device steps, all partitions at once:
+//   1. H = relu(X W1 + b1)                 fp32 MFMA GEMM, bias + ReLU in the epilogue
+//   2. per row: Z2 = H W2 + b2, P = softmax(Z2), dZ2 = P - onehot(label);
+//      dW2 += H^T dZ2, db2 += dZ2; dZ1 = (dZ2 W2^T) * [H > 0] written over H;
+//      db1 += dZ1                          one pass over H, block partials
+//   3. dW1_j = X_j^T dZ1_j                 fp32 MFMA GEMM per partition, written into G
+// and a fixed-order sum of the block partials of step 2 into the tail of G.
+//
+// MFMA tile: v_mfma_f32_32x32x2_f32.  A block of 4 waves computes a 128 x 128
+// tile of the output, each wave 64 x 64 as 2 x 2 MFMA blocks; operand tiles are
+// staged in LDS k-major ([k][m] and [k][n]) so that the 32 lanes that feed one
+// MFMA column read consecutive words.  Within a wave, MFMA block bm holds the
+// tile rows 2*i + bm (i = MFMA row), so a lane fetches its two A values (and two
+// B values) with one 8-byte LDS read and stores two adjacent output columns.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <string>
+
 #include "ngc_internal.h"
 
-int ngc_mlp2_grads(ngc_ctx* ctx, const float*, const int*, const float*, int64_t, float*) {
-    return ngc_fail(ctx, NGC_ERR_STATE, "NGC_LOSS_MLP2 is not available in this build");
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+
+#define NGC_HIP(ctx, call)                                                                  \
+    do {                                                                                    \
+        hipError_t e_ = (call);                                                             \
+        if (e_ != hipSuccess)                                                               \
+            return ngc_fail(ctx, NGC_ERR_HIP, std::string(#call) + ": " + hipGetErrorString(e_)); \
+    } while (0)
+
+namespace {
+
+constexpr int BM = 128, BN = 128, BK = 16;
+constexpr int LDT = BM + 4;  // LDS row stride in floats (BM == BN)
+
+enum { EPI_STORE = 0, EPI_BIAS_RELU = 1 };
+
+// 4 consecutive elements starting at p[0], of which `left` are inside the matrix
+__device__ __forceinline__ v4f load4(const float* __restrict__ p, int64_t left, bool vec_ok) {
+    v4f v = (v4f)(0.0f);
+    if (left >= 4 && vec_ok) {
+        v = *reinterpret_cast<const v4f*>(p);
+    } else {
+        if (left > 0) v.x = p[0];
+        if (left > 1) v.y = p[1];
+        if (left > 2) v.z = p[2];
+        if (left > 3) v.w = p[3];
+    }
+    return v;
+}
+
+// C[M x N] = A * B (+ epilogue), batched over blockIdx.z.
+//   A_KMAJOR: A is stored [K][M] (element (m,k) at A[k*lda + m]); else [M][K].
+//   B is stored [K][N].  C is stored [M][N].
+template <bool A_KMAJOR, int EPI>
+__global__ __launch_bounds__(256) void mlp_gemm_kernel(
+    const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C,
+    const float* __restrict__ bias, int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
+    int64_t strideA, int64_t strideB, int64_t strideC, int a_vec_ok, int b_vec_ok, int c_vec_ok) {
+    __shared__ float As[2][BK][LDT];
+    __shared__ float Bs[2][BK][LDT];
+    const int t = threadIdx.x;
+    const int lane = t & 63;
+    const int wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    A += (int64_t)blockIdx.z * strideA;
+    B += (int64_t)blockIdx.z * strideB;
+    C += (int64_t)blockIdx.z * strideC;
+
+    v16f acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    v4f ra[2], rb[2];
+    auto gload = [&](int k0) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int idx = t + h * 256;
+            if (A_KMAJOR) {
+                const int k = idx >> 5, m4 = (idx & 31) * 4;
+                const int gk = k0 + k, gm = m0 + m4;
+                ra[h] = (gk < K) ? load4(A + (int64_t)gk * lda + gm, (int64_t)M - gm, a_vec_ok) : (v4f)(0.0f);
+            } else {
+                const int m = idx >> 2, k4 = (idx & 3) * 4;
+                const int gm = m0 + m, gk = k0 + k4;
+                ra[h] = (gm < M) ? load4(A + (int64_t)gm * lda + gk, (int64_t)K - gk, a_vec_ok) : (v4f)(0.0f);
+            }
+            const int k = idx >> 5, n4 = (idx & 31) * 4;
+            const int gk = k0 + k, gn = n0 + n4;
+            rb[h] = (gk < K) ? load4(B + (int64_t)gk * ldb + gn, (int64_t)N - gn, b_vec_ok) : (v4f)(0.0f);
+        }
+    };
+    auto sstore = [&](int buf) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int idx = t + h * 256;
+            if (A_KMAJOR) {
+                const int k = idx >> 5, m4 = (idx & 31) * 4;
+                *reinterpret_cast<v4f*>(&As[buf][k][m4]) = ra[h];
+            } else {
+                const int m = idx >> 2, k4 = (idx & 3) * 4;
+                As[buf][k4 + 0][m] = ra[h].x;
+                As[buf][k4 + 1][m] = ra[h].y;
+                As[buf][k4 + 2][m] = ra[h].z;
+                As[buf][k4 + 3][m] = ra[h].w;
+            }
+            const int k = idx >> 5, n4 = (idx & 31) * 4;
+            *reinterpret_cast<v4f*>(&Bs[buf][k][n4]) = rb[h];
+        }
+    };
+
+    const int nk = (K + BK - 1) / BK;
+    gload(0);
+    sstore(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) gload((kt + 1) * BK);
+#pragma unroll
+        for (int kk = 0; kk < BK / 2; ++kk) {
+            const int k = 2 * kk + lhi;
+            const v2f a2 = *reinterpret_cast<const v2f*>(&As[buf][k][wm * 64 + 2 * l32]);
+            const v2f b2 = *reinterpret_cast<const v2f*>(&Bs[buf][k][wn * 64 + 2 * l32]);
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.x, b2.x, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.x, b2.y, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.y, b2.x, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.y, b2.y, acc[1][1], 0, 0, 0);
+        }
+        if (kt + 1 < nk) sstore(buf ^ 1);
+        __syncthreads();
+    }
+
+    // MFMA 32x32 result layout: register r of lane l is element (row, col) with
+    // col = l % 32 and row = (r / 4) * 8 + (l / 32) * 4 + r % 4.
+    const int gn = n0 + wn * 64 + 2 * l32;
+    float bias0 = 0.0f, bias1 = 0.0f;
+    if (EPI == EPI_BIAS_RELU) {
+        if (gn < N) bias0 = bias[gn];
+        if (gn + 1 < N) bias1 = bias[gn + 1];
+    }
+#pragma unroll
+    for (int bm = 0; bm < 2; ++bm) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int i = (r >> 2) * 8 + lhi * 4 + (r & 3);
+            const int gm = m0 + wm * 64 + 2 * i + bm;
+            if (gm >= M) continue;
+            float v0 = acc[bm][0][r], v1 = acc[bm][1][r];
+            if (EPI == EPI_BIAS_RELU) {
+                v0 = fmaxf(v0 + bias0, 0.0f);
+                v1 = fmaxf(v1 + bias1, 0.0f);
+            }
+            float* out = C + (int64_t)gm * ldc + gn;
+            if (gn + 1 < N && c_vec_ok) {
+                v2f v;
+                v.x = v0;
+                v.y = v1;
+                *reinterpret_cast<v2f*>(out) = v;
+            } else {
+                if (gn < N) out[0] = v0;
+                if (gn + 1 < N) out[1] = v1;
+            }
+        }
+    }
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_step(float v) {
+    int iv = __builtin_bit_cast(int, v);
+    int sh = __builtin_amdgcn_update_dpp(iv, iv, CTRL, 0xF, 0xF, false);
+    return v + __builtin_bit_cast(float, sh);
+}
+__device__ __forceinline__ float wave_sum(float v) {
+    v = dpp_step<0xB1>(v);
+    v = dpp_step<0x4E>(v);
+    v = dpp_step<0x141>(v);
+    v = dpp_step<0x140>(v);
+    int iv = __builtin_bit_cast(int, v);
+    float s0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 0));
+    float s1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 16));
+    float s2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32));
+    float s3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 48));
+    return (s0 + s1) + (s2 + s3);
+}
+
+// Step 2.  A block owns a run of rows of one partition; thread t owns hidden
+// units 4t..4t+3 (hidden <= 1024).  W2's rows for those units, the dW2 and db1
+// accumulators stay in registers.  Per row the 4 waves exchange their partial
+// logits through LDS (one barrier per row, double-buffered area).  NCP is the
+// class count rounded up; classes beyond `classes` get logit -inf.
+// Block partial layout = tail of theta: [db1 (hidden) | dW2 (hidden x classes) | db2 (classes)].
+template <int NCP>
+__global__ __launch_bounds__(256) void mlp_head_kernel(
+    float* __restrict__ H, const int* __restrict__ labels, const float* __restrict__ W2,
+    const float* __restrict__ b2, float* __restrict__ partial, int hidden, int classes,
+    int64_t rows, int chunks, int64_t rows_per_chunk, int h_vec_ok) {
+    __shared__ float ex[2][NCP][4];
+    const int t = threadIdx.x;
+    const int wave = t >> 6;
+    const int j = blockIdx.x / chunks, c = blockIdx.x % chunks;
+    const int64_t r0 = (int64_t)c * rows_per_chunk;
+    const int64_t r1 = rows < r0 + rows_per_chunk ? rows : r0 + rows_per_chunk;
+    const int h0 = 4 * t;
+    const int hleft = hidden - h0;  // may be <= 0
+
+    float w2[4][NCP], dw2[4][NCP], db1[4], db2[NCP], bias2[NCP];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        db1[e] = 0.0f;
+#pragma unroll
+        for (int q = 0; q < NCP; ++q) {
+            w2[e][q] = (e < hleft && q < classes) ? W2[(int64_t)(h0 + e) * classes + q] : 0.0f;
+            dw2[e][q] = 0.0f;
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < NCP; ++q) {
+        db2[q] = 0.0f;
+        bias2[q] = q < classes ? b2[q] : 0.0f;
+    }
+
+    float* Hp = H + ((int64_t)j * rows) * hidden + h0;
+    const int* lp = labels + (int64_t)j * rows;
+    for (int64_t r = r0; r < r1; ++r) {
+        float* hrow = Hp + r * hidden;
+        v4f h = load4(hrow, hleft, h_vec_ok);
+        float hv[4] = {h.x, h.y, h.z, h.w};
+        float z[NCP];
+#pragma unroll
+        for (int q = 0; q < NCP; ++q) {
+            float p = hv[0] * w2[0][q];
+            p += hv[1] * w2[1][q];
+            p += hv[2] * w2[2][q];
+            p += hv[3] * w2[3][q];
+            z[q] = wave_sum(p);
+        }
+        float* e = &ex[r & 1][0][0];
+#pragma unroll
+        for (int q = 0; q < NCP; ++q) e[q * 4 + wave] = z[q];
+        __syncthreads();
+        const int label = lp[r];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int q = 0; q < NCP; ++q) {
+            float s = ((e[q * 4] + e[q * 4 + 1]) + e[q * 4 + 2]) + e[q * 4 + 3] + bias2[q];
+            z[q] = q < classes ? s : -INFINITY;
+            mx = fmaxf(mx, z[q]);
+        }
+        float den = 0.0f;
+#pragma unroll
+        for (int q = 0; q < NCP; ++q) {
+            z[q] = expf(z[q] - mx);
+            den += z[q];
+        }
+        const float inv = 1.0f / den;
+        float dh[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int q = 0; q < NCP; ++q) {
+            const float dz = z[q] * inv - (q == label ? 1.0f : 0.0f);  // dZ2 = P - onehot
+            db2[q] += dz;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                dw2[k][q] += hv[k] * dz;
+                dh[k] += dz * w2[k][q];
+            }
+        }
+        v4f out;
+        out.x = hv[0] > 0.0f ? dh[0] : 0.0f;  // ReLU'(0) = 0
+        out.y = hv[1] > 0.0f ? dh[1] : 0.0f;
+        out.z = hv[2] > 0.0f ? dh[2] : 0.0f;
+        out.w = hv[3] > 0.0f ? dh[3] : 0.0f;
+        db1[0] += out.x;
+        db1[1] += out.y;
+        db1[2] += out.z;
+        db1[3] += out.w;
+        if (hleft >= 4 && h_vec_ok) {
+            *reinterpret_cast<v4f*>(hrow) = out;
+        } else {
+            if (hleft > 0) hrow[0] = out.x;
+            if (hleft > 1) hrow[1] = out.y;
+            if (hleft > 2) hrow[2] = out.z;
+            if (hleft > 3) hrow[3] = out.w;
+        }
+    }
+    const int64_t T = (int64_t)hidden + (int64_t)hidden * classes + classes;
+    float* P = partial + (int64_t)blockIdx.x * T;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (e < hleft) {
+            P[h0 + e] = db1[e];
+#pragma unroll
+            for (int q = 0; q < NCP; ++q)
+                if (q < classes) P[hidden + (int64_t)(h0 + e) * classes + q] = dw2[e][q];
+        }
+    }
+    if (t == 0) {
+#pragma unroll
+        for (int q = 0; q < NCP; ++q)
+            if (q < classes) P[hidden + (int64_t)hidden * classes + q] = db2[q];
+    }
+}
+
+// out[j*out_stride + t] = sum over chunks (in index order) of partial[(j*chunks + c)*T + t]
+__global__ __launch_bounds__(256) void mlp_tail_reduce_kernel(const float* __restrict__ partial,
+                                                              float* __restrict__ out, int64_t T,
+                                                              int chunks, int64_t out_stride) {
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int j = blockIdx.y;
+    if (t >= T) return;
+    const float* p = partial + (int64_t)j * chunks * T + t;
+    float acc = p[0];
+    for (int c = 1; c < chunks; ++c) acc += p[(int64_t)c * T];
+    out[(int64_t)j * out_stride + t] = acc;
+}
+
+struct mlp_prof {
+    ngc_ctx* ctx;
+    hipEvent_t stop = nullptr;
+    bool on = false;
+    explicit mlp_prof(ngc_ctx* c) : ctx(c) {
+        if (!((c->profile_mask >> NGC_KERNEL_MLP) & 1u) || c->prof.size() >= (size_t)NGC_MAX_PROFILE) return;
+        ngc_profile_rec r;
+        r.kernel = NGC_KERNEL_MLP;
+        if (hipEventCreate(&r.start) != hipSuccess) return;
+        if (hipEventCreate(&r.stop) != hipSuccess) {
+            (void)hipEventDestroy(r.start);
+            return;
+        }
+        (void)hipEventRecord(r.start, c->stream);
+        stop = r.stop;
+        c->prof.push_back(r);
+        on = true;
+    }
+    ~mlp_prof() {
+        if (on) (void)hipEventRecord(stop, ctx->stream);
+    }
+};
+
+bool al(const void* p, uintptr_t m) { return (reinterpret_cast<uintptr_t>(p) & (m - 1)) == 0; }
+
+}  // namespace
+
+int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float* theta,
+                   int64_t rows, float* G) {
+    const int k = ctx->n;
+    const int din = ctx->mlp_din, hid = ctx->mlp_hidden, cls = ctx->mlp_classes;
+    const int64_t d = ctx->d;
+    if (hid > 1024) return ngc_fail(ctx, NGC_ERR_INVALID, "MLP hidden width above 1024 is not supported");
+    if (cls > 16) return ngc_fail(ctx, NGC_ERR_INVALID, "MLP with more than 16 classes is not supported");
+    const int64_t total = (int64_t)k * rows;
+    if (total > 0x7fffffffLL) return ngc_fail(ctx, NGC_ERR_INVALID, "too many rows");
+    const float* W1 = theta;
+    const float* b1 = theta + (int64_t)din * hid;
+    const float* W2 = b1 + hid;
+    const float* b2 = W2 + (int64_t)hid * cls;
+    const int64_t T = (int64_t)hid + (int64_t)hid * cls + cls;
+
+    // workspace: H [total][hid] | block partials [k*chunks][T]
+    int64_t chunks = std::max<int64_t>(1, ((int64_t)ctx->cu_count * 2 + k - 1) / k);
+    int64_t rpc = (rows + chunks - 1) / chunks;
+    chunks = (rows + rpc - 1) / rpc;
+    const size_t h_floats = (((size_t)total * hid) + 63) / 64 * 64;
+    const size_t need = sizeof(float) * (h_floats + (size_t)k * chunks * T);
+    if (need > ctx->d_ws_bytes) {
+        if (ctx->d_ws) {
+            NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
+            NGC_HIP(ctx, hipFree(ctx->d_ws));
+            ctx->d_ws = nullptr;
+            ctx->d_ws_bytes = 0;
+        }
+        void* p = nullptr;
+        if (hipMalloc(&p, need) != hipSuccess) {
+            (void)hipGetLastError();
+            return ngc_fail(ctx, NGC_ERR_NOMEM, "workspace allocation failed");
+        }
+        ctx->d_ws = (float*)p;
+        ctx->d_ws_bytes = need;
+    }
+    float* H = ctx->d_ws;
+    float* partial = ctx->d_ws + h_floats;
+
+    mlp_prof ps(ctx);
+    {   // 1. H = relu(X W1 + b1), all partitions as one matrix
+        dim3 grid((unsigned)((hid + BN - 1) / BN), (unsigned)((total + BM - 1) / BM), 1);
+        if (grid.y > 65535) return ngc_fail(ctx, NGC_ERR_INVALID, "too many rows for one launch");
+        hipLaunchKernelGGL((mlp_gemm_kernel<false, EPI_BIAS_RELU>), grid, dim3(256), 0, ctx->stream, X, W1, H, b1,
+                           (int)total, hid, din, (int64_t)din, (int64_t)hid, (int64_t)hid, (int64_t)0,
+                           (int64_t)0, (int64_t)0, (int)(din % 4 == 0 && al(X, 16)),
+                           (int)(hid % 4 == 0 && al(W1, 16)), (int)(hid % 2 == 0));
+        NGC_HIP(ctx, hipGetLastError());
+    }
+    {   // 2. logits, softmax, dZ2, dW2/db2/db1 partials, dZ1 over H
+        dim3 grid((unsigned)(k * chunks));
+        const int hv = hid % 4 == 0;
+        if (cls <= 4)
+            hipLaunchKernelGGL((mlp_head_kernel<4>), grid, dim3(256), 0, ctx->stream, H, labels, W2, b2, partial,
+                               hid, cls, rows, (int)chunks, rpc, hv);
+        else if (cls <= 10)
+            hipLaunchKernelGGL((mlp_head_kernel<10>), grid, dim3(256), 0, ctx->stream, H, labels, W2, b2, partial,
+                               hid, cls, rows, (int)chunks, rpc, hv);
+        else
+            hipLaunchKernelGGL((mlp_head_kernel<16>), grid, dim3(256), 0, ctx->stream, H, labels, W2, b2, partial,
+                               hid, cls, rows, (int)chunks, rpc, hv);
+        NGC_HIP(ctx, hipGetLastError());
+        dim3 rgrid((unsigned)((T + 255) / 256), (unsigned)k);
+        hipLaunchKernelGGL(mlp_tail_reduce_kernel, rgrid, dim3(256), 0, ctx->stream, (const float*)partial,
+                           G + (int64_t)din * hid, T, (int)chunks, d);
+        NGC_HIP(ctx, hipGetLastError());
+    }
+    {   // 3. dW1_j = X_j^T dZ1_j, one batch entry per partition, straight into G[j]
+        dim3 grid((unsigned)((hid + BN - 1) / BN), (unsigned)((din + BM - 1) / BM), (unsigned)k);
+        hipLaunchKernelGGL((mlp_gemm_kernel<true, EPI_STORE>), grid, dim3(256), 0, ctx->stream, X, (const float*)H, G,
+                           (const float*)nullptr, din, hid, (int)rows, (int64_t)din, (int64_t)hid, (int64_t)hid,
+                           rows * (int64_t)din, rows * (int64_t)hid, d, (int)(din % 4 == 0 && al(X, 16)),
+                           (int)(hid % 4 == 0), (int)(hid % 2 == 0 && d % 2 == 0 && al(G, 8)));
+        NGC_HIP(ctx, hipGetLastError());
+    }
+    return NGC_OK;
 }

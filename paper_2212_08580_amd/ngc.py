@@ -12,6 +12,9 @@ import ctypes
 import os
 
 import numpy as np
+# torch owns the device memory handed to the library and ships its own HIP runtime; it is
+# imported first so that libngc.so binds to that same runtime instead of loading a second one.
+import torch  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libngc.so")
@@ -190,8 +193,19 @@ def ngc_probe_read(ctx, src, nbytes):
     _check(_lib.ngc_probe_read(ctx, _dev(src), int(nbytes)), ctx)
 
 
-def ngc_profile_enable(ctx, on):
-    _check(_lib.ngc_profile_enable(ctx, int(bool(on))), ctx)
+def ngc_profile_enable(ctx, kernels):
+    """kernels: True/-1 = all, False/0 = off, or an iterable of kernel names to time."""
+    if kernels is True:
+        mask = -1
+    elif not kernels:
+        mask = 0
+    elif isinstance(kernels, int):
+        mask = kernels
+    else:
+        mask = 0
+        for name in kernels:
+            mask |= 1 << NGC_KERNEL_NAMES.index(name)
+    _check(_lib.ngc_profile_enable(ctx, mask), ctx)
 
 
 def ngc_profile_read(ctx):
