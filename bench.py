@@ -81,6 +81,88 @@ def cpu_baseline(w, wl, parts_host, theta, masks, budget_parts):
     }
 
 
+def bench_codec(args, w, wl, ngc, torch, np):
+    """Encode/decode stress (no data): per round encode every layer from resident partial
+    gradients, choose layer and decode vector for a Binomial(n, 0.2) straggler set on the host,
+    decode.  Reports algorithmic GB/s (G read once + every message written; responders' messages
+    read + one vector written) and per-round latency."""
+    dev = torch.device("cuda:0")
+    K, W = args.steps, args.warmup
+    L = len(w.layers)
+    G = torch.from_numpy(wl.partial_gradients(w, 0)).to(dev)
+    C = torch.empty((L, w.n, w.d), dtype=torch.float32, device=dev)
+    g = torch.empty(w.d, dtype=torch.float32, device=dev)
+    masks = wl.binomial_count_masks(w, K + W, seed=0)
+    masks[masks.sum(axis=1) > w.layers[-1]] = 0
+    ctx = ngc.ngc_create(w.n, w.n, w.layers, w.d, torch.cuda.current_stream().cuda_stream)
+    ngc.ngc_build_code(ctx, ngc.NGC_CODE_CYCLIC if w.code == wl.CODE_CYCLIC else ngc.NGC_CODE_FRACREP, 0)
+
+    def step(t):
+        ngc.ngc_encode(ctx, G, -1, C)
+        u, a, _ = ngc.ngc_select_decode_vec(ctx, masks[t], w.n)
+        ngc.ngc_decode(ctx, u, a, C, g)
+        return a
+
+    for t in range(W):
+        step(t)
+    torch.cuda.synchronize()
+    ngc.ngc_profile_enable(ctx, ["encode"])
+    resp = 0
+    t0 = time.perf_counter()
+    for t in range(W, W + K):
+        resp += int(np.count_nonzero(step(t)))
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = ngc.ngc_profile_read(ctx)
+    ngc.ngc_profile_enable(ctx, ["decode"])
+    for t in range(W, W + min(K, 200)):
+        step(t)
+    prof_d = ngc.ngc_profile_read(ctx)
+    ngc.ngc_profile_enable(ctx, False)
+    enc_ms = prof["encode"][1] / max(1, prof["encode"][0])
+    dec_ms = prof_d["decode"][1] / max(1, prof_d["decode"][0])
+    enc_bytes = 4.0 * w.n * w.d * (1 + L)
+    dec_bytes = 4.0 * w.d * (resp / K + 1)
+    achieved = enc_bytes / (enc_ms * 1e-3) / 1e9
+    out = {
+        "metric": "partition-gradient samples/s + encode/decode GB/s vs HBM peak, n=32 d=4096",
+        "value": round((enc_bytes + dec_bytes) * K / elapsed / 1e9, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": K, "warmup": W, "ms_per_step": round(elapsed / K * 1e3, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "n": w.n, "d": w.d, "layers": list(w.layers),
+                   "p_straggle": w.p_straggle, "mean_responders": resp / K},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes": enc_bytes, "kernel": "encode_kernel",
+                     "avg_ms": round(enc_ms, 4), "launches": prof["encode"][0]},
+        "stages": {"encode_ms": round(enc_ms, 4), "encode_GBps": round(achieved, 1),
+                   "decode_ms": round(dec_ms, 4),
+                   "decode_GBps": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1)},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import codes, coding
+        Bs = codes.nested_code(w.n, w.layers, "cyclic", seed=0, draws=2)
+        Gh = G.cpu().numpy()
+        rounds = min(K, 20)
+        t0 = time.perf_counter()
+        for t in range(rounds):
+            Co = coding.encode_layers(Bs, Gh)
+            u = coding.select_layer(w.layers, masks[W + t])
+            a, _ = coding.decode_vector(Bs[u], masks[W + t])
+            coding.decode(a, Co[u])
+        dt = (time.perf_counter() - t0) / rounds
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        out["cpu_baseline"] = {"value": (enc_bytes + dec_bytes) / dt / 1e9, "unit": "GB/s",
+                               "cores": int(cores), "kind": "oracle",
+                               "sample": "%d rounds of encode + select + decode at full n, d" % rounds}
+    ngc.ngc_destroy(ctx)
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -106,6 +188,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     w = wl.CONFIGS[args.workload]
+    if w.loss < 0:
+        return bench_codec(args, w, wl, ngc, torch, np)
     if w.loss not in (wl.LOSS_LSQ, wl.LOSS_LOGISTIC, wl.LOSS_MLP2):
         print("bench.py times the gradient workloads (C1, C2, C3, C4)", file=sys.stderr)
         sys.exit(2)

@@ -9,6 +9,7 @@ LIB = os.path.join(HERE, "libngc.so")
 SOURCES = ["ngc_host.cpp", "ngc_solve.cpp", "ngc_device.hip", "ngc_mlp.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Xarch_host", "-mavx2", "-Xarch_host", "-mfma",
          "-Wall", "-Wno-unused-function"]
 
 

@@ -243,10 +243,14 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const VT* __restri
 }
 
 // ---------------------------------------------------------------------------
-// K3: layered encode.  A block stages a tile of G (all n rows, 16*V columns) in
-// LDS, then writes the messages of its share of (layer, worker) pairs from
-// there: every pair is one sparse row of B^(u) in compressed form.
-// pair p = u*n + i is also the row index of C viewed as [L*n][d].
+// K3: layered encode.  A block stages a tile of G (all n rows, 64*V columns) in
+// LDS, then each of its waves writes the messages of (layer, worker) pairs from
+// there, one pair at a time: a pair is one sparse row of B^(u) in compressed
+// form, and since the whole wave works on the same pair its column indices and
+// coefficients are wave-uniform (scalar loads); only the tile reads and the
+// FMAs are per lane.  pair p = u*n + i is also the row index of C viewed as
+// [L*n][d].  G is read from HBM once per column tile however many layers there
+// are (blocks that share a tile re-read it from L2).
 // ---------------------------------------------------------------------------
 template <typename VT, int V>
 __global__ __launch_bounds__(256) void encode_kernel(const float* __restrict__ G,
@@ -256,31 +260,52 @@ __global__ __launch_bounds__(256) void encode_kernel(const float* __restrict__ G
                                                      const float* __restrict__ coef, int n,
                                                      int64_t d, int pair_begin, int pair_end,
                                                      int pairs_per_group) {
-    __shared__ VT tile[NGC_MAX_N * 16];
-    const int lane16 = threadIdx.x & 15;
-    const int slot = threadIdx.x >> 4;
-    const int64_t c = ((int64_t)blockIdx.x * 16 + lane16) * V;
+    extern __shared__ float tile_raw[];
+    VT* tile = reinterpret_cast<VT*>(tile_raw);  // [n][64]
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t c = ((int64_t)blockIdx.x * 64 + lane) * V;
     const bool in = c < d;
-    for (int r = slot; r < n; r += 16) {
+    for (int r = wave; r < n; r += 4) {
         VT v = (VT)(0.0f);
         if (in) v = *reinterpret_cast<const VT*>(G + (int64_t)r * d + c);
-        tile[r * 16 + lane16] = v;
+        tile[r * 64 + lane] = v;
     }
     __syncthreads();
     const int p0 = pair_begin + blockIdx.y * pairs_per_group;
     const int p1 = pair_end < p0 + pairs_per_group ? pair_end : p0 + pairs_per_group;
-    for (int p = p0 + slot; p < p1; p += 16) {
+    for (int p = p0 + wave; p < p1; p += 4) {
         const int b = rowptr[p], e = rowptr[p + 1];
-        VT acc = (VT)(0.0f);
-        for (int t = b; t < e; ++t) acc += coef[t] * tile[col[t] * 16 + lane16];
-        if (in) *reinterpret_cast<VT*>(C + (int64_t)p * d + c) = acc;
+        VT acc0 = (VT)(0.0f), acc1 = (VT)(0.0f);
+        int t = b;
+        // eight terms at a time: their indices and coefficients arrive in two wide
+        // scalar loads and the eight tile reads are in flight together
+        for (; t + 8 <= e; t += 8) {
+            int cc[8];
+            float ww[8];
+            VT x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                cc[u] = col[t + u];
+                ww[u] = coef[t + u];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) x[u] = tile[cc[u] * 64 + lane];
+#pragma unroll
+            for (int u = 0; u < 8; u += 2) {
+                acc0 += ww[u] * x[u];
+                acc1 += ww[u + 1] * x[u + 1];
+            }
+        }
+        for (; t < e; ++t) acc0 += coef[t] * tile[col[t] * 64 + lane];
+        if (in) *reinterpret_cast<VT*>(C + (int64_t)p * d + c) = acc0 + acc1;
     }
 }
 
 // ---------------------------------------------------------------------------
 // K4: decode.  g = sum_t a[t] * C[idx[t]][:], products and sum in fp64, one
-// rounding to fp32.  The four waves of a block take every fourth responder and
-// their partial sums are added in wave order.
+// rounding to fp32.  A block covers 16*V columns; its 16 groups of 16 lanes take
+// every sixteenth responder and their partial sums are added in group order.
 // ---------------------------------------------------------------------------
 struct decode_args {
     double a[NGC_MAX_N];
@@ -292,15 +317,15 @@ template <typename VT, int V>
 __global__ __launch_bounds__(256) void decode_kernel(const float* __restrict__ Cl,
                                                      float* __restrict__ g, int64_t d,
                                                      decode_args args) {
-    __shared__ double part[4][64][V];
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int64_t c = ((int64_t)blockIdx.x * 64 + lane) * V;
+    __shared__ double part[16][16 * V + 1];
+    const int lane16 = threadIdx.x & 15;
+    const int slot = threadIdx.x >> 4;
+    const int64_t c = ((int64_t)blockIdx.x * 16 + lane16) * V;
     double acc[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) acc[v] = 0.0;
     if (c < d) {
-        for (int t = wave; t < args.count; t += 4) {
+        for (int t = slot; t < args.count; t += 16) {
             VT m = *reinterpret_cast<const VT*>(Cl + (int64_t)args.idx[t] * d + c);
             const double a = args.a[t];
             if constexpr (V == 1) {
@@ -312,13 +337,17 @@ __global__ __launch_bounds__(256) void decode_kernel(const float* __restrict__ C
         }
     }
 #pragma unroll
-    for (int v = 0; v < V; ++v) part[wave][lane][v] = acc[v];
+    for (int v = 0; v < V; ++v) part[slot][lane16 * V + v] = acc[v];
     __syncthreads();
-    if (wave == 0 && c < d) {
+    // thread q < 16*V sums column q of the tile over the 16 groups, in group order
+    const int q = threadIdx.x;
+    if (q < 16 * V) {
+        const int64_t cq = (int64_t)blockIdx.x * 16 * V + q;
+        if (cq < d) {
+            double s = part[0][q];
 #pragma unroll
-        for (int v = 0; v < V; ++v) {
-            double s = ((part[0][lane][v] + part[1][lane][v]) + part[2][lane][v]) + part[3][lane][v];
-            g[c + v] = (float)s;
+            for (int k = 1; k < 16; ++k) s += part[k][q];
+            g[cq] = (float)s;
         }
     }
 }
@@ -682,25 +711,27 @@ extern "C" int ngc_encode(ngc_ctx* ctx, const float* G_dev, int layer, float* C_
     const int pb = layer < 0 ? 0 : layer * n;
     const int pe = layer < 0 ? (int)np : (layer + 1) * n;
     const int V = vec_width(d, G_dev, C_dev);
-    const int64_t gx = (d + 16 * V - 1) / (16 * V);
+    const int64_t gx = (d + 64 * V - 1) / (64 * V);
     const int pairs = pe - pb;
-    int64_t gy = std::max<int64_t>(1, (2 * (int64_t)ctx->cu_count + gx - 1) / gx);
-    gy = std::min<int64_t>(gy, (pairs + 15) / 16);
+    // enough blocks for about three per CU; each wave of a block takes every fourth pair
+    int64_t gy = std::max<int64_t>(1, (3 * (int64_t)ctx->cu_count + gx - 1) / gx);
+    gy = std::min<int64_t>(gy, (pairs + 3) / 4);
     int ppg = (int)((pairs + gy - 1) / gy);
-    ppg = ((ppg + 15) / 16) * 16;
+    ppg = ((ppg + 3) / 4) * 4;
     gy = (pairs + ppg - 1) / ppg;
     if (gx > 0x7fffffffLL) return ngc_fail(ctx, NGC_ERR_INVALID, "d too large");
     dim3 grid((unsigned)gx, (unsigned)gy);
+    const size_t lds = (size_t)n * 64 * V * sizeof(float);
     {
         prof_scope ps(ctx, NGC_KERNEL_ENCODE);
         if (V == 4)
-            hipLaunchKernelGGL((encode_kernel<v4f, 4>), grid, dim3(256), 0, ctx->stream, G_dev, C_dev,
+            hipLaunchKernelGGL((encode_kernel<v4f, 4>), grid, dim3(256), lds, ctx->stream, G_dev, C_dev,
                                rowptr, col, coef, n, d, pb, pe, ppg);
         else if (V == 2)
-            hipLaunchKernelGGL((encode_kernel<v2f, 2>), grid, dim3(256), 0, ctx->stream, G_dev, C_dev,
+            hipLaunchKernelGGL((encode_kernel<v2f, 2>), grid, dim3(256), lds, ctx->stream, G_dev, C_dev,
                                rowptr, col, coef, n, d, pb, pe, ppg);
         else
-            hipLaunchKernelGGL((encode_kernel<float, 1>), grid, dim3(256), 0, ctx->stream, G_dev, C_dev,
+            hipLaunchKernelGGL((encode_kernel<float, 1>), grid, dim3(256), lds, ctx->stream, G_dev, C_dev,
                                rowptr, col, coef, n, d, pb, pe, ppg);
     }
     NGC_HIP(ctx, hipGetLastError());
@@ -732,7 +763,7 @@ extern "C" int ngc_decode(ngc_ctx* ctx, int layer, const double* a_host, const f
     }
     const float* Cl = C_dev + (size_t)layer * n * d;
     const int V = vec_width(d, Cl, g_dev);
-    const int64_t gx = (d + 64 * V - 1) / (64 * V);
+    const int64_t gx = (d + 16 * V - 1) / (16 * V);
     {
         prof_scope ps(ctx, NGC_KERNEL_DECODE);
         if (V == 4)

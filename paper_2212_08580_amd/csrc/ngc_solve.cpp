@@ -15,6 +15,21 @@
 
 #include "ngc_internal.h"
 
+// dot product with four running sums (lets the compiler use 4-wide vectors without
+// being allowed to reassociate a single sum)
+static inline double dot4(const double* __restrict__ x, const double* __restrict__ y, int len) {
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    int i = 0;
+    for (; i + 4 <= len; i += 4) {
+        s0 += x[i] * y[i];
+        s1 += x[i + 1] * y[i + 1];
+        s2 += x[i + 2] * y[i + 2];
+        s3 += x[i + 3] * y[i + 3];
+    }
+    for (; i < len; ++i) s0 += x[i] * y[i];
+    return (s0 + s1) + (s2 + s3);
+}
+
 int ngc_min_norm_decode(const double* B, int n, const int* rows, int ns, double* a_out,
                         double* resid) {
     for (int i = 0; i < n; ++i) a_out[i] = 0.0;
@@ -30,31 +45,48 @@ int ngc_min_norm_decode(const double* B, int n, const int* rows, int ns, double*
     for (int j = 0; j < n; ++j) piv[j] = j;
     std::vector<double> tau(std::min(ns, n), 0.0);
 
+    // squared norms of the not yet eliminated part of every column; downdated after each
+    // reflection and recomputed when cancellation has eaten most of the digits
+    std::vector<double> cn(n), cn_ref(n);
+    for (int j = 0; j < n; ++j) {
+        const double* c = &M[(size_t)j * ns];
+        cn[j] = cn_ref[j] = dot4(c, c, ns);
+    }
     double norm0 = 0.0;
     const int kmax = std::min(ns, n);
     int rank = 0;
     for (int k = 0; k < kmax; ++k) {
-        // remaining column norms, recomputed (cheap at this size, no downdating error)
         int best = k;
         double bestn = -1.0;
-        for (int j = k; j < n; ++j) {
-            double sq = 0.0;
-            const double* c = &M[(size_t)j * ns];
-            for (int i = k; i < ns; ++i) sq += c[i] * c[i];
-            if (sq > bestn) { bestn = sq; best = j; }
+        for (int j = k; j < n; ++j)
+            if (cn[j] > bestn) { bestn = cn[j]; best = j; }
+        {   // the pivot's norm is always taken from the data itself
+            const double* c = &M[(size_t)best * ns];
+            bestn = std::sqrt(dot4(c + k, c + k, ns - k));
         }
-        bestn = std::sqrt(bestn);
         if (k == 0) norm0 = bestn;
-        if (!(bestn > 1e-11 * norm0) || bestn == 0.0) break;
+        if (!(bestn > 1e-11 * norm0) || bestn == 0.0) {
+            // the downdated norms may have drifted: look again with exact norms before stopping
+            bestn = -1.0;
+            for (int j = k; j < n; ++j) {
+                const double* c = &M[(size_t)j * ns];
+                const double sq = dot4(c + k, c + k, ns - k);
+                cn[j] = cn_ref[j] = sq;
+                if (sq > bestn) { bestn = sq; best = j; }
+            }
+            bestn = std::sqrt(bestn);
+            if (!(bestn > 1e-11 * norm0) || bestn == 0.0) break;
+        }
         if (best != k) {
             std::swap(piv[best], piv[k]);
+            std::swap(cn[best], cn[k]);
+            std::swap(cn_ref[best], cn_ref[k]);
             for (int i = 0; i < ns; ++i) std::swap(M[(size_t)best * ns + i], M[(size_t)k * ns + i]);
         }
         // Householder reflector H = I - tau v v^T, v[k] = 1, zeroing M[k+1:, k]
         double* c = &M[(size_t)k * ns];
         double alpha = c[k];
-        double xn = 0.0;
-        for (int i = k + 1; i < ns; ++i) xn += c[i] * c[i];
+        const double xn = dot4(c + k + 1, c + k + 1, ns - k - 1);
         if (xn == 0.0) {
             tau[k] = 0.0;
         } else {
@@ -65,11 +97,17 @@ int ngc_min_norm_decode(const double* B, int n, const int* rows, int ns, double*
             c[k] = beta;
             for (int j = k + 1; j < n; ++j) {
                 double* cj = &M[(size_t)j * ns];
-                double w = cj[k];
-                for (int i = k + 1; i < ns; ++i) w += c[i] * cj[i];
-                w *= tau[k];
+                double w = (cj[k] + dot4(c + k + 1, cj + k + 1, ns - k - 1)) * tau[k];
                 cj[k] -= w;
                 for (int i = k + 1; i < ns; ++i) cj[i] -= w * c[i];
+            }
+        }
+        for (int j = k + 1; j < n; ++j) {
+            const double rkj = M[(size_t)j * ns + k];
+            cn[j] -= rkj * rkj;
+            if (!(cn[j] > 1e-4 * cn_ref[j])) {  // too much cancellation: recompute
+                const double* cj = &M[(size_t)j * ns];
+                cn[j] = cn_ref[j] = dot4(cj + k + 1, cj + k + 1, ns - k - 1);
             }
         }
         rank = k + 1;
