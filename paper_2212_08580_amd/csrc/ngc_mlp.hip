@@ -59,7 +59,7 @@ __device__ __forceinline__ v4f load4(const float* __restrict__ p, int64_t left, 
 //   A_KMAJOR: A is stored [K][M] (element (m,k) at A[k*lda + m]); else [M][K].
 //   B is stored [K][N].  C is stored [M][N].
 template <bool A_KMAJOR, int EPI>
-__global__ __launch_bounds__(256) void mlp_gemm_kernel(
+__global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(
     const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C,
     const float* __restrict__ bias, int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
     int64_t strideA, int64_t strideB, int64_t strideC, int a_vec_ok, int b_vec_ok, int c_vec_ok) {
@@ -83,26 +83,43 @@ __global__ __launch_bounds__(256) void mlp_gemm_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    v4f ra[2], rb[2];
-    auto gload = [&](int k0) {
+    // Tiles that lie wholly inside the matrices and are 16-byte addressable take
+    // unguarded vector loads (no branch in the main loop); edge tiles and odd
+    // leading dimensions take the guarded element-wise path.
+    const bool a_inside = a_vec_ok && (m0 + BM <= M);
+    const bool b_inside = b_vec_ok && (n0 + BN <= N);
+    auto gload = [&](int k0, v4f (&ra)[2], v4f (&rb)[2]) {
+        const bool k_inside = k0 + BK <= K;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int idx = t + h * 256;
             if (A_KMAJOR) {
                 const int k = idx >> 5, m4 = (idx & 31) * 4;
                 const int gk = k0 + k, gm = m0 + m4;
-                ra[h] = (gk < K) ? load4(A + (int64_t)gk * lda + gm, (int64_t)M - gm, a_vec_ok) : (v4f)(0.0f);
+                const float* p = A + (int64_t)gk * lda + gm;
+                if (a_inside && k_inside)
+                    ra[h] = *reinterpret_cast<const v4f*>(p);
+                else
+                    ra[h] = (gk < K) ? load4(p, (int64_t)M - gm, a_vec_ok) : (v4f)(0.0f);
             } else {
                 const int m = idx >> 2, k4 = (idx & 3) * 4;
                 const int gm = m0 + m, gk = k0 + k4;
-                ra[h] = (gm < M) ? load4(A + (int64_t)gm * lda + gk, (int64_t)K - gk, a_vec_ok) : (v4f)(0.0f);
+                const float* p = A + (int64_t)gm * lda + gk;
+                if (a_inside && k_inside)
+                    ra[h] = *reinterpret_cast<const v4f*>(p);
+                else
+                    ra[h] = (gm < M) ? load4(p, (int64_t)K - gk, a_vec_ok) : (v4f)(0.0f);
             }
             const int k = idx >> 5, n4 = (idx & 31) * 4;
             const int gk = k0 + k, gn = n0 + n4;
-            rb[h] = (gk < K) ? load4(B + (int64_t)gk * ldb + gn, (int64_t)N - gn, b_vec_ok) : (v4f)(0.0f);
+            const float* q = B + (int64_t)gk * ldb + gn;
+            if (b_inside && k_inside)
+                rb[h] = *reinterpret_cast<const v4f*>(q);
+            else
+                rb[h] = (gk < K) ? load4(q, (int64_t)N - gn, b_vec_ok) : (v4f)(0.0f);
         }
     };
-    auto sstore = [&](int buf) {
+    auto sstore = [&](int buf, const v4f (&ra)[2], const v4f (&rb)[2]) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int idx = t + h * 256;
@@ -121,13 +138,7 @@ __global__ __launch_bounds__(256) void mlp_gemm_kernel(
         }
     };
 
-    const int nk = (K + BK - 1) / BK;
-    gload(0);
-    sstore(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) gload((kt + 1) * BK);
+    auto compute = [&](int buf) {
 #pragma unroll
         for (int kk = 0; kk < BK / 2; ++kk) {
             const int k = 2 * kk + lhi;
@@ -138,7 +149,30 @@ __global__ __launch_bounds__(256) void mlp_gemm_kernel(
             acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.y, b2.x, acc[1][0], 0, 0, 0);
             acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.y, b2.y, acc[1][1], 0, 0, 0);
         }
-        if (kt + 1 < nk) sstore(buf ^ 1);
+    };
+
+    // Software pipeline, two k tiles deep: while tile kt is multiplied out of LDS,
+    // tile kt+1 waits in registers for its turn in the other LDS buffer and tile
+    // kt+2 is on its way from memory.  Two register stages (p, q) alternate, the
+    // loop is unrolled twice so that each has a fixed role.
+    const int nk = (K + BK - 1) / BK;
+    v4f pa[2], pb[2], qa[2], qb[2];
+    gload(0, pa, pb);
+    sstore(0, pa, pb);
+    if (nk > 1) gload(BK, qa, qb);
+    __syncthreads();
+    const int npairs = (nk + 1) / 2;
+    for (int pr = 0; pr < npairs; ++pr) {
+        const int kt = 2 * pr;
+        // even tile kt from buffer 0; q holds tile kt+1
+        if (kt + 2 < nk) gload((kt + 2) * BK, pa, pb);
+        compute(0);
+        if (kt + 1 < nk) sstore(1, qa, qb);
+        __syncthreads();
+        // odd tile kt+1 from buffer 1 (all zeros past the end of K); p holds tile kt+2
+        if (kt + 3 < nk) gload((kt + 3) * BK, qa, qb);
+        if (kt + 1 < nk) compute(1);
+        if (kt + 2 < nk) sstore(0, pa, pb);
         __syncthreads();
     }
 
@@ -195,27 +229,122 @@ __device__ __forceinline__ float wave_sum(float v) {
     return (s0 + s1) + (s2 + s3);
 }
 
-// Step 2.  A block owns a run of rows of one partition; thread t owns hidden
-// units 4t..4t+3 (hidden <= 1024).  W2's rows for those units, the dW2 and db1
-// accumulators stay in registers.  Per row the 4 waves exchange their partial
-// logits through LDS (one barrier per row, double-buffered area).  NCP is the
-// class count rounded up; classes beyond `classes` get logit -inf.
+// Step 2a.  Logits, softmax and dZ2 = P - onehot(label), one thread per row so
+// that no value ever crosses lanes: a block of 64 threads takes 64 consecutive
+// rows; their hidden activations pass through LDS in tiles of 64 rows x 32
+// units (coalesced 128-byte row segments in, one padded row per thread out), and
+// each thread adds h * W2[unit][class] into its own NCP logits.  The 32 rows of
+// W2 that go with a tile sit in LDS as well and are read as broadcasts (every
+// lane the same address).  The next tile is fetched into registers while the
+// current one is consumed.  NCP is the class
+// count rounded up; classes beyond `classes` get logit -inf.
+template <int NCP>
+__global__ __launch_bounds__(64) void mlp_logits_kernel(
+    const float* __restrict__ H, const int* __restrict__ labels, const float* __restrict__ W2,
+    const float* __restrict__ b2, float* __restrict__ dZ2, int hidden, int classes,
+    int64_t total_rows, int h_vec_ok) {
+    constexpr int TR = 64, TH = 32, LD = TH + 4;
+    constexpr int NCQ = (NCP + 3) / 4 * 4;  // W2 row padded to whole float4
+    __shared__ float tile[TR * LD];
+    __shared__ float w2s[TH * NCQ];
+    const int lane = threadIdx.x;
+    const int64_t row0 = (int64_t)blockIdx.x * TR;
+    const int64_t my_row = row0 + lane;
+    float z[NCP];
+#pragma unroll
+    for (int q = 0; q < NCP; ++q) z[q] = 0.0f;
+
+    // tile element idx = u*64 + lane: row idx/8, float4 idx%8
+    v4f stage[8];
+    float wstage[(TH * NCQ + 63) / 64];
+    auto fetch = [&](int hc) {
+#pragma unroll
+        for (int u = 0; u < (TH * NCQ + 63) / 64; ++u) {
+            const int idx = u * 64 + lane;
+            const int h = hc + idx / NCQ, q = idx % NCQ;
+            wstage[u] = (idx < TH * NCQ && h < hidden && q < classes) ? W2[(int64_t)h * classes + q] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int idx = u * 64 + lane;
+            const int64_t r = row0 + (idx >> 3);
+            const int h0 = hc + (idx & 7) * 4;
+            stage[u] = r < total_rows ? load4(H + r * hidden + h0, (int64_t)hidden - h0, h_vec_ok)
+                                      : (v4f)(0.0f);
+        }
+    };
+    fetch(0);
+    for (int hc = 0; hc < hidden; hc += TH) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int idx = u * 64 + lane;
+            *reinterpret_cast<v4f*>(&tile[(idx >> 3) * LD + (idx & 7) * 4]) = stage[u];
+        }
+#pragma unroll
+        for (int u = 0; u < (TH * NCQ + 63) / 64; ++u) {
+            const int idx = u * 64 + lane;
+            if (idx < TH * NCQ) w2s[idx] = wstage[u];
+        }
+        __syncthreads();
+        if (hc + TH < hidden) fetch(hc + TH);
+        // units past `hidden` carry zeros in both the tile and the W2 rows
+#pragma unroll
+        for (int g = 0; g < TH / 4; ++g) {
+            const v4f hv = *reinterpret_cast<const v4f*>(&tile[lane * LD + g * 4]);
+            const float he[4] = {hv.x, hv.y, hv.z, hv.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float* wrow = &w2s[(g * 4 + e) * NCQ];
+#pragma unroll
+                for (int q4 = 0; q4 < NCQ / 4; ++q4) {
+                    const v4f w = *reinterpret_cast<const v4f*>(wrow + q4 * 4);  // broadcast read
+                    const float we[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (q4 * 4 + c < NCP) z[q4 * 4 + c] += he[e] * we[c];
+                }
+            }
+        }
+        __syncthreads();
+    }
+    if (my_row >= total_rows) return;
+    const int label = labels[my_row];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int q = 0; q < NCP; ++q) {
+        z[q] = q < classes ? z[q] + b2[q] : -INFINITY;
+        mx = fmaxf(mx, z[q]);
+    }
+    float den = 0.0f;
+#pragma unroll
+    for (int q = 0; q < NCP; ++q) {
+        z[q] = expf(z[q] - mx);
+        den += z[q];
+    }
+    const float inv = 1.0f / den;
+#pragma unroll
+    for (int q = 0; q < NCP; ++q)
+        if (q < classes) dZ2[my_row * classes + q] = z[q] * inv - (q == label ? 1.0f : 0.0f);
+}
+
+// Step 2b.  A block owns a run of rows of one partition; thread t owns hidden
+// units 4t..4t+3.  Per row it reads dZ2 (the same for the whole block), forms
+// dH = dZ2 W2^T for its units, writes dZ1 = dH * [H > 0] over H and accumulates
+// dW2 += h dZ2, db1 += dZ1, db2 += dZ2 in registers: no exchange between threads.
 // Block partial layout = tail of theta: [db1 (hidden) | dW2 (hidden x classes) | db2 (classes)].
 template <int NCP>
-__global__ __launch_bounds__(256) void mlp_head_kernel(
-    float* __restrict__ H, const int* __restrict__ labels, const float* __restrict__ W2,
-    const float* __restrict__ b2, float* __restrict__ partial, int hidden, int classes,
-    int64_t rows, int chunks, int64_t rows_per_chunk, int h_vec_ok) {
-    __shared__ float ex[2][NCP][4];
+__global__ __launch_bounds__(256) void mlp_back_kernel(
+    float* __restrict__ H, const float* __restrict__ dZ2, const float* __restrict__ W2,
+    float* __restrict__ partial, int hidden, int classes, int64_t rows, int chunks,
+    int64_t rows_per_chunk, int h_vec_ok) {
     const int t = threadIdx.x;
-    const int wave = t >> 6;
     const int j = blockIdx.x / chunks, c = blockIdx.x % chunks;
     const int64_t r0 = (int64_t)c * rows_per_chunk;
     const int64_t r1 = rows < r0 + rows_per_chunk ? rows : r0 + rows_per_chunk;
     const int h0 = 4 * t;
     const int hleft = hidden - h0;  // may be <= 0
 
-    float w2[4][NCP], dw2[4][NCP], db1[4], db2[NCP], bias2[NCP];
+    float w2[4][NCP], dw2[4][NCP], db1[4], db2[NCP];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         db1[e] = 0.0f;
@@ -226,72 +355,53 @@ __global__ __launch_bounds__(256) void mlp_head_kernel(
         }
     }
 #pragma unroll
-    for (int q = 0; q < NCP; ++q) {
-        db2[q] = 0.0f;
-        bias2[q] = q < classes ? b2[q] : 0.0f;
-    }
+    for (int q = 0; q < NCP; ++q) db2[q] = 0.0f;
 
     float* Hp = H + ((int64_t)j * rows) * hidden + h0;
-    const int* lp = labels + (int64_t)j * rows;
-    for (int64_t r = r0; r < r1; ++r) {
-        float* hrow = Hp + r * hidden;
-        v4f h = load4(hrow, hleft, h_vec_ok);
-        float hv[4] = {h.x, h.y, h.z, h.w};
-        float z[NCP];
+    const float* dzp = dZ2 + ((int64_t)j * rows) * classes;
+    // four rows per trip: their loads are issued together before any is used
+    for (int64_t rb = r0; rb < r1; rb += 4) {
+        v4f hq[4];
 #pragma unroll
-        for (int q = 0; q < NCP; ++q) {
-            float p = hv[0] * w2[0][q];
-            p += hv[1] * w2[1][q];
-            p += hv[2] * w2[2][q];
-            p += hv[3] * w2[3][q];
-            z[q] = wave_sum(p);
+        for (int u = 0; u < 4; ++u) {
+            const int64_t r = rb + u < r1 ? rb + u : r1 - 1;
+            hq[u] = load4(Hp + r * hidden, hleft, h_vec_ok);
         }
-        float* e = &ex[r & 1][0][0];
 #pragma unroll
-        for (int q = 0; q < NCP; ++q) e[q * 4 + wave] = z[q];
-        __syncthreads();
-        const int label = lp[r];
-        float mx = -INFINITY;
+        for (int u = 0; u < 4; ++u) {
+            const int64_t r = rb + u;
+            if (r < r1) {  // block-uniform
+                float* hrow = Hp + r * hidden;
+                const float hv[4] = {hq[u].x, hq[u].y, hq[u].z, hq[u].w};
+                float dh[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-        for (int q = 0; q < NCP; ++q) {
-            float s = ((e[q * 4] + e[q * 4 + 1]) + e[q * 4 + 2]) + e[q * 4 + 3] + bias2[q];
-            z[q] = q < classes ? s : -INFINITY;
-            mx = fmaxf(mx, z[q]);
-        }
-        float den = 0.0f;
+                for (int q = 0; q < NCP; ++q) {
+                    const float dz = q < classes ? dzp[r * classes + q] : 0.0f;  // block-uniform
+                    db2[q] += dz;
 #pragma unroll
-        for (int q = 0; q < NCP; ++q) {
-            z[q] = expf(z[q] - mx);
-            den += z[q];
-        }
-        const float inv = 1.0f / den;
-        float dh[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-        for (int q = 0; q < NCP; ++q) {
-            const float dz = z[q] * inv - (q == label ? 1.0f : 0.0f);  // dZ2 = P - onehot
-            db2[q] += dz;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                dw2[k][q] += hv[k] * dz;
-                dh[k] += dz * w2[k][q];
+                    for (int e = 0; e < 4; ++e) {
+                        dw2[e][q] += hv[e] * dz;
+                        dh[e] += dz * w2[e][q];
+                    }
+                }
+                v4f out;
+                out.x = hv[0] > 0.0f ? dh[0] : 0.0f;  // ReLU'(0) = 0
+                out.y = hv[1] > 0.0f ? dh[1] : 0.0f;
+                out.z = hv[2] > 0.0f ? dh[2] : 0.0f;
+                out.w = hv[3] > 0.0f ? dh[3] : 0.0f;
+                db1[0] += out.x;
+                db1[1] += out.y;
+                db1[2] += out.z;
+                db1[3] += out.w;
+                if (hleft >= 4 && h_vec_ok) {
+                    *reinterpret_cast<v4f*>(hrow) = out;
+                } else {
+                    if (hleft > 0) hrow[0] = out.x;
+                    if (hleft > 1) hrow[1] = out.y;
+                    if (hleft > 2) hrow[2] = out.z;
+                    if (hleft > 3) hrow[3] = out.w;
+                }
             }
-        }
-        v4f out;
-        out.x = hv[0] > 0.0f ? dh[0] : 0.0f;  // ReLU'(0) = 0
-        out.y = hv[1] > 0.0f ? dh[1] : 0.0f;
-        out.z = hv[2] > 0.0f ? dh[2] : 0.0f;
-        out.w = hv[3] > 0.0f ? dh[3] : 0.0f;
-        db1[0] += out.x;
-        db1[1] += out.y;
-        db1[2] += out.z;
-        db1[3] += out.w;
-        if (hleft >= 4 && h_vec_ok) {
-            *reinterpret_cast<v4f*>(hrow) = out;
-        } else {
-            if (hleft > 0) hrow[0] = out.x;
-            if (hleft > 1) hrow[1] = out.y;
-            if (hleft > 2) hrow[2] = out.z;
-            if (hleft > 3) hrow[3] = out.w;
         }
     }
     const int64_t T = (int64_t)hidden + (int64_t)hidden * classes + classes;
@@ -367,12 +477,13 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
     const float* b2 = W2 + (int64_t)hid * cls;
     const int64_t T = (int64_t)hid + (int64_t)hid * cls + cls;
 
-    // workspace: H [total][hid] | block partials [k*chunks][T]
-    int64_t chunks = std::max<int64_t>(1, ((int64_t)ctx->cu_count * 2 + k - 1) / k);
+    // workspace: H [total][hid] | dZ2 [total][cls] | block partials [k*chunks][T]
+    int64_t chunks = std::max<int64_t>(1, ((int64_t)ctx->cu_count * 4 + k - 1) / k);
     int64_t rpc = (rows + chunks - 1) / chunks;
     chunks = (rows + rpc - 1) / rpc;
     const size_t h_floats = (((size_t)total * hid) + 63) / 64 * 64;
-    const size_t need = sizeof(float) * (h_floats + (size_t)k * chunks * T);
+    const size_t z_floats = (((size_t)total * cls) + 63) / 64 * 64;
+    const size_t need = sizeof(float) * (h_floats + z_floats + (size_t)k * chunks * T);
     if (need > ctx->d_ws_bytes) {
         if (ctx->d_ws) {
             NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
@@ -389,7 +500,8 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
         ctx->d_ws_bytes = need;
     }
     float* H = ctx->d_ws;
-    float* partial = ctx->d_ws + h_floats;
+    float* dZ2 = ctx->d_ws + h_floats;
+    float* partial = dZ2 + z_floats;
 
     mlp_prof ps(ctx);
     {   // 1. H = relu(X W1 + b1), all partitions as one matrix
@@ -401,18 +513,23 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
                            (int)(hid % 4 == 0 && al(W1, 16)), (int)(hid % 2 == 0));
         NGC_HIP(ctx, hipGetLastError());
     }
-    {   // 2. logits, softmax, dZ2, dW2/db2/db1 partials, dZ1 over H
-        dim3 grid((unsigned)(k * chunks));
+    {   // 2. logits, softmax, dZ2; then dW2/db2/db1 partials and dZ1 over H
         const int hv = hid % 4 == 0;
-        if (cls <= 4)
-            hipLaunchKernelGGL((mlp_head_kernel<4>), grid, dim3(256), 0, ctx->stream, H, labels, W2, b2, partial,
-                               hid, cls, rows, (int)chunks, rpc, hv);
-        else if (cls <= 10)
-            hipLaunchKernelGGL((mlp_head_kernel<10>), grid, dim3(256), 0, ctx->stream, H, labels, W2, b2, partial,
-                               hid, cls, rows, (int)chunks, rpc, hv);
-        else
-            hipLaunchKernelGGL((mlp_head_kernel<16>), grid, dim3(256), 0, ctx->stream, H, labels, W2, b2, partial,
-                               hid, cls, rows, (int)chunks, rpc, hv);
+        dim3 lgrid((unsigned)((total + 63) / 64));
+        dim3 grid((unsigned)(k * chunks));
+#define NGC_MLP_HEAD(NCP)                                                                              \
+    hipLaunchKernelGGL((mlp_logits_kernel<NCP>), lgrid, dim3(64), 0, ctx->stream, (const float*)H, labels, W2, \
+                       b2, dZ2, hid, cls, total, hv);                                                  \
+    hipLaunchKernelGGL((mlp_back_kernel<NCP>), grid, dim3(256), 0, ctx->stream, H, (const float*)dZ2, W2,      \
+                       partial, hid, cls, rows, (int)chunks, rpc, hv);
+        if (cls <= 4) {
+            NGC_MLP_HEAD(4)
+        } else if (cls <= 10) {
+            NGC_MLP_HEAD(10)
+        } else {
+            NGC_MLP_HEAD(16)
+        }
+#undef NGC_MLP_HEAD
         NGC_HIP(ctx, hipGetLastError());
         dim3 rgrid((unsigned)((T + 255) / 256), (unsigned)k);
         hipLaunchKernelGGL(mlp_tail_reduce_kernel, rgrid, dim3(256), 0, ctx->stream, (const float*)partial,
