@@ -166,6 +166,42 @@ int ngc_select_decode_vec_first(const ngc_ctx* ctx, const uint8_t* straggler_mas
  */
 int ngc_decode(ngc_ctx* ctx, int layer, const double* a_host, const float* C_dev, float* g_dev);
 
+/*
+ * Redundancy-faithful execution (Sec. III, layered task scheduling): worker i
+ * works through the partitions of its nested supports layer by layer -- its own
+ * partition first (sigma = 0), then what each larger sigma adds, new partitions
+ * of a layer in cyclic order from index i -- and computes every partial gradient
+ * itself, so a partition held by s+1 workers is read s+1 times.
+ *
+ * ngc_worker_task_count: length T of the longest schedule (s_max + 1 for the
+ *   codes built here).  ngc_worker_schedule: the partitions of one worker in
+ *   task order (parts_out has room for T entries).
+ * ngc_worker_grads: progress_host[i] = number of tasks worker i has finished
+ *   (0..T).  W_dev: float [n][T][d]; row (i, t) receives the partial gradient
+ *   of the t-th partition of worker i's schedule for t < progress[i]; other
+ *   rows are left untouched.  Least squares and logistic losses.
+ * ngc_worker_encode: C[u][i][:] = sum_t B^(u)[i][part(i,t)] W[i][t][:] (Sec.
+ *   II-C, X = B G, from the worker's own copies) for every layer u whose
+ *   s[u]+1 tasks worker i has finished; rows of unfinished (u, i) are set to
+ *   zero.  C_dev: float [L][n][d].  At most 8 layers.
+ * ngc_select_from_progress: the main node's termination rule (Sec. IV, proof of
+ *   Theorem 1): the smallest layer u >= min_layer for which at least n - s[u]
+ *   workers have finished their layer-u tasks; mask_out[i] = 1 for workers not
+ *   among them; a_out = least-norm decode vector over those that are.
+ *   NGC_ERR_UNDECODABLE if no layer qualifies yet.  min_layer = index of sigma
+ *   restricts the scheme to a conventional gradient code with that fixed
+ *   sigma (Def. 1).  Host only.
+ */
+int ngc_worker_task_count(const ngc_ctx* ctx, int* tasks_out);
+int ngc_worker_schedule(const ngc_ctx* ctx, int worker, int* parts_out, int* count_out);
+int ngc_worker_grads(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_dev,
+                     const float* theta_dev, int64_t rows_per_part, const int* progress_host,
+                     float* W_dev);
+int ngc_worker_encode(ngc_ctx* ctx, const float* W_dev, const int* progress_host, float* C_dev);
+int ngc_select_from_progress(const ngc_ctx* ctx, const int* progress_host, int min_layer,
+                             int* layer_out, uint8_t* mask_out, double* a_out,
+                             double* residual_out);
+
 /* theta[:] -= scale * g[:]  with scale = eta/m  (Sec. II-B eq. (1)). */
 int ngc_update(ngc_ctx* ctx, float* theta_dev, const float* g_dev, double scale);
 

@@ -135,12 +135,16 @@ __device__ __forceinline__ void consume_group(const row_group<NV, R>& b, v4f (&a
 template <int NV, int R, int NBUF, int WAVES, int LOSS>
 __global__ __launch_bounds__(WAVES * 64) void grad_stream_kernel(
     const float* __restrict__ X, const float* __restrict__ y, const float* __restrict__ theta,
-    float* __restrict__ partial, int64_t rows, int chunks, int64_t rows_per_chunk) {
+    float* __restrict__ partial, int64_t rows, int chunks, int64_t rows_per_chunk,
+    const int* __restrict__ unit_part) {
     constexpr int DV = WAVES * 64 * NV;  // float4 per row
     __shared__ float ex_s[2][R * WAVES];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int j = blockIdx.x / chunks;
+    // a unit is one partial-gradient computation; by default unit j is partition j,
+    // with unit_part several units may work on the same partition (one per worker)
+    const int unit = blockIdx.x / chunks;
+    const int j = unit_part ? unit_part[unit] : unit;
     const int c = blockIdx.x % chunks;
     const int64_t r0 = (int64_t)c * rows_per_chunk;
     const int64_t r1 = rows < r0 + rows_per_chunk ? rows : r0 + rows_per_chunk;
@@ -192,30 +196,35 @@ __global__ __launch_bounds__(256) void resid_kernel(const float* __restrict__ X,
                                                     const float* __restrict__ y,
                                                     const float* __restrict__ theta,
                                                     float* __restrict__ resid, int64_t total_rows,
-                                                    int64_t d) {
+                                                    int64_t d, int64_t rows,
+                                                    const int* __restrict__ unit_part) {
     const int lane = threadIdx.x & 63;
     const int64_t wave0 = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t nwaves = (int64_t)gridDim.x * 4;
     for (int64_t r = wave0; r < total_rows; r += nwaves) {
-        const float* xr = X + r * d;
+        // row r of the unit list is row (r % rows) of partition unit_part[r / rows]
+        const int64_t src = unit_part ? (int64_t)unit_part[r / rows] * rows + r % rows : r;
+        const float* xr = X + src * d;
         float dot = 0.0f;
         for (int64_t c = lane; c < d; c += 64) dot += xr[c] * theta[c];
         float z = wave_sum(dot);
-        if (lane == 0) resid[r] = loss_slope<LOSS>(z, y[r]);
+        if (lane == 0) resid[r] = loss_slope<LOSS>(z, y[src]);
     }
 }
 
 __global__ __launch_bounds__(256) void xtr_kernel(const float* __restrict__ X,
                                                   const float* __restrict__ resid,
                                                   float* __restrict__ partial, int64_t rows,
-                                                  int64_t d, int chunks, int64_t rows_per_chunk) {
+                                                  int64_t d, int chunks, int64_t rows_per_chunk,
+                                                  const int* __restrict__ unit_part) {
     const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int chunk = blockIdx.y;
-    const int j = blockIdx.z;
+    const int j = blockIdx.z;  // unit
     if (c >= d) return;
     const int64_t r0 = (int64_t)chunk * rows_per_chunk;
     const int64_t r1 = rows < r0 + rows_per_chunk ? rows : r0 + rows_per_chunk;
-    const float* xp = X + ((int64_t)j * rows) * d + c;
+    const int part = unit_part ? unit_part[j] : j;
+    const float* xp = X + ((int64_t)part * rows) * d + c;
     const float* rp = resid + (int64_t)j * rows;
     float acc = 0.0f;
     for (int64_t r = r0; r < r1; ++r) acc += rp[r] * xp[r * d];
@@ -226,7 +235,8 @@ __global__ __launch_bounds__(256) void xtr_kernel(const float* __restrict__ X,
 template <typename VT>
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const VT* __restrict__ partial,
                                                               VT* __restrict__ G, int64_t dv,
-                                                              int chunks) {
+                                                              int chunks,
+                                                              const int* __restrict__ unit_row) {
     const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int j = blockIdx.y;
     if (c >= dv) return;
@@ -239,7 +249,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const VT* __restri
         acc = (((acc + a0) + a1) + a2) + a3;
     }
     for (; t < chunks; ++t) acc += p[(int64_t)t * dv];
-    G[(int64_t)j * dv + c] = acc;
+    G[(int64_t)(unit_row ? unit_row[j] : j) * dv + c] = acc;
 }
 
 // ---------------------------------------------------------------------------
@@ -361,6 +371,46 @@ __global__ __launch_bounds__(256) void update_kernel(float* __restrict__ theta,
 }
 
 // ---------------------------------------------------------------------------
+// Worker-side encode: message of worker i under layer u formed from the partial
+// gradients the worker computed itself, W[i][t] in task order,
+//   C[u][i][:] = sum_t wcoef[u][i][t] * W[i][t][:]
+// for every layer the worker has finished (unfinished ones are zero-filled).
+// By nesting, task t feeds every layer whose support contains its partition, so
+// each W row is read once and added into up to LMAX accumulators.
+// ---------------------------------------------------------------------------
+struct worker_progress {
+    unsigned char done[NGC_MAX_N];
+};
+
+template <typename VT, int V, int LMAX>
+__global__ __launch_bounds__(64) void worker_encode_kernel(const float* __restrict__ W,
+                                                           float* __restrict__ C,
+                                                           const int* __restrict__ needed,
+                                                           const float* __restrict__ wcoef, int n,
+                                                           int L, int T, int64_t d,
+                                                           worker_progress prog) {
+    const int i = blockIdx.y;
+    const int64_t c = ((int64_t)blockIdx.x * 64 + threadIdx.x) * V;
+    if (c >= d) return;
+    const int done = prog.done[i] < T ? prog.done[i] : T;
+    VT acc[LMAX];
+#pragma unroll
+    for (int u = 0; u < LMAX; ++u) acc[u] = (VT)(0.0f);
+    for (int t = 0; t < done; ++t) {
+        const VT x = *reinterpret_cast<const VT*>(W + ((int64_t)i * T + t) * d + c);
+#pragma unroll
+        for (int u = 0; u < LMAX; ++u)
+            if (u < L) acc[u] += wcoef[((int64_t)u * n + i) * T + t] * x;
+    }
+#pragma unroll
+    for (int u = 0; u < LMAX; ++u)
+        if (u < L) {
+            const VT out = prog.done[i] >= needed[u * n + i] ? acc[u] : (VT)(0.0f);
+            *reinterpret_cast<VT*>(C + ((int64_t)u * n + i) * d + c) = out;
+        }
+}
+
+// ---------------------------------------------------------------------------
 // Measurement probes (not part of the method): a plain copy and a plain read of
 // a known number of bytes, used to calibrate HBM byte counters and to find the
 // read bandwidth a trivial kernel reaches on the same buffers.
@@ -417,6 +467,8 @@ void ngc_dev_release(ngc_ctx* ctx) {
     for (auto e : ctx->event_pool) (void)hipEventDestroy(e);
     if (ctx->d_code) (void)hipFree(ctx->d_code);
     if (ctx->d_ws) (void)hipFree(ctx->d_ws);
+    if (ctx->d_units) (void)hipFree(ctx->d_units);
+    ctx->d_units = nullptr;
     ctx->d_code = nullptr;
     ctx->d_ws = nullptr;
     ctx->dev_ready = false;
@@ -510,14 +562,14 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 template <int NV, int R, int NBUF, int WAVES>
 static void launch_stream(ngc_ctx* ctx, int loss, const float* X, const float* y,
                           const float* theta, float* partial, int k, int64_t rows, int chunks,
-                          int64_t rpc) {
+                          int64_t rpc, const int* unit_part) {
     dim3 grid((unsigned)(k * chunks));
     if (loss == NGC_LOSS_LSQ)
         hipLaunchKernelGGL((grad_stream_kernel<NV, R, NBUF, WAVES, NGC_LOSS_LSQ>), grid, dim3(WAVES * 64), 0,
-                           ctx->stream, X, y, theta, partial, rows, chunks, rpc);
+                           ctx->stream, X, y, theta, partial, rows, chunks, rpc, unit_part);
     else
         hipLaunchKernelGGL((grad_stream_kernel<NV, R, NBUF, WAVES, NGC_LOSS_LOGISTIC>), grid, dim3(WAVES * 64),
-                           0, ctx->stream, X, y, theta, partial, rows, chunks, rpc);
+                           0, ctx->stream, X, y, theta, partial, rows, chunks, rpc, unit_part);
 }
 
 // Shape of the single-pass kernel for a given d, or waves = 0 if d has none.
@@ -539,21 +591,14 @@ static stream_shape pick_stream_shape(int64_t d) {
 int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float* theta,
                    int64_t rows, float* G);  // ngc_mlp.hip
 
-extern "C" int ngc_partition_grads(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_dev,
-                                   const float* theta_dev, int64_t rows, float* G_dev) {
-    if (!ctx) return NGC_ERR_INVALID;
-    if (!X_dev || !y_dev || !theta_dev || !G_dev) return ngc_fail(ctx, NGC_ERR_INVALID, "null device pointer");
-    if (rows < 1) return ngc_fail(ctx, NGC_ERR_INVALID, "rows_per_part must be positive");
-    if (!aligned16(X_dev) || !aligned16(theta_dev) || !aligned16(G_dev))
-        return ngc_fail(ctx, NGC_ERR_INVALID, "X, theta and G must be 16-byte aligned");
-    int rc = dev_init(ctx);
-    if (rc) return rc;
-    if (loss == NGC_LOSS_MLP2) {
-        if (!ctx->mlp_din) return ngc_fail(ctx, NGC_ERR_STATE, "call ngc_set_mlp2_shape first");
-        return ngc_mlp2_grads(ctx, X_dev, (const int*)y_dev, theta_dev, rows, G_dev);
-    }
-    if (loss != NGC_LOSS_LSQ && loss != NGC_LOSS_LOGISTIC) return ngc_fail(ctx, NGC_ERR_INVALID, "unknown loss");
-    const int k = ctx->n;
+// Gradients of `units` partial-gradient computations (least squares / logistic).  Unit q works
+// on partition unit_part[q] (q itself if unit_part is null) and its result goes to row
+// unit_row[q] of G_dev (row q if null); both maps are device arrays.
+static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_dev,
+                      const float* theta_dev, int64_t rows, float* G_dev, int units,
+                      const int* unit_part, const int* unit_row) {
+    int rc = NGC_OK;
+    const int k = units;
     const int64_t d = ctx->d;
     const float* y = (const float*)y_dev;
     const int64_t wave_slots = (int64_t)ctx->cu_count * 8;  // 2 waves per SIMD
@@ -572,22 +617,22 @@ extern "C" int ngc_partition_grads(ngc_ctx* ctx, int loss, const float* X_dev, c
         {
             prof_scope ps(ctx, NGC_KERNEL_GRAD);
 #define NGC_STREAM_CASE(W) \
-    case W: launch_stream<4, 4, 2, W>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc); break;
+    case W: launch_stream<4, 4, 2, W>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc, unit_part); break;
             if (sh.nv == 4) {
                 switch (sh.waves) {
                     NGC_STREAM_CASE(1) NGC_STREAM_CASE(2) NGC_STREAM_CASE(3) NGC_STREAM_CASE(4)
                     NGC_STREAM_CASE(6) NGC_STREAM_CASE(8)
                 }
             } else if (sh.nv == 8 && sh.waves == 6) {
-                launch_stream<8, 2, 2, 6>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc);
+                launch_stream<8, 2, 2, 6>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc, unit_part);
             } else if (sh.nv == 8) {
-                launch_stream<8, 2, 2, 8>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc);
+                launch_stream<8, 2, 2, 8>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc, unit_part);
             } else if (sh.nv == 1) {
-                launch_stream<1, 16, 2, 1>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc);
+                launch_stream<1, 16, 2, 1>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc, unit_part);
             } else if (sh.nv == 2) {
-                launch_stream<2, 8, 2, 1>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc);
+                launch_stream<2, 8, 2, 1>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc, unit_part);
             } else {
-                launch_stream<3, 4, 2, 1>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc);
+                launch_stream<3, 4, 2, 1>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc, unit_part);
             }
 #undef NGC_STREAM_CASE
         }
@@ -597,7 +642,7 @@ extern "C" int ngc_partition_grads(ngc_ctx* ctx, int loss, const float* X_dev, c
             const int64_t dv = d / 4;
             dim3 grid((unsigned)((dv + 255) / 256), (unsigned)k);
             hipLaunchKernelGGL((reduce_partials_kernel<v4f>), grid, dim3(256), 0, ctx->stream,
-                               (const v4f*)ctx->d_ws, (v4f*)G_dev, dv, (int)chunks);
+                               (const v4f*)ctx->d_ws, (v4f*)G_dev, dv, (int)chunks, unit_row);
         }
         NGC_HIP(ctx, hipGetLastError());
         return NGC_OK;
@@ -619,24 +664,41 @@ extern "C" int ngc_partition_grads(ngc_ctx* ctx, int loss, const float* X_dev, c
         const int64_t blocks = std::min<int64_t>((total_rows + 3) / 4, (int64_t)ctx->cu_count * 8);
         if (loss == NGC_LOSS_LSQ)
             hipLaunchKernelGGL((resid_kernel<NGC_LOSS_LSQ>), dim3((unsigned)blocks), dim3(256), 0, ctx->stream,
-                               X_dev, y, theta_dev, resid, total_rows, d);
+                               X_dev, y, theta_dev, resid, total_rows, d, rows, unit_part);
         else
             hipLaunchKernelGGL((resid_kernel<NGC_LOSS_LOGISTIC>), dim3((unsigned)blocks), dim3(256), 0,
-                               ctx->stream, X_dev, y, theta_dev, resid, total_rows, d);
+                               ctx->stream, X_dev, y, theta_dev, resid, total_rows, d, rows, unit_part);
         NGC_HIP(ctx, hipGetLastError());
         dim3 grid((unsigned)col_blocks, (unsigned)chunks, (unsigned)k);
         hipLaunchKernelGGL(xtr_kernel, grid, dim3(256), 0, ctx->stream, X_dev, resid, partial, rows, d,
-                           (int)chunks, rpc);
+                           (int)chunks, rpc, unit_part);
     }
     NGC_HIP(ctx, hipGetLastError());
     {
         prof_scope ps(ctx, NGC_KERNEL_REDUCE);
         dim3 grid((unsigned)((d + 255) / 256), (unsigned)k);
         hipLaunchKernelGGL((reduce_partials_kernel<float>), grid, dim3(256), 0, ctx->stream,
-                           (const float*)partial, G_dev, d, (int)chunks);
+                           (const float*)partial, G_dev, d, (int)chunks, unit_row);
     }
     NGC_HIP(ctx, hipGetLastError());
     return NGC_OK;
+}
+
+extern "C" int ngc_partition_grads(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_dev,
+                                   const float* theta_dev, int64_t rows, float* G_dev) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (!X_dev || !y_dev || !theta_dev || !G_dev) return ngc_fail(ctx, NGC_ERR_INVALID, "null device pointer");
+    if (rows < 1) return ngc_fail(ctx, NGC_ERR_INVALID, "rows_per_part must be positive");
+    if (!aligned16(X_dev) || !aligned16(theta_dev) || !aligned16(G_dev))
+        return ngc_fail(ctx, NGC_ERR_INVALID, "X, theta and G must be 16-byte aligned");
+    int rc = dev_init(ctx);
+    if (rc) return rc;
+    if (loss == NGC_LOSS_MLP2) {
+        if (!ctx->mlp_din) return ngc_fail(ctx, NGC_ERR_STATE, "call ngc_set_mlp2_shape first");
+        return ngc_mlp2_grads(ctx, X_dev, (const int*)y_dev, theta_dev, rows, G_dev);
+    }
+    if (loss != NGC_LOSS_LSQ && loss != NGC_LOSS_LOGISTIC) return ngc_fail(ctx, NGC_ERR_INVALID, "unknown loss");
+    return grads_impl(ctx, loss, X_dev, y_dev, theta_dev, rows, G_dev, ctx->n, nullptr, nullptr);
 }
 
 // ---- code tables on the device --------------------------------------------
@@ -823,6 +885,114 @@ extern "C" int ngc_probe_read(ngc_ctx* ctx, const void* src_dev, int64_t bytes) 
         prof_scope ps(ctx, NGC_KERNEL_PROBE);
         hipLaunchKernelGGL(probe_read_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream,
                            (const v4f*)src_dev, ctx->d_ws, nvec);
+    }
+    NGC_HIP(ctx, hipGetLastError());
+    return NGC_OK;
+}
+
+// ---- redundancy-faithful worker execution ------------------------------------------------------
+static int ensure_units(ngc_ctx* ctx, size_t bytes) {
+    if (bytes <= ctx->d_units_bytes) return NGC_OK;
+    if (ctx->d_units) {
+        NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        NGC_HIP(ctx, hipFree(ctx->d_units));
+        ctx->d_units = nullptr;
+        ctx->d_units_bytes = 0;
+    }
+    void* p = nullptr;
+    if (hipMalloc(&p, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return ngc_fail(ctx, NGC_ERR_NOMEM, "table allocation failed");
+    }
+    ctx->d_units = (int*)p;
+    ctx->d_units_bytes = bytes;
+    return NGC_OK;
+}
+
+extern "C" int ngc_worker_grads(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_dev,
+                                const float* theta_dev, int64_t rows, const int* progress_host,
+                                float* W_dev) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (!X_dev || !y_dev || !theta_dev || !W_dev || !progress_host) return ngc_fail(ctx, NGC_ERR_INVALID, "null pointer");
+    if (rows < 1) return ngc_fail(ctx, NGC_ERR_INVALID, "rows_per_part must be positive");
+    if (loss != NGC_LOSS_LSQ && loss != NGC_LOSS_LOGISTIC)
+        return ngc_fail(ctx, NGC_ERR_INVALID, "worker execution supports the least-squares and logistic losses");
+    if (!aligned16(X_dev) || !aligned16(theta_dev) || !aligned16(W_dev))
+        return ngc_fail(ctx, NGC_ERR_INVALID, "X, theta and W must be 16-byte aligned");
+    int rc = dev_init(ctx);
+    if (rc) return rc;
+    ngc_worker_plan plan;
+    rc = ngc_make_worker_plan(ctx, plan);
+    if (rc) return rc;
+    const int n = ctx->n, T = plan.T;
+    std::vector<int> maps;  // unit_part | unit_row
+    std::vector<int> part, row;
+    for (int i = 0; i < n; ++i) {
+        if (progress_host[i] < 0) return ngc_fail(ctx, NGC_ERR_INVALID, "negative progress");
+        const int done = std::min<int>(progress_host[i], (int)plan.order[i].size());
+        for (int t = 0; t < done; ++t) {
+            part.push_back(plan.order[i][t]);
+            row.push_back(i * T + t);
+        }
+    }
+    const int units = (int)part.size();
+    if (units == 0) return NGC_OK;
+    maps = part;
+    maps.insert(maps.end(), row.begin(), row.end());
+    rc = ensure_units(ctx, maps.size() * sizeof(int));
+    if (rc) return rc;
+    // the maps of an earlier call may still be in use by its kernels
+    NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    NGC_HIP(ctx, hipMemcpy(ctx->d_units, maps.data(), maps.size() * sizeof(int), hipMemcpyHostToDevice));
+    return grads_impl(ctx, loss, X_dev, y_dev, theta_dev, rows, W_dev, units, ctx->d_units,
+                      ctx->d_units + units);
+}
+
+extern "C" int ngc_worker_encode(ngc_ctx* ctx, const float* W_dev, const int* progress_host,
+                                 float* C_dev) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (!W_dev || !C_dev || !progress_host) return ngc_fail(ctx, NGC_ERR_INVALID, "null pointer");
+    if (ctx->L > 8) return ngc_fail(ctx, NGC_ERR_INVALID, "worker encode supports at most 8 layers");
+    int rc = dev_init(ctx);
+    if (rc) return rc;
+    ngc_worker_plan plan;
+    rc = ngc_make_worker_plan(ctx, plan);
+    if (rc) return rc;
+    const int n = ctx->n, L = ctx->L, T = plan.T;
+    const int64_t d = ctx->d;
+    // tables: int needed[L*n] | float wcoef[L*n*T]
+    std::vector<int> tab((size_t)L * n + (size_t)L * n * T, 0);
+    float* wcoef = reinterpret_cast<float*>(tab.data() + (size_t)L * n);
+    for (int u = 0; u < L; ++u)
+        for (int i = 0; i < n; ++i) {
+            tab[(size_t)u * n + i] = plan.needed[(size_t)u * n + i];
+            for (size_t t = 0; t < plan.order[i].size(); ++t)
+                wcoef[((size_t)u * n + i) * T + t] = (float)ctx->code[u].B[(size_t)i * n + plan.order[i][t]];
+        }
+    worker_progress prog;
+    for (int i = 0; i < NGC_MAX_N; ++i) prog.done[i] = 0;
+    for (int i = 0; i < n; ++i) {
+        if (progress_host[i] < 0) return ngc_fail(ctx, NGC_ERR_INVALID, "negative progress");
+        prog.done[i] = (unsigned char)std::min<int>(progress_host[i], 255);
+    }
+    // the gradient maps share the buffer: tables go behind them
+    const size_t off = ((size_t)2 * n * T + 63) / 64 * 64;
+    rc = ensure_units(ctx, (off + tab.size()) * sizeof(int));
+    if (rc) return rc;
+    NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    NGC_HIP(ctx, hipMemcpy(ctx->d_units + off, tab.data(), tab.size() * sizeof(int), hipMemcpyHostToDevice));
+    const int* needed = ctx->d_units + off;
+    const float* wc = reinterpret_cast<const float*>(needed + (size_t)L * n);
+    const int V = vec_width(d, W_dev, C_dev);
+    dim3 grid((unsigned)((d + 64 * V - 1) / (64 * V)), (unsigned)n);
+    {
+        prof_scope ps(ctx, NGC_KERNEL_ENCODE);
+        if (V == 4)
+            hipLaunchKernelGGL((worker_encode_kernel<v4f, 4, 8>), grid, dim3(64), 0, ctx->stream, W_dev, C_dev, needed, wc, n, L, T, d, prog);
+        else if (V == 2)
+            hipLaunchKernelGGL((worker_encode_kernel<v2f, 2, 8>), grid, dim3(64), 0, ctx->stream, W_dev, C_dev, needed, wc, n, L, T, d, prog);
+        else
+            hipLaunchKernelGGL((worker_encode_kernel<float, 1, 8>), grid, dim3(64), 0, ctx->stream, W_dev, C_dev, needed, wc, n, L, T, d, prog);
     }
     NGC_HIP(ctx, hipGetLastError());
     return NGC_OK;

@@ -330,3 +330,90 @@ extern "C" int ngc_select_decode_vec_first(const ngc_ctx* ctx, const uint8_t* st
                                            int* layer_out, double* a_out, double* residual_out) {
     return select_impl(ctx, straggler_mask, layer_out, a_out, residual_out, true);
 }
+
+// ---------------------------------------------------------------------------
+// Redundancy-faithful execution (Sec. III, layered task scheduling; Sec. IV,
+// termination): every worker works through its own partitions layer by layer.
+// ---------------------------------------------------------------------------
+int ngc_make_worker_plan(const ngc_ctx* ctx, ngc_worker_plan& plan) {
+    const int n = ctx->n, L = ctx->L;
+    for (int u = 0; u < L; ++u)
+        if (!ctx->code[u].set) return ngc_fail(ctx, NGC_ERR_STATE, "a layer has no code yet");
+    plan.order.assign(n, {});
+    plan.needed.assign((size_t)L * n, 0);
+    plan.T = 0;
+    for (int i = 0; i < n; ++i) {
+        std::vector<char> have(n, 0);
+        for (int u = 0; u < L; ++u) {
+            const std::vector<double>& B = ctx->code[u].B;
+            int weight = 0;
+            // a layer adds its new partitions in cyclic order starting at the worker's own index
+            for (int t = 0; t < n; ++t) {
+                const int j = (i + t) % n;
+                if (B[(size_t)i * n + j] == 0.0) continue;
+                ++weight;
+                if (!have[j]) {
+                    have[j] = 1;
+                    plan.order[i].push_back(j);
+                }
+            }
+            plan.needed[(size_t)u * n + i] = weight;
+        }
+        plan.T = std::max(plan.T, (int)plan.order[i].size());
+    }
+    return NGC_OK;
+}
+
+extern "C" int ngc_worker_task_count(const ngc_ctx* ctx, int* tasks_out) {
+    if (!ctx || !tasks_out) return NGC_ERR_INVALID;
+    ngc_worker_plan plan;
+    int rc = ngc_make_worker_plan(ctx, plan);
+    if (rc) return rc;
+    *tasks_out = plan.T;
+    return NGC_OK;
+}
+
+extern "C" int ngc_worker_schedule(const ngc_ctx* ctx, int worker, int* parts_out, int* count_out) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (worker < 0 || worker >= ctx->n || !parts_out || !count_out) return ngc_fail(ctx, NGC_ERR_INVALID, "bad worker or null output");
+    ngc_worker_plan plan;
+    int rc = ngc_make_worker_plan(ctx, plan);
+    if (rc) return rc;
+    *count_out = (int)plan.order[worker].size();
+    for (size_t t = 0; t < plan.order[worker].size(); ++t) parts_out[t] = plan.order[worker][t];
+    return NGC_OK;
+}
+
+extern "C" int ngc_select_from_progress(const ngc_ctx* ctx, const int* progress, int min_layer,
+                                        int* layer_out, uint8_t* mask_out, double* a_out,
+                                        double* residual_out) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (!progress || !layer_out || !mask_out || !a_out) return ngc_fail(ctx, NGC_ERR_INVALID, "null argument");
+    if (min_layer < 0 || min_layer >= ctx->L) return ngc_fail(ctx, NGC_ERR_INVALID, "min_layer out of range");
+    const int n = ctx->n;
+    ngc_worker_plan plan;
+    int rc = ngc_make_worker_plan(ctx, plan);
+    if (rc) return rc;
+    for (int i = 0; i < n; ++i) {
+        a_out[i] = 0.0;
+        mask_out[i] = 1;
+        if (progress[i] < 0) return ngc_fail(ctx, NGC_ERR_INVALID, "negative progress");
+    }
+    *layer_out = -1;
+    if (residual_out) *residual_out = 0.0;
+    for (int u = min_layer; u < ctx->L; ++u) {
+        int rows[NGC_MAX_N];
+        int ns = 0;
+        for (int i = 0; i < n; ++i)
+            if (progress[i] >= plan.needed[(size_t)u * n + i]) rows[ns++] = i;
+        if (ns < n - ctx->s[u]) continue;  // not enough finished workers for this component code
+        *layer_out = u;
+        for (int t = 0; t < ns; ++t) mask_out[rows[t]] = 0;
+        double resid = 0.0;
+        ngc_min_norm_decode(ctx->code[u].B.data(), n, rows, ns, a_out, &resid);
+        if (residual_out) *residual_out = resid;
+        if (!(resid <= 1e-6)) return ngc_fail(ctx, NGC_ERR_SINGULAR, "decode residual above tolerance");
+        return NGC_OK;
+    }
+    return ngc_fail(ctx, NGC_ERR_UNDECODABLE, "no component code has enough finished workers");
+}

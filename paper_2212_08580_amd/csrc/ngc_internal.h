@@ -48,6 +48,8 @@ struct ngc_ctx {
     size_t code_nnz = 0;             // non-zeros over all layers in d_code
     float* d_ws = nullptr;           // workspace: block partials / residuals / MLP activations
     size_t d_ws_bytes = 0;
+    int* d_units = nullptr;          // unit -> partition / output row maps, worker tables
+    size_t d_units_bytes = 0;
 
     unsigned profile_mask = 0;       // bit k: time launches of kernel id k
     std::vector<ngc_profile_rec> prof;
@@ -60,6 +62,16 @@ int ngc_fail(const ngc_ctx* ctx, int code, const std::string& msg);
 
 // defined in ngc_device.hip
 void ngc_dev_release(ngc_ctx* ctx);
+
+// Layered task schedule of every worker derived from the code tables (ngc_host.cpp):
+// order[i] = partitions in the order worker i computes them, needed[u*n+i] = tasks worker i must
+// have finished to form its layer-u message, T = longest schedule.  All layers must be set.
+struct ngc_worker_plan {
+    std::vector<std::vector<int>> order;
+    std::vector<int> needed;
+    int T = 0;
+};
+int ngc_make_worker_plan(const ngc_ctx* ctx, ngc_worker_plan& plan);
 
 // defined in ngc_solve.cpp: least-norm a_S with a_S^T B_S = 1^T.
 // rows: indices of responders (size ns).  B: n x n row-major.  a_out: n entries,

@@ -36,6 +36,8 @@ EXPORTS = (
     "ngc_create", "ngc_destroy", "ngc_set_code", "ngc_get_code", "ngc_build_code",
     "ngc_set_mlp2_shape", "ngc_partition_grads", "ngc_encode", "ngc_select_decode_vec",
     "ngc_select_decode_vec_first", "ngc_decode", "ngc_update", "ngc_sync",
+    "ngc_worker_task_count", "ngc_worker_schedule", "ngc_worker_grads", "ngc_worker_encode",
+    "ngc_select_from_progress",
     "ngc_profile_enable", "ngc_profile_read", "ngc_probe_copy", "ngc_probe_read",
     "ngc_strerror", "ngc_last_error",
 )
@@ -62,6 +64,12 @@ _lib.ngc_select_decode_vec.argtypes = [_vp, _vp, ctypes.POINTER(_i), _vp, ctypes
 _lib.ngc_select_decode_vec_first.argtypes = _lib.ngc_select_decode_vec.argtypes
 _lib.ngc_decode.argtypes = [_vp, _i, _vp, _vp, _vp]
 _lib.ngc_update.argtypes = [_vp, _vp, _vp, _dbl]
+_lib.ngc_worker_task_count.argtypes = [_vp, ctypes.POINTER(_i)]
+_lib.ngc_worker_schedule.argtypes = [_vp, _i, _vp, ctypes.POINTER(_i)]
+_lib.ngc_worker_grads.argtypes = [_vp, _i, _vp, _vp, _vp, _i64, _vp, _vp]
+_lib.ngc_worker_encode.argtypes = [_vp, _vp, _vp, _vp]
+_lib.ngc_select_from_progress.argtypes = [_vp, _vp, _i, ctypes.POINTER(_i), _vp, _vp,
+                                          ctypes.POINTER(_dbl)]
 _lib.ngc_sync.argtypes = [_vp]
 _lib.ngc_profile_enable.argtypes = [_vp, _i]
 _lib.ngc_profile_read.argtypes = [_vp, _vp, _vp]
@@ -175,6 +183,48 @@ def ngc_select_decode_vec_first(ctx, mask, n):
 def ngc_decode(ctx, layer, a, C, g):
     a, pa = _host(a, np.float64)
     _check(_lib.ngc_decode(ctx, int(layer), pa, _dev(C), _dev(g)), ctx)
+
+
+def ngc_worker_task_count(ctx):
+    t = ctypes.c_int(0)
+    _check(_lib.ngc_worker_task_count(ctx, ctypes.byref(t)), ctx)
+    return t.value
+
+
+def ngc_worker_schedule(ctx, worker):
+    T = ngc_worker_task_count(ctx)
+    parts = np.zeros(max(T, 1), np.int32)
+    cnt = ctypes.c_int(0)
+    _check(_lib.ngc_worker_schedule(ctx, int(worker), parts.ctypes.data_as(ctypes.c_void_p),
+                                    ctypes.byref(cnt)), ctx)
+    return [int(p) for p in parts[:cnt.value]]
+
+
+def ngc_worker_grads(ctx, loss, X, y, theta, rows_per_part, progress, W):
+    progress, pp = _host(progress, np.int32)
+    _check(_lib.ngc_worker_grads(ctx, int(loss), _dev(X), _dev(y), _dev(theta), int(rows_per_part),
+                                 pp, _dev(W)), ctx)
+
+
+def ngc_worker_encode(ctx, W, progress, C):
+    progress, pp = _host(progress, np.int32)
+    _check(_lib.ngc_worker_encode(ctx, _dev(W), pp, _dev(C)), ctx)
+
+
+def ngc_select_from_progress(ctx, progress, n, min_layer=0):
+    """-> (layer, mask [n] uint8, a [n] fp64, residual)."""
+    progress, pp = _host(progress, np.int32)
+    if progress.size != n:
+        raise ValueError("progress must have n entries")
+    a = np.zeros(n, np.float64)
+    mask = np.ones(n, np.uint8)
+    layer = ctypes.c_int(-1)
+    resid = ctypes.c_double(0.0)
+    rc = _lib.ngc_select_from_progress(ctx, pp, int(min_layer), ctypes.byref(layer),
+                                       mask.ctypes.data_as(ctypes.c_void_p),
+                                       a.ctypes.data_as(ctypes.c_void_p), ctypes.byref(resid))
+    _check(rc, ctx)
+    return layer.value, mask, a, resid.value
 
 
 def ngc_update(ctx, theta, g, scale):

@@ -231,3 +231,57 @@ def test_null_arguments_are_rejected_not_dereferenced(ngc):
         assert ngc.ngc_strerror(-2).startswith("more stragglers")
     finally:
         ngc.ngc_destroy(ctx)
+
+
+# ---- redundancy-faithful execution: schedule and termination rule (host only) -----------------
+@pytest.mark.parametrize("n,layers,kind", [(8, [0, 1, 3], "cyclic"), (8, [0, 1, 3, 7], "fracrep"),
+                                           (6, [0, 2, 3], "cyclic")])
+def test_worker_schedule_matches_oracle(ngc, n, layers, kind):
+    from oracle import workers as ow
+    Bs = codes.nested_code(n, layers, kind, seed=0, draws=2)
+    ctx = ngc.ngc_create(n, n, layers, 4)
+    try:
+        for u, B in enumerate(Bs):
+            ngc.ngc_set_code(ctx, u, B)
+        assert ngc.ngc_worker_task_count(ctx) == layers[-1] + 1
+        for i in range(n):
+            assert ngc.ngc_worker_schedule(ctx, i) == ow.task_order(Bs, i)
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
+def test_select_from_progress_matches_oracle_rule(ngc):
+    from oracle import workers as ow
+    n, layers = 6, [0, 1, 3]
+    Bs = codes.nested_code(n, layers, "cyclic", seed=1, draws=2)
+    ctx = ngc.ngc_create(n, n, layers, 4)
+    try:
+        for u, B in enumerate(Bs):
+            ngc.ngc_set_code(ctx, u, B)
+        rng = np.random.default_rng(0)
+        seen = set()
+        cases = [rng.integers(0, 5, n) for _ in range(300)] + [np.full(n, t) for t in range(5)]
+        for progress in cases:
+            for min_layer in (0, 2):
+                try:
+                    u_o, mask_o = ow.terminate(Bs, layers, progress, min_layer)
+                except coding.Undecodable:
+                    with pytest.raises(ngc.NgcError) as e:
+                        ngc.ngc_select_from_progress(ctx, progress, n, min_layer)
+                    assert e.value.code == ngc.NGC_ERR_UNDECODABLE
+                    seen.add(-1)
+                    continue
+                u, mask, a, r = ngc.ngc_select_from_progress(ctx, progress, n, min_layer)
+                assert u == u_o and np.array_equal(mask, mask_o)
+                a_o = codes.min_norm_decode_vector(Bs[u_o], np.flatnonzero(mask_o == 0))
+                assert np.array_equal(a != 0, a_o != 0)
+                assert np.abs(a - a_o).max() <= 1e-8 * max(1.0, np.abs(a_o).max())
+                assert r < 1e-8
+                seen.add(u)
+        assert seen == {-1, 0, 1, 2}
+        with pytest.raises(ngc.NgcError):
+            ngc.ngc_select_from_progress(ctx, [1] * n, n, 7)
+        with pytest.raises(ngc.NgcError):
+            ngc.ngc_select_from_progress(ctx, [-1] * n, n, 0)
+    finally:
+        ngc.ngc_destroy(ctx)
