@@ -18,4 +18,4 @@ B_sigma beyond the properties of Def. 1 (the paper delegates them to a cited
 routine and prints no example); B is therefore handed to the library as an
 input.
 """
-from . import codes, coding, gradients, workers  # noqa: F401
+from . import codes, coding, gradients, latency, workers  # noqa: F401
