@@ -237,6 +237,51 @@ def bench_workers(args, w, wl, ngc, torch, np):
     print(json.dumps(out), flush=True)
 
 
+def bench_latency(args, ngc, torch, np):
+    """Latency model of Sec. IV at the parameters of the paper's figures (n = k = 8, lambda = 0.5,
+    rho = 0.5, eps = 0.1, p_e = 0.05, t - gamma in [2, 18]): closed-form CDFs of the nested code
+    (s_max = 2, 3, 4, 6) and of conventional codes (sigma = 0..6), and a Monte-Carlo simulation of
+    the same model on the GPU.  value = simulated trials per second for s_max = 6."""
+    dev = torch.device("cuda:0")
+    n, par = 8, (0.5, 0.5, 0.1, 0.0, 0.05)
+    ts = np.linspace(2.0, 18.0, 33)
+    trials = 1 << 22
+    curves, worst = {}, 0.0
+    rate = None
+    for smax in (2, 3, 4, 6):
+        L = torch.empty((smax + 1, trials), dtype=torch.float64, device=dev)
+        T = torch.empty(trials, dtype=torch.float64, device=dev)
+        stream = torch.cuda.current_stream().cuda_stream
+        ngc.ngc_latency_simulate(stream, n, smax, *par, 99, trials, L, T)      # warm-up
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for rep in range(args.steps):
+            ngc.ngc_latency_simulate(stream, n, smax, *par, 100 + rep, trials, L, T)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / args.steps
+        if smax == 6:
+            rate = trials / dt
+        closed = ngc.ngc_latency_cdf_ngc(n, smax, *par, ts)
+        emp = np.array([float((T <= float(t)).double().mean().item()) for t in ts])
+        worst = max(worst, float(np.max(np.abs(emp - closed))))
+        curves["nested_smax_%d" % smax] = [round(float(v), 5) for v in closed[::4]]
+    for sigma in (0, 1, 2, 3, 4, 6):
+        curves["fixed_sigma_%d" % sigma] = [round(float(v), 5) for v in
+                                            ngc.ngc_latency_cdf_gc(n, sigma, *par, ts)[::4]]
+    out = {
+        "metric": "partition-gradient samples/s + encode/decode GB/s vs HBM peak, n=32 d=4096",
+        "value": round(rate, 1), "unit": "simulated iterations/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": 1, "ms_per_step": round(trials / rate * 1e3, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "latency model, n=k=8, lambda=0.5, rho=0.5, eps=0.1, p_e=0.05",
+                   "trials_per_step": trials},
+        "t_minus_gamma": [float(t) for t in ts[::4]], "cdf": curves,
+        "max_abs_deviation_simulation_vs_closed_form": round(worst, 6),
+        "uncoded_limit": float(ngc.ngc_latency_cdf_gc(n, 0, *par, [1e6])[0]),
+    }
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -245,7 +290,7 @@ def main():
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
-    ap.add_argument("--mode", default="pipeline", choices=["pipeline", "workers"])
+    ap.add_argument("--mode", default="pipeline", choices=["pipeline", "workers", "latency"])
     ap.add_argument("--cpu-parts", type=int, default=32)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -262,6 +307,8 @@ def main():
         sys.exit(2)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.mode == "latency":
+        return bench_latency(args, ngc, torch, np)
     w = wl.CONFIGS[args.workload]
     if w.loss < 0:
         return bench_codec(args, w, wl, ngc, torch, np)

@@ -202,6 +202,36 @@ int ngc_select_from_progress(const ngc_ctx* ctx, const int* progress_host, int m
                              int* layer_out, uint8_t* mask_out, double* a_out,
                              double* residual_out);
 
+/*
+ * Latency model (Secs. II-D and IV).  A non-failing worker finishes u tasks at
+ * gamma + eps + u*rho + Erlang(u, lambda) (eq. (2)); it fails for good with
+ * probability pe.  1 <= n <= 64, 0 <= sigma, smax < n, lambda > 0, the other
+ * parameters >= 0, pe <= 1.
+ *
+ * ngc_latency_cdf_gc: P(T_GC <= t[q]) of a conventional (n,k,sigma) gradient
+ *   code (Lemma 1).  ngc_latency_cdf_ngc: P(T_NGC <= t[q]) of an (n,k,smax)
+ *   nested code with component codes sigma = 0..smax (Theorem 1, summation
+ *   limits as in its proof: a configuration is undecodable when at every layer
+ *   u fewer than n-u+1 workers have finished u tasks).  t and cdf_out are host
+ *   arrays of nt entries.  Host only.
+ * ngc_latency_simulate: Monte-Carlo draws of the same model on the device,
+ *   one wave per trial.  L_dev: double [smax+1][trials]; L[u-1][r] = time at
+ *   which n-u+1 workers have finished u tasks in trial r (+inf if never), so
+ *   the conventional code with tolerance sigma has latency L[sigma][r].
+ *   Tngc_dev (may be NULL): double [trials], min_u L[u-1][r], the nested
+ *   code's latency.  Random numbers: Philox-4x32-10 with key = seed and
+ *   counter = (trial, worker, block, 0); word 0 of a worker decides failure
+ *   (U < pe), word u is its u-th task time rho - log(U)/lambda,
+ *   U = (word + 0.5)/2^32.  trials < 2^32.  hip_stream: hipStream_t or NULL.
+ */
+int ngc_latency_cdf_gc(int n, int sigma, double lambda, double rho, double eps, double gamma,
+                       double pe, const double* t, int nt, double* cdf_out);
+int ngc_latency_cdf_ngc(int n, int smax, double lambda, double rho, double eps, double gamma,
+                        double pe, const double* t, int nt, double* cdf_out);
+int ngc_latency_simulate(void* hip_stream, int n, int smax, double lambda, double rho, double eps,
+                         double gamma, double pe, uint64_t seed, int64_t trials, double* L_dev,
+                         double* Tngc_dev);
+
 /* theta[:] -= scale * g[:]  with scale = eta/m  (Sec. II-B eq. (1)). */
 int ngc_update(ngc_ctx* ctx, float* theta_dev, const float* g_dev, double scale);
 

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libngc.so")
-SOURCES = ["ngc_host.cpp", "ngc_solve.cpp", "ngc_device.hip", "ngc_mlp.hip"]
+SOURCES = ["ngc_host.cpp", "ngc_solve.cpp", "ngc_device.hip", "ngc_mlp.hip", "ngc_latency.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Xarch_host", "-mavx2", "-Xarch_host", "-mfma",

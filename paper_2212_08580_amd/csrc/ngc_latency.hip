@@ -1,0 +1,218 @@
+// Latency model of Secs. II-D and IV: closed forms on the host (Lemma 1,
+// Theorem 1) and a Monte-Carlo simulation of eq. (2) on the device.
+//
+// A non-failing worker finishes u tasks at gamma + eps + u*rho + Erlang(u, lambda);
+// a worker fails for good with probability p_e.  A conventional code with
+// tolerance sigma is done when n - sigma workers have finished sigma + 1 tasks,
+// a nested code when any of its component codes sigma = 0..s_max is.
+//
+// Readings: the Erlang CDF sums to u-1 (eq. (3) prints u; the identity in the
+// proof of Corollary 1 needs u-1); the summation limits of Theorem 1 follow its
+// proof (a configuration counts as "not decodable" when at every layer u fewer
+// than n-u+1 workers have finished u tasks), not the limit printed in the
+// statement, which lets decodable configurations through.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <vector>
+
+#include "../../include/ngc.h"
+
+namespace {
+
+// F_u(t): P(gamma + eps + u rho + Erlang(u, lam) <= t)
+double layer_cdf(int u, double t, double lam, double rho, double eps, double gamma) {
+    const double tau = t - (gamma + eps + u * rho);
+    if (tau < 0.0) return 0.0;
+    if (u == 0) return 1.0;
+    const double x = lam * tau;
+    double term = 1.0, sum = 1.0;  // sum_{v<u} x^v / v!
+    for (int v = 1; v < u; ++v) {
+        term *= x / v;
+        sum += term;
+    }
+    return 1.0 - std::exp(-x) * sum;
+}
+
+struct binomials {
+    std::vector<double> c;
+    int n;
+    explicit binomials(int n_) : c((size_t)(n_ + 1) * (n_ + 1), 0.0), n(n_) {
+        for (int a = 0; a <= n; ++a) {
+            c[(size_t)a * (n + 1)] = 1.0;
+            for (int b = 1; b <= a; ++b)
+                c[(size_t)a * (n + 1) + b] = c[(size_t)(a - 1) * (n + 1) + b - 1] +
+                                             (b <= a - 1 ? c[(size_t)(a - 1) * (n + 1) + b] : 0.0);
+        }
+    }
+    double operator()(int a, int b) const { return (b < 0 || b > a) ? 0.0 : c[(size_t)a * (n + 1) + b]; }
+};
+
+bool bad_params(int n, int s, double lam, double rho, double eps, double gamma, double pe) {
+    return n < 1 || n > 64 || s < 0 || s >= n || !(lam > 0.0) || !(rho >= 0.0) || !(eps >= 0.0) ||
+           !(gamma >= 0.0) || !(pe >= 0.0) || !(pe <= 1.0);
+}
+
+// Philox-4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): counter-based generator
+__host__ __device__ inline void philox4x32(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                           uint32_t k0, uint32_t k1, uint32_t (&out)[4]) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+template <int CTRL>
+__device__ __forceinline__ double dpp_max_step(double v) {
+    const long long bits = __builtin_bit_cast(long long, v);
+    int lo = (int)(bits & 0xFFFFFFFFLL), hi = (int)(bits >> 32);
+    lo = __builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xF, 0xF, false);
+    hi = __builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xF, 0xF, false);
+    const long long other = ((long long)hi << 32) | (unsigned int)lo;
+    return fmax(v, __builtin_bit_cast(double, other));
+}
+
+// maximum over the 64 lanes, result in every lane
+__device__ __forceinline__ double wave_max(double v) {
+    v = dpp_max_step<0xB1>(v);   // quad_perm [1,0,3,2]
+    v = dpp_max_step<0x4E>(v);   // quad_perm [2,3,0,1]
+    v = dpp_max_step<0x141>(v);  // row_half_mirror
+    v = dpp_max_step<0x140>(v);  // row_mirror
+    const long long bits = __builtin_bit_cast(long long, v);
+    const int lo = (int)(bits & 0xFFFFFFFFLL), hi = (int)(bits >> 32);
+    double m = -INFINITY;
+#pragma unroll
+    for (int row = 0; row < 4; ++row) {
+        const int l = __builtin_amdgcn_readlane(lo, row * 16);
+        const int h = __builtin_amdgcn_readlane(hi, row * 16);
+        m = fmax(m, __builtin_bit_cast(double, ((long long)h << 32) | (unsigned int)l));
+    }
+    return m;
+}
+
+// One wave per trial, lane = worker.  Word 0 of a worker's random stream decides
+// failure, word u its u-th task time rho - log(U)/lambda (counter = (trial, worker,
+// block, 0), key = seed; U = (word + 0.5) / 2^32).  For u = 1..top the u-th largest
+// completion time of u tasks over the workers (= time at which n-u+1 workers have
+// finished u tasks) is found by knocking out the current maximum u-1 times.
+__global__ __launch_bounds__(256) void latency_sim_kernel(double* __restrict__ L,
+                                                          double* __restrict__ Tmin, int n, int top,
+                                                          double lam, double rho, double eps,
+                                                          double gamma, double pe, uint32_t k0,
+                                                          uint32_t k1, int64_t trials) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave0 = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    const double base = gamma + eps;
+    for (int64_t r = wave0; r < trials; r += nwaves) {
+        uint32_t w[4];
+        philox4x32((uint32_t)r, (uint32_t)lane, 0u, 0u, k0, k1, w);
+        const bool failed = ((double)w[0] + 0.5) / 4294967296.0 < pe;
+        double cs = 0.0, best = INFINITY;
+        for (int u = 1; u <= top; ++u) {
+            if ((u & 3) == 0) philox4x32((uint32_t)r, (uint32_t)lane, (uint32_t)(u >> 2), 0u, k0, k1, w);
+            const double U = ((double)w[u & 3] + 0.5) / 4294967296.0;
+            cs += rho - log(U) / lam;
+            double v = failed ? INFINITY : base + cs;
+            if (lane >= n) v = -INFINITY;
+            for (int kth = 1; kth < u; ++kth) {
+                const double m = wave_max(v);
+                const unsigned long long holders = __ballot(v == m);
+                const int first = __ffsll((long long)holders) - 1;
+                if (lane == first) v = -INFINITY;
+            }
+            const double Lu = wave_max(v);
+            if (lane == 0) L[(int64_t)(u - 1) * trials + r] = Lu;
+            best = fmin(best, Lu);
+        }
+        if (Tmin && lane == 0) Tmin[r] = best;
+    }
+}
+
+}  // namespace
+
+extern "C" int ngc_latency_cdf_gc(int n, int sigma, double lam, double rho, double eps, double gamma,
+                                  double pe, const double* t, int nt, double* cdf_out) {
+    if (bad_params(n, sigma, lam, rho, eps, gamma, pe) || !t || !cdf_out || nt < 0) return NGC_ERR_INVALID;
+    binomials C(n);
+    for (int q = 0; q < nt; ++q) {
+        const double F = layer_cdf(sigma + 1, t[q], lam, rho, eps, gamma);
+        double total = 0.0;
+        for (int kappa = 0; kappa <= sigma; ++kappa) {
+            const int alive = n - kappa;
+            double cond = 0.0;
+            for (int m = n - sigma; m <= alive; ++m)
+                cond += C(alive, m) * std::pow(F, m) * std::pow(1.0 - F, alive - m);
+            total += cond * C(n, kappa) * std::pow(pe, kappa) * std::pow(1.0 - pe, n - kappa);
+        }
+        cdf_out[q] = total;
+    }
+    return NGC_OK;
+}
+
+extern "C" int ngc_latency_cdf_ngc(int n, int smax, double lam, double rho, double eps, double gamma,
+                                   double pe, const double* t, int nt, double* cdf_out) {
+    if (bad_params(n, smax, lam, rho, eps, gamma, pe) || !t || !cdf_out || nt < 0) return NGC_ERR_INVALID;
+    binomials C(n);
+    const int top = smax + 1;
+    std::vector<double> p(top + 2), g(n + 1), h(n + 1);
+    for (int q = 0; q < nt; ++q) {
+        std::vector<double> F(top + 2);
+        for (int u = 0; u <= top + 1; ++u) F[u] = layer_cdf(u, t[q], lam, rho, eps, gamma);
+        for (int u = 1; u < top; ++u) p[u] = F[u] - F[u + 1];   // finished exactly u tasks
+        p[top] = F[top];                                        // finished all of them
+        const double q0 = 1.0 - F[1];                           // finished none
+        double total = 0.0;
+        for (int kappa = 0; kappa <= smax; ++kappa) {
+            const int alive = n - kappa;
+            // g[S] = weight of all assignments of S workers to the layers above the current one
+            // in which none of those layers has its n-u+1 finishers
+            std::fill(g.begin(), g.end(), 0.0);
+            g[0] = 1.0;
+            for (int u = top; u >= 1; --u) {
+                std::fill(h.begin(), h.end(), 0.0);
+                const int cap = std::min(n - u, alive);  // at most n-u workers with >= u tasks
+                for (int S = 0; S <= cap; ++S) {
+                    if (g[S] == 0.0) continue;
+                    double pw = 1.0;
+                    for (int S2 = S; S2 <= cap; ++S2) {
+                        h[S2] += g[S] * C(alive - S, S2 - S) * pw;
+                        pw *= p[u];
+                    }
+                }
+                g.swap(h);
+            }
+            double stuck = 0.0;
+            for (int S = 0; S <= alive; ++S) stuck += g[S] * std::pow(q0, alive - S);
+            total += (1.0 - stuck) * C(n, kappa) * std::pow(pe, kappa) * std::pow(1.0 - pe, n - kappa);
+        }
+        cdf_out[q] = total;
+    }
+    return NGC_OK;
+}
+
+extern "C" int ngc_latency_simulate(void* hip_stream, int n, int smax, double lam, double rho, double eps,
+                                    double gamma, double pe, uint64_t seed, int64_t trials,
+                                    double* L_dev, double* Tngc_dev) {
+    if (bad_params(n, smax, lam, rho, eps, gamma, pe) || !L_dev || trials < 1 || trials > 0xFFFFFFFFLL)
+        return NGC_ERR_INVALID;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return NGC_ERR_HIP;
+    const int64_t want = (trials + 3) / 4;
+    const int64_t cap = (int64_t)(prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256) * 16;
+    const unsigned blocks = (unsigned)(want < cap ? want : cap);
+    hipLaunchKernelGGL(latency_sim_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, L_dev, Tngc_dev,
+                       n, smax + 1, lam, rho, eps, gamma, pe, (uint32_t)seed, (uint32_t)(seed >> 32), trials);
+    return hipGetLastError() == hipSuccess ? NGC_OK : NGC_ERR_HIP;
+}

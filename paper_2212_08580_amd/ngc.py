@@ -37,7 +37,7 @@ EXPORTS = (
     "ngc_set_mlp2_shape", "ngc_partition_grads", "ngc_encode", "ngc_select_decode_vec",
     "ngc_select_decode_vec_first", "ngc_decode", "ngc_update", "ngc_sync",
     "ngc_worker_task_count", "ngc_worker_schedule", "ngc_worker_grads", "ngc_worker_encode",
-    "ngc_select_from_progress",
+    "ngc_select_from_progress", "ngc_latency_cdf_gc", "ngc_latency_cdf_ngc", "ngc_latency_simulate",
     "ngc_profile_enable", "ngc_profile_read", "ngc_probe_copy", "ngc_probe_read",
     "ngc_strerror", "ngc_last_error",
 )
@@ -64,6 +64,9 @@ _lib.ngc_select_decode_vec.argtypes = [_vp, _vp, ctypes.POINTER(_i), _vp, ctypes
 _lib.ngc_select_decode_vec_first.argtypes = _lib.ngc_select_decode_vec.argtypes
 _lib.ngc_decode.argtypes = [_vp, _i, _vp, _vp, _vp]
 _lib.ngc_update.argtypes = [_vp, _vp, _vp, _dbl]
+_lib.ngc_latency_cdf_gc.argtypes = [_i, _i, _dbl, _dbl, _dbl, _dbl, _dbl, _vp, _i, _vp]
+_lib.ngc_latency_cdf_ngc.argtypes = _lib.ngc_latency_cdf_gc.argtypes
+_lib.ngc_latency_simulate.argtypes = [_vp, _i, _i, _dbl, _dbl, _dbl, _dbl, _dbl, _u64, _i64, _vp, _vp]
 _lib.ngc_worker_task_count.argtypes = [_vp, ctypes.POINTER(_i)]
 _lib.ngc_worker_schedule.argtypes = [_vp, _i, _vp, ctypes.POINTER(_i)]
 _lib.ngc_worker_grads.argtypes = [_vp, _i, _vp, _vp, _vp, _i64, _vp, _vp]
@@ -225,6 +228,28 @@ def ngc_select_from_progress(ctx, progress, n, min_layer=0):
                                        a.ctypes.data_as(ctypes.c_void_p), ctypes.byref(resid))
     _check(rc, ctx)
     return layer.value, mask, a, resid.value
+
+
+def _latency_cdf(fn, n, s, lam, rho, eps, gamma, pe, t):
+    t, pt = _host(np.atleast_1d(t), np.float64)
+    out = np.zeros(t.size, np.float64)
+    _check(fn(int(n), int(s), float(lam), float(rho), float(eps), float(gamma), float(pe), pt,
+              int(t.size), out.ctypes.data_as(ctypes.c_void_p)))
+    return out
+
+
+def ngc_latency_cdf_gc(n, sigma, lam, rho, eps, gamma, pe, t):
+    return _latency_cdf(_lib.ngc_latency_cdf_gc, n, sigma, lam, rho, eps, gamma, pe, t)
+
+
+def ngc_latency_cdf_ngc(n, smax, lam, rho, eps, gamma, pe, t):
+    return _latency_cdf(_lib.ngc_latency_cdf_ngc, n, smax, lam, rho, eps, gamma, pe, t)
+
+
+def ngc_latency_simulate(hip_stream, n, smax, lam, rho, eps, gamma, pe, seed, trials, L, Tngc=None):
+    _check(_lib.ngc_latency_simulate(ctypes.c_void_p(int(hip_stream)), int(n), int(smax), float(lam),
+                                     float(rho), float(eps), float(gamma), float(pe), int(seed),
+                                     int(trials), _dev(L), _dev(Tngc)))
 
 
 def ngc_update(ctx, theta, g, scale):

@@ -285,3 +285,28 @@ def test_select_from_progress_matches_oracle_rule(ngc):
             ngc.ngc_select_from_progress(ctx, [-1] * n, n, 0)
     finally:
         ngc.ngc_destroy(ctx)
+
+
+# ---- latency model: closed forms on the host against the oracle ---------------------------------
+def test_latency_closed_forms_match_oracle(ngc):
+    from oracle import latency as ol
+    t = np.linspace(0.0, 20.0, 41)
+    for (n, lam, rho, eps, gamma, pe) in [(8, 0.5, 0.5, 0.1, 0.0, 0.05), (6, 1.3, 0.0, 0.0, 0.2, 0.2),
+                                          (12, 0.8, 0.25, 0.05, 0.1, 0.0)]:
+        for s in (0, 1, 3, 5):
+            gc = ngc.ngc_latency_cdf_gc(n, s, lam, rho, eps, gamma, pe, t)
+            nested = ngc.ngc_latency_cdf_ngc(n, s, lam, rho, eps, gamma, pe, t)
+            for q, tq in enumerate(t):
+                assert abs(gc[q] - ol.gc_cdf(tq, n, s, lam, rho, eps, gamma, pe)) < 1e-12
+                if n <= 8:      # the oracle's nested sum is exponential in s
+                    assert abs(nested[q] - ol.ngc_cdf(tq, n, s, lam, rho, eps, gamma, pe)) < 1e-12
+            assert np.all(np.diff(nested) >= -1e-13) and np.all(nested >= gc - 1e-13)
+    # the one number the paper prints: n = 8, p_e = 0.05, sigma = 0 tends to ~0.66
+    assert abs(ngc.ngc_latency_cdf_gc(8, 0, 0.5, 0.5, 0.1, 0.0, 0.05, [1e4])[0] - 0.95 ** 8) < 1e-12
+    # a size the nested sum could not enumerate
+    big = ngc.ngc_latency_cdf_ngc(64, 31, 0.5, 0.5, 0.1, 0.0, 0.05, [5.0, 50.0, 1e4])
+    assert 0.0 <= big[0] <= big[1] <= big[2] <= 1.0 and big[2] > 0.999999
+    with pytest.raises(ngc.NgcError):
+        ngc.ngc_latency_cdf_gc(8, 8, 0.5, 0.5, 0.1, 0.0, 0.05, [1.0])
+    with pytest.raises(ngc.NgcError):
+        ngc.ngc_latency_cdf_ngc(8, 3, -1.0, 0.5, 0.1, 0.0, 0.05, [1.0])
