@@ -232,6 +232,32 @@ int ngc_latency_simulate(void* hip_stream, int n, int smax, double lambda, doubl
                          double gamma, double pe, uint64_t seed, int64_t trials, double* L_dev,
                          double* Tngc_dev);
 
+/*
+ * Explicit decoding matrix A_sigma of one layer (Def. 1, first, fourth and
+ * fifth bullet): one row per straggler set of size sigma = s[layer], in
+ * lexicographic order of the sorted sets; row j is supported on the n - sigma
+ * responders of its set and satisfies a_j B_sigma = 1.  Only for small codes:
+ * refused above 2^20 rows.
+ *
+ * ngc_build_decoding_table: build (or rebuild) the table on the host; rows_out
+ *   (may be NULL) receives C(n, sigma).  Installing a new B for the layer
+ *   discards the table.
+ * ngc_decoding_row_index: row that serves a straggler mask.  With fewer than
+ *   sigma stragglers the responders of highest index are left unused, i.e.
+ *   the n - sigma responders of lowest index decode.  More than sigma
+ *   stragglers: NGC_ERR_UNDECODABLE.
+ * ngc_get_decoding_row: copy one row (n doubles) to a_out.
+ * ngc_decode_lookup: ngc_decode with the decode vector read by the kernel from
+ *   the table's device copy (uploaded on first use); the host only ranks the
+ *   mask, no system is solved per iteration.
+ */
+int ngc_build_decoding_table(ngc_ctx* ctx, int layer, int64_t* rows_out);
+int ngc_decoding_row_index(const ngc_ctx* ctx, int layer, const uint8_t* straggler_mask,
+                           int64_t* row_out);
+int ngc_get_decoding_row(const ngc_ctx* ctx, int layer, int64_t row, double* a_out);
+int ngc_decode_lookup(ngc_ctx* ctx, int layer, const uint8_t* straggler_mask, const float* C_dev,
+                      float* g_dev);
+
 /* theta[:] -= scale * g[:]  with scale = eta/m  (Sec. II-B eq. (1)). */
 int ngc_update(ngc_ctx* ctx, float* theta_dev, const float* g_dev, double scale);
 

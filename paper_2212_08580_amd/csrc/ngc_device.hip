@@ -362,6 +362,65 @@ __global__ __launch_bounds__(256) void decode_kernel(const float* __restrict__ C
     }
 }
 
+// Decode with the decode vector taken from a row of the explicit decoding matrix
+// A_sigma held on the device: thread 0 compacts the non-zero entries of the row
+// into LDS, then the combination runs exactly as in decode_kernel (same order of
+// additions, so both routes give the same bits for the same vector).
+template <typename VT, int V>
+__global__ __launch_bounds__(256) void decode_lookup_kernel(const float* __restrict__ Cl,
+                                                            float* __restrict__ g, int64_t d, int n,
+                                                            const double* __restrict__ a_row) {
+    __shared__ double part[16][16 * V + 1];
+    __shared__ double a_s[NGC_MAX_N];
+    __shared__ int idx_s[NGC_MAX_N];
+    __shared__ int count_s;
+    if (threadIdx.x == 0) {
+        int cnt = 0;
+        for (int i = 0; i < n; ++i) {
+            const double a = a_row[i];
+            if (a != 0.0) {
+                a_s[cnt] = a;
+                idx_s[cnt] = i;
+                ++cnt;
+            }
+        }
+        count_s = cnt;
+    }
+    __syncthreads();
+    const int count = count_s;
+    const int lane16 = threadIdx.x & 15;
+    const int slot = threadIdx.x >> 4;
+    const int64_t c = ((int64_t)blockIdx.x * 16 + lane16) * V;
+    double acc[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[v] = 0.0;
+    if (c < d) {
+        for (int t = slot; t < count; t += 16) {
+            VT m = *reinterpret_cast<const VT*>(Cl + (int64_t)idx_s[t] * d + c);
+            const double a = a_s[t];
+            if constexpr (V == 1) {
+                acc[0] += a * (double)m;
+            } else {
+#pragma unroll
+                for (int v = 0; v < V; ++v) acc[v] += a * (double)m[v];
+            }
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < V; ++v) part[slot][lane16 * V + v] = acc[v];
+    __syncthreads();
+    const int q = threadIdx.x;
+    if (q < 16 * V) {
+        const int64_t cq = (int64_t)blockIdx.x * 16 * V + q;
+        if (cq < d) {
+            double s = part[0][q];
+#pragma unroll
+            for (int k = 1; k < 16; ++k) s += part[k][q];
+            g[cq] = (float)s;
+        }
+    }
+}
+
 // K6: theta -= scale * g
 __global__ __launch_bounds__(256) void update_kernel(float* __restrict__ theta,
                                                      const float* __restrict__ g, float scale,
@@ -468,6 +527,11 @@ void ngc_dev_release(ngc_ctx* ctx) {
     if (ctx->d_code) (void)hipFree(ctx->d_code);
     if (ctx->d_ws) (void)hipFree(ctx->d_ws);
     if (ctx->d_units) (void)hipFree(ctx->d_units);
+    for (auto& lc : ctx->code) {
+        if (lc.d_A) (void)hipFree(lc.d_A);
+        lc.d_A = nullptr;
+        lc.A_stale = true;
+    }
     ctx->d_units = nullptr;
     ctx->d_code = nullptr;
     ctx->d_ws = nullptr;
@@ -993,6 +1057,51 @@ extern "C" int ngc_worker_encode(ngc_ctx* ctx, const float* W_dev, const int* pr
             hipLaunchKernelGGL((worker_encode_kernel<v2f, 2, 8>), grid, dim3(64), 0, ctx->stream, W_dev, C_dev, needed, wc, n, L, T, d, prog);
         else
             hipLaunchKernelGGL((worker_encode_kernel<float, 1, 8>), grid, dim3(64), 0, ctx->stream, W_dev, C_dev, needed, wc, n, L, T, d, prog);
+    }
+    NGC_HIP(ctx, hipGetLastError());
+    return NGC_OK;
+}
+
+// ---- decode through the explicit decoding matrix ------------------------------------------------
+extern "C" int ngc_decode_lookup(ngc_ctx* ctx, int layer, const uint8_t* straggler_mask,
+                                 const float* C_dev, float* g_dev) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (!straggler_mask || !C_dev || !g_dev) return ngc_fail(ctx, NGC_ERR_INVALID, "null pointer");
+    if (layer < 0 || layer >= ctx->L) return ngc_fail(ctx, NGC_ERR_INVALID, "layer out of range");
+    ngc_layer_code& lc = ctx->code[layer];
+    if (lc.A_rows == 0) return ngc_fail(ctx, NGC_ERR_STATE, "call ngc_build_decoding_table for this layer first");
+    int64_t row = 0;
+    int rc = ngc_decoding_row_index(ctx, layer, straggler_mask, &row);
+    if (rc) return rc;
+    rc = dev_init(ctx);
+    if (rc) return rc;
+    const int n = ctx->n;
+    const int64_t d = ctx->d;
+    if (lc.A_stale || !lc.d_A) {
+        NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        if (lc.d_A) NGC_HIP(ctx, hipFree(lc.d_A));
+        lc.d_A = nullptr;
+        void* p = nullptr;
+        if (hipMalloc(&p, lc.A.size() * sizeof(double)) != hipSuccess) {
+            (void)hipGetLastError();
+            return ngc_fail(ctx, NGC_ERR_NOMEM, "decoding table allocation failed");
+        }
+        lc.d_A = (double*)p;
+        NGC_HIP(ctx, hipMemcpy(lc.d_A, lc.A.data(), lc.A.size() * sizeof(double), hipMemcpyHostToDevice));
+        lc.A_stale = false;
+    }
+    const float* Cl = C_dev + (size_t)layer * n * d;
+    const double* a_row = lc.d_A + (size_t)row * n;
+    const int V = vec_width(d, Cl, g_dev);
+    const int64_t gx = (d + 16 * V - 1) / (16 * V);
+    {
+        prof_scope ps(ctx, NGC_KERNEL_DECODE);
+        if (V == 4)
+            hipLaunchKernelGGL((decode_lookup_kernel<v4f, 4>), dim3((unsigned)gx), dim3(256), 0, ctx->stream, Cl, g_dev, d, n, a_row);
+        else if (V == 2)
+            hipLaunchKernelGGL((decode_lookup_kernel<v2f, 2>), dim3((unsigned)gx), dim3(256), 0, ctx->stream, Cl, g_dev, d, n, a_row);
+        else
+            hipLaunchKernelGGL((decode_lookup_kernel<float, 1>), dim3((unsigned)gx), dim3(256), 0, ctx->stream, Cl, g_dev, d, n, a_row);
     }
     NGC_HIP(ctx, hipGetLastError());
     return NGC_OK;

@@ -46,6 +46,9 @@ static void compress_layer(ngc_layer_code& lc, int n) {
 
 static void install_layer(ngc_ctx* ctx, int layer, const double* B) {
     ngc_layer_code& lc = ctx->code[layer];
+    lc.A.clear();  // a decoding table belongs to the matrix it was built from
+    lc.A_rows = 0;
+    lc.A_stale = true;
     lc.B.assign(B, B + (size_t)ctx->n * ctx->n);
     compress_layer(lc, ctx->n);
     lc.set = true;
@@ -416,4 +419,104 @@ extern "C" int ngc_select_from_progress(const ngc_ctx* ctx, const int* progress,
         return NGC_OK;
     }
     return ngc_fail(ctx, NGC_ERR_UNDECODABLE, "no component code has enough finished workers");
+}
+
+// ---------------------------------------------------------------------------
+// Explicit decoding matrix A_sigma (Def. 1): one row per straggler set of size
+// sigma, supported on the n - sigma responders, with A_sigma B_sigma = 1.
+// Rows are in lexicographic order of the (sorted) straggler sets.
+// ---------------------------------------------------------------------------
+static uint64_t binom_u64(int a, int b) {
+    if (b < 0 || b > a) return 0;
+    if (b > a - b) b = a - b;
+    uint64_t r = 1;
+    for (int i = 1; i <= b; ++i) {
+        // r * (a - b + i) / i stays integral; guard against overflow
+        const uint64_t f = (uint64_t)(a - b + i);
+        if (r > UINT64_MAX / f) return UINT64_MAX;
+        r = r * f / i;
+    }
+    return r;
+}
+
+// rank of the sorted subset c[0..sigma) of {0..n-1} among all subsets of that size
+static int64_t subset_rank(const int* c, int sigma, int n) {
+    uint64_t rank = 0;
+    int prev = -1;
+    for (int j = 0; j < sigma; ++j) {
+        for (int v = prev + 1; v < c[j]; ++v) rank += binom_u64(n - 1 - v, sigma - 1 - j);
+        prev = c[j];
+    }
+    return (int64_t)rank;
+}
+
+extern "C" int ngc_build_decoding_table(ngc_ctx* ctx, int layer, int64_t* rows_out) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (layer < 0 || layer >= ctx->L) return ngc_fail(ctx, NGC_ERR_INVALID, "layer out of range");
+    ngc_layer_code& lc = ctx->code[layer];
+    if (!lc.set) return ngc_fail(ctx, NGC_ERR_STATE, "layer has no code yet");
+    const int n = ctx->n, sigma = ctx->s[layer];
+    const uint64_t rows = binom_u64(n, sigma);
+    if (rows > (1ull << 20)) return ngc_fail(ctx, NGC_ERR_INVALID, "decoding table would exceed 2^20 rows");
+    lc.A.assign((size_t)rows * n, 0.0);
+    std::vector<int> out(sigma), resp(n);
+    for (int j = 0; j < sigma; ++j) out[j] = j;
+    for (uint64_t r = 0; r < rows; ++r) {
+        int ns = 0, q = 0;
+        for (int i = 0; i < n; ++i) {
+            if (q < sigma && out[q] == i) { ++q; continue; }
+            resp[ns++] = i;
+        }
+        double resid = 0.0;
+        ngc_min_norm_decode(lc.B.data(), n, resp.data(), ns, &lc.A[(size_t)r * n], &resid);
+        if (!(resid <= 1e-6)) {
+            lc.A.clear();
+            return ngc_fail(ctx, NGC_ERR_SINGULAR, "a straggler set of size sigma cannot be decoded");
+        }
+        // next subset in lexicographic order
+        int j = sigma - 1;
+        while (j >= 0 && out[j] == n - sigma + j) --j;
+        if (j >= 0) {
+            ++out[j];
+            for (int t = j + 1; t < sigma; ++t) out[t] = out[t - 1] + 1;
+        }
+    }
+    lc.A_rows = (int64_t)rows;
+    lc.A_stale = true;
+    if (rows_out) *rows_out = lc.A_rows;
+    return NGC_OK;
+}
+
+extern "C" int ngc_decoding_row_index(const ngc_ctx* ctx, int layer, const uint8_t* straggler_mask,
+                                      int64_t* row_out) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (layer < 0 || layer >= ctx->L || !straggler_mask || !row_out) return ngc_fail(ctx, NGC_ERR_INVALID, "bad layer or null argument");
+    const int n = ctx->n, sigma = ctx->s[layer];
+    int out[NGC_MAX_N];
+    int cnt = 0;
+    for (int i = 0; i < n; ++i)
+        if (straggler_mask[i]) {
+            if (cnt == sigma) return ngc_fail(ctx, NGC_ERR_UNDECODABLE, "more stragglers than this layer tolerates");
+            out[cnt++] = i;
+        }
+    // fewer stragglers than sigma: the responders of highest index are left unused
+    uint8_t used[NGC_MAX_N];
+    for (int i = 0; i < n; ++i) used[i] = straggler_mask[i] != 0;
+    for (int i = n - 1; i >= 0 && cnt < sigma; --i)
+        if (!used[i]) { used[i] = 1; ++cnt; }
+    cnt = 0;
+    for (int i = 0; i < n; ++i)
+        if (used[i]) out[cnt++] = i;
+    *row_out = subset_rank(out, sigma, n);
+    return NGC_OK;
+}
+
+extern "C" int ngc_get_decoding_row(const ngc_ctx* ctx, int layer, int64_t row, double* a_out) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (layer < 0 || layer >= ctx->L || !a_out) return ngc_fail(ctx, NGC_ERR_INVALID, "bad layer or null output");
+    const ngc_layer_code& lc = ctx->code[layer];
+    if (lc.A_rows == 0) return ngc_fail(ctx, NGC_ERR_STATE, "no decoding table for this layer");
+    if (row < 0 || row >= lc.A_rows) return ngc_fail(ctx, NGC_ERR_INVALID, "row out of range");
+    std::memcpy(a_out, &lc.A[(size_t)row * ctx->n], sizeof(double) * ctx->n);
+    return NGC_OK;
 }

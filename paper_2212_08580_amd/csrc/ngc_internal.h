@@ -17,6 +17,12 @@ constexpr int NGC_MAX_PROFILE = 4096;
 // entries rowptr[i] .. rowptr[i+1]-1 of (col, coef).
 struct ngc_layer_code {
     bool set = false;
+    // explicit decoding matrix A_sigma (Def. 1), one row per straggler set of size sigma in
+    // lexicographic order; empty until ngc_build_decoding_table
+    std::vector<double> A;
+    int64_t A_rows = 0;
+    double* d_A = nullptr;  // device copy, uploaded on first use
+    bool A_stale = true;    // host table changed since the upload
     std::vector<double> B;      // n x n dense, fp64, as given
     std::vector<int> rowptr;    // n + 1
     std::vector<int> col;

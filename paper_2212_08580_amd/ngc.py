@@ -37,7 +37,8 @@ EXPORTS = (
     "ngc_set_mlp2_shape", "ngc_partition_grads", "ngc_encode", "ngc_select_decode_vec",
     "ngc_select_decode_vec_first", "ngc_decode", "ngc_update", "ngc_sync",
     "ngc_worker_task_count", "ngc_worker_schedule", "ngc_worker_grads", "ngc_worker_encode",
-    "ngc_select_from_progress", "ngc_latency_cdf_gc", "ngc_latency_cdf_ngc", "ngc_latency_simulate",
+    "ngc_select_from_progress", "ngc_build_decoding_table", "ngc_decoding_row_index",
+    "ngc_get_decoding_row", "ngc_decode_lookup", "ngc_latency_cdf_gc", "ngc_latency_cdf_ngc", "ngc_latency_simulate",
     "ngc_profile_enable", "ngc_profile_read", "ngc_probe_copy", "ngc_probe_read",
     "ngc_strerror", "ngc_last_error",
 )
@@ -64,6 +65,10 @@ _lib.ngc_select_decode_vec.argtypes = [_vp, _vp, ctypes.POINTER(_i), _vp, ctypes
 _lib.ngc_select_decode_vec_first.argtypes = _lib.ngc_select_decode_vec.argtypes
 _lib.ngc_decode.argtypes = [_vp, _i, _vp, _vp, _vp]
 _lib.ngc_update.argtypes = [_vp, _vp, _vp, _dbl]
+_lib.ngc_build_decoding_table.argtypes = [_vp, _i, ctypes.POINTER(_i64)]
+_lib.ngc_decoding_row_index.argtypes = [_vp, _i, _vp, ctypes.POINTER(_i64)]
+_lib.ngc_get_decoding_row.argtypes = [_vp, _i, _i64, _vp]
+_lib.ngc_decode_lookup.argtypes = [_vp, _i, _vp, _vp, _vp]
 _lib.ngc_latency_cdf_gc.argtypes = [_i, _i, _dbl, _dbl, _dbl, _dbl, _dbl, _vp, _i, _vp]
 _lib.ngc_latency_cdf_ngc.argtypes = _lib.ngc_latency_cdf_gc.argtypes
 _lib.ngc_latency_simulate.argtypes = [_vp, _i, _i, _dbl, _dbl, _dbl, _dbl, _dbl, _u64, _i64, _vp, _vp]
@@ -250,6 +255,30 @@ def ngc_latency_simulate(hip_stream, n, smax, lam, rho, eps, gamma, pe, seed, tr
     _check(_lib.ngc_latency_simulate(ctypes.c_void_p(int(hip_stream)), int(n), int(smax), float(lam),
                                      float(rho), float(eps), float(gamma), float(pe), int(seed),
                                      int(trials), _dev(L), _dev(Tngc)))
+
+
+def ngc_build_decoding_table(ctx, layer):
+    rows = ctypes.c_int64(0)
+    _check(_lib.ngc_build_decoding_table(ctx, int(layer), ctypes.byref(rows)), ctx)
+    return rows.value
+
+
+def ngc_decoding_row_index(ctx, layer, mask):
+    mask, pm = _host(mask, np.uint8)
+    row = ctypes.c_int64(-1)
+    _check(_lib.ngc_decoding_row_index(ctx, int(layer), pm, ctypes.byref(row)), ctx)
+    return row.value
+
+
+def ngc_get_decoding_row(ctx, layer, row, n):
+    a = np.zeros(n, np.float64)
+    _check(_lib.ngc_get_decoding_row(ctx, int(layer), int(row), a.ctypes.data_as(ctypes.c_void_p)), ctx)
+    return a
+
+
+def ngc_decode_lookup(ctx, layer, mask, C, g):
+    mask, pm = _host(mask, np.uint8)
+    _check(_lib.ngc_decode_lookup(ctx, int(layer), pm, _dev(C), _dev(g)), ctx)
 
 
 def ngc_update(ctx, theta, g, scale):

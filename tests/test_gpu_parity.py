@@ -367,3 +367,44 @@ def test_c3_full_size_sampled(ngc, torch_dev):
                 assert rel(g, G64.sum(axis=0)) <= TOL
     finally:
         p.close()
+
+
+# --------------------------------------------------------------------------------------------
+# decode through the explicit decoding matrix A_sigma held on the device (small codes)
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,layers,kind,d", [(8, (0, 1, 3), "cyclic", 4096), (12, (0, 2, 5), "cyclic", 1002),
+                                             (8, (0, 1, 3, 7), "fracrep", 77)])
+def test_decode_lookup_matches_oracle_and_solve_route(ngc, torch_dev, n, layers, kind, d):
+    w = wl.C5.scaled(n=n, d=d, layers=layers)
+    G_h = wl.partial_gradients(w, seed=3)
+    p = Pipeline(ngc, torch_dev, w, kind=kind)
+    try:
+        for u in range(len(layers)):
+            ngc.ngc_build_decoding_table(p.ctx, u)
+        p.G.copy_(torch_dev.from_numpy(G_h))
+        C = p.encode()
+        full = G_h.astype(np.float64).sum(axis=0)
+        rng = np.random.default_rng(1)
+        g2 = torch_dev.empty_like(p.g)
+        for t in range(20):
+            u = int(rng.integers(0, len(layers)))
+            s = int(rng.integers(0, layers[u] + 1))
+            m = np.zeros(n, np.uint8)
+            m[rng.choice(n, size=s, replace=False)] = 1
+            ngc.ngc_decode_lookup(p.ctx, u, m, p.C, p.g)
+            a_o, _ = coding.decode_vector_first(p.Bs[u], layers[u], m)
+            row = ngc.ngc_decoding_row_index(p.ctx, u, m)
+            a = ngc.ngc_get_decoding_row(p.ctx, u, row, n)
+            assert np.array_equal(a != 0, a_o != 0)
+            ngc.ngc_decode(p.ctx, u, a, p.C, g2)                  # same vector through the kernel arguments
+            ngc.ngc_sync(p.ctx)
+            assert np.array_equal(p.g.cpu().numpy(), g2.cpu().numpy())
+            g = p.g.cpu().numpy()
+            assert rel(g, coding.decode(a_o, C[u])) <= 1e-6
+            kappa = coding.conditioning(a_o, coding.encode(p.Bs[u], G_h), full)
+            assert rel(g, full) <= max(TOL, 4 * 2.0 ** -24 * kappa)
+        m = np.ones(n, np.uint8)
+        with pytest.raises(ngc.NgcError):
+            ngc.ngc_decode_lookup(p.ctx, 1, m, p.C, p.g)
+    finally:
+        p.close()

@@ -310,3 +310,60 @@ def test_latency_closed_forms_match_oracle(ngc):
         ngc.ngc_latency_cdf_gc(8, 8, 0.5, 0.5, 0.1, 0.0, 0.05, [1.0])
     with pytest.raises(ngc.NgcError):
         ngc.ngc_latency_cdf_ngc(8, 3, -1.0, 0.5, 0.1, 0.0, 0.05, [1.0])
+
+
+# ---- explicit decoding matrix A_sigma (Def. 1) --------------------------------------------------
+@pytest.mark.parametrize("n,layers,kind", [(8, [0, 1, 3], "cyclic"), (7, [0, 2, 5], "cyclic"),
+                                           (8, [0, 1, 3, 7], "fracrep")])
+def test_decoding_table_satisfies_def1_and_matches_oracle(ngc, n, layers, kind):
+    Bs = codes.nested_code(n, layers, kind, seed=0, draws=2)
+    ctx = ngc.ngc_create(n, n, layers, 4)
+    try:
+        for u, B in enumerate(Bs):
+            ngc.ngc_set_code(ctx, u, B)
+        for u, sigma in enumerate(layers):
+            with pytest.raises(ngc.NgcError) as e:
+                ngc.ngc_get_decoding_row(ctx, u, 0, n)
+            assert e.value.code == ngc.NGC_ERR_STATE
+            rows = ngc.ngc_build_decoding_table(ctx, u)
+            assert rows == len(list(itertools.combinations(range(n), sigma)))
+            A_o = codes.decoding_matrix(Bs[u], sigma)                 # same (lexicographic) row order
+            for r, out in enumerate(itertools.combinations(range(n), sigma)):
+                m = np.zeros(n, np.uint8)
+                m[list(out)] = 1
+                assert ngc.ngc_decoding_row_index(ctx, u, m) == r
+                a = ngc.ngc_get_decoding_row(ctx, u, r, n)
+                assert np.all(a[list(out)] == 0.0)                    # supported on the responders
+                assert np.allclose(a @ Bs[u], 1.0, atol=1e-9)         # A B = 1
+                assert np.abs(a - A_o[r]).max() <= 1e-8 * max(1.0, np.abs(A_o[r]).max())
+            # fewer stragglers than sigma: the lowest n - sigma responders decode
+            if sigma >= 2:
+                m = np.zeros(n, np.uint8)
+                m[1] = 1
+                r = ngc.ngc_decoding_row_index(ctx, u, m)
+                a = ngc.ngc_get_decoding_row(ctx, u, r, n)
+                a_first, _ = coding.decode_vector_first(Bs[u], sigma, m)
+                assert a[1] == 0.0 and np.allclose(a, a_first, atol=1e-8)
+            if sigma + 1 < n:
+                m = np.zeros(n, np.uint8)
+                m[: sigma + 1] = 1
+                with pytest.raises(ngc.NgcError) as e:
+                    ngc.ngc_decoding_row_index(ctx, u, m)
+                assert e.value.code == ngc.NGC_ERR_UNDECODABLE
+        # a new matrix for the layer discards its table
+        ngc.ngc_set_code(ctx, 1, Bs[1])
+        with pytest.raises(ngc.NgcError):
+            ngc.ngc_get_decoding_row(ctx, 1, 0, n)
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
+def test_decoding_table_size_limit(ngc):
+    ctx = ngc.ngc_create(32, 32, [0, 15], 4)
+    try:
+        ngc.ngc_build_code(ctx, ngc.NGC_CODE_CYCLIC, 0)
+        with pytest.raises(ngc.NgcError) as e:
+            ngc.ngc_build_decoding_table(ctx, 1)                      # C(32,15) rows
+        assert e.value.code == ngc.NGC_ERR_INVALID
+    finally:
+        ngc.ngc_destroy(ctx)
