@@ -137,6 +137,14 @@ def nested_code(n, layers, kind="cyclic", seed=0, draws=16):
     return out
 
 
+def expand_partitions(Bs, c):
+    """Codes for k = c*n partitions (Sec. II-C: an atomic task is k/n partial
+    gradients, assigned jointly): worker i treats the c partitions of group j
+    like the single partition j of the k = n code, B = B' (x) 1_{1 x c}.  Row
+    weight becomes (k/n)(sigma+1) and a B = 1_k whenever a B' = 1_n."""
+    return [np.kron(np.asarray(B, np.float64), np.ones((1, int(c)))) for B in Bs]
+
+
 def decoding_matrix(B, sigma):
     """A_sigma with one row per straggler set of size sigma (Def. 1): row j is
     supported on the j-th (n-sigma)-subset and satisfies a_j B = 1.

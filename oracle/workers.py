@@ -27,28 +27,31 @@ def task_order(Bs, i):
     only adds partitions to those of the layer below.  Within a layer new
     partitions are taken in cyclic order starting at the worker's own index.
     """
-    n = Bs[0].shape[0]
+    n, k = Bs[0].shape
+    c = k // n
     order = []
     for B in Bs:
-        for t in range(n):
-            j = (i + t) % n
+        for t in range(k):
+            j = (i * c + t) % k
             if B[i, j] != 0.0 and j not in order:
                 order.append(j)
     return order
 
 
 def tasks_needed(Bs, i, u):
-    """Number of finished tasks after which worker i can form its layer-u message."""
-    return int(np.count_nonzero(Bs[u][i]))
+    """Number of finished atomic tasks (k/n partial gradients each, Sec. II-C) after
+    which worker i can form its layer-u message."""
+    n, k = Bs[0].shape
+    return int(np.count_nonzero(Bs[u][i])) // (k // n)
 
 
 def worker_partials(loss, X, Y, theta, Bs, progress, hidden=0, classes=0):
     """W[i] = list of the partial gradients worker i has finished, in task order.
     Every worker computes its own copy (no sharing between workers)."""
-    n = Bs[0].shape[0]
+    n, k = Bs[0].shape
     out = []
     for i in range(n):
-        order = task_order(Bs, i)[: int(progress[i])]
+        order = task_order(Bs, i)[: int(progress[i]) * (k // n)]
         out.append([gradients.partial_gradients(loss, X[j:j + 1], Y[j:j + 1], theta,
                                                 hidden, classes)[0] for j in order])
     return out
@@ -57,7 +60,7 @@ def worker_partials(loss, X, Y, theta, Bs, progress, hidden=0, classes=0):
 def worker_messages(Bs, W, progress):
     """C[u][i] = sum_t B_u[i][task_t] * W[i][t] for every layer the worker has
     finished; None where it has not."""
-    n = Bs[0].shape[0]
+    n, k = Bs[0].shape
     C = []
     for u, B in enumerate(Bs):
         row = []
@@ -67,7 +70,7 @@ def worker_messages(Bs, W, progress):
                 continue
             order = task_order(Bs, i)
             acc = 0.0
-            for t, j in enumerate(order[: int(progress[i])]):
+            for t, j in enumerate(order[: int(progress[i]) * (k // n)]):
                 if B[i, j] != 0.0:
                     acc = acc + B[i, j] * np.asarray(W[i][t], np.float64)
             row.append(acc)

@@ -235,3 +235,43 @@ def test_fp32_messages_stay_within_the_forward_error_bound():
         kap = coding.conditioning(a, coding.encode(Bs[u], G), full)
         err = np.linalg.norm(g32 - full) / np.linalg.norm(full)
         assert err <= 2.0 ** -24 * kap * 4
+
+
+@pytest.mark.parametrize("n,c,layers,kind", [(4, 2, [0, 1], "fracrep"), (6, 3, [0, 1, 3], "cyclic"),
+                                              (5, 2, [0, 2], "cyclic")])
+def test_codes_for_k_equal_c_times_n_partitions(n, c, layers, kind):
+    """Sec. II-C: with k = c n partitions an atomic task is k/n partial gradients;
+    Def. 1 then asks for row weight >= (k/n)(sigma+1) and for the all-ones row of
+    length k in the span of any n - sigma rows."""
+    k = c * n
+    Bs = codes.expand_partitions(codes.nested_code(n, layers, kind, seed=1, draws=2), c)
+    G = np.random.default_rng(0).standard_normal((k, 7))
+    full = G.sum(axis=0)
+    for B, sigma in zip(Bs, layers):
+        assert B.shape == (n, k)
+        assert np.all((B != 0).sum(axis=1) == c * (sigma + 1))
+        for out in itertools.combinations(range(n), sigma):
+            S = [i for i in range(n) if i not in out]
+            assert np.linalg.matrix_rank(np.vstack([B[S], np.ones(k)]), tol=1e-9) == \
+                np.linalg.matrix_rank(B[S], tol=1e-9)
+            m = np.zeros(n, np.uint8)
+            m[list(out)] = 1
+            a, resid = coding.decode_vector(B, m)
+            assert resid < 1e-9 and np.all(a[m == 1] == 0)
+            assert np.allclose(coding.decode(a, coding.encode(B, G)), full, rtol=1e-9, atol=1e-9)
+    for i in range(n):
+        for u in range(len(layers) - 1):
+            assert set(np.flatnonzero(Bs[u][i])) <= set(np.flatnonzero(Bs[u + 1][i]))
+
+
+def test_zero_padded_rows_do_not_change_the_gradient():
+    """Sec. II-C footnote: if k does not divide m the data can be zero-padded."""
+    rng = np.random.default_rng(2)
+    X = rng.standard_normal((10, 4))
+    y = rng.standard_normal(10)
+    th = rng.standard_normal(4)
+    Xp = np.vstack([X, np.zeros((2, 4))])
+    yp = np.concatenate([y, np.zeros(2)])
+    assert np.allclose(og.lsq_gradient(Xp, yp, th), og.lsq_gradient(X, y, th), rtol=1e-14)
+    ypm = np.concatenate([np.sign(y), np.ones(2)])
+    assert np.allclose(og.logistic_gradient(Xp, ypm, th), og.logistic_gradient(X, np.sign(y), th), rtol=1e-14)

@@ -114,3 +114,19 @@ def test_load_of_nested_code_versus_fixed_sigma_code():
         assert work_ngc == (n - s) * (s + 1)
         assert work_gc == (n - s) * (smax + 1)
         assert work_gc / work_ngc == (smax + 1) / (s + 1)
+
+
+def test_schedule_with_several_partitions_per_task():
+    """k = 2n: a task is the two partitions of a group; worker i starts with group i."""
+    Bs = codes.expand_partitions(codes.nested_code(4, [0, 1], seed=0, draws=2), 2)
+    assert ow.task_order(Bs, 1) == [2, 3, 4, 5]
+    assert ow.task_order(Bs, 3) == [6, 7, 0, 1]
+    assert [ow.tasks_needed(Bs, 0, u) for u in range(2)] == [1, 2]
+    X, Y, th = _data(8)
+    G = og.partial_gradients(0, X, Y, th)
+    progress = [2, 2, 0, 2]
+    W = ow.worker_partials(0, X, Y, th, Bs, progress)
+    assert [len(w) for w in W] == [4, 4, 0, 4]
+    u, mask, a, g = ow.decode_from_workers(Bs, [0, 1], W, progress)
+    assert u == 1 and list(mask) == [0, 0, 1, 0]
+    assert np.allclose(g, G.sum(axis=0), rtol=1e-10, atol=1e-10)
