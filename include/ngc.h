@@ -39,7 +39,7 @@ typedef struct ngc_ctx ngc_ctx;
 
 enum {
     NGC_OK = 0,
-    NGC_ERR_INVALID = -1,     /* bad shape, null pointer, layer out of range, k != n        */
+    NGC_ERR_INVALID = -1,     /* bad shape, null pointer, layer out of range, n does not divide k */
     NGC_ERR_UNDECODABLE = -2, /* more stragglers than the largest tolerance s_{L-1}          */
     NGC_ERR_SINGULAR = -3,    /* no a with |a^T B_S - 1| below tolerance (B violates Def. 1) */
     NGC_ERR_HIP = -4,         /* a HIP runtime call failed                                   */
@@ -67,9 +67,12 @@ enum {
  * (Sec. III, Def. 2).  s[0..L-1] are the straggler tolerances of the layers,
  * strictly ascending with s[0] == 0 and s[L-1] < n; they may be a subset of
  * 0..s_max (a subset of component codes of a nested code is nested).  d is the
- * gradient length (the paper's l).  k must equal n (Sec. II-C takes k = n),
- * 1 <= n <= 64.  hip_stream is a hipStream_t (NULL = the default stream); it
- * must outlive the context.  Layer 0 is preset to B_0 = I (Alg. 1); the other
+ * gradient length (the paper's l).  k = c*n for an integer c >= 1 (Sec. II-C
+ * works with k = n and notes that k/n partial gradients can be assigned
+ * jointly as one atomic task: worker i then treats the c partitions
+ * j*c .. j*c+c-1 of group j like the single partition j), 1 <= n <= k <= 64.
+ * hip_stream is a hipStream_t (NULL = the default stream); it must outlive the
+ * context.  Layer 0 is preset to B_0 = I (x) 1_{1 x c} (Alg. 1); the other
  * layers must be given by ngc_set_code() or ngc_build_code() before use.
  * No HIP call is made here.
  */
@@ -81,7 +84,7 @@ void ngc_destroy(ngc_ctx* ctx);
 /*
  * Install the encoding matrix B_sigma of one layer (Def. 1): B_host is n x k
  * fp64 row-major with zeros outside each row's support.  Rejected with
- * NGC_ERR_INVALID if a row is empty, if worker i does not hold partition i
+ * NGC_ERR_INVALID if worker i does not hold its own partition(s) i*c..i*c+c-1
  * (needed for nesting with B_0 = I), or if a row's support does not contain
  * the support of the same row in the layer below (Def. 2, second bullet;
  * checked against layers already set).  The values are copied.
@@ -99,7 +102,9 @@ int ngc_get_code(const ngc_ctx* ctx, int layer, double* B_host_out);
  * so any n-sigma rows span a space containing the all-ones vector (Def. 1);
  * out of several random draws the one that magnifies message rounding least is
  * kept.  NGC_CODE_FRACREP: all-ones rows on blocks of sigma+1 consecutive
- * partitions; needs (s[u]+1) | n and (s[u]+1) | (s[u+1]+1).  Random numbers
+ * partitions; needs (s[u]+1) | n and (s[u]+1) | (s[u+1]+1).  For k = c*n the
+ * n x n matrix is widened to n x k by repeating each column c times (row
+ * weight (k/n)(sigma+1), Def. 1 third bullet).  Random numbers
  * come from a counter-based generator keyed by seed; the same seed gives the
  * same code on every machine.
  */
@@ -173,12 +178,13 @@ int ngc_decode(ngc_ctx* ctx, int layer, const double* a_host, const float* C_dev
  * of a layer in cyclic order from index i -- and computes every partial gradient
  * itself, so a partition held by s+1 workers is read s+1 times.
  *
- * ngc_worker_task_count: length T of the longest schedule (s_max + 1 for the
- *   codes built here).  ngc_worker_schedule: the partitions of one worker in
- *   task order (parts_out has room for T entries).
+ * ngc_worker_task_count: length T of the longest schedule in atomic tasks of
+ *   c = k/n partitions (s_max + 1 for the codes built here).
+ *   ngc_worker_schedule: the partitions of one worker in the order it works
+ *   through them, c per task (parts_out has room for T*c entries).
  * ngc_worker_grads: progress_host[i] = number of tasks worker i has finished
- *   (0..T).  W_dev: float [n][T][d]; row (i, t) receives the partial gradient
- *   of the t-th partition of worker i's schedule for t < progress[i]; other
+ *   (0..T).  W_dev: float [n][T*c][d]; row (i, t) receives the partial gradient
+ *   of the t-th partition of worker i's schedule for t < c*progress[i]; other
  *   rows are left untouched.  Least squares and logistic losses.
  * ngc_worker_encode: C[u][i][:] = sum_t B^(u)[i][part(i,t)] W[i][t][:] (Sec.
  *   II-C, X = B G, from the worker's own copies) for every layer u whose

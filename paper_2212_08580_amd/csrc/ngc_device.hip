@@ -270,8 +270,9 @@ __global__ __launch_bounds__(256) void encode_kernel(const float* __restrict__ G
                                                      const float* __restrict__ coef, int n,
                                                      int64_t d, int pair_begin, int pair_end,
                                                      int pairs_per_group) {
+    // n here: rows of G (the k partitions)
     extern __shared__ float tile_raw[];
-    VT* tile = reinterpret_cast<VT*>(tile_raw);  // [n][64]
+    VT* tile = reinterpret_cast<VT*>(tile_raw);  // [k][64]
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t c = ((int64_t)blockIdx.x * 64 + lane) * V;
@@ -446,12 +447,13 @@ __global__ __launch_bounds__(64) void worker_encode_kernel(const float* __restri
                                                            float* __restrict__ C,
                                                            const int* __restrict__ needed,
                                                            const float* __restrict__ wcoef, int n,
-                                                           int L, int T, int64_t d,
+                                                           int L, int T, int per_task, int64_t d,
                                                            worker_progress prog) {
+    // T: rows of W per worker (partitions); prog.done counts atomic tasks of per_task partitions
     const int i = blockIdx.y;
     const int64_t c = ((int64_t)blockIdx.x * 64 + threadIdx.x) * V;
     if (c >= d) return;
-    const int done = prog.done[i] < T ? prog.done[i] : T;
+    const int done = prog.done[i] * per_task < T ? prog.done[i] * per_task : T;
     VT acc[LMAX];
 #pragma unroll
     for (int u = 0; u < LMAX; ++u) acc[u] = (VT)(0.0f);
@@ -762,7 +764,7 @@ extern "C" int ngc_partition_grads(ngc_ctx* ctx, int loss, const float* X_dev, c
         return ngc_mlp2_grads(ctx, X_dev, (const int*)y_dev, theta_dev, rows, G_dev);
     }
     if (loss != NGC_LOSS_LSQ && loss != NGC_LOSS_LOGISTIC) return ngc_fail(ctx, NGC_ERR_INVALID, "unknown loss");
-    return grads_impl(ctx, loss, X_dev, y_dev, theta_dev, rows, G_dev, ctx->n, nullptr, nullptr);
+    return grads_impl(ctx, loss, X_dev, y_dev, theta_dev, rows, G_dev, ctx->k, nullptr, nullptr);
 }
 
 // ---- code tables on the device --------------------------------------------
@@ -847,18 +849,18 @@ extern "C" int ngc_encode(ngc_ctx* ctx, const float* G_dev, int layer, float* C_
     gy = (pairs + ppg - 1) / ppg;
     if (gx > 0x7fffffffLL) return ngc_fail(ctx, NGC_ERR_INVALID, "d too large");
     dim3 grid((unsigned)gx, (unsigned)gy);
-    const size_t lds = (size_t)n * 64 * V * sizeof(float);
+    const size_t lds = (size_t)ctx->k * 64 * V * sizeof(float);  // all k rows of G, 64*V columns
     {
         prof_scope ps(ctx, NGC_KERNEL_ENCODE);
         if (V == 4)
             hipLaunchKernelGGL((encode_kernel<v4f, 4>), grid, dim3(256), lds, ctx->stream, G_dev, C_dev,
-                               rowptr, col, coef, n, d, pb, pe, ppg);
+                               rowptr, col, coef, ctx->k, d, pb, pe, ppg);
         else if (V == 2)
             hipLaunchKernelGGL((encode_kernel<v2f, 2>), grid, dim3(256), lds, ctx->stream, G_dev, C_dev,
-                               rowptr, col, coef, n, d, pb, pe, ppg);
+                               rowptr, col, coef, ctx->k, d, pb, pe, ppg);
         else
             hipLaunchKernelGGL((encode_kernel<float, 1>), grid, dim3(256), lds, ctx->stream, G_dev, C_dev,
-                               rowptr, col, coef, n, d, pb, pe, ppg);
+                               rowptr, col, coef, ctx->k, d, pb, pe, ppg);
     }
     NGC_HIP(ctx, hipGetLastError());
     return NGC_OK;
@@ -988,15 +990,16 @@ extern "C" int ngc_worker_grads(ngc_ctx* ctx, int loss, const float* X_dev, cons
     ngc_worker_plan plan;
     rc = ngc_make_worker_plan(ctx, plan);
     if (rc) return rc;
-    const int n = ctx->n, T = plan.T;
+    const int n = ctx->n, Tp = plan.T * ctx->c;  // partitions per worker schedule
     std::vector<int> maps;  // unit_part | unit_row
     std::vector<int> part, row;
     for (int i = 0; i < n; ++i) {
         if (progress_host[i] < 0) return ngc_fail(ctx, NGC_ERR_INVALID, "negative progress");
-        const int done = std::min<int>(progress_host[i], (int)plan.order[i].size());
+        const int64_t want = (int64_t)progress_host[i] * ctx->c;  // c partitions per finished task
+        const int done = (int)std::min<int64_t>(want, (int64_t)plan.order[i].size());
         for (int t = 0; t < done; ++t) {
             part.push_back(plan.order[i][t]);
-            row.push_back(i * T + t);
+            row.push_back(i * Tp + t);
         }
     }
     const int units = (int)part.size();
@@ -1022,16 +1025,16 @@ extern "C" int ngc_worker_encode(ngc_ctx* ctx, const float* W_dev, const int* pr
     ngc_worker_plan plan;
     rc = ngc_make_worker_plan(ctx, plan);
     if (rc) return rc;
-    const int n = ctx->n, L = ctx->L, T = plan.T;
+    const int n = ctx->n, L = ctx->L, T = plan.T * ctx->c;  // T: partitions per worker schedule
     const int64_t d = ctx->d;
-    // tables: int needed[L*n] | float wcoef[L*n*T]
+    // tables: int needed[L*n] (atomic tasks) | float wcoef[L*n*T]
     std::vector<int> tab((size_t)L * n + (size_t)L * n * T, 0);
     float* wcoef = reinterpret_cast<float*>(tab.data() + (size_t)L * n);
     for (int u = 0; u < L; ++u)
         for (int i = 0; i < n; ++i) {
             tab[(size_t)u * n + i] = plan.needed[(size_t)u * n + i];
             for (size_t t = 0; t < plan.order[i].size(); ++t)
-                wcoef[((size_t)u * n + i) * T + t] = (float)ctx->code[u].B[(size_t)i * n + plan.order[i][t]];
+                wcoef[((size_t)u * n + i) * T + t] = (float)ctx->code[u].B[(size_t)i * ctx->k + plan.order[i][t]];
         }
     worker_progress prog;
     for (int i = 0; i < NGC_MAX_N; ++i) prog.done[i] = 0;
@@ -1040,7 +1043,7 @@ extern "C" int ngc_worker_encode(ngc_ctx* ctx, const float* W_dev, const int* pr
         prog.done[i] = (unsigned char)std::min<int>(progress_host[i], 255);
     }
     // the gradient maps share the buffer: tables go behind them
-    const size_t off = ((size_t)2 * n * T + 63) / 64 * 64;
+    const size_t off = ((size_t)2 * n * T + 63) / 64 * 64;  // behind the largest possible gradient maps
     rc = ensure_units(ctx, (off + tab.size()) * sizeof(int));
     if (rc) return rc;
     NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
@@ -1052,11 +1055,11 @@ extern "C" int ngc_worker_encode(ngc_ctx* ctx, const float* W_dev, const int* pr
     {
         prof_scope ps(ctx, NGC_KERNEL_ENCODE);
         if (V == 4)
-            hipLaunchKernelGGL((worker_encode_kernel<v4f, 4, 8>), grid, dim3(64), 0, ctx->stream, W_dev, C_dev, needed, wc, n, L, T, d, prog);
+            hipLaunchKernelGGL((worker_encode_kernel<v4f, 4, 8>), grid, dim3(64), 0, ctx->stream, W_dev, C_dev, needed, wc, n, L, T, ctx->c, d, prog);
         else if (V == 2)
-            hipLaunchKernelGGL((worker_encode_kernel<v2f, 2, 8>), grid, dim3(64), 0, ctx->stream, W_dev, C_dev, needed, wc, n, L, T, d, prog);
+            hipLaunchKernelGGL((worker_encode_kernel<v2f, 2, 8>), grid, dim3(64), 0, ctx->stream, W_dev, C_dev, needed, wc, n, L, T, ctx->c, d, prog);
         else
-            hipLaunchKernelGGL((worker_encode_kernel<float, 1, 8>), grid, dim3(64), 0, ctx->stream, W_dev, C_dev, needed, wc, n, L, T, d, prog);
+            hipLaunchKernelGGL((worker_encode_kernel<float, 1, 8>), grid, dim3(64), 0, ctx->stream, W_dev, C_dev, needed, wc, n, L, T, ctx->c, d, prog);
     }
     NGC_HIP(ctx, hipGetLastError());
     return NGC_OK;

@@ -28,13 +28,13 @@ extern "C" const char* ngc_strerror(int code) {
 
 extern "C" const char* ngc_last_error(const ngc_ctx* ctx) { return ctx ? ctx->err.c_str() : ""; }
 
-static void compress_layer(ngc_layer_code& lc, int n) {
+static void compress_layer(ngc_layer_code& lc, int n, int k) {
     lc.rowptr.assign(n + 1, 0);
     lc.col.clear();
     lc.coef.clear();
     for (int i = 0; i < n; ++i) {
-        for (int j = 0; j < n; ++j) {
-            double v = lc.B[(size_t)i * n + j];
+        for (int j = 0; j < k; ++j) {
+            double v = lc.B[(size_t)i * k + j];
             if (v != 0.0) {
                 lc.col.push_back(j);
                 lc.coef.push_back(v);
@@ -49,8 +49,8 @@ static void install_layer(ngc_ctx* ctx, int layer, const double* B) {
     lc.A.clear();  // a decoding table belongs to the matrix it was built from
     lc.A_rows = 0;
     lc.A_stale = true;
-    lc.B.assign(B, B + (size_t)ctx->n * ctx->n);
-    compress_layer(lc, ctx->n);
+    lc.B.assign(B, B + (size_t)ctx->n * ctx->k);
+    compress_layer(lc, ctx->n, ctx->k);
     lc.set = true;
     ctx->code_dirty = true;
 }
@@ -59,7 +59,8 @@ extern "C" int ngc_create(ngc_ctx** out, int n, int k, int L, const int* s, int6
                           void* hip_stream) {
     if (!out) return NGC_ERR_INVALID;
     *out = nullptr;
-    if (n < 1 || n > NGC_MAX_N || k != n || L < 1 || L > NGC_MAX_N || !s || d < 1)
+    if (n < 1 || n > NGC_MAX_N || k < n || k > NGC_MAX_N || k % n != 0 || L < 1 || L > NGC_MAX_N ||
+        !s || d < 1)
         return NGC_ERR_INVALID;
     if (s[0] != 0) return NGC_ERR_INVALID;
     for (int u = 1; u < L; ++u)
@@ -68,14 +69,18 @@ extern "C" int ngc_create(ngc_ctx** out, int n, int k, int L, const int* s, int6
     ngc_ctx* ctx = new (std::nothrow) ngc_ctx;
     if (!ctx) return NGC_ERR_NOMEM;
     ctx->n = n;
+    ctx->k = k;
+    ctx->c = k / n;
     ctx->L = L;
     ctx->d = d;
     ctx->s.assign(s, s + L);
     ctx->stream = (hipStream_t)hip_stream;
     ctx->code.resize(L);
-    std::vector<double> I((size_t)n * n, 0.0);
-    for (int i = 0; i < n; ++i) I[(size_t)i * n + i] = 1.0;
-    install_layer(ctx, 0, I.data());  // Alg. 1: B_0 = I
+    // Alg. 1: B_0 = I; with c partitions per atomic task worker i holds group i: I (x) 1_{1 x c}
+    std::vector<double> I((size_t)n * k, 0.0);
+    for (int i = 0; i < n; ++i)
+        for (int q = 0; q < ctx->c; ++q) I[(size_t)i * k + i * ctx->c + q] = 1.0;
+    install_layer(ctx, 0, I.data());
     *out = ctx;
     return NGC_OK;
 }
@@ -89,18 +94,19 @@ extern "C" void ngc_destroy(ngc_ctx* ctx) {
 extern "C" int ngc_set_code(ngc_ctx* ctx, int layer, const double* B_host) {
     if (!ctx) return NGC_ERR_INVALID;
     if (layer < 0 || layer >= ctx->L || !B_host) return ngc_fail(ctx, NGC_ERR_INVALID, "bad layer or null B");
-    const int n = ctx->n;
-    for (size_t t = 0; t < (size_t)n * n; ++t)
+    const int n = ctx->n, k = ctx->k, c = ctx->c;
+    for (size_t t = 0; t < (size_t)n * k; ++t)
         if (!std::isfinite(B_host[t])) return ngc_fail(ctx, NGC_ERR_INVALID, "B has a non-finite entry");
     for (int i = 0; i < n; ++i) {
-        if (B_host[(size_t)i * n + i] == 0.0)
-            return ngc_fail(ctx, NGC_ERR_INVALID, "worker i must hold partition i (B[i][i] != 0)");
+        for (int q = 0; q < c; ++q)
+            if (B_host[(size_t)i * k + i * c + q] == 0.0)
+                return ngc_fail(ctx, NGC_ERR_INVALID, "worker i must hold its own partition(s) (B[i][i*c..] != 0)");
         // Def. 2: supports grow with the layer
-        for (int j = 0; j < n; ++j) {
-            bool here = B_host[(size_t)i * n + j] != 0.0;
+        for (int j = 0; j < k; ++j) {
+            bool here = B_host[(size_t)i * k + j] != 0.0;
             for (int v = 0; v < ctx->L; ++v) {
                 if (v == layer || !ctx->code[v].set) continue;
-                bool there = ctx->code[v].B[(size_t)i * n + j] != 0.0;
+                bool there = ctx->code[v].B[(size_t)i * k + j] != 0.0;
                 if (v < layer && there && !here)
                     return ngc_fail(ctx, NGC_ERR_INVALID, "row support does not contain the layer below (Def. 2)");
                 if (v > layer && here && !there)
@@ -116,7 +122,7 @@ extern "C" int ngc_get_code(const ngc_ctx* ctx, int layer, double* B_host_out) {
     if (!ctx) return NGC_ERR_INVALID;
     if (layer < 0 || layer >= ctx->L || !B_host_out) return ngc_fail(ctx, NGC_ERR_INVALID, "bad layer or null output");
     if (!ctx->code[layer].set) return ngc_fail(ctx, NGC_ERR_STATE, "layer has no code yet");
-    std::memcpy(B_host_out, ctx->code[layer].B.data(), sizeof(double) * ctx->n * ctx->n);
+    std::memcpy(B_host_out, ctx->code[layer].B.data(), sizeof(double) * ctx->n * ctx->k);
     return NGC_OK;
 }
 
@@ -249,7 +255,7 @@ double amplification(const std::vector<double>& B, int n, int sigma, uint64_t se
         rows.assign(perm.begin() + sigma, perm.end());
         std::sort(rows.begin(), rows.end());
         double resid = 0.0;
-        ngc_min_norm_decode(B.data(), n, rows.data(), (int)rows.size(), a.data(), &resid);
+        ngc_min_norm_decode(B.data(), n, n, rows.data(), (int)rows.size(), a.data(), &resid);
         if (!(resid < 1e-6)) return INFINITY;
         for (int i = 0; i < n; ++i) tot += std::fabs(a[i]) * l1[i];
     }
@@ -292,8 +298,15 @@ extern "C" int ngc_build_code(ngc_ctx* ctx, int kind, uint64_t seed) {
             if (!(best < INFINITY)) return ngc_fail(ctx, NGC_ERR_SINGULAR, "no valid cyclic draw found");
         }
     }
+    // k = c n partitions: worker i treats the c partitions of group j like partition j, B' (x) 1_{1 x c}
+    const int k = ctx->k, c = ctx->c;
+    std::vector<double> wide((size_t)n * k);
     for (int u = 0; u < ctx->L; ++u) ctx->code[u].set = false;
-    for (int u = 0; u < ctx->L; ++u) install_layer(ctx, u, built[u].data());
+    for (int u = 0; u < ctx->L; ++u) {
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < k; ++j) wide[(size_t)i * k + j] = built[u][(size_t)i * n + j / c];
+        install_layer(ctx, u, wide.data());
+    }
     return NGC_OK;
 }
 
@@ -318,7 +331,7 @@ static int select_impl(const ngc_ctx* ctx, const uint8_t* mask, int* layer_out, 
     for (int i = 0; i < n && ns < want; ++i)
         if (!mask[i]) rows[ns++] = i;
     double resid = 0.0;
-    ngc_min_norm_decode(ctx->code[u].B.data(), n, rows, ns, a_out, &resid);
+    ngc_min_norm_decode(ctx->code[u].B.data(), n, ctx->k, rows, ns, a_out, &resid);
     if (residual_out) *residual_out = resid;
     if (!(resid <= 1e-6)) return ngc_fail(ctx, NGC_ERR_SINGULAR, "decode residual above tolerance");
     return NGC_OK;
@@ -342,27 +355,29 @@ int ngc_make_worker_plan(const ngc_ctx* ctx, ngc_worker_plan& plan) {
     const int n = ctx->n, L = ctx->L;
     for (int u = 0; u < L; ++u)
         if (!ctx->code[u].set) return ngc_fail(ctx, NGC_ERR_STATE, "a layer has no code yet");
+    const int k = ctx->k, c = ctx->c;
     plan.order.assign(n, {});
     plan.needed.assign((size_t)L * n, 0);
     plan.T = 0;
     for (int i = 0; i < n; ++i) {
-        std::vector<char> have(n, 0);
+        std::vector<char> have(k, 0);
         for (int u = 0; u < L; ++u) {
             const std::vector<double>& B = ctx->code[u].B;
             int weight = 0;
-            // a layer adds its new partitions in cyclic order starting at the worker's own index
-            for (int t = 0; t < n; ++t) {
-                const int j = (i + t) % n;
-                if (B[(size_t)i * n + j] == 0.0) continue;
+            // a layer adds its new partitions in cyclic order starting at the worker's own group
+            for (int t = 0; t < k; ++t) {
+                const int j = (i * c + t) % k;
+                if (B[(size_t)i * k + j] == 0.0) continue;
                 ++weight;
                 if (!have[j]) {
                     have[j] = 1;
                     plan.order[i].push_back(j);
                 }
             }
-            plan.needed[(size_t)u * n + i] = weight;
+            if (weight % c) return ngc_fail(ctx, NGC_ERR_INVALID, "a row's support is not a whole number of atomic tasks");
+            plan.needed[(size_t)u * n + i] = weight / c;
         }
-        plan.T = std::max(plan.T, (int)plan.order[i].size());
+        plan.T = std::max(plan.T, (int)plan.order[i].size() / c);
     }
     return NGC_OK;
 }
@@ -413,7 +428,7 @@ extern "C" int ngc_select_from_progress(const ngc_ctx* ctx, const int* progress,
         *layer_out = u;
         for (int t = 0; t < ns; ++t) mask_out[rows[t]] = 0;
         double resid = 0.0;
-        ngc_min_norm_decode(ctx->code[u].B.data(), n, rows, ns, a_out, &resid);
+        ngc_min_norm_decode(ctx->code[u].B.data(), n, ctx->k, rows, ns, a_out, &resid);
         if (residual_out) *residual_out = resid;
         if (!(resid <= 1e-6)) return ngc_fail(ctx, NGC_ERR_SINGULAR, "decode residual above tolerance");
         return NGC_OK;
@@ -468,7 +483,7 @@ extern "C" int ngc_build_decoding_table(ngc_ctx* ctx, int layer, int64_t* rows_o
             resp[ns++] = i;
         }
         double resid = 0.0;
-        ngc_min_norm_decode(lc.B.data(), n, resp.data(), ns, &lc.A[(size_t)r * n], &resid);
+        ngc_min_norm_decode(lc.B.data(), n, ctx->k, resp.data(), ns, &lc.A[(size_t)r * n], &resid);
         if (!(resid <= 1e-6)) {
             lc.A.clear();
             return ngc_fail(ctx, NGC_ERR_SINGULAR, "a straggler set of size sigma cannot be decoded");

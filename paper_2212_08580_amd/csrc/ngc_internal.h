@@ -23,7 +23,7 @@ struct ngc_layer_code {
     int64_t A_rows = 0;
     double* d_A = nullptr;  // device copy, uploaded on first use
     bool A_stale = true;    // host table changed since the upload
-    std::vector<double> B;      // n x n dense, fp64, as given
+    std::vector<double> B;      // n x k dense, fp64, as given
     std::vector<int> rowptr;    // n + 1
     std::vector<int> col;
     std::vector<double> coef;
@@ -35,7 +35,9 @@ struct ngc_profile_rec {
 };
 
 struct ngc_ctx {
-    int n = 0;
+    int n = 0;   // workers
+    int k = 0;   // partitions, k = c * n
+    int c = 1;   // partitions per atomic task (Sec. II-C)
     int L = 0;
     int64_t d = 0;
     std::vector<int> s;
@@ -70,8 +72,9 @@ int ngc_fail(const ngc_ctx* ctx, int code, const std::string& msg);
 void ngc_dev_release(ngc_ctx* ctx);
 
 // Layered task schedule of every worker derived from the code tables (ngc_host.cpp):
-// order[i] = partitions in the order worker i computes them, needed[u*n+i] = tasks worker i must
-// have finished to form its layer-u message, T = longest schedule.  All layers must be set.
+// order[i] = partitions in the order worker i computes them (c per atomic task),
+// needed[u*n+i] = atomic tasks worker i must have finished to form its layer-u message,
+// T = longest schedule in atomic tasks.  All layers must be set.
 struct ngc_worker_plan {
     std::vector<std::vector<int>> order;
     std::vector<int> needed;
@@ -80,7 +83,7 @@ struct ngc_worker_plan {
 int ngc_make_worker_plan(const ngc_ctx* ctx, ngc_worker_plan& plan);
 
 // defined in ngc_solve.cpp: least-norm a_S with a_S^T B_S = 1^T.
-// rows: indices of responders (size ns).  B: n x n row-major.  a_out: n entries,
+// rows: indices of responders (size ns).  B: n x k row-major.  a_out: n entries,
 // zero outside rows.  Returns the numerical rank found; resid = max_j |a^T B - 1|.
-int ngc_min_norm_decode(const double* B, int n, const int* rows, int ns, double* a_out,
+int ngc_min_norm_decode(const double* B, int n, int k, const int* rows, int ns, double* a_out,
                         double* resid);

@@ -464,7 +464,7 @@ bool al(const void* p, uintptr_t m) { return (reinterpret_cast<uintptr_t>(p) & (
 
 int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float* theta,
                    int64_t rows, float* G) {
-    const int k = ctx->n;
+    const int k = ctx->k;
     const int din = ctx->mlp_din, hid = ctx->mlp_hidden, cls = ctx->mlp_classes;
     const int64_t d = ctx->d;
     if (hid > 1024) return ngc_fail(ctx, NGC_ERR_INVALID, "MLP hidden width above 1024 is not supported");

@@ -8,7 +8,7 @@
 //   (Q R11)^T a = 1   =>   R11^T z = 1,   a = Q [z; 0].
 // The remaining n - r equations are linear combinations of these because the
 // system is consistent whenever B is a gradient code and |S| >= n - sigma; the
-// caller checks the residual over all n columns.  fp64 throughout, n <= 64.
+// caller checks the residual over all k columns.  fp64 throughout, n, k <= 64.
 #include <algorithm>
 #include <cmath>
 #include <vector>
@@ -30,9 +30,10 @@ static inline double dot4(const double* __restrict__ x, const double* __restrict
     return (s0 + s1) + (s2 + s3);
 }
 
-int ngc_min_norm_decode(const double* B, int n, const int* rows, int ns, double* a_out,
+int ngc_min_norm_decode(const double* B, int nw, int n, const int* rows, int ns, double* a_out,
                         double* resid) {
-    for (int i = 0; i < n; ++i) a_out[i] = 0.0;
+    // nw workers (length of a), n = k columns of B
+    for (int i = 0; i < nw; ++i) a_out[i] = 0.0;
     if (ns <= 0) {
         if (resid) *resid = 1.0;
         return 0;

@@ -144,8 +144,8 @@ def ngc_set_code(ctx, layer, B):
     _check(_lib.ngc_set_code(ctx, int(layer), p), ctx)
 
 
-def ngc_get_code(ctx, layer, n):
-    out = np.empty((n, n), np.float64)
+def ngc_get_code(ctx, layer, n, k=None):
+    out = np.empty((n, k or n), np.float64)
     _check(_lib.ngc_get_code(ctx, int(layer), out.ctypes.data_as(ctypes.c_void_p)), ctx)
     return out
 
@@ -200,8 +200,7 @@ def ngc_worker_task_count(ctx):
 
 
 def ngc_worker_schedule(ctx, worker):
-    T = ngc_worker_task_count(ctx)
-    parts = np.zeros(max(T, 1), np.int32)
+    parts = np.zeros(64, np.int32)      # at most k <= 64 partitions
     cnt = ctypes.c_int(0)
     _check(_lib.ngc_worker_schedule(ctx, int(worker), parts.ctypes.data_as(ctypes.c_void_p),
                                     ctypes.byref(cnt)), ctx)

@@ -408,3 +408,76 @@ def test_decode_lookup_matches_oracle_and_solve_route(ngc, torch_dev, n, layers,
             ngc.ngc_decode_lookup(p.ctx, 1, m, p.C, p.g)
     finally:
         p.close()
+
+
+# --------------------------------------------------------------------------------------------
+# k = c*n partitions: an atomic task is k/n partial gradients (Sec. II-C); zero-padded rows
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,c,layers,kind,d,rows", [(8, 2, (0, 1, 3), "cyclic", 1024, 45),
+                                                     (4, 4, (0, 1), "fracrep", 4096, 19),
+                                                     (6, 3, (0, 2), "cyclic", 200, 12)])
+def test_several_partitions_per_worker(ngc, torch_dev, n, c, layers, kind, d, rows):
+    from oracle import workers as ow
+    torch = torch_dev
+    dev = torch.device("cuda:0")
+    k = n * c
+    w = wl.C3.scaled(rows=rows, d=d, n=k, layers=layers)             # k data partitions
+    X, Y = wl.dataset(w, seed=5, threads=1)
+    X[-1, rows - 3:] = 0.0                                           # last partition zero-padded
+    Y[-1, rows - 3:] = 0.0
+    th = wl.theta(w, seed=6)
+    Bs = codes.expand_partitions(codes.nested_code(n, layers, kind, seed=0, draws=2), c)
+    G_o = gradients.partial_gradients(w.loss, X, Y, th)
+    assert np.allclose(G_o[-1], gradients.lsq_gradient(X[-1, :rows - 3], Y[-1, :rows - 3], th))
+    full = G_o.sum(axis=0)
+    ctx = ngc.ngc_create(n, k, layers, d, torch.cuda.current_stream().cuda_stream)
+    try:
+        for u, B in enumerate(Bs):
+            ngc.ngc_set_code(ctx, u, B)
+        Xd, Yd, thd = (torch.from_numpy(a).to(dev) for a in (X, Y, th))
+        G = torch.empty((k, d), dtype=torch.float32, device=dev)
+        C = torch.empty((len(layers), n, d), dtype=torch.float32, device=dev)
+        g = torch.empty(d, dtype=torch.float32, device=dev)
+        ngc.ngc_partition_grads(ctx, w.loss, Xd, Yd, thd, rows, G)
+        ngc.ngc_encode(ctx, G, -1, C)
+        ngc.ngc_sync(ctx)
+        for j in range(k):
+            assert rel(G[j].cpu().numpy(), G_o[j]) <= TOL
+        Ch = C.cpu().numpy()
+        for u in range(len(layers)):
+            assert rel(Ch[u], coding.encode(Bs[u], G_o)) <= TOL
+        rng = np.random.default_rng(2)
+        for t in range(10):
+            m = np.zeros(n, np.uint8)
+            m[rng.choice(n, size=int(rng.integers(0, layers[-1] + 1)), replace=False)] = 1
+            u, a, r = ngc.ngc_select_decode_vec(ctx, m, n)
+            a_o, _ = coding.decode_vector(Bs[u], m)
+            assert u == coding.select_layer(layers, m) and np.array_equal(a != 0, a_o != 0)
+            ngc.ngc_decode(ctx, u, a, C, g)
+            ngc.ngc_sync(ctx)
+            kappa = coding.conditioning(a_o, coding.encode(Bs[u], G_o), full)
+            assert rel(g.cpu().numpy(), full) <= max(TOL, 4 * 2.0 ** -24 * kappa)
+        # redundancy-faithful mode: a task is c partitions
+        T = ngc.ngc_worker_task_count(ctx)
+        assert T == layers[-1] + 1
+        progress = np.array([T] * (n - 1) + [0])
+        W = torch.full((n, T * c, d), 7.0, dtype=torch.float32, device=dev)
+        ngc.ngc_worker_grads(ctx, w.loss, Xd, Yd, thd, rows, progress, W)
+        ngc.ngc_worker_encode(ctx, W, progress, C)
+        u, mask, a, r = ngc.ngc_select_from_progress(ctx, progress, n)
+        ngc.ngc_decode(ctx, u, a, C, g)
+        ngc.ngc_sync(ctx)
+        W_o = ow.worker_partials(w.loss, X, Y, th, Bs, progress)
+        u_o, mask_o, a_o, g_o = ow.decode_from_workers(Bs, layers, W_o, progress)
+        assert u == u_o and np.array_equal(mask, mask_o)
+        Wh = W.cpu().numpy()
+        for i in range(n - 1):
+            for t in range(T * c):
+                assert rel(Wh[i, t], W_o[i][t]) <= TOL
+        assert np.all(Wh[n - 1] == 7.0)
+        C_o = ow.worker_messages(Bs, W_o, progress)
+        for i in range(n - 1):
+            assert rel(C[u, i].cpu().numpy(), C_o[u][i]) <= TOL
+        assert rel(g.cpu().numpy(), full) <= TOL
+    finally:
+        ngc.ngc_destroy(ctx)

@@ -367,3 +367,47 @@ def test_decoding_table_size_limit(ngc):
         assert e.value.code == ngc.NGC_ERR_INVALID
     finally:
         ngc.ngc_destroy(ctx)
+
+
+# ---- k = c*n partitions (an atomic task is k/n partial gradients, Sec. II-C) --------------------
+def test_context_with_several_partitions_per_worker(ngc):
+    from oracle import workers as ow
+    n, c, layers = 6, 2, [0, 1, 3]
+    k = n * c
+    ctx = ngc.ngc_create(n, k, layers, 4)
+    try:
+        assert np.array_equal(ngc.ngc_get_code(ctx, 0, n, k), np.kron(np.eye(n), np.ones((1, c))))
+        ngc.ngc_build_code(ctx, ngc.NGC_CODE_CYCLIC, 3)
+        Bs = [ngc.ngc_get_code(ctx, u, n, k) for u in range(3)]
+        for B, sigma in zip(Bs, layers):
+            assert np.all((B != 0).sum(axis=1) == c * (sigma + 1))            # Def. 1: weight (k/n)(sigma+1)
+            assert np.array_equal(B[:, 0::2], B[:, 1::2])
+            for out in itertools.combinations(range(n), sigma):
+                m = np.zeros(n, np.uint8)
+                m[list(out)] = 1
+                u, a, r = ngc.ngc_select_decode_vec(ctx, m, n)
+                assert r < 1e-8
+        # the oracle's widened code through set_code, decode vectors against the oracle
+        Bo = codes.expand_partitions(codes.nested_code(n, layers, "cyclic", seed=0, draws=2), c)
+        for u, B in enumerate(Bo):
+            ngc.ngc_set_code(ctx, u, B)
+        rng = np.random.default_rng(0)
+        for _ in range(40):
+            m = np.zeros(n, np.uint8)
+            m[rng.choice(n, size=int(rng.integers(0, 4)), replace=False)] = 1
+            u, a, r = ngc.ngc_select_decode_vec(ctx, m, n)
+            u_o = coding.select_layer(layers, m)
+            a_o, _ = coding.decode_vector(Bo[u_o], m)
+            assert u == u_o and np.abs(a - a_o).max() <= 1e-8 * max(1.0, np.abs(a_o).max())
+        assert ngc.ngc_worker_task_count(ctx) == 4
+        for i in range(n):
+            assert ngc.ngc_worker_schedule(ctx, i) == ow.task_order(Bo, i)
+        bad = Bo[1].copy()
+        bad[2, 2 * c + 1] = 0.0                                            # worker 2 must hold all of group 2
+        with pytest.raises(ngc.NgcError):
+            ngc.ngc_set_code(ctx, 1, bad)
+    finally:
+        ngc.ngc_destroy(ctx)
+    for n, k in ((4, 6), (8, 4), (40, 80)):
+        with pytest.raises(ngc.NgcError):
+            ngc.ngc_create(n, k, [0, 1], 4)
