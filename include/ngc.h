@@ -59,7 +59,8 @@ enum {
     NGC_KERNEL_UPDATE = 4,
     NGC_KERNEL_MLP = 5,     /* all GEMM-shaped kernels of the MLP gradient                  */
     NGC_KERNEL_PROBE = 6,   /* ngc_probe_copy / ngc_probe_read                              */
-    NGC_KERNEL_COUNT = 7
+    NGC_KERNEL_TAIL = 7,    /* fused reduce + encode + decode + update of ngc_iteration     */
+    NGC_KERNEL_COUNT = 8
 };
 
 /*
@@ -266,6 +267,23 @@ int ngc_decode_lookup(ngc_ctx* ctx, int layer, const uint8_t* straggler_mask, co
 
 /* theta[:] -= scale * g[:]  with scale = eta/m  (Sec. II-B eq. (1)). */
 int ngc_update(ngc_ctx* ctx, float* theta_dev, const float* g_dev, double scale);
+
+/*
+ * One whole iteration (Sec. II-C; update of Sec. II-B eq. (1)): partition
+ * gradients at theta, messages of every layer, layer and least-norm decode
+ * vector for the straggler mask, decode, theta <- theta - scale * g.  Same
+ * results, bit for bit, as ngc_partition_grads, ngc_encode(-1),
+ * ngc_select_decode_vec, ngc_decode, ngc_update in sequence, but for the two
+ * regression losses everything after the gradient kernel is one launch that
+ * reads that kernel's block partials column tile by column tile.  G_dev
+ * [k][d], C_dev [L][n][d], g_dev [d] are all written; theta_dev is read and
+ * updated; all five device buffers 16-byte aligned.  layer_out / a_out (n
+ * doubles) may be NULL.  An undecodable mask returns NGC_ERR_UNDECODABLE before
+ * anything is launched (theta stays as it is).
+ */
+int ngc_iteration(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_dev, float* theta_dev,
+                  int64_t rows_per_part, const uint8_t* straggler_mask, double scale, float* G_dev,
+                  float* C_dev, float* g_dev, int* layer_out, double* a_out);
 
 /* Block until the context's stream is idle. */
 int ngc_sync(ngc_ctx* ctx);

@@ -422,6 +422,117 @@ __global__ __launch_bounds__(256) void decode_lookup_kernel(const float* __restr
     }
 }
 
+// ---------------------------------------------------------------------------
+// Fused tail of one iteration for a tile of 16*V columns: sum of the gradient
+// kernel's block partials (-> G), messages of every layer (-> C), decode with the
+// given vector (-> g) and the descent update of theta, all from LDS.  Every step
+// adds in the same order as the stand-alone kernels (reduce_partials, encode,
+// decode, update), so the results are the same bits.
+//   threads: 16 groups ("slots") of 16 lanes; a lane owns V columns.
+// ---------------------------------------------------------------------------
+template <typename VT, int V>
+__global__ __launch_bounds__(256) void iteration_tail_kernel(
+    const float* __restrict__ partial, int chunks, float* __restrict__ G, float* __restrict__ C,
+    const int* __restrict__ rowptr, const int* __restrict__ col, const float* __restrict__ coef,
+    int nnz, int n, int k, int L, int64_t d, int layer, decode_args args, float* __restrict__ g,
+    float* __restrict__ theta, float scale) {
+    extern __shared__ float lds_raw[];
+    constexpr int PW = 16 * V + 1;
+    VT* tile = reinterpret_cast<VT*>(lds_raw);                        // [k][16]   G tile
+    VT* msg = tile + (size_t)k * 16;                                  // [n][16]   messages of the decode layer
+    double* part = reinterpret_cast<double*>(msg + (size_t)n * 16);   // [16][PW]
+    int* rp_s = reinterpret_cast<int*>(part + 16 * PW);               // [L*n + 1]
+    int* col_s = rp_s + L * n + 1;                                    // [nnz]
+    float* coef_s = reinterpret_cast<float*>(col_s + nnz);            // [nnz]
+    const int lane16 = threadIdx.x & 15;
+    const int slot = threadIdx.x >> 4;
+    const int64_t c = ((int64_t)blockIdx.x * 16 + lane16) * V;
+    const bool in = c < d;
+    // the code tables are small: one copy per block in LDS
+    for (int t = threadIdx.x; t <= L * n; t += 256) rp_s[t] = rowptr[t];
+    for (int t = threadIdx.x; t < nnz; t += 256) {
+        col_s[t] = col[t];
+        coef_s[t] = coef[t];
+    }
+    // 1. G tile = sum of block partials, chunks added in index order (sixteen loads in flight)
+    for (int j = slot; j < k; j += 16) {
+        VT acc = (VT)(0.0f);
+        if (in) {
+            const float* p = partial + (int64_t)j * chunks * d + c;
+            acc = *reinterpret_cast<const VT*>(p);
+            int t = 1;
+            for (; t + 16 <= chunks; t += 16) {
+                VT x[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) x[u] = *reinterpret_cast<const VT*>(p + (int64_t)(t + u) * d);
+#pragma unroll
+                for (int u = 0; u < 16; ++u) acc += x[u];
+            }
+            if (t + 8 <= chunks) {
+                VT x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = *reinterpret_cast<const VT*>(p + (int64_t)(t + u) * d);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc += x[u];
+                t += 8;
+            }
+            for (; t < chunks; ++t) acc += *reinterpret_cast<const VT*>(p + (int64_t)t * d);
+            *reinterpret_cast<VT*>(G + (int64_t)j * d + c) = acc;
+        }
+        tile[j * 16 + lane16] = acc;
+    }
+    __syncthreads();
+    // 2. messages of every (layer, worker) pair; those of the decode layer are kept in LDS
+    const int np = L * n;
+    for (int p = slot; p < np; p += 16) {
+        const int b = rp_s[p], e = rp_s[p + 1];
+        VT acc0 = (VT)(0.0f), acc1 = (VT)(0.0f);
+        int t = b;
+        for (; t + 8 <= e; t += 8) {
+#pragma unroll
+            for (int u = 0; u < 8; u += 2) {
+                acc0 += coef_s[t + u] * tile[col_s[t + u] * 16 + lane16];
+                acc1 += coef_s[t + u + 1] * tile[col_s[t + u + 1] * 16 + lane16];
+            }
+        }
+        for (; t < e; ++t) acc0 += coef_s[t] * tile[col_s[t] * 16 + lane16];
+        const VT m = acc0 + acc1;
+        if (in) *reinterpret_cast<VT*>(C + (int64_t)p * d + c) = m;
+        if (p / n == layer) msg[(p - layer * n) * 16 + lane16] = m;
+    }
+    __syncthreads();
+    // 3. decode: fp64 products and sums, responders dealt to the 16 groups in turn
+    double acc[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[v] = 0.0;
+    for (int t = slot; t < args.count; t += 16) {
+        const VT m = msg[args.idx[t] * 16 + lane16];
+        const double a = args.a[t];
+        if constexpr (V == 1) {
+            acc[0] += a * (double)m;
+        } else {
+#pragma unroll
+            for (int v = 0; v < V; ++v) acc[v] += a * (double)m[v];
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < V; ++v) part[slot * PW + lane16 * V + v] = acc[v];
+    __syncthreads();
+    const int q = threadIdx.x;
+    if (q < 16 * V) {
+        const int64_t cq = (int64_t)blockIdx.x * 16 * V + q;
+        if (cq < d) {
+            double s = part[q];
+#pragma unroll
+            for (int kk = 1; kk < 16; ++kk) s += part[kk * PW + q];
+            const float gq = (float)s;
+            g[cq] = gq;
+            // 4. theta <- theta - scale * g
+            theta[cq] = theta[cq] - scale * gq;
+        }
+    }
+}
+
 // K6: theta -= scale * g
 __global__ __launch_bounds__(256) void update_kernel(float* __restrict__ theta,
                                                      const float* __restrict__ g, float scale,
@@ -660,9 +771,16 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
 // Gradients of `units` partial-gradient computations (least squares / logistic).  Unit q works
 // on partition unit_part[q] (q itself if unit_part is null) and its result goes to row
 // unit_row[q] of G_dev (row q if null); both maps are device arrays.
+struct partial_info {
+    const float* ptr = nullptr;  // [units][chunks][d]
+    int chunks = 0;
+};
+
+// If `defer` is given the block partials are left unreduced for the caller to sum (in chunk
+// order) and G_dev is not written.
 static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_dev,
                       const float* theta_dev, int64_t rows, float* G_dev, int units,
-                      const int* unit_part, const int* unit_row) {
+                      const int* unit_part, const int* unit_row, partial_info* defer = nullptr) {
     int rc = NGC_OK;
     const int k = units;
     const int64_t d = ctx->d;
@@ -703,6 +821,11 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
 #undef NGC_STREAM_CASE
         }
         NGC_HIP(ctx, hipGetLastError());
+        if (defer) {
+            defer->ptr = ctx->d_ws;
+            defer->chunks = (int)chunks;
+            return NGC_OK;
+        }
         {
             prof_scope ps(ctx, NGC_KERNEL_REDUCE);
             const int64_t dv = d / 4;
@@ -740,6 +863,11 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
                            (int)chunks, rpc, unit_part);
     }
     NGC_HIP(ctx, hipGetLastError());
+    if (defer) {
+        defer->ptr = partial;
+        defer->chunks = (int)chunks;
+        return NGC_OK;
+    }
     {
         prof_scope ps(ctx, NGC_KERNEL_REDUCE);
         dim3 grid((unsigned)((d + 255) / 256), (unsigned)k);
@@ -1105,6 +1233,82 @@ extern "C" int ngc_decode_lookup(ngc_ctx* ctx, int layer, const uint8_t* straggl
             hipLaunchKernelGGL((decode_lookup_kernel<v2f, 2>), dim3((unsigned)gx), dim3(256), 0, ctx->stream, Cl, g_dev, d, n, a_row);
         else
             hipLaunchKernelGGL((decode_lookup_kernel<float, 1>), dim3((unsigned)gx), dim3(256), 0, ctx->stream, Cl, g_dev, d, n, a_row);
+    }
+    NGC_HIP(ctx, hipGetLastError());
+    return NGC_OK;
+}
+
+// ---- one whole iteration in two launches ----------------------------------------------------------
+extern "C" int ngc_iteration(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_dev,
+                             float* theta_dev, int64_t rows, const uint8_t* straggler_mask,
+                             double scale, float* G_dev, float* C_dev, float* g_dev, int* layer_out,
+                             double* a_out) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (!X_dev || !y_dev || !theta_dev || !G_dev || !C_dev || !g_dev || !straggler_mask)
+        return ngc_fail(ctx, NGC_ERR_INVALID, "null pointer");
+    if (rows < 1) return ngc_fail(ctx, NGC_ERR_INVALID, "rows_per_part must be positive");
+    if (loss != NGC_LOSS_LSQ && loss != NGC_LOSS_LOGISTIC && loss != NGC_LOSS_MLP2)
+        return ngc_fail(ctx, NGC_ERR_INVALID, "unknown loss");
+    if (!aligned16(X_dev) || !aligned16(theta_dev) || !aligned16(G_dev) || !aligned16(C_dev) || !aligned16(g_dev))
+        return ngc_fail(ctx, NGC_ERR_INVALID, "device buffers must be 16-byte aligned");
+    // main-node bookkeeping first: an undecodable round launches nothing
+    double a[NGC_MAX_N];
+    int layer = -1;
+    double resid = 0.0;
+    int rc = ngc_select_decode_vec(ctx, straggler_mask, &layer, a, &resid);
+    if (layer_out) *layer_out = layer;
+    if (rc) return rc;
+    if (a_out) std::memcpy(a_out, a, sizeof(double) * ctx->n);
+    if (loss == NGC_LOSS_MLP2) {  // no block partials to fuse: the stand-alone calls in sequence
+        rc = ngc_partition_grads(ctx, loss, X_dev, y_dev, theta_dev, rows, G_dev);
+        if (!rc) rc = ngc_encode(ctx, G_dev, -1, C_dev);
+        if (!rc) rc = ngc_decode(ctx, layer, a, C_dev, g_dev);
+        if (!rc) rc = ngc_update(ctx, theta_dev, g_dev, scale);
+        return rc;
+    }
+    rc = dev_init(ctx);
+    if (rc) return rc;
+    rc = upload_code(ctx);
+    if (rc) return rc;
+    partial_info pi;
+    rc = grads_impl(ctx, loss, X_dev, y_dev, theta_dev, rows, G_dev, ctx->k, nullptr, nullptr, &pi);
+    if (rc) return rc;
+    const int n = ctx->n, k = ctx->k, L = ctx->L;
+    const int64_t d = ctx->d;
+    decode_args args;
+    args.count = 0;
+    for (int i = 0; i < n; ++i)
+        if (a[i] != 0.0) {
+            args.a[args.count] = a[i];
+            args.idx[args.count] = i;
+            ++args.count;
+        }
+    for (int t = args.count; t < NGC_MAX_N; ++t) {
+        args.a[t] = 0.0;
+        args.idx[t] = 0;
+    }
+    const size_t np = (size_t)L * n;
+    const int* rowptr = (const int*)ctx->d_code;
+    const int* col = rowptr + np + 1;
+    const float* coef = (const float*)(col + ctx->code_nnz);
+    // widest vector that still leaves about a block per four CUs
+    int V = d % 4 == 0 ? 4 : (d % 2 == 0 ? 2 : 1);
+    while (V > 1 && (d + 16 * V - 1) / (16 * V) < ctx->cu_count / 4) V /= 2;
+    const int64_t gx = (d + 16 * V - 1) / (16 * V);
+    const int nnz = (int)ctx->code_nnz;
+    const size_t lds = ((size_t)k + n) * 16 * V * sizeof(float) + (size_t)16 * (16 * V + 1) * sizeof(double) +
+                       (np + 1 + 2 * (size_t)nnz) * sizeof(int);
+    {
+        prof_scope ps(ctx, NGC_KERNEL_TAIL);
+        if (V == 4)
+            hipLaunchKernelGGL((iteration_tail_kernel<v4f, 4>), dim3((unsigned)gx), dim3(256), lds, ctx->stream, pi.ptr,
+                               pi.chunks, G_dev, C_dev, rowptr, col, coef, nnz, n, k, L, d, layer, args, g_dev, theta_dev, (float)scale);
+        else if (V == 2)
+            hipLaunchKernelGGL((iteration_tail_kernel<v2f, 2>), dim3((unsigned)gx), dim3(256), lds, ctx->stream, pi.ptr,
+                               pi.chunks, G_dev, C_dev, rowptr, col, coef, nnz, n, k, L, d, layer, args, g_dev, theta_dev, (float)scale);
+        else
+            hipLaunchKernelGGL((iteration_tail_kernel<float, 1>), dim3((unsigned)gx), dim3(256), lds, ctx->stream, pi.ptr,
+                               pi.chunks, G_dev, C_dev, rowptr, col, coef, nnz, n, k, L, d, layer, args, g_dev, theta_dev, (float)scale);
     }
     NGC_HIP(ctx, hipGetLastError());
     return NGC_OK;

@@ -29,13 +29,13 @@ NGC_ERR_STATE = -6
 
 NGC_LOSS_LSQ, NGC_LOSS_LOGISTIC, NGC_LOSS_MLP2 = 0, 1, 2
 NGC_CODE_CYCLIC, NGC_CODE_FRACREP = 0, 1
-NGC_KERNEL_NAMES = ("grad", "reduce", "encode", "decode", "update", "mlp", "probe")
+NGC_KERNEL_NAMES = ("grad", "reduce", "encode", "decode", "update", "mlp", "probe", "tail")
 NGC_KERNEL_COUNT = len(NGC_KERNEL_NAMES)
 
 EXPORTS = (
     "ngc_create", "ngc_destroy", "ngc_set_code", "ngc_get_code", "ngc_build_code",
     "ngc_set_mlp2_shape", "ngc_partition_grads", "ngc_encode", "ngc_select_decode_vec",
-    "ngc_select_decode_vec_first", "ngc_decode", "ngc_update", "ngc_sync",
+    "ngc_select_decode_vec_first", "ngc_decode", "ngc_update", "ngc_iteration", "ngc_sync",
     "ngc_worker_task_count", "ngc_worker_schedule", "ngc_worker_grads", "ngc_worker_encode",
     "ngc_select_from_progress", "ngc_build_decoding_table", "ngc_decoding_row_index",
     "ngc_get_decoding_row", "ngc_decode_lookup", "ngc_latency_cdf_gc", "ngc_latency_cdf_ngc", "ngc_latency_simulate",
@@ -65,6 +65,8 @@ _lib.ngc_select_decode_vec.argtypes = [_vp, _vp, ctypes.POINTER(_i), _vp, ctypes
 _lib.ngc_select_decode_vec_first.argtypes = _lib.ngc_select_decode_vec.argtypes
 _lib.ngc_decode.argtypes = [_vp, _i, _vp, _vp, _vp]
 _lib.ngc_update.argtypes = [_vp, _vp, _vp, _dbl]
+_lib.ngc_iteration.argtypes = [_vp, _i, _vp, _vp, _vp, _i64, _vp, _dbl, _vp, _vp, _vp,
+                               ctypes.POINTER(_i), _vp]
 _lib.ngc_build_decoding_table.argtypes = [_vp, _i, ctypes.POINTER(_i64)]
 _lib.ngc_decoding_row_index.argtypes = [_vp, _i, _vp, ctypes.POINTER(_i64)]
 _lib.ngc_get_decoding_row.argtypes = [_vp, _i, _i64, _vp]
@@ -278,6 +280,17 @@ def ngc_get_decoding_row(ctx, layer, row, n):
 def ngc_decode_lookup(ctx, layer, mask, C, g):
     mask, pm = _host(mask, np.uint8)
     _check(_lib.ngc_decode_lookup(ctx, int(layer), pm, _dev(C), _dev(g)), ctx)
+
+
+def ngc_iteration(ctx, loss, X, y, theta, rows_per_part, mask, scale, G, C, g, n):
+    """-> (layer, a [n] fp64)."""
+    mask, pm = _host(mask, np.uint8)
+    a = np.zeros(n, np.float64)
+    layer = ctypes.c_int(-1)
+    _check(_lib.ngc_iteration(ctx, int(loss), _dev(X), _dev(y), _dev(theta), int(rows_per_part), pm,
+                              float(scale), _dev(G), _dev(C), _dev(g), ctypes.byref(layer),
+                              a.ctypes.data_as(ctypes.c_void_p)), ctx)
+    return layer.value, a
 
 
 def ngc_update(ctx, theta, g, scale):

@@ -481,3 +481,67 @@ def test_several_partitions_per_worker(ngc, torch_dev, n, c, layers, kind, d, ro
         assert rel(g.cpu().numpy(), full) <= TOL
     finally:
         ngc.ngc_destroy(ctx)
+
+
+# --------------------------------------------------------------------------------------------
+# ngc_iteration: the whole iteration in two launches, same bits as the stand-alone calls
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("base,n,c,rows,d,layers", [
+    (wl.C3, 32, 1, 70, 4096, (0, 1, 3, 7, 15)), (wl.C2, 16, 1, 130, 1024, (0, 1, 3, 7)),
+    (wl.C3, 6, 1, 33, 200, (0, 1, 3)), (wl.C2, 5, 1, 21, 77, (0, 2)), (wl.C3, 4, 2, 25, 512, (0, 1)),
+    (wl.C3, 64, 1, 5, 16384, (0, 1, 3, 7, 15, 31)),
+])
+def test_fused_iteration_equals_separate_calls(ngc, torch_dev, base, n, c, rows, d, layers):
+    torch = torch_dev
+    dev = torch.device("cuda:0")
+    k = n * c
+    w = base.scaled(rows=rows, d=d, n=k, layers=layers)
+    X, Y = wl.dataset(w, seed=9, threads=2)
+    scale = None if w.loss == wl.LOSS_LSQ else 2.0 / np.sqrt(d)
+    th = wl.theta(w, seed=4, scale=scale)
+    Bs = codes.expand_partitions(codes.nested_code(n, layers, "cyclic", seed=0, draws=2), c)
+    ctx = ngc.ngc_create(n, k, layers, d, torch.cuda.current_stream().cuda_stream)
+    try:
+        for u, B in enumerate(Bs):
+            ngc.ngc_set_code(ctx, u, B)
+        Xd, Yd = torch.from_numpy(X).to(dev), torch.from_numpy(Y).to(dev)
+        L = len(layers)
+        bufs = [[torch.empty((k, d), dtype=torch.float32, device=dev),
+                 torch.empty((L, n, d), dtype=torch.float32, device=dev),
+                 torch.empty(d, dtype=torch.float32, device=dev),
+                 torch.from_numpy(th.copy()).to(dev)] for _ in range(2)]
+        rng = np.random.default_rng(0)
+        eta = 0.3 / w.m
+        for t in range(4):
+            m = np.zeros(n, np.uint8)
+            m[rng.choice(n, size=int(rng.integers(0, layers[-1] + 1)), replace=False)] = 1
+            G0, C0, g0, th0 = bufs[0]
+            ngc.ngc_partition_grads(ctx, w.loss, Xd, Yd, th0, rows, G0)
+            ngc.ngc_encode(ctx, G0, -1, C0)
+            u0, a0, _ = ngc.ngc_select_decode_vec(ctx, m, n)
+            ngc.ngc_decode(ctx, u0, a0, C0, g0)
+            ngc.ngc_update(ctx, th0, g0, eta)
+            G1, C1, g1, th1 = bufs[1]
+            u1, a1 = ngc.ngc_iteration(ctx, w.loss, Xd, Yd, th1, rows, m, eta, G1, C1, g1, n)
+            ngc.ngc_sync(ctx)
+            assert u0 == u1 and np.array_equal(a0, a1)
+            assert torch.equal(G0, G1) and torch.equal(C0, C1) and torch.equal(g0, g1)
+            assert torch.equal(th0, th1)
+        # and against the oracle for the last round's gradient at the last theta before the update
+        # (theta after t rounds is the same on both routes, so check the fused outputs directly)
+        m = np.zeros(n, np.uint8)
+        th_now = bufs[1][3].cpu().numpy()
+        u1, a1 = ngc.ngc_iteration(ctx, w.loss, Xd, Yd, bufs[1][3], rows, m, 0.0, *bufs[1][:3], n)
+        ngc.ngc_sync(ctx)
+        G_o = gradients.partial_gradients(w.loss, X, Y, th_now)
+        assert u1 == 0 and rel(bufs[1][0].cpu().numpy(), G_o) <= TOL
+        assert rel(bufs[1][2].cpu().numpy(), G_o.sum(axis=0)) <= TOL
+        bad = np.ones(n, np.uint8)
+        before = bufs[1][3].clone()
+        with pytest.raises(ngc.NgcError) as e:
+            ngc.ngc_iteration(ctx, w.loss, Xd, Yd, bufs[1][3], rows, bad, eta, *bufs[1][:3], n)
+        assert e.value.code == ngc.NGC_ERR_UNDECODABLE
+        ngc.ngc_sync(ctx)
+        assert torch.equal(before, bufs[1][3])                      # theta untouched
+    finally:
+        ngc.ngc_destroy(ctx)
