@@ -254,7 +254,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const VT* __restri
 
 // ---------------------------------------------------------------------------
 // K3: layered encode.  A block stages a tile of G (all n rows, 64*V columns) in
-// LDS, then each of its waves writes the messages of (layer, worker) pairs from
+// LDS, then each of its eight waves writes the messages of (layer, worker) pairs from
 // there, one pair at a time: a pair is one sparse row of B^(u) in compressed
 // form, and since the whole wave works on the same pair its column indices and
 // coefficients are wave-uniform (scalar loads); only the tile reads and the
@@ -262,8 +262,10 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const VT* __restri
 // [L*n][d].  G is read from HBM once per column tile however many layers there
 // are (blocks that share a tile re-read it from L2).
 // ---------------------------------------------------------------------------
+constexpr int ENC_WAVES = 8;  // waves per block sharing one LDS tile of G
+
 template <typename VT, int V>
-__global__ __launch_bounds__(256) void encode_kernel(const float* __restrict__ G,
+__global__ __launch_bounds__(ENC_WAVES * 64) void encode_kernel(const float* __restrict__ G,
                                                      float* __restrict__ C,
                                                      const int* __restrict__ rowptr,
                                                      const int* __restrict__ col,
@@ -277,15 +279,27 @@ __global__ __launch_bounds__(256) void encode_kernel(const float* __restrict__ G
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t c = ((int64_t)blockIdx.x * 64 + lane) * V;
     const bool in = c < d;
-    for (int r = wave; r < n; r += 4) {
-        VT v = (VT)(0.0f);
-        if (in) v = *reinterpret_cast<const VT*>(G + (int64_t)r * d + c);
-        tile[r * 64 + lane] = v;
+    // staging: eight rows per trip so that their loads are in flight together
+    for (int r0 = wave; r0 < n; r0 += 8 * ENC_WAVES) {
+        VT v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int r = r0 + ENC_WAVES * u;
+            v[u] = (VT)(0.0f);
+            if (in && r < n) v[u] = *reinterpret_cast<const VT*>(G + (int64_t)r * d + c);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int r = r0 + ENC_WAVES * u;
+            if (r < n) tile[r * 64 + lane] = v[u];
+        }
     }
     __syncthreads();
-    const int p0 = pair_begin + blockIdx.y * pairs_per_group;
-    const int p1 = pair_end < p0 + pairs_per_group ? pair_end : p0 + pairs_per_group;
-    for (int p = p0 + wave; p < p1; p += 4) {
+    // pairs are dealt to the blocks of a column tile and to their waves in turn, so that
+    // every wave gets rows of every layer (layers differ in row weight by up to s_max+1)
+    (void)pairs_per_group;
+    const int stride = (int)gridDim.y * ENC_WAVES;
+    for (int p = pair_begin + (int)blockIdx.y * ENC_WAVES + wave; p < pair_end; p += stride) {
         const int b = rowptr[p], e = rowptr[p + 1];
         VT acc0 = (VT)(0.0f), acc1 = (VT)(0.0f);
         int t = b;
@@ -308,7 +322,31 @@ __global__ __launch_bounds__(256) void encode_kernel(const float* __restrict__ G
                 acc1 += ww[u + 1] * x[u + 1];
             }
         }
-        for (; t < e; ++t) acc0 += coef[t] * tile[col[t] * 64 + lane];
+        // remainder: same order of additions as one term at a time, loads batched
+        if (t + 4 <= e) {
+            int cc[4];
+            float ww[4];
+            VT x[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                cc[u] = col[t + u];
+                ww[u] = coef[t + u];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) x[u] = tile[cc[u] * 64 + lane];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc0 += ww[u] * x[u];
+            t += 4;
+        }
+        if (t + 2 <= e) {
+            const int c0 = col[t], c1 = col[t + 1];
+            const float w0 = coef[t], w1 = coef[t + 1];
+            const VT x0 = tile[c0 * 64 + lane], x1 = tile[c1 * 64 + lane];
+            acc0 += w0 * x0;
+            acc0 += w1 * x1;
+            t += 2;
+        }
+        if (t < e) acc0 += coef[t] * tile[col[t] * 64 + lane];
         if (in) *reinterpret_cast<VT*>(C + (int64_t)p * d + c) = acc0 + acc1;
     }
 }
@@ -969,25 +1007,23 @@ extern "C" int ngc_encode(ngc_ctx* ctx, const float* G_dev, int layer, float* C_
     const int V = vec_width(d, G_dev, C_dev);
     const int64_t gx = (d + 64 * V - 1) / (64 * V);
     const int pairs = pe - pb;
-    // enough blocks for about three per CU; each wave of a block takes every fourth pair
+    // enough blocks for about three per CU; the pairs are dealt to blocks and waves in turn
     int64_t gy = std::max<int64_t>(1, (3 * (int64_t)ctx->cu_count + gx - 1) / gx);
-    gy = std::min<int64_t>(gy, (pairs + 3) / 4);
-    int ppg = (int)((pairs + gy - 1) / gy);
-    ppg = ((ppg + 3) / 4) * 4;
-    gy = (pairs + ppg - 1) / ppg;
+    gy = std::min<int64_t>(gy, (pairs + ENC_WAVES - 1) / ENC_WAVES);
+    const int ppg = 0;  // pairs are dealt to blocks and waves in turn
     if (gx > 0x7fffffffLL) return ngc_fail(ctx, NGC_ERR_INVALID, "d too large");
     dim3 grid((unsigned)gx, (unsigned)gy);
     const size_t lds = (size_t)ctx->k * 64 * V * sizeof(float);  // all k rows of G, 64*V columns
     {
         prof_scope ps(ctx, NGC_KERNEL_ENCODE);
         if (V == 4)
-            hipLaunchKernelGGL((encode_kernel<v4f, 4>), grid, dim3(256), lds, ctx->stream, G_dev, C_dev,
+            hipLaunchKernelGGL((encode_kernel<v4f, 4>), grid, dim3(ENC_WAVES * 64), lds, ctx->stream, G_dev, C_dev,
                                rowptr, col, coef, ctx->k, d, pb, pe, ppg);
         else if (V == 2)
-            hipLaunchKernelGGL((encode_kernel<v2f, 2>), grid, dim3(256), lds, ctx->stream, G_dev, C_dev,
+            hipLaunchKernelGGL((encode_kernel<v2f, 2>), grid, dim3(ENC_WAVES * 64), lds, ctx->stream, G_dev, C_dev,
                                rowptr, col, coef, ctx->k, d, pb, pe, ppg);
         else
-            hipLaunchKernelGGL((encode_kernel<float, 1>), grid, dim3(256), lds, ctx->stream, G_dev, C_dev,
+            hipLaunchKernelGGL((encode_kernel<float, 1>), grid, dim3(ENC_WAVES * 64), lds, ctx->stream, G_dev, C_dev,
                                rowptr, col, coef, ctx->k, d, pb, pe, ppg);
     }
     NGC_HIP(ctx, hipGetLastError());
