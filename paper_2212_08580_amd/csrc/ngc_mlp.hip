@@ -55,6 +55,27 @@ __device__ __forceinline__ v4f load4(const float* __restrict__ p, int64_t left, 
     return v;
 }
 
+// Blocks are handed to the 8 XCDs in turn (block b runs on XCD b % 8) and each XCD
+// has its own L2.  This renumbering gives every XCD one contiguous run of tiles in
+// column-tile-fastest order, so that the tiles sharing a row panel of A (and the
+// panels of one batch entry) meet in the same L2 instead of being fetched by all
+// eight.
+struct tile_id {
+    int x, y, z;
+};
+__device__ __forceinline__ tile_id xcd_tile() {
+    const int gx = gridDim.x, gy = gridDim.y, gz = gridDim.z;
+    const int total = gx * gy * gz;
+    const int b = blockIdx.x + gx * (blockIdx.y + gy * blockIdx.z);
+    const int per = total / 8;
+    const int v = b < per * 8 ? (b % 8) * per + b / 8 : b;
+    tile_id t;
+    t.x = v % gx;
+    t.y = (v / gx) % gy;
+    t.z = v / (gx * gy);
+    return t;
+}
+
 // C[M x N] = A * B (+ epilogue), batched over blockIdx.z.
 //   A_KMAJOR: A is stored [K][M] (element (m,k) at A[k*lda + m]); else [M][K].
 //   B is stored [K][N].  C is stored [M][N].
@@ -70,10 +91,11 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(
     const int wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lhi = lane >> 5;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-    A += (int64_t)blockIdx.z * strideA;
-    B += (int64_t)blockIdx.z * strideB;
-    C += (int64_t)blockIdx.z * strideC;
+    const tile_id tile = xcd_tile();
+    const int m0 = tile.y * BM, n0 = tile.x * BN;
+    A += (int64_t)tile.z * strideA;
+    B += (int64_t)tile.z * strideB;
+    C += (int64_t)tile.z * strideC;
 
     v16f acc[2][2];
 #pragma unroll
@@ -205,6 +227,119 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(
             } else {
                 if (gn < N) out[0] = v0;
                 if (gn + 1 < N) out[1] = v1;
+            }
+        }
+    }
+}
+
+// Variant for outputs whose row count suits tiles of 112 better than tiles of 128
+// (784 = 7 * 112): C[M x N] = A^T-stored-k-major * B, A at A[k*lda + m], batched
+// over blockIdx.z.  v_mfma_f32_16x16x4_f32; a block of 4 waves computes a
+// 112 x 128 tile, wave w the 112 x 32 slab of columns 32w.., as 7 x 2 MFMA blocks.
+// Lane l feeds element (row or column l % 16, depth l / 16) of each operand block
+// and holds rows 4*(l/16)..+3 of column l % 16 of each result block.
+constexpr int TM = 112, TN = 128, TK = 8, LDA = TM + 4, LDB = TN + 4;
+typedef float v4acc __attribute__((ext_vector_type(4)));
+
+// 8-deep k tiles and one float4 of each operand per thread and stage keep the kernel
+// under 100 registers and 16 KiB of LDS, so five blocks fit a CU: 1280 slots for the
+// 1120 tiles of the 20 x 784 x 1024 backward product, which then run as one resident set
+// instead of a full round plus a mostly empty one.
+__global__ __launch_bounds__(256, 5) void mlp_gemm112_kernel(
+    const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C, int M, int N,
+    int K, int64_t lda, int64_t ldb, int64_t ldc, int64_t strideA, int64_t strideB,
+    int64_t strideC, int a_vec_ok, int b_vec_ok) {
+    __shared__ float As[2][TK][LDA];
+    __shared__ float Bs[2][TK][LDB];
+    const int t = threadIdx.x;
+    const int lane = t & 63;
+    const int wave = t >> 6;
+    const int l16 = lane & 15, kq = lane >> 4;
+    const tile_id tile = xcd_tile();
+    const int m0 = tile.y * TM, n0 = tile.x * TN;
+    A += (int64_t)tile.z * strideA;
+    B += (int64_t)tile.z * strideB;
+    C += (int64_t)tile.z * strideC;
+
+    v4acc acc[7][2];
+#pragma unroll
+    for (int i = 0; i < 7; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = (v4acc)(0.0f);
+
+    const bool a_inside = a_vec_ok && (m0 + TM <= M);
+    const bool b_inside = b_vec_ok && (n0 + TN <= N);
+    // A tile: 8 x 112 floats = 224 float4 (threads 0..223); B tile: 8 x 128 = 256 float4
+    const int ak = t / (TM / 4), am4 = (t % (TM / 4)) * 4;
+    const int bk = t >> 5, bn4 = (t & 31) * 4;
+    auto gload = [&](int k0, v4f& ra, v4f& rb) {
+        const bool k_inside = k0 + TK <= K;
+        ra = (v4f)(0.0f);
+        if (t < TK * (TM / 4)) {
+            const int gk = k0 + ak, gm = m0 + am4;
+            const float* p = A + (int64_t)gk * lda + gm;
+            if (a_inside && k_inside)
+                ra = *reinterpret_cast<const v4f*>(p);
+            else if (gk < K)
+                ra = load4(p, (int64_t)M - gm, a_vec_ok);
+        }
+        const int gk = k0 + bk, gn = n0 + bn4;
+        const float* q = B + (int64_t)gk * ldb + gn;
+        if (b_inside && k_inside)
+            rb = *reinterpret_cast<const v4f*>(q);
+        else
+            rb = (gk < K) ? load4(q, (int64_t)N - gn, b_vec_ok) : (v4f)(0.0f);
+    };
+    auto sstore = [&](int buf, const v4f& ra, const v4f& rb) {
+        if (t < TK * (TM / 4)) *reinterpret_cast<v4f*>(&As[buf][ak][am4]) = ra;
+        *reinterpret_cast<v4f*>(&Bs[buf][bk][bn4]) = rb;
+    };
+    auto compute = [&](int buf) {
+#pragma unroll
+        for (int ks = 0; ks < TK / 4; ++ks) {
+            const int k = 4 * ks + kq;
+            const float b0 = Bs[buf][k][wave * 32 + l16];
+            const float b1 = Bs[buf][k][wave * 32 + 16 + l16];
+#pragma unroll
+            for (int bm = 0; bm < 7; ++bm) {
+                const float a = As[buf][k][bm * 16 + l16];
+                acc[bm][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b0, acc[bm][0], 0, 0, 0);
+                acc[bm][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b1, acc[bm][1], 0, 0, 0);
+            }
+        }
+    };
+
+    // two k tiles deep, as in mlp_gemm_kernel
+    const int nk = (K + TK - 1) / TK;
+    v4f pa, pb, qa, qb;
+    gload(0, pa, pb);
+    sstore(0, pa, pb);
+    if (nk > 1) gload(TK, qa, qb);
+    __syncthreads();
+    const int npairs = (nk + 1) / 2;
+    for (int pr = 0; pr < npairs; ++pr) {
+        const int kt = 2 * pr;
+        if (kt + 2 < nk) gload((kt + 2) * TK, pa, pb);
+        compute(0);
+        if (kt + 1 < nk) sstore(1, qa, qb);
+        __syncthreads();
+        if (kt + 3 < nk) gload((kt + 3) * TK, qa, qb);
+        if (kt + 1 < nk) compute(1);
+        if (kt + 2 < nk) sstore(0, pa, pb);
+        __syncthreads();
+    }
+
+    // result block: register r of lane l is element (row 4*(l/16) + r, column l % 16)
+#pragma unroll
+    for (int bn = 0; bn < 2; ++bn) {
+        const int gn = n0 + wave * 32 + bn * 16 + l16;
+        if (gn >= N) continue;
+#pragma unroll
+        for (int bm = 0; bm < 7; ++bm) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int gm = m0 + bm * 16 + 4 * kq + r;
+                if (gm < M) C[(int64_t)gm * ldc + gn] = acc[bm][bn][r];
             }
         }
     }
@@ -537,11 +672,21 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
         NGC_HIP(ctx, hipGetLastError());
     }
     {   // 3. dW1_j = X_j^T dZ1_j, one batch entry per partition, straight into G[j]
-        dim3 grid((unsigned)((hid + BN - 1) / BN), (unsigned)((din + BM - 1) / BM), (unsigned)k);
-        hipLaunchKernelGGL((mlp_gemm_kernel<true, EPI_STORE>), grid, dim3(256), 0, ctx->stream, X, (const float*)H, G,
-                           (const float*)nullptr, din, hid, (int)rows, (int64_t)din, (int64_t)hid, (int64_t)hid,
-                           rows * (int64_t)din, rows * (int64_t)hid, d, (int)(din % 4 == 0 && al(X, 16)),
-                           (int)(hid % 4 == 0), (int)(hid % 2 == 0 && d % 2 == 0 && al(G, 8)));
+        const int a_ok = (int)(din % 4 == 0 && al(X, 16)), b_ok = (int)(hid % 4 == 0);
+        // tiles of 112 rows when they pad the d_in rows less than tiles of 128 (784 = 7 * 112)
+        const int64_t pad128 = (int64_t)((din + BM - 1) / BM) * BM, pad112 = (int64_t)((din + TM - 1) / TM) * TM;
+        if (pad112 < pad128) {
+            dim3 grid((unsigned)((hid + TN - 1) / TN), (unsigned)((din + TM - 1) / TM), (unsigned)k);
+            hipLaunchKernelGGL(mlp_gemm112_kernel, grid, dim3(256), 0, ctx->stream, X, (const float*)H, G, din, hid,
+                               (int)rows, (int64_t)din, (int64_t)hid, (int64_t)hid, rows * (int64_t)din,
+                               rows * (int64_t)hid, d, a_ok, b_ok);
+        } else {
+            dim3 grid((unsigned)((hid + BN - 1) / BN), (unsigned)((din + BM - 1) / BM), (unsigned)k);
+            hipLaunchKernelGGL((mlp_gemm_kernel<true, EPI_STORE>), grid, dim3(256), 0, ctx->stream, X, (const float*)H, G,
+                               (const float*)nullptr, din, hid, (int)rows, (int64_t)din, (int64_t)hid, (int64_t)hid,
+                               rows * (int64_t)din, rows * (int64_t)hid, d, a_ok, b_ok,
+                               (int)(hid % 2 == 0 && d % 2 == 0 && al(G, 8)));
+        }
         NGC_HIP(ctx, hipGetLastError());
     }
     return NGC_OK;

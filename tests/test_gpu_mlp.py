@@ -113,6 +113,8 @@ def check_blocks(w, X, Y, th, G, G_o):
     (2, 300, 784, 1024, 10),     # the real layer sizes, few rows
     (1, 257, 33, 1000, 16),
     (2, 5, 784, 1024, 10),       # fewer rows than one K tile
+    (2, 40, 256, 64, 5),         # d_in a multiple of 128: backward GEMM on 128-row tiles
+    (1, 70, 300, 260, 7),        # both tile shapes ragged in every dimension
 ])
 def test_mlp_partition_gradients_match_oracle(ngc, n, rows, d_in, hidden, classes):
     import torch
