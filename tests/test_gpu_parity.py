@@ -545,3 +545,61 @@ def test_fused_iteration_equals_separate_calls(ngc, torch_dev, base, n, c, rows,
         assert torch.equal(before, bufs[1][3])                      # theta untouched
     finally:
         ngc.ngc_destroy(ctx)
+
+
+# --------------------------------------------------------------------------------------------
+# C2 at full size: logistic regression, n = 16, 16 x 8192 rows, d = 1024, layers 0,1,3,7,
+# 200 descent iterations with Bernoulli(0.2) stragglers, through ngc_iteration
+# --------------------------------------------------------------------------------------------
+def test_c2_full_size_200_iterations(ngc, torch_dev):
+    torch = torch_dev
+    dev = torch.device("cuda:0")
+    w = wl.C2
+    X, Y = wl.dataset(w, 0, threads=8)
+    th0 = wl.theta(w, 0, scale=0.01)
+    masks = wl.bernoulli_masks(w, 200, seed=0)
+    p = Pipeline(ngc, torch, w)
+    try:
+        Xd, Yd, thd = p.to_dev(X), p.to_dev(Y), p.to_dev(th0)
+        eta = 1.0
+        usage = np.zeros(len(w.layers) + 1, int)
+        checked = 0
+        loss0 = gradients.logistic_loss(X.reshape(-1, w.d), Y.reshape(-1), th0)
+        for t in range(200):
+            check = t < 3 or t % 10 == 0 or t == 199
+            th_t = thd.cpu().numpy() if check else None
+            try:
+                u, a = ngc.ngc_iteration(p.ctx, w.loss, Xd, Yd, thd, w.rows, masks[t], eta / w.m,
+                                         p.G, p.C, p.g, w.n)
+            except ngc.NgcError as e:
+                assert e.code == ngc.NGC_ERR_UNDECODABLE and masks[t].sum() > w.layers[-1]
+                usage[-1] += 1                                    # theta stays as it is this round
+                continue
+            usage[u] += 1
+            assert u == coding.select_layer(w.layers, masks[t])
+            if check:
+                ngc.ngc_sync(p.ctx)
+                G_o = gradients.partial_gradients(w.loss, X, Y, th_t)
+                u_o, a_o, g_o = coding.coded_gradient(p.Bs, w.layers, G_o, masks[t])
+                assert np.array_equal(a != 0, a_o != 0)
+                # near a stationary point the gradient is a difference of large terms: floor the
+                # denominator at 1e-3 of the size it would have without cancellation
+                Xf = X.reshape(-1, w.d).astype(np.float64)
+                z = Y.reshape(-1) * (Xf @ th_t.astype(np.float64))
+                slope = 1.0 / (1.0 + np.exp(z))
+                floor = 1e-3 * np.sqrt(np.sum(slope ** 2 * np.sum(Xf ** 2, axis=1)))
+                err = np.linalg.norm(p.g.cpu().numpy() - g_o) / max(np.linalg.norm(g_o), floor)
+                assert err <= TOL, (t, err)
+                assert rel(p.G.cpu().numpy(), G_o) <= TOL
+                assert rel(thd.cpu().numpy(), gradients.gd_update(th_t, g_o, eta, w.m)) <= 1e-6
+                checked += 1
+        assert checked >= 20
+        loss1 = gradients.logistic_loss(X.reshape(-1, w.d), Y.reshape(-1), thd.cpu().numpy())
+        assert loss1 < 0.5 * loss0                                # the run actually descends
+        share = usage / 200.0
+        print("C2: layer usage %s, undecodable %d of 200, loss %.4g -> %.4g" %
+              (np.round(share[:-1], 3), usage[-1], loss0, loss1))
+        # expected shares 2.8 / 11.3 / 45.7 / 39.5 % and 0.7 % undecodable
+        assert share[2] + share[3] > 0.7 and usage[-1] <= 6
+    finally:
+        p.close()
