@@ -270,8 +270,7 @@ __global__ __launch_bounds__(ENC_WAVES * 64) void encode_kernel(const float* __r
                                                      const int* __restrict__ rowptr,
                                                      const int* __restrict__ col,
                                                      const float* __restrict__ coef, int n,
-                                                     int64_t d, int pair_begin, int pair_end,
-                                                     int pairs_per_group) {
+                                                     int64_t d, int pair_begin, int pair_end) {
     // n here: rows of G (the k partitions)
     extern __shared__ float tile_raw[];
     VT* tile = reinterpret_cast<VT*>(tile_raw);  // [k][64]
@@ -297,7 +296,6 @@ __global__ __launch_bounds__(ENC_WAVES * 64) void encode_kernel(const float* __r
     __syncthreads();
     // pairs are dealt to the blocks of a column tile and to their waves in turn, so that
     // every wave gets rows of every layer (layers differ in row weight by up to s_max+1)
-    (void)pairs_per_group;
     const int stride = (int)gridDim.y * ENC_WAVES;
     for (int p = pair_begin + (int)blockIdx.y * ENC_WAVES + wave; p < pair_end; p += stride) {
         const int b = rowptr[p], e = rowptr[p + 1];
@@ -677,13 +675,24 @@ void ngc_dev_release(ngc_ctx* ctx) {
     for (auto e : ctx->event_pool) (void)hipEventDestroy(e);
     if (ctx->d_code) (void)hipFree(ctx->d_code);
     if (ctx->d_ws) (void)hipFree(ctx->d_ws);
-    if (ctx->d_units) (void)hipFree(ctx->d_units);
+    for (int q = 0; q < 2; ++q) {
+        if (ctx->d_maps[q]) (void)hipFree(ctx->d_maps[q]);
+        if (ctx->h_maps[q]) (void)hipHostFree(ctx->h_maps[q]);
+        if (ctx->maps_ev[q]) (void)hipEventDestroy(ctx->maps_ev[q]);
+        ctx->d_maps[q] = ctx->h_maps[q] = nullptr;
+        ctx->maps_ev[q] = nullptr;
+        ctx->maps_ev_set[q] = false;
+    }
+    ctx->maps_cap = 0;
+    if (ctx->d_wtab) (void)hipFree(ctx->d_wtab);
+    ctx->d_wtab = nullptr;
+    ctx->d_wtab_bytes = 0;
+    ctx->wtab_dirty = true;
     for (auto& lc : ctx->code) {
         if (lc.d_A) (void)hipFree(lc.d_A);
         lc.d_A = nullptr;
         lc.A_stale = true;
     }
-    ctx->d_units = nullptr;
     ctx->d_code = nullptr;
     ctx->d_ws = nullptr;
     ctx->dev_ready = false;
@@ -1010,7 +1019,6 @@ extern "C" int ngc_encode(ngc_ctx* ctx, const float* G_dev, int layer, float* C_
     // enough blocks for about three per CU; the pairs are dealt to blocks and waves in turn
     int64_t gy = std::max<int64_t>(1, (3 * (int64_t)ctx->cu_count + gx - 1) / gx);
     gy = std::min<int64_t>(gy, (pairs + ENC_WAVES - 1) / ENC_WAVES);
-    const int ppg = 0;  // pairs are dealt to blocks and waves in turn
     if (gx > 0x7fffffffLL) return ngc_fail(ctx, NGC_ERR_INVALID, "d too large");
     dim3 grid((unsigned)gx, (unsigned)gy);
     const size_t lds = (size_t)ctx->k * 64 * V * sizeof(float);  // all k rows of G, 64*V columns
@@ -1018,13 +1026,13 @@ extern "C" int ngc_encode(ngc_ctx* ctx, const float* G_dev, int layer, float* C_
         prof_scope ps(ctx, NGC_KERNEL_ENCODE);
         if (V == 4)
             hipLaunchKernelGGL((encode_kernel<v4f, 4>), grid, dim3(ENC_WAVES * 64), lds, ctx->stream, G_dev, C_dev,
-                               rowptr, col, coef, ctx->k, d, pb, pe, ppg);
+                               rowptr, col, coef, ctx->k, d, pb, pe);
         else if (V == 2)
             hipLaunchKernelGGL((encode_kernel<v2f, 2>), grid, dim3(ENC_WAVES * 64), lds, ctx->stream, G_dev, C_dev,
-                               rowptr, col, coef, ctx->k, d, pb, pe, ppg);
+                               rowptr, col, coef, ctx->k, d, pb, pe);
         else
             hipLaunchKernelGGL((encode_kernel<float, 1>), grid, dim3(ENC_WAVES * 64), lds, ctx->stream, G_dev, C_dev,
-                               rowptr, col, coef, ctx->k, d, pb, pe, ppg);
+                               rowptr, col, coef, ctx->k, d, pb, pe);
     }
     NGC_HIP(ctx, hipGetLastError());
     return NGC_OK;
@@ -1121,21 +1129,30 @@ extern "C" int ngc_probe_read(ngc_ctx* ctx, const void* src_dev, int64_t bytes) 
 }
 
 // ---- redundancy-faithful worker execution ------------------------------------------------------
-static int ensure_units(ngc_ctx* ctx, size_t bytes) {
-    if (bytes <= ctx->d_units_bytes) return NGC_OK;
-    if (ctx->d_units) {
-        NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
-        NGC_HIP(ctx, hipFree(ctx->d_units));
-        ctx->d_units = nullptr;
-        ctx->d_units_bytes = 0;
+// room for `ints` map entries in both copies (device + pinned host staging)
+static int ensure_maps(ngc_ctx* ctx, size_t ints) {
+    if (ints <= ctx->maps_cap) return NGC_OK;
+    NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    for (int q = 0; q < 2; ++q) {
+        if (ctx->d_maps[q]) NGC_HIP(ctx, hipFree(ctx->d_maps[q]));
+        if (ctx->h_maps[q]) NGC_HIP(ctx, hipHostFree(ctx->h_maps[q]));
+        ctx->d_maps[q] = ctx->h_maps[q] = nullptr;
+        ctx->maps_ev_set[q] = false;
     }
-    void* p = nullptr;
-    if (hipMalloc(&p, bytes) != hipSuccess) {
-        (void)hipGetLastError();
-        return ngc_fail(ctx, NGC_ERR_NOMEM, "table allocation failed");
+    ctx->maps_cap = 0;
+    for (int q = 0; q < 2; ++q) {
+        void* dp = nullptr;
+        void* hp = nullptr;
+        if (hipMalloc(&dp, ints * sizeof(int)) != hipSuccess || hipHostMalloc(&hp, ints * sizeof(int)) != hipSuccess) {
+            (void)hipGetLastError();
+            if (dp) (void)hipFree(dp);
+            return ngc_fail(ctx, NGC_ERR_NOMEM, "map allocation failed");
+        }
+        ctx->d_maps[q] = (int*)dp;
+        ctx->h_maps[q] = (int*)hp;
+        if (!ctx->maps_ev[q]) NGC_HIP(ctx, hipEventCreateWithFlags(&ctx->maps_ev[q], hipEventDisableTiming));
     }
-    ctx->d_units = (int*)p;
-    ctx->d_units_bytes = bytes;
+    ctx->maps_cap = ints;
     return NGC_OK;
 }
 
@@ -1155,7 +1172,6 @@ extern "C" int ngc_worker_grads(ngc_ctx* ctx, int loss, const float* X_dev, cons
     rc = ngc_make_worker_plan(ctx, plan);
     if (rc) return rc;
     const int n = ctx->n, Tp = plan.T * ctx->c;  // partitions per worker schedule
-    std::vector<int> maps;  // unit_part | unit_row
     std::vector<int> part, row;
     for (int i = 0; i < n; ++i) {
         if (progress_host[i] < 0) return ngc_fail(ctx, NGC_ERR_INVALID, "negative progress");
@@ -1168,15 +1184,19 @@ extern "C" int ngc_worker_grads(ngc_ctx* ctx, int loss, const float* X_dev, cons
     }
     const int units = (int)part.size();
     if (units == 0) return NGC_OK;
-    maps = part;
-    maps.insert(maps.end(), row.begin(), row.end());
-    rc = ensure_units(ctx, maps.size() * sizeof(int));
+    rc = ensure_maps(ctx, (size_t)2 * n * Tp);
     if (rc) return rc;
-    // the maps of an earlier call may still be in use by its kernels
-    NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    NGC_HIP(ctx, hipMemcpy(ctx->d_units, maps.data(), maps.size() * sizeof(int), hipMemcpyHostToDevice));
-    return grads_impl(ctx, loss, X_dev, y_dev, theta_dev, rows, W_dev, units, ctx->d_units,
-                      ctx->d_units + units);
+    // maps: unit_part | unit_row.  The copy used two calls ago is free once its kernels are done.
+    const int q = ctx->maps_turn ^= 1;
+    if (ctx->maps_ev_set[q]) NGC_HIP(ctx, hipEventSynchronize(ctx->maps_ev[q]));
+    std::memcpy(ctx->h_maps[q], part.data(), sizeof(int) * units);
+    std::memcpy(ctx->h_maps[q] + units, row.data(), sizeof(int) * units);
+    NGC_HIP(ctx, hipMemcpyAsync(ctx->d_maps[q], ctx->h_maps[q], sizeof(int) * 2 * units, hipMemcpyHostToDevice,
+                                ctx->stream));
+    rc = grads_impl(ctx, loss, X_dev, y_dev, theta_dev, rows, W_dev, units, ctx->d_maps[q], ctx->d_maps[q] + units);
+    NGC_HIP(ctx, hipEventRecord(ctx->maps_ev[q], ctx->stream));
+    ctx->maps_ev_set[q] = true;
+    return rc;
 }
 
 extern "C" int ngc_worker_encode(ngc_ctx* ctx, const float* W_dev, const int* progress_host,
@@ -1191,28 +1211,41 @@ extern "C" int ngc_worker_encode(ngc_ctx* ctx, const float* W_dev, const int* pr
     if (rc) return rc;
     const int n = ctx->n, L = ctx->L, T = plan.T * ctx->c;  // T: partitions per worker schedule
     const int64_t d = ctx->d;
-    // tables: int needed[L*n] (atomic tasks) | float wcoef[L*n*T]
-    std::vector<int> tab((size_t)L * n + (size_t)L * n * T, 0);
-    float* wcoef = reinterpret_cast<float*>(tab.data() + (size_t)L * n);
-    for (int u = 0; u < L; ++u)
-        for (int i = 0; i < n; ++i) {
-            tab[(size_t)u * n + i] = plan.needed[(size_t)u * n + i];
-            for (size_t t = 0; t < plan.order[i].size(); ++t)
-                wcoef[((size_t)u * n + i) * T + t] = (float)ctx->code[u].B[(size_t)i * ctx->k + plan.order[i][t]];
-        }
     worker_progress prog;
     for (int i = 0; i < NGC_MAX_N; ++i) prog.done[i] = 0;
     for (int i = 0; i < n; ++i) {
         if (progress_host[i] < 0) return ngc_fail(ctx, NGC_ERR_INVALID, "negative progress");
         prog.done[i] = (unsigned char)std::min<int>(progress_host[i], 255);
     }
-    // the gradient maps share the buffer: tables go behind them
-    const size_t off = ((size_t)2 * n * T + 63) / 64 * 64;  // behind the largest possible gradient maps
-    rc = ensure_units(ctx, (off + tab.size()) * sizeof(int));
-    if (rc) return rc;
-    NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    NGC_HIP(ctx, hipMemcpy(ctx->d_units + off, tab.data(), tab.size() * sizeof(int), hipMemcpyHostToDevice));
-    const int* needed = ctx->d_units + off;
+    // tables: int needed[L*n] (atomic tasks) | float wcoef[L*n*T]; they depend on the code only
+    if (ctx->wtab_dirty || !ctx->d_wtab || ctx->wtab_T != T) {
+        std::vector<int> tab((size_t)L * n + (size_t)L * n * T, 0);
+        float* wcoef = reinterpret_cast<float*>(tab.data() + (size_t)L * n);
+        for (int u = 0; u < L; ++u)
+            for (int i = 0; i < n; ++i) {
+                tab[(size_t)u * n + i] = plan.needed[(size_t)u * n + i];
+                for (size_t t = 0; t < plan.order[i].size(); ++t)
+                    wcoef[((size_t)u * n + i) * T + t] =
+                        (float)ctx->code[u].B[(size_t)i * ctx->k + plan.order[i][t]];
+            }
+        NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        if (tab.size() * sizeof(int) > ctx->d_wtab_bytes) {
+            if (ctx->d_wtab) NGC_HIP(ctx, hipFree(ctx->d_wtab));
+            ctx->d_wtab = nullptr;
+            ctx->d_wtab_bytes = 0;
+            void* p = nullptr;
+            if (hipMalloc(&p, tab.size() * sizeof(int)) != hipSuccess) {
+                (void)hipGetLastError();
+                return ngc_fail(ctx, NGC_ERR_NOMEM, "table allocation failed");
+            }
+            ctx->d_wtab = (int*)p;
+            ctx->d_wtab_bytes = tab.size() * sizeof(int);
+        }
+        NGC_HIP(ctx, hipMemcpy(ctx->d_wtab, tab.data(), tab.size() * sizeof(int), hipMemcpyHostToDevice));
+        ctx->wtab_dirty = false;
+        ctx->wtab_T = T;
+    }
+    const int* needed = ctx->d_wtab;
     const float* wc = reinterpret_cast<const float*>(needed + (size_t)L * n);
     const int V = vec_width(d, W_dev, C_dev);
     dim3 grid((unsigned)((d + 64 * V - 1) / (64 * V)), (unsigned)n);

@@ -53,6 +53,7 @@ static void install_layer(ngc_ctx* ctx, int layer, const double* B) {
     compress_layer(lc, ctx->n, ctx->k);
     lc.set = true;
     ctx->code_dirty = true;
+    ctx->wtab_dirty = true;
 }
 
 extern "C" int ngc_create(ngc_ctx** out, int n, int k, int L, const int* s, int64_t d,

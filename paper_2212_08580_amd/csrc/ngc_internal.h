@@ -56,8 +56,18 @@ struct ngc_ctx {
     size_t code_nnz = 0;             // non-zeros over all layers in d_code
     float* d_ws = nullptr;           // workspace: block partials / residuals / MLP activations
     size_t d_ws_bytes = 0;
-    int* d_units = nullptr;          // unit -> partition / output row maps, worker tables
-    size_t d_units_bytes = 0;
+    // worker mode: unit -> partition / output-row maps, two copies used in turn so that a call
+    // can fill one while the kernels of the previous call still read the other
+    int* d_maps[2] = {nullptr, nullptr};
+    int* h_maps[2] = {nullptr, nullptr};  // pinned staging
+    size_t maps_cap = 0;                  // ints per copy
+    hipEvent_t maps_ev[2] = {nullptr, nullptr};
+    bool maps_ev_set[2] = {false, false};
+    int maps_turn = 0;
+    int* d_wtab = nullptr;                // worker-encode tables, rebuilt when a code changes
+    size_t d_wtab_bytes = 0;
+    bool wtab_dirty = true;
+    int wtab_T = 0;
 
     unsigned profile_mask = 0;       // bit k: time launches of kernel id k
     std::vector<ngc_profile_rec> prof;
