@@ -29,7 +29,7 @@ def test_cyclic_nested_code_satisfies_def1_and_def2(n, layers):
     for B, sigma in zip(Bs, layers):
         supp = [set(np.flatnonzero(B[i])) for i in range(n)]
         for i in range(n):
-            assert supp[i] == set(codes.cyclic_support(n, sigma, i))   # Lemma 2, size sigma+1
+            assert supp[i] == {(i + t) % n for t in range(sigma + 1)}   # Lemma 2: i and its sigma successors
             assert len(supp[i]) == sigma + 1                           # load (k/n)(sigma+1)
             if prev is not None:
                 assert prev[i] <= supp[i]                              # Def. 2 nesting
