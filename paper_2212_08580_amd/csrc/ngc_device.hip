@@ -72,42 +72,54 @@ __device__ __forceinline__ float loss_slope(float z, float y) {
 // Each block writes one partial sum per partition run; K2 adds them in a fixed
 // order.
 // ---------------------------------------------------------------------------
-template <int NV, int R>
+template <int NV, int R, typename VT>
 struct row_group {
-    v4f x[R][NV];
+    VT x[R][NV];
     float y;  // lane l < R holds the label of row l of the group
 };
 
-template <int NV, int R, int DV>
-__device__ __forceinline__ void load_group(row_group<NV, R>& b, const char* __restrict__ xbase,
+// The lane's i-th element (a float4, or a float when rows are not 16-byte
+// aligned) sits lane_off + i*64 elements into the row, `pitch` is the row length
+// in bytes.  For the exact shapes lane_off counts from the wave's slice and the
+// rest are compile-time constants; for ragged rows (RAGGED) lane_off counts
+// from the row's start and offsets past `last_off`, the row's last element,
+// are clamped to it.
+template <int NV, int R, int DV, bool RAGGED, typename VT>
+__device__ __forceinline__ void load_group(row_group<NV, R, VT>& b, const char* __restrict__ xbase,
                                            const float* __restrict__ yp, uint32_t lane_off,
-                                           int lane, int64_t row, int64_t last_row) {
+                                           uint32_t last_off, int64_t pitch, int lane,
+                                           int64_t row, int64_t last_row) {
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
         int64_t r = row + rr;
         r = r < last_row ? r : last_row;  // past the end: re-read the last row; its weight is 0
-        const char* p = xbase + r * (int64_t)(DV * 16);  // wave-uniform
+        const char* p = xbase + r * (RAGGED ? pitch : (int64_t)(DV * sizeof(VT)));  // wave-uniform
 #pragma unroll
-        for (int i = 0; i < NV; ++i)
-            b.x[rr][i] = __builtin_nontemporal_load(
-                reinterpret_cast<const v4f*>(p + lane_off + i * 1024));
+        for (int i = 0; i < NV; ++i) {
+            uint32_t o = lane_off + i * 64 * (int)sizeof(VT);
+            if (RAGGED) o = o < last_off ? o : last_off;
+            b.x[rr][i] = __builtin_nontemporal_load(reinterpret_cast<const VT*>(p + o));
+        }
     }
     int64_t ry = row + (lane < R ? lane : R - 1);
     ry = ry < last_row ? ry : last_row;
     b.y = yp[ry];
 }
 
-template <int NV, int R, int WAVES, int LOSS>
-__device__ __forceinline__ void consume_group(const row_group<NV, R>& b, v4f (&acc)[NV],
-                                              const v4f (&th)[NV], float* ex, int wave,
-                                              int64_t row, int64_t end_row) {
+__device__ __forceinline__ float hsum(float q) { return q; }
+__device__ __forceinline__ float hsum(v4f q) { return (q.x + q.y) + (q.z + q.w); }
+
+template <int NV, int R, int WAVES, int LOSS, typename VT>
+__device__ __forceinline__ void consume_group(const row_group<NV, R, VT>& b, VT (&acc)[NV],
+                                              const VT (&th)[NV], float* ex, int wave,
+                                              int lane, int64_t row, int64_t end_row) {
     float dot[R];
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
-        v4f q = b.x[rr][0] * th[0];
+        VT q = b.x[rr][0] * th[0];
 #pragma unroll
         for (int i = 1; i < NV; ++i) q += b.x[rr][i] * th[i];
-        dot[rr] = wave_sum((q.x + q.y) + (q.z + q.w));
+        dot[rr] = wave_sum(hsum(q));
     }
     if (WAVES > 1) {
         // ex[rr*WAVES + w]: every lane of wave w stores the same value
@@ -122,22 +134,47 @@ __device__ __forceinline__ void consume_group(const row_group<NV, R>& b, v4f (&a
             dot[rr] = z;
         }
     }
-    const int yi = __builtin_bit_cast(int, b.y);
+    if (LOSS == NGC_LOSS_LSQ) {
+        const int yi = __builtin_bit_cast(int, b.y);
 #pragma unroll
-    for (int rr = 0; rr < R; ++rr) {
-        float yv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(yi, rr));
-        float res = (row + rr < end_row) ? loss_slope<LOSS>(dot[rr], yv) : 0.0f;
+        for (int rr = 0; rr < R; ++rr) {
+            float yv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(yi, rr));
+            float res = (row + rr < end_row) ? loss_slope<LOSS>(dot[rr], yv) : 0.0f;
 #pragma unroll
-        for (int i = 0; i < NV; ++i) acc[i] += res * b.x[rr][i];
+            for (int i = 0; i < NV; ++i) acc[i] += res * b.x[rr][i];
+        }
+    } else {
+        // The slope costs an exponential and a division.  The R margins of the
+        // group are wave-uniform, so lane l takes the margin of row l (its label is
+        // already there) and the slopes of all R rows come out of one pass; each is
+        // then broadcast from its lane.  Rows past the end get weight 0 as a factor
+        // (the re-read row's slope is finite), which keeps the loop body free of
+        // branches.
+        float zv = 0.0f;
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) zv = (lane == rr) ? dot[rr] : zv;
+        const float live = (row + lane < end_row) ? 1.0f : 0.0f;
+        const int sv = __builtin_bit_cast(int, loss_slope<LOSS>(zv, b.y) * live);
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) {
+            float res = __builtin_bit_cast(float, __builtin_amdgcn_readlane(sv, rr));
+#pragma unroll
+            for (int i = 0; i < NV; ++i) acc[i] += res * b.x[rr][i];
+        }
     }
 }
 
-template <int NV, int R, int NBUF, int WAVES, int LOSS>
+template <int NV, int R, int NBUF, int WAVES, int LOSS, bool RAGGED, typename VT>
 __global__ __launch_bounds__(WAVES * 64) void grad_stream_kernel(
     const float* __restrict__ X, const float* __restrict__ y, const float* __restrict__ theta,
     float* __restrict__ partial, int64_t rows, int chunks, int64_t rows_per_chunk,
-    const int* __restrict__ unit_part) {
-    constexpr int DV = WAVES * 64 * NV;  // float4 per row
+    const int* __restrict__ unit_part, int dq) {
+    // elements (VT: float4, or float for rows that are not 16-byte aligned) per
+    // row: the block's WAVES*64*NV slots for the exact shapes; for ragged rows the
+    // true count dq (<= the slots), slots past it are idle: they re-read the
+    // row's last element against a zero of theta and store nothing
+    constexpr int SLOTS = WAVES * 64 * NV;
+    const int64_t dv = RAGGED ? dq : SLOTS;
     __shared__ float ex_s[2][R * WAVES];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -149,15 +186,22 @@ __global__ __launch_bounds__(WAVES * 64) void grad_stream_kernel(
     const int64_t r0 = (int64_t)c * rows_per_chunk;
     const int64_t r1 = rows < r0 + rows_per_chunk ? rows : r0 + rows_per_chunk;
     const char* xbase = reinterpret_cast<const char*>(X) +
-                        ((int64_t)j * rows * DV + (int64_t)wave * 64 * NV) * 16;
+                        ((int64_t)j * rows * dv + (RAGGED ? 0 : (int64_t)wave * 64 * NV)) * (int64_t)sizeof(VT);
     const float* yp = y + (int64_t)j * rows;
-    const uint32_t lane_off = (uint32_t)lane * 16u;
+    const uint32_t lane_off =
+        (uint32_t)((RAGGED ? wave * 64 * NV : 0) + lane) * (uint32_t)sizeof(VT);
+    const uint32_t last_off = (uint32_t)(dv - 1) * (uint32_t)sizeof(VT);
+    const int64_t pitch = dv * (int64_t)sizeof(VT);
 
-    v4f th[NV], acc[NV];
+    VT th[NV], acc[NV];
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-        th[i] = reinterpret_cast<const v4f*>(theta)[wave * 64 * NV + i * 64 + lane];
-        acc[i] = (v4f)(0.0f);
+        const int slot = wave * 64 * NV + i * 64 + lane;
+        if (RAGGED)
+            th[i] = slot < dq ? reinterpret_cast<const VT*>(theta)[slot] : (VT)(0.0f);
+        else
+            th[i] = reinterpret_cast<const VT*>(theta)[slot];
+        acc[i] = (VT)(0.0f);
     }
 
     // Groups are taken NBUF at a time with no branch inside the loop, so that the
@@ -167,23 +211,27 @@ __global__ __launch_bounds__(WAVES * 64) void grad_stream_kernel(
     const int64_t ngroups = r0 < r1 ? (r1 - r0 + R - 1) / R : 0;  // block-uniform
     if (ngroups > 0) {
         const int64_t last = r1 - 1;
-        row_group<NV, R> buf[NBUF];
+        row_group<NV, R, VT> buf[NBUF];
 #pragma unroll
         for (int p = 0; p < NBUF - 1; ++p)
-            load_group<NV, R, DV>(buf[p], xbase, yp, lane_off, lane, r0 + (int64_t)p * R, last);
+            load_group<NV, R, SLOTS, RAGGED, VT>(buf[p], xbase, yp, lane_off, last_off, pitch, lane,
+                                             r0 + (int64_t)p * R, last);
         for (int64_t gb = 0; gb < ngroups; gb += NBUF) {
 #pragma unroll
             for (int p = 0; p < NBUF; ++p) {
                 const int64_t gi = gb + p;
-                load_group<NV, R, DV>(buf[(p + NBUF - 1) % NBUF], xbase, yp, lane_off, lane,
-                                      r0 + (gi + NBUF - 1) * R, last);
-                consume_group<NV, R, WAVES, LOSS>(buf[p], acc, th, ex_s[gi & 1], wave, r0 + gi * R, r1);
+                load_group<NV, R, SLOTS, RAGGED, VT>(buf[(p + NBUF - 1) % NBUF], xbase, yp, lane_off,
+                                                     last_off, pitch, lane, r0 + (gi + NBUF - 1) * R, last);
+                consume_group<NV, R, WAVES, LOSS, VT>(buf[p], acc, th, ex_s[gi & 1], wave, lane, r0 + gi * R, r1);
             }
         }
     }
-    v4f* out = reinterpret_cast<v4f*>(partial) + (int64_t)blockIdx.x * DV + wave * 64 * NV + lane;
+    VT* out = reinterpret_cast<VT*>(partial) + (int64_t)blockIdx.x * dv;
 #pragma unroll
-    for (int i = 0; i < NV; ++i) out[i * 64] = acc[i];
+    for (int i = 0; i < NV; ++i) {
+        const int slot = wave * 64 * NV + i * 64 + lane;
+        if (!RAGGED || slot < dq) out[slot] = acc[i];
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -783,33 +831,54 @@ extern "C" int ngc_sync(ngc_ctx* ctx) {
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 // ---- partition gradients --------------------------------------------------
-template <int NV, int R, int NBUF, int WAVES>
+template <int NV, int R, int NBUF, int WAVES, bool RAGGED, typename VT = v4f>
 static void launch_stream(ngc_ctx* ctx, int loss, const float* X, const float* y,
                           const float* theta, float* partial, int k, int64_t rows, int chunks,
-                          int64_t rpc, const int* unit_part) {
+                          int64_t rpc, const int* unit_part, int dq) {
     dim3 grid((unsigned)(k * chunks));
     if (loss == NGC_LOSS_LSQ)
-        hipLaunchKernelGGL((grad_stream_kernel<NV, R, NBUF, WAVES, NGC_LOSS_LSQ>), grid, dim3(WAVES * 64), 0,
-                           ctx->stream, X, y, theta, partial, rows, chunks, rpc, unit_part);
+        hipLaunchKernelGGL((grad_stream_kernel<NV, R, NBUF, WAVES, NGC_LOSS_LSQ, RAGGED, VT>), grid,
+                           dim3(WAVES * 64), 0, ctx->stream, X, y, theta, partial, rows, chunks, rpc,
+                           unit_part, dq);
     else
-        hipLaunchKernelGGL((grad_stream_kernel<NV, R, NBUF, WAVES, NGC_LOSS_LOGISTIC>), grid, dim3(WAVES * 64),
-                           0, ctx->stream, X, y, theta, partial, rows, chunks, rpc, unit_part);
+        hipLaunchKernelGGL((grad_stream_kernel<NV, R, NBUF, WAVES, NGC_LOSS_LOGISTIC, RAGGED, VT>), grid,
+                           dim3(WAVES * 64), 0, ctx->stream, X, y, theta, partial, rows, chunks, rpc,
+                           unit_part, dq);
 }
 
-// Shape of the single-pass kernel for a given d, or waves = 0 if d has none.
+// Shape of the single-pass kernel for a given d, or waves = 0 if d has none
+// (above 16384, or above 8192 and not a multiple of 4).  A block offers
+// nv*waves*64 slots per row, each a float4, or a float (`scalar`) when d is not
+// a multiple of 4 and rows are therefore not 16-byte aligned; `ragged` when
+// the row has fewer elements than the block has slots.
 struct stream_shape {
     int nv, r, waves;
+    bool ragged, scalar;
 };
 static stream_shape pick_stream_shape(int64_t d) {
     if (d % 1024 == 0) {
         const int w = (int)(d / 1024);
-        if (w == 1 || w == 2 || w == 3 || w == 4 || w == 6 || w == 8) return {4, 4, w};
-        if (w == 12 || w == 16) return {8, 2, w / 2};
+        if (w == 3) return {3, 5, 4, false, false};  // four waves fill a CU's eight wave slots, three do not
+        if (w == 1 || w == 2 || w == 4 || w == 6 || w == 8) return {4, 4, w, false, false};
+        if (w == 12 || w == 16) return {8, 2, w / 2, false, false};
     }
-    if (d == 256) return {1, 16, 1};
-    if (d == 512) return {2, 8, 1};
-    if (d == 768) return {3, 4, 1};
-    return {0, 0, 0};
+    if (d == 256) return {1, 16, 1, false, false};
+    if (d == 512) return {2, 8, 1, false, false};
+    if (d == 768) return {3, 5, 1, false, false};
+    if (d < 1 || d > 16384) return {0, 0, 0, false, false};
+    if (d % 4 != 0) {
+        if (d <= 256) return {4, 16, 1, true, true};
+        if (d <= 4096) return {8, 8, (int)((d + 511) / 512), true, true};
+        if (d <= 8192) return {16, 3, (int)((d + 1023) / 1024), true, true};
+        return {0, 0, 0, false, false};
+    }
+    const int dq = (int)(d / 4);
+    if (dq <= 64) return {1, 16, 1, true, false};
+    if (dq <= 128) return {2, 8, 1, true, false};
+    if (dq <= 192) return {3, 5, 1, true, false};
+    if (dq > 512 && dq <= 768) return {3, 5, 4, true, false};
+    if (dq <= 2048) return {4, 4, (dq + 255) / 256, true, false};
+    return {8, 2, (dq + 511) / 512, true, false};
 }
 
 int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float* theta,
@@ -837,8 +906,12 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
     const stream_shape sh = pick_stream_shape(d);
     if (sh.waves) {
         // enough blocks to give every SIMD two waves, split evenly over the partitions
-        const int64_t block_slots = std::max<int64_t>(1, wave_slots / sh.waves);
-        int64_t chunks = std::max<int64_t>(1, (block_slots + k - 1) / k);
+        // a CU holds 8 such waves (2 per SIMD at up to 256 registers), so it takes
+        // 8 / waves whole blocks; more blocks than that would run as a second,
+        // partly filled round
+        const int per_cu = std::max(1, 8 / sh.waves);
+        const int64_t block_slots = (int64_t)ctx->cu_count * per_cu;
+        int64_t chunks = std::max<int64_t>(1, block_slots / k);
         int64_t rpc = (rows + chunks - 1) / chunks;
         const int64_t quantum = 2 * sh.r;  // two row groups: one trip of the kernel's loop
         rpc = ((rpc + quantum - 1) / quantum) * quantum;
@@ -847,24 +920,69 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
         if (rc) return rc;
         {
             prof_scope ps(ctx, NGC_KERNEL_GRAD);
-#define NGC_STREAM_CASE(W) \
-    case W: launch_stream<4, 4, 2, W>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc, unit_part); break;
-            if (sh.nv == 4) {
-                switch (sh.waves) {
-                    NGC_STREAM_CASE(1) NGC_STREAM_CASE(2) NGC_STREAM_CASE(3) NGC_STREAM_CASE(4)
-                    NGC_STREAM_CASE(6) NGC_STREAM_CASE(8)
+#define NGC_STREAM_ARGS ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc, unit_part, (int)(sh.scalar ? d : d / 4)
+#define NGC_STREAM_CASE(NV, R, W, RG) \
+    case W: launch_stream<NV, R, 2, W, RG>(NGC_STREAM_ARGS); break;
+#define NGC_STREAM_SCALAR(NV, R, W) \
+    case W: launch_stream<NV, R, 2, W, true, float>(NGC_STREAM_ARGS); break;
+            if (sh.scalar) {
+                if (sh.nv == 4) {
+                    launch_stream<4, 16, 2, 1, true, float>(NGC_STREAM_ARGS);
+                } else if (sh.nv == 8) {
+                    switch (sh.waves) {
+                        NGC_STREAM_SCALAR(8, 8, 1) NGC_STREAM_SCALAR(8, 8, 2) NGC_STREAM_SCALAR(8, 8, 3)
+                        NGC_STREAM_SCALAR(8, 8, 4) NGC_STREAM_SCALAR(8, 8, 5) NGC_STREAM_SCALAR(8, 8, 6)
+                        NGC_STREAM_SCALAR(8, 8, 7) NGC_STREAM_SCALAR(8, 8, 8)
+                    }
+                } else {
+                    switch (sh.waves) {
+                        NGC_STREAM_SCALAR(16, 3, 5) NGC_STREAM_SCALAR(16, 3, 6)
+                        NGC_STREAM_SCALAR(16, 3, 7) NGC_STREAM_SCALAR(16, 3, 8)
+                    }
                 }
-            } else if (sh.nv == 8 && sh.waves == 6) {
-                launch_stream<8, 2, 2, 6>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc, unit_part);
+            } else if (!sh.ragged) {
+                if (sh.nv == 4) {
+                    switch (sh.waves) {
+                        NGC_STREAM_CASE(4, 4, 1, false) NGC_STREAM_CASE(4, 4, 2, false)
+                        NGC_STREAM_CASE(4, 4, 4, false) NGC_STREAM_CASE(4, 4, 6, false)
+                        NGC_STREAM_CASE(4, 4, 8, false)
+                    }
+                } else if (sh.nv == 8) {
+                    switch (sh.waves) {
+                        NGC_STREAM_CASE(8, 2, 6, false) NGC_STREAM_CASE(8, 2, 8, false)
+                    }
+                } else if (sh.nv == 1) {
+                    launch_stream<1, 16, 2, 1, false>(NGC_STREAM_ARGS);
+                } else if (sh.nv == 2) {
+                    launch_stream<2, 8, 2, 1, false>(NGC_STREAM_ARGS);
+                } else if (sh.waves == 4) {
+                    launch_stream<3, 5, 2, 4, false>(NGC_STREAM_ARGS);
+                } else {
+                    launch_stream<3, 5, 2, 1, false>(NGC_STREAM_ARGS);
+                }
+            } else if (sh.nv == 4) {
+                switch (sh.waves) {
+                    NGC_STREAM_CASE(4, 4, 1, true) NGC_STREAM_CASE(4, 4, 2, true)
+                    NGC_STREAM_CASE(4, 4, 4, true)
+                    NGC_STREAM_CASE(4, 4, 5, true) NGC_STREAM_CASE(4, 4, 6, true)
+                    NGC_STREAM_CASE(4, 4, 7, true) NGC_STREAM_CASE(4, 4, 8, true)
+                }
             } else if (sh.nv == 8) {
-                launch_stream<8, 2, 2, 8>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc, unit_part);
+                switch (sh.waves) {
+                    NGC_STREAM_CASE(8, 2, 5, true) NGC_STREAM_CASE(8, 2, 6, true)
+                    NGC_STREAM_CASE(8, 2, 7, true) NGC_STREAM_CASE(8, 2, 8, true)
+                }
             } else if (sh.nv == 1) {
-                launch_stream<1, 16, 2, 1>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc, unit_part);
+                launch_stream<1, 16, 2, 1, true>(NGC_STREAM_ARGS);
             } else if (sh.nv == 2) {
-                launch_stream<2, 8, 2, 1>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc, unit_part);
+                launch_stream<2, 8, 2, 1, true>(NGC_STREAM_ARGS);
+            } else if (sh.waves == 4) {
+                launch_stream<3, 5, 2, 4, true>(NGC_STREAM_ARGS);
             } else {
-                launch_stream<3, 4, 2, 1>(ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc, unit_part);
+                launch_stream<3, 5, 2, 1, true>(NGC_STREAM_ARGS);
             }
+#undef NGC_STREAM_ARGS
+#undef NGC_STREAM_SCALAR
 #undef NGC_STREAM_CASE
         }
         NGC_HIP(ctx, hipGetLastError());
@@ -875,10 +993,14 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
         }
         {
             prof_scope ps(ctx, NGC_KERNEL_REDUCE);
-            const int64_t dv = d / 4;
+            const int64_t dv = sh.scalar ? d : d / 4;
             dim3 grid((unsigned)((dv + 255) / 256), (unsigned)k);
-            hipLaunchKernelGGL((reduce_partials_kernel<v4f>), grid, dim3(256), 0, ctx->stream,
-                               (const v4f*)ctx->d_ws, (v4f*)G_dev, dv, (int)chunks, unit_row);
+            if (sh.scalar)
+                hipLaunchKernelGGL((reduce_partials_kernel<float>), grid, dim3(256), 0, ctx->stream,
+                                   (const float*)ctx->d_ws, G_dev, dv, (int)chunks, unit_row);
+            else
+                hipLaunchKernelGGL((reduce_partials_kernel<v4f>), grid, dim3(256), 0, ctx->stream,
+                                   (const v4f*)ctx->d_ws, (v4f*)G_dev, dv, (int)chunks, unit_row);
         }
         NGC_HIP(ctx, hipGetLastError());
         return NGC_OK;

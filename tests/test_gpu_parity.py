@@ -135,6 +135,11 @@ GRAD_SHAPES = [
     (4096, 4, 67), (6144, 2, 7), (8192, 2, 13), (12288, 2, 5), (16384, 2, 6),
     (64, 4, 256), (200, 3, 50), (77, 2, 19), (1000, 2, 33), (4100, 2, 10), (5120, 2, 9),
     (4096, 2, 1), (1024, 1, 3), (4096, 64, 9),
+    # rows shorter than the block's slots (d a multiple of 4) and rows that are not 16-byte
+    # aligned (d not a multiple of 4), one case per kernel shape family; the last three take
+    # the two-pass route (no single-pass shape)
+    (3000, 2, 11), (7000, 2, 6), (13000, 2, 4), (54, 3, 100), (1002, 3, 40), (2050, 2, 17),
+    (4094, 2, 9), (5002, 2, 7), (8190, 2, 5), (8194, 2, 3), (20000, 2, 3), (16388, 2, 2),
 ]
 
 
