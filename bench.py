@@ -180,8 +180,9 @@ def bench_workers(args, w, wl, ngc, torch, np):
     K, W = args.steps, args.warmup
     L = len(w.layers)
     Xd = torch.empty((w.n, w.rows, w.d_in), dtype=torch.float32, device=dev)
-    Yd = torch.empty((w.n, w.rows), dtype=torch.float32, device=dev)
-    truth = wl.truth_vector(w, 0)
+    mlp = w.loss == wl.LOSS_MLP2
+    Yd = torch.empty((w.n, w.rows), dtype=torch.int32 if mlp else torch.float32, device=dev)
+    truth = None if mlp else wl.truth_vector(w, 0)
     from concurrent.futures import ThreadPoolExecutor
     with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
         for j, (X, Y) in enumerate(ex.map(lambda j: wl.partition(w, j, 0, truth), range(w.n))):
@@ -192,6 +193,8 @@ def bench_workers(args, w, wl, ngc, torch, np):
     masks[masks.sum(axis=1) > w.layers[-1]] = 0
     ctx = ngc.ngc_create(w.n, w.n, w.layers, w.d, torch.cuda.current_stream().cuda_stream)
     ngc.ngc_build_code(ctx, ngc.NGC_CODE_CYCLIC if w.code == wl.CODE_CYCLIC else ngc.NGC_CODE_FRACREP, 0)
+    if mlp:
+        ngc.ngc_set_mlp2_shape(ctx, w.d_in, w.hidden, w.classes)
     T = ngc.ngc_worker_task_count(ctx)
     Wd = torch.empty((w.n, T, w.d), dtype=torch.float32, device=dev)
     C = torch.empty((L, w.n, w.d), dtype=torch.float32, device=dev)
@@ -319,9 +322,6 @@ def main():
     if w.loss < 0:
         return bench_codec(args, w, wl, ngc, torch, np)
     if args.mode == "workers":
-        if w.loss not in (wl.LOSS_LSQ, wl.LOSS_LOGISTIC):
-            print("--mode workers times the regression workloads", file=sys.stderr)
-            sys.exit(2)
         return bench_workers(args, w, wl, ngc, torch, np)
     if w.loss not in (wl.LOSS_LSQ, wl.LOSS_LOGISTIC, wl.LOSS_MLP2):
         print("bench.py times the gradient workloads (C1, C2, C3, C4)", file=sys.stderr)

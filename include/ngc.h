@@ -187,7 +187,8 @@ int ngc_decode(ngc_ctx* ctx, int layer, const double* a_host, const float* C_dev
  * ngc_worker_grads: progress_host[i] = number of tasks worker i has finished
  *   (0..T).  W_dev: float [n][T*c][d]; row (i, t) receives the partial gradient
  *   of the t-th partition of worker i's schedule for t < c*progress[i]; other
- *   rows are left untouched.  Least squares and logistic losses.
+ *   rows are left untouched.  All three losses (the perceptron after
+ *   ngc_set_mlp2_shape; its units run as one batched launch per stage).
  * ngc_worker_encode: C[u][i][:] = sum_t B^(u)[i][part(i,t)] W[i][t][:] (Sec.
  *   II-C, X = B G, from the worker's own copies) for every layer u whose
  *   s[u]+1 tasks worker i has finished; rows of unfinished (u, i) are set to

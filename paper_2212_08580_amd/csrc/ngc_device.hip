@@ -881,8 +881,8 @@ static stream_shape pick_stream_shape(int64_t d) {
     return {8, 2, (dq + 511) / 512, true, false};
 }
 
-int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float* theta,
-                   int64_t rows, float* G);  // ngc_mlp.hip
+int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float* theta, int64_t rows,
+                   float* G, int units, const int* unit_part, const int* unit_row);  // ngc_mlp.hip
 
 // Gradients of `units` partial-gradient computations (least squares / logistic).  Unit q works
 // on partition unit_part[q] (q itself if unit_part is null) and its result goes to row
@@ -1058,7 +1058,7 @@ extern "C" int ngc_partition_grads(ngc_ctx* ctx, int loss, const float* X_dev, c
     if (rc) return rc;
     if (loss == NGC_LOSS_MLP2) {
         if (!ctx->mlp_din) return ngc_fail(ctx, NGC_ERR_STATE, "call ngc_set_mlp2_shape first");
-        return ngc_mlp2_grads(ctx, X_dev, (const int*)y_dev, theta_dev, rows, G_dev);
+        return ngc_mlp2_grads(ctx, X_dev, (const int*)y_dev, theta_dev, rows, G_dev, ctx->k, nullptr, nullptr);
     }
     if (loss != NGC_LOSS_LSQ && loss != NGC_LOSS_LOGISTIC) return ngc_fail(ctx, NGC_ERR_INVALID, "unknown loss");
     return grads_impl(ctx, loss, X_dev, y_dev, theta_dev, rows, G_dev, ctx->k, nullptr, nullptr);
@@ -1284,8 +1284,9 @@ extern "C" int ngc_worker_grads(ngc_ctx* ctx, int loss, const float* X_dev, cons
     if (!ctx) return NGC_ERR_INVALID;
     if (!X_dev || !y_dev || !theta_dev || !W_dev || !progress_host) return ngc_fail(ctx, NGC_ERR_INVALID, "null pointer");
     if (rows < 1) return ngc_fail(ctx, NGC_ERR_INVALID, "rows_per_part must be positive");
-    if (loss != NGC_LOSS_LSQ && loss != NGC_LOSS_LOGISTIC)
-        return ngc_fail(ctx, NGC_ERR_INVALID, "worker execution supports the least-squares and logistic losses");
+    if (loss != NGC_LOSS_LSQ && loss != NGC_LOSS_LOGISTIC && loss != NGC_LOSS_MLP2)
+        return ngc_fail(ctx, NGC_ERR_INVALID, "unknown loss");
+    if (loss == NGC_LOSS_MLP2 && !ctx->mlp_din) return ngc_fail(ctx, NGC_ERR_STATE, "call ngc_set_mlp2_shape first");
     if (!aligned16(X_dev) || !aligned16(theta_dev) || !aligned16(W_dev))
         return ngc_fail(ctx, NGC_ERR_INVALID, "X, theta and W must be 16-byte aligned");
     int rc = dev_init(ctx);
@@ -1315,7 +1316,12 @@ extern "C" int ngc_worker_grads(ngc_ctx* ctx, int loss, const float* X_dev, cons
     std::memcpy(ctx->h_maps[q] + units, row.data(), sizeof(int) * units);
     NGC_HIP(ctx, hipMemcpyAsync(ctx->d_maps[q], ctx->h_maps[q], sizeof(int) * 2 * units, hipMemcpyHostToDevice,
                                 ctx->stream));
-    rc = grads_impl(ctx, loss, X_dev, y_dev, theta_dev, rows, W_dev, units, ctx->d_maps[q], ctx->d_maps[q] + units);
+    if (loss == NGC_LOSS_MLP2)
+        rc = ngc_mlp2_grads(ctx, X_dev, (const int*)y_dev, theta_dev, rows, W_dev, units, ctx->d_maps[q],
+                            ctx->d_maps[q] + units);
+    else
+        rc = grads_impl(ctx, loss, X_dev, y_dev, theta_dev, rows, W_dev, units, ctx->d_maps[q],
+                        ctx->d_maps[q] + units);
     NGC_HIP(ctx, hipEventRecord(ctx->maps_ev[q], ctx->stream));
     ctx->maps_ev_set[q] = true;
     return rc;

@@ -79,11 +79,14 @@ __device__ __forceinline__ tile_id xcd_tile() {
 // C[M x N] = A * B (+ epilogue), batched over blockIdx.z.
 //   A_KMAJOR: A is stored [K][M] (element (m,k) at A[k*lda + m]); else [M][K].
 //   B is stored [K][N].  C is stored [M][N].
+//   Batch entry z reads A at batch index a_batch[z] and writes C at c_batch[z]
+//   (z itself where the map is null): several entries may read the same A.
 template <bool A_KMAJOR, int EPI>
 __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(
     const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C,
     const float* __restrict__ bias, int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
-    int64_t strideA, int64_t strideB, int64_t strideC, int a_vec_ok, int b_vec_ok, int c_vec_ok) {
+    int64_t strideA, int64_t strideB, int64_t strideC, int a_vec_ok, int b_vec_ok, int c_vec_ok,
+    const int* __restrict__ a_batch, const int* __restrict__ c_batch) {
     __shared__ float As[2][BK][LDT];
     __shared__ float Bs[2][BK][LDT];
     const int t = threadIdx.x;
@@ -93,9 +96,9 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(
     const int l32 = lane & 31, lhi = lane >> 5;
     const tile_id tile = xcd_tile();
     const int m0 = tile.y * BM, n0 = tile.x * BN;
-    A += (int64_t)tile.z * strideA;
+    A += (int64_t)(a_batch ? a_batch[tile.z] : tile.z) * strideA;
     B += (int64_t)tile.z * strideB;
-    C += (int64_t)tile.z * strideC;
+    C += (int64_t)(c_batch ? c_batch[tile.z] : tile.z) * strideC;
 
     v16f acc[2][2];
 #pragma unroll
@@ -248,7 +251,8 @@ typedef float v4acc __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(256, 5) void mlp_gemm112_kernel(
     const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C, int M, int N,
     int K, int64_t lda, int64_t ldb, int64_t ldc, int64_t strideA, int64_t strideB,
-    int64_t strideC, int a_vec_ok, int b_vec_ok) {
+    int64_t strideC, int a_vec_ok, int b_vec_ok, const int* __restrict__ a_batch,
+    const int* __restrict__ c_batch) {
     __shared__ float As[2][TK][LDA];
     __shared__ float Bs[2][TK][LDB];
     const int t = threadIdx.x;
@@ -257,9 +261,9 @@ __global__ __launch_bounds__(256, 5) void mlp_gemm112_kernel(
     const int l16 = lane & 15, kq = lane >> 4;
     const tile_id tile = xcd_tile();
     const int m0 = tile.y * TM, n0 = tile.x * TN;
-    A += (int64_t)tile.z * strideA;
+    A += (int64_t)(a_batch ? a_batch[tile.z] : tile.z) * strideA;
     B += (int64_t)tile.z * strideB;
-    C += (int64_t)tile.z * strideC;
+    C += (int64_t)(c_batch ? c_batch[tile.z] : tile.z) * strideC;
 
     v4acc acc[7][2];
 #pragma unroll
@@ -377,7 +381,7 @@ template <int NCP>
 __global__ __launch_bounds__(64) void mlp_logits_kernel(
     const float* __restrict__ H, const int* __restrict__ labels, const float* __restrict__ W2,
     const float* __restrict__ b2, float* __restrict__ dZ2, int hidden, int classes,
-    int64_t total_rows, int h_vec_ok) {
+    int64_t total_rows, int h_vec_ok, int64_t rows, const int* __restrict__ unit_part) {
     constexpr int TR = 64, TH = 32, LD = TH + 4;
     constexpr int NCQ = (NCP + 3) / 4 * 4;  // W2 row padded to whole float4
     __shared__ float tile[TR * LD];
@@ -443,7 +447,8 @@ __global__ __launch_bounds__(64) void mlp_logits_kernel(
         __syncthreads();
     }
     if (my_row >= total_rows) return;
-    const int label = labels[my_row];
+    // row r of H belongs to unit r / rows, which works on partition unit_part[unit]
+    const int label = labels[unit_part ? (int64_t)unit_part[my_row / rows] * rows + my_row % rows : my_row];
     float mx = -INFINITY;
 #pragma unroll
     for (int q = 0; q < NCP; ++q) {
@@ -557,17 +562,19 @@ __global__ __launch_bounds__(256) void mlp_back_kernel(
     }
 }
 
-// out[j*out_stride + t] = sum over chunks (in index order) of partial[(j*chunks + c)*T + t]
+// out[row(j)*out_stride + t] = sum over chunks (in index order) of partial[(j*chunks + c)*T + t],
+// row(j) = unit_row[j], or j without a map
 __global__ __launch_bounds__(256) void mlp_tail_reduce_kernel(const float* __restrict__ partial,
                                                               float* __restrict__ out, int64_t T,
-                                                              int chunks, int64_t out_stride) {
+                                                              int chunks, int64_t out_stride,
+                                                              const int* __restrict__ unit_row) {
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int j = blockIdx.y;
     if (t >= T) return;
     const float* p = partial + (int64_t)j * chunks * T + t;
     float acc = p[0];
     for (int c = 1; c < chunks; ++c) acc += p[(int64_t)c * T];
-    out[(int64_t)j * out_stride + t] = acc;
+    out[(int64_t)(unit_row ? unit_row[j] : j) * out_stride + t] = acc;
 }
 
 struct mlp_prof {
@@ -597,9 +604,12 @@ bool al(const void* p, uintptr_t m) { return (reinterpret_cast<uintptr_t>(p) & (
 
 }  // namespace
 
+// Perceptron gradients of `units` partial-gradient computations.  Unit q works on partition
+// unit_part[q] (q itself if the map is null) and its gradient goes to row unit_row[q] of G
+// (row q if null); both maps are device arrays.  Without maps the units are the k partitions.
 int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float* theta,
-                   int64_t rows, float* G) {
-    const int k = ctx->k;
+                   int64_t rows, float* G, int units, const int* unit_part, const int* unit_row) {
+    const int k = units;
     const int din = ctx->mlp_din, hid = ctx->mlp_hidden, cls = ctx->mlp_classes;
     const int64_t d = ctx->d;
     if (hid > 1024) return ngc_fail(ctx, NGC_ERR_INVALID, "MLP hidden width above 1024 is not supported");
@@ -639,13 +649,24 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
     float* partial = dZ2 + z_floats;
 
     mlp_prof ps(ctx);
-    {   // 1. H = relu(X W1 + b1), all partitions as one matrix
+    if (!unit_part) {   // 1. H = relu(X W1 + b1), all partitions as one matrix
         dim3 grid((unsigned)((hid + BN - 1) / BN), (unsigned)((total + BM - 1) / BM), 1);
         if (grid.y > 65535) return ngc_fail(ctx, NGC_ERR_INVALID, "too many rows for one launch");
         hipLaunchKernelGGL((mlp_gemm_kernel<false, EPI_BIAS_RELU>), grid, dim3(256), 0, ctx->stream, X, W1, H, b1,
                            (int)total, hid, din, (int64_t)din, (int64_t)hid, (int64_t)hid, (int64_t)0,
                            (int64_t)0, (int64_t)0, (int)(din % 4 == 0 && al(X, 16)),
-                           (int)(hid % 4 == 0 && al(W1, 16)), (int)(hid % 2 == 0));
+                           (int)(hid % 4 == 0 && al(W1, 16)), (int)(hid % 2 == 0), (const int*)nullptr,
+                           (const int*)nullptr);
+        NGC_HIP(ctx, hipGetLastError());
+    } else {   // the same, one batch entry per unit: entry q reads partition unit_part[q], writes H block q
+        dim3 grid((unsigned)((hid + BN - 1) / BN), (unsigned)((rows + BM - 1) / BM), (unsigned)k);
+        if (grid.y > 65535 || k > 65535) return ngc_fail(ctx, NGC_ERR_INVALID, "too many rows or units for one launch");
+        hipLaunchKernelGGL((mlp_gemm_kernel<false, EPI_BIAS_RELU>), grid, dim3(256), 0, ctx->stream, X, W1, H, b1,
+                           (int)rows, hid, din, (int64_t)din, (int64_t)hid, (int64_t)hid, rows * (int64_t)din,
+                           (int64_t)0, rows * (int64_t)hid,
+                           (int)(din % 4 == 0 && al(X, 16) && (rows * (int64_t)din) % 4 == 0),
+                           (int)(hid % 4 == 0 && al(W1, 16)), (int)(hid % 2 == 0), unit_part,
+                           (const int*)nullptr);
         NGC_HIP(ctx, hipGetLastError());
     }
     {   // 2. logits, softmax, dZ2; then dW2/db2/db1 partials and dZ1 over H
@@ -654,7 +675,7 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
         dim3 grid((unsigned)(k * chunks));
 #define NGC_MLP_HEAD(NCP)                                                                              \
     hipLaunchKernelGGL((mlp_logits_kernel<NCP>), lgrid, dim3(64), 0, ctx->stream, (const float*)H, labels, W2, \
-                       b2, dZ2, hid, cls, total, hv);                                                  \
+                       b2, dZ2, hid, cls, total, hv, rows, unit_part);                                 \
     hipLaunchKernelGGL((mlp_back_kernel<NCP>), grid, dim3(256), 0, ctx->stream, H, (const float*)dZ2, W2,      \
                        partial, hid, cls, rows, (int)chunks, rpc, hv);
         if (cls <= 4) {
@@ -668,7 +689,7 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
         NGC_HIP(ctx, hipGetLastError());
         dim3 rgrid((unsigned)((T + 255) / 256), (unsigned)k);
         hipLaunchKernelGGL(mlp_tail_reduce_kernel, rgrid, dim3(256), 0, ctx->stream, (const float*)partial,
-                           G + (int64_t)din * hid, T, (int)chunks, d);
+                           G + (int64_t)din * hid, T, (int)chunks, d, unit_row);
         NGC_HIP(ctx, hipGetLastError());
     }
     {   // 3. dW1_j = X_j^T dZ1_j, one batch entry per partition, straight into G[j]
@@ -679,13 +700,13 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
             dim3 grid((unsigned)((hid + TN - 1) / TN), (unsigned)((din + TM - 1) / TM), (unsigned)k);
             hipLaunchKernelGGL(mlp_gemm112_kernel, grid, dim3(256), 0, ctx->stream, X, (const float*)H, G, din, hid,
                                (int)rows, (int64_t)din, (int64_t)hid, (int64_t)hid, rows * (int64_t)din,
-                               rows * (int64_t)hid, d, a_ok, b_ok);
+                               rows * (int64_t)hid, d, a_ok, b_ok, unit_part, unit_row);
         } else {
             dim3 grid((unsigned)((hid + BN - 1) / BN), (unsigned)((din + BM - 1) / BM), (unsigned)k);
             hipLaunchKernelGGL((mlp_gemm_kernel<true, EPI_STORE>), grid, dim3(256), 0, ctx->stream, X, (const float*)H, G,
                                (const float*)nullptr, din, hid, (int)rows, (int64_t)din, (int64_t)hid, (int64_t)hid,
                                rows * (int64_t)din, rows * (int64_t)hid, d, a_ok, b_ok,
-                               (int)(hid % 2 == 0 && d % 2 == 0 && al(G, 8)));
+                               (int)(hid % 2 == 0 && d % 2 == 0 && al(G, 8)), unit_part, unit_row);
         }
         NGC_HIP(ctx, hipGetLastError());
     }

@@ -90,6 +90,73 @@ def test_worker_execution_matches_oracle(ngc, base, n, rows, d, layers, kind):
         ngc.ngc_destroy(ctx)
 
 
+@pytest.mark.parametrize("n,rows,d_in,hidden,classes,layers", [
+    (5, 37, 20, 24, 5, (0, 1, 3)),          # guarded loads everywhere (nothing a multiple of 4 but d_in)
+    (4, 150, 112, 128, 10, (0, 2)),         # vector loads, the 112-row tile of the backward product
+])
+def test_worker_execution_with_the_perceptron_loss(ngc, n, rows, d_in, hidden, classes, layers):
+    """Each worker's own copies of the perceptron gradients (several units reading the same
+    partition in one batched launch), the messages formed from them, and the decoded sum."""
+    import dataclasses
+    import torch
+    dev = torch.device("cuda:0")
+    d = wl.mlp_param_count(d_in, hidden, classes)
+    w = dataclasses.replace(wl.C4, name="mlp-workers", n=n, rows=rows, d_in=d_in, hidden=hidden,
+                            classes=classes, d=d, layers=tuple(layers))
+    X, Y = wl.dataset(w, seed=4, threads=1)
+    th = wl.theta(w, seed=5)
+    Bs = codes.nested_code(n, layers, "cyclic", seed=0, draws=2)
+    G_o = gradients.partial_gradients(wl.LOSS_MLP2, X, Y, th, hidden, classes)
+    full = G_o.sum(axis=0)
+    ctx = ngc.ngc_create(n, n, layers, d, torch.cuda.current_stream().cuda_stream)
+    try:
+        for u, B in enumerate(Bs):
+            ngc.ngc_set_code(ctx, u, B)
+        ngc.ngc_set_mlp2_shape(ctx, d_in, hidden, classes)
+        T = ngc.ngc_worker_task_count(ctx)
+        Xd, Yd, thd = (torch.from_numpy(a).to(dev) for a in (X, Y, th))
+        C = torch.empty((len(layers), n, d), dtype=torch.float32, device=dev)
+        g = torch.empty(d, dtype=torch.float32, device=dev)
+        rng = np.random.default_rng(6)
+        decoded = 0
+        for progress in (np.full(n, T), rng.integers(1, T + 1, n), np.array([0] + [T] * (n - 1))):
+            W = torch.full((n, T, d), 7.0, dtype=torch.float32, device=dev)
+            ngc.ngc_worker_grads(ctx, wl.LOSS_MLP2, Xd, Yd, thd, rows, progress, W)
+            ngc.ngc_worker_encode(ctx, W, progress, C)
+            ngc.ngc_sync(ctx)
+            Wh, Ch = W.cpu().numpy(), C.cpu().numpy()
+            W_o = ow.worker_partials(wl.LOSS_MLP2, X, Y, th, Bs, progress, hidden, classes)
+            C_o = ow.worker_messages(Bs, W_o, progress)
+            for i in range(n):
+                for t in range(T):
+                    if t < progress[i]:
+                        assert rel(Wh[i, t], W_o[i][t]) <= TOL, (i, t)
+                    else:
+                        assert np.all(Wh[i, t] == 7.0)
+            for u in range(len(layers)):
+                for i in range(n):
+                    if C_o[u][i] is None:
+                        assert np.all(Ch[u, i] == 0.0)
+                    else:
+                        assert rel(Ch[u, i], C_o[u][i]) <= TOL
+            try:
+                u_o, mask_o, a_o, g_o = ow.decode_from_workers(Bs, layers, W_o, progress, 0)
+            except coding.Undecodable:
+                continue
+            u, mask, a, r = ngc.ngc_select_from_progress(ctx, progress, n, 0)
+            assert u == u_o and np.array_equal(mask, mask_o)
+            ngc.ngc_decode(ctx, u, a, C, g)
+            ngc.ngc_sync(ctx)
+            msgs = np.stack([C_o[u_o][i] if C_o[u_o][i] is not None else np.zeros(d) for i in range(n)])
+            kappa = coding.conditioning(a_o, msgs, full)
+            err = rel(g.cpu().numpy(), full)
+            assert err <= max(TOL, 4 * 2.0 ** -24 * kappa), (err, kappa)
+            decoded += 1
+        assert decoded >= 2
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
 def test_worker_calls_reject_bad_arguments(ngc):
     import torch
     dev = torch.device("cuda:0")
@@ -100,8 +167,11 @@ def test_worker_calls_reject_bad_arguments(ngc):
             ngc.ngc_worker_grads(ctx, 0, z, z, z, 1, [1, 1, 1, 1], z)
         assert e.value.code == ngc.NGC_ERR_STATE
         ngc.ngc_build_code(ctx, ngc.NGC_CODE_FRACREP, 0)
+        with pytest.raises(ngc.NgcError) as e:                       # perceptron loss without its shape
+            ngc.ngc_worker_grads(ctx, 2, z, z, z, 1, [1, 1, 1, 1], z)
+        assert e.value.code == ngc.NGC_ERR_STATE
         with pytest.raises(ngc.NgcError):
-            ngc.ngc_worker_grads(ctx, 2, z, z, z, 1, [1, 1, 1, 1], z)    # perceptron loss not offered here
+            ngc.ngc_worker_grads(ctx, 3, z, z, z, 1, [1, 1, 1, 1], z)    # no such loss
         with pytest.raises(ngc.NgcError):
             ngc.ngc_worker_grads(ctx, 0, z, z, z, 1, [1, -1, 1, 1], z)
     finally:
