@@ -241,7 +241,10 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(
 // 112 x 128 tile, wave w the 112 x 32 slab of columns 32w.., as 7 x 2 MFMA blocks.
 // Lane l feeds element (row or column l % 16, depth l / 16) of each operand block
 // and holds rows 4*(l/16)..+3 of column l % 16 of each result block.
-constexpr int TM = 112, TN = 128, TK = 8, LDA = TM + 4, LDB = TN + 4;
+// LDS row strides: the four 16-lane groups of a wave read 16 consecutive words of four
+// consecutive k rows, so a stride of 16 or 48 modulo 64 words puts the four groups on four
+// disjoint sets of 16 banks (112 = 64 + 48 needs no padding, 128 gets 16 words).
+constexpr int TM = 112, TN = 128, TK = 8, LDA = TM, LDB = TN + 16;
 typedef float v4acc __attribute__((ext_vector_type(4)));
 
 // 8-deep k tiles and one float4 of each operand per thread and stage keep the kernel
@@ -368,25 +371,32 @@ __device__ __forceinline__ float wave_sum(float v) {
     return (s0 + s1) + (s2 + s3);
 }
 
-// Step 2a.  Logits, softmax and dZ2 = P - onehot(label), one thread per row so
-// that no value ever crosses lanes: a block of 64 threads takes 64 consecutive
-// rows; their hidden activations pass through LDS in tiles of 64 rows x 32
-// units (coalesced 128-byte row segments in, one padded row per thread out), and
-// each thread adds h * W2[unit][class] into its own NCP logits.  The 32 rows of
-// W2 that go with a tile sit in LDS as well and are read as broadcasts (every
-// lane the same address).  The next tile is fetched into registers while the
-// current one is consumed.  NCP is the class
-// count rounded up; classes beyond `classes` get logit -inf.
+// Step 2a.  Logits, softmax and dZ2 = P - onehot(label), one lane per row so
+// that no value crosses lanes inside a wave: a block takes 64 consecutive rows;
+// their hidden activations pass through LDS in tiles of 64 rows x 32 units
+// (coalesced 128-byte row segments in, one padded row per lane out), and each
+// lane adds h * W2[unit][class] into its own NCP logits.  The 32 rows of W2
+// that go with a tile sit in LDS as well and are read as broadcasts (every lane
+// the same address).  The block's four waves share the hidden layer (wave w
+// takes slices w, w+4, ... through a tile of its own; with one wave per block
+// the launch had fewer waves than the chip has SIMDs) and their partial logits
+// are added in wave order at the end.  The next tile is fetched into registers
+// while the current one is consumed.  NCP is the class count rounded up;
+// classes beyond `classes` get logit -inf.
 template <int NCP>
-__global__ __launch_bounds__(64) void mlp_logits_kernel(
+__global__ __launch_bounds__(256) void mlp_logits_kernel(
     const float* __restrict__ H, const int* __restrict__ labels, const float* __restrict__ W2,
     const float* __restrict__ b2, float* __restrict__ dZ2, int hidden, int classes,
     int64_t total_rows, int h_vec_ok, int64_t rows, const int* __restrict__ unit_part) {
-    constexpr int TR = 64, TH = 32, LD = TH + 4;
+    constexpr int TR = 64, TH = 32, LD = TH + 4, NW = 4;
     constexpr int NCQ = (NCP + 3) / 4 * 4;  // W2 row padded to whole float4
-    __shared__ float tile[TR * LD];
-    __shared__ float w2s[TH * NCQ];
-    const int lane = threadIdx.x;
+    static_assert(NW * NCP * 64 <= NW * TR * LD, "the exchange of partial logits fits the tiles");
+    __shared__ float tile_s[NW][TR * LD];
+    __shared__ float w2s_s[NW][TH * NCQ];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    float* tile = tile_s[wave];
+    float* w2s = w2s_s[wave];
     const int64_t row0 = (int64_t)blockIdx.x * TR;
     const int64_t my_row = row0 + lane;
     float z[NCP];
@@ -412,39 +422,62 @@ __global__ __launch_bounds__(64) void mlp_logits_kernel(
                                       : (v4f)(0.0f);
         }
     };
-    fetch(0);
-    for (int hc = 0; hc < hidden; hc += TH) {
+    // the four waves take the 32-unit slices of the hidden layer in turn (wave w: slices w,
+    // w+4, ...), each through its own tile; a slice past the end is skipped by its wave,
+    // which still meets the others at the barriers
+    if (wave * TH < hidden) fetch(wave * TH);
+    for (int hb = 0; hb < hidden; hb += NW * TH) {
+        const int hc = hb + wave * TH;
+        const bool live = hc < hidden;  // wave-uniform
+        if (live) {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int idx = u * 64 + lane;
-            *reinterpret_cast<v4f*>(&tile[(idx >> 3) * LD + (idx & 7) * 4]) = stage[u];
-        }
+            for (int u = 0; u < 8; ++u) {
+                const int idx = u * 64 + lane;
+                *reinterpret_cast<v4f*>(&tile[(idx >> 3) * LD + (idx & 7) * 4]) = stage[u];
+            }
 #pragma unroll
-        for (int u = 0; u < (TH * NCQ + 63) / 64; ++u) {
-            const int idx = u * 64 + lane;
-            if (idx < TH * NCQ) w2s[idx] = wstage[u];
+            for (int u = 0; u < (TH * NCQ + 63) / 64; ++u) {
+                const int idx = u * 64 + lane;
+                if (idx < TH * NCQ) w2s[idx] = wstage[u];
+            }
         }
         __syncthreads();
-        if (hc + TH < hidden) fetch(hc + TH);
+        if (hc + NW * TH < hidden) fetch(hc + NW * TH);
         // units past `hidden` carry zeros in both the tile and the W2 rows
+        if (live) {
 #pragma unroll
-        for (int g = 0; g < TH / 4; ++g) {
-            const v4f hv = *reinterpret_cast<const v4f*>(&tile[lane * LD + g * 4]);
-            const float he[4] = {hv.x, hv.y, hv.z, hv.w};
+            for (int g = 0; g < TH / 4; ++g) {
+                const v4f hv = *reinterpret_cast<const v4f*>(&tile[lane * LD + g * 4]);
+                const float he[4] = {hv.x, hv.y, hv.z, hv.w};
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float* wrow = &w2s[(g * 4 + e) * NCQ];
+                for (int e = 0; e < 4; ++e) {
+                    const float* wrow = &w2s[(g * 4 + e) * NCQ];
 #pragma unroll
-                for (int q4 = 0; q4 < NCQ / 4; ++q4) {
-                    const v4f w = *reinterpret_cast<const v4f*>(wrow + q4 * 4);  // broadcast read
-                    const float we[4] = {w.x, w.y, w.z, w.w};
+                    for (int q4 = 0; q4 < NCQ / 4; ++q4) {
+                        const v4f w = *reinterpret_cast<const v4f*>(wrow + q4 * 4);  // broadcast read
+                        const float we[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        if (q4 * 4 + c < NCP) z[q4 * 4 + c] += he[e] * we[c];
+                        for (int c = 0; c < 4; ++c)
+                            if (q4 * 4 + c < NCP) z[q4 * 4 + c] += he[e] * we[c];
+                    }
                 }
             }
         }
         __syncthreads();
+    }
+    // the waves' partial logits meet in LDS (the tiles are free now) and wave 0 adds them in
+    // wave order: a fixed order, whatever the timing
+    float* zx = &tile_s[0][0];  // [NW][NCP][64]
+#pragma unroll
+    for (int q = 0; q < NCP; ++q) zx[(wave * NCP + q) * 64 + lane] = z[q];
+    __syncthreads();
+    if (wave != 0) return;
+#pragma unroll
+    for (int q = 0; q < NCP; ++q) {
+        float acc = zx[q * 64 + lane];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) acc += zx[(w * NCP + q) * 64 + lane];
+        z[q] = acc;
     }
     if (my_row >= total_rows) return;
     // row r of H belongs to unit r / rows, which works on partition unit_part[unit]
@@ -499,16 +532,17 @@ __global__ __launch_bounds__(256) void mlp_back_kernel(
 
     float* Hp = H + ((int64_t)j * rows) * hidden + h0;
     const float* dzp = dZ2 + ((int64_t)j * rows) * classes;
-    // four rows per trip: their loads are issued together before any is used
-    for (int64_t rb = r0; rb < r1; rb += 4) {
-        v4f hq[4];
+    // RB rows per trip: their loads are issued together before any is used
+    constexpr int RB = 8;
+    for (int64_t rb = r0; rb < r1; rb += RB) {
+        v4f hq[RB];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < RB; ++u) {
             const int64_t r = rb + u < r1 ? rb + u : r1 - 1;
             hq[u] = load4(Hp + r * hidden, hleft, h_vec_ok);
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < RB; ++u) {
             const int64_t r = rb + u;
             if (r < r1) {  // block-uniform
                 float* hrow = Hp + r * hidden;
@@ -623,7 +657,10 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
     const int64_t T = (int64_t)hid + (int64_t)hid * cls + cls;
 
     // workspace: H [total][hid] | dZ2 [total][cls] | block partials [k*chunks][T]
-    int64_t chunks = std::max<int64_t>(1, ((int64_t)ctx->cu_count * 4 + k - 1) / k);
+    // blocks of the backward head kernel: as many as are resident at once (its register count
+    // allows 5, 3 or 2 blocks per CU for up to 4, 10 or 16 classes), so there is no second round
+    const int back_per_cu = cls <= 4 ? 5 : (cls <= 10 ? 3 : 2);
+    int64_t chunks = std::max<int64_t>(1, (int64_t)ctx->cu_count * back_per_cu / k);
     int64_t rpc = (rows + chunks - 1) / chunks;
     chunks = (rows + rpc - 1) / rpc;
     const size_t h_floats = (((size_t)total * hid) + 63) / 64 * 64;
@@ -674,7 +711,7 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
         dim3 lgrid((unsigned)((total + 63) / 64));
         dim3 grid((unsigned)(k * chunks));
 #define NGC_MLP_HEAD(NCP)                                                                              \
-    hipLaunchKernelGGL((mlp_logits_kernel<NCP>), lgrid, dim3(64), 0, ctx->stream, (const float*)H, labels, W2, \
+    hipLaunchKernelGGL((mlp_logits_kernel<NCP>), lgrid, dim3(256), 0, ctx->stream, (const float*)H, labels, W2, \
                        b2, dZ2, hid, cls, total, hv, rows, unit_part);                                 \
     hipLaunchKernelGGL((mlp_back_kernel<NCP>), grid, dim3(256), 0, ctx->stream, H, (const float*)dZ2, W2,      \
                        partial, hid, cls, rows, (int)chunks, rpc, hv);
