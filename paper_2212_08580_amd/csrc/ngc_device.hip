@@ -795,13 +795,15 @@ struct prof_scope {
 };
 }  // namespace
 
-extern "C" int ngc_profile_enable(ngc_ctx* ctx, int kernel_mask) {
+extern "C" int ngc_profile_enable(ngc_ctx* ctx, int kernel_mask) try {
     if (!ctx) return NGC_ERR_INVALID;
     ctx->profile_mask = (unsigned)kernel_mask;
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
-extern "C" int ngc_profile_read(ngc_ctx* ctx, int64_t* launches_out, double* total_ms_out) {
+extern "C" int ngc_profile_read(ngc_ctx* ctx, int64_t* launches_out, double* total_ms_out) try {
     if (!ctx || !launches_out || !total_ms_out) return NGC_ERR_INVALID;
     for (int i = 0; i < NGC_KERNEL_COUNT; ++i) {
         launches_out[i] = 0;
@@ -820,12 +822,16 @@ extern "C" int ngc_profile_read(ngc_ctx* ctx, int64_t* launches_out, double* tot
     }
     ctx->prof.clear();
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
-extern "C" int ngc_sync(ngc_ctx* ctx) {
+extern "C" int ngc_sync(ngc_ctx* ctx) try {
     if (!ctx) return NGC_ERR_INVALID;
     NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -1048,7 +1054,7 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
 }
 
 extern "C" int ngc_partition_grads(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_dev,
-                                   const float* theta_dev, int64_t rows, float* G_dev) {
+                                   const float* theta_dev, int64_t rows, float* G_dev) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (!X_dev || !y_dev || !theta_dev || !G_dev) return ngc_fail(ctx, NGC_ERR_INVALID, "null device pointer");
     if (rows < 1) return ngc_fail(ctx, NGC_ERR_INVALID, "rows_per_part must be positive");
@@ -1062,6 +1068,8 @@ extern "C" int ngc_partition_grads(ngc_ctx* ctx, int loss, const float* X_dev, c
     }
     if (loss != NGC_LOSS_LSQ && loss != NGC_LOSS_LOGISTIC) return ngc_fail(ctx, NGC_ERR_INVALID, "unknown loss");
     return grads_impl(ctx, loss, X_dev, y_dev, theta_dev, rows, G_dev, ctx->k, nullptr, nullptr);
+} catch (...) {
+    return ngc_on_exception();
 }
 
 // ---- code tables on the device --------------------------------------------
@@ -1116,7 +1124,7 @@ static int vec_width(int64_t d, const void* p0, const void* p1) {
     return 1;
 }
 
-extern "C" int ngc_encode(ngc_ctx* ctx, const float* G_dev, int layer, float* C_dev) {
+extern "C" int ngc_encode(ngc_ctx* ctx, const float* G_dev, int layer, float* C_dev) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (!G_dev || !C_dev) return ngc_fail(ctx, NGC_ERR_INVALID, "null device pointer");
     if (layer < -1 || layer >= ctx->L) return ngc_fail(ctx, NGC_ERR_INVALID, "layer out of range");
@@ -1158,10 +1166,12 @@ extern "C" int ngc_encode(ngc_ctx* ctx, const float* G_dev, int layer, float* C_
     }
     NGC_HIP(ctx, hipGetLastError());
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
 extern "C" int ngc_decode(ngc_ctx* ctx, int layer, const double* a_host, const float* C_dev,
-                          float* g_dev) {
+                          float* g_dev) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (!a_host || !C_dev || !g_dev) return ngc_fail(ctx, NGC_ERR_INVALID, "null pointer");
     if (layer < 0 || layer >= ctx->L) return ngc_fail(ctx, NGC_ERR_INVALID, "layer out of range");
@@ -1197,9 +1207,11 @@ extern "C" int ngc_decode(ngc_ctx* ctx, int layer, const double* a_host, const f
     }
     NGC_HIP(ctx, hipGetLastError());
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
-extern "C" int ngc_update(ngc_ctx* ctx, float* theta_dev, const float* g_dev, double scale) {
+extern "C" int ngc_update(ngc_ctx* ctx, float* theta_dev, const float* g_dev, double scale) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (!theta_dev || !g_dev) return ngc_fail(ctx, NGC_ERR_INVALID, "null device pointer");
     int rc = dev_init(ctx);
@@ -1211,10 +1223,12 @@ extern "C" int ngc_update(ngc_ctx* ctx, float* theta_dev, const float* g_dev, do
     }
     NGC_HIP(ctx, hipGetLastError());
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
 // ---- measurement probes -----------------------------------------------------
-extern "C" int ngc_probe_copy(ngc_ctx* ctx, const void* src_dev, void* dst_dev, int64_t bytes) {
+extern "C" int ngc_probe_copy(ngc_ctx* ctx, const void* src_dev, void* dst_dev, int64_t bytes) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (!src_dev || !dst_dev || bytes < 16 || bytes % 16 || !aligned16(src_dev) || !aligned16(dst_dev))
         return ngc_fail(ctx, NGC_ERR_INVALID, "probe buffers must be 16-byte aligned, size a multiple of 16");
@@ -1229,9 +1243,11 @@ extern "C" int ngc_probe_copy(ngc_ctx* ctx, const void* src_dev, void* dst_dev, 
     }
     NGC_HIP(ctx, hipGetLastError());
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
-extern "C" int ngc_probe_read(ngc_ctx* ctx, const void* src_dev, int64_t bytes) {
+extern "C" int ngc_probe_read(ngc_ctx* ctx, const void* src_dev, int64_t bytes) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (!src_dev || bytes < 16 || bytes % 16 || !aligned16(src_dev))
         return ngc_fail(ctx, NGC_ERR_INVALID, "probe buffer must be 16-byte aligned, size a multiple of 16");
@@ -1248,6 +1264,8 @@ extern "C" int ngc_probe_read(ngc_ctx* ctx, const void* src_dev, int64_t bytes) 
     }
     NGC_HIP(ctx, hipGetLastError());
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
 // ---- redundancy-faithful worker execution ------------------------------------------------------
@@ -1280,7 +1298,7 @@ static int ensure_maps(ngc_ctx* ctx, size_t ints) {
 
 extern "C" int ngc_worker_grads(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_dev,
                                 const float* theta_dev, int64_t rows, const int* progress_host,
-                                float* W_dev) {
+                                float* W_dev) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (!X_dev || !y_dev || !theta_dev || !W_dev || !progress_host) return ngc_fail(ctx, NGC_ERR_INVALID, "null pointer");
     if (rows < 1) return ngc_fail(ctx, NGC_ERR_INVALID, "rows_per_part must be positive");
@@ -1325,10 +1343,12 @@ extern "C" int ngc_worker_grads(ngc_ctx* ctx, int loss, const float* X_dev, cons
     NGC_HIP(ctx, hipEventRecord(ctx->maps_ev[q], ctx->stream));
     ctx->maps_ev_set[q] = true;
     return rc;
+} catch (...) {
+    return ngc_on_exception();
 }
 
 extern "C" int ngc_worker_encode(ngc_ctx* ctx, const float* W_dev, const int* progress_host,
-                                 float* C_dev) {
+                                 float* C_dev) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (!W_dev || !C_dev || !progress_host) return ngc_fail(ctx, NGC_ERR_INVALID, "null pointer");
     if (ctx->L > 8) return ngc_fail(ctx, NGC_ERR_INVALID, "worker encode supports at most 8 layers");
@@ -1388,11 +1408,13 @@ extern "C" int ngc_worker_encode(ngc_ctx* ctx, const float* W_dev, const int* pr
     }
     NGC_HIP(ctx, hipGetLastError());
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
 // ---- decode through the explicit decoding matrix ------------------------------------------------
 extern "C" int ngc_decode_lookup(ngc_ctx* ctx, int layer, const uint8_t* straggler_mask,
-                                 const float* C_dev, float* g_dev) {
+                                 const float* C_dev, float* g_dev) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (!straggler_mask || !C_dev || !g_dev) return ngc_fail(ctx, NGC_ERR_INVALID, "null pointer");
     if (layer < 0 || layer >= ctx->L) return ngc_fail(ctx, NGC_ERR_INVALID, "layer out of range");
@@ -1433,13 +1455,15 @@ extern "C" int ngc_decode_lookup(ngc_ctx* ctx, int layer, const uint8_t* straggl
     }
     NGC_HIP(ctx, hipGetLastError());
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
 // ---- one whole iteration in two launches ----------------------------------------------------------
 extern "C" int ngc_iteration(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_dev,
                              float* theta_dev, int64_t rows, const uint8_t* straggler_mask,
                              double scale, float* G_dev, float* C_dev, float* g_dev, int* layer_out,
-                             double* a_out) {
+                             double* a_out) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (!X_dev || !y_dev || !theta_dev || !G_dev || !C_dev || !g_dev || !straggler_mask)
         return ngc_fail(ctx, NGC_ERR_INVALID, "null pointer");
@@ -1509,4 +1533,6 @@ extern "C" int ngc_iteration(ngc_ctx* ctx, int loss, const float* X_dev, const v
     }
     NGC_HIP(ctx, hipGetLastError());
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }

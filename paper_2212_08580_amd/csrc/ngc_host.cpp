@@ -13,6 +13,16 @@ int ngc_fail(const ngc_ctx* ctx, int code, const std::string& msg) {
     return code;
 }
 
+int ngc_on_exception() {
+    try {
+        throw;
+    } catch (const std::bad_alloc&) {
+        return NGC_ERR_NOMEM;
+    } catch (...) {
+        return NGC_ERR_INVALID;
+    }
+}
+
 extern "C" const char* ngc_strerror(int code) {
     switch (code) {
         case NGC_OK: return "ok";
@@ -57,7 +67,7 @@ static void install_layer(ngc_ctx* ctx, int layer, const double* B) {
 }
 
 extern "C" int ngc_create(ngc_ctx** out, int n, int k, int L, const int* s, int64_t d,
-                          void* hip_stream) {
+                          void* hip_stream) try {
     if (!out) return NGC_ERR_INVALID;
     *out = nullptr;
     if (n < 1 || n > NGC_MAX_N || k < n || k > NGC_MAX_N || k % n != 0 || L < 1 || L > NGC_MAX_N ||
@@ -84,6 +94,8 @@ extern "C" int ngc_create(ngc_ctx** out, int n, int k, int L, const int* s, int6
     install_layer(ctx, 0, I.data());
     *out = ctx;
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
 extern "C" void ngc_destroy(ngc_ctx* ctx) {
@@ -92,7 +104,7 @@ extern "C" void ngc_destroy(ngc_ctx* ctx) {
     delete ctx;
 }
 
-extern "C" int ngc_set_code(ngc_ctx* ctx, int layer, const double* B_host) {
+extern "C" int ngc_set_code(ngc_ctx* ctx, int layer, const double* B_host) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (layer < 0 || layer >= ctx->L || !B_host) return ngc_fail(ctx, NGC_ERR_INVALID, "bad layer or null B");
     const int n = ctx->n, k = ctx->k, c = ctx->c;
@@ -117,17 +129,21 @@ extern "C" int ngc_set_code(ngc_ctx* ctx, int layer, const double* B_host) {
     }
     install_layer(ctx, layer, B_host);
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
-extern "C" int ngc_get_code(const ngc_ctx* ctx, int layer, double* B_host_out) {
+extern "C" int ngc_get_code(const ngc_ctx* ctx, int layer, double* B_host_out) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (layer < 0 || layer >= ctx->L || !B_host_out) return ngc_fail(ctx, NGC_ERR_INVALID, "bad layer or null output");
     if (!ctx->code[layer].set) return ngc_fail(ctx, NGC_ERR_STATE, "layer has no code yet");
     std::memcpy(B_host_out, ctx->code[layer].B.data(), sizeof(double) * ctx->n * ctx->k);
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
-extern "C" int ngc_set_mlp2_shape(ngc_ctx* ctx, int d_in, int hidden, int classes) {
+extern "C" int ngc_set_mlp2_shape(ngc_ctx* ctx, int d_in, int hidden, int classes) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (d_in < 1 || hidden < 1 || classes < 2) return ngc_fail(ctx, NGC_ERR_INVALID, "bad MLP shape");
     int64_t need = (int64_t)d_in * hidden + hidden + (int64_t)hidden * classes + classes;
@@ -136,6 +152,8 @@ extern "C" int ngc_set_mlp2_shape(ngc_ctx* ctx, int d_in, int hidden, int classe
     ctx->mlp_hidden = hidden;
     ctx->mlp_classes = classes;
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
 // ---------------------------------------------------------------------------
@@ -265,7 +283,7 @@ double amplification(const std::vector<double>& B, int n, int sigma, uint64_t se
 
 }  // namespace
 
-extern "C" int ngc_build_code(ngc_ctx* ctx, int kind, uint64_t seed) {
+extern "C" int ngc_build_code(ngc_ctx* ctx, int kind, uint64_t seed) try {
     if (!ctx) return NGC_ERR_INVALID;
     const int n = ctx->n;
     if (kind != NGC_CODE_CYCLIC && kind != NGC_CODE_FRACREP) return ngc_fail(ctx, NGC_ERR_INVALID, "unknown code kind");
@@ -309,6 +327,8 @@ extern "C" int ngc_build_code(ngc_ctx* ctx, int kind, uint64_t seed) {
         install_layer(ctx, u, wide.data());
     }
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
 static int select_impl(const ngc_ctx* ctx, const uint8_t* mask, int* layer_out, double* a_out,
@@ -339,13 +359,17 @@ static int select_impl(const ngc_ctx* ctx, const uint8_t* mask, int* layer_out, 
 }
 
 extern "C" int ngc_select_decode_vec(const ngc_ctx* ctx, const uint8_t* straggler_mask, int* layer_out,
-                                     double* a_out, double* residual_out) {
+                                     double* a_out, double* residual_out) try {
     return select_impl(ctx, straggler_mask, layer_out, a_out, residual_out, false);
+} catch (...) {
+    return ngc_on_exception();
 }
 
 extern "C" int ngc_select_decode_vec_first(const ngc_ctx* ctx, const uint8_t* straggler_mask,
-                                           int* layer_out, double* a_out, double* residual_out) {
+                                           int* layer_out, double* a_out, double* residual_out) try {
     return select_impl(ctx, straggler_mask, layer_out, a_out, residual_out, true);
+} catch (...) {
+    return ngc_on_exception();
 }
 
 // ---------------------------------------------------------------------------
@@ -383,16 +407,18 @@ int ngc_make_worker_plan(const ngc_ctx* ctx, ngc_worker_plan& plan) {
     return NGC_OK;
 }
 
-extern "C" int ngc_worker_task_count(const ngc_ctx* ctx, int* tasks_out) {
+extern "C" int ngc_worker_task_count(const ngc_ctx* ctx, int* tasks_out) try {
     if (!ctx || !tasks_out) return NGC_ERR_INVALID;
     ngc_worker_plan plan;
     int rc = ngc_make_worker_plan(ctx, plan);
     if (rc) return rc;
     *tasks_out = plan.T;
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
-extern "C" int ngc_worker_schedule(const ngc_ctx* ctx, int worker, int* parts_out, int* count_out) {
+extern "C" int ngc_worker_schedule(const ngc_ctx* ctx, int worker, int* parts_out, int* count_out) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (worker < 0 || worker >= ctx->n || !parts_out || !count_out) return ngc_fail(ctx, NGC_ERR_INVALID, "bad worker or null output");
     ngc_worker_plan plan;
@@ -401,11 +427,13 @@ extern "C" int ngc_worker_schedule(const ngc_ctx* ctx, int worker, int* parts_ou
     *count_out = (int)plan.order[worker].size();
     for (size_t t = 0; t < plan.order[worker].size(); ++t) parts_out[t] = plan.order[worker][t];
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
 extern "C" int ngc_select_from_progress(const ngc_ctx* ctx, const int* progress, int min_layer,
                                         int* layer_out, uint8_t* mask_out, double* a_out,
-                                        double* residual_out) {
+                                        double* residual_out) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (!progress || !layer_out || !mask_out || !a_out) return ngc_fail(ctx, NGC_ERR_INVALID, "null argument");
     if (min_layer < 0 || min_layer >= ctx->L) return ngc_fail(ctx, NGC_ERR_INVALID, "min_layer out of range");
@@ -435,6 +463,8 @@ extern "C" int ngc_select_from_progress(const ngc_ctx* ctx, const int* progress,
         return NGC_OK;
     }
     return ngc_fail(ctx, NGC_ERR_UNDECODABLE, "no component code has enough finished workers");
+} catch (...) {
+    return ngc_on_exception();
 }
 
 // ---------------------------------------------------------------------------
@@ -466,7 +496,7 @@ static int64_t subset_rank(const int* c, int sigma, int n) {
     return (int64_t)rank;
 }
 
-extern "C" int ngc_build_decoding_table(ngc_ctx* ctx, int layer, int64_t* rows_out) {
+extern "C" int ngc_build_decoding_table(ngc_ctx* ctx, int layer, int64_t* rows_out) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (layer < 0 || layer >= ctx->L) return ngc_fail(ctx, NGC_ERR_INVALID, "layer out of range");
     ngc_layer_code& lc = ctx->code[layer];
@@ -501,10 +531,12 @@ extern "C" int ngc_build_decoding_table(ngc_ctx* ctx, int layer, int64_t* rows_o
     lc.A_stale = true;
     if (rows_out) *rows_out = lc.A_rows;
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
 extern "C" int ngc_decoding_row_index(const ngc_ctx* ctx, int layer, const uint8_t* straggler_mask,
-                                      int64_t* row_out) {
+                                      int64_t* row_out) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (layer < 0 || layer >= ctx->L || !straggler_mask || !row_out) return ngc_fail(ctx, NGC_ERR_INVALID, "bad layer or null argument");
     const int n = ctx->n, sigma = ctx->s[layer];
@@ -525,9 +557,11 @@ extern "C" int ngc_decoding_row_index(const ngc_ctx* ctx, int layer, const uint8
         if (used[i]) out[cnt++] = i;
     *row_out = subset_rank(out, sigma, n);
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
-extern "C" int ngc_get_decoding_row(const ngc_ctx* ctx, int layer, int64_t row, double* a_out) {
+extern "C" int ngc_get_decoding_row(const ngc_ctx* ctx, int layer, int64_t row, double* a_out) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (layer < 0 || layer >= ctx->L || !a_out) return ngc_fail(ctx, NGC_ERR_INVALID, "bad layer or null output");
     const ngc_layer_code& lc = ctx->code[layer];
@@ -535,4 +569,6 @@ extern "C" int ngc_get_decoding_row(const ngc_ctx* ctx, int layer, int64_t row, 
     if (row < 0 || row >= lc.A_rows) return ngc_fail(ctx, NGC_ERR_INVALID, "row out of range");
     std::memcpy(a_out, &lc.A[(size_t)row * ctx->n], sizeof(double) * ctx->n);
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }

@@ -77,6 +77,9 @@ struct ngc_ctx {
 };
 
 int ngc_fail(const ngc_ctx* ctx, int code, const std::string& msg);
+// Status for a C++ exception caught at the C boundary (called inside a catch block): no
+// exception leaves the library.
+int ngc_on_exception();
 
 // defined in ngc_device.hip
 void ngc_dev_release(ngc_ctx* ctx);

@@ -19,6 +19,8 @@
 
 #include "../../include/ngc.h"
 
+int ngc_on_exception();  // ngc_host.cpp: status for an exception caught at the C boundary
+
 namespace {
 
 // F_u(t): P(gamma + eps + u rho + Erlang(u, lam) <= t)
@@ -142,7 +144,7 @@ __global__ __launch_bounds__(256) void latency_sim_kernel(double* __restrict__ L
 }  // namespace
 
 extern "C" int ngc_latency_cdf_gc(int n, int sigma, double lam, double rho, double eps, double gamma,
-                                  double pe, const double* t, int nt, double* cdf_out) {
+                                  double pe, const double* t, int nt, double* cdf_out) try {
     if (bad_params(n, sigma, lam, rho, eps, gamma, pe) || !t || !cdf_out || nt < 0) return NGC_ERR_INVALID;
     binomials C(n);
     for (int q = 0; q < nt; ++q) {
@@ -158,10 +160,12 @@ extern "C" int ngc_latency_cdf_gc(int n, int sigma, double lam, double rho, doub
         cdf_out[q] = total;
     }
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
 extern "C" int ngc_latency_cdf_ngc(int n, int smax, double lam, double rho, double eps, double gamma,
-                                   double pe, const double* t, int nt, double* cdf_out) {
+                                   double pe, const double* t, int nt, double* cdf_out) try {
     if (bad_params(n, smax, lam, rho, eps, gamma, pe) || !t || !cdf_out || nt < 0) return NGC_ERR_INVALID;
     binomials C(n);
     const int top = smax + 1;
@@ -199,11 +203,13 @@ extern "C" int ngc_latency_cdf_ngc(int n, int smax, double lam, double rho, doub
         cdf_out[q] = total;
     }
     return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
 extern "C" int ngc_latency_simulate(void* hip_stream, int n, int smax, double lam, double rho, double eps,
                                     double gamma, double pe, uint64_t seed, int64_t trials,
-                                    double* L_dev, double* Tngc_dev) {
+                                    double* L_dev, double* Tngc_dev) try {
     if (bad_params(n, smax, lam, rho, eps, gamma, pe) || !L_dev || trials < 1 || trials > 0xFFFFFFFFLL)
         return NGC_ERR_INVALID;
     int dev = 0;
@@ -215,4 +221,6 @@ extern "C" int ngc_latency_simulate(void* hip_stream, int n, int smax, double la
     hipLaunchKernelGGL(latency_sim_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, L_dev, Tngc_dev,
                        n, smax + 1, lam, rho, eps, gamma, pe, (uint32_t)seed, (uint32_t)(seed >> 32), trials);
     return hipGetLastError() == hipSuccess ? NGC_OK : NGC_ERR_HIP;
+} catch (...) {
+    return ngc_on_exception();
 }
