@@ -108,11 +108,31 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // Tiles that lie wholly inside the matrices and are 16-byte addressable take
-    // unguarded vector loads (no branch in the main loop); edge tiles and odd
-    // leading dimensions take the guarded element-wise path.
+    // Tiles that lie wholly inside the matrices and are 16-byte addressable, with K a
+    // whole number of k tiles, take the fast loads: one unguarded vector load per
+    // operand piece and nothing else, so that the main loop below has no branch
+    // and the compiler can count the loads in flight (a wait before a stage's LDS
+    // stores then covers that stage only; with a branch around any load it has to
+    // wait for every outstanding load, the ones just issued included).  Edge
+    // tiles and odd leading dimensions take the guarded element-wise loads.
     const bool a_inside = a_vec_ok && (m0 + BM <= M);
     const bool b_inside = b_vec_ok && (n0 + BN <= N);
+    const bool fast = a_inside && b_inside && (K % BK == 0);
+    auto gload_fast = [&](int k0, v4f (&ra)[2], v4f (&rb)[2]) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int idx = t + h * 256;
+            if (A_KMAJOR) {
+                const int k = idx >> 5, m4 = (idx & 31) * 4;
+                ra[h] = *reinterpret_cast<const v4f*>(A + (int64_t)(k0 + k) * lda + m0 + m4);
+            } else {
+                const int m = idx >> 2, k4 = (idx & 3) * 4;
+                ra[h] = *reinterpret_cast<const v4f*>(A + (int64_t)(m0 + m) * lda + k0 + k4);
+            }
+            const int k = idx >> 5, n4 = (idx & 31) * 4;
+            rb[h] = *reinterpret_cast<const v4f*>(B + (int64_t)(k0 + k) * ldb + n0 + n4);
+        }
+    };
     auto gload = [&](int k0, v4f (&ra)[2], v4f (&rb)[2]) {
         const bool k_inside = k0 + BK <= K;
 #pragma unroll
@@ -164,6 +184,7 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(
     };
 
     auto compute = [&](int buf) {
+        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int kk = 0; kk < BK / 2; ++kk) {
             const int k = 2 * kk + lhi;
@@ -174,27 +195,52 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(
             acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.y, b2.x, acc[1][0], 0, 0, 0);
             acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.y, b2.y, acc[1][1], 0, 0, 0);
         }
+        __builtin_amdgcn_s_setprio(0);
     };
 
     // Software pipeline, two k tiles deep: while tile kt is multiplied out of LDS,
     // tile kt+1 waits in registers for its turn in the other LDS buffer and tile
     // kt+2 is on its way from memory.  Two register stages (p, q) alternate, the
-    // loop is unrolled twice so that each has a fixed role.
+    // loop is unrolled twice so that each has a fixed role.  Fast tiles run the
+    // pairs that need no end-of-K test in a loop without conditions; the guarded
+    // loop finishes (or, for the other tiles, does) the rest.
     const int nk = (K + BK - 1) / BK;
     v4f pa[2], pb[2], qa[2], qb[2];
-    gload(0, pa, pb);
-    sstore(0, pa, pb);
-    if (nk > 1) gload(BK, qa, qb);
-    __syncthreads();
-    const int npairs = (nk + 1) / 2;
-    for (int pr = 0; pr < npairs; ++pr) {
-        const int kt = 2 * pr;
+    int kt = 0;
+    if (fast) {
+        gload_fast(0, pa, pb);
+        sstore(0, pa, pb);
+        if (nk > 1) gload_fast(BK, qa, qb);
+        __syncthreads();
+        // the scheduling barriers keep the loads where they are written, ahead of the
+        // multiplication (left alone, the scheduler moves them down towards their use)
+        for (; kt + 3 < nk; kt += 2) {
+            gload_fast((kt + 2) * BK, pa, pb);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(0);
+            __builtin_amdgcn_sched_barrier(0);
+            sstore(1, qa, qb);
+            __syncthreads();
+            gload_fast((kt + 3) * BK, qa, qb);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(1);
+            __builtin_amdgcn_sched_barrier(0);
+            sstore(0, pa, pb);
+            __syncthreads();
+        }
+    } else {
+        gload(0, pa, pb);
+        sstore(0, pa, pb);
+        if (nk > 1) gload(BK, qa, qb);
+        __syncthreads();
+    }
+    for (; kt < nk; kt += 2) {
         // even tile kt from buffer 0; q holds tile kt+1
         if (kt + 2 < nk) gload((kt + 2) * BK, pa, pb);
         compute(0);
         if (kt + 1 < nk) sstore(1, qa, qb);
         __syncthreads();
-        // odd tile kt+1 from buffer 1 (all zeros past the end of K); p holds tile kt+2
+        // odd tile kt+1 from buffer 1; p holds tile kt+2
         if (kt + 3 < nk) gload((kt + 3) * BK, qa, qb);
         if (kt + 1 < nk) compute(1);
         if (kt + 2 < nk) sstore(0, pa, pb);
@@ -251,12 +297,13 @@ typedef float v4acc __attribute__((ext_vector_type(4)));
 // under 100 registers and 16 KiB of LDS, so five blocks fit a CU: 1280 slots for the
 // 1120 tiles of the 20 x 784 x 1024 backward product, which then run as one resident set
 // instead of a full round plus a mostly empty one.
+template <bool FAST>
 __global__ __launch_bounds__(256, 5) void mlp_gemm112_kernel(
     const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C, int M, int N,
     int K, int64_t lda, int64_t ldb, int64_t ldc, int64_t strideA, int64_t strideB,
     int64_t strideC, int a_vec_ok, int b_vec_ok, const int* __restrict__ a_batch,
     const int* __restrict__ c_batch) {
-    __shared__ float As[2][TK][LDA];
+    __shared__ float As[2][TK + 2][LDA];  // rows TK, TK+1: landing area for the 32 threads without an A element
     __shared__ float Bs[2][TK][LDB];
     const int t = threadIdx.x;
     const int lane = t & 63;
@@ -277,12 +324,27 @@ __global__ __launch_bounds__(256, 5) void mlp_gemm112_kernel(
     const bool a_inside = a_vec_ok && (m0 + TM <= M);
     const bool b_inside = b_vec_ok && (n0 + TN <= N);
     // A tile: 8 x 112 floats = 224 float4 (threads 0..223); B tile: 8 x 128 = 256 float4
-    const int ak = t / (TM / 4), am4 = (t % (TM / 4)) * 4;
+    const bool a_thread = t < TK * (TM / 4);
+    const int ak = a_thread ? t / (TM / 4) : 0, am4 = a_thread ? (t % (TM / 4)) * 4 : 0;
     const int bk = t >> 5, bn4 = (t & 31) * 4;
+    // every thread loads and stores (threads 224..255 repeat element 0 of the A tile and park
+    // it behind the tile), so neither the number of loads in flight nor the place of the
+    // load in the instruction stream depends on the thread: a store under a per-thread
+    // condition would pull its load in right before it
+    float* a_dst = a_thread ? &As[0][ak][am4] : &As[0][TK][0] + (t - TK * (TM / 4)) * 4;
+    // uniform base (row k0 of the operand) plus a 32-bit per-thread byte offset
+    const uint32_t a_off = (uint32_t)(((int64_t)ak * lda + m0 + am4) * 4);
+    const uint32_t b_off = (uint32_t)(((int64_t)bk * ldb + n0 + bn4) * 4);
+    auto gload_fast = [&](int k0, v4f& ra, v4f& rb) {
+        const char* abase = reinterpret_cast<const char*>(A + (int64_t)k0 * lda);
+        const char* bbase = reinterpret_cast<const char*>(B + (int64_t)k0 * ldb);
+        ra = *reinterpret_cast<const v4f*>(abase + a_off);
+        rb = *reinterpret_cast<const v4f*>(bbase + b_off);
+    };
     auto gload = [&](int k0, v4f& ra, v4f& rb) {
         const bool k_inside = k0 + TK <= K;
         ra = (v4f)(0.0f);
-        if (t < TK * (TM / 4)) {
+        if (a_thread) {
             const int gk = k0 + ak, gm = m0 + am4;
             const float* p = A + (int64_t)gk * lda + gm;
             if (a_inside && k_inside)
@@ -298,10 +360,11 @@ __global__ __launch_bounds__(256, 5) void mlp_gemm112_kernel(
             rb = (gk < K) ? load4(q, (int64_t)N - gn, b_vec_ok) : (v4f)(0.0f);
     };
     auto sstore = [&](int buf, const v4f& ra, const v4f& rb) {
-        if (t < TK * (TM / 4)) *reinterpret_cast<v4f*>(&As[buf][ak][am4]) = ra;
+        *reinterpret_cast<v4f*>(a_dst + buf * ((TK + 2) * LDA)) = ra;
         *reinterpret_cast<v4f*>(&Bs[buf][bk][bn4]) = rb;
     };
     auto compute = [&](int buf) {
+        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int ks = 0; ks < TK / 4; ++ks) {
             const int k = 4 * ks + kq;
@@ -314,26 +377,63 @@ __global__ __launch_bounds__(256, 5) void mlp_gemm112_kernel(
                 acc[bm][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b1, acc[bm][1], 0, 0, 0);
             }
         }
+        __builtin_amdgcn_s_setprio(0);
     };
 
-    // two k tiles deep, as in mlp_gemm_kernel
+    // two k tiles deep, as in mlp_gemm_kernel.  FAST (chosen by the host when every tile of
+    // the launch is interior, 16-byte addressable and K a whole number of k tiles): loads
+    // without guards and a steady-state loop without conditions, so that the wait before a
+    // stage's LDS stores covers that stage's loads only.
     const int nk = (K + TK - 1) / TK;
     v4f pa, pb, qa, qb;
-    gload(0, pa, pb);
-    sstore(0, pa, pb);
-    if (nk > 1) gload(TK, qa, qb);
-    __syncthreads();
-    const int npairs = (nk + 1) / 2;
-    for (int pr = 0; pr < npairs; ++pr) {
-        const int kt = 2 * pr;
-        if (kt + 2 < nk) gload((kt + 2) * TK, pa, pb);
+    int kt = 0;
+    if (FAST) {
+        // one register stage here: the accumulators leave room for no second one at five
+        // blocks per CU, and a tile fetched at the start of a multiplication has all of it
+        // (28 MFMAs per wave, five waves per SIMD) to arrive
+        gload_fast(0, pa, pb);
+        sstore(0, pa, pb);
+        __syncthreads();
+        // the scheduling barriers keep the loads where they are written, ahead of the
+        // multiplication that hides them (left alone, the scheduler moves them down to
+        // the wait in front of the LDS stores)
+        for (; kt + 2 < nk; kt += 2) {
+            gload_fast((kt + 1) * TK, pa, pb);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(0);
+            __builtin_amdgcn_sched_barrier(0);
+            sstore(1, pa, pb);
+            __syncthreads();
+            gload_fast((kt + 2) * TK, pa, pb);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(1);
+            __builtin_amdgcn_sched_barrier(0);
+            sstore(0, pa, pb);
+            __syncthreads();
+        }
+        // one or two tiles left; buffer 0 holds tile kt
+        if (kt + 1 < nk) gload_fast((kt + 1) * TK, pa, pb);
         compute(0);
-        if (kt + 1 < nk) sstore(1, qa, qb);
+        if (kt + 1 < nk) {
+            sstore(1, pa, pb);
+            __syncthreads();
+            compute(1);
+        }
+    } else {
+        gload(0, pa, pb);
+        sstore(0, pa, pb);
+        if (nk > 1) gload(TK, qa, qb);
         __syncthreads();
-        if (kt + 3 < nk) gload((kt + 3) * TK, qa, qb);
-        if (kt + 1 < nk) compute(1);
-        if (kt + 2 < nk) sstore(0, pa, pb);
-        __syncthreads();
+        for (; kt < nk; kt += 2) {
+            if (kt + 2 < nk) gload((kt + 2) * TK, pa, pb);
+            compute(0);
+            if (kt + 1 < nk) sstore(1, qa, qb);
+            __syncthreads();
+            if (kt + 3 < nk) gload((kt + 3) * TK, qa, qb);
+            if (kt + 1 < nk) compute(1);
+            if (kt + 2 < nk) sstore(0, pa, pb);
+            __syncthreads();
+        }
     }
 
     // result block: register r of lane l is element (row 4*(l/16) + r, column l % 16)
@@ -735,9 +835,15 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
         const int64_t pad128 = (int64_t)((din + BM - 1) / BM) * BM, pad112 = (int64_t)((din + TM - 1) / TM) * TM;
         if (pad112 < pad128) {
             dim3 grid((unsigned)((hid + TN - 1) / TN), (unsigned)((din + TM - 1) / TM), (unsigned)k);
-            hipLaunchKernelGGL(mlp_gemm112_kernel, grid, dim3(256), 0, ctx->stream, X, (const float*)H, G, din, hid,
-                               (int)rows, (int64_t)din, (int64_t)hid, (int64_t)hid, rows * (int64_t)din,
-                               rows * (int64_t)hid, d, a_ok, b_ok, unit_part, unit_row);
+            const bool all_fast = a_ok && b_ok && din % TM == 0 && hid % TN == 0 && rows % TK == 0;
+            if (all_fast)
+                hipLaunchKernelGGL(mlp_gemm112_kernel<true>, grid, dim3(256), 0, ctx->stream, X, (const float*)H, G,
+                                   din, hid, (int)rows, (int64_t)din, (int64_t)hid, (int64_t)hid,
+                                   rows * (int64_t)din, rows * (int64_t)hid, d, a_ok, b_ok, unit_part, unit_row);
+            else
+                hipLaunchKernelGGL(mlp_gemm112_kernel<false>, grid, dim3(256), 0, ctx->stream, X, (const float*)H, G,
+                                   din, hid, (int)rows, (int64_t)din, (int64_t)hid, (int64_t)hid,
+                                   rows * (int64_t)din, rows * (int64_t)hid, d, a_ok, b_ok, unit_part, unit_row);
         } else {
             dim3 grid((unsigned)((hid + BN - 1) / BN), (unsigned)((din + BM - 1) / BM), (unsigned)k);
             hipLaunchKernelGGL((mlp_gemm_kernel<true, EPI_STORE>), grid, dim3(256), 0, ctx->stream, X, (const float*)H, G,
