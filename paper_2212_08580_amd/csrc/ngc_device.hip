@@ -447,6 +447,52 @@ __global__ __launch_bounds__(256) void decode_kernel(const float* __restrict__ C
     }
 }
 
+// The same combination for long gradients (d of several hundred thousand): one thread per
+// V columns, so a wave reads 64*V consecutive floats of a message at a time, sixteen
+// messages in flight.  The sixteen partial sums of decode_kernel's lane groups are kept in
+// registers and added in the same order, so both kernels give the same bits.
+template <typename VT, int V>
+__global__ __launch_bounds__(256) void decode_wide_kernel(const float* __restrict__ Cl,
+                                                          float* __restrict__ g, int64_t d,
+                                                          decode_args args) {
+    const int64_t c = ((int64_t)blockIdx.x * 256 + threadIdx.x) * V;
+    if (c >= d) return;
+    double acc[16][V];
+#pragma unroll
+    for (int k = 0; k < 16; ++k)
+#pragma unroll
+        for (int v = 0; v < V; ++v) acc[k][v] = 0.0;
+    for (int t0 = 0; t0 < args.count; t0 += 16) {
+        VT m[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int t = t0 + k < args.count ? t0 + k : args.count - 1;  // repeats get weight 0
+            m[k] = *reinterpret_cast<const VT*>(Cl + (int64_t)args.idx[t] * d + c);
+        }
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            if (t0 + k < args.count) {  // block-uniform
+                const double a = args.a[t0 + k];
+                if constexpr (V == 1) {
+                    acc[k][0] += a * (double)m[k];
+                } else {
+#pragma unroll
+                    for (int v = 0; v < V; ++v) acc[k][v] += a * (double)m[k][v];
+                }
+            }
+        }
+    }
+    VT out;
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        double s = acc[0][v];
+#pragma unroll
+        for (int k = 1; k < 16; ++k) s += acc[k][v];
+        if constexpr (V == 1) out = (float)s; else out[v] = (float)s;
+    }
+    *reinterpret_cast<VT*>(g + c) = out;
+}
+
 // Decode with the decode vector taken from a row of the explicit decoding matrix
 // A_sigma held on the device: thread 0 compacts the non-zero entries of the row
 // into LDS, then the combination runs exactly as in decode_kernel (same order of
@@ -1196,7 +1242,17 @@ extern "C" int ngc_decode(ngc_ctx* ctx, int layer, const double* a_host, const f
     const float* Cl = C_dev + (size_t)layer * n * d;
     const int V = vec_width(d, Cl, g_dev);
     const int64_t gx = (d + 16 * V - 1) / (16 * V);
-    {
+    const int64_t gw = (d + 256 * V - 1) / (256 * V);
+    if (args.count > 0 && gw >= 2 * (int64_t)ctx->cu_count) {
+        // long gradient: enough column blocks to fill the chip with one thread per V columns
+        prof_scope ps(ctx, NGC_KERNEL_DECODE);
+        if (V == 4)
+            hipLaunchKernelGGL((decode_wide_kernel<v4f, 4>), dim3((unsigned)gw), dim3(256), 0, ctx->stream, Cl, g_dev, d, args);
+        else if (V == 2)
+            hipLaunchKernelGGL((decode_wide_kernel<v2f, 2>), dim3((unsigned)gw), dim3(256), 0, ctx->stream, Cl, g_dev, d, args);
+        else
+            hipLaunchKernelGGL((decode_wide_kernel<float, 1>), dim3((unsigned)gw), dim3(256), 0, ctx->stream, Cl, g_dev, d, args);
+    } else {
         prof_scope ps(ctx, NGC_KERNEL_DECODE);
         if (V == 4)
             hipLaunchKernelGGL((decode_kernel<v4f, 4>), dim3((unsigned)gx), dim3(256), 0, ctx->stream, Cl, g_dev, d, args);

@@ -378,7 +378,12 @@ def test_c3_full_size_sampled(ngc, torch_dev):
 # decode through the explicit decoding matrix A_sigma held on the device (small codes)
 # --------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("n,layers,kind,d", [(8, (0, 1, 3), "cyclic", 4096), (12, (0, 2, 5), "cyclic", 1002),
-                                             (8, (0, 1, 3, 7), "fracrep", 77)])
+                                             (8, (0, 1, 3, 7), "fracrep", 77),
+                                             # long gradients: ngc_decode takes its one-thread-per-column
+                                             # kernel (float4, float2 and float columns), which must give the
+                                             # bits of the lookup kernel's group-wise combination
+                                             (6, (0, 2), "cyclic", 524292), (6, (0, 2), "cyclic", 262146),
+                                             (5, (0, 1), "cyclic", 131073)])
 def test_decode_lookup_matches_oracle_and_solve_route(ngc, torch_dev, n, layers, kind, d):
     w = wl.C5.scaled(n=n, d=d, layers=layers)
     G_h = wl.partial_gradients(w, seed=3)
