@@ -480,7 +480,11 @@ def main():
     }
     if not args.no_cpu_baseline:
         ngc.ngc_sync(ctx)
-        out["cpu_baseline"] = cpu_baseline(w, wl, keep, theta_h, masks, min(args.cpu_parts, w.n))
+        cb = cpu_baseline(w, wl, keep, theta_h, masks, min(args.cpu_parts, w.n))
+        # the same algorithmic bytes (fp32 sizes) per sample as the GPU figure, and the ratio
+        cb["GBps"] = round(cb["value"] * 4.0 * w.d_in / 1e9, 2) if w.loss != wl.LOSS_MLP2 else None
+        cb["gpu_over_oracle"] = round(out["value"] / cb["value"], 1) if cb["value"] else None
+        out["cpu_baseline"] = cb
     ngc.ngc_destroy(ctx)
     print(json.dumps(out), flush=True)
 
