@@ -707,7 +707,15 @@ __global__ __launch_bounds__(256) void mlp_tail_reduce_kernel(const float* __res
     if (t >= T) return;
     const float* p = partial + (int64_t)j * chunks * T + t;
     float acc = p[0];
-    for (int c = 1; c < chunks; ++c) acc += p[(int64_t)c * T];
+    int c = 1;
+    for (; c + 8 <= chunks; c += 8) {  // eight loads in flight, added in index order
+        float a[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a[u] = p[(int64_t)(c + u) * T];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += a[u];
+    }
+    for (; c < chunks; ++c) acc += p[(int64_t)c * T];
     out[(int64_t)(unit_row ? unit_row[j] : j) * out_stride + t] = acc;
 }
 
