@@ -335,9 +335,10 @@ def test_c5_rounds(ngc, torch_dev):
 
 # --------------------------------------------------------------------------------------------
 # Full headline size (C3: 32 x 16384 x 4096, 8.6 GB) in the launch configuration the benchmark
-# times: sampled partitions against the oracle one by one, the rest through properties.
+# times: every partition's gradient against the oracle, element by element (the oracle needs
+# a few seconds for all of X), messages and decoding on top of the GPU's own G.
 # --------------------------------------------------------------------------------------------
-def test_c3_full_size_sampled(ngc, torch_dev):
+def test_c3_full_size_every_partition(ngc, torch_dev):
     torch = torch_dev
     w = wl.C3
     dev = torch.device("cuda:0")
@@ -345,7 +346,7 @@ def test_c3_full_size_sampled(ngc, torch_dev):
     th = wl.theta(w, 0)
     Xd = torch.empty((w.n, w.rows, w.d), dtype=torch.float32, device=dev)
     Yd = torch.empty((w.n, w.rows), dtype=torch.float32, device=dev)
-    sampled = {0: None, 13: None, 31: None}
+    sampled = {j: None for j in range(w.n)}
     from concurrent.futures import ThreadPoolExecutor
     with ThreadPoolExecutor(max_workers=8) as ex:
         for j, (X, Y) in enumerate(ex.map(lambda j: wl.partition(w, j, 0, truth), range(w.n))):
