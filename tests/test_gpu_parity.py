@@ -306,12 +306,12 @@ def test_c3_scaled_pipeline(ngc, torch_dev):
 
 # --------------------------------------------------------------------------------------------
 # C5: encode/decode stress, n = 64, d = 16384, layers (0,1,3,7,15,31), straggler count
-# Binomial(64, 0.2), decode vector solved per round (100 of the 1000 rounds here)
+# Binomial(64, 0.2), decode vector solved per round, all 1000 rounds
 # --------------------------------------------------------------------------------------------
 def test_c5_rounds(ngc, torch_dev):
     w = wl.C5
     G_h = wl.partial_gradients(w, 0)
-    masks = wl.binomial_count_masks(w, 100, seed=0)
+    masks = wl.binomial_count_masks(w, 1000, seed=0)
     p = Pipeline(ngc, torch_dev, w)
     try:
         p.G.copy_(torch_dev.from_numpy(G_h))
