@@ -910,8 +910,11 @@ struct stream_shape {
 static stream_shape pick_stream_shape(int64_t d) {
     if (d % 1024 == 0) {
         const int w = (int)(d / 1024);
+        // narrow rows: one float4 per lane and many waves per block rather than one wave with
+        // four; the kernel runs as fast and leaves a quarter of the block partials to be summed
+        if (w == 1 || w == 2) return {1, 16, 4 * w, false, false};
         if (w == 3) return {3, 5, 4, false, false};  // four waves fill a CU's eight wave slots, three do not
-        if (w == 1 || w == 2 || w == 4 || w == 6 || w == 8) return {4, 4, w, false, false};
+        if (w == 4 || w == 6 || w == 8) return {4, 4, w, false, false};
         if (w == 12 || w == 16) return {8, 2, w / 2, false, false};
     }
     if (d == 256) return {1, 16, 1, false, false};
@@ -995,7 +998,6 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
             } else if (!sh.ragged) {
                 if (sh.nv == 4) {
                     switch (sh.waves) {
-                        NGC_STREAM_CASE(4, 4, 1, false) NGC_STREAM_CASE(4, 4, 2, false)
                         NGC_STREAM_CASE(4, 4, 4, false) NGC_STREAM_CASE(4, 4, 6, false)
                         NGC_STREAM_CASE(4, 4, 8, false)
                     }
@@ -1004,7 +1006,10 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
                         NGC_STREAM_CASE(8, 2, 6, false) NGC_STREAM_CASE(8, 2, 8, false)
                     }
                 } else if (sh.nv == 1) {
-                    launch_stream<1, 16, 2, 1, false>(NGC_STREAM_ARGS);
+                    switch (sh.waves) {
+                        NGC_STREAM_CASE(1, 16, 1, false) NGC_STREAM_CASE(1, 16, 4, false)
+                        NGC_STREAM_CASE(1, 16, 8, false)
+                    }
                 } else if (sh.nv == 2) {
                     launch_stream<2, 8, 2, 1, false>(NGC_STREAM_ARGS);
                 } else if (sh.waves == 4) {
