@@ -84,60 +84,73 @@ __device__ __forceinline__ double dpp_max_step(double v) {
     return fmax(v, __builtin_bit_cast(double, other));
 }
 
-// maximum over the 64 lanes, result in every lane
-__device__ __forceinline__ double wave_max(double v) {
+// maximum over each group of G consecutive lanes (G = 8, 16, 32 or 64), result in every lane
+// of the group
+template <int G>
+__device__ __forceinline__ double group_max(double v, int lane) {
     v = dpp_max_step<0xB1>(v);   // quad_perm [1,0,3,2]
     v = dpp_max_step<0x4E>(v);   // quad_perm [2,3,0,1]
-    v = dpp_max_step<0x141>(v);  // row_half_mirror
-    v = dpp_max_step<0x140>(v);  // row_mirror
+    v = dpp_max_step<0x141>(v);  // row_half_mirror: groups of 8 done
+    if (G == 8) return v;
+    v = dpp_max_step<0x140>(v);  // row_mirror: rows of 16 done
+    if (G == 16) return v;
     const long long bits = __builtin_bit_cast(long long, v);
     const int lo = (int)(bits & 0xFFFFFFFFLL), hi = (int)(bits >> 32);
-    double m = -INFINITY;
+    double m[4];
 #pragma unroll
     for (int row = 0; row < 4; ++row) {
         const int l = __builtin_amdgcn_readlane(lo, row * 16);
         const int h = __builtin_amdgcn_readlane(hi, row * 16);
-        m = fmax(m, __builtin_bit_cast(double, ((long long)h << 32) | (unsigned int)l));
+        m[row] = __builtin_bit_cast(double, ((long long)h << 32) | (unsigned int)l);
     }
-    return m;
+    const double m01 = fmax(m[0], m[1]), m23 = fmax(m[2], m[3]);
+    if (G == 32) return lane < 32 ? m01 : m23;
+    return fmax(m01, m23);
 }
 
-// One wave per trial, lane = worker.  Word 0 of a worker's random stream decides
-// failure, word u its u-th task time rho - log(U)/lambda (counter = (trial, worker,
+// A group of G lanes per trial (G = the smallest of 8, 16, 32, 64 that holds the n workers,
+// so a wave runs 64 / G trials at once), lane = worker.  Word 0 of a worker's random stream
+// decides failure, word u its u-th task time rho - log(U)/lambda (counter = (trial, worker,
 // block, 0), key = seed; U = (word + 0.5) / 2^32).  For u = 1..top the u-th largest
 // completion time of u tasks over the workers (= time at which n-u+1 workers have
 // finished u tasks) is found by knocking out the current maximum u-1 times.
+template <int G>
 __global__ __launch_bounds__(256) void latency_sim_kernel(double* __restrict__ L,
                                                           double* __restrict__ Tmin, int n, int top,
                                                           double lam, double rho, double eps,
                                                           double gamma, double pe, uint32_t k0,
                                                           uint32_t k1, int64_t trials) {
+    constexpr int PER = 64 / G;  // trials per wave
     const int lane = threadIdx.x & 63;
+    const int worker = lane % G, sub = lane / G;
+    const unsigned long long gmask = (G == 64 ? ~0ull : ((1ull << G) - 1ull)) << (sub * G);
     const int64_t wave0 = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t nwaves = (int64_t)gridDim.x * 4;
     const double base = gamma + eps;
-    for (int64_t r = wave0; r < trials; r += nwaves) {
+    for (int64_t rw = wave0 * PER; rw < trials; rw += nwaves * PER) {  // wave-uniform trip count
+        const int64_t r = rw + sub;
+        const bool live = r < trials;  // groups past the end idle along
         uint32_t w[4];
-        philox4x32((uint32_t)r, (uint32_t)lane, 0u, 0u, k0, k1, w);
+        philox4x32((uint32_t)r, (uint32_t)worker, 0u, 0u, k0, k1, w);
         const bool failed = ((double)w[0] + 0.5) / 4294967296.0 < pe;
         double cs = 0.0, best = INFINITY;
         for (int u = 1; u <= top; ++u) {
-            if ((u & 3) == 0) philox4x32((uint32_t)r, (uint32_t)lane, (uint32_t)(u >> 2), 0u, k0, k1, w);
+            if ((u & 3) == 0) philox4x32((uint32_t)r, (uint32_t)worker, (uint32_t)(u >> 2), 0u, k0, k1, w);
             const double U = ((double)w[u & 3] + 0.5) / 4294967296.0;
             cs += rho - log(U) / lam;
             double v = failed ? INFINITY : base + cs;
-            if (lane >= n) v = -INFINITY;
+            if (worker >= n) v = -INFINITY;
             for (int kth = 1; kth < u; ++kth) {
-                const double m = wave_max(v);
-                const unsigned long long holders = __ballot(v == m);
+                const double m = group_max<G>(v, lane);
+                const unsigned long long holders = __ballot(v == m) & gmask;
                 const int first = __ffsll((long long)holders) - 1;
                 if (lane == first) v = -INFINITY;
             }
-            const double Lu = wave_max(v);
-            if (lane == 0) L[(int64_t)(u - 1) * trials + r] = Lu;
+            const double Lu = group_max<G>(v, lane);
+            if (worker == 0 && live) L[(int64_t)(u - 1) * trials + r] = Lu;
             best = fmin(best, Lu);
         }
-        if (Tmin && lane == 0) Tmin[r] = best;
+        if (Tmin && worker == 0 && live) Tmin[r] = best;
     }
 }
 
@@ -215,11 +228,23 @@ extern "C" int ngc_latency_simulate(void* hip_stream, int n, int smax, double la
     int dev = 0;
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return NGC_ERR_HIP;
-    const int64_t want = (trials + 3) / 4;
+    const int G = n <= 8 ? 8 : (n <= 16 ? 16 : (n <= 32 ? 32 : 64));  // lanes per trial
+    const int64_t want = (trials + 4 * (64 / G) - 1) / (4 * (64 / G));
     const int64_t cap = (int64_t)(prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256) * 16;
     const unsigned blocks = (unsigned)(want < cap ? want : cap);
-    hipLaunchKernelGGL(latency_sim_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, L_dev, Tngc_dev,
-                       n, smax + 1, lam, rho, eps, gamma, pe, (uint32_t)seed, (uint32_t)(seed >> 32), trials);
+#define NGC_LATENCY_LAUNCH(GG)                                                                             \
+    hipLaunchKernelGGL(latency_sim_kernel<GG>, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, L_dev, \
+                       Tngc_dev, n, smax + 1, lam, rho, eps, gamma, pe, (uint32_t)seed,                    \
+                       (uint32_t)(seed >> 32), trials)
+    if (G == 8)
+        NGC_LATENCY_LAUNCH(8);
+    else if (G == 16)
+        NGC_LATENCY_LAUNCH(16);
+    else if (G == 32)
+        NGC_LATENCY_LAUNCH(32);
+    else
+        NGC_LATENCY_LAUNCH(64);
+#undef NGC_LATENCY_LAUNCH
     return hipGetLastError() == hipSuccess ? NGC_OK : NGC_ERR_HIP;
 } catch (...) {
     return ngc_on_exception();

@@ -17,6 +17,8 @@ pytestmark = pytest.mark.gpu
     (5, 0, 1.0, 0.0, 0.0, 0.3, 0.2, 13),
     (64, 15, 2.0, 0.1, 0.01, 0.0, 0.1, (7 << 32) | 5),
     (33, 8, 0.7, 0.2, 0.0, 0.0, 0.0, 14),
+    (12, 5, 0.9, 0.3, 0.05, 0.1, 0.1, 15),          # 16 lanes per trial, four trials per wave
+    (20, 9, 0.6, 0.4, 0.0, 0.0, 0.08, 16),          # 32 lanes per trial
 ])
 def test_device_draws_equal_oracle_draws(ngc, n, smax, lam, rho, eps, gamma, pe, seed):
     import torch
