@@ -140,6 +140,7 @@ GRAD_SHAPES = [
     # the two-pass route (no single-pass shape)
     (3000, 2, 11), (7000, 2, 6), (13000, 2, 4), (54, 3, 100), (1002, 3, 40), (2050, 2, 17),
     (4094, 2, 9), (5002, 2, 7), (8190, 2, 5), (8194, 2, 3), (20000, 2, 3), (16388, 2, 2),
+    (1, 3, 40), (2, 2, 17), (5, 2, 33), (4, 2, 64), (16384, 1, 40),
 ]
 
 
