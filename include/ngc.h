@@ -113,7 +113,8 @@ int ngc_build_code(ngc_ctx* ctx, int kind, uint64_t seed);
 
 /* Shape of the 2-layer perceptron for NGC_LOSS_MLP2: theta is the concatenation
  * [W1 (d_in x hidden) | b1 (hidden) | W2 (hidden x classes) | b2 (classes)] and
- * its length must equal the context's d. */
+ * its length must equal the context's d.  Any d_in and hidden width; at most 16
+ * classes (ngc_partition_grads returns NGC_ERR_INVALID beyond that). */
 int ngc_set_mlp2_shape(ngc_ctx* ctx, int d_in, int hidden, int classes);
 
 /*

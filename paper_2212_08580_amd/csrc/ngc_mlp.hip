@@ -600,8 +600,8 @@ __global__ __launch_bounds__(256) void mlp_logits_kernel(
         if (q < classes) dZ2[my_row * classes + q] = z[q] * inv - (q == label ? 1.0f : 0.0f);
 }
 
-// Step 2b.  A block owns a run of rows of one partition; thread t owns hidden
-// units 4t..4t+3.  Per row it reads dZ2 (the same for the whole block), forms
+// Step 2b.  A block owns a run of rows of one partition and a slice of 1024 hidden
+// units (blockIdx.y); thread t owns units 4t..4t+3 of the slice.  Per row it reads dZ2 (the same for the whole block), forms
 // dH = dZ2 W2^T for its units, writes dZ1 = dH * [H > 0] over H and accumulates
 // dW2 += h dZ2, db1 += dZ1, db2 += dZ2 in registers: no exchange between threads.
 // Block partial layout = tail of theta: [db1 (hidden) | dW2 (hidden x classes) | db2 (classes)].
@@ -614,7 +614,7 @@ __global__ __launch_bounds__(256) void mlp_back_kernel(
     const int j = blockIdx.x / chunks, c = blockIdx.x % chunks;
     const int64_t r0 = (int64_t)c * rows_per_chunk;
     const int64_t r1 = rows < r0 + rows_per_chunk ? rows : r0 + rows_per_chunk;
-    const int h0 = 4 * t;
+    const int h0 = 4 * t + 1024 * blockIdx.y;  // blockIdx.y: 1024-unit slice of the hidden layer
     const int hleft = hidden - h0;  // may be <= 0
 
     float w2[4][NCP], dw2[4][NCP], db1[4], db2[NCP];
@@ -689,7 +689,7 @@ __global__ __launch_bounds__(256) void mlp_back_kernel(
                 if (q < classes) P[hidden + (int64_t)(h0 + e) * classes + q] = dw2[e][q];
         }
     }
-    if (t == 0) {
+    if (t == 0 && blockIdx.y == 0) {
 #pragma unroll
         for (int q = 0; q < NCP; ++q)
             if (q < classes) P[hidden + (int64_t)hidden * classes + q] = db2[q];
@@ -754,7 +754,7 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
     const int k = units;
     const int din = ctx->mlp_din, hid = ctx->mlp_hidden, cls = ctx->mlp_classes;
     const int64_t d = ctx->d;
-    if (hid > 1024) return ngc_fail(ctx, NGC_ERR_INVALID, "MLP hidden width above 1024 is not supported");
+    if (hid > 65535 * 1024) return ngc_fail(ctx, NGC_ERR_INVALID, "MLP hidden width too large");
     if (cls > 16) return ngc_fail(ctx, NGC_ERR_INVALID, "MLP with more than 16 classes is not supported");
     const int64_t total = (int64_t)k * rows;
     if (total > 0x7fffffffLL) return ngc_fail(ctx, NGC_ERR_INVALID, "too many rows");
@@ -768,7 +768,8 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
     // blocks of the backward head kernel: as many as are resident at once (its register count
     // allows 5, 3 or 2 blocks per CU for up to 4, 10 or 16 classes), so there is no second round
     const int back_per_cu = cls <= 4 ? 5 : (cls <= 10 ? 3 : 2);
-    int64_t chunks = std::max<int64_t>(1, (int64_t)ctx->cu_count * back_per_cu / k);
+    const int64_t slices = (hid + 1023) / 1024;  // the backward head kernel covers 1024 hidden units per block
+    int64_t chunks = std::max<int64_t>(1, (int64_t)ctx->cu_count * back_per_cu / (k * slices));
     int64_t rpc = (rows + chunks - 1) / chunks;
     chunks = (rows + rpc - 1) / rpc;
     const size_t h_floats = (((size_t)total * hid) + 63) / 64 * 64;
@@ -817,7 +818,7 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
     {   // 2. logits, softmax, dZ2; then dW2/db2/db1 partials and dZ1 over H
         const int hv = hid % 4 == 0;
         dim3 lgrid((unsigned)((total + 63) / 64));
-        dim3 grid((unsigned)(k * chunks));
+        dim3 grid((unsigned)(k * chunks), (unsigned)((hid + 1023) / 1024));  // y: 1024-unit hidden slices
 #define NGC_MLP_HEAD(NCP)                                                                              \
     hipLaunchKernelGGL((mlp_logits_kernel<NCP>), lgrid, dim3(256), 0, ctx->stream, (const float*)H, labels, W2, \
                        b2, dZ2, hid, cls, total, hv, rows, unit_part);                                 \

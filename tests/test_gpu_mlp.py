@@ -115,6 +115,8 @@ def check_blocks(w, X, Y, th, G, G_o):
     (2, 5, 784, 1024, 10),       # fewer rows than one K tile
     (2, 40, 256, 64, 5),         # d_in a multiple of 128: backward GEMM on 128-row tiles
     (1, 70, 300, 260, 7),        # both tile shapes ragged in every dimension
+    (2, 45, 64, 2048, 10),       # hidden layer wider than one 1024-unit slice of the backward kernel
+    (1, 33, 40, 1500, 4),        # ... and a ragged second slice
 ])
 def test_mlp_partition_gradients_match_oracle(ngc, n, rows, d_in, hidden, classes):
     import torch
