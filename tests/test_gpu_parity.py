@@ -364,14 +364,19 @@ def test_c3_full_size_every_partition(ngc, torch_dev):
             assert rel(G[j], g_o) <= TOL, (j, rel(G[j], g_o))
         assert np.all(np.isfinite(G))
         C = p.encode()
-        G64 = G.astype(np.float64)
-        # messages and decoding, given the GPU's own G (exact recovery: decode == sum_j g_j)
-        assert rel(C, coding.encode_layers(p.Bs, G64)) <= 1e-6
+        # messages and decoding against the oracle's own gradients (exact recovery: decode == sum_j g_j)
+        G_o = np.stack([sampled[j] for j in range(w.n)])
+        C_o = coding.encode_layers(p.Bs, G_o)
+        assert rel(C, C_o) <= TOL
+        full = G_o.sum(axis=0)
         masks = wl.bernoulli_masks(w, 20, seed=2)
         for m in masks:
             if m.sum() <= w.layers[-1]:
                 u, a, r, g = p.decode(m)
-                assert rel(g, G64.sum(axis=0)) <= TOL
+                u_o, a_o, g_o = coding.coded_gradient(p.Bs, w.layers, G_o, m)
+                assert u == u_o and np.array_equal(a != 0, a_o != 0)
+                kappa = coding.conditioning(a_o, C_o[u_o], full)
+                assert rel(g, full) <= max(TOL, 4 * 2.0 ** -24 * kappa)
     finally:
         p.close()
 
@@ -578,9 +583,22 @@ def test_c2_full_size_200_iterations(ngc, torch_dev):
         usage = np.zeros(len(w.layers) + 1, int)
         checked = 0
         loss0 = gradients.logistic_loss(X.reshape(-1, w.d), Y.reshape(-1), th0)
+        # the oracle's own run from the same start with the same masks: no number of it
+        # comes from the GPU (the per-iteration checks below evaluate the oracle at the GPU's
+        # theta_t instead, which pins each step; this pins the trajectory)
+        th_free = th0.astype(np.float64)
+        drift = 0.0
         for t in range(200):
             check = t < 3 or t % 10 == 0 or t == 199
             th_t = thd.cpu().numpy() if check else None
+            if check:
+                drift = max(drift, rel(th_t, th_free))
+            try:
+                _, _, g_free = coding.coded_gradient(p.Bs, w.layers,
+                                                     gradients.partial_gradients(w.loss, X, Y, th_free), masks[t])
+                th_free = gradients.gd_update(th_free, g_free, eta, w.m)
+            except coding.Undecodable:
+                pass
             try:
                 u, a = ngc.ngc_iteration(p.ctx, w.loss, Xd, Yd, thd, w.rows, masks[t], eta / w.m,
                                          p.G, p.C, p.g, w.n)
@@ -607,6 +625,10 @@ def test_c2_full_size_200_iterations(ngc, torch_dev):
                 assert rel(thd.cpu().numpy(), gradients.gd_update(th_t, g_o, eta, w.m)) <= 1e-6
                 checked += 1
         assert checked >= 20
+        final_drift = rel(thd.cpu().numpy(), th_free)
+        print("C2: theta of the GPU run against the oracle's own run: worst %.2e, after 200 iterations %.2e"
+              % (max(drift, final_drift), final_drift))
+        assert max(drift, final_drift) <= 1e-5
         loss1 = gradients.logistic_loss(X.reshape(-1, w.d), Y.reshape(-1), thd.cpu().numpy())
         assert loss1 < 0.5 * loss0                                # the run actually descends
         share = usage / 200.0
