@@ -246,7 +246,8 @@ def test_decode_rejects_bad_arguments_and_update_matches(ngc, torch_dev):
 
 # --------------------------------------------------------------------------------------------
 # C2 shrunk (logistic, n = 16, layers 0,1,3,7, Bernoulli(0.2) stragglers): a short descent run,
-# each iteration checked against the oracle evaluated at the GPU's own theta_t
+# each iteration checked against the oracle evaluated at the GPU's own theta_t, and the whole
+# trajectory against the oracle's own run from the same start
 # --------------------------------------------------------------------------------------------
 def test_c2_scaled_descent_with_stragglers(ngc, torch_dev):
     w = wl.C2.scaled(rows=515, name="C2-rows515")              # d = 1024, 16 partitions
@@ -257,8 +258,16 @@ def test_c2_scaled_descent_with_stragglers(ngc, torch_dev):
     try:
         Xd, Yd, thd = p.to_dev(X), p.to_dev(Y), p.to_dev(th0)
         eta, used, skipped = 1.0, set(), 0
+        th_free = th0.astype(np.float64)                      # the oracle's own run, no GPU number in it
         for t in range(12):
             th_t = thd.cpu().numpy()
+            assert rel(th_t, th_free) <= 1e-5
+            try:
+                _, _, g_free = coding.coded_gradient(p.Bs, w.layers,
+                                                     gradients.partial_gradients(w.loss, X, Y, th_free), masks[t])
+                th_free = gradients.gd_update(th_free, g_free, eta, w.m)
+            except coding.Undecodable:
+                pass
             ngc.ngc_partition_grads(p.ctx, w.loss, Xd, Yd, thd, w.rows, p.G)
             ngc.ngc_encode(p.ctx, p.G, -1, p.C)
             try:
@@ -277,6 +286,7 @@ def test_c2_scaled_descent_with_stragglers(ngc, torch_dev):
             assert rel(p.g.cpu().numpy(), g_o) <= TOL
             assert rel(thd.cpu().numpy(), gradients.gd_update(th_t, g_o, eta, w.m)) <= 1e-6
             used.add(u)
+        assert rel(thd.cpu().numpy(), th_free) <= 1e-5
         assert len(used) >= 2 and skipped <= 2
     finally:
         p.close()
