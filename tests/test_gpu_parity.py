@@ -245,6 +245,34 @@ def test_decode_rejects_bad_arguments_and_update_matches(ngc, torch_dev):
 
 
 # --------------------------------------------------------------------------------------------
+# C1 as a whole: coded gradient descent on the GPU, a straggler in most iterations, ends at the
+# least-squares solution that a library routine gives (a textbook endpoint, no oracle step in it)
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("kind", ["fracrep", "cyclic"])
+def test_c1_descent_reaches_the_least_squares_solution(ngc, torch_dev, kind):
+    w = wl.C1
+    X, Y = wl.dataset(w, 0, threads=1)
+    Xa, ya = X.reshape(-1, w.d).astype(np.float64), Y.reshape(-1).astype(np.float64)
+    th_ls = np.linalg.lstsq(Xa, ya, rcond=None)[0]
+    p = Pipeline(ngc, torch_dev, w, kind=kind)
+    try:
+        Xd, Yd, thd = p.to_dev(X), p.to_dev(Y), p.to_dev(wl.theta(w, 0))
+        rng = np.random.default_rng(4)
+        layers_used = set()
+        for t in range(120):
+            m = np.zeros(w.n, np.uint8)
+            if rng.random() < 0.7:
+                m[rng.integers(0, w.n)] = 1                       # one straggler: still decodable
+            u, a = ngc.ngc_iteration(p.ctx, w.loss, Xd, Yd, thd, w.rows, m, 1.0 / w.m, p.G, p.C, p.g, w.n)
+            layers_used.add(u)
+        ngc.ngc_sync(p.ctx)
+        assert layers_used == {0, 1}
+        assert rel(thd.cpu().numpy(), th_ls) <= 2e-5              # fp32 iterates, fp32 data
+    finally:
+        p.close()
+
+
+# --------------------------------------------------------------------------------------------
 # C2 shrunk (logistic, n = 16, layers 0,1,3,7, Bernoulli(0.2) stragglers): a short descent run,
 # each iteration checked against the oracle evaluated at the GPU's own theta_t, and the whole
 # trajectory against the oracle's own run from the same start
