@@ -245,6 +245,26 @@ def test_decode_rejects_bad_arguments_and_update_matches(ngc, torch_dev):
 
 
 # --------------------------------------------------------------------------------------------
+# closed forms at theta = 0, straight from the data (no oracle function in between):
+# least squares g_j = -X_j^T y_j, logistic g_j = -(1/2) sum_i y_i x_i
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("base,d,rows", [(wl.C3, 4096, 300), (wl.C2, 1024, 700), (wl.C3, 1002, 90),
+                                         (wl.C2, 5000, 64)])
+def test_gradients_at_zero_are_the_closed_forms(ngc, torch_dev, base, d, rows):
+    w = base.scaled(rows=rows, d=d, n=4, layers=(0,), name="zero")
+    X, Y = wl.dataset(w, seed=9, threads=1)
+    p = Pipeline(ngc, torch_dev, w, Bs=[np.eye(w.n)])
+    try:
+        G = p.grads(X, Y, np.zeros(d, np.float32))
+        for j in range(w.n):
+            xty = X[j].astype(np.float64).T @ Y[j].astype(np.float64)
+            want = -xty if w.loss == wl.LOSS_LSQ else -0.5 * xty
+            assert rel(G[j], want) <= 1e-5, (j, rel(G[j], want))
+    finally:
+        p.close()
+
+
+# --------------------------------------------------------------------------------------------
 # C1 as a whole: coded gradient descent on the GPU, a straggler in most iterations, ends at the
 # least-squares solution that a library routine gives (a textbook endpoint, no oracle step in it)
 # --------------------------------------------------------------------------------------------
