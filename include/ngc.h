@@ -95,6 +95,12 @@ int ngc_set_code(ngc_ctx* ctx, int layer, const double* B_host);
 /* Copy the layer's B (n x k fp64 row-major) to B_host_out. */
 int ngc_get_code(const ngc_ctx* ctx, int layer, double* B_host_out);
 
+/* The sizes the context was created with (any output pointer may be null), and the
+ * input width of the perceptron (0 until ngc_set_mlp2_shape).  For callers and bindings
+ * that want to check buffer sizes before handing raw pointers over. */
+int ngc_get_shape(const ngc_ctx* ctx, int* n_out, int* k_out, int* layers_out, int64_t* d_out,
+                  int* mlp_d_in_out);
+
 /*
  * Build all layers (Alg. 1).  NGC_CODE_CYCLIC: row i of the layer with
  * tolerance sigma is supported on columns {i..i+sigma} mod n (Lemma 2, with the

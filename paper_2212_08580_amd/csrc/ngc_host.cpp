@@ -143,6 +143,19 @@ extern "C" int ngc_get_code(const ngc_ctx* ctx, int layer, double* B_host_out) t
     return ngc_on_exception();
 }
 
+extern "C" int ngc_get_shape(const ngc_ctx* ctx, int* n_out, int* k_out, int* layers_out, int64_t* d_out,
+                             int* mlp_d_in_out) try {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (n_out) *n_out = ctx->n;
+    if (k_out) *k_out = ctx->k;
+    if (layers_out) *layers_out = ctx->L;
+    if (d_out) *d_out = ctx->d;
+    if (mlp_d_in_out) *mlp_d_in_out = ctx->mlp_din;
+    return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
+}
+
 extern "C" int ngc_set_mlp2_shape(ngc_ctx* ctx, int d_in, int hidden, int classes) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (d_in < 1 || hidden < 1 || classes < 2) return ngc_fail(ctx, NGC_ERR_INVALID, "bad MLP shape");

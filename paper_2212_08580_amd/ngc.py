@@ -33,7 +33,7 @@ NGC_KERNEL_NAMES = ("grad", "reduce", "encode", "decode", "update", "mlp", "prob
 NGC_KERNEL_COUNT = len(NGC_KERNEL_NAMES)
 
 EXPORTS = (
-    "ngc_create", "ngc_destroy", "ngc_set_code", "ngc_get_code", "ngc_build_code",
+    "ngc_create", "ngc_destroy", "ngc_set_code", "ngc_get_code", "ngc_get_shape", "ngc_build_code",
     "ngc_set_mlp2_shape", "ngc_partition_grads", "ngc_encode", "ngc_select_decode_vec",
     "ngc_select_decode_vec_first", "ngc_decode", "ngc_update", "ngc_iteration", "ngc_sync",
     "ngc_worker_task_count", "ngc_worker_schedule", "ngc_worker_grads", "ngc_worker_encode",
@@ -58,6 +58,8 @@ _lib.ngc_destroy.restype = None
 _lib.ngc_set_code.argtypes = [_vp, _i, _vp]
 _lib.ngc_get_code.argtypes = [_vp, _i, _vp]
 _lib.ngc_build_code.argtypes = [_vp, _i, _u64]
+_lib.ngc_get_shape.argtypes = [_vp, ctypes.POINTER(_i), ctypes.POINTER(_i), ctypes.POINTER(_i),
+                               ctypes.POINTER(_i64), ctypes.POINTER(_i)]
 _lib.ngc_set_mlp2_shape.argtypes = [_vp, _i, _i, _i]
 _lib.ngc_partition_grads.argtypes = [_vp, _i, _vp, _vp, _vp, _i64, _vp]
 _lib.ngc_encode.argtypes = [_vp, _vp, _i, _vp]
@@ -104,13 +106,40 @@ def _check(rc, ctx=None):
         raise NgcError(rc, detail)
 
 
-def _dev(t):
-    """Raw device address of a torch tensor (contiguous, on the GPU)."""
+def _dev(t, need=None, dtype=None):
+    """Raw device address of a torch tensor (contiguous, on the GPU).  With `need` the tensor
+    must hold at least that many elements, with `dtype` ("float32", "int32", "float64") be of
+    that type: the library gets a bare pointer and cannot check either."""
     if t is None:
         return None
     if not t.is_cuda or not t.is_contiguous():
         raise ValueError("device buffers must be contiguous GPU tensors")
+    if dtype is not None and str(t.dtype) != "torch." + dtype:
+        raise ValueError("device buffer has dtype %s, expected %s" % (t.dtype, dtype))
+    if need is not None and t.numel() < need:
+        raise ValueError("device buffer holds %d elements, the call needs %d" % (t.numel(), need))
     return ctypes.c_void_p(t.data_ptr())
+
+
+def ngc_get_shape(ctx):
+    """-> (n, k, layers, d, mlp_d_in) of the context."""
+    n, k, L, din = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0)
+    d = ctypes.c_int64(0)
+    _check(_lib.ngc_get_shape(ctx, ctypes.byref(n), ctypes.byref(k), ctypes.byref(L), ctypes.byref(d),
+                              ctypes.byref(din)), ctx)
+    return n.value, k.value, L.value, d.value, din.value
+
+
+def _data_args(ctx, loss, X, y, theta, rows):
+    """Checked pointers of the data arguments shared by the gradient calls."""
+    n, k, L, d, din = ngc_get_shape(ctx)
+    rows = int(rows)
+    mlp = int(loss) == NGC_LOSS_MLP2
+    width = din if mlp else d
+    if rows < 1:
+        raise ValueError("rows_per_part must be positive")
+    return (_dev(X, k * rows * max(width, 1), "float32"), _dev(y, k * rows, "int32" if mlp else "float32"),
+            _dev(theta, d, "float32"))
 
 
 def _host(a, dtype):
@@ -143,11 +172,15 @@ def ngc_destroy(ctx):
 
 def ngc_set_code(ctx, layer, B):
     B, p = _host(B, np.float64)
+    n, k = ngc_get_shape(ctx)[:2]
+    if B.size != n * k:
+        raise ValueError("B must be n x k")
     _check(_lib.ngc_set_code(ctx, int(layer), p), ctx)
 
 
-def ngc_get_code(ctx, layer, n, k=None):
-    out = np.empty((n, k or n), np.float64)
+def ngc_get_code(ctx, layer, n=None, k=None):
+    n, k = ngc_get_shape(ctx)[:2]                      # sizes come from the context
+    out = np.empty((n, k), np.float64)
     _check(_lib.ngc_get_code(ctx, int(layer), out.ctypes.data_as(ctypes.c_void_p)), ctx)
     return out
 
@@ -161,17 +194,20 @@ def ngc_set_mlp2_shape(ctx, d_in, hidden, classes):
 
 
 def ngc_partition_grads(ctx, loss, X, y, theta, rows_per_part, G):
-    _check(_lib.ngc_partition_grads(ctx, int(loss), _dev(X), _dev(y), _dev(theta),
-                                    int(rows_per_part), _dev(G)), ctx)
+    n, k, L, d, din = ngc_get_shape(ctx)
+    pX, py, pt = _data_args(ctx, loss, X, y, theta, rows_per_part)
+    _check(_lib.ngc_partition_grads(ctx, int(loss), pX, py, pt, int(rows_per_part),
+                                    _dev(G, k * d, "float32")), ctx)
 
 
 def ngc_encode(ctx, G, layer, C):
-    _check(_lib.ngc_encode(ctx, _dev(G), int(layer), _dev(C)), ctx)
+    n, k, L, d, din = ngc_get_shape(ctx)
+    _check(_lib.ngc_encode(ctx, _dev(G, k * d, "float32"), int(layer), _dev(C, L * n * d, "float32")), ctx)
 
 
 def _select(fn, ctx, mask, n):
     mask, pm = _host(mask, np.uint8)
-    if mask.size != n:
+    if n != ngc_get_shape(ctx)[0] or mask.size != n:
         raise ValueError("mask must have n entries")
     a = np.zeros(n, np.float64)
     layer = ctypes.c_int(-1)
@@ -192,7 +228,10 @@ def ngc_select_decode_vec_first(ctx, mask, n):
 
 def ngc_decode(ctx, layer, a, C, g):
     a, pa = _host(a, np.float64)
-    _check(_lib.ngc_decode(ctx, int(layer), pa, _dev(C), _dev(g)), ctx)
+    n, k, L, d, din = ngc_get_shape(ctx)
+    if a.size != n:
+        raise ValueError("the decode vector must have n entries")
+    _check(_lib.ngc_decode(ctx, int(layer), pa, _dev(C, L * n * d, "float32"), _dev(g, d, "float32")), ctx)
 
 
 def ngc_worker_task_count(ctx):
@@ -209,21 +248,35 @@ def ngc_worker_schedule(ctx, worker):
     return [int(p) for p in parts[:cnt.value]]
 
 
+def _worker_rows(ctx):
+    """Rows of W: n workers x (tasks x partitions per task)."""
+    n, k = ngc_get_shape(ctx)[:2]
+    return n * ngc_worker_task_count(ctx) * (k // n)
+
+
 def ngc_worker_grads(ctx, loss, X, y, theta, rows_per_part, progress, W):
     progress, pp = _host(progress, np.int32)
-    _check(_lib.ngc_worker_grads(ctx, int(loss), _dev(X), _dev(y), _dev(theta), int(rows_per_part),
-                                 pp, _dev(W)), ctx)
+    n, k, L, d, din = ngc_get_shape(ctx)
+    if progress.size != n:
+        raise ValueError("progress must have n entries")
+    pX, py, pt = _data_args(ctx, loss, X, y, theta, rows_per_part)
+    _check(_lib.ngc_worker_grads(ctx, int(loss), pX, py, pt, int(rows_per_part), pp,
+                                 _dev(W, _worker_rows(ctx) * d, "float32")), ctx)
 
 
 def ngc_worker_encode(ctx, W, progress, C):
     progress, pp = _host(progress, np.int32)
-    _check(_lib.ngc_worker_encode(ctx, _dev(W), pp, _dev(C)), ctx)
+    n, k, L, d, din = ngc_get_shape(ctx)
+    if progress.size != n:
+        raise ValueError("progress must have n entries")
+    _check(_lib.ngc_worker_encode(ctx, _dev(W, _worker_rows(ctx) * d, "float32"), pp,
+                                  _dev(C, L * n * d, "float32")), ctx)
 
 
 def ngc_select_from_progress(ctx, progress, n, min_layer=0):
     """-> (layer, mask [n] uint8, a [n] fp64, residual)."""
     progress, pp = _host(progress, np.int32)
-    if progress.size != n:
+    if n != ngc_get_shape(ctx)[0] or progress.size != n:
         raise ValueError("progress must have n entries")
     a = np.zeros(n, np.float64)
     mask = np.ones(n, np.uint8)
@@ -255,7 +308,8 @@ def ngc_latency_cdf_ngc(n, smax, lam, rho, eps, gamma, pe, t):
 def ngc_latency_simulate(hip_stream, n, smax, lam, rho, eps, gamma, pe, seed, trials, L, Tngc=None):
     _check(_lib.ngc_latency_simulate(ctypes.c_void_p(int(hip_stream)), int(n), int(smax), float(lam),
                                      float(rho), float(eps), float(gamma), float(pe), int(seed),
-                                     int(trials), _dev(L), _dev(Tngc)))
+                                     int(trials), _dev(L, (int(smax) + 1) * int(trials), "float64"),
+                                     _dev(Tngc, int(trials), "float64")))
 
 
 def ngc_build_decoding_table(ctx, layer):
@@ -266,46 +320,65 @@ def ngc_build_decoding_table(ctx, layer):
 
 def ngc_decoding_row_index(ctx, layer, mask):
     mask, pm = _host(mask, np.uint8)
+    if mask.size != ngc_get_shape(ctx)[0]:
+        raise ValueError("mask must have n entries")
     row = ctypes.c_int64(-1)
     _check(_lib.ngc_decoding_row_index(ctx, int(layer), pm, ctypes.byref(row)), ctx)
     return row.value
 
 
-def ngc_get_decoding_row(ctx, layer, row, n):
-    a = np.zeros(n, np.float64)
+def ngc_get_decoding_row(ctx, layer, row, n=None):
+    a = np.zeros(ngc_get_shape(ctx)[0], np.float64)
     _check(_lib.ngc_get_decoding_row(ctx, int(layer), int(row), a.ctypes.data_as(ctypes.c_void_p)), ctx)
     return a
 
 
 def ngc_decode_lookup(ctx, layer, mask, C, g):
     mask, pm = _host(mask, np.uint8)
-    _check(_lib.ngc_decode_lookup(ctx, int(layer), pm, _dev(C), _dev(g)), ctx)
+    n, k, L, d, din = ngc_get_shape(ctx)
+    if mask.size != n:
+        raise ValueError("mask must have n entries")
+    _check(_lib.ngc_decode_lookup(ctx, int(layer), pm, _dev(C, L * n * d, "float32"), _dev(g, d, "float32")), ctx)
 
 
 def ngc_iteration(ctx, loss, X, y, theta, rows_per_part, mask, scale, G, C, g, n):
     """-> (layer, a [n] fp64)."""
     mask, pm = _host(mask, np.uint8)
+    n_ctx, k, L, d, din = ngc_get_shape(ctx)
+    if n != n_ctx or mask.size != n:
+        raise ValueError("mask must have n entries")
     a = np.zeros(n, np.float64)
     layer = ctypes.c_int(-1)
-    _check(_lib.ngc_iteration(ctx, int(loss), _dev(X), _dev(y), _dev(theta), int(rows_per_part), pm,
-                              float(scale), _dev(G), _dev(C), _dev(g), ctypes.byref(layer),
+    pX, py, pt = _data_args(ctx, loss, X, y, theta, rows_per_part)
+    _check(_lib.ngc_iteration(ctx, int(loss), pX, py, pt, int(rows_per_part), pm,
+                              float(scale), _dev(G, k * d, "float32"), _dev(C, L * n * d, "float32"),
+                              _dev(g, d, "float32"), ctypes.byref(layer),
                               a.ctypes.data_as(ctypes.c_void_p)), ctx)
     return layer.value, a
 
 
 def ngc_update(ctx, theta, g, scale):
-    _check(_lib.ngc_update(ctx, _dev(theta), _dev(g), float(scale)), ctx)
+    d = ngc_get_shape(ctx)[3]
+    _check(_lib.ngc_update(ctx, _dev(theta, d, "float32"), _dev(g, d, "float32"), float(scale)), ctx)
 
 
 def ngc_sync(ctx):
     _check(_lib.ngc_sync(ctx), ctx)
 
 
+def _bytes(t):
+    return t.numel() * t.element_size()
+
+
 def ngc_probe_copy(ctx, src, dst, nbytes):
+    if int(nbytes) > min(_bytes(src), _bytes(dst)):
+        raise ValueError("nbytes exceeds a buffer")
     _check(_lib.ngc_probe_copy(ctx, _dev(src), _dev(dst), int(nbytes)), ctx)
 
 
 def ngc_probe_read(ctx, src, nbytes):
+    if int(nbytes) > _bytes(src):
+        raise ValueError("nbytes exceeds the buffer")
     _check(_lib.ngc_probe_read(ctx, _dev(src), int(nbytes)), ctx)
 
 

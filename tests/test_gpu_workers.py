@@ -167,11 +167,24 @@ def test_worker_calls_reject_bad_arguments(ngc):
             ngc.ngc_worker_grads(ctx, 0, z, z, z, 1, [1, 1, 1, 1], z)
         assert e.value.code == ngc.NGC_ERR_STATE
         ngc.ngc_build_code(ctx, ngc.NGC_CODE_FRACREP, 0)
+        lab = torch.zeros(16, dtype=torch.int32, device=dev)
         with pytest.raises(ngc.NgcError) as e:                       # perceptron loss without its shape
-            ngc.ngc_worker_grads(ctx, 2, z, z, z, 1, [1, 1, 1, 1], z)
+            ngc.ngc_worker_grads(ctx, 2, z, lab, z, 1, [1, 1, 1, 1], z)
         assert e.value.code == ngc.NGC_ERR_STATE
         with pytest.raises(ngc.NgcError):
             ngc.ngc_worker_grads(ctx, 3, z, z, z, 1, [1, 1, 1, 1], z)    # no such loss
+        # the binding checks what the library cannot see behind a bare pointer
+        short = torch.zeros(100, dtype=torch.float32, device=dev)
+        with pytest.raises(ValueError):
+            ngc.ngc_worker_grads(ctx, 0, z, z, z, 1, [1, 1, 1, 1], short)   # W too small
+        with pytest.raises(ValueError):
+            ngc.ngc_worker_grads(ctx, 0, z, z, z, 1, [1, 1, 1], z)          # progress of the wrong length
+        with pytest.raises(ValueError):
+            ngc.ngc_partition_grads(ctx, 0, z, z.double(), z, 1, z)         # labels of the wrong type
+        with pytest.raises(ValueError):
+            ngc.ngc_partition_grads(ctx, 0, short, z, z, 1, z)              # X too small for k x rows x d
+        with pytest.raises(ValueError):
+            ngc.ngc_decode(ctx, 0, np.ones(3), z, z)                        # decode vector of the wrong length
         with pytest.raises(ngc.NgcError):
             ngc.ngc_worker_grads(ctx, 0, z, z, z, 1, [1, -1, 1, 1], z)
     finally:

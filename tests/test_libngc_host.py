@@ -25,6 +25,21 @@ def test_library_exports_every_declared_symbol(ngc):
         assert hasattr(lib, name), name
 
 
+def test_shape_query_returns_what_the_context_was_created_with(ngc):
+    d = 8 * 6 + 6 + 6 * 3 + 3
+    ctx = ngc.ngc_create(6, 12, [0, 2, 5], d)
+    try:
+        assert ngc.ngc_get_shape(ctx) == (6, 12, 3, d, 0)
+        ngc.ngc_set_mlp2_shape(ctx, 8, 6, 3)
+        assert ngc.ngc_get_shape(ctx) == (6, 12, 3, d, 8)
+        with pytest.raises(ValueError):
+            ngc.ngc_set_code(ctx, 1, np.eye(6))                  # B must be n x k
+        with pytest.raises(ValueError):
+            ngc.ngc_select_decode_vec(ctx, np.zeros(5, np.uint8), 5)   # mask of the wrong length
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
 def test_create_rejects_bad_arguments(ngc):
     bad = [
         dict(n=4, k=5, layers=[0, 1], d=8),          # k != n (Sec. II-C)
