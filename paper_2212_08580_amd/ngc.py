@@ -121,13 +121,22 @@ def _dev(t, need=None, dtype=None):
     return ctypes.c_void_p(t.data_ptr())
 
 
+_shapes = {}   # context address -> shape, so that the checks cost no library call per use
+
+
 def ngc_get_shape(ctx):
     """-> (n, k, layers, d, mlp_d_in) of the context."""
+    key = ctx.value if isinstance(ctx, ctypes.c_void_p) else None
+    if key in _shapes:
+        return _shapes[key]
     n, k, L, din = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0)
     d = ctypes.c_int64(0)
     _check(_lib.ngc_get_shape(ctx, ctypes.byref(n), ctypes.byref(k), ctypes.byref(L), ctypes.byref(d),
                               ctypes.byref(din)), ctx)
-    return n.value, k.value, L.value, d.value, din.value
+    shape = (n.value, k.value, L.value, d.value, din.value)
+    if key is not None:
+        _shapes[key] = shape
+    return shape
 
 
 def _data_args(ctx, loss, X, y, theta, rows):
@@ -167,6 +176,7 @@ def ngc_create(n, k, layers, d, hip_stream=0):
 
 
 def ngc_destroy(ctx):
+    _shapes.pop(getattr(ctx, "value", None), None)
     _lib.ngc_destroy(ctx)
 
 
@@ -190,6 +200,7 @@ def ngc_build_code(ctx, kind, seed):
 
 
 def ngc_set_mlp2_shape(ctx, d_in, hidden, classes):
+    _shapes.pop(getattr(ctx, "value", None), None)
     _check(_lib.ngc_set_mlp2_shape(ctx, int(d_in), int(hidden), int(classes)), ctx)
 
 
