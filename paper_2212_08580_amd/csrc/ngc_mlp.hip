@@ -4,9 +4,9 @@
 //
 // Three device steps, all partitions at once:
 //   1. H = relu(X W1 + b1)                 fp32 MFMA GEMM, bias + ReLU in the epilogue
-//   2. per row: Z2 = H W2 + b2, P = softmax(Z2), dZ2 = P - onehot(label);
-//      dW2 += H^T dZ2, db2 += dZ2; dZ1 = (dZ2 W2^T) * [H > 0] written over H;
-//      db1 += dZ1                          one pass over H, block partials
+//   2. per row: Z2 = H W2 + b2, P = softmax(Z2), dZ2 = P - onehot(label)   (one read of H);
+//      then dW2 += H^T dZ2, db2 += dZ2; dZ1 = (dZ2 W2^T) * [H > 0] written over H;
+//      db1 += dZ1                          (one read and one write of H, block partials)
 //   3. dW1_j = X_j^T dZ1_j                 fp32 MFMA GEMM per partition, written into G
 // and a fixed-order sum of the block partials of step 2 into the tail of G.
 //
