@@ -2,8 +2,8 @@
  * libngc -- nested gradient coding (NGC) on one AMD Instinct MI355X (gfx950).
  *
  * One GPU plays all n workers of the coded distributed gradient descent of
- * Sec. II-C: the data matrix is split into k = n row blocks, block j yields the
- * partial gradient g_j, worker i sends the linear combination
+ * Sec. II-C: the data matrix is split into k row blocks (k = n, or k = c*n with
+ * c blocks per atomic task), block j yields the partial gradient g_j, worker i sends the linear combination
  * c_i = sum_j B_sigma[i][j] g_j under the component code sigma chosen for this
  * iteration (Sec. III, Defs. 1-2), and the main node recovers the full gradient
  * sum_j g_j = sum_{i in responders} a_i c_i with a decode vector a that
@@ -19,9 +19,10 @@
  *    only its private workspace (block partials, uploaded code tables).
  *  - Device work is enqueued on the HIP stream given to ngc_create() and is
  *    asynchronous; outputs are fully overwritten, never accumulated into.
- *  - ngc_create, ngc_set_code, ngc_build_code, ngc_get_code,
- *    ngc_select_decode_vec, ngc_destroy, ngc_strerror touch no device state and
- *    work on a machine without a GPU.
+ *  - ngc_create, ngc_set_code, ngc_build_code, ngc_get_code, ngc_get_shape,
+ *    the ngc_select_* calls, the worker schedule and decoding-table queries,
+ *    the closed-form latency calls, ngc_destroy and ngc_strerror touch no
+ *    device state and work on a machine without a GPU.
  *  - All matrices are row-major and dense unless stated otherwise.  Device data
  *    is fp32; code matrices and decode vectors are fp64 on the host.
  *  - Calls on one context must not overlap in time from several host threads.
