@@ -1,0 +1,84 @@
+"""Property pins for the oracle on randomly drawn small codes (hypothesis): Def. 1 by brute
+force over every tolerated straggler set, Def. 2, exact recovery of the sum of the partial
+gradients from every sufficient layer, and agreement of the library's host-side selection
+with the oracle's on the same code."""
+import itertools
+
+import numpy as np
+from hypothesis import given, settings, strategies as st
+
+from oracle import codes, coding
+
+
+@st.composite
+def small_nested_code(draw):
+    n = draw(st.integers(min_value=2, max_value=8))
+    extra = draw(st.sets(st.integers(min_value=1, max_value=n - 1), max_size=3))
+    layers = [0] + sorted(extra)
+    seed = draw(st.integers(min_value=0, max_value=2 ** 16))
+    return n, layers, seed
+
+
+@settings(max_examples=30, deadline=None)
+@given(small_nested_code())
+def test_every_tolerated_straggler_set_decodes_to_the_plain_sum(case):
+    n, layers, seed = case
+    Bs = codes.nested_code(n, layers, "cyclic", seed=seed, draws=2)
+    rng = np.random.default_rng(seed)
+    G = rng.standard_normal((n, 5))
+    full = G.sum(axis=0)
+    for u, (B, sigma) in enumerate(zip(Bs, layers)):
+        assert np.count_nonzero(B, axis=1).tolist() == [sigma + 1] * n          # load (k/n)(sigma+1)
+        if u:
+            assert np.all((Bs[u - 1] != 0) <= (B != 0))                         # Def. 2
+        C = coding.encode(B, G)
+        for s in range(sigma + 1):
+            for out in itertools.combinations(range(n), s):
+                mask = np.zeros(n, np.uint8)
+                mask[list(out)] = 1
+                a, resid = coding.decode_vector(B, mask)
+                assert resid < 1e-8 and np.all(a[mask == 1] == 0.0)
+                assert np.allclose(coding.decode(a, C), full, rtol=0, atol=1e-7 * (1 + np.abs(a).sum()))
+    # the layer rule picks the cheapest sufficient layer
+    for s in range(n + 1):
+        mask = np.zeros(n, np.uint8)
+        mask[:s] = 1
+        if s > layers[-1]:
+            try:
+                coding.select_layer(layers, mask)
+                raise AssertionError("more stragglers than the code tolerates must not decode")
+            except coding.Undecodable:
+                pass
+        else:
+            u = coding.select_layer(layers, mask)
+            assert layers[u] >= s and (u == 0 or layers[u - 1] < s)
+
+
+@settings(max_examples=20, deadline=None)
+@given(small_nested_code(), st.integers(min_value=0, max_value=2 ** 16))
+def test_library_selection_agrees_with_the_oracle_on_the_same_code(ngc, case, mask_seed):
+    n, layers, seed = case
+    Bs = codes.nested_code(n, layers, "cyclic", seed=seed, draws=2)
+    ctx = ngc.ngc_create(n, n, layers, 8)
+    try:
+        for u, B in enumerate(Bs):
+            ngc.ngc_set_code(ctx, u, B)
+        rng = np.random.default_rng(mask_seed)
+        for _ in range(6):
+            mask = (rng.random(n) < 0.3).astype(np.uint8)
+            try:
+                u_o = coding.select_layer(layers, mask)
+            except coding.Undecodable:
+                try:
+                    ngc.ngc_select_decode_vec(ctx, mask, n)
+                    raise AssertionError("the library decoded what the oracle calls undecodable")
+                except ngc.NgcError as e:
+                    assert e.code == ngc.NGC_ERR_UNDECODABLE
+                continue
+            a_o, _ = coding.decode_vector(Bs[u_o], mask)
+            u, a, resid = ngc.ngc_select_decode_vec(ctx, mask, n)
+            assert u == u_o and resid < 1e-8
+            assert np.array_equal(a != 0, a_o != 0)
+            assert np.allclose(a, a_o, rtol=0, atol=1e-8 * (1 + np.abs(a_o).max()))
+    finally:
+        ngc.ngc_destroy(ctx)
