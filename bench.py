@@ -10,6 +10,7 @@ HBM before the timed region.  Prints ONE JSON line.
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3|C2|C1] [--no-cpu-baseline]
 """
 import argparse
+import gc
 import json
 import os
 import sys
@@ -125,6 +126,16 @@ def bench_codec(args, w, wl, ngc, torch, np):
         step(t)
     prof_d = ngc.ngc_profile_read(ctx)
     ngc.ngc_profile_enable(ctx, False)
+    # the same K rounds twice more without event records: K rounds last tens of milliseconds,
+    # so one scheduling stall of the host thread shows in a single region's time
+    repeats = []
+    for _ in range(2):
+        torch.cuda.synchronize()
+        tr = time.perf_counter()
+        for t in range(W, W + K):
+            step(t)
+        torch.cuda.synchronize()
+        repeats.append(round((time.perf_counter() - tr) / K * 1e3, 4))
     # batched: the decode vectors of all rounds chosen beforehand, then encode + decode of every
     # round queued back to back (what the device sustains once the host is out of the loop)
     chosen = [ngc.ngc_select_decode_vec(ctx, masks[t], w.n)[:2] for t in range(W, W + K)]
@@ -154,6 +165,7 @@ def bench_codec(args, w, wl, ngc, torch, np):
         "stages": {"encode_ms": round(enc_ms, 4), "encode_GBps": round(achieved, 1),
                    "decode_ms": round(dec_ms, 4),
                    "decode_GBps": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
+                   "round_ms_repeats": repeats,
                    "batched_ms_per_round": round(batched / K * 1e3, 4),
                    "batched_GBps": round((enc_bytes + dec_bytes) * K / batched / 1e9, 1)},
     }
@@ -328,6 +340,11 @@ def main():
         sys.exit(2)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    # With torch imported a full pass of the interpreter's cycle collector takes tens of
+    # milliseconds, as long as a thousand encode/decode rounds; the objects alive now are set
+    # aside so that a pass triggered inside a timed region only looks at what the loop made.
+    gc.collect()
+    gc.freeze()
     if args.mode == "latency":
         return bench_latency(args, ngc, torch, np)
     w = wl.CONFIGS[args.workload]

@@ -61,6 +61,11 @@ static void install_layer(ngc_ctx* ctx, int layer, const double* B) {
     lc.A_stale = true;
     lc.B.assign(B, B + (size_t)ctx->n * ctx->k);
     compress_layer(lc, ctx->n, ctx->k);
+    lc.a0.assign(ctx->n, 0.0);
+    lc.N.assign((size_t)ctx->n * ctx->n, 0.0);
+    double full_resid = 1.0;
+    lc.q = ngc_null_factor(lc.B.data(), ctx->n, ctx->k, lc.a0.data(), lc.N.data(), &full_resid);
+    lc.null_ok = full_resid <= 1e-9;
     lc.set = true;
     ctx->code_dirty = true;
     ctx->wtab_dirty = true;
@@ -344,6 +349,20 @@ extern "C" int ngc_build_code(ngc_ctx* ctx, int kind, uint64_t seed) try {
     return ngc_on_exception();
 }
 
+void ngc_layer_decode_vec(const ngc_ctx* ctx, int layer, const int* rows, int ns, double* a_out,
+                          double* resid) {
+    const ngc_layer_code& lc = ctx->code[layer];
+    const int n = ctx->n, k = ctx->k;
+    const int nt = n - ns, rank = n - lc.q;
+    // operation counts of the two factorisations: n_S x k to rank `rank` against q x |T|
+    const long direct = (long)ns * k * std::min(ns, rank);
+    const long via_null = (long)lc.q * nt * nt + (long)ns * lc.q;
+    if (lc.null_ok && via_null < direct)
+        ngc_min_norm_decode_null(lc.B.data(), n, k, lc.a0.data(), lc.N.data(), lc.q, rows, ns, a_out, resid);
+    else
+        ngc_min_norm_decode(lc.B.data(), n, k, rows, ns, a_out, resid);
+}
+
 static int select_impl(const ngc_ctx* ctx, const uint8_t* mask, int* layer_out, double* a_out,
                        double* residual_out, bool first_only) {
     if (!ctx) return NGC_ERR_INVALID;
@@ -365,7 +384,7 @@ static int select_impl(const ngc_ctx* ctx, const uint8_t* mask, int* layer_out, 
     for (int i = 0; i < n && ns < want; ++i)
         if (!mask[i]) rows[ns++] = i;
     double resid = 0.0;
-    ngc_min_norm_decode(ctx->code[u].B.data(), n, ctx->k, rows, ns, a_out, &resid);
+    ngc_layer_decode_vec(ctx, u, rows, ns, a_out, &resid);
     if (residual_out) *residual_out = resid;
     if (!(resid <= 1e-6)) return ngc_fail(ctx, NGC_ERR_SINGULAR, "decode residual above tolerance");
     return NGC_OK;
@@ -470,7 +489,7 @@ extern "C" int ngc_select_from_progress(const ngc_ctx* ctx, const int* progress,
         *layer_out = u;
         for (int t = 0; t < ns; ++t) mask_out[rows[t]] = 0;
         double resid = 0.0;
-        ngc_min_norm_decode(ctx->code[u].B.data(), n, ctx->k, rows, ns, a_out, &resid);
+        ngc_layer_decode_vec(ctx, u, rows, ns, a_out, &resid);
         if (residual_out) *residual_out = resid;
         if (!(resid <= 1e-6)) return ngc_fail(ctx, NGC_ERR_SINGULAR, "decode residual above tolerance");
         return NGC_OK;

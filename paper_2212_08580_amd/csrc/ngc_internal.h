@@ -27,6 +27,12 @@ struct ngc_layer_code {
     std::vector<int> rowptr;    // n + 1
     std::vector<int> col;
     std::vector<double> coef;
+    // full-response factor for decode-vector selection (ngc_solve.cpp): least-norm a0 with
+    // a0^T B = 1^T and an orthonormal basis N (n x q, row-major) of {v : v^T B = 0};
+    // null_ok is false when B has no exact full-response solution
+    std::vector<double> a0, N;
+    int q = 0;
+    bool null_ok = false;
 };
 
 struct ngc_profile_rec {
@@ -100,3 +106,14 @@ int ngc_make_worker_plan(const ngc_ctx* ctx, ngc_worker_plan& plan);
 // zero outside rows.  Returns the numerical rank found; resid = max_j |a^T B - 1|.
 int ngc_min_norm_decode(const double* B, int n, int k, const int* rows, int ns, double* a_out,
                         double* resid);
+// Full-response factor of B (n x k): a0 [n], N [n][q] row-major; returns q = n - rank(B).
+// resid = max_j |a0^T B - 1|.
+int ngc_null_factor(const double* B, int n, int k, double* a0, double* N, double* resid);
+// The same vector as ngc_min_norm_decode, obtained from the factor: one small system with an
+// equation per straggler.  rows ascending.
+int ngc_min_norm_decode_null(const double* B, int n, int k, const double* a0, const double* N,
+                             int q, const int* rows, int ns, double* a_out, double* resid);
+// Decode vector of layer `layer` for the responders in rows (ascending), by whichever of the
+// two routes is cheaper for this code and straggler count.
+void ngc_layer_decode_vec(const ngc_ctx* ctx, int layer, const int* rows, int ns, double* a_out,
+                          double* resid);

@@ -232,6 +232,33 @@ def test_select_reports_singular_for_a_matrix_that_is_no_gradient_code(ngc):
         ngc.ngc_destroy(ctx)
 
 
+def test_select_on_a_degenerate_code_with_dependent_straggler_rows(ngc):
+    """B = 1 1^T + u v^T with u = e_2 + e_3: workers 2 and 3 hold the same row, so whatever is
+    orthogonal to B's columns has dependent entries on them.  Losing both of them is decodable
+    (a = (1/2, 1/2, 0, 0) by symmetry); losing workers 0 and 1 is not."""
+    n = 4
+    ctx = ngc.ngc_create(n, n, [0, 2], 4)
+    try:
+        B = np.ones((n, n))
+        B[2:, 3] += 1.0
+        ngc.ngc_set_code(ctx, 1, B)
+        m = np.array([0, 0, 1, 1], np.uint8)
+        u, a, r = ngc.ngc_select_decode_vec(ctx, m, n)
+        assert u == 1 and r < 1e-12
+        assert np.allclose(a, [0.5, 0.5, 0.0, 0.0], atol=1e-14)
+        a_o, _ = coding.decode_vector(B, m)
+        assert np.allclose(a, a_o, atol=1e-12)
+        m = np.array([0, 0, 0, 1], np.uint8)                  # one of the twins still responds
+        u, a, r = ngc.ngc_select_decode_vec(ctx, m, n)
+        a_o, _ = coding.decode_vector(B, m)
+        assert r < 1e-12 and a[3] == 0.0 and np.allclose(a, a_o, atol=1e-12)
+        with pytest.raises(ngc.NgcError) as e:
+            ngc.ngc_select_decode_vec(ctx, np.array([1, 1, 0, 0], np.uint8), n)
+        assert e.value.code == ngc.NGC_ERR_SINGULAR
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
 def test_null_arguments_are_rejected_not_dereferenced(ngc):
     ctx = ngc.ngc_create(4, 4, [0, 1], 8)
     try:
