@@ -6,6 +6,8 @@ support of the decode vector exact.  Where decoding is ill-conditioned
 addition stay inside the forward-error bound 4 * 2^-24 * kappa, and the share of
 rounds above 1e-4 is reported.
 """
+import dataclasses
+
 import numpy as np
 import pytest
 
@@ -435,6 +437,56 @@ def test_c3_full_size_every_partition(ngc, torch_dev):
                 assert u == u_o and np.array_equal(a != 0, a_o != 0)
                 kappa = coding.conditioning(a_o, C_o[u_o], full)
                 assert rel(g, full) <= max(TOL, 4 * 2.0 ** -24 * kappa)
+    finally:
+        p.close()
+
+
+# --------------------------------------------------------------------------------------------
+# More than 2^32 matrix elements (17 GB of X): element offsets no longer fit 32 bits, neither
+# signed nor unsigned.  Both regression losses on the same features; the oracle adds up row
+# chunks of every partition (the gradient is a sum over rows).
+# --------------------------------------------------------------------------------------------
+def test_gradients_beyond_2_to_32_elements(ngc, torch_dev):
+    torch = torch_dev
+    w = dataclasses.replace(wl.C3, name="huge-lsq", n=4, rows=266240, layers=(0, 1))
+    assert w.n * w.rows * w.d > 2 ** 32
+    dev = torch.device("cuda:0")
+    truth = wl.truth_vector(w, 0)
+    th = wl.theta(w, 0)
+    th_log = (0.02 * th).astype(np.float32)      # margins of order one for the logistic loss
+    Xd = torch.empty((w.n, w.rows, w.d), dtype=torch.float32, device=dev)
+    Yd = torch.empty((w.n, w.rows), dtype=torch.float32, device=dev)
+    Ys = torch.empty((w.n, w.rows), dtype=torch.float32, device=dev)
+    G_lsq = np.zeros((w.n, w.d))
+    G_log = np.zeros((w.n, w.d))
+
+    def one(j):
+        X, Y = wl.partition(w, j, 0, truth)
+        S = np.where(Y >= 0.0, 1.0, -1.0).astype(np.float32)
+        for r0 in range(0, w.rows, 65536):
+            sl = slice(r0, min(w.rows, r0 + 65536))
+            G_lsq[j] += gradients.lsq_gradient(X[sl], Y[sl], th)
+            G_log[j] += gradients.logistic_gradient(X[sl], S[sl], th_log)
+        return X, Y, S
+
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=4) as ex:
+        for j, (X, Y, S) in enumerate(ex.map(one, range(w.n))):
+            Xd[j].copy_(torch.from_numpy(X))
+            Yd[j].copy_(torch.from_numpy(Y))
+            Ys[j].copy_(torch.from_numpy(S))
+    p = Pipeline(ngc, torch, w)
+    try:
+        ngc.ngc_partition_grads(p.ctx, wl.LOSS_LSQ, Xd, Yd, p.to_dev(th), w.rows, p.G)
+        ngc.ngc_sync(p.ctx)
+        G = p.G.cpu().numpy()
+        for j in range(w.n):
+            assert rel(G[j], G_lsq[j]) <= TOL, (j, rel(G[j], G_lsq[j]))
+        ngc.ngc_partition_grads(p.ctx, wl.LOSS_LOGISTIC, Xd, Ys, p.to_dev(th_log), w.rows, p.G)
+        ngc.ngc_sync(p.ctx)
+        G = p.G.cpu().numpy()
+        for j in range(w.n):
+            assert rel(G[j], G_log[j]) <= TOL, (j, rel(G[j], G_log[j]))
     finally:
         p.close()
 
