@@ -275,6 +275,50 @@ def test_null_arguments_are_rejected_not_dereferenced(ngc):
         ngc.ngc_destroy(ctx)
 
 
+def test_empty_and_misaligned_inputs_are_rejected_before_any_device_work(ngc):
+    """No rows, a buffer that is not 16-byte aligned, an unknown loss: the call returns
+    INVALID from its argument checks (the addresses below are never dereferenced and no GPU is
+    needed to get that far)."""
+    import ctypes
+    n = 4
+    ctx = ngc.ngc_create(n, n, [0, 1], 8)
+    try:
+        lib = ngc._lib
+        ok = ctypes.c_void_p(0x10000)             # stands for an aligned device address
+        odd = ctypes.c_void_p(0x10004)
+        prog = (ctypes.c_int * n)(*([2] * n))
+        mask = (ctypes.c_uint8 * n)()
+        a = (ctypes.c_double * n)()
+        u = ctypes.c_int(0)
+        rows = ctypes.c_int64
+        for r in (0, -3):
+            assert lib.ngc_partition_grads(ctx, 0, ok, ok, ok, rows(r), ok) == ngc.NGC_ERR_INVALID
+            assert "rows" in ngc.ngc_last_error(ctx)
+            assert lib.ngc_worker_grads(ctx, 0, ok, ok, ok, rows(r), prog, ok) == ngc.NGC_ERR_INVALID
+            assert lib.ngc_iteration(ctx, 0, ok, ok, ok, rows(r), mask, ctypes.c_double(0.1), ok, ok, ok,
+                                     ctypes.byref(u), a) == ngc.NGC_ERR_INVALID
+        assert lib.ngc_partition_grads(ctx, 0, odd, ok, ok, rows(4), ok) == ngc.NGC_ERR_INVALID
+        assert "aligned" in ngc.ngc_last_error(ctx)
+        assert lib.ngc_partition_grads(ctx, 0, ok, ok, odd, rows(4), ok) == ngc.NGC_ERR_INVALID
+        assert lib.ngc_partition_grads(ctx, 0, ok, ok, ok, rows(4), odd) == ngc.NGC_ERR_INVALID
+        assert lib.ngc_worker_grads(ctx, 0, ok, ok, ok, rows(4), prog, odd) == ngc.NGC_ERR_INVALID
+        assert lib.ngc_worker_grads(ctx, 9, ok, ok, ok, rows(4), prog, ok) == ngc.NGC_ERR_INVALID
+        assert "loss" in ngc.ngc_last_error(ctx)
+        assert lib.ngc_iteration(ctx, 9, ok, ok, ok, rows(4), mask, ctypes.c_double(0.1), ok, ok, ok,
+                                 ctypes.byref(u), a) == ngc.NGC_ERR_INVALID
+        assert lib.ngc_iteration(ctx, 0, ok, ok, ok, rows(4), mask, ctypes.c_double(0.1), ok, odd, ok,
+                                 ctypes.byref(u), a) == ngc.NGC_ERR_INVALID
+        # the perceptron loss before its shape is known
+        assert lib.ngc_worker_grads(ctx, 2, ok, ok, ok, rows(4), prog, ok) == ngc.NGC_ERR_STATE
+        # an undecodable round launches nothing: three stragglers against a tolerance of one
+        for i in range(3):
+            mask[i] = 1
+        assert lib.ngc_iteration(ctx, 0, ok, ok, ok, rows(4), mask, ctypes.c_double(0.1), ok, ok, ok,
+                                 ctypes.byref(u), a) == ngc.NGC_ERR_UNDECODABLE
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
 # ---- redundancy-faithful execution: schedule and termination rule (host only) -----------------
 @pytest.mark.parametrize("n,layers,kind", [(8, [0, 1, 3], "cyclic"), (8, [0, 1, 3, 7], "fracrep"),
                                            (6, [0, 2, 3], "cyclic")])
