@@ -72,7 +72,8 @@ enum {
  * gradient length (the paper's l).  k = c*n for an integer c >= 1 (Sec. II-C
  * works with k = n and notes that k/n partial gradients can be assigned
  * jointly as one atomic task: worker i then treats the c partitions
- * j*c .. j*c+c-1 of group j like the single partition j), 1 <= n <= k <= 64.
+ * j*c .. j*c+c-1 of group j like the single partition j), 1 <= n <= k <= 64,
+ * 1 <= d <= 2^33.
  * hip_stream is a hipStream_t (NULL = the default stream); it must outlive the
  * context.  Layer 0 is preset to B_0 = I (x) 1_{1 x c} (Alg. 1); the other
  * layers must be given by ngc_set_code() or ngc_build_code() before use.

@@ -82,6 +82,9 @@ extern "C" int ngc_create(ngc_ctx** out, int n, int k, int L, const int* s, int6
     for (int u = 1; u < L; ++u)
         if (s[u] <= s[u - 1]) return NGC_ERR_INVALID;
     if (s[L - 1] >= n) return NGC_ERR_INVALID;
+    // 2^33 floats are 32 GiB per gradient row; beyond that the column-tile counts of the
+    // kernels' grids would no longer fit their 31 bits
+    if (d > ((int64_t)1 << 33)) return NGC_ERR_INVALID;
     ngc_ctx* ctx = new (std::nothrow) ngc_ctx;
     if (!ctx) return NGC_ERR_NOMEM;
     ctx->n = n;

@@ -49,11 +49,13 @@ def test_create_rejects_bad_arguments(ngc):
         dict(n=0, k=0, layers=[0], d=8),
         dict(n=65, k=65, layers=[0], d=8),
         dict(n=4, k=4, layers=[0, 1], d=0),
+        dict(n=4, k=4, layers=[0, 1], d=2 ** 33 + 1),   # column-tile counts would not fit a grid
     ]
     for kw in bad:
         with pytest.raises(ngc.NgcError) as e:
             ngc.ngc_create(kw["n"], kw["k"], kw["layers"], kw["d"])
         assert e.value.code == ngc.NGC_ERR_INVALID
+    ngc.ngc_destroy(ngc.ngc_create(4, 4, [0, 1], 2 ** 33))    # the largest d (no memory is touched)
     ngc.ngc_destroy(None)
 
 
