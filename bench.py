@@ -415,6 +415,7 @@ def main():
         resp += int(np.count_nonzero(a))
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    per_launch = ngc.ngc_profile_launches(ctx, "mlp" if is_mlp else "grad")
     prof = ngc.ngc_profile_read(ctx)
     ms_per_step = elapsed / K * 1e3
     # the small kernels are timed in a pass of their own, after the timed region
@@ -455,6 +456,10 @@ def main():
                     "algorithmic_bytes": grad_bytes,
                     "kernel": "grad_stream_kernel", "avg_ms": round(grad_avg_ms, 4),
                     "launches": grad_launches}
+    if per_launch.size:
+        # the same launches one by one (HIP events of the timed region): spread of the kernel's time
+        roofline["median_ms"] = round(float(np.median(per_launch)), 4)
+        roofline["min_ms"] = round(float(per_launch.min()), 4)
     enc_ms = prof["encode"][1] / max(1, prof["encode"][0])
     dec_ms = prof["decode"][1] / max(1, prof["decode"][0])
     enc_bytes = 4.0 * w.n * w.d * (1 + L)
@@ -485,6 +490,9 @@ def main():
         ceiling = {"plain_read_GBps": round(Xd.numel() * 4 * n_read / (ms_read * 1e-3) / 1e9, 1),
                    "plain_copy_GBps_read_plus_write": round(2 * nb * n_copy / (ms_copy * 1e-3) / 1e9, 1)}
 
+    if ceiling and roofline.get("bound") == "hbm":
+        # the same rate against what a plain read of the same buffer reaches on this machine
+        roofline["frac_of_plain_read"] = round(roofline["achieved"] / ceiling["plain_read_GBps"], 4)
     out = {
         "metric": metric_name(w.n, w.d),
         "value": round(w.m * K / elapsed, 1), "unit": "samples/s", "n_gpus": 1, "steps": K,

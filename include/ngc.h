@@ -309,6 +309,14 @@ int ngc_sync(ngc_ctx* ctx);
  */
 int ngc_profile_enable(ngc_ctx* ctx, int kernel_mask);
 int ngc_profile_read(ngc_ctx* ctx, int64_t* launches_out, double* total_ms_out);
+/*
+ * The recorded launches of one kernel id one by one, in launch order:
+ * synchronises, writes up to `capacity` durations in milliseconds to ms_out
+ * (host) and the number of recorded launches of that kernel to count_out.  The
+ * record is left as it is; call before ngc_profile_read(), which clears it.
+ */
+int ngc_profile_launches(ngc_ctx* ctx, int kernel, double* ms_out, int64_t capacity,
+                         int64_t* count_out);
 
 /*
  * Measurement aids, not part of the method.  ngc_probe_copy copies `bytes`

@@ -872,6 +872,27 @@ extern "C" int ngc_profile_read(ngc_ctx* ctx, int64_t* launches_out, double* tot
     return ngc_on_exception();
 }
 
+extern "C" int ngc_profile_launches(ngc_ctx* ctx, int kernel, double* ms_out, int64_t capacity,
+                                    int64_t* count_out) try {
+    if (!ctx || !count_out || capacity < 0 || (capacity > 0 && !ms_out)) return NGC_ERR_INVALID;
+    if (kernel < 0 || kernel >= NGC_KERNEL_COUNT) return ngc_fail(ctx, NGC_ERR_INVALID, "unknown kernel id");
+    *count_out = 0;
+    if (ctx->prof.empty()) return NGC_OK;
+    NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    int64_t seen = 0;
+    for (auto& r : ctx->prof) {
+        if (r.kernel != kernel) continue;
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) continue;
+        if (seen < capacity) ms_out[seen] = ms;
+        ++seen;
+    }
+    *count_out = seen;
+    return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
+}
+
 extern "C" int ngc_sync(ngc_ctx* ctx) try {
     if (!ctx) return NGC_ERR_INVALID;
     NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));

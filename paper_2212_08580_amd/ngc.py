@@ -39,7 +39,7 @@ EXPORTS = (
     "ngc_worker_task_count", "ngc_worker_schedule", "ngc_worker_grads", "ngc_worker_encode",
     "ngc_select_from_progress", "ngc_build_decoding_table", "ngc_decoding_row_index",
     "ngc_get_decoding_row", "ngc_decode_lookup", "ngc_latency_cdf_gc", "ngc_latency_cdf_ngc", "ngc_latency_simulate",
-    "ngc_profile_enable", "ngc_profile_read", "ngc_probe_copy", "ngc_probe_read",
+    "ngc_profile_enable", "ngc_profile_read", "ngc_profile_launches", "ngc_probe_copy", "ngc_probe_read",
     "ngc_strerror", "ngc_last_error",
 )
 
@@ -85,6 +85,7 @@ _lib.ngc_select_from_progress.argtypes = [_vp, _vp, _i, ctypes.POINTER(_i), _vp,
 _lib.ngc_sync.argtypes = [_vp]
 _lib.ngc_profile_enable.argtypes = [_vp, _i]
 _lib.ngc_profile_read.argtypes = [_vp, _vp, _vp]
+_lib.ngc_profile_launches.argtypes = [_vp, _i, _vp, _i64, ctypes.POINTER(_i64)]
 _lib.ngc_probe_copy.argtypes = [_vp, _vp, _vp, _i64]
 _lib.ngc_probe_read.argtypes = [_vp, _vp, _i64]
 _lib.ngc_strerror.argtypes = [_i]
@@ -406,6 +407,15 @@ def ngc_profile_enable(ctx, kernels):
         for name in kernels:
             mask |= 1 << NGC_KERNEL_NAMES.index(name)
     _check(_lib.ngc_profile_enable(ctx, mask), ctx)
+
+
+def ngc_profile_launches(ctx, name):
+    """-> durations [ms] of the recorded launches of one kernel, in launch order."""
+    ms = np.zeros(4096, np.float64)
+    cnt = ctypes.c_int64(0)
+    _check(_lib.ngc_profile_launches(ctx, NGC_KERNEL_NAMES.index(name), ms.ctypes.data_as(ctypes.c_void_p),
+                                     ms.size, ctypes.byref(cnt)), ctx)
+    return ms[:min(cnt.value, ms.size)].copy()
 
 
 def ngc_profile_read(ctx):

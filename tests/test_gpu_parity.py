@@ -442,6 +442,35 @@ def test_c3_full_size_every_partition(ngc, torch_dev):
 
 
 # --------------------------------------------------------------------------------------------
+# per-kernel timing: what the benchmark's roofline figures are read from
+# --------------------------------------------------------------------------------------------
+def test_profile_records_every_launch_of_the_selected_kernels(ngc, torch_dev):
+    w = wl.C3.scaled(rows=64, d=1024, n=4, layers=(0, 1), name="prof")
+    X, Y = wl.dataset(w, seed=0, threads=1)
+    th = wl.theta(w, seed=1)
+    p = Pipeline(ngc, torch_dev, w)
+    try:
+        Xd, Yd, thd = p.to_dev(X), p.to_dev(Y), p.to_dev(th)
+        ngc.ngc_profile_enable(p.ctx, ["grad", "encode"])
+        for _ in range(5):
+            ngc.ngc_partition_grads(p.ctx, w.loss, Xd, Yd, thd, w.rows, p.G)
+            ngc.ngc_encode(p.ctx, p.G, -1, p.C)
+            ngc.ngc_update(p.ctx, thd, p.g, 0.0)                      # not selected: not recorded
+        each = ngc.ngc_profile_launches(p.ctx, "grad")
+        assert each.size == 5 and np.all(each > 0.0) and np.all(each < 50.0)
+        assert ngc.ngc_profile_launches(p.ctx, "update").size == 0
+        prof = ngc.ngc_profile_read(p.ctx)
+        assert prof["grad"][0] == 5 and prof["encode"][0] == 5 and prof["update"][0] == 0
+        assert abs(prof["grad"][1] - each.sum()) <= 1e-6 * each.sum()
+        assert ngc.ngc_profile_launches(p.ctx, "grad").size == 0       # the read cleared the record
+        ngc.ngc_profile_enable(p.ctx, False)
+        ngc.ngc_partition_grads(p.ctx, w.loss, Xd, Yd, thd, w.rows, p.G)
+        assert ngc.ngc_profile_read(p.ctx)["grad"][0] == 0
+    finally:
+        p.close()
+
+
+# --------------------------------------------------------------------------------------------
 # More than 2^32 matrix elements (17 GB of X): element offsets no longer fit 32 bits, neither
 # signed nor unsigned.  Both regression losses on the same features; the oracle adds up row
 # chunks of every partition (the gradient is a sum over rows).
