@@ -33,11 +33,11 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def measured_traffic(workload_name):
-    """HBM bytes per launch of the gradient kernel from the committed rocprofv3 counter summary,
+def measured_traffic(workload_name, summary="grad_stream"):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary,
     or None if the kernel source has changed since those counters were taken."""
     import hashlib
-    path = os.path.join(ROOT, "profiles", "grad_stream_%s.txt" % workload_name)
+    path = os.path.join(ROOT, "profiles", "%s_%s.txt" % (summary, workload_name))
     src = os.path.join(ROOT, "paper_2212_08580_amd", "csrc", "ngc_device.hip")
     try:
         sha = hashlib.sha256(open(src, "rb").read()).hexdigest()
@@ -159,7 +159,8 @@ def bench_codec(args, w, wl, ngc, torch, np):
         "config": {"workload": w.name, "n": w.n, "d": w.d, "layers": list(w.layers),
                    "p_straggle": w.p_straggle, "mean_responders": resp / K},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": measured_traffic(w.name, "encode_decode"),
                      "algorithmic_bytes": enc_bytes, "kernel": "encode_kernel",
                      "avg_ms": round(enc_ms, 4), "launches": prof["encode"][0]},
         "stages": {"encode_ms": round(enc_ms, 4), "encode_GBps": round(achieved, 1),
