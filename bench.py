@@ -52,6 +52,23 @@ def measured_traffic(workload_name, summary="grad_stream"):
     return None
 
 
+def measured_figure(summary, source, key):
+    """A number that a committed rocprofv3 counter summary holds as a line 'key: value', or None
+    if the kernel source has changed since the counters were taken."""
+    import hashlib
+    try:
+        sha = hashlib.sha256(open(os.path.join(ROOT, "paper_2212_08580_amd", "csrc", source), "rb").read()).hexdigest()
+        text = open(os.path.join(ROOT, "profiles", summary)).read()
+    except OSError:
+        return None
+    if (source + ": " + sha) not in text:
+        return None
+    for line in text.splitlines():
+        if line.startswith(key + ":"):
+            return float(line.split(":")[1])
+    return None
+
+
 def cpu_baseline(w, wl, parts_host, theta, masks, budget_parts):
     """The fp64 checker timed on the host cores over a bounded sample of the same
     workload: `budget_parts` partitions for the gradients, then encode of all
@@ -208,12 +225,19 @@ def bench_workers(args, w, wl, ngc, torch, np):
     mlp = w.loss == wl.LOSS_MLP2
     Yd = torch.empty((w.n, w.rows), dtype=torch.int32 if mlp else torch.float32, device=dev)
     truth = None if mlp else wl.truth_vector(w, 0)
+    keep = None                                          # host copies for the oracle's leg
+    if not args.no_cpu_baseline:
+        keep = (np.empty((w.n, w.rows, w.d_in), np.float32), np.empty((w.n, w.rows), np.int32 if mlp else np.float32))
     from concurrent.futures import ThreadPoolExecutor
     with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
         for j, (X, Y) in enumerate(ex.map(lambda j: wl.partition(w, j, 0, truth), range(w.n))):
             Xd[j].copy_(torch.from_numpy(X))
             Yd[j].copy_(torch.from_numpy(Y))
-    thd = torch.from_numpy(wl.theta(w, 0)).to(dev)
+            if keep is not None:
+                keep[0][j] = X
+                keep[1][j] = Y
+    theta_h = wl.theta(w, 0)
+    thd = torch.from_numpy(theta_h).to(dev)
     masks = wl.bernoulli_masks(w, K + W, seed=0)
     masks[masks.sum(axis=1) > w.layers[-1]] = 0
     ctx = ngc.ngc_create(w.n, w.n, w.layers, w.d, torch.cuda.current_stream().cuda_stream)
@@ -242,19 +266,44 @@ def bench_workers(args, w, wl, ngc, torch, np):
         return int(progress.sum())
 
     res = {}
+    kern = "mlp" if mlp else "grad"
     for name, min_layer in (("nested", 0), ("fixed_sigma", L - 1)):
         for t in range(W):
             iteration(masks[t], min_layer)
         torch.cuda.synchronize()
+        if name == "nested":
+            ngc.ngc_profile_enable(ctx, [kern])          # events around the gradient kernels
         tasks = 0
         t0 = time.perf_counter()
         for t in range(W, W + K):
             tasks += iteration(masks[t], min_layer)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
+        if name == "nested":
+            launches, kern_ms = ngc.ngc_profile_read(ctx)[kern]
+            ngc.ngc_profile_enable(ctx, False)
+            nested_tasks = tasks
         res[name] = {"ms_per_iteration": round(dt / K * 1e3, 4), "tasks_per_iteration": tasks / K,
                      "useful_samples_per_s": round(w.m * K / dt, 1),
                      "computed_samples_per_s": round(tasks * w.rows / dt, 1)}
+    # Roofline of the gradient kernel over the timed iterations of the nested code.  Algorithmic
+    # work counts every worker's own pass over each partition it computes (the paper's model:
+    # every worker holds its copies); workers that read the same partition at the same time
+    # share the caches, so the HBM traffic is lower than these bytes.
+    if mlp:
+        flops = nested_tasks * w.rows * (2.0 * w.d_in * w.hidden * 2 + 2.0 * w.hidden * w.classes * 3)
+        achieved = flops / (kern_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": 157.3, "unit": "TFLOP/s",
+                    "frac": round(achieved / 157.3, 4), "traffic": None, "algorithmic_flops": flops / K,
+                    "kernel": "mlp_gemm_kernel (whole MLP gradient call, one unit per worker task)",
+                    "avg_ms": round(kern_ms / max(1, launches), 4), "launches": launches}
+    else:
+        nbytes = nested_tasks * w.rows * (4.0 * w.d + 4.0) + K * 4.0 * w.d
+        achieved = nbytes / (kern_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                    "algorithmic_bytes": nbytes / K, "kernel": "grad_stream_kernel (one unit per worker task)",
+                    "avg_ms": round(kern_ms / max(1, launches), 4), "launches": launches}
     out = {
         "metric": metric_name(w.n, w.d) + " (worker execution, useful samples/s)",
         "value": res["nested"]["useful_samples_per_s"], "unit": "samples/s", "n_gpus": 1, "steps": K,
@@ -266,8 +315,35 @@ def bench_workers(args, w, wl, ngc, torch, np):
         "nested_code": res["nested"], "fixed_sigma_code": res["fixed_sigma"],
         "speedup_over_fixed_sigma": round(res["fixed_sigma"]["ms_per_iteration"] /
                                           res["nested"]["ms_per_iteration"], 3),
+        "roofline": roofline,
     }
     ngc.ngc_destroy(ctx)
+    if keep is not None:
+        # the oracle's worker execution of one iteration (the first timed straggler pattern):
+        # every task of every worker recomputed in fp64, messages, termination rule, decoding
+        from oracle import codes, coding, workers as ow
+        Bs = codes.nested_code(w.n, w.layers, "cyclic" if w.code == wl.CODE_CYCLIC else "fracrep", seed=0, draws=2)
+        Xh, Yh = keep
+        alive = (masks[W] == 0).astype(np.int64)
+        for t in range(1, T + 1):
+            progress = alive * t
+            try:
+                ow.terminate(Bs, w.layers, progress, 0)
+                break
+            except coding.Undecodable:
+                continue
+        t0 = time.perf_counter()
+        Wp = ow.worker_partials(w.loss, Xh, Yh, theta_h, Bs, progress, w.hidden, w.classes)
+        ow.decode_from_workers(Bs, w.layers, Wp, progress, 0)
+        dt = time.perf_counter() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        out["cpu_baseline"] = {"value": w.m / dt, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+                               "sample": "one iteration of the worker execution (%d tasks of %d samples) in %.2f s"
+                                         % (int(progress.sum()), w.rows, dt)}
     print(json.dumps(out), flush=True)
 
 
@@ -313,6 +389,29 @@ def bench_latency(args, ngc, torch, np):
         "max_abs_deviation_simulation_vs_closed_form": round(worst, 6),
         "uncoded_limit": float(ngc.ngc_latency_cdf_gc(n, 0, *par, [1e6])[0]),
     }
+    # Bound by plain vector arithmetic (integer Philox rounds, fp64 logarithms, compare-exchange
+    # sorting): achieved = vector instructions per launch (counter summary) x 64 lanes / launch
+    # time, against one vector instruction per SIMD every four clocks over 64 lanes
+    # (256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz).
+    valu = measured_figure("latency_sim_n8.txt", "ngc_latency.hip", "valu-instructions-per-launch-smax6")
+    peak = 256 * 4 * 16 * 2.4e9 / 1e12
+    ach = None if valu is None else valu * 64.0 / (trials / rate) / 1e12
+    out["roofline"] = {"bound": "alu", "achieved": None if ach is None else round(ach, 2), "peak": round(peak, 1),
+                       "unit": "T lane-ops/s", "frac": None if ach is None else round(ach / peak, 4),
+                       "traffic": None, "kernel": "latency_sim_kernel (s_max = 6)",
+                       "note": "achieved = counted vector instructions x 64 lanes / launch time; the counter reads "
+                               "a few per cent above the issue limit, i.e. the vector ALUs are saturated",
+                       "avg_ms": round(trials / rate * 1e3, 4), "launches": args.steps}
+    if not args.no_cpu_baseline:
+        from oracle import latency as ol
+        chunk, chunks = 1 << 20, 8                      # in pieces: the oracle holds a trial's draws in memory
+        sample = chunk * chunks
+        t0 = time.perf_counter()
+        for q in range(chunks):
+            ol.simulate(chunk, n, 6, *par, seed=1 + q)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": sample / dt, "unit": "simulated iterations/s", "cores": 1, "kind": "oracle",
+                               "sample": "%d trials of the s_max = 6 model in %.2f s (NumPy, one thread)" % (sample, dt)}
     print(json.dumps(out), flush=True)
 
 
