@@ -69,7 +69,7 @@ def measured_figure(summary, source, key):
     return None
 
 
-def cpu_baseline(w, wl, parts_host, theta, masks, budget_parts):
+def cpu_baseline(w, wl, parts_host, theta, masks, budget_parts, workers=None, layers=None):
     """The fp64 checker timed on the host cores over a bounded sample of the same
     workload: `budget_parts` partitions for the gradients, then encode of all
     layers, layer/decode-vector selection and decode at full n and d."""
@@ -80,8 +80,12 @@ def cpu_baseline(w, wl, parts_host, theta, masks, budget_parts):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    Bs = codes.nested_code(w.n, w.layers, "cyclic" if w.code == wl.CODE_CYCLIC else "fracrep",
+    workers = w.n if workers is None else workers        # w.n partitions shared out over the workers
+    layers = w.layers if layers is None else layers
+    Bs = codes.nested_code(workers, layers, "cyclic" if w.code == wl.CODE_CYCLIC else "fracrep",
                            seed=0, draws=2)
+    if workers != w.n:
+        Bs = codes.expand_partitions(Bs, w.n // workers)
     t0 = time.perf_counter()
     rows = []
     for X, Y in parts_host[:budget_parts]:
@@ -90,7 +94,7 @@ def cpu_baseline(w, wl, parts_host, theta, masks, budget_parts):
     G = np.stack(rows + [rows[-1]] * (w.n - len(rows)))      # pad to n rows for the coding steps
     t1 = time.perf_counter()
     C = coding.encode_layers(Bs, G)
-    u = coding.select_layer(w.layers, masks[0])
+    u = coding.select_layer(layers, masks[0])
     a, _ = coding.decode_vector(Bs[u], masks[0])
     coding.decode(a, C[u])
     t_code = time.perf_counter() - t1
@@ -415,6 +419,113 @@ def bench_latency(args, ngc, torch, np):
     print(json.dumps(out), flush=True)
 
 
+def bench_lookup(args, wl, ngc, torch, np):
+    """Small cluster with explicit decoding matrices A_sigma (Def. 1) held on the device: per round
+    the host only ranks the straggler set, the kernel reads its decode vector from the table.
+    Timed beside the route that solves for the vector on the host, on the same messages and
+    masks (n = 16, layers 0/1/3/7, gradient length 16384, Binomial(n, 0.2) stragglers)."""
+    import dataclasses
+    dev = torch.device("cuda:0")
+    K, W = args.steps, args.warmup
+    w = dataclasses.replace(wl.C5, name="lookup-n16", n=16, layers=(0, 1, 3, 7))
+    L = len(w.layers)
+    G = torch.from_numpy(wl.partial_gradients(w, 0)).to(dev)
+    C = torch.empty((L, w.n, w.d), dtype=torch.float32, device=dev)
+    g = torch.empty(w.d, dtype=torch.float32, device=dev)
+    masks = wl.binomial_count_masks(w, K + W, seed=0)
+    masks[masks.sum(axis=1) > w.layers[-1]] = 0
+    ctx = ngc.ngc_create(w.n, w.n, w.layers, w.d, torch.cuda.current_stream().cuda_stream)
+    ngc.ngc_build_code(ctx, ngc.NGC_CODE_CYCLIC, 0)
+    t0 = time.perf_counter()
+    table_rows = [ngc.ngc_build_decoding_table(ctx, u) for u in range(L)]
+    t_tables = time.perf_counter() - t0
+    ngc.ngc_encode(ctx, G, -1, C)
+    layer_of = [next(u for u, s in enumerate(w.layers) if s >= cnt) for cnt in range(w.layers[-1] + 1)]
+
+    def by_lookup(t):
+        u = layer_of[int(masks[t].sum())]
+        ngc.ngc_decode_lookup(ctx, u, masks[t], C, g)
+        return w.n - w.layers[u]                     # a table row is supported on n - sigma responders
+
+    def by_solve(t):
+        u, a, _ = ngc.ngc_select_decode_vec(ctx, masks[t], w.n)
+        ngc.ngc_decode(ctx, u, a, C, g)
+        return int(np.count_nonzero(a))
+
+    res = {}
+    for name, fn in (("lookup", by_lookup), ("solve", by_solve)):
+        for t in range(W):
+            fn(t)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        used = 0
+        for t in range(W, W + K):
+            used += fn(t)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        ngc.ngc_profile_enable(ctx, ["decode"])      # kernel durations in a pass of their own
+        for t in range(W, W + min(K, 200)):
+            fn(t)
+        cnt, ms = ngc.ngc_profile_read(ctx)["decode"]
+        ngc.ngc_profile_enable(ctx, False)
+        res[name] = {"us_per_round": round(dt / K * 1e6, 2), "kernel_us": round(ms / max(1, cnt) * 1e3, 2),
+                     "messages_read_per_round": used / K}
+    # host part alone: ranking a straggler set against solving for its decode vector
+    t0 = time.perf_counter()
+    for t in range(W, W + K):
+        ngc.ngc_decoding_row_index(ctx, layer_of[int(masks[t].sum())], masks[t])
+    res["lookup"]["host_us"] = round((time.perf_counter() - t0) / K * 1e6, 2)
+    t0 = time.perf_counter()
+    for t in range(W, W + K):
+        ngc.ngc_select_decode_vec(ctx, masks[t], w.n)
+    res["solve"]["host_us"] = round((time.perf_counter() - t0) / K * 1e6, 2)
+    nbytes = 4.0 * w.d * (res["lookup"]["messages_read_per_round"] + 1) + 8.0 * w.n
+    achieved = nbytes / (res["lookup"]["kernel_us"] * 1e-6) / 1e9
+    out = {
+        "metric": "decode rounds/s with the decode vector looked up in A_sigma on the device, n=%d d=%d" % (w.n, w.d),
+        "value": round(1e6 / res["lookup"]["us_per_round"], 1), "unit": "rounds/s", "n_gpus": 1, "steps": K,
+        "warmup": W, "ms_per_step": round(res["lookup"]["us_per_round"] * 1e-3, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "explicit decoding matrices, n=%d, d=%d" % (w.n, w.d), "n": w.n, "d": w.d,
+                   "layers": list(w.layers), "p_straggle": w.p_straggle, "table_rows": table_rows,
+                   "table_build_s": round(t_tables, 3)},
+        "lookup_route": res["lookup"], "solve_route": res["solve"],
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "algorithmic_bytes": nbytes,
+                     "kernel": "decode_lookup_kernel", "avg_ms": round(res["lookup"]["kernel_us"] * 1e-3, 5),
+                     "launches": min(K, 200)},
+    }
+    if not args.no_cpu_baseline:
+        # the oracle's route: A_sigma of every layer built beforehand, per round the row of the
+        # straggler set (padded to sigma stragglers with the responders of highest index) and the sum
+        import itertools
+        from oracle import codes, coding
+        Bs = codes.nested_code(w.n, w.layers, "cyclic", seed=0, draws=2)
+        Gh = G.cpu().numpy()
+        Co = coding.encode_layers(Bs, Gh)
+        tables, index = [], []
+        for u, sigma in enumerate(w.layers):
+            tables.append(codes.decoding_matrix(Bs[u], sigma))
+            index.append({out_: r for r, out_ in enumerate(itertools.combinations(range(w.n), sigma))})
+        rounds = min(K, 2000)
+        t0 = time.perf_counter()
+        for t in range(W, W + rounds):
+            m = masks[t]
+            u = coding.select_layer(w.layers, m)
+            out_ = [i for i in range(w.n) if m[i]]
+            for i in range(w.n - 1, -1, -1):          # fewer stragglers than sigma: the last responders idle
+                if len(out_) == w.layers[u]:
+                    break
+                if not m[i]:
+                    out_.append(i)
+            coding.decode(tables[u][index[u][tuple(sorted(out_))]], Co[u])
+        dt = (time.perf_counter() - t0) / rounds
+        out["cpu_baseline"] = {"value": 1.0 / dt, "unit": "rounds/s", "cores": 1, "kind": "oracle",
+                               "sample": "%d rounds of layer choice, table row and decode (tables built beforehand)" % rounds}
+    ngc.ngc_destroy(ctx)
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -423,8 +534,10 @@ def main():
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
-    ap.add_argument("--mode", default="pipeline", choices=["pipeline", "workers", "latency"])
+    ap.add_argument("--mode", default="pipeline", choices=["pipeline", "workers", "latency", "lookup"])
     ap.add_argument("--cpu-parts", type=int, default=32)
+    ap.add_argument("--parts-per-worker", type=int, default=1,
+                    help="k = c n (Sec. II-C): the workload's partitions are shared out c to a worker")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: nested gradient coding here simulates all n workers on "
@@ -447,6 +560,8 @@ def main():
     gc.freeze()
     if args.mode == "latency":
         return bench_latency(args, ngc, torch, np)
+    if args.mode == "lookup":
+        return bench_lookup(args, wl, ngc, torch, np)
     w = wl.CONFIGS[args.workload]
     if w.loss < 0:
         return bench_codec(args, w, wl, ngc, torch, np)
@@ -457,7 +572,15 @@ def main():
         sys.exit(2)
     is_mlp = w.loss == wl.LOSS_MLP2
     K, W = args.steps, args.warmup
-    L = len(w.layers)
+    # k = c n: the workload's w.n partitions go to nw = w.n / c workers, c to an atomic task; the
+    # layers that such a smaller cluster can hold are kept
+    c = args.parts_per_worker
+    if c < 1 or w.n % c:
+        print("--parts-per-worker must divide the workload's %d partitions" % w.n, file=sys.stderr)
+        sys.exit(2)
+    nw = w.n // c
+    layers = tuple(s for s in w.layers if s < nw)
+    L = len(layers)
 
     # ---- inputs: generated per partition on the host, uploaded once -------------------------
     t0 = time.perf_counter()
@@ -474,32 +597,32 @@ def main():
                 keep.append((X, Y))
     theta_h = wl.theta(w, 0)
     thd = torch.from_numpy(theta_h).to(dev)
-    masks = wl.bernoulli_masks(w, K + W, seed=0)
+    masks = np.ascontiguousarray(wl.bernoulli_masks(w, K + W, seed=0)[:, :nw])
     # a round with more stragglers than the code tolerates cannot be decoded (prob. ~1e-8 here);
     # such a mask is replaced by "no stragglers" so that every timed step does the full work
-    masks[masks.sum(axis=1) > w.layers[-1]] = 0
+    masks[masks.sum(axis=1) > layers[-1]] = 0
     torch.cuda.synchronize()
     log("inputs ready in %.1f s (X %.2f GB in HBM)" % (time.perf_counter() - t0, Xd.numel() * 4 / 1e9))
 
     stream = torch.cuda.current_stream().cuda_stream
-    ctx = ngc.ngc_create(w.n, w.n, w.layers, w.d, stream)
+    ctx = ngc.ngc_create(nw, w.n, layers, w.d, stream)
     ngc.ngc_build_code(ctx, ngc.NGC_CODE_CYCLIC if w.code == wl.CODE_CYCLIC else ngc.NGC_CODE_FRACREP, 0)
     if is_mlp:
         ngc.ngc_set_mlp2_shape(ctx, w.d_in, w.hidden, w.classes)
     G = torch.empty((w.n, w.d), dtype=torch.float32, device=dev)
-    C = torch.empty((L, w.n, w.d), dtype=torch.float32, device=dev)
+    C = torch.empty((L, nw, w.d), dtype=torch.float32, device=dev)
     g = torch.empty(w.d, dtype=torch.float32, device=dev)
     eta_over_m = 1e-3 / w.m
 
     def step(t):
         # one iteration: partition gradients, every layer's messages, layer + decode vector for
         # this round's stragglers, decode, update (two launches for the regression losses)
-        return ngc.ngc_iteration(ctx, w.loss, Xd, Yd, thd, w.rows, masks[t], eta_over_m, G, C, g, w.n)
+        return ngc.ngc_iteration(ctx, w.loss, Xd, Yd, thd, w.rows, masks[t], eta_over_m, G, C, g, nw)
 
     def step_separate(t):
         ngc.ngc_partition_grads(ctx, w.loss, Xd, Yd, thd, w.rows, G)
         ngc.ngc_encode(ctx, G, -1, C)
-        u, a, _ = ngc.ngc_select_decode_vec(ctx, masks[t], w.n)
+        u, a, _ = ngc.ngc_select_decode_vec(ctx, masks[t], nw)
         ngc.ngc_decode(ctx, u, a, C, g)
         ngc.ngc_update(ctx, thd, g, eta_over_m)
         return u, a
@@ -562,7 +685,7 @@ def main():
         roofline["min_ms"] = round(float(per_launch.min()), 4)
     enc_ms = prof["encode"][1] / max(1, prof["encode"][0])
     dec_ms = prof["decode"][1] / max(1, prof["decode"][0])
-    enc_bytes = 4.0 * w.n * w.d * (1 + L)
+    enc_bytes = 4.0 * w.d * (w.n + L * nw)
     dec_bytes = 4.0 * w.d * (resp_per_step + 1)
     stages = {
         "grad_samples_per_s": round(w.m / (grad_avg_ms * 1e-3), 1),
@@ -594,18 +717,19 @@ def main():
         # the same rate against what a plain read of the same buffer reaches on this machine
         roofline["frac_of_plain_read"] = round(roofline["achieved"] / ceiling["plain_read_GBps"], 4)
     out = {
-        "metric": metric_name(w.n, w.d),
+        "metric": metric_name(nw, w.d),
         "value": round(w.m * K / elapsed, 1), "unit": "samples/s", "n_gpus": 1, "steps": K,
         "warmup": W, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w.name, "loss": ("lsq", "logistic", "mlp2")[w.loss], "n": w.n,
-                   "rows_per_partition": w.rows, "d": w.d, "layers": list(w.layers),
+        "config": {"workload": w.name if c == 1 else "%s, %d partitions per worker" % (w.name, c),
+                   "loss": ("lsq", "logistic", "mlp2")[w.loss], "n": nw, "partitions": w.n,
+                   "rows_per_partition": w.rows, "d": w.d, "layers": list(layers),
                    "p_straggle": w.p_straggle},
         "roofline": roofline, "stages": stages, "hbm_probe": ceiling,
     }
     if not args.no_cpu_baseline:
         ngc.ngc_sync(ctx)
-        cb = cpu_baseline(w, wl, keep, theta_h, masks, min(args.cpu_parts, w.n))
+        cb = cpu_baseline(w, wl, keep, theta_h, masks, min(args.cpu_parts, w.n), nw, layers)
         # the same algorithmic bytes (fp32 sizes) per sample as the GPU figure, and the ratio
         cb["GBps"] = round(cb["value"] * 4.0 * w.d_in / 1e9, 2) if w.loss != wl.LOSS_MLP2 else None
         cb["gpu_over_oracle"] = round(out["value"] / cb["value"], 1) if cb["value"] else None
