@@ -69,17 +69,22 @@ def measured_figure(summary, source, key):
     return None
 
 
+def blas_threads():
+    """Threads the oracle's NumPy/BLAS calls run on."""
+    try:
+        from threadpoolctl import threadpool_info
+        return int(max([p.get("num_threads", 1) for p in threadpool_info()] or [1]))
+    except Exception:
+        return os.cpu_count() or 1
+
+
 def cpu_baseline(w, wl, parts_host, theta, masks, budget_parts, workers=None, layers=None):
     """The fp64 checker timed on the host cores over a bounded sample of the same
     workload: `budget_parts` partitions for the gradients, then encode of all
     layers, layer/decode-vector selection and decode at full n and d."""
     import numpy as np
     from oracle import codes, coding, gradients
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        cores = os.cpu_count() or 1
+    cores = blas_threads()
     workers = w.n if workers is None else workers        # w.n partitions shared out over the workers
     layers = w.layers if layers is None else layers
     Bs = codes.nested_code(workers, layers, "cyclic" if w.code == wl.CODE_CYCLIC else "fracrep",
@@ -203,13 +208,8 @@ def bench_codec(args, w, wl, ngc, torch, np):
             a, _ = coding.decode_vector(Bs[u], masks[W + t])
             coding.decode(a, Co[u])
         dt = (time.perf_counter() - t0) / rounds
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-        except Exception:
-            cores = os.cpu_count() or 1
         out["cpu_baseline"] = {"value": (enc_bytes + dec_bytes) / dt / 1e9, "unit": "GB/s",
-                               "cores": int(cores), "kind": "oracle",
+                               "cores": blas_threads(), "kind": "oracle",
                                "sample": "%d rounds of encode + select + decode at full n, d" % rounds}
     ngc.ngc_destroy(ctx)
     print(json.dumps(out), flush=True)
@@ -340,12 +340,7 @@ def bench_workers(args, w, wl, ngc, torch, np):
         Wp = ow.worker_partials(w.loss, Xh, Yh, theta_h, Bs, progress, w.hidden, w.classes)
         ow.decode_from_workers(Bs, w.layers, Wp, progress, 0)
         dt = time.perf_counter() - t0
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-        except Exception:
-            cores = os.cpu_count() or 1
-        out["cpu_baseline"] = {"value": w.m / dt, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+        out["cpu_baseline"] = {"value": w.m / dt, "unit": "samples/s", "cores": blas_threads(), "kind": "oracle",
                                "sample": "one iteration of the worker execution (%d tasks of %d samples) in %.2f s"
                                          % (int(progress.sum()), w.rows, dt)}
     print(json.dumps(out), flush=True)
