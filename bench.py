@@ -398,8 +398,7 @@ def bench_latency(args, ngc, torch, np):
     out["roofline"] = {"bound": "alu", "achieved": None if ach is None else round(ach, 2), "peak": round(peak, 1),
                        "unit": "T lane-ops/s", "frac": None if ach is None else round(ach / peak, 4),
                        "traffic": None, "kernel": "latency_sim_kernel (s_max = 6)",
-                       "note": "achieved = counted vector instructions x 64 lanes / launch time; the counter reads "
-                               "a few per cent above the issue limit, i.e. the vector ALUs are saturated",
+                       "note": "achieved = counted vector instructions of a launch x 64 lanes / launch time",
                        "avg_ms": round(trials / rate * 1e3, 4), "launches": args.steps}
     if not args.no_cpu_baseline:
         from oracle import latency as ol

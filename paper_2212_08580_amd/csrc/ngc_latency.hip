@@ -74,38 +74,53 @@ __host__ __device__ inline void philox4x32(uint32_t c0, uint32_t c1, uint32_t c2
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-template <int CTRL>
-__device__ __forceinline__ double dpp_max_step(double v) {
-    const long long bits = __builtin_bit_cast(long long, v);
-    int lo = (int)(bits & 0xFFFFFFFFLL), hi = (int)(bits >> 32);
-    lo = __builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xF, 0xF, false);
-    hi = __builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xF, 0xF, false);
-    const long long other = ((long long)hi << 32) | (unsigned int)lo;
-    return fmax(v, __builtin_bit_cast(double, other));
+// Values of each group of G consecutive lanes (G = 8, 16, 32 or 64) sorted in descending order
+// over the group's lanes: a bitonic network of log2(G) (log2(G) + 1) / 2 compare-exchange steps;
+// the partner's value comes through the cross-lane shuffle (LDS crossbar, not the vector ALU).
+// idx = lane % G.  +-inf are ordinary values here, NaN does not occur.
+template <int G>
+__device__ __forceinline__ double group_sort_desc(double v, int idx) {
+#pragma unroll
+    for (int k = 2; k <= G; k <<= 1) {
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            const double pv = __shfl_xor(v, j, 64);
+            // blocks of k lanes alternate between descending and ascending, the last pass
+            // (k = G) is descending everywhere; the lane with the lower index of a pair keeps
+            // the larger value in a descending block
+            const bool desc = k == G || (idx & k) == 0;
+            const bool lower = (idx & j) == 0;
+            const double hi = fmax(v, pv), lo = fmin(v, pv);
+            v = (lower == desc) ? hi : lo;
+        }
+    }
+    return v;
 }
 
-// maximum over each group of G consecutive lanes (G = 8, 16, 32 or 64), result in every lane
-// of the group
-template <int G>
-__device__ __forceinline__ double group_max(double v, int lane) {
-    v = dpp_max_step<0xB1>(v);   // quad_perm [1,0,3,2]
-    v = dpp_max_step<0x4E>(v);   // quad_perm [2,3,0,1]
-    v = dpp_max_step<0x141>(v);  // row_half_mirror: groups of 8 done
-    if (G == 8) return v;
-    v = dpp_max_step<0x140>(v);  // row_mirror: rows of 16 done
-    if (G == 16) return v;
-    const long long bits = __builtin_bit_cast(long long, v);
-    const int lo = (int)(bits & 0xFFFFFFFFLL), hi = (int)(bits >> 32);
-    double m[4];
-#pragma unroll
-    for (int row = 0; row < 4; ++row) {
-        const int l = __builtin_amdgcn_readlane(lo, row * 16);
-        const int h = __builtin_amdgcn_readlane(hi, row * 16);
-        m[row] = __builtin_bit_cast(double, ((long long)h << 32) | (unsigned int)l);
-    }
-    const double m01 = fmax(m[0], m[1]), m23 = fmax(m[2], m[3]);
-    if (G == 32) return lane < 32 ? m01 : m23;
-    return fmax(m01, m23);
+// -log((w + 0.5) / 2^32) for a 32-bit word w, to about 2e-16 absolute.
+// x = w + 0.5 = m 2^e with m in [1, 2); the top seven mantissa bits pick c = 1 + (i + 1/2)/128,
+// and with r = m / c - 1 (|r| <= 2^-8, one fused multiply-add on the tabulated 1/c)
+//   log x = e ln 2 + log c + log1p(r),
+// log1p by its series up to r^6 (the next term is below 2e-18).  tab[i] = (1/c, -log(1/c)): the
+// second entry belongs to the rounded first one, so the rounding of 1/c cancels.  ln 2 is split
+// so that its multiples by the small integer 32 - e carry no rounding error worth the name.
+__device__ __forceinline__ double neg_log_word(uint32_t w, const double2* __restrict__ tab) {
+    const double x = (double)w + 0.5;  // exact
+    const long long bits = __builtin_bit_cast(long long, x);
+    const int e = (int)(bits >> 52) - 1023;
+    const double m = __builtin_bit_cast(double, (bits & 0x000FFFFFFFFFFFFFLL) | 0x3FF0000000000000LL);
+    const double2 t = tab[(int)(bits >> 45) & 127];
+    const double r = fma(m, t.x, -1.0);
+    double p = fma(r, -1.0 / 6.0, 1.0 / 5.0);
+    p = fma(r, p, -1.0 / 4.0);
+    p = fma(r, p, 1.0 / 3.0);
+    p = fma(r, p, -1.0 / 2.0);
+    p = fma(r, p, 1.0);
+    const double ee = (double)(32 - e);
+    constexpr double LN2_HI = 0x1.62e42fefa38p-1, LN2_LO = 0x1.ef35793c7673p-45;  // hi: 42 bits
+    double acc = fma(ee, LN2_HI, -t.y);
+    acc = fma(ee, LN2_LO, acc);
+    return fma(-r, p, acc);
 }
 
 // A group of G lanes per trial (G = the smallest of 8, 16, 32, 64 that holds the n workers,
@@ -113,17 +128,23 @@ __device__ __forceinline__ double group_max(double v, int lane) {
 // decides failure, word u its u-th task time rho - log(U)/lambda (counter = (trial, worker,
 // block, 0), key = seed; U = (word + 0.5) / 2^32).  For u = 1..top the u-th largest
 // completion time of u tasks over the workers (= time at which n-u+1 workers have
-// finished u tasks) is found by knocking out the current maximum u-1 times.
+// finished u tasks) is lane u-1 of the group's times sorted in descending order.
 template <int G>
 __global__ __launch_bounds__(256) void latency_sim_kernel(double* __restrict__ L,
                                                           double* __restrict__ Tmin, int n, int top,
-                                                          double lam, double rho, double eps,
+                                                          double inv_lam, double rho, double eps,
                                                           double gamma, double pe, uint32_t k0,
                                                           uint32_t k1, int64_t trials) {
     constexpr int PER = 64 / G;  // trials per wave
+    // table of the logarithm: one copy per block, from the library logarithm
+    __shared__ double2 logtab[128];
+    if (threadIdx.x < 128) {
+        const double inv_c = 1.0 / (1.0 + ((double)threadIdx.x + 0.5) / 128.0);
+        logtab[threadIdx.x] = make_double2(inv_c, -log(inv_c));
+    }
+    __syncthreads();
     const int lane = threadIdx.x & 63;
     const int worker = lane % G, sub = lane / G;
-    const unsigned long long gmask = (G == 64 ? ~0ull : ((1ull << G) - 1ull)) << (sub * G);
     const int64_t wave0 = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t nwaves = (int64_t)gridDim.x * 4;
     const double base = gamma + eps;
@@ -136,17 +157,10 @@ __global__ __launch_bounds__(256) void latency_sim_kernel(double* __restrict__ L
         double cs = 0.0, best = INFINITY;
         for (int u = 1; u <= top; ++u) {
             if ((u & 3) == 0) philox4x32((uint32_t)r, (uint32_t)worker, (uint32_t)(u >> 2), 0u, k0, k1, w);
-            const double U = ((double)w[u & 3] + 0.5) / 4294967296.0;
-            cs += rho - log(U) / lam;
+            cs += fma(neg_log_word(w[u & 3], logtab), inv_lam, rho);
             double v = failed ? INFINITY : base + cs;
             if (worker >= n) v = -INFINITY;
-            for (int kth = 1; kth < u; ++kth) {
-                const double m = group_max<G>(v, lane);
-                const unsigned long long holders = __ballot(v == m) & gmask;
-                const int first = __ffsll((long long)holders) - 1;
-                if (lane == first) v = -INFINITY;
-            }
-            const double Lu = group_max<G>(v, lane);
+            const double Lu = __shfl(group_sort_desc<G>(v, worker), sub * G + (u - 1), 64);
             if (worker == 0 && live) L[(int64_t)(u - 1) * trials + r] = Lu;
             best = fmin(best, Lu);
         }
@@ -234,7 +248,7 @@ extern "C" int ngc_latency_simulate(void* hip_stream, int n, int smax, double la
     const unsigned blocks = (unsigned)(want < cap ? want : cap);
 #define NGC_LATENCY_LAUNCH(GG)                                                                             \
     hipLaunchKernelGGL(latency_sim_kernel<GG>, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, L_dev, \
-                       Tngc_dev, n, smax + 1, lam, rho, eps, gamma, pe, (uint32_t)seed,                    \
+                       Tngc_dev, n, smax + 1, 1.0 / lam, rho, eps, gamma, pe, (uint32_t)seed,              \
                        (uint32_t)(seed >> 32), trials)
     if (G == 8)
         NGC_LATENCY_LAUNCH(8);
