@@ -483,7 +483,13 @@ __device__ __forceinline__ float wave_sum(float v) {
 // are added in wave order at the end.  The next tile is fetched into registers
 // while the current one is consumed.  NCP is the class count rounded up;
 // classes beyond `classes` get logit -inf.
-template <int NCP>
+// FAST: the class count is NCP itself, rows of H are 16-byte addressable and the hidden layer is
+// a whole number of 128-unit rounds.  Then no load sits behind a condition (rows past the end
+// are read from the last row and dropped), and the W2 rows, which are the same for every lane,
+// come through wide scalar loads straight into the multiply-adds instead of being staged in
+// LDS and read back as broadcasts (three quarters of the LDS reads of the other variant).
+// Same order of additions either way.
+template <int NCP, bool FAST>
 __global__ __launch_bounds__(256) void mlp_logits_kernel(
     const float* __restrict__ H, const int* __restrict__ labels, const float* __restrict__ W2,
     const float* __restrict__ b2, float* __restrict__ dZ2, int hidden, int classes,
@@ -492,11 +498,13 @@ __global__ __launch_bounds__(256) void mlp_logits_kernel(
     constexpr int NCQ = (NCP + 3) / 4 * 4;  // W2 row padded to whole float4
     static_assert(NW * NCP * 64 <= NW * TR * LD, "the exchange of partial logits fits the tiles");
     __shared__ float tile_s[NW][TR * LD];
-    __shared__ float w2s_s[NW][TH * NCQ];
+    // the fast variant keeps no W2 rows in LDS: 36 KiB per block, so that four blocks fit a CU and
+    // the 64-row tiles of the usual batch sizes are all resident in one round
+    __shared__ float w2s_s[FAST ? 1 : NW][FAST ? 4 : TH * NCQ];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     float* tile = tile_s[wave];
-    float* w2s = w2s_s[wave];
+    float* w2s = w2s_s[FAST ? 0 : wave];
     const int64_t row0 = (int64_t)blockIdx.x * TR;
     const int64_t my_row = row0 + lane;
     float z[NCP];
@@ -507,6 +515,16 @@ __global__ __launch_bounds__(256) void mlp_logits_kernel(
     v4f stage[8];
     float wstage[(TH * NCQ + 63) / 64];
     auto fetch = [&](int hc) {
+        if (FAST) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = u * 64 + lane;
+                int64_t r = row0 + (idx >> 3);
+                r = r < total_rows ? r : total_rows - 1;
+                stage[u] = *reinterpret_cast<const v4f*>(H + r * hidden + hc + (idx & 7) * 4);
+            }
+            return;
+        }
 #pragma unroll
         for (int u = 0; u < (TH * NCQ + 63) / 64; ++u) {
             const int idx = u * 64 + lane;
@@ -523,8 +541,7 @@ __global__ __launch_bounds__(256) void mlp_logits_kernel(
         }
     };
     // the four waves take the 32-unit slices of the hidden layer in turn (wave w: slices w,
-    // w+4, ...), each through its own tile; a slice past the end is skipped by its wave,
-    // which still meets the others at the barriers
+    // w+4, ...), each through its own tile; a slice past the end is skipped by its wave
     if (wave * TH < hidden) fetch(wave * TH);
     for (int hb = 0; hb < hidden; hb += NW * TH) {
         const int hc = hb + wave * TH;
@@ -535,16 +552,30 @@ __global__ __launch_bounds__(256) void mlp_logits_kernel(
                 const int idx = u * 64 + lane;
                 *reinterpret_cast<v4f*>(&tile[(idx >> 3) * LD + (idx & 7) * 4]) = stage[u];
             }
+            if (!FAST) {
 #pragma unroll
-            for (int u = 0; u < (TH * NCQ + 63) / 64; ++u) {
-                const int idx = u * 64 + lane;
-                if (idx < TH * NCQ) w2s[idx] = wstage[u];
+                for (int u = 0; u < (TH * NCQ + 63) / 64; ++u) {
+                    const int idx = u * 64 + lane;
+                    if (idx < TH * NCQ) w2s[idx] = wstage[u];
+                }
             }
         }
-        __syncthreads();
+        // the tile and the W2 rows in LDS belong to this wave alone: its LDS writes and reads
+        // execute in program order, no barrier is needed between them
         if (hc + NW * TH < hidden) fetch(hc + NW * TH);
-        // units past `hidden` carry zeros in both the tile and the W2 rows
-        if (live) {
+        if (FAST) {
+            const float* wslice = W2 + (int64_t)hc * NCP;  // wave-uniform: scalar loads
+#pragma unroll
+            for (int g = 0; g < TH / 4; ++g) {
+                const v4f hv = *reinterpret_cast<const v4f*>(&tile[lane * LD + g * 4]);
+                const float he[4] = {hv.x, hv.y, hv.z, hv.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int q = 0; q < NCP; ++q) z[q] += he[e] * wslice[(g * 4 + e) * NCP + q];
+            }
+        } else if (live) {
+            // units past `hidden` carry zeros in both the tile and the W2 rows
 #pragma unroll
             for (int g = 0; g < TH / 4; ++g) {
                 const v4f hv = *reinterpret_cast<const v4f*>(&tile[lane * LD + g * 4]);
@@ -563,10 +594,10 @@ __global__ __launch_bounds__(256) void mlp_logits_kernel(
                 }
             }
         }
-        __syncthreads();
     }
-    // the waves' partial logits meet in LDS (the tiles are free now) and wave 0 adds them in
-    // wave order: a fixed order, whatever the timing
+    // the waves' partial logits meet in LDS, in the space of the tiles, once every wave is done
+    // with its own, and wave 0 adds them in wave order: a fixed order, whatever the timing
+    __syncthreads();
     float* zx = &tile_s[0][0];  // [NW][NCP][64]
 #pragma unroll
     for (int q = 0; q < NCP; ++q) zx[(wave * NCP + q) * 64 + lane] = z[q];
@@ -605,7 +636,12 @@ __global__ __launch_bounds__(256) void mlp_logits_kernel(
 // dH = dZ2 W2^T for its units, writes dZ1 = dH * [H > 0] over H and accumulates
 // dW2 += h dZ2, db1 += dZ1, db2 += dZ2 in registers: no exchange between threads.
 // Block partial layout = tail of theta: [db1 (hidden) | dW2 (hidden x classes) | db2 (classes)].
-template <int NCP>
+// FAST: the class count is NCP itself, rows of H are 16-byte addressable and every thread of
+// the block owns four existing units (hidden a multiple of 1024).  Whole trips of RB rows then
+// run without a condition around any load or store, so that each row's arithmetic waits for
+// its own load only and the dZ2 values of a row arrive in wide scalar loads; what is left of
+// the chunk, and every other shape, takes the guarded trip.  Same order of additions either way.
+template <int NCP, bool FAST>
 __global__ __launch_bounds__(256) void mlp_back_kernel(
     float* __restrict__ H, const float* __restrict__ dZ2, const float* __restrict__ W2,
     float* __restrict__ partial, int hidden, int classes, int64_t rows, int chunks,
@@ -632,9 +668,48 @@ __global__ __launch_bounds__(256) void mlp_back_kernel(
 
     float* Hp = H + ((int64_t)j * rows) * hidden + h0;
     const float* dzp = dZ2 + ((int64_t)j * rows) * classes;
+    // one row: dz = its dZ2 values (block-uniform), hq = this thread's four activations
+    auto one_row = [&](const float (&dz)[NCP], const v4f hq) -> v4f {
+        const float hv[4] = {hq.x, hq.y, hq.z, hq.w};
+        float dh[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int q = 0; q < NCP; ++q) {
+            db2[q] += dz[q];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                dw2[e][q] += hv[e] * dz[q];
+                dh[e] += dz[q] * w2[e][q];
+            }
+        }
+        v4f out;
+        out.x = hv[0] > 0.0f ? dh[0] : 0.0f;  // ReLU'(0) = 0
+        out.y = hv[1] > 0.0f ? dh[1] : 0.0f;
+        out.z = hv[2] > 0.0f ? dh[2] : 0.0f;
+        out.w = hv[3] > 0.0f ? dh[3] : 0.0f;
+        db1[0] += out.x;
+        db1[1] += out.y;
+        db1[2] += out.z;
+        db1[3] += out.w;
+        return out;
+    };
     // RB rows per trip: their loads are issued together before any is used
     constexpr int RB = 8;
-    for (int64_t rb = r0; rb < r1; rb += RB) {
+    int64_t rb = r0;
+    if (FAST) {
+        for (; rb + RB <= r1; rb += RB) {
+            v4f hq[RB];
+#pragma unroll
+            for (int u = 0; u < RB; ++u) hq[u] = *reinterpret_cast<const v4f*>(Hp + (rb + u) * hidden);
+#pragma unroll
+            for (int u = 0; u < RB; ++u) {
+                float dz[NCP];
+#pragma unroll
+                for (int q = 0; q < NCP; ++q) dz[q] = dzp[(rb + u) * NCP + q];  // block-uniform
+                *reinterpret_cast<v4f*>(Hp + (rb + u) * hidden) = one_row(dz, hq[u]);
+            }
+        }
+    }
+    for (; rb < r1; rb += RB) {
         v4f hq[RB];
 #pragma unroll
         for (int u = 0; u < RB; ++u) {
@@ -646,27 +721,10 @@ __global__ __launch_bounds__(256) void mlp_back_kernel(
             const int64_t r = rb + u;
             if (r < r1) {  // block-uniform
                 float* hrow = Hp + r * hidden;
-                const float hv[4] = {hq[u].x, hq[u].y, hq[u].z, hq[u].w};
-                float dh[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                float dz[NCP];
 #pragma unroll
-                for (int q = 0; q < NCP; ++q) {
-                    const float dz = q < classes ? dzp[r * classes + q] : 0.0f;  // block-uniform
-                    db2[q] += dz;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        dw2[e][q] += hv[e] * dz;
-                        dh[e] += dz * w2[e][q];
-                    }
-                }
-                v4f out;
-                out.x = hv[0] > 0.0f ? dh[0] : 0.0f;  // ReLU'(0) = 0
-                out.y = hv[1] > 0.0f ? dh[1] : 0.0f;
-                out.z = hv[2] > 0.0f ? dh[2] : 0.0f;
-                out.w = hv[3] > 0.0f ? dh[3] : 0.0f;
-                db1[0] += out.x;
-                db1[1] += out.y;
-                db1[2] += out.z;
-                db1[3] += out.w;
+                for (int q = 0; q < NCP; ++q) dz[q] = q < classes ? dzp[r * classes + q] : 0.0f;  // block-uniform
+                const v4f out = one_row(dz, hq[u]);
                 if (hleft >= 4 && h_vec_ok) {
                     *reinterpret_cast<v4f*>(hrow) = out;
                 } else {
@@ -820,10 +878,18 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
         dim3 lgrid((unsigned)((total + 63) / 64));
         dim3 grid((unsigned)(k * chunks), (unsigned)((hid + 1023) / 1024));  // y: 1024-unit hidden slices
 #define NGC_MLP_HEAD(NCP)                                                                              \
-    hipLaunchKernelGGL((mlp_logits_kernel<NCP>), lgrid, dim3(256), 0, ctx->stream, (const float*)H, labels, W2, \
-                       b2, dZ2, hid, cls, total, hv, rows, unit_part);                                 \
-    hipLaunchKernelGGL((mlp_back_kernel<NCP>), grid, dim3(256), 0, ctx->stream, H, (const float*)dZ2, W2,      \
-                       partial, hid, cls, rows, (int)chunks, rpc, hv);
+    if (hv && hid % 128 == 0 && cls == NCP)                                                            \
+        hipLaunchKernelGGL((mlp_logits_kernel<NCP, true>), lgrid, dim3(256), 0, ctx->stream, (const float*)H, \
+                           labels, W2, b2, dZ2, hid, cls, total, hv, rows, unit_part);                 \
+    else                                                                                               \
+        hipLaunchKernelGGL((mlp_logits_kernel<NCP, false>), lgrid, dim3(256), 0, ctx->stream, (const float*)H, \
+                           labels, W2, b2, dZ2, hid, cls, total, hv, rows, unit_part);                 \
+    if (hv && hid % 1024 == 0 && cls == NCP)                                                           \
+        hipLaunchKernelGGL((mlp_back_kernel<NCP, true>), grid, dim3(256), 0, ctx->stream, H, (const float*)dZ2, \
+                           W2, partial, hid, cls, rows, (int)chunks, rpc, hv);                         \
+    else                                                                                               \
+        hipLaunchKernelGGL((mlp_back_kernel<NCP, false>), grid, dim3(256), 0, ctx->stream, H, (const float*)dZ2, \
+                           W2, partial, hid, cls, rows, (int)chunks, rpc, hv);
         if (cls <= 4) {
             NGC_MLP_HEAD(4)
         } else if (cls <= 10) {
