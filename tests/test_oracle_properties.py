@@ -82,3 +82,32 @@ def test_library_selection_agrees_with_the_oracle_on_the_same_code(ngc, case, ma
             assert np.allclose(a, a_o, rtol=0, atol=1e-8 * (1 + np.abs(a_o).max()))
     finally:
         ngc.ngc_destroy(ctx)
+
+
+# ---- latency model: the library's dynamic programme against the oracle's nested sum, and the
+# ---- properties any latency distribution of Sec. IV must have -----------------------------------
+@settings(max_examples=60, deadline=None)
+@given(st.integers(2, 7), st.data())
+def test_latency_closed_forms_on_random_parameters(ngc, n, data):
+    from oracle import latency as ol
+    smax = data.draw(st.integers(0, n - 1))
+    lam = data.draw(st.floats(0.2, 3.0))
+    rho = data.draw(st.floats(0.0, 1.0))
+    eps = data.draw(st.floats(0.0, 0.5))
+    gamma = data.draw(st.floats(0.0, 0.5))
+    pe = data.draw(st.floats(0.0, 0.4))
+    ts = np.linspace(gamma + eps, gamma + eps + (smax + 1) * (rho + 6.0 / lam), 9)
+    nested = ngc.ngc_latency_cdf_ngc(n, smax, lam, rho, eps, gamma, pe, ts)
+    nested_o = np.array([ol.ngc_cdf(t, n, smax, lam, rho, eps, gamma, pe) for t in ts])
+    assert np.allclose(nested, nested_o, rtol=1e-9, atol=1e-12)
+    assert np.all(np.diff(nested) >= -1e-12) and nested[0] <= 1e-12 and nested[-1] <= 1.0 + 1e-12
+    for sigma in range(smax + 1):
+        fixed = ngc.ngc_latency_cdf_gc(n, sigma, lam, rho, eps, gamma, pe, ts)
+        fixed_o = np.array([ol.gc_cdf(t, n, sigma, lam, rho, eps, gamma, pe) for t in ts])
+        assert np.allclose(fixed, fixed_o, rtol=1e-9, atol=1e-12)
+        # the nested code stops no later than any of its component codes (Sec. IV)
+        assert np.all(nested >= fixed - 1e-9)
+    # a code with a single layer sigma = 0 is the uncoded scheme: every worker must finish one task
+    uncoded = ngc.ngc_latency_cdf_gc(n, 0, lam, rho, eps, gamma, pe, ts)
+    F1 = np.array([ol.layer_cdf(1, t, lam, rho, eps, gamma) for t in ts])
+    assert np.allclose(uncoded, (1.0 - pe) ** n * F1 ** n, rtol=1e-9, atol=1e-12)
