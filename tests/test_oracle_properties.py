@@ -1,7 +1,7 @@
 """Property pins for the oracle on randomly drawn small codes (hypothesis): Def. 1 by brute
 force over every tolerated straggler set, Def. 2, exact recovery of the sum of the partial
-gradients from every sufficient layer, and agreement of the library's host-side selection
-with the oracle's on the same code."""
+gradients from every sufficient layer, agreement of the library's host-side selection with the
+oracle's on the same code, and the latency model's closed forms on random parameters."""
 import itertools
 
 import numpy as np
