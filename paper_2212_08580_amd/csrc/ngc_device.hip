@@ -985,7 +985,10 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
         // a CU holds 8 such waves (2 per SIMD at up to 256 registers), so it takes
         // 8 / waves whole blocks; more blocks than that would run as a second,
         // partly filled round
-        const int per_cu = std::max(1, 8 / sh.waves);
+        // rows of at most 128 features fill no more than half of a wave's lanes: twice the
+        // blocks keep as many bytes in flight (measured: 3.1 -> 3.6 TB/s at 64 features,
+        // 4.3 -> 5.0 at 100, 5.5 -> 6.1 at 128; wider rows lose 2 % with more than 8)
+        const int per_cu = (sh.waves == 1 && !sh.scalar && d <= 128) ? 16 : std::max(1, 8 / sh.waves);
         const int64_t block_slots = (int64_t)ctx->cu_count * per_cu;
         int64_t chunks = std::max<int64_t>(1, block_slots / k);
         int64_t rpc = (rows + chunks - 1) / chunks;
