@@ -145,6 +145,26 @@ int ngc_partition_grads(ngc_ctx* ctx, int loss, const float* X_dev, const void* 
                         const float* theta_dev, int64_t rows_per_part, float* G_dev);
 
 /*
+ * ngc_partition_grads for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and, for a shape it accepts, the same bits as ngc_partition_grads, but the block
+ * partials of the gradient kernels go to a device array of fixed size that is part of the
+ * library image (20 MiB, held by every GPU the library runs on until the process ends)
+ * instead of the context's workspace.  The call makes no hipMalloc / hipFree and creates no
+ * event (its launches are not recorded by ngc_profile_*).  The very first call on a device
+ * looks up the array's address there; make that call outside a capture.
+ *   Limits: NGC_LOSS_LSQ and NGC_LOSS_LOGISTIC only (the perceptron's activations do not
+ *   fit), and shapes whose block partials fit the array: every single-pass shape
+ *   (d <= 16384) does; beyond that 4 * k * (d + rows_per_part) bytes plus 0.5 MiB must
+ *   stay below 20 MiB.  Anything else returns NGC_ERR_INVALID and launches nothing.
+ *   All calls on one GPU share the one array, whichever context they use: calls that
+ *   overlap in time on one GPU (two streams, two host threads) race on it.  Nothing in it
+ *   has to start at zero (every partial is written before it is read), so it is not cleared.
+ */
+int ngc_partition_grads_static(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_dev,
+                               const float* theta_dev, int64_t rows_per_part, float* G_dev);
+
+/*
  * Worker messages C = B G (Sec. II-C) layer by layer:
  *   C[u][i][:] = sum_j B^(u)[i][j] G[j][:]   in fp32.
  * G_dev: float [k][d].  C_dev: float [L][n][d].  layer = -1 encodes every

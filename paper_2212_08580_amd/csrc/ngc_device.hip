@@ -13,6 +13,8 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
+#include <string>
 
 #include "ngc_internal.h"
 
@@ -815,7 +817,7 @@ struct prof_scope {
     ngc_ctx* ctx;
     int rec = -1;
     prof_scope(ngc_ctx* c, int kernel) : ctx(c) {
-        if (!((c->profile_mask >> kernel) & 1u) || c->prof.size() >= (size_t)NGC_MAX_PROFILE) return;
+        if (c->prof_suspended || !((c->profile_mask >> kernel) & 1u) || c->prof.size() >= (size_t)NGC_MAX_PROFILE) return;
         ngc_profile_rec r;
         r.kernel = kernel;
         auto get = [&](hipEvent_t& e) {
@@ -970,10 +972,27 @@ struct partial_info {
 
 // If `defer` is given the block partials are left unreduced for the caller to sum (in chunk
 // order) and G_dev is not written.
+// With `fixed_ws` the block partials go to that buffer of fixed_bytes bytes instead of the
+// context's workspace, nothing is allocated, and a need beyond it is NGC_ERR_INVALID.
 static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_dev,
                       const float* theta_dev, int64_t rows, float* G_dev, int units,
-                      const int* unit_part, const int* unit_row, partial_info* defer = nullptr) {
+                      const int* unit_part, const int* unit_row, partial_info* defer = nullptr,
+                      float* fixed_ws = nullptr, size_t fixed_bytes = 0) {
     int rc = NGC_OK;
+    float* ws = nullptr;
+    auto get_ws = [&](size_t bytes) -> int {
+        if (fixed_ws) {
+            if (bytes > fixed_bytes)
+                return ngc_fail(ctx, NGC_ERR_INVALID,
+                                "this shape needs " + std::to_string(bytes) + " bytes of scratch, the static scratch holds " +
+                                    std::to_string(fixed_bytes));
+            ws = fixed_ws;
+            return NGC_OK;
+        }
+        const int e = ensure_ws(ctx, bytes);
+        ws = ctx->d_ws;
+        return e;
+    };
     const int k = units;
     const int64_t d = ctx->d;
     const float* y = (const float*)y_dev;
@@ -995,11 +1014,11 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
         const int64_t quantum = 2 * sh.r;  // two row groups: one trip of the kernel's loop
         rpc = ((rpc + quantum - 1) / quantum) * quantum;
         chunks = (rows + rpc - 1) / rpc;
-        rc = ensure_ws(ctx, sizeof(float) * (size_t)k * chunks * d);
+        rc = get_ws(sizeof(float) * (size_t)k * chunks * d);
         if (rc) return rc;
         {
             prof_scope ps(ctx, NGC_KERNEL_GRAD);
-#define NGC_STREAM_ARGS ctx, loss, X_dev, y, theta_dev, ctx->d_ws, k, rows, (int)chunks, rpc, unit_part, (int)(sh.scalar ? d : d / 4)
+#define NGC_STREAM_ARGS ctx, loss, X_dev, y, theta_dev, ws, k, rows, (int)chunks, rpc, unit_part, (int)(sh.scalar ? d : d / 4)
 #define NGC_STREAM_CASE(NV, R, W, RG) \
     case W: launch_stream<NV, R, 2, W, RG>(NGC_STREAM_ARGS); break;
 #define NGC_STREAM_SCALAR(NV, R, W) \
@@ -1068,7 +1087,7 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
         }
         NGC_HIP(ctx, hipGetLastError());
         if (defer) {
-            defer->ptr = ctx->d_ws;
+            defer->ptr = ws;
             defer->chunks = (int)chunks;
             return NGC_OK;
         }
@@ -1078,10 +1097,10 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
             dim3 grid((unsigned)((dv + 255) / 256), (unsigned)k);
             if (sh.scalar)
                 hipLaunchKernelGGL((reduce_partials_kernel<float>), grid, dim3(256), 0, ctx->stream,
-                                   (const float*)ctx->d_ws, G_dev, dv, (int)chunks, unit_row);
+                                   (const float*)ws, G_dev, dv, (int)chunks, unit_row);
             else
                 hipLaunchKernelGGL((reduce_partials_kernel<v4f>), grid, dim3(256), 0, ctx->stream,
-                                   (const v4f*)ctx->d_ws, (v4f*)G_dev, dv, (int)chunks, unit_row);
+                                   (const v4f*)ws, (v4f*)G_dev, dv, (int)chunks, unit_row);
         }
         NGC_HIP(ctx, hipGetLastError());
         return NGC_OK;
@@ -1094,10 +1113,10 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
     int64_t rpc = (rows + chunks - 1) / chunks;
     chunks = (rows + rpc - 1) / rpc;
     const size_t resid_floats = ((size_t)total_rows + 63) / 64 * 64;
-    rc = ensure_ws(ctx, sizeof(float) * (resid_floats + (size_t)k * chunks * d));
+    rc = get_ws(sizeof(float) * (resid_floats + (size_t)k * chunks * d));
     if (rc) return rc;
-    float* resid = ctx->d_ws;
-    float* partial = ctx->d_ws + resid_floats;
+    float* resid = ws;
+    float* partial = ws + resid_floats;
     {
         prof_scope ps(ctx, NGC_KERNEL_GRAD);
         const int64_t blocks = std::min<int64_t>((total_rows + 3) / 4, (int64_t)ctx->cu_count * 8);
@@ -1143,6 +1162,58 @@ extern "C" int ngc_partition_grads(ngc_ctx* ctx, int loss, const float* X_dev, c
     }
     if (loss != NGC_LOSS_LSQ && loss != NGC_LOSS_LOGISTIC) return ngc_fail(ctx, NGC_ERR_INVALID, "unknown loss");
     return grads_impl(ctx, loss, X_dev, y_dev, theta_dev, rows, G_dev, ctx->k, nullptr, nullptr);
+} catch (...) {
+    return ngc_on_exception();
+}
+
+// ---- partition gradients without any allocation ------------------------------------------
+// The block partials of the gradient kernels go to a file-scope device array instead of the
+// context's workspace.  Its name is only a host-side handle: the address a kernel can use is
+// looked up once per device with hipGetSymbolAddress (each GPU holds its own copy of the array
+// at its own address) and that pointer is what the launches get.
+constexpr size_t NGC_STATIC_SCRATCH_BYTES = (size_t)20 << 20;
+constexpr int NGC_MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[NGC_STATIC_SCRATCH_BYTES];
+static float* static_scratch_ptr[NGC_MAX_DEVICES];  // per device, filled on the first call there
+static std::mutex static_scratch_lock;
+
+static int static_scratch(ngc_ctx* ctx, float** out) {
+    int dev = -1;
+    NGC_HIP(ctx, hipGetDevice(&dev));
+    if (dev < 0 || dev >= NGC_MAX_DEVICES) return ngc_fail(ctx, NGC_ERR_INVALID, "device index out of range");
+    std::lock_guard<std::mutex> hold(static_scratch_lock);
+    if (!static_scratch_ptr[dev]) {
+        void* p = nullptr;
+        NGC_HIP(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return ngc_fail(ctx, NGC_ERR_HIP, "hipGetSymbolAddress gave a null address");
+        static_scratch_ptr[dev] = (float*)p;
+    }
+    *out = static_scratch_ptr[dev];
+    return NGC_OK;
+}
+
+extern "C" int ngc_partition_grads_static(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_dev,
+                                          const float* theta_dev, int64_t rows, float* G_dev) try {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (!X_dev || !y_dev || !theta_dev || !G_dev) return ngc_fail(ctx, NGC_ERR_INVALID, "null device pointer");
+    if (rows < 1) return ngc_fail(ctx, NGC_ERR_INVALID, "rows_per_part must be positive");
+    if (!aligned16(X_dev) || !aligned16(theta_dev) || !aligned16(G_dev))
+        return ngc_fail(ctx, NGC_ERR_INVALID, "X, theta and G must be 16-byte aligned");
+    if (loss == NGC_LOSS_MLP2)
+        return ngc_fail(ctx, NGC_ERR_INVALID, "the perceptron's activations do not fit the static scratch");
+    if (loss != NGC_LOSS_LSQ && loss != NGC_LOSS_LOGISTIC) return ngc_fail(ctx, NGC_ERR_INVALID, "unknown loss");
+    int rc = dev_init(ctx);
+    if (rc) return rc;
+    float* ws = nullptr;
+    rc = static_scratch(ctx, &ws);
+    if (rc) return rc;
+    // no event is created on this path: launches here are not recorded by the profiler
+    const bool was = ctx->prof_suspended;
+    ctx->prof_suspended = true;
+    rc = grads_impl(ctx, loss, X_dev, y_dev, theta_dev, rows, G_dev, ctx->k, nullptr, nullptr, nullptr, ws,
+                    NGC_STATIC_SCRATCH_BYTES);
+    ctx->prof_suspended = was;
+    return rc;
 } catch (...) {
     return ngc_on_exception();
 }

@@ -76,6 +76,7 @@ struct ngc_ctx {
     int wtab_T = 0;
 
     unsigned profile_mask = 0;       // bit k: time launches of kernel id k
+    bool prof_suspended = false;     // set while an entry point that must not create events runs
     std::vector<ngc_profile_rec> prof;
     std::vector<hipEvent_t> event_pool;
 

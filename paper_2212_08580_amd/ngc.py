@@ -34,7 +34,7 @@ NGC_KERNEL_COUNT = len(NGC_KERNEL_NAMES)
 
 EXPORTS = (
     "ngc_create", "ngc_destroy", "ngc_set_code", "ngc_get_code", "ngc_get_shape", "ngc_build_code",
-    "ngc_set_mlp2_shape", "ngc_partition_grads", "ngc_encode", "ngc_select_decode_vec",
+    "ngc_set_mlp2_shape", "ngc_partition_grads", "ngc_partition_grads_static", "ngc_encode", "ngc_select_decode_vec",
     "ngc_select_decode_vec_first", "ngc_decode", "ngc_update", "ngc_iteration", "ngc_sync",
     "ngc_worker_task_count", "ngc_worker_schedule", "ngc_worker_grads", "ngc_worker_encode",
     "ngc_select_from_progress", "ngc_build_decoding_table", "ngc_decoding_row_index",
@@ -62,6 +62,7 @@ _lib.ngc_get_shape.argtypes = [_vp, ctypes.POINTER(_i), ctypes.POINTER(_i), ctyp
                                ctypes.POINTER(_i64), ctypes.POINTER(_i)]
 _lib.ngc_set_mlp2_shape.argtypes = [_vp, _i, _i, _i]
 _lib.ngc_partition_grads.argtypes = [_vp, _i, _vp, _vp, _vp, _i64, _vp]
+_lib.ngc_partition_grads_static.argtypes = _lib.ngc_partition_grads.argtypes
 _lib.ngc_encode.argtypes = [_vp, _vp, _i, _vp]
 _lib.ngc_select_decode_vec.argtypes = [_vp, _vp, ctypes.POINTER(_i), _vp, ctypes.POINTER(_dbl)]
 _lib.ngc_select_decode_vec_first.argtypes = _lib.ngc_select_decode_vec.argtypes
@@ -210,6 +211,13 @@ def ngc_partition_grads(ctx, loss, X, y, theta, rows_per_part, G):
     pX, py, pt = _data_args(ctx, loss, X, y, theta, rows_per_part)
     _check(_lib.ngc_partition_grads(ctx, int(loss), pX, py, pt, int(rows_per_part),
                                     _dev(G, k * d, "float32")), ctx)
+
+
+def ngc_partition_grads_static(ctx, loss, X, y, theta, rows_per_part, G):
+    n, k, L, d, din = ngc_get_shape(ctx)
+    pX, py, pt = _data_args(ctx, loss, X, y, theta, rows_per_part)
+    _check(_lib.ngc_partition_grads_static(ctx, int(loss), pX, py, pt, int(rows_per_part),
+                                           _dev(G, k * d, "float32")), ctx)
 
 
 def ngc_encode(ctx, G, layer, C):
