@@ -61,7 +61,8 @@ enum {
     NGC_KERNEL_MLP = 5,     /* all GEMM-shaped kernels of the MLP gradient                  */
     NGC_KERNEL_PROBE = 6,   /* ngc_probe_copy / ngc_probe_read                              */
     NGC_KERNEL_TAIL = 7,    /* fused reduce + encode + decode + update of ngc_iteration     */
-    NGC_KERNEL_COUNT = 8
+    NGC_KERNEL_ROUNDS = 8,  /* fused encode + decode of ngc_encode_decode / ngc_coded_rounds */
+    NGC_KERNEL_COUNT = 9
 };
 
 /*
@@ -203,6 +204,41 @@ int ngc_select_decode_vec_first(const ngc_ctx* ctx, const uint8_t* straggler_mas
 int ngc_decode(ngc_ctx* ctx, int layer, const double* a_host, const float* C_dev, float* g_dev);
 
 /*
+ * Encode and decode of one round in one pass over G (Sec. II-C, X = B G, followed by the
+ * recovery of Def. 1): for every worker i with a[i] != 0 the message of the given layer
+ *   M[i][:] = fp32( sum_j B^(layer)[i][j] G[j][:] )
+ * is formed, rounded to fp32 and written (a worker sends fp32; rows of stragglers are left
+ * untouched), and  g[:] = fp32( sum_i a[i] * (double) M[i][:] )  is accumulated from the
+ * rounded messages while they are still in registers: G is read once, no message is read
+ * back.  Same bits as ngc_encode(layer) followed by ngc_decode(layer, a) on the rows it
+ * writes.  G_dev: float [k][d].  a_host: double [n], as returned by ngc_select_decode_vec.
+ * M_dev: float [n][d].  g_dev: float [d].  Asynchronous on the context's stream.
+ */
+int ngc_encode_decode(ngc_ctx* ctx, const float* G_dev, int layer, const double* a_host,
+                      float* M_dev, float* g_dev);
+
+/*
+ * Many rounds of encode + decode in one launch.  masks_host: uint8 [rounds][n], one
+ * straggler mask per round (1 = straggler).  For every round r the main node's bookkeeping
+ * (layer by the Observation after Def. 2, least-norm decode vector as in
+ * ngc_select_decode_vec) is done on the host up front, the vectors go to the device as one
+ * table, and one kernel then forms, for every round, the messages of that round's layer for
+ * its responders and the recovered gradient, exactly as ngc_encode_decode does (same bits):
+ *   G of round r  = G_dev + r * g_round_stride   (float [k][d]; stride 0: one G for all rounds,
+ *                                                 read from HBM once per block, else >= k*d)
+ *   messages      -> M_dev + r * m_round_stride  (float [n][d]; stride >= n*d)
+ *   gradient      -> g_dev + r * d               (float [rounds][d])
+ * layers_out (int [rounds], may be NULL) receives each round's layer, -1 for a round with
+ * more stragglers than the largest tolerance: such a round writes a zero gradient and no
+ * message and is not an error.  a_out (double [rounds][n], may be NULL) receives the decode
+ * vectors.  NGC_ERR_SINGULAR if a round's residual is above tolerance (nothing is launched).
+ * The host part runs on a few threads; the call returns when the kernel is enqueued.
+ */
+int ngc_coded_rounds(ngc_ctx* ctx, const float* G_dev, int64_t g_round_stride, int rounds,
+                     const uint8_t* masks_host, float* M_dev, int64_t m_round_stride, float* g_dev,
+                     int* layers_out, double* a_out);
+
+/*
  * Redundancy-faithful execution (Sec. III, layered task scheduling): worker i
  * works through the partitions of its nested supports layer by layer -- its own
  * partition first (sigma = 0), then what each larger sigma adds, new partitions
@@ -221,7 +257,9 @@ int ngc_decode(ngc_ctx* ctx, int layer, const double* a_host, const float* C_dev
  * ngc_worker_encode: C[u][i][:] = sum_t B^(u)[i][part(i,t)] W[i][t][:] (Sec.
  *   II-C, X = B G, from the worker's own copies) for every layer u whose
  *   s[u]+1 tasks worker i has finished; rows of unfinished (u, i) are set to
- *   zero.  C_dev: float [L][n][d].  At most 8 layers.
+ *   zero.  C_dev: float [L][n][d].  Any number of layers (Def. 2: sigma = 0..s_max);
+ *   a worker's rows of W are read once per run of eight layers.  Only rows the worker
+ *   has computed are read (at most its own schedule's length).
  * ngc_select_from_progress: the main node's termination rule (Sec. IV, proof of
  *   Theorem 1): the smallest layer u >= min_layer for which at least n - s[u]
  *   workers have finished their layer-u tasks; mask_out[i] = 1 for workers not
@@ -310,11 +348,20 @@ int ngc_update(ngc_ctx* ctx, float* theta_dev, const float* g_dev, double scale)
  * [k][d], C_dev [L][n][d], g_dev [d] are all written; theta_dev is read and
  * updated; all five device buffers 16-byte aligned.  layer_out / a_out (n
  * doubles) may be NULL.  An undecodable mask returns NGC_ERR_UNDECODABLE before
- * anything is launched (theta stays as it is).
+ * anything is launched (theta stays as it is).  The second launch keeps its column
+ * tiles, and the compressed code tables if they fit beside them, in LDS; tables too
+ * large for that (the full layer set sigma = 0..31 of 64 workers has 33 792 non-zeros)
+ * are read from global memory instead, with the same results.
  */
 int ngc_iteration(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_dev, float* theta_dev,
                   int64_t rows_per_part, const uint8_t* straggler_mask, double scale, float* G_dev,
                   float* C_dev, float* g_dev, int* layer_out, double* a_out);
+
+/* LDS bytes per block of ngc_iteration's second launch at vector width 1, 2 or 4 floats per
+ * lane, with the code tables in LDS and without (either output may be NULL).  Host only;
+ * every layer must have its code. */
+int ngc_tail_lds_bytes(const ngc_ctx* ctx, int vec_width, int64_t* with_tables_out,
+                       int64_t* without_tables_out);
 
 /* Block until the context's stream is idle. */
 int ngc_sync(ngc_ctx* ctx);

@@ -1,12 +1,10 @@
-// Device side of libngc for gfx950 (CDNA4, wave64): partition gradients,
-// layered encode, decode and the descent update, plus their launchers.
+// Device side of libngc for gfx950 (CDNA4, wave64): partition gradients and the
+// descent update, their launchers, per-kernel timing and the measurement probes.
+// Encode, decode and the fused passes are in ngc_codec.hip.
 //
-// Bandwidth picture (fp32 everywhere on the device):
-//  * partition gradients read every row of X from HBM exactly once; all other
-//    traffic (theta, labels, block partials, G) is below 2 % of that;
-//  * encode reads a column tile of G once into LDS and writes every layer's
-//    messages from it;
-//  * decode reads the responders' messages once.
+// Bandwidth picture (fp32 everywhere on the device): partition gradients read every
+// row of X from HBM exactly once; all other traffic (theta, labels, block partials,
+// G) is below 2 % of that.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -16,17 +14,7 @@
 #include <mutex>
 #include <string>
 
-#include "ngc_internal.h"
-
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef float v2f __attribute__((ext_vector_type(2)));
-
-#define NGC_HIP(ctx, call)                                                                  \
-    do {                                                                                    \
-        hipError_t e_ = (call);                                                             \
-        if (e_ != hipSuccess)                                                               \
-            return ngc_fail(ctx, NGC_ERR_HIP, std::string(#call) + ": " + hipGetErrorString(e_)); \
-    } while (0)
+#include "ngc_dev_common.h"
 
 // ---------------------------------------------------------------------------
 // wave-wide sum, result in every lane.  Four DPP steps give each row of 16
@@ -302,416 +290,12 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const VT* __restri
     G[(int64_t)(unit_row ? unit_row[j] : j) * dv + c] = acc;
 }
 
-// ---------------------------------------------------------------------------
-// K3: layered encode.  A block stages a tile of G (all n rows, 64*V columns) in
-// LDS, then each of its eight waves writes the messages of (layer, worker) pairs from
-// there, one pair at a time: a pair is one sparse row of B^(u) in compressed
-// form, and since the whole wave works on the same pair its column indices and
-// coefficients are wave-uniform (scalar loads); only the tile reads and the
-// FMAs are per lane.  pair p = u*n + i is also the row index of C viewed as
-// [L*n][d].  G is read from HBM once per column tile however many layers there
-// are (blocks that share a tile re-read it from L2).
-// ---------------------------------------------------------------------------
-constexpr int ENC_WAVES = 8;  // waves per block sharing one LDS tile of G
-
-template <typename VT, int V>
-__global__ __launch_bounds__(ENC_WAVES * 64) void encode_kernel(const float* __restrict__ G,
-                                                     float* __restrict__ C,
-                                                     const int* __restrict__ rowptr,
-                                                     const int* __restrict__ col,
-                                                     const float* __restrict__ coef, int n,
-                                                     int64_t d, int pair_begin, int pair_end) {
-    // n here: rows of G (the k partitions)
-    extern __shared__ float tile_raw[];
-    VT* tile = reinterpret_cast<VT*>(tile_raw);  // [k][64]
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t c = ((int64_t)blockIdx.x * 64 + lane) * V;
-    const bool in = c < d;
-    // staging: eight rows per trip so that their loads are in flight together
-    for (int r0 = wave; r0 < n; r0 += 8 * ENC_WAVES) {
-        VT v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int r = r0 + ENC_WAVES * u;
-            v[u] = (VT)(0.0f);
-            if (in && r < n) v[u] = *reinterpret_cast<const VT*>(G + (int64_t)r * d + c);
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int r = r0 + ENC_WAVES * u;
-            if (r < n) tile[r * 64 + lane] = v[u];
-        }
-    }
-    __syncthreads();
-    // pairs are dealt to the blocks of a column tile and to their waves in turn, so that
-    // every wave gets rows of every layer (layers differ in row weight by up to s_max+1)
-    const int stride = (int)gridDim.y * ENC_WAVES;
-    for (int p = pair_begin + (int)blockIdx.y * ENC_WAVES + wave; p < pair_end; p += stride) {
-        const int b = rowptr[p], e = rowptr[p + 1];
-        VT acc0 = (VT)(0.0f), acc1 = (VT)(0.0f);
-        int t = b;
-        // eight terms at a time: their indices and coefficients arrive in two wide
-        // scalar loads and the eight tile reads are in flight together
-        for (; t + 8 <= e; t += 8) {
-            int cc[8];
-            float ww[8];
-            VT x[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                cc[u] = col[t + u];
-                ww[u] = coef[t + u];
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) x[u] = tile[cc[u] * 64 + lane];
-#pragma unroll
-            for (int u = 0; u < 8; u += 2) {
-                acc0 += ww[u] * x[u];
-                acc1 += ww[u + 1] * x[u + 1];
-            }
-        }
-        // remainder: same order of additions as one term at a time, loads batched
-        if (t + 4 <= e) {
-            int cc[4];
-            float ww[4];
-            VT x[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                cc[u] = col[t + u];
-                ww[u] = coef[t + u];
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) x[u] = tile[cc[u] * 64 + lane];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) acc0 += ww[u] * x[u];
-            t += 4;
-        }
-        if (t + 2 <= e) {
-            const int c0 = col[t], c1 = col[t + 1];
-            const float w0 = coef[t], w1 = coef[t + 1];
-            const VT x0 = tile[c0 * 64 + lane], x1 = tile[c1 * 64 + lane];
-            acc0 += w0 * x0;
-            acc0 += w1 * x1;
-            t += 2;
-        }
-        if (t < e) acc0 += coef[t] * tile[col[t] * 64 + lane];
-        if (in) *reinterpret_cast<VT*>(C + (int64_t)p * d + c) = acc0 + acc1;
-    }
-}
-
-// ---------------------------------------------------------------------------
-// K4: decode.  g = sum_t a[t] * C[idx[t]][:], products and sum in fp64, one
-// rounding to fp32.  A block covers 16*V columns; its 16 groups of 16 lanes take
-// every sixteenth responder and their partial sums are added in group order.
-// ---------------------------------------------------------------------------
-struct decode_args {
-    double a[NGC_MAX_N];
-    int idx[NGC_MAX_N];
-    int count;
-};
-
-template <typename VT, int V>
-__global__ __launch_bounds__(256) void decode_kernel(const float* __restrict__ Cl,
-                                                     float* __restrict__ g, int64_t d,
-                                                     decode_args args) {
-    __shared__ double part[16][16 * V + 1];
-    const int lane16 = threadIdx.x & 15;
-    const int slot = threadIdx.x >> 4;
-    const int64_t c = ((int64_t)blockIdx.x * 16 + lane16) * V;
-    double acc[V];
-#pragma unroll
-    for (int v = 0; v < V; ++v) acc[v] = 0.0;
-    if (c < d) {
-        for (int t = slot; t < args.count; t += 16) {
-            VT m = *reinterpret_cast<const VT*>(Cl + (int64_t)args.idx[t] * d + c);
-            const double a = args.a[t];
-            if constexpr (V == 1) {
-                acc[0] += a * (double)m;
-            } else {
-#pragma unroll
-                for (int v = 0; v < V; ++v) acc[v] += a * (double)m[v];
-            }
-        }
-    }
-#pragma unroll
-    for (int v = 0; v < V; ++v) part[slot][lane16 * V + v] = acc[v];
-    __syncthreads();
-    // thread q < 16*V sums column q of the tile over the 16 groups, in group order
-    const int q = threadIdx.x;
-    if (q < 16 * V) {
-        const int64_t cq = (int64_t)blockIdx.x * 16 * V + q;
-        if (cq < d) {
-            double s = part[0][q];
-#pragma unroll
-            for (int k = 1; k < 16; ++k) s += part[k][q];
-            g[cq] = (float)s;
-        }
-    }
-}
-
-// The same combination for long gradients (d of several hundred thousand): one thread per
-// V columns, so a wave reads 64*V consecutive floats of a message at a time, sixteen
-// messages in flight.  The sixteen partial sums of decode_kernel's lane groups are kept in
-// registers and added in the same order, so both kernels give the same bits.
-template <typename VT, int V>
-__global__ __launch_bounds__(256) void decode_wide_kernel(const float* __restrict__ Cl,
-                                                          float* __restrict__ g, int64_t d,
-                                                          decode_args args) {
-    const int64_t c = ((int64_t)blockIdx.x * 256 + threadIdx.x) * V;
-    if (c >= d) return;
-    double acc[16][V];
-#pragma unroll
-    for (int k = 0; k < 16; ++k)
-#pragma unroll
-        for (int v = 0; v < V; ++v) acc[k][v] = 0.0;
-    for (int t0 = 0; t0 < args.count; t0 += 16) {
-        VT m[16];
-#pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            const int t = t0 + k < args.count ? t0 + k : args.count - 1;  // repeats get weight 0
-            m[k] = *reinterpret_cast<const VT*>(Cl + (int64_t)args.idx[t] * d + c);
-        }
-#pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            if (t0 + k < args.count) {  // block-uniform
-                const double a = args.a[t0 + k];
-                if constexpr (V == 1) {
-                    acc[k][0] += a * (double)m[k];
-                } else {
-#pragma unroll
-                    for (int v = 0; v < V; ++v) acc[k][v] += a * (double)m[k][v];
-                }
-            }
-        }
-    }
-    VT out;
-#pragma unroll
-    for (int v = 0; v < V; ++v) {
-        double s = acc[0][v];
-#pragma unroll
-        for (int k = 1; k < 16; ++k) s += acc[k][v];
-        if constexpr (V == 1) out = (float)s; else out[v] = (float)s;
-    }
-    *reinterpret_cast<VT*>(g + c) = out;
-}
-
-// Decode with the decode vector taken from a row of the explicit decoding matrix
-// A_sigma held on the device: thread 0 compacts the non-zero entries of the row
-// into LDS, then the combination runs exactly as in decode_kernel (same order of
-// additions, so both routes give the same bits for the same vector).
-template <typename VT, int V>
-__global__ __launch_bounds__(256) void decode_lookup_kernel(const float* __restrict__ Cl,
-                                                            float* __restrict__ g, int64_t d, int n,
-                                                            const double* __restrict__ a_row) {
-    __shared__ double part[16][16 * V + 1];
-    __shared__ double a_s[NGC_MAX_N];
-    __shared__ int idx_s[NGC_MAX_N];
-    __shared__ int count_s;
-    if (threadIdx.x == 0) {
-        int cnt = 0;
-        for (int i = 0; i < n; ++i) {
-            const double a = a_row[i];
-            if (a != 0.0) {
-                a_s[cnt] = a;
-                idx_s[cnt] = i;
-                ++cnt;
-            }
-        }
-        count_s = cnt;
-    }
-    __syncthreads();
-    const int count = count_s;
-    const int lane16 = threadIdx.x & 15;
-    const int slot = threadIdx.x >> 4;
-    const int64_t c = ((int64_t)blockIdx.x * 16 + lane16) * V;
-    double acc[V];
-#pragma unroll
-    for (int v = 0; v < V; ++v) acc[v] = 0.0;
-    if (c < d) {
-        for (int t = slot; t < count; t += 16) {
-            VT m = *reinterpret_cast<const VT*>(Cl + (int64_t)idx_s[t] * d + c);
-            const double a = a_s[t];
-            if constexpr (V == 1) {
-                acc[0] += a * (double)m;
-            } else {
-#pragma unroll
-                for (int v = 0; v < V; ++v) acc[v] += a * (double)m[v];
-            }
-        }
-    }
-#pragma unroll
-    for (int v = 0; v < V; ++v) part[slot][lane16 * V + v] = acc[v];
-    __syncthreads();
-    const int q = threadIdx.x;
-    if (q < 16 * V) {
-        const int64_t cq = (int64_t)blockIdx.x * 16 * V + q;
-        if (cq < d) {
-            double s = part[0][q];
-#pragma unroll
-            for (int k = 1; k < 16; ++k) s += part[k][q];
-            g[cq] = (float)s;
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------
-// Fused tail of one iteration for a tile of 16*V columns: sum of the gradient
-// kernel's block partials (-> G), messages of every layer (-> C), decode with the
-// given vector (-> g) and the descent update of theta, all from LDS.  Every step
-// adds in the same order as the stand-alone kernels (reduce_partials, encode,
-// decode, update), so the results are the same bits.
-//   threads: 16 groups ("slots") of 16 lanes; a lane owns V columns.
-// ---------------------------------------------------------------------------
-template <typename VT, int V>
-__global__ __launch_bounds__(256) void iteration_tail_kernel(
-    const float* __restrict__ partial, int chunks, float* __restrict__ G, float* __restrict__ C,
-    const int* __restrict__ rowptr, const int* __restrict__ col, const float* __restrict__ coef,
-    int nnz, int n, int k, int L, int64_t d, int layer, decode_args args, float* __restrict__ g,
-    float* __restrict__ theta, float scale) {
-    extern __shared__ float lds_raw[];
-    constexpr int PW = 16 * V + 1;
-    VT* tile = reinterpret_cast<VT*>(lds_raw);                        // [k][16]   G tile
-    VT* msg = tile + (size_t)k * 16;                                  // [n][16]   messages of the decode layer
-    double* part = reinterpret_cast<double*>(msg + (size_t)n * 16);   // [16][PW]
-    int* rp_s = reinterpret_cast<int*>(part + 16 * PW);               // [L*n + 1]
-    int* col_s = rp_s + L * n + 1;                                    // [nnz]
-    float* coef_s = reinterpret_cast<float*>(col_s + nnz);            // [nnz]
-    const int lane16 = threadIdx.x & 15;
-    const int slot = threadIdx.x >> 4;
-    const int64_t c = ((int64_t)blockIdx.x * 16 + lane16) * V;
-    const bool in = c < d;
-    // the code tables are small: one copy per block in LDS
-    for (int t = threadIdx.x; t <= L * n; t += 256) rp_s[t] = rowptr[t];
-    for (int t = threadIdx.x; t < nnz; t += 256) {
-        col_s[t] = col[t];
-        coef_s[t] = coef[t];
-    }
-    // 1. G tile = sum of block partials, chunks added in index order (sixteen loads in flight)
-    for (int j = slot; j < k; j += 16) {
-        VT acc = (VT)(0.0f);
-        if (in) {
-            const float* p = partial + (int64_t)j * chunks * d + c;
-            acc = *reinterpret_cast<const VT*>(p);
-            int t = 1;
-            for (; t + 16 <= chunks; t += 16) {
-                VT x[16];
-#pragma unroll
-                for (int u = 0; u < 16; ++u) x[u] = *reinterpret_cast<const VT*>(p + (int64_t)(t + u) * d);
-#pragma unroll
-                for (int u = 0; u < 16; ++u) acc += x[u];
-            }
-            if (t + 8 <= chunks) {
-                VT x[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) x[u] = *reinterpret_cast<const VT*>(p + (int64_t)(t + u) * d);
-#pragma unroll
-                for (int u = 0; u < 8; ++u) acc += x[u];
-                t += 8;
-            }
-            for (; t < chunks; ++t) acc += *reinterpret_cast<const VT*>(p + (int64_t)t * d);
-            *reinterpret_cast<VT*>(G + (int64_t)j * d + c) = acc;
-        }
-        tile[j * 16 + lane16] = acc;
-    }
-    __syncthreads();
-    // 2. messages of every (layer, worker) pair; those of the decode layer are kept in LDS
-    const int np = L * n;
-    for (int p = slot; p < np; p += 16) {
-        const int b = rp_s[p], e = rp_s[p + 1];
-        VT acc0 = (VT)(0.0f), acc1 = (VT)(0.0f);
-        int t = b;
-        for (; t + 8 <= e; t += 8) {
-#pragma unroll
-            for (int u = 0; u < 8; u += 2) {
-                acc0 += coef_s[t + u] * tile[col_s[t + u] * 16 + lane16];
-                acc1 += coef_s[t + u + 1] * tile[col_s[t + u + 1] * 16 + lane16];
-            }
-        }
-        for (; t < e; ++t) acc0 += coef_s[t] * tile[col_s[t] * 16 + lane16];
-        const VT m = acc0 + acc1;
-        if (in) *reinterpret_cast<VT*>(C + (int64_t)p * d + c) = m;
-        if (p / n == layer) msg[(p - layer * n) * 16 + lane16] = m;
-    }
-    __syncthreads();
-    // 3. decode: fp64 products and sums, responders dealt to the 16 groups in turn
-    double acc[V];
-#pragma unroll
-    for (int v = 0; v < V; ++v) acc[v] = 0.0;
-    for (int t = slot; t < args.count; t += 16) {
-        const VT m = msg[args.idx[t] * 16 + lane16];
-        const double a = args.a[t];
-        if constexpr (V == 1) {
-            acc[0] += a * (double)m;
-        } else {
-#pragma unroll
-            for (int v = 0; v < V; ++v) acc[v] += a * (double)m[v];
-        }
-    }
-#pragma unroll
-    for (int v = 0; v < V; ++v) part[slot * PW + lane16 * V + v] = acc[v];
-    __syncthreads();
-    const int q = threadIdx.x;
-    if (q < 16 * V) {
-        const int64_t cq = (int64_t)blockIdx.x * 16 * V + q;
-        if (cq < d) {
-            double s = part[q];
-#pragma unroll
-            for (int kk = 1; kk < 16; ++kk) s += part[kk * PW + q];
-            const float gq = (float)s;
-            g[cq] = gq;
-            // 4. theta <- theta - scale * g
-            theta[cq] = theta[cq] - scale * gq;
-        }
-    }
-}
-
 // K6: theta -= scale * g
 __global__ __launch_bounds__(256) void update_kernel(float* __restrict__ theta,
                                                      const float* __restrict__ g, float scale,
                                                      int64_t d) {
     const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (c < d) theta[c] = theta[c] - scale * g[c];
-}
-
-// ---------------------------------------------------------------------------
-// Worker-side encode: message of worker i under layer u formed from the partial
-// gradients the worker computed itself, W[i][t] in task order,
-//   C[u][i][:] = sum_t wcoef[u][i][t] * W[i][t][:]
-// for every layer the worker has finished (unfinished ones are zero-filled).
-// By nesting, task t feeds every layer whose support contains its partition, so
-// each W row is read once and added into up to LMAX accumulators.
-// ---------------------------------------------------------------------------
-struct worker_progress {
-    unsigned char done[NGC_MAX_N];
-};
-
-template <typename VT, int V, int LMAX>
-__global__ __launch_bounds__(64) void worker_encode_kernel(const float* __restrict__ W,
-                                                           float* __restrict__ C,
-                                                           const int* __restrict__ needed,
-                                                           const float* __restrict__ wcoef, int n,
-                                                           int L, int T, int per_task, int64_t d,
-                                                           worker_progress prog) {
-    // T: rows of W per worker (partitions); prog.done counts atomic tasks of per_task partitions
-    const int i = blockIdx.y;
-    const int64_t c = ((int64_t)blockIdx.x * 64 + threadIdx.x) * V;
-    if (c >= d) return;
-    const int done = prog.done[i] * per_task < T ? prog.done[i] * per_task : T;
-    VT acc[LMAX];
-#pragma unroll
-    for (int u = 0; u < LMAX; ++u) acc[u] = (VT)(0.0f);
-    for (int t = 0; t < done; ++t) {
-        const VT x = *reinterpret_cast<const VT*>(W + ((int64_t)i * T + t) * d + c);
-#pragma unroll
-        for (int u = 0; u < LMAX; ++u)
-            if (u < L) acc[u] += wcoef[((int64_t)u * n + i) * T + t] * x;
-    }
-#pragma unroll
-    for (int u = 0; u < LMAX; ++u)
-        if (u < L) {
-            const VT out = prog.done[i] >= needed[u * n + i] ? acc[u] : (VT)(0.0f);
-            *reinterpret_cast<VT*>(C + ((int64_t)u * n + i) * d + c) = out;
-        }
 }
 
 // ---------------------------------------------------------------------------
@@ -750,13 +334,14 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const v4f* __restrict__
 // ===========================================================================
 // host-side launchers
 // ===========================================================================
-static int dev_init(ngc_ctx* ctx) {
+int ngc_dev_init(ngc_ctx* ctx) {
     if (ctx->dev_ready) return NGC_OK;
     int dev = 0;
     NGC_HIP(ctx, hipGetDevice(&dev));
     hipDeviceProp_t prop;
     NGC_HIP(ctx, hipGetDeviceProperties(&prop, dev));
     ctx->cu_count = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    ctx->lds_limit = prop.sharedMemPerBlock > 0 ? (int)std::min<size_t>(prop.sharedMemPerBlock, 160 * 1024) : 64 * 1024;
     ctx->dev_ready = true;
     return NGC_OK;
 }
@@ -780,6 +365,13 @@ void ngc_dev_release(ngc_ctx* ctx) {
         ctx->maps_ev_set[q] = false;
     }
     ctx->maps_cap = 0;
+    if (ctx->d_rounds) (void)hipFree(ctx->d_rounds);
+    if (ctx->h_rounds) (void)hipHostFree(ctx->h_rounds);
+    if (ctx->rounds_ev) (void)hipEventDestroy(ctx->rounds_ev);
+    ctx->d_rounds = ctx->h_rounds = nullptr;
+    ctx->rounds_ev = nullptr;
+    ctx->rounds_ev_set = false;
+    ctx->rounds_cap = 0;
     if (ctx->d_wtab) (void)hipFree(ctx->d_wtab);
     ctx->d_wtab = nullptr;
     ctx->d_wtab_bytes = 0;
@@ -811,37 +403,6 @@ static int ensure_ws(ngc_ctx* ctx, size_t bytes) {
     ctx->d_ws_bytes = bytes;
     return NGC_OK;
 }
-
-namespace {
-struct prof_scope {
-    ngc_ctx* ctx;
-    int rec = -1;
-    prof_scope(ngc_ctx* c, int kernel) : ctx(c) {
-        if (c->prof_suspended || !((c->profile_mask >> kernel) & 1u) || c->prof.size() >= (size_t)NGC_MAX_PROFILE) return;
-        ngc_profile_rec r;
-        r.kernel = kernel;
-        auto get = [&](hipEvent_t& e) {
-            if (!c->event_pool.empty()) {
-                e = c->event_pool.back();
-                c->event_pool.pop_back();
-                return true;
-            }
-            return hipEventCreate(&e) == hipSuccess;
-        };
-        if (!get(r.start)) return;
-        if (!get(r.stop)) {
-            c->event_pool.push_back(r.start);
-            return;
-        }
-        (void)hipEventRecord(r.start, c->stream);
-        c->prof.push_back(r);
-        rec = (int)c->prof.size() - 1;
-    }
-    ~prof_scope() {
-        if (rec >= 0) (void)hipEventRecord(ctx->prof[rec].stop, ctx->stream);
-    }
-};
-}  // namespace
 
 extern "C" int ngc_profile_enable(ngc_ctx* ctx, int kernel_mask) try {
     if (!ctx) return NGC_ERR_INVALID;
@@ -903,7 +464,6 @@ extern "C" int ngc_sync(ngc_ctx* ctx) try {
     return ngc_on_exception();
 }
 
-static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 // ---- partition gradients --------------------------------------------------
 template <int NV, int R, int NBUF, int WAVES, bool RAGGED, typename VT = v4f>
@@ -961,6 +521,9 @@ static stream_shape pick_stream_shape(int64_t d) {
 
 int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float* theta, int64_t rows,
                    float* G, int units, const int* unit_part, const int* unit_row);  // ngc_mlp.hip
+// ngc_codec.hip: everything of an iteration after the gradient kernel, in one launch
+int ngc_launch_tail(ngc_ctx* ctx, const float* partial, int chunks, int layer, const double* a,
+                    float* G_dev, float* C_dev, float* g_dev, float* theta_dev, double scale);
 
 // Gradients of `units` partial-gradient computations (least squares / logistic).  Unit q works
 // on partition unit_part[q] (q itself if unit_part is null) and its result goes to row
@@ -1017,7 +580,7 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
         rc = get_ws(sizeof(float) * (size_t)k * chunks * d);
         if (rc) return rc;
         {
-            prof_scope ps(ctx, NGC_KERNEL_GRAD);
+            ngc_prof_scope ps(ctx, NGC_KERNEL_GRAD);
 #define NGC_STREAM_ARGS ctx, loss, X_dev, y, theta_dev, ws, k, rows, (int)chunks, rpc, unit_part, (int)(sh.scalar ? d : d / 4)
 #define NGC_STREAM_CASE(NV, R, W, RG) \
     case W: launch_stream<NV, R, 2, W, RG>(NGC_STREAM_ARGS); break;
@@ -1092,7 +655,7 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
             return NGC_OK;
         }
         {
-            prof_scope ps(ctx, NGC_KERNEL_REDUCE);
+            ngc_prof_scope ps(ctx, NGC_KERNEL_REDUCE);
             const int64_t dv = sh.scalar ? d : d / 4;
             dim3 grid((unsigned)((dv + 255) / 256), (unsigned)k);
             if (sh.scalar)
@@ -1118,7 +681,7 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
     float* resid = ws;
     float* partial = ws + resid_floats;
     {
-        prof_scope ps(ctx, NGC_KERNEL_GRAD);
+        ngc_prof_scope ps(ctx, NGC_KERNEL_GRAD);
         const int64_t blocks = std::min<int64_t>((total_rows + 3) / 4, (int64_t)ctx->cu_count * 8);
         if (loss == NGC_LOSS_LSQ)
             hipLaunchKernelGGL((resid_kernel<NGC_LOSS_LSQ>), dim3((unsigned)blocks), dim3(256), 0, ctx->stream,
@@ -1138,7 +701,7 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
         return NGC_OK;
     }
     {
-        prof_scope ps(ctx, NGC_KERNEL_REDUCE);
+        ngc_prof_scope ps(ctx, NGC_KERNEL_REDUCE);
         dim3 grid((unsigned)((d + 255) / 256), (unsigned)k);
         hipLaunchKernelGGL((reduce_partials_kernel<float>), grid, dim3(256), 0, ctx->stream,
                            (const float*)partial, G_dev, d, (int)chunks, unit_row);
@@ -1152,9 +715,9 @@ extern "C" int ngc_partition_grads(ngc_ctx* ctx, int loss, const float* X_dev, c
     if (!ctx) return NGC_ERR_INVALID;
     if (!X_dev || !y_dev || !theta_dev || !G_dev) return ngc_fail(ctx, NGC_ERR_INVALID, "null device pointer");
     if (rows < 1) return ngc_fail(ctx, NGC_ERR_INVALID, "rows_per_part must be positive");
-    if (!aligned16(X_dev) || !aligned16(theta_dev) || !aligned16(G_dev))
+    if (!ngc_aligned16(X_dev) || !ngc_aligned16(theta_dev) || !ngc_aligned16(G_dev))
         return ngc_fail(ctx, NGC_ERR_INVALID, "X, theta and G must be 16-byte aligned");
-    int rc = dev_init(ctx);
+    int rc = ngc_dev_init(ctx);
     if (rc) return rc;
     if (loss == NGC_LOSS_MLP2) {
         if (!ctx->mlp_din) return ngc_fail(ctx, NGC_ERR_STATE, "call ngc_set_mlp2_shape first");
@@ -1197,12 +760,12 @@ extern "C" int ngc_partition_grads_static(ngc_ctx* ctx, int loss, const float* X
     if (!ctx) return NGC_ERR_INVALID;
     if (!X_dev || !y_dev || !theta_dev || !G_dev) return ngc_fail(ctx, NGC_ERR_INVALID, "null device pointer");
     if (rows < 1) return ngc_fail(ctx, NGC_ERR_INVALID, "rows_per_part must be positive");
-    if (!aligned16(X_dev) || !aligned16(theta_dev) || !aligned16(G_dev))
+    if (!ngc_aligned16(X_dev) || !ngc_aligned16(theta_dev) || !ngc_aligned16(G_dev))
         return ngc_fail(ctx, NGC_ERR_INVALID, "X, theta and G must be 16-byte aligned");
     if (loss == NGC_LOSS_MLP2)
         return ngc_fail(ctx, NGC_ERR_INVALID, "the perceptron's activations do not fit the static scratch");
     if (loss != NGC_LOSS_LSQ && loss != NGC_LOSS_LOGISTIC) return ngc_fail(ctx, NGC_ERR_INVALID, "unknown loss");
-    int rc = dev_init(ctx);
+    int rc = ngc_dev_init(ctx);
     if (rc) return rc;
     float* ws = nullptr;
     rc = static_scratch(ctx, &ws);
@@ -1218,162 +781,13 @@ extern "C" int ngc_partition_grads_static(ngc_ctx* ctx, int loss, const float* X
     return ngc_on_exception();
 }
 
-// ---- code tables on the device --------------------------------------------
-// layout of d_code: int rowptr[L*n + 1] | int col[nnz] | float coef[nnz]
-static int upload_code(ngc_ctx* ctx) {
-    if (!ctx->code_dirty && ctx->d_code) return NGC_OK;
-    const int n = ctx->n, L = ctx->L;
-    for (int u = 0; u < L; ++u)
-        if (!ctx->code[u].set) return ngc_fail(ctx, NGC_ERR_STATE, "a layer has no code yet");
-    size_t nnz = 0;
-    for (int u = 0; u < L; ++u) nnz += ctx->code[u].col.size();
-    const size_t np = (size_t)L * n;
-    std::vector<int> host(np + 1 + 2 * nnz);
-    int* rowptr = host.data();
-    int* col = rowptr + np + 1;
-    float* coef = reinterpret_cast<float*>(col + nnz);
-    size_t at = 0;
-    for (int u = 0; u < L; ++u) {
-        const ngc_layer_code& lc = ctx->code[u];
-        for (int i = 0; i < n; ++i) {
-            rowptr[(size_t)u * n + i] = (int)at;
-            for (int t = lc.rowptr[i]; t < lc.rowptr[i + 1]; ++t) {
-                col[at] = lc.col[t];
-                coef[at] = (float)lc.coef[t];
-                ++at;
-            }
-        }
-    }
-    rowptr[np] = (int)at;
-    const size_t bytes = host.size() * sizeof(int);
-    NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    if (bytes > ctx->d_code_bytes) {
-        if (ctx->d_code) NGC_HIP(ctx, hipFree(ctx->d_code));
-        ctx->d_code = nullptr;
-        ctx->d_code_bytes = 0;
-        if (hipMalloc(&ctx->d_code, bytes) != hipSuccess) {
-            (void)hipGetLastError();
-            return ngc_fail(ctx, NGC_ERR_NOMEM, "code table allocation failed");
-        }
-        ctx->d_code_bytes = bytes;
-    }
-    NGC_HIP(ctx, hipMemcpy(ctx->d_code, host.data(), bytes, hipMemcpyHostToDevice));
-    ctx->code_nnz = nnz;
-    ctx->code_dirty = false;
-    return NGC_OK;
-}
-
-static int vec_width(int64_t d, const void* p0, const void* p1) {
-    auto al = [](const void* p, uintptr_t m) { return (reinterpret_cast<uintptr_t>(p) & (m - 1)) == 0; };
-    if (d % 4 == 0 && al(p0, 16) && al(p1, 16)) return 4;
-    if (d % 2 == 0 && al(p0, 8) && al(p1, 8)) return 2;
-    return 1;
-}
-
-extern "C" int ngc_encode(ngc_ctx* ctx, const float* G_dev, int layer, float* C_dev) try {
-    if (!ctx) return NGC_ERR_INVALID;
-    if (!G_dev || !C_dev) return ngc_fail(ctx, NGC_ERR_INVALID, "null device pointer");
-    if (layer < -1 || layer >= ctx->L) return ngc_fail(ctx, NGC_ERR_INVALID, "layer out of range");
-    if ((reinterpret_cast<uintptr_t>(G_dev) | reinterpret_cast<uintptr_t>(C_dev)) & 3)
-        return ngc_fail(ctx, NGC_ERR_INVALID, "G and C must be 4-byte aligned");
-    int rc = dev_init(ctx);
-    if (rc) return rc;
-    rc = upload_code(ctx);
-    if (rc) return rc;
-    const int n = ctx->n;
-    const int64_t d = ctx->d;
-    const size_t np = (size_t)ctx->L * n;
-    const size_t nnz = ctx->code_nnz;
-    const int* rowptr = (const int*)ctx->d_code;
-    const int* col = rowptr + np + 1;
-    const float* coef = (const float*)(col + nnz);
-    const int pb = layer < 0 ? 0 : layer * n;
-    const int pe = layer < 0 ? (int)np : (layer + 1) * n;
-    const int V = vec_width(d, G_dev, C_dev);
-    const int64_t gx = (d + 64 * V - 1) / (64 * V);
-    const int pairs = pe - pb;
-    // enough blocks for about three per CU; the pairs are dealt to blocks and waves in turn
-    int64_t gy = std::max<int64_t>(1, (3 * (int64_t)ctx->cu_count + gx - 1) / gx);
-    gy = std::min<int64_t>(gy, (pairs + ENC_WAVES - 1) / ENC_WAVES);
-    if (gx > 0x7fffffffLL) return ngc_fail(ctx, NGC_ERR_INVALID, "d too large");
-    dim3 grid((unsigned)gx, (unsigned)gy);
-    const size_t lds = (size_t)ctx->k * 64 * V * sizeof(float);  // all k rows of G, 64*V columns
-    {
-        prof_scope ps(ctx, NGC_KERNEL_ENCODE);
-        if (V == 4)
-            hipLaunchKernelGGL((encode_kernel<v4f, 4>), grid, dim3(ENC_WAVES * 64), lds, ctx->stream, G_dev, C_dev,
-                               rowptr, col, coef, ctx->k, d, pb, pe);
-        else if (V == 2)
-            hipLaunchKernelGGL((encode_kernel<v2f, 2>), grid, dim3(ENC_WAVES * 64), lds, ctx->stream, G_dev, C_dev,
-                               rowptr, col, coef, ctx->k, d, pb, pe);
-        else
-            hipLaunchKernelGGL((encode_kernel<float, 1>), grid, dim3(ENC_WAVES * 64), lds, ctx->stream, G_dev, C_dev,
-                               rowptr, col, coef, ctx->k, d, pb, pe);
-    }
-    NGC_HIP(ctx, hipGetLastError());
-    return NGC_OK;
-} catch (...) {
-    return ngc_on_exception();
-}
-
-extern "C" int ngc_decode(ngc_ctx* ctx, int layer, const double* a_host, const float* C_dev,
-                          float* g_dev) try {
-    if (!ctx) return NGC_ERR_INVALID;
-    if (!a_host || !C_dev || !g_dev) return ngc_fail(ctx, NGC_ERR_INVALID, "null pointer");
-    if (layer < 0 || layer >= ctx->L) return ngc_fail(ctx, NGC_ERR_INVALID, "layer out of range");
-    int rc = dev_init(ctx);
-    if (rc) return rc;
-    const int n = ctx->n;
-    const int64_t d = ctx->d;
-    decode_args args;
-    args.count = 0;
-    for (int i = 0; i < n; ++i) {
-        if (!std::isfinite(a_host[i])) return ngc_fail(ctx, NGC_ERR_INVALID, "decode vector has a non-finite entry");
-        if (a_host[i] != 0.0) {
-            args.a[args.count] = a_host[i];
-            args.idx[args.count] = i;
-            ++args.count;
-        }
-    }
-    for (int t = args.count; t < NGC_MAX_N; ++t) {
-        args.a[t] = 0.0;
-        args.idx[t] = 0;
-    }
-    const float* Cl = C_dev + (size_t)layer * n * d;
-    const int V = vec_width(d, Cl, g_dev);
-    const int64_t gx = (d + 16 * V - 1) / (16 * V);
-    const int64_t gw = (d + 256 * V - 1) / (256 * V);
-    if (args.count > 0 && gw >= 2 * (int64_t)ctx->cu_count) {
-        // long gradient: enough column blocks to fill the chip with one thread per V columns
-        prof_scope ps(ctx, NGC_KERNEL_DECODE);
-        if (V == 4)
-            hipLaunchKernelGGL((decode_wide_kernel<v4f, 4>), dim3((unsigned)gw), dim3(256), 0, ctx->stream, Cl, g_dev, d, args);
-        else if (V == 2)
-            hipLaunchKernelGGL((decode_wide_kernel<v2f, 2>), dim3((unsigned)gw), dim3(256), 0, ctx->stream, Cl, g_dev, d, args);
-        else
-            hipLaunchKernelGGL((decode_wide_kernel<float, 1>), dim3((unsigned)gw), dim3(256), 0, ctx->stream, Cl, g_dev, d, args);
-    } else {
-        prof_scope ps(ctx, NGC_KERNEL_DECODE);
-        if (V == 4)
-            hipLaunchKernelGGL((decode_kernel<v4f, 4>), dim3((unsigned)gx), dim3(256), 0, ctx->stream, Cl, g_dev, d, args);
-        else if (V == 2)
-            hipLaunchKernelGGL((decode_kernel<v2f, 2>), dim3((unsigned)gx), dim3(256), 0, ctx->stream, Cl, g_dev, d, args);
-        else
-            hipLaunchKernelGGL((decode_kernel<float, 1>), dim3((unsigned)gx), dim3(256), 0, ctx->stream, Cl, g_dev, d, args);
-    }
-    NGC_HIP(ctx, hipGetLastError());
-    return NGC_OK;
-} catch (...) {
-    return ngc_on_exception();
-}
-
 extern "C" int ngc_update(ngc_ctx* ctx, float* theta_dev, const float* g_dev, double scale) try {
     if (!ctx) return NGC_ERR_INVALID;
     if (!theta_dev || !g_dev) return ngc_fail(ctx, NGC_ERR_INVALID, "null device pointer");
-    int rc = dev_init(ctx);
+    int rc = ngc_dev_init(ctx);
     if (rc) return rc;
     {
-        prof_scope ps(ctx, NGC_KERNEL_UPDATE);
+        ngc_prof_scope ps(ctx, NGC_KERNEL_UPDATE);
         hipLaunchKernelGGL(update_kernel, dim3((unsigned)((ctx->d + 255) / 256)), dim3(256), 0, ctx->stream,
                            theta_dev, g_dev, (float)scale, ctx->d);
     }
@@ -1386,14 +800,14 @@ extern "C" int ngc_update(ngc_ctx* ctx, float* theta_dev, const float* g_dev, do
 // ---- measurement probes -----------------------------------------------------
 extern "C" int ngc_probe_copy(ngc_ctx* ctx, const void* src_dev, void* dst_dev, int64_t bytes) try {
     if (!ctx) return NGC_ERR_INVALID;
-    if (!src_dev || !dst_dev || bytes < 16 || bytes % 16 || !aligned16(src_dev) || !aligned16(dst_dev))
+    if (!src_dev || !dst_dev || bytes < 16 || bytes % 16 || !ngc_aligned16(src_dev) || !ngc_aligned16(dst_dev))
         return ngc_fail(ctx, NGC_ERR_INVALID, "probe buffers must be 16-byte aligned, size a multiple of 16");
-    int rc = dev_init(ctx);
+    int rc = ngc_dev_init(ctx);
     if (rc) return rc;
     const int64_t nvec = bytes / 16;
     const int64_t blocks = std::min<int64_t>((nvec + 255) / 256, (int64_t)ctx->cu_count * 16);
     {
-        prof_scope ps(ctx, NGC_KERNEL_PROBE);
+        ngc_prof_scope ps(ctx, NGC_KERNEL_PROBE);
         hipLaunchKernelGGL(probe_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream,
                            (const v4f*)src_dev, (v4f*)dst_dev, nvec);
     }
@@ -1405,16 +819,16 @@ extern "C" int ngc_probe_copy(ngc_ctx* ctx, const void* src_dev, void* dst_dev, 
 
 extern "C" int ngc_probe_read(ngc_ctx* ctx, const void* src_dev, int64_t bytes) try {
     if (!ctx) return NGC_ERR_INVALID;
-    if (!src_dev || bytes < 16 || bytes % 16 || !aligned16(src_dev))
+    if (!src_dev || bytes < 16 || bytes % 16 || !ngc_aligned16(src_dev))
         return ngc_fail(ctx, NGC_ERR_INVALID, "probe buffer must be 16-byte aligned, size a multiple of 16");
-    int rc = dev_init(ctx);
+    int rc = ngc_dev_init(ctx);
     if (rc) return rc;
     const int64_t nvec = bytes / 16;
     const int64_t blocks = std::min<int64_t>((nvec + 255) / 256, (int64_t)ctx->cu_count * 8);
     rc = ensure_ws(ctx, sizeof(float) * 4 * (size_t)blocks);
     if (rc) return rc;
     {
-        prof_scope ps(ctx, NGC_KERNEL_PROBE);
+        ngc_prof_scope ps(ctx, NGC_KERNEL_PROBE);
         hipLaunchKernelGGL(probe_read_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream,
                            (const v4f*)src_dev, ctx->d_ws, nvec);
     }
@@ -1461,9 +875,9 @@ extern "C" int ngc_worker_grads(ngc_ctx* ctx, int loss, const float* X_dev, cons
     if (loss != NGC_LOSS_LSQ && loss != NGC_LOSS_LOGISTIC && loss != NGC_LOSS_MLP2)
         return ngc_fail(ctx, NGC_ERR_INVALID, "unknown loss");
     if (loss == NGC_LOSS_MLP2 && !ctx->mlp_din) return ngc_fail(ctx, NGC_ERR_STATE, "call ngc_set_mlp2_shape first");
-    if (!aligned16(X_dev) || !aligned16(theta_dev) || !aligned16(W_dev))
+    if (!ngc_aligned16(X_dev) || !ngc_aligned16(theta_dev) || !ngc_aligned16(W_dev))
         return ngc_fail(ctx, NGC_ERR_INVALID, "X, theta and W must be 16-byte aligned");
-    int rc = dev_init(ctx);
+    int rc = ngc_dev_init(ctx);
     if (rc) return rc;
     ngc_worker_plan plan;
     rc = ngc_make_worker_plan(ctx, plan);
@@ -1503,118 +917,6 @@ extern "C" int ngc_worker_grads(ngc_ctx* ctx, int loss, const float* X_dev, cons
     return ngc_on_exception();
 }
 
-extern "C" int ngc_worker_encode(ngc_ctx* ctx, const float* W_dev, const int* progress_host,
-                                 float* C_dev) try {
-    if (!ctx) return NGC_ERR_INVALID;
-    if (!W_dev || !C_dev || !progress_host) return ngc_fail(ctx, NGC_ERR_INVALID, "null pointer");
-    if (ctx->L > 8) return ngc_fail(ctx, NGC_ERR_INVALID, "worker encode supports at most 8 layers");
-    int rc = dev_init(ctx);
-    if (rc) return rc;
-    ngc_worker_plan plan;
-    rc = ngc_make_worker_plan(ctx, plan);
-    if (rc) return rc;
-    const int n = ctx->n, L = ctx->L, T = plan.T * ctx->c;  // T: partitions per worker schedule
-    const int64_t d = ctx->d;
-    worker_progress prog;
-    for (int i = 0; i < NGC_MAX_N; ++i) prog.done[i] = 0;
-    for (int i = 0; i < n; ++i) {
-        if (progress_host[i] < 0) return ngc_fail(ctx, NGC_ERR_INVALID, "negative progress");
-        prog.done[i] = (unsigned char)std::min<int>(progress_host[i], 255);
-    }
-    // tables: int needed[L*n] (atomic tasks) | float wcoef[L*n*T]; they depend on the code only
-    if (ctx->wtab_dirty || !ctx->d_wtab || ctx->wtab_T != T) {
-        std::vector<int> tab((size_t)L * n + (size_t)L * n * T, 0);
-        float* wcoef = reinterpret_cast<float*>(tab.data() + (size_t)L * n);
-        for (int u = 0; u < L; ++u)
-            for (int i = 0; i < n; ++i) {
-                tab[(size_t)u * n + i] = plan.needed[(size_t)u * n + i];
-                for (size_t t = 0; t < plan.order[i].size(); ++t)
-                    wcoef[((size_t)u * n + i) * T + t] =
-                        (float)ctx->code[u].B[(size_t)i * ctx->k + plan.order[i][t]];
-            }
-        NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
-        if (tab.size() * sizeof(int) > ctx->d_wtab_bytes) {
-            if (ctx->d_wtab) NGC_HIP(ctx, hipFree(ctx->d_wtab));
-            ctx->d_wtab = nullptr;
-            ctx->d_wtab_bytes = 0;
-            void* p = nullptr;
-            if (hipMalloc(&p, tab.size() * sizeof(int)) != hipSuccess) {
-                (void)hipGetLastError();
-                return ngc_fail(ctx, NGC_ERR_NOMEM, "table allocation failed");
-            }
-            ctx->d_wtab = (int*)p;
-            ctx->d_wtab_bytes = tab.size() * sizeof(int);
-        }
-        NGC_HIP(ctx, hipMemcpy(ctx->d_wtab, tab.data(), tab.size() * sizeof(int), hipMemcpyHostToDevice));
-        ctx->wtab_dirty = false;
-        ctx->wtab_T = T;
-    }
-    const int* needed = ctx->d_wtab;
-    const float* wc = reinterpret_cast<const float*>(needed + (size_t)L * n);
-    const int V = vec_width(d, W_dev, C_dev);
-    dim3 grid((unsigned)((d + 64 * V - 1) / (64 * V)), (unsigned)n);
-    {
-        prof_scope ps(ctx, NGC_KERNEL_ENCODE);
-        if (V == 4)
-            hipLaunchKernelGGL((worker_encode_kernel<v4f, 4, 8>), grid, dim3(64), 0, ctx->stream, W_dev, C_dev, needed, wc, n, L, T, ctx->c, d, prog);
-        else if (V == 2)
-            hipLaunchKernelGGL((worker_encode_kernel<v2f, 2, 8>), grid, dim3(64), 0, ctx->stream, W_dev, C_dev, needed, wc, n, L, T, ctx->c, d, prog);
-        else
-            hipLaunchKernelGGL((worker_encode_kernel<float, 1, 8>), grid, dim3(64), 0, ctx->stream, W_dev, C_dev, needed, wc, n, L, T, ctx->c, d, prog);
-    }
-    NGC_HIP(ctx, hipGetLastError());
-    return NGC_OK;
-} catch (...) {
-    return ngc_on_exception();
-}
-
-// ---- decode through the explicit decoding matrix ------------------------------------------------
-extern "C" int ngc_decode_lookup(ngc_ctx* ctx, int layer, const uint8_t* straggler_mask,
-                                 const float* C_dev, float* g_dev) try {
-    if (!ctx) return NGC_ERR_INVALID;
-    if (!straggler_mask || !C_dev || !g_dev) return ngc_fail(ctx, NGC_ERR_INVALID, "null pointer");
-    if (layer < 0 || layer >= ctx->L) return ngc_fail(ctx, NGC_ERR_INVALID, "layer out of range");
-    ngc_layer_code& lc = ctx->code[layer];
-    if (lc.A_rows == 0) return ngc_fail(ctx, NGC_ERR_STATE, "call ngc_build_decoding_table for this layer first");
-    int64_t row = 0;
-    int rc = ngc_decoding_row_index(ctx, layer, straggler_mask, &row);
-    if (rc) return rc;
-    rc = dev_init(ctx);
-    if (rc) return rc;
-    const int n = ctx->n;
-    const int64_t d = ctx->d;
-    if (lc.A_stale || !lc.d_A) {
-        NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
-        if (lc.d_A) NGC_HIP(ctx, hipFree(lc.d_A));
-        lc.d_A = nullptr;
-        void* p = nullptr;
-        if (hipMalloc(&p, lc.A.size() * sizeof(double)) != hipSuccess) {
-            (void)hipGetLastError();
-            return ngc_fail(ctx, NGC_ERR_NOMEM, "decoding table allocation failed");
-        }
-        lc.d_A = (double*)p;
-        NGC_HIP(ctx, hipMemcpy(lc.d_A, lc.A.data(), lc.A.size() * sizeof(double), hipMemcpyHostToDevice));
-        lc.A_stale = false;
-    }
-    const float* Cl = C_dev + (size_t)layer * n * d;
-    const double* a_row = lc.d_A + (size_t)row * n;
-    const int V = vec_width(d, Cl, g_dev);
-    const int64_t gx = (d + 16 * V - 1) / (16 * V);
-    {
-        prof_scope ps(ctx, NGC_KERNEL_DECODE);
-        if (V == 4)
-            hipLaunchKernelGGL((decode_lookup_kernel<v4f, 4>), dim3((unsigned)gx), dim3(256), 0, ctx->stream, Cl, g_dev, d, n, a_row);
-        else if (V == 2)
-            hipLaunchKernelGGL((decode_lookup_kernel<v2f, 2>), dim3((unsigned)gx), dim3(256), 0, ctx->stream, Cl, g_dev, d, n, a_row);
-        else
-            hipLaunchKernelGGL((decode_lookup_kernel<float, 1>), dim3((unsigned)gx), dim3(256), 0, ctx->stream, Cl, g_dev, d, n, a_row);
-    }
-    NGC_HIP(ctx, hipGetLastError());
-    return NGC_OK;
-} catch (...) {
-    return ngc_on_exception();
-}
-
 // ---- one whole iteration in two launches ----------------------------------------------------------
 extern "C" int ngc_iteration(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_dev,
                              float* theta_dev, int64_t rows, const uint8_t* straggler_mask,
@@ -1626,7 +928,7 @@ extern "C" int ngc_iteration(ngc_ctx* ctx, int loss, const float* X_dev, const v
     if (rows < 1) return ngc_fail(ctx, NGC_ERR_INVALID, "rows_per_part must be positive");
     if (loss != NGC_LOSS_LSQ && loss != NGC_LOSS_LOGISTIC && loss != NGC_LOSS_MLP2)
         return ngc_fail(ctx, NGC_ERR_INVALID, "unknown loss");
-    if (!aligned16(X_dev) || !aligned16(theta_dev) || !aligned16(G_dev) || !aligned16(C_dev) || !aligned16(g_dev))
+    if (!ngc_aligned16(X_dev) || !ngc_aligned16(theta_dev) || !ngc_aligned16(G_dev) || !ngc_aligned16(C_dev) || !ngc_aligned16(g_dev))
         return ngc_fail(ctx, NGC_ERR_INVALID, "device buffers must be 16-byte aligned");
     // main-node bookkeeping first: an undecodable round launches nothing
     double a[NGC_MAX_N];
@@ -1643,52 +945,12 @@ extern "C" int ngc_iteration(ngc_ctx* ctx, int loss, const float* X_dev, const v
         if (!rc) rc = ngc_update(ctx, theta_dev, g_dev, scale);
         return rc;
     }
-    rc = dev_init(ctx);
-    if (rc) return rc;
-    rc = upload_code(ctx);
+    rc = ngc_dev_init(ctx);
     if (rc) return rc;
     partial_info pi;
     rc = grads_impl(ctx, loss, X_dev, y_dev, theta_dev, rows, G_dev, ctx->k, nullptr, nullptr, &pi);
     if (rc) return rc;
-    const int n = ctx->n, k = ctx->k, L = ctx->L;
-    const int64_t d = ctx->d;
-    decode_args args;
-    args.count = 0;
-    for (int i = 0; i < n; ++i)
-        if (a[i] != 0.0) {
-            args.a[args.count] = a[i];
-            args.idx[args.count] = i;
-            ++args.count;
-        }
-    for (int t = args.count; t < NGC_MAX_N; ++t) {
-        args.a[t] = 0.0;
-        args.idx[t] = 0;
-    }
-    const size_t np = (size_t)L * n;
-    const int* rowptr = (const int*)ctx->d_code;
-    const int* col = rowptr + np + 1;
-    const float* coef = (const float*)(col + ctx->code_nnz);
-    // widest vector that still leaves about a block per four CUs
-    int V = d % 4 == 0 ? 4 : (d % 2 == 0 ? 2 : 1);
-    while (V > 1 && (d + 16 * V - 1) / (16 * V) < ctx->cu_count / 4) V /= 2;
-    const int64_t gx = (d + 16 * V - 1) / (16 * V);
-    const int nnz = (int)ctx->code_nnz;
-    const size_t lds = ((size_t)k + n) * 16 * V * sizeof(float) + (size_t)16 * (16 * V + 1) * sizeof(double) +
-                       (np + 1 + 2 * (size_t)nnz) * sizeof(int);
-    {
-        prof_scope ps(ctx, NGC_KERNEL_TAIL);
-        if (V == 4)
-            hipLaunchKernelGGL((iteration_tail_kernel<v4f, 4>), dim3((unsigned)gx), dim3(256), lds, ctx->stream, pi.ptr,
-                               pi.chunks, G_dev, C_dev, rowptr, col, coef, nnz, n, k, L, d, layer, args, g_dev, theta_dev, (float)scale);
-        else if (V == 2)
-            hipLaunchKernelGGL((iteration_tail_kernel<v2f, 2>), dim3((unsigned)gx), dim3(256), lds, ctx->stream, pi.ptr,
-                               pi.chunks, G_dev, C_dev, rowptr, col, coef, nnz, n, k, L, d, layer, args, g_dev, theta_dev, (float)scale);
-        else
-            hipLaunchKernelGGL((iteration_tail_kernel<float, 1>), dim3((unsigned)gx), dim3(256), lds, ctx->stream, pi.ptr,
-                               pi.chunks, G_dev, C_dev, rowptr, col, coef, nnz, n, k, L, d, layer, args, g_dev, theta_dev, (float)scale);
-    }
-    NGC_HIP(ctx, hipGetLastError());
-    return NGC_OK;
+    return ngc_launch_tail(ctx, pi.ptr, pi.chunks, layer, a, G_dev, C_dev, g_dev, theta_dev, scale);
 } catch (...) {
     return ngc_on_exception();
 }

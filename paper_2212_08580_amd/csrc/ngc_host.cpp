@@ -366,10 +366,8 @@ void ngc_layer_decode_vec(const ngc_ctx* ctx, int layer, const int* rows, int ns
         ngc_min_norm_decode(lc.B.data(), n, k, rows, ns, a_out, resid);
 }
 
-static int select_impl(const ngc_ctx* ctx, const uint8_t* mask, int* layer_out, double* a_out,
-                       double* residual_out, bool first_only) {
-    if (!ctx) return NGC_ERR_INVALID;
-    if (!mask || !layer_out || !a_out) return ngc_fail(ctx, NGC_ERR_INVALID, "null argument");
+int ngc_select_core(const ngc_ctx* ctx, const uint8_t* mask, int* layer_out, double* a_out,
+                    double* residual_out, bool first_only) {
     const int n = ctx->n;
     int stragglers = 0;
     for (int i = 0; i < n; ++i) stragglers += mask[i] != 0;
@@ -379,8 +377,8 @@ static int select_impl(const ngc_ctx* ctx, const uint8_t* mask, int* layer_out, 
         if (ctx->s[v] >= stragglers) { u = v; break; }
     *layer_out = u;
     if (residual_out) *residual_out = 0.0;
-    if (u < 0) return ngc_fail(ctx, NGC_ERR_UNDECODABLE, "stragglers exceed the largest tolerance");
-    if (!ctx->code[u].set) return ngc_fail(ctx, NGC_ERR_STATE, "chosen layer has no code yet");
+    if (u < 0) return NGC_ERR_UNDECODABLE;
+    if (!ctx->code[u].set) return NGC_ERR_STATE;
     int rows[NGC_MAX_N];
     int ns = 0;
     const int want = first_only ? n - ctx->s[u] : n;
@@ -389,8 +387,21 @@ static int select_impl(const ngc_ctx* ctx, const uint8_t* mask, int* layer_out, 
     double resid = 0.0;
     ngc_layer_decode_vec(ctx, u, rows, ns, a_out, &resid);
     if (residual_out) *residual_out = resid;
-    if (!(resid <= 1e-6)) return ngc_fail(ctx, NGC_ERR_SINGULAR, "decode residual above tolerance");
+    if (!(resid <= 1e-6)) return NGC_ERR_SINGULAR;
     return NGC_OK;
+}
+
+static int select_impl(const ngc_ctx* ctx, const uint8_t* mask, int* layer_out, double* a_out,
+                       double* residual_out, bool first_only) {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (!mask || !layer_out || !a_out) return ngc_fail(ctx, NGC_ERR_INVALID, "null argument");
+    const int rc = ngc_select_core(ctx, mask, layer_out, a_out, residual_out, first_only);
+    switch (rc) {
+        case NGC_OK: return NGC_OK;
+        case NGC_ERR_UNDECODABLE: return ngc_fail(ctx, rc, "stragglers exceed the largest tolerance");
+        case NGC_ERR_STATE: return ngc_fail(ctx, rc, "chosen layer has no code yet");
+        default: return ngc_fail(ctx, rc, "decode residual above tolerance");
+    }
 }
 
 extern "C" int ngc_select_decode_vec(const ngc_ctx* ctx, const uint8_t* straggler_mask, int* layer_out,

@@ -60,6 +60,16 @@ struct ngc_ctx {
     void* d_code = nullptr;          // packed tables for all layers (see ngc_device.hip)
     size_t d_code_bytes = 0;
     size_t code_nnz = 0;             // non-zeros over all layers in d_code
+    size_t code_gmask_off = 0;       // byte offsets of the worker-group tables inside d_code
+    size_t code_gcoef_off = 0;
+    int code_ng = 0, code_kp = 0;    // groups of four workers, k rounded up to a multiple of 4
+    int lds_limit = 0;               // LDS bytes one block may use on this device
+    // per-round records of ngc_coded_rounds: device table, pinned staging, event after the copy
+    void* d_rounds = nullptr;
+    void* h_rounds = nullptr;
+    size_t rounds_cap = 0;           // records both hold
+    hipEvent_t rounds_ev = nullptr;
+    bool rounds_ev_set = false;
     float* d_ws = nullptr;           // workspace: block partials / residuals / MLP activations
     size_t d_ws_bytes = 0;
     // worker mode: unit -> partition / output-row maps, two copies used in turn so that a call
@@ -114,6 +124,10 @@ int ngc_null_factor(const double* B, int n, int k, double* a0, double* N, double
 // equation per straggler.  rows ascending.
 int ngc_min_norm_decode_null(const double* B, int n, int k, const double* a0, const double* N,
                              int q, const int* rows, int ns, double* a_out, double* resid);
+// Layer choice and decode vector for one straggler mask (the work of ngc_select_decode_vec)
+// without touching the context's error text, so that several host threads may call it at once.
+int ngc_select_core(const ngc_ctx* ctx, const uint8_t* mask, int* layer_out, double* a_out,
+                    double* residual_out, bool first_only);
 // Decode vector of layer `layer` for the responders in rows (ascending), by whichever of the
 // two routes is cheaper for this code and straggler count.
 void ngc_layer_decode_vec(const ngc_ctx* ctx, int layer, const int* rows, int ns, double* a_out,

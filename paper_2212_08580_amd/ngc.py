@@ -29,13 +29,14 @@ NGC_ERR_STATE = -6
 
 NGC_LOSS_LSQ, NGC_LOSS_LOGISTIC, NGC_LOSS_MLP2 = 0, 1, 2
 NGC_CODE_CYCLIC, NGC_CODE_FRACREP = 0, 1
-NGC_KERNEL_NAMES = ("grad", "reduce", "encode", "decode", "update", "mlp", "probe", "tail")
+NGC_KERNEL_NAMES = ("grad", "reduce", "encode", "decode", "update", "mlp", "probe", "tail", "rounds")
 NGC_KERNEL_COUNT = len(NGC_KERNEL_NAMES)
 
 EXPORTS = (
     "ngc_create", "ngc_destroy", "ngc_set_code", "ngc_get_code", "ngc_get_shape", "ngc_build_code",
     "ngc_set_mlp2_shape", "ngc_partition_grads", "ngc_partition_grads_static", "ngc_encode", "ngc_select_decode_vec",
-    "ngc_select_decode_vec_first", "ngc_decode", "ngc_update", "ngc_iteration", "ngc_sync",
+    "ngc_select_decode_vec_first", "ngc_decode", "ngc_encode_decode", "ngc_coded_rounds", "ngc_update",
+    "ngc_iteration", "ngc_tail_lds_bytes", "ngc_sync",
     "ngc_worker_task_count", "ngc_worker_schedule", "ngc_worker_grads", "ngc_worker_encode",
     "ngc_select_from_progress", "ngc_build_decoding_table", "ngc_decoding_row_index",
     "ngc_get_decoding_row", "ngc_decode_lookup", "ngc_latency_cdf_gc", "ngc_latency_cdf_ngc", "ngc_latency_simulate",
@@ -67,6 +68,9 @@ _lib.ngc_encode.argtypes = [_vp, _vp, _i, _vp]
 _lib.ngc_select_decode_vec.argtypes = [_vp, _vp, ctypes.POINTER(_i), _vp, ctypes.POINTER(_dbl)]
 _lib.ngc_select_decode_vec_first.argtypes = _lib.ngc_select_decode_vec.argtypes
 _lib.ngc_decode.argtypes = [_vp, _i, _vp, _vp, _vp]
+_lib.ngc_encode_decode.argtypes = [_vp, _vp, _i, _vp, _vp, _vp]
+_lib.ngc_coded_rounds.argtypes = [_vp, _vp, _i64, _i, _vp, _vp, _i64, _vp, _vp, _vp]
+_lib.ngc_tail_lds_bytes.argtypes = [_vp, _i, ctypes.POINTER(_i64), ctypes.POINTER(_i64)]
 _lib.ngc_update.argtypes = [_vp, _vp, _vp, _dbl]
 _lib.ngc_iteration.argtypes = [_vp, _i, _vp, _vp, _vp, _i64, _vp, _dbl, _vp, _vp, _vp,
                                ctypes.POINTER(_i), _vp]
@@ -252,6 +256,41 @@ def ngc_decode(ctx, layer, a, C, g):
     if a.size != n:
         raise ValueError("the decode vector must have n entries")
     _check(_lib.ngc_decode(ctx, int(layer), pa, _dev(C, L * n * d, "float32"), _dev(g, d, "float32")), ctx)
+
+
+def ngc_encode_decode(ctx, G, layer, a, M, g):
+    a, pa = _host(a, np.float64)
+    n, k, L, d, din = ngc_get_shape(ctx)
+    if a.size != n:
+        raise ValueError("the decode vector must have n entries")
+    _check(_lib.ngc_encode_decode(ctx, _dev(G, k * d, "float32"), int(layer), pa, _dev(M, n * d, "float32"),
+                                  _dev(g, d, "float32")), ctx)
+
+
+def ngc_coded_rounds(ctx, G, g_round_stride, masks, M, m_round_stride, g):
+    """-> (layers [rounds] int32, a [rounds, n] fp64).  masks: [rounds, n] uint8."""
+    masks, pm = _host(masks, np.uint8)
+    n, k, L, d, din = ngc_get_shape(ctx)
+    if masks.ndim != 2 or masks.shape[1] != n or masks.shape[0] < 1:
+        raise ValueError("masks must be [rounds, n]")
+    rounds = masks.shape[0]
+    gs, ms = int(g_round_stride), int(m_round_stride)
+    if gs < 0 or ms < 0:
+        raise ValueError("strides must not be negative")
+    layers = np.zeros(rounds, np.int32)
+    a = np.zeros((rounds, n), np.float64)
+    _check(_lib.ngc_coded_rounds(ctx, _dev(G, (rounds - 1) * gs + k * d, "float32"), gs, rounds, pm,
+                                 _dev(M, (rounds - 1) * ms + n * d, "float32"), ms,
+                                 _dev(g, rounds * d, "float32"), layers.ctypes.data_as(ctypes.c_void_p),
+                                 a.ctypes.data_as(ctypes.c_void_p)), ctx)
+    return layers, a
+
+
+def ngc_tail_lds_bytes(ctx, vec_width):
+    """-> (bytes with the code tables in LDS, bytes without)."""
+    w, wo = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(_lib.ngc_tail_lds_bytes(ctx, int(vec_width), ctypes.byref(w), ctypes.byref(wo)), ctx)
+    return w.value, wo.value
 
 
 def ngc_worker_task_count(ctx):

@@ -1,0 +1,245 @@
+"""Fused encode + decode (Sec. II-C, X = B G, then the recovery of Def. 1) through the C ABI:
+one round (ngc_encode_decode) and many rounds in one launch (ngc_coded_rounds).
+
+Checked per round: layer and support of the decode vector exact against the oracle; every
+message that is written against the oracle's B G (rel-L2 <= 1e-6) and bit for bit against
+ngc_encode; the recovered gradient against the oracle's fp64 combination of the fp32-rounded
+messages (<= 2e-7: the kernel must use the rounded message, not the unrounded sum), bit for bit
+against ngc_decode, and against the exact sum of the partial gradients within
+max(1e-4, 4 * 2^-24 * kappa).
+"""
+import numpy as np
+import pytest
+
+from oracle import codes, coding
+from paper_2212_08580_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def torch_dev():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (run on the MI355X box)")
+    torch.cuda.set_device(0)
+    return torch
+
+
+def rel(x, ref):
+    x = np.asarray(x, np.float64)
+    ref = np.asarray(ref, np.float64)
+    return float(np.linalg.norm(x - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def make_ctx(ngc, torch, n, k, layers, d, Bs):
+    ctx = ngc.ngc_create(n, k, layers, d, torch.cuda.current_stream().cuda_stream)
+    for u, B in enumerate(Bs):
+        ngc.ngc_set_code(ctx, u, B)
+    return ctx
+
+
+def random_masks(rng, n, smax, rounds):
+    masks = np.zeros((rounds, n), np.uint8)
+    for t in range(rounds):
+        s = int(rng.integers(0, smax + 1))
+        masks[t, rng.choice(n, size=s, replace=False)] = 1
+    return masks
+
+
+def oracle_round(Bs, layers, G64, mask):
+    """layer, decode vector, fp32-rounded messages of the layer, their fp64 combination, kappa."""
+    u = coding.select_layer(layers, mask)
+    a, _ = coding.decode_vector(Bs[u], mask)
+    C = coding.encode(Bs[u], G64)
+    C32 = C.astype(np.float32)
+    g = coding.decode(a, C32)
+    kappa = coding.conditioning(a, C, G64.sum(axis=0))
+    return u, a, C, C32, g, kappa
+
+
+@pytest.mark.parametrize("n,c,layers,kind,d", [
+    (4, 1, (0, 1), "fracrep", 64), (16, 1, (0, 1, 3, 7), "cyclic", 1024), (32, 1, (0, 1, 3, 7, 15), "cyclic", 4096),
+    (64, 1, (0, 1, 3, 7, 15, 31), "cyclic", 16384), (64, 1, (0, 1, 3, 7, 15, 31), "fracrep", 4096),
+    (20, 1, (0, 1, 4, 9), "cyclic", 1002), (20, 1, (0, 1, 4, 9), "cyclic", 999), (7, 1, (0, 2, 5), "cyclic", 100),
+    (1, 1, (0,), "cyclic", 5), (33, 1, (0, 32), "cyclic", 68), (8, 2, (0, 1, 3), "cyclic", 1024),
+    (6, 3, (0, 2), "cyclic", 200), (16, 1, tuple(range(8)), "cyclic", 300),
+])
+def test_one_round_fused_equals_encode_then_decode(ngc, torch_dev, n, c, layers, kind, d):
+    torch = torch_dev
+    dev = torch.device("cuda:0")
+    k = n * c
+    w = wl.C5.scaled(n=k, d=d, layers=layers)
+    G_h = wl.partial_gradients(w, seed=n + d)
+    G64 = G_h.astype(np.float64)
+    Bs = codes.expand_partitions(codes.nested_code(n, layers, kind, seed=0, draws=2), c)
+    ctx = make_ctx(ngc, torch, n, k, layers, d, Bs)
+    try:
+        L = len(layers)
+        G = torch.from_numpy(G_h).to(dev)
+        C = torch.empty((L, n, d), dtype=torch.float32, device=dev)
+        g_sep = torch.empty(d, dtype=torch.float32, device=dev)
+        g_fused = torch.empty(d, dtype=torch.float32, device=dev)
+        ngc.ngc_encode(ctx, G, -1, C)
+        rng = np.random.default_rng(7)
+        for mask in random_masks(rng, n, layers[-1], 10):
+            u, a, resid = ngc.ngc_select_decode_vec(ctx, mask, n)
+            u_o, a_o, C_o, C32_o, g_o, kappa = oracle_round(Bs, layers, G64, mask)
+            assert u == u_o and np.array_equal(a != 0, a_o != 0)
+            M = torch.full((n, d), -7.0, dtype=torch.float32, device=dev)
+            ngc.ngc_decode(ctx, u, a, C, g_sep)
+            ngc.ngc_encode_decode(ctx, G, u, a, M, g_fused)
+            ngc.ngc_sync(ctx)
+            resp = np.flatnonzero(a != 0)
+            out = np.flatnonzero(a == 0)
+            ridx = torch.from_numpy(resp).to(dev)
+            assert torch.equal(M[ridx], C[u][ridx])                      # same bits as ngc_encode
+            assert torch.equal(g_fused, g_sep)                           # same bits as ngc_decode
+            if out.size:
+                assert bool((M[torch.from_numpy(out).to(dev)] == -7.0).all())   # stragglers send nothing
+            Mh = M.cpu().numpy()
+            for i in resp:
+                assert rel(Mh[i], C_o[i]) <= 1e-6
+            gh = g_fused.cpu().numpy()
+            assert rel(gh, coding.decode(a, Mh)) <= 2e-7                 # fp64 combination of the written messages
+            assert rel(gh, G64.sum(axis=0)) <= max(TOL, 4 * 2.0 ** -24 * kappa)
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
+def run_rounds(ngc, torch, ctx, w, Bs, G_h, masks, g_stride, check_messages_every=1, oracle_every=1):
+    """ngc_coded_rounds over `masks`, checked round by round.  G_h: [k, d] (g_stride 0) or
+    [rounds, k, d].  Returns the decode errors against the exact gradient sum."""
+    dev = torch.device("cuda:0")
+    n, d, layers = w.n, w.d, w.layers
+    rounds = masks.shape[0]
+    L = len(layers)
+    G = torch.from_numpy(G_h).to(dev)
+    M = torch.full((rounds, n, d), -7.0, dtype=torch.float32, device=dev)
+    gh = torch.full((rounds, d), -7.0, dtype=torch.float32, device=dev)
+    lay, a_all = ngc.ngc_coded_rounds(ctx, G, g_stride, masks, M, n * d, gh)
+    ngc.ngc_sync(ctx)
+    C = torch.empty((L, n, d), dtype=torch.float32, device=dev)
+    g_sep = torch.empty(d, dtype=torch.float32, device=dev)
+    if g_stride == 0:
+        ngc.ngc_encode(ctx, G, -1, C)
+    errs, worst_msg, worst_comb = [], 0.0, 0.0
+    for r in range(rounds):
+        Gr = G_h if g_stride == 0 else G_h[r]
+        mask = masks[r]
+        if mask.sum() > layers[-1]:
+            assert lay[r] == -1 and not a_all[r].any()
+            assert bool((gh[r] == 0.0).all()) and bool((M[r] == -7.0).all())
+            continue
+        u, a = int(lay[r]), a_all[r]
+        assert u == coding.select_layer(layers, mask)
+        assert np.all(a[mask == 1] == 0)
+        resp = np.flatnonzero(a != 0)
+        ridx = torch.from_numpy(resp).to(dev)
+        if r % check_messages_every == 0:
+            # bit for bit against the separate calls
+            if g_stride != 0:
+                ngc.ngc_encode(ctx, G[r], u, C)
+            ngc.ngc_decode(ctx, u, a, C, g_sep)
+            ngc.ngc_sync(ctx)
+            assert torch.equal(M[r][ridx], C[u][ridx]), r
+            assert torch.equal(gh[r], g_sep), r
+            out = np.flatnonzero(a == 0)
+            if out.size:
+                assert bool((M[r][torch.from_numpy(out).to(dev)] == -7.0).all())
+        if r % oracle_every == 0:
+            G64 = Gr.astype(np.float64)
+            u_o, a_o, C_o, C32_o, g_o, kappa = oracle_round(Bs, layers, G64, mask)
+            assert u == u_o and np.array_equal(a != 0, a_o != 0)
+            Mh = M[r].cpu().numpy()
+            worst_msg = max(worst_msg, max(rel(Mh[i], C_o[i]) for i in resp))
+            g_r = gh[r].cpu().numpy()
+            worst_comb = max(worst_comb, rel(g_r, coding.decode(a, Mh)))
+            err = rel(g_r, G64.sum(axis=0))
+            assert err <= max(TOL, 4 * 2.0 ** -24 * kappa), (r, err, kappa)
+            errs.append(err)
+    assert worst_msg <= 1e-6 and worst_comb <= 2e-7, (worst_msg, worst_comb)
+    return np.array(errs)
+
+
+def test_coded_rounds_c5_all_1000_rounds(ngc, torch_dev):
+    """The encode/decode stress workload as a whole: n = 64, d = 16384, layers 0..31 in six steps,
+    1000 rounds with Binomial(64, 0.2) straggler counts, one G, one launch."""
+    w = wl.C5
+    G_h = wl.partial_gradients(w, 0)
+    masks = wl.binomial_count_masks(w, 1000, seed=0)
+    Bs = codes.nested_code(w.n, w.layers, "cyclic", seed=0, draws=2)
+    ctx = make_ctx(ngc, torch_dev, w.n, w.n, w.layers, w.d, Bs)
+    try:
+        errs = run_rounds(ngc, torch_dev, ctx, w, Bs, G_h, masks, 0)
+        assert errs.size >= 990
+        print("C5 fused rounds: %d rounds, median rel-L2 %.2e, worst %.2e, share above 1e-4: %.3f"
+              % (errs.size, np.median(errs), errs.max(), float(np.mean(errs > TOL))))
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
+def test_coded_rounds_c3_masks(ngc, torch_dev):
+    """The headline code (n = 32, d = 4096, layers 0,1,3,7,15) under its own Bernoulli(0.1)
+    stragglers, 400 rounds on one G."""
+    w = wl.C3
+    G_h = wl.partial_gradients(wl.C5.scaled(n=w.n, d=w.d, layers=w.layers), 3)
+    masks = wl.bernoulli_masks(w, 400, seed=5)
+    Bs = codes.nested_code(w.n, w.layers, "cyclic", seed=0, draws=2)
+    ctx = make_ctx(ngc, torch_dev, w.n, w.n, w.layers, w.d, Bs)
+    try:
+        errs = run_rounds(ngc, torch_dev, ctx, w, Bs, G_h, masks, 0)
+        assert errs.size >= 395 and errs.max() <= TOL
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
+@pytest.mark.parametrize("n,layers,kind,d,rounds", [(16, (0, 1, 3, 7), "cyclic", 1000, 70),
+                                                    (12, (0, 1, 2, 3, 5), "cyclic", 4099, 33),
+                                                    (8, (0, 1, 3), "fracrep", 66, 300)])
+def test_coded_rounds_with_a_gradient_per_round_and_undecodable_rounds(ngc, torch_dev, n, layers, kind, d, rounds):
+    """Every round has its own G (stride k*d: the tile is staged anew each round); some rounds
+    have more stragglers than the code tolerates: zero gradient, no message, not an error."""
+    w = wl.C5.scaled(n=n, d=d, layers=layers)
+    rng = np.random.default_rng(n + d)
+    G_h = rng.standard_normal((rounds, n, d)).astype(np.float32)
+    masks = random_masks(rng, n, layers[-1], rounds)
+    for r in range(0, rounds, 9):
+        masks[r] = 0
+        masks[r, rng.choice(n, size=layers[-1] + 1, replace=False)] = 1      # one too many
+    Bs = codes.nested_code(n, layers, kind, seed=0, draws=2)
+    ctx = make_ctx(ngc, torch_dev, n, n, layers, d, Bs)
+    try:
+        run_rounds(ngc, torch_dev, ctx, w, Bs, G_h, masks, n * d)
+        run_rounds(ngc, torch_dev, ctx, w, Bs, G_h[0], masks[:5], 0)        # fewer rounds afterwards
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
+def test_coded_rounds_rejects_bad_arguments(ngc, torch_dev):
+    torch = torch_dev
+    dev = torch.device("cuda:0")
+    n, d, layers = 4, 64, (0, 1)
+    Bs = codes.nested_code(n, layers, "cyclic", seed=0, draws=2)
+    ctx = make_ctx(ngc, torch, n, n, layers, d, Bs)
+    try:
+        G = torch.zeros((3, n, d), dtype=torch.float32, device=dev)
+        M = torch.zeros((3, n, d), dtype=torch.float32, device=dev)
+        g = torch.zeros((3, d), dtype=torch.float32, device=dev)
+        masks = np.zeros((3, n), np.uint8)
+        with pytest.raises(ngc.NgcError):
+            ngc.ngc_coded_rounds(ctx, G, 5, masks, M, n * d, g)               # stride neither 0 nor >= k*d
+        with pytest.raises(ngc.NgcError):
+            ngc.ngc_coded_rounds(ctx, G, 0, masks, M, n * d - 1, g)           # rounds' messages would overlap
+        with pytest.raises(ValueError):
+            ngc.ngc_coded_rounds(ctx, G, 0, masks, M[:2], n * d, g)           # buffer too small for 3 rounds
+        with pytest.raises(ngc.NgcError):
+            ngc.ngc_encode_decode(ctx, G, 2, np.ones(n), M, g)                # no such layer
+        bad = np.ones(n)
+        bad[1] = np.nan
+        with pytest.raises(ngc.NgcError):
+            ngc.ngc_encode_decode(ctx, G, 1, bad, M, g)
+    finally:
+        ngc.ngc_destroy(ctx)

@@ -647,6 +647,10 @@ def test_several_partitions_per_worker(ngc, torch_dev, n, c, layers, kind, d, ro
     (wl.C3, 6, 1, 33, 200, (0, 1, 3)), (wl.C2, 5, 1, 21, 77, (0, 2)), (wl.C3, 4, 2, 25, 512, (0, 1)),
     (wl.C3, 64, 1, 5, 16384, (0, 1, 3, 7, 15, 31)),
     (wl.C2, 6, 1, 19, 1002, (0, 2)), (wl.C3, 4, 1, 9, 5000, (0, 1)), (wl.C3, 3, 1, 4, 20000, (0, 1)),
+    # the paper's own layer set, every sigma = 0..s_max (Def. 2); the last one's code tables
+    # (33 792 non-zeros) do not fit the LDS of a block and stay in global memory
+    (wl.C3, 16, 1, 7, 256, tuple(range(8))), (wl.C2, 32, 1, 5, 128, tuple(range(16))),
+    (wl.C3, 64, 1, 3, 64, tuple(range(32))),
 ])
 def test_fused_iteration_equals_separate_calls(ngc, torch_dev, base, n, c, rows, d, layers):
     torch = torch_dev

@@ -20,8 +20,12 @@ def rel(x, ref):
 @pytest.mark.parametrize("base,n,rows,d,layers,kind", [
     (wl.C3, 8, 37, 4096, (0, 1, 3), "cyclic"),
     (wl.C2, 8, 50, 1024, (0, 1, 3, 7), "fracrep"),
-    (wl.C1, 4, 256, 64, (0, 1), "fracrep"),          # two-pass route (d = 64)
+    (wl.C1, 4, 256, 64, (0, 1), "fracrep"),          # the narrowest single-pass shape (d = 64)
     (wl.C3, 6, 21, 200, (0, 2, 3), "cyclic"),
+    # the paper's own layer set, every sigma = 0..s_max (Def. 2): more than eight layers
+    (wl.C3, 16, 5, 256, tuple(range(8)), "cyclic"),
+    (wl.C3, 32, 3, 128, tuple(range(16)), "cyclic"),
+    (wl.C2, 64, 2, 64, tuple(range(32)), "cyclic"),
 ])
 def test_worker_execution_matches_oracle(ngc, base, n, rows, d, layers, kind):
     import torch
@@ -153,6 +157,67 @@ def test_worker_execution_with_the_perceptron_loss(ngc, n, rows, d_in, hidden, c
             assert err <= max(TOL, 4 * 2.0 ** -24 * kappa), (err, kappa)
             decoded += 1
         assert decoded >= 2
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
+def test_worker_encode_with_rows_of_unequal_weight(ngc):
+    """A nested code installed by hand whose rows differ in weight: worker 0 holds three
+    partitions, the others two, so the schedules differ in length and the rows of W beyond a
+    worker's own schedule are never written.  They are filled with NaN here: a finished worker's
+    message must not touch them."""
+    import torch
+    dev = torch.device("cuda:0")
+    n, d, rows, layers = 4, 300, 9, (0, 1)
+    w = wl.C3.scaled(rows=rows, d=d, n=n, layers=layers)
+    X, Y = wl.dataset(w, seed=8, threads=1)
+    th = wl.theta(w, seed=9)
+    # rows in the null space of h = (1, 2, -4, 1) (h . 1 = 0): any three of them span {x : h . x = 0},
+    # which contains the all-ones vector; row 0 carries a third partition
+    h = np.array([1.0, 2.0, -4.0, 1.0])
+    B1 = np.zeros((n, n))
+    B1[0, [0, 1, 2]] = [1.0, 1.5, 1.0]
+    for i in range(1, n):
+        j = (i + 1) % n
+        B1[i, i], B1[i, j] = 1.0, -h[i] / h[j]
+    assert np.allclose(B1 @ h, 0.0)
+    Bs = [np.eye(n), B1]
+    for out in range(n):                                      # Def. 1 for sigma = 1, by hand
+        S = [i for i in range(n) if i != out]
+        a = codes.min_norm_decode_vector(B1, S)
+        assert np.max(np.abs(a @ B1 - 1.0)) <= 1e-12
+    G_o = gradients.partial_gradients(w.loss, X, Y, th)
+    ctx = ngc.ngc_create(n, n, layers, d, torch.cuda.current_stream().cuda_stream)
+    try:
+        for u, B in enumerate(Bs):
+            ngc.ngc_set_code(ctx, u, B)
+        T = ngc.ngc_worker_task_count(ctx)
+        assert T == 3
+        assert [len(ngc.ngc_worker_schedule(ctx, i)) for i in range(n)] == [3, 2, 2, 2]
+        Xd, Yd, thd = (torch.from_numpy(a).to(dev) for a in (X, Y, th))
+        C = torch.empty((2, n, d), dtype=torch.float32, device=dev)
+        g = torch.empty(d, dtype=torch.float32, device=dev)
+        for progress in (np.array([3, 3, 3, 3]), np.array([3, 2, 0, 3]), np.array([2, 2, 2, 2])):
+            W = torch.full((n, T, d), float("nan"), dtype=torch.float32, device=dev)
+            ngc.ngc_worker_grads(ctx, w.loss, Xd, Yd, thd, rows, progress, W)
+            ngc.ngc_worker_encode(ctx, W, progress, C)
+            ngc.ngc_sync(ctx)
+            Ch = C.cpu().numpy()
+            assert np.all(np.isfinite(Ch))
+            W_o = ow.worker_partials(w.loss, X, Y, th, Bs, progress)
+            C_o = ow.worker_messages(Bs, W_o, progress)
+            for u in range(2):
+                for i in range(n):
+                    if C_o[u][i] is None:
+                        assert np.all(Ch[u, i] == 0.0)
+                    else:
+                        assert rel(Ch[u, i], C_o[u][i]) <= TOL, (u, i)
+            u, mask, a, r = ngc.ngc_select_from_progress(ctx, progress, n, 0)
+            u_o, mask_o, a_o, g_o = ow.decode_from_workers(Bs, layers, W_o, progress, 0)
+            assert u == u_o and np.array_equal(mask, mask_o)
+            ngc.ngc_decode(ctx, u, a, C, g)
+            ngc.ngc_sync(ctx)
+            assert rel(g.cpu().numpy(), G_o.sum(axis=0)) <= TOL
     finally:
         ngc.ngc_destroy(ctx)
 

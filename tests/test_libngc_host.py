@@ -499,3 +499,42 @@ def test_context_with_several_partitions_per_worker(ngc):
     for n, k in ((4, 6), (8, 4), (40, 80)):
         with pytest.raises(ngc.NgcError):
             ngc.ngc_create(n, k, [0, 1], 4)
+
+
+def test_lds_need_of_the_iteration_tail(ngc):
+    """Size formula of ngc_iteration's second launch, retyped here from the layout the header
+    states: sixteen fp64 partial-sum rows of 16 V + 1, a G tile of k x 16 V floats, the decode
+    layer's messages n x 16 V floats, and (if kept in LDS) the compressed code tables
+    L n + 1 row pointers + a column index and a coefficient per non-zero."""
+    def want(n, k, L, nnz, V, tables):
+        b = 16 * (16 * V + 1) * 8 + (k + n) * 16 * V * 4
+        return b + (L * n + 1 + 2 * nnz) * 4 if tables else b
+
+    cases = [(4, 4, (0, 1)), (32, 32, (0, 1, 3, 7, 15)), (64, 64, (0, 1, 3, 7, 15, 31)),
+             (8, 16, (0, 1, 3)), (64, 64, tuple(range(32)))]
+    for n, k, layers in cases:
+        ctx = ngc.ngc_create(n, k, layers, 1024)
+        try:
+            with pytest.raises(ngc.NgcError) as e:
+                ngc.ngc_tail_lds_bytes(ctx, 4)                     # a layer without its code
+            assert e.value.code == ngc.NGC_ERR_STATE
+            ngc.ngc_build_code(ctx, ngc.NGC_CODE_CYCLIC, 1)
+            nnz = sum(int(np.count_nonzero(ngc.ngc_get_code(ctx, u))) for u in range(len(layers)))
+            assert nnz == sum((s + 1) * k for s in layers)          # row weight (k/n)(sigma+1), Def. 1
+            for V in (1, 2, 4):
+                w, wo = ngc.ngc_tail_lds_bytes(ctx, V)
+                assert w == want(n, k, len(layers), nnz, V, True)
+                assert wo == want(n, k, len(layers), nnz, V, False)
+            with pytest.raises(ngc.NgcError):
+                ngc.ngc_tail_lds_bytes(ctx, 3)
+        finally:
+            ngc.ngc_destroy(ctx)
+    # the full layer set of 64 workers: the tables alone exceed the 160 KiB of LDS a CU has,
+    # the tiles without them fit easily
+    ctx = ngc.ngc_create(64, 64, tuple(range(32)), 1024)
+    try:
+        ngc.ngc_build_code(ctx, ngc.NGC_CODE_CYCLIC, 1)
+        w, wo = ngc.ngc_tail_lds_bytes(ctx, 4)
+        assert w > 160 * 1024 > 64 * 1024 > wo
+    finally:
+        ngc.ngc_destroy(ctx)
