@@ -33,40 +33,40 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def measured_traffic(workload_name, summary="grad_stream"):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary,
-    or None if the kernel source has changed since those counters were taken."""
+def measured(summary, key):
+    """(value, source) of the line 'key: value' in a committed rocprofv3 counter summary under
+    profiles/, or (None, None) if a kernel source has changed since those counters were taken:
+    the summary names every source file its kernels are built from with its sha256."""
     import hashlib
-    path = os.path.join(ROOT, "profiles", "%s_%s.txt" % (summary, workload_name))
-    src = os.path.join(ROOT, "paper_2212_08580_amd", "csrc", "ngc_device.hip")
+    import re
+    path = os.path.join(ROOT, "profiles", summary)
     try:
-        sha = hashlib.sha256(open(src, "rb").read()).hexdigest()
         text = open(path).read()
     except OSError:
-        return None
-    if ("ngc_device.hip: " + sha) not in text:
-        return None
-    for line in text.splitlines():
-        if line.startswith("traffic-bytes-per-launch:"):
-            return float(line.split(":")[1])
-    return None
-
-
-def measured_figure(summary, source, key):
-    """A number that a committed rocprofv3 counter summary holds as a line 'key: value', or None
-    if the kernel source has changed since the counters were taken."""
-    import hashlib
-    try:
-        sha = hashlib.sha256(open(os.path.join(ROOT, "paper_2212_08580_amd", "csrc", source), "rb").read()).hexdigest()
-        text = open(os.path.join(ROOT, "profiles", summary)).read()
-    except OSError:
-        return None
-    if (source + ": " + sha) not in text:
-        return None
+        return None, None
+    named = re.findall(r"^source-sha256 (\S+): ([0-9a-f]{64})$", text, flags=re.M)
+    if not named:
+        return None, None
+    for rel_path, sha in named:
+        try:
+            now = hashlib.sha256(open(os.path.join(ROOT, rel_path), "rb").read()).hexdigest()
+        except OSError:
+            return None, None
+        if now != sha:
+            return None, None
     for line in text.splitlines():
         if line.startswith(key + ":"):
-            return float(line.split(":")[1])
-    return None
+            return float(line.split(":")[1]), ("profiles/%s (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs, committed; "
+                                               "taken with the kernel sources as they are now)" % summary)
+    return None, None
+
+
+def with_traffic(roofline, summary, key="traffic-bytes-per-launch"):
+    """Adds the measured HBM bytes per launch (or null) and where they come from."""
+    value, source = measured(summary, key)
+    roofline["traffic"] = value
+    roofline["traffic_source"] = source
+    return roofline
 
 
 def blas_threads():
@@ -78,19 +78,13 @@ def blas_threads():
         return os.cpu_count() or 1
 
 
-def cpu_baseline(w, wl, parts_host, theta, masks, budget_parts, workers=None, layers=None):
+def cpu_baseline(w, wl, parts_host, theta, masks, budget_parts, Bs, layers):
     """The fp64 checker timed on the host cores over a bounded sample of the same
     workload: `budget_parts` partitions for the gradients, then encode of all
     layers, layer/decode-vector selection and decode at full n and d."""
     import numpy as np
-    from oracle import codes, coding, gradients
+    from oracle import coding, gradients
     cores = blas_threads()
-    workers = w.n if workers is None else workers        # w.n partitions shared out over the workers
-    layers = w.layers if layers is None else layers
-    Bs = codes.nested_code(workers, layers, "cyclic" if w.code == wl.CODE_CYCLIC else "fracrep",
-                           seed=0, draws=2)
-    if workers != w.n:
-        Bs = codes.expand_partitions(Bs, w.n // workers)
     t0 = time.perf_counter()
     rows = []
     for X, Y in parts_host[:budget_parts]:
@@ -114,105 +108,195 @@ def cpu_baseline(w, wl, parts_host, theta, masks, budget_parts, workers=None, la
     }
 
 
-def bench_codec(args, w, wl, ngc, torch, np):
-    """Encode/decode stress (no data): per round encode every layer from resident partial
-    gradients, choose layer and decode vector for a Binomial(n, 0.2) straggler set on the host,
-    decode.  Reports algorithmic GB/s (G read once + every message written; responders' messages
-    read + one vector written) and per-round latency."""
+def oracle_code(ngc, ctx, L):
+    """The code the library built, read back through the C ABI, as the oracle's input."""
+    return [ngc.ngc_get_code(ctx, u) for u in range(L)]
+
+
+def def1_residual(np, Bs, layers, seed=0, sets_per_layer=4):
+    """Def. 1 checked in the oracle on sampled straggler sets of the design size sigma of every
+    layer: largest |a B - 1| of the decode vectors (the responders must span the all-ones row)."""
+    from oracle import coding
+    rng = np.random.default_rng(seed)
+    n = Bs[0].shape[0]
+    worst = 0.0
+    for u, sigma in enumerate(layers):
+        for _ in range(sets_per_layer):
+            m = np.zeros(n, np.uint8)
+            m[rng.choice(n, size=sigma, replace=False)] = 1
+            worst = max(worst, coding.decode_vector(Bs[u], m)[1])
+    return worst
+
+
+def rel_l2(np, x, ref):
+    x = np.asarray(x, np.float64)
+    ref = np.asarray(ref, np.float64)
+    return float(np.linalg.norm(x - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def codec_parity(np, Bs, layers, G64, masks, lay, a_all, M_rows, g_rows):
+    """Rounds of the fused encode + decode against the oracle.  M_rows(r) / g_rows(r) give the
+    GPU's messages [n, d] and recovered gradient [d] of round r as host arrays."""
+    from oracle import coding
+    full = G64.sum(axis=0)
+    msg, errs, kappas = 0.0, [], []
+    layer_ok = support_ok = True
+    for r in range(masks.shape[0]):
+        u_o = coding.select_layer(layers, masks[r])
+        a_o, _ = coding.decode_vector(Bs[u_o], masks[r])
+        layer_ok &= int(lay[r]) == u_o
+        support_ok &= bool(np.array_equal(a_all[r] != 0, a_o != 0))
+        C_o = coding.encode(Bs[u_o], G64)
+        Mh = M_rows(r)
+        resp = np.flatnonzero(a_o != 0)
+        msg = max(msg, rel_l2(np, Mh[resp], C_o[resp]))
+        errs.append(rel_l2(np, g_rows(r), full))
+        kappas.append(coding.conditioning(a_o, C_o, full))
+    errs = np.array(errs)
+    return {"rounds_checked": int(errs.size), "messages_rel_l2_max": msg,
+            "decoded_rel_l2_max": float(errs.max()), "decoded_rel_l2_median": float(np.median(errs)),
+            "share_of_rounds_within_1e-4": float(np.mean(errs <= 1e-4)), "kappa_max": float(max(kappas)),
+            "decoded_within_4eps_kappa": bool(np.all(errs <= np.maximum(1e-4, 4 * 2.0 ** -24 * np.array(kappas)))),
+            "layer_exact": bool(layer_ok), "support_exact": bool(support_ok)}
+
+
+def bench_codec(args, w, wl, ngc, torch, np, rounds=None, cpu_leg=True):
+    """Encode/decode stress (no data), n = 64 partial gradients of length 16384 resident in HBM.
+    A step is one round: the messages of the round's layer for the responders of a
+    Binomial(n, 0.2) straggler set and the recovered gradient.  Timed as the workload states it,
+    `rounds` rounds with decode vectors solved per round: one ngc_coded_rounds call (host
+    bookkeeping of every round, one table upload, one launch).  Beside it: the same with a new G
+    every round (the tile cannot stay in LDS: every byte comes from HBM), the stand-alone
+    kernels, and a loop of one launch pair per round with the host in it."""
     dev = torch.device("cuda:0")
-    K, W = args.steps, args.warmup
+    K = rounds if rounds is not None else args.steps
+    W = args.warmup
     L = len(w.layers)
+    n, d = w.n, w.d
     G = torch.from_numpy(wl.partial_gradients(w, 0)).to(dev)
-    C = torch.empty((L, w.n, w.d), dtype=torch.float32, device=dev)
-    g = torch.empty(w.d, dtype=torch.float32, device=dev)
-    masks = wl.binomial_count_masks(w, K + W, seed=0)
+    C = torch.empty((L, n, d), dtype=torch.float32, device=dev)
+    g = torch.empty(d, dtype=torch.float32, device=dev)
+    M = torch.empty((K, n, d), dtype=torch.float32, device=dev)
+    gh = torch.empty((K, d), dtype=torch.float32, device=dev)
+    masks = wl.binomial_count_masks(w, K, seed=0)
     masks[masks.sum(axis=1) > w.layers[-1]] = 0
-    ctx = ngc.ngc_create(w.n, w.n, w.layers, w.d, torch.cuda.current_stream().cuda_stream)
+    ctx = ngc.ngc_create(n, n, w.layers, d, torch.cuda.current_stream().cuda_stream)
     ngc.ngc_build_code(ctx, ngc.NGC_CODE_CYCLIC if w.code == wl.CODE_CYCLIC else ngc.NGC_CODE_FRACREP, 0)
 
-    def step(t):
-        ngc.ngc_encode(ctx, G, -1, C)
-        u, a, _ = ngc.ngc_select_decode_vec(ctx, masks[t], w.n)
-        ngc.ngc_decode(ctx, u, a, C, g)
-        return a
-
-    for t in range(W):
-        step(t)
+    # ---- the timed region: all K rounds in one call (warm-up calls first) ---------------------
+    for _ in range(max(1, min(W, 3))):
+        ngc.ngc_coded_rounds(ctx, G, 0, masks, M, n * d, gh)
     torch.cuda.synchronize()
-    ngc.ngc_profile_enable(ctx, ["encode"])
-    resp = 0
+    ngc.ngc_profile_enable(ctx, ["rounds"])
     t0 = time.perf_counter()
-    for t in range(W, W + K):
-        resp += int(np.count_nonzero(step(t)))
+    lay, a_all = ngc.ngc_coded_rounds(ctx, G, 0, masks, M, n * d, gh)
+    t_host = time.perf_counter() - t0
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    prof = ngc.ngc_profile_read(ctx)
-    ngc.ngc_profile_enable(ctx, ["decode"])
-    for t in range(W, W + min(K, 200)):
-        step(t)
-    prof_d = ngc.ngc_profile_read(ctx)
-    ngc.ngc_profile_enable(ctx, False)
-    # the same K rounds twice more without event records: K rounds last tens of milliseconds,
-    # so one scheduling stall of the host thread shows in a single region's time
-    repeats = []
-    for _ in range(2):
+    launches, kern_ms = ngc.ngc_profile_read(ctx)["rounds"]
+    resp = float(np.count_nonzero(a_all)) / K
+    fused_bytes = 4.0 * d * (n + resp + 1)                  # G read + responders' messages written + gradient
+    # a few more calls: spread of the kernel time, and of the call's wall time with the host part
+    walls = []
+    for _ in range(4):
         torch.cuda.synchronize()
-        tr = time.perf_counter()
-        for t in range(W, W + K):
-            step(t)
+        tw = time.perf_counter()
+        ngc.ngc_coded_rounds(ctx, G, 0, masks, M, n * d, gh)
         torch.cuda.synchronize()
-        repeats.append(round((time.perf_counter() - tr) / K * 1e3, 4))
-    # batched: the decode vectors of all rounds chosen beforehand, then encode + decode of every
-    # round queued back to back (what the device sustains once the host is out of the loop)
-    chosen = [ngc.ngc_select_decode_vec(ctx, masks[t], w.n)[:2] for t in range(W, W + K)]
-    torch.cuda.synchronize()
-    tb = time.perf_counter()
-    for u, a in chosen:
+        walls.append(time.perf_counter() - tw)
+    per_call = ngc.ngc_profile_launches(ctx, "rounds")
+    ngc.ngc_profile_read(ctx)
+    achieved = fused_bytes * K / (kern_ms * 1e-3) / 1e9
+    # parity of exactly these rounds against the oracle (the library-built code goes to the oracle),
+    # on rounds spread over the run, taken before the buffers are used again below
+    Bs = oracle_code(ngc, ctx, L)
+    G64 = G.cpu().numpy().astype(np.float64)
+    sel = np.linspace(0, K - 1, min(K, 24)).astype(int)
+    M_sel = [M[int(r)].cpu().numpy() for r in sel]
+    g_sel = [gh[int(r)].cpu().numpy() for r in sel]
+    parity = codec_parity(np, Bs, w.layers, G64, masks[sel], lay[sel], a_all[sel], lambda r: M_sel[r], lambda r: g_sel[r])
+    parity["code"] = "ngc_build_code(seed 0), read back with ngc_get_code and handed to the oracle"
+    parity["def1_residual_max"] = def1_residual(np, Bs, w.layers)
+    del M_sel, g_sel
+
+    # ---- the same rounds with a G of its own per round (streamed from HBM) --------------------
+    Ks = min(K, 256)
+    Gs = torch.randn((Ks, n, d), dtype=torch.float32, device=dev)
+    ngc.ngc_coded_rounds(ctx, Gs, n * d, masks[:Ks], M, n * d, gh)
+    ngc.ngc_profile_read(ctx)
+    for _ in range(3):
+        ngc.ngc_coded_rounds(ctx, Gs, n * d, masks[:Ks], M, n * d, gh)
+    ls, ms_s = ngc.ngc_profile_read(ctx)["rounds"]
+    resp_s = float(np.count_nonzero(a_all[:Ks])) / Ks
+    stream_GBps = 4.0 * d * (n + resp_s + 1) * Ks * ls / (ms_s * 1e-3) / 1e9
+    del Gs
+
+    # ---- stand-alone kernels and the per-round loop (host in the loop) -------------------------
+    Kl = min(K, 300)
+    ngc.ngc_profile_enable(ctx, ["encode", "decode", "rounds"])
+    for t in range(Kl):
         ngc.ngc_encode(ctx, G, -1, C)
-        ngc.ngc_decode(ctx, u, a, C, g)
-    torch.cuda.synchronize()
-    batched = time.perf_counter() - tb
+        ngc.ngc_decode(ctx, int(lay[t]), a_all[t], C, g)
+        ngc.ngc_encode_decode(ctx, G, int(lay[t]), a_all[t], M[0], g)
+    prof = ngc.ngc_profile_read(ctx)
+    ngc.ngc_profile_enable(ctx, False)
     enc_ms = prof["encode"][1] / max(1, prof["encode"][0])
-    dec_ms = prof_d["decode"][1] / max(1, prof_d["decode"][0])
-    enc_bytes = 4.0 * w.n * w.d * (1 + L)
-    dec_bytes = 4.0 * w.d * (resp / K + 1)
-    achieved = enc_bytes / (enc_ms * 1e-3) / 1e9
+    dec_ms = prof["decode"][1] / max(1, prof["decode"][0])
+    one_ms = prof["rounds"][1] / max(1, prof["rounds"][0])
+    torch.cuda.synchronize()
+    tl = time.perf_counter()
+    for t in range(Kl):
+        u, a, _ = ngc.ngc_select_decode_vec(ctx, masks[t], n)
+        ngc.ngc_encode_decode(ctx, G, u, a, M[0], g)
+    torch.cuda.synchronize()
+    loop_ms = (time.perf_counter() - tl) / Kl * 1e3
+    enc_bytes = 4.0 * n * d * (1 + L)
+    dec_bytes = 4.0 * d * (resp + 1)
+
+    roofline = with_traffic(
+        {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+         "frac": round(achieved / HBM_PEAK_GBS, 4), "algorithmic_bytes": fused_bytes * K,
+         "kernel": "coded_rounds_kernel (%d rounds per launch, one G for all rounds)" % K,
+         "avg_ms": round(kern_ms / max(1, launches), 4), "launches": launches,
+         "median_ms": round(float(np.median(per_call)), 4) if per_call.size else None,
+         "note": "algorithmic bytes per round = 4 n d (G) + 4 n_S d (messages written) + 4 d; with one G for all "
+                 "rounds a block reads its tile of G once and keeps it in LDS, so the HBM traffic is mostly the "
+                 "messages (see traffic)"},
+        "coded_rounds_%s.txt" % w.name)
     out = {
-        "metric": metric_name(w.n, w.d),
-        "value": round((enc_bytes + dec_bytes) * K / elapsed / 1e9, 1), "unit": "GB/s", "n_gpus": 1,
-        "steps": K, "warmup": W, "ms_per_step": round(elapsed / K * 1e3, 4), "higher_is_better": True,
+        "metric": metric_name(n, d),
+        "value": round(fused_bytes * K / elapsed / 1e9, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": K, "warmup": W, "ms_per_step": round(elapsed / K * 1e3, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w.name, "n": w.n, "d": w.d, "layers": list(w.layers),
-                   "p_straggle": w.p_straggle, "mean_responders": resp / K},
-        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": measured_traffic(w.name, "encode_decode"),
-                     "algorithmic_bytes": enc_bytes, "kernel": "encode_kernel",
-                     "avg_ms": round(enc_ms, 4), "launches": prof["encode"][0]},
-        "stages": {"encode_ms": round(enc_ms, 4), "encode_GBps": round(achieved, 1),
-                   "decode_ms": round(dec_ms, 4),
-                   "decode_GBps": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
-                   "round_ms_repeats": repeats,
-                   "batched_ms_per_round": round(batched / K * 1e3, 4),
-                   "batched_GBps": round((enc_bytes + dec_bytes) * K / batched / 1e9, 1)},
+        "config": {"workload": w.name, "n": n, "d": d, "layers": list(w.layers),
+                   "p_straggle": w.p_straggle, "mean_responders": resp, "rounds_per_call": K},
+        "roofline": roofline,
+        "stages": {"host_bookkeeping_ms_per_call": round(t_host * 1e3, 3),
+                   "call_ms_repeats": [round(x * 1e3, 3) for x in walls],
+                   "kernel_us_per_round": round(kern_ms / K * 1e3, 4),
+                   "batched_GBps": round(achieved, 1),
+                   "batched_GBps_new_G_every_round": round(stream_GBps, 1),
+                   "encode_all_layers_ms": round(enc_ms, 4), "encode_GBps": round(enc_bytes / (enc_ms * 1e-3) / 1e9, 1),
+                   "decode_ms": round(dec_ms, 4), "decode_GBps": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
+                   "fused_one_round_ms": round(one_ms, 4),
+                   "fused_one_round_GBps": round(fused_bytes / (one_ms * 1e-3) / 1e9, 1),
+                   "round_ms_host_in_loop": round(loop_ms, 4)},
+        "parity": parity,
     }
-    if not args.no_cpu_baseline:
-        from oracle import codes, coding
-        Bs = codes.nested_code(w.n, w.layers, "cyclic", seed=0, draws=2)
-        Gh = G.cpu().numpy()
-        rounds = min(K, 20)
+    if cpu_leg and not args.no_cpu_baseline:
+        from oracle import coding
+        cnt = min(K, 20)
         t0 = time.perf_counter()
-        for t in range(rounds):
-            Co = coding.encode_layers(Bs, Gh)
-            u = coding.select_layer(w.layers, masks[W + t])
-            a, _ = coding.decode_vector(Bs[u], masks[W + t])
-            coding.decode(a, Co[u])
-        dt = (time.perf_counter() - t0) / rounds
-        out["cpu_baseline"] = {"value": (enc_bytes + dec_bytes) / dt / 1e9, "unit": "GB/s",
+        for t in range(cnt):
+            u = coding.select_layer(w.layers, masks[t])
+            a, _ = coding.decode_vector(Bs[u], masks[t])
+            coding.decode(a, coding.encode(Bs[u], G64).astype(np.float32))
+        dt = (time.perf_counter() - t0) / cnt
+        out["cpu_baseline"] = {"value": fused_bytes / dt / 1e9, "unit": "GB/s",
                                "cores": blas_threads(), "kind": "oracle",
-                               "sample": "%d rounds of encode + select + decode at full n, d" % rounds}
+                               "sample": "%d rounds of layer choice, decode vector, encode of the layer and decode at full n, d" % cnt}
     ngc.ngc_destroy(ctx)
-    print(json.dumps(out), flush=True)
+    return out
 
 
 def bench_workers(args, w, wl, ngc, torch, np):
@@ -392,7 +476,7 @@ def bench_latency(args, ngc, torch, np):
     # sorting): achieved = vector instructions per launch (counter summary) x 64 lanes / launch
     # time, against one vector instruction per SIMD every four clocks over 64 lanes
     # (256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz).
-    valu = measured_figure("latency_sim_n8.txt", "ngc_latency.hip", "valu-instructions-per-launch-smax6")
+    valu, valu_source = measured("latency_sim_n8.txt", "valu-instructions-per-launch-smax6")
     peak = 256 * 4 * 16 * 2.4e9 / 1e12
     ach = None if valu is None else valu * 64.0 / (trials / rate) / 1e12
     out["roofline"] = {"bound": "alu", "achieved": None if ach is None else round(ach, 2), "peak": round(peak, 1),
@@ -520,61 +604,20 @@ def bench_lookup(args, wl, ngc, torch, np):
     print(json.dumps(out), flush=True)
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C3")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-probe", action="store_true")
-    ap.add_argument("--mode", default="pipeline", choices=["pipeline", "workers", "latency", "lookup"])
-    ap.add_argument("--cpu-parts", type=int, default=32)
-    ap.add_argument("--parts-per-worker", type=int, default=1,
-                    help="k = c n (Sec. II-C): the workload's partitions are shared out c to a worker")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: nested gradient coding here simulates all n workers on "
-              "a single MI355X; --gpus %d is not supported" % args.gpus, file=sys.stderr)
-        sys.exit(2)
-
-    import numpy as np
-    import torch
-    from paper_2212_08580_amd import ngc, workloads as wl
-
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        sys.exit(2)
+def bench_pipeline(args, w, wl, ngc, torch, np, K, W, cpu_leg=True, probe=True, parity_parts=None):
+    """One workload through the whole path.  A step is one iteration: partition gradients,
+    every layer's messages, layer + decode vector for the round's stragglers, decode, update
+    (two launches for the regression losses).  Returns the result line as a dict."""
     dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    # With torch imported a full pass of the interpreter's cycle collector takes tens of
-    # milliseconds, as long as a thousand encode/decode rounds; the objects alive now are set
-    # aside so that a pass triggered inside a timed region only looks at what the loop made.
-    gc.collect()
-    gc.freeze()
-    if args.mode == "latency":
-        return bench_latency(args, ngc, torch, np)
-    if args.mode == "lookup":
-        return bench_lookup(args, wl, ngc, torch, np)
-    w = wl.CONFIGS[args.workload]
-    if w.loss < 0:
-        return bench_codec(args, w, wl, ngc, torch, np)
-    if args.mode == "workers":
-        return bench_workers(args, w, wl, ngc, torch, np)
-    if w.loss not in (wl.LOSS_LSQ, wl.LOSS_LOGISTIC, wl.LOSS_MLP2):
-        print("bench.py times the gradient workloads (C1, C2, C3, C4)", file=sys.stderr)
-        sys.exit(2)
     is_mlp = w.loss == wl.LOSS_MLP2
-    K, W = args.steps, args.warmup
     # k = c n: the workload's w.n partitions go to nw = w.n / c workers, c to an atomic task; the
     # layers that such a smaller cluster can hold are kept
     c = args.parts_per_worker
-    if c < 1 or w.n % c:
-        print("--parts-per-worker must divide the workload's %d partitions" % w.n, file=sys.stderr)
-        sys.exit(2)
     nw = w.n // c
     layers = tuple(s for s in w.layers if s < nw)
     L = len(layers)
+    parity_parts = w.n if parity_parts is None else min(parity_parts, w.n)
+    keep_parts = max(parity_parts, min(args.cpu_parts, w.n) if cpu_leg and not args.no_cpu_baseline else 0)
 
     # ---- inputs: generated per partition on the host, uploaded once -------------------------
     t0 = time.perf_counter()
@@ -587,7 +630,7 @@ def main():
         for j, (X, Y) in enumerate(ex.map(lambda j: wl.partition(w, j, 0, truth), range(w.n))):
             Xd[j].copy_(torch.from_numpy(X))
             Yd[j].copy_(torch.from_numpy(Y))
-            if j < args.cpu_parts:
+            if j < keep_parts:
                 keep.append((X, Y))
     theta_h = wl.theta(w, 0)
     thd = torch.from_numpy(theta_h).to(dev)
@@ -596,7 +639,7 @@ def main():
     # such a mask is replaced by "no stragglers" so that every timed step does the full work
     masks[masks.sum(axis=1) > layers[-1]] = 0
     torch.cuda.synchronize()
-    log("inputs ready in %.1f s (X %.2f GB in HBM)" % (time.perf_counter() - t0, Xd.numel() * 4 / 1e9))
+    log("%s: inputs ready in %.1f s (X %.2f GB in HBM)" % (w.name, time.perf_counter() - t0, Xd.numel() * 4 / 1e9))
 
     stream = torch.cuda.current_stream().cuda_stream
     ctx = ngc.ngc_create(nw, w.n, layers, w.d, stream)
@@ -609,8 +652,6 @@ def main():
     eta_over_m = 1e-3 / w.m
 
     def step(t):
-        # one iteration: partition gradients, every layer's messages, layer + decode vector for
-        # this round's stragglers, decode, update (two launches for the regression losses)
         return ngc.ngc_iteration(ctx, w.loss, Xd, Yd, thd, w.rows, masks[t], eta_over_m, G, C, g, nw)
 
     def step_separate(t):
@@ -659,7 +700,8 @@ def main():
         flops = w.m * (2.0 * w.d_in * w.hidden * 2 + 2.0 * w.hidden * w.classes * 3)
         achieved = flops / (grad_avg_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": 157.3, "unit": "TFLOP/s",
-                    "frac": round(achieved / 157.3, 4), "traffic": None, "algorithmic_flops": flops,
+                    "frac": round(achieved / 157.3, 4), "traffic": None, "traffic_source": None,
+                    "algorithmic_flops": flops,
                     "kernel": "mlp_gemm_kernel (whole MLP gradient call)", "avg_ms": round(grad_avg_ms, 4),
                     "launches": grad_launches}
     else:
@@ -668,11 +710,11 @@ def main():
         # algorithmic bytes per launch: X once + labels + theta + G  (4*d bytes per sample)
         grad_bytes = 4.0 * w.m * w.d + 4.0 * w.m + 4.0 * w.d + 4.0 * w.n * w.d
         achieved = grad_bytes / (grad_avg_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(w.name),
-                    "algorithmic_bytes": grad_bytes,
-                    "kernel": "grad_stream_kernel", "avg_ms": round(grad_avg_ms, 4),
-                    "launches": grad_launches}
+        roofline = with_traffic(
+            {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+             "frac": round(achieved / HBM_PEAK_GBS, 4), "algorithmic_bytes": grad_bytes,
+             "kernel": "grad_stream_kernel", "avg_ms": round(grad_avg_ms, 4), "launches": grad_launches},
+            "grad_stream_%s.txt" % w.name)
     if per_launch.size:
         # the same launches one by one (HIP events of the timed region): spread of the kernel's time
         roofline["median_ms"] = round(float(np.median(per_launch)), 4)
@@ -690,9 +732,38 @@ def main():
         "fused_tail_ms": round(prof["tail"][1] / max(1, prof["tail"][0]), 4),
     }
 
+    # ---- encode/decode of this workload's code batched: many rounds on this G in one launch ------
+    if c == 1:
+        Rb = int(max(8, min(512, (1 << 30) // (4 * nw * w.d))))          # at most 1 GiB of messages
+        bm = wl.bernoulli_masks(w, Rb, seed=1)
+        bm[bm.sum(axis=1) > layers[-1]] = 0
+        Mb = torch.empty((Rb, nw, w.d), dtype=torch.float32, device=dev)
+        gb = torch.empty((Rb, w.d), dtype=torch.float32, device=dev)
+        ngc.ngc_partition_grads(ctx, w.loss, Xd, Yd, thd, w.rows, G)
+        ngc.ngc_coded_rounds(ctx, G, 0, bm, Mb, nw * w.d, gb)
+        torch.cuda.synchronize()
+        ngc.ngc_profile_enable(ctx, ["rounds"])
+        wall_b = []
+        for _ in range(3):
+            tb = time.perf_counter()
+            lay_b, a_b = ngc.ngc_coded_rounds(ctx, G, 0, bm, Mb, nw * w.d, gb)
+            torch.cuda.synchronize()
+            wall_b.append(time.perf_counter() - tb)
+        wall_b = sorted(wall_b)[1]
+        cnt_b, ms_b = ngc.ngc_profile_read(ctx)["rounds"]
+        ms_b /= max(1, cnt_b)
+        ngc.ngc_profile_enable(ctx, False)
+        rb = float(np.count_nonzero(a_b)) / Rb
+        fb = 4.0 * w.d * (w.n + rb + 1)
+        stages["batched_rounds"] = {"rounds_per_call": Rb, "kernel_us_per_round": round(ms_b / Rb * 1e3, 4),
+                                    "GBps": round(fb * Rb / (ms_b * 1e-3) / 1e9, 1),
+                                    "GBps_with_host_bookkeeping": round(fb * Rb / wall_b / 1e9, 1),
+                                    "bytes_per_round": fb}
+        del Mb, gb
+
     # ---- context figures outside the timed region: what a trivial kernel reaches ---------------
     ceiling = None
-    if not args.no_probe:
+    if probe:
         ngc.ngc_profile_enable(ctx, True)
         for _ in range(3):
             ngc.ngc_probe_read(ctx, Xd, Xd.numel() * 4)
@@ -706,10 +777,10 @@ def main():
         del scratch
         ceiling = {"plain_read_GBps": round(Xd.numel() * 4 * n_read / (ms_read * 1e-3) / 1e9, 1),
                    "plain_copy_GBps_read_plus_write": round(2 * nb * n_copy / (ms_copy * 1e-3) / 1e9, 1)}
-
     if ceiling and roofline.get("bound") == "hbm":
         # the same rate against what a plain read of the same buffer reaches on this machine
         roofline["frac_of_plain_read"] = round(roofline["achieved"] / ceiling["plain_read_GBps"], 4)
+
     out = {
         "metric": metric_name(nw, w.d),
         "value": round(w.m * K / elapsed, 1), "unit": "samples/s", "n_gpus": 1, "steps": K,
@@ -721,14 +792,126 @@ def main():
                    "p_straggle": w.p_straggle},
         "roofline": roofline, "stages": stages, "hbm_probe": ceiling,
     }
-    if not args.no_cpu_baseline:
-        ngc.ngc_sync(ctx)
-        cb = cpu_baseline(w, wl, keep, theta_h, masks, min(args.cpu_parts, w.n), nw, layers)
+
+    # ---- parity of exactly this configuration against the oracle, after the timed region -------
+    # the library-built code goes to the oracle; theta is reset to the start point; the oracle's
+    # partial gradients come from the host copies of the same partitions
+    ngc.ngc_sync(ctx)
+    from oracle import coding, gradients
+    Bs = oracle_code(ngc, ctx, L)
+    thd.copy_(torch.from_numpy(theta_h))
+    ngc.ngc_partition_grads(ctx, w.loss, Xd, Yd, thd, w.rows, G)
+    ngc.ngc_encode(ctx, G, -1, C)
+    ngc.ngc_sync(ctx)
+    t_or = time.perf_counter()
+    G_o = np.stack([gradients.partial_gradients(w.loss, X[None], Y[None], theta_h, w.hidden, w.classes)[0]
+                    for X, Y in keep[:parity_parts]])
+    t_or = time.perf_counter() - t_or
+    Gh = G.cpu().numpy()
+    parity = {"code": "ngc_build_code(seed 0), read back with ngc_get_code and handed to the oracle",
+              "def1_residual_max": def1_residual(np, Bs, layers),
+              "G_partitions_checked": parity_parts,
+              "G_rel_l2_max": max(rel_l2(np, Gh[j], G_o[j]) for j in range(parity_parts))}
+    if parity_parts == w.n:
+        C_o = coding.encode_layers(Bs, G_o)
+        parity["C_rel_l2"] = rel_l2(np, C.cpu().numpy(), C_o)
+        Rp = min(K, 16)
+        pm = masks[W:W + Rp]
+        lay_p = np.zeros(Rp, np.int32)
+        a_p = np.zeros((Rp, nw))
+        g_p, M_p = [], []
+        for r in range(Rp):
+            lay_p[r], a_p[r], _ = ngc.ngc_select_decode_vec(ctx, pm[r], nw)
+            ngc.ngc_decode(ctx, int(lay_p[r]), a_p[r], C, g)
+            ngc.ngc_sync(ctx)
+            g_p.append(g.cpu().numpy())
+            M_p.append(C[int(lay_p[r])].cpu().numpy())
+        parity.update(codec_parity(np, Bs, layers, G_o, pm, lay_p, a_p, lambda r: M_p[r], lambda r: g_p[r]))
+    out["parity"] = parity
+
+    if cpu_leg and not args.no_cpu_baseline:
+        cb = cpu_baseline(w, wl, keep, theta_h, masks, min(args.cpu_parts, w.n), Bs, layers)
         # the same algorithmic bytes (fp32 sizes) per sample as the GPU figure, and the ratio
         cb["GBps"] = round(cb["value"] * 4.0 * w.d_in / 1e9, 2) if w.loss != wl.LOSS_MLP2 else None
         cb["gpu_over_oracle"] = round(out["value"] / cb["value"], 1) if cb["value"] else None
         out["cpu_baseline"] = cb
     ngc.ngc_destroy(ctx)
+    del Xd, Yd, G, C, g, keep
+    torch.cuda.empty_cache()
+    return out
+
+
+def compact(line):
+    """What the other workloads contribute to the headline line."""
+    keep = ("value", "unit", "steps", "ms_per_step", "dtype", "config", "roofline", "parity")
+    out = {k: line[k] for k in keep if k in line}
+    st = line.get("stages", {})
+    out["stages"] = {k: st[k] for k in ("batched_GBps", "batched_GBps_new_G_every_round", "kernel_us_per_round",
+                                        "encode_GBps", "decode_GBps", "fused_one_round_ms", "grad_samples_per_s",
+                                        "fused_tail_ms", "batched_rounds") if k in st}
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=None, help="C1..C5; default: C3 (the headline) followed by short "
+                                                     "legs of C2, C4 and C5 under other_workloads")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-probe", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="headline workload only")
+    ap.add_argument("--mode", default="pipeline", choices=["pipeline", "workers", "latency", "lookup"])
+    ap.add_argument("--cpu-parts", type=int, default=32)
+    ap.add_argument("--parts-per-worker", type=int, default=1,
+                    help="k = c n (Sec. II-C): the workload's partitions are shared out c to a worker")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: nested gradient coding here simulates all n workers on "
+              "a single MI355X; --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2212_08580_amd import ngc, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    # With torch imported a full pass of the interpreter's cycle collector takes tens of
+    # milliseconds, as long as a thousand encode/decode rounds; the objects alive now are set
+    # aside so that a pass triggered inside a timed region only looks at what the loop made.
+    gc.collect()
+    gc.freeze()
+    if args.mode == "latency":
+        return bench_latency(args, ngc, torch, np)
+    if args.mode == "lookup":
+        return bench_lookup(args, wl, ngc, torch, np)
+    headline_only = args.workload is not None or args.no_others or args.parts_per_worker != 1 or args.mode != "pipeline"
+    w = wl.CONFIGS[args.workload or "C3"]
+    if args.mode == "workers":
+        if w.loss < 0:
+            print("--mode workers needs a gradient workload (C1..C4)", file=sys.stderr)
+            sys.exit(2)
+        return bench_workers(args, w, wl, ngc, torch, np)
+    if w.loss < 0:
+        print(json.dumps(bench_codec(args, w, wl, ngc, torch, np)), flush=True)
+        return
+    if args.parts_per_worker < 1 or w.n % args.parts_per_worker:
+        print("--parts-per-worker must divide the workload's %d partitions" % w.n, file=sys.stderr)
+        sys.exit(2)
+    out = bench_pipeline(args, w, wl, ngc, torch, np, args.steps, args.warmup, probe=not args.no_probe)
+    if not headline_only:
+        # the other workloads of the benchmark definition, short legs, same code path
+        others = {}
+        others["C2"] = compact(bench_pipeline(args, wl.C2, wl, ngc, torch, np, 100, 5, cpu_leg=False, probe=False))
+        others["C4"] = compact(bench_pipeline(args, wl.C4, wl, ngc, torch, np, 10, 2, cpu_leg=False, probe=False,
+                                              parity_parts=2))
+        others["C5"] = compact(bench_codec(args, wl.C5, wl, ngc, torch, np, rounds=1000, cpu_leg=False))
+        out["other_workloads"] = others
     print(json.dumps(out), flush=True)
 
 

@@ -22,13 +22,11 @@
 
 #include "ngc_dev_common.h"
 
-typedef unsigned long long u64;
-
 // ---------------------------------------------------------------------------
 // Code tables on the device.  Layout of d_code:
 //   int   rowptr[L*n + 1] | int col[nnz] | float coef[nnz]      compressed rows, all layers
-//   u64   gmask[L*ng]                (64-byte aligned)  bit j: column j is in the support of
-//                                                       one of the workers 4g..4g+3
+//   u32   gmask[L*ng]                (64-byte aligned)  bit t: one of the columns 4t..4t+3 is in the
+//                                                       support of one of the workers 4g..4g+3
 //   float gcoef[L*ng][kp][4]         (64-byte aligned)  gcoef[(u*ng+g)*kp + j][r] = B^(u)[4g+r][j]
 // ng = ceil(n/4) groups of four workers, kp = k rounded up to a multiple of 4; rows and
 // columns that do not exist hold zeros.
@@ -37,7 +35,7 @@ struct code_view {
     const int* rowptr;
     const int* col;
     const float* coef;
-    const u64* gmask;
+    const unsigned* gmask;
     const float* gcoef;
     int nnz, ng, kp;
 };
@@ -54,13 +52,13 @@ static int upload_code(ngc_ctx* ctx) {
     const size_t np = (size_t)L * n;
     const int ng = (n + 3) / 4, kp = (k + 3) / 4 * 4;
     const size_t gmask_off = round_up((np + 1 + 2 * nnz) * sizeof(int), 64);
-    const size_t gcoef_off = round_up(gmask_off + (size_t)L * ng * sizeof(u64), 64);
+    const size_t gcoef_off = round_up(gmask_off + (size_t)L * ng * sizeof(unsigned), 64);
     const size_t bytes = gcoef_off + (size_t)L * ng * kp * 4 * sizeof(float);
     std::vector<unsigned char> host(bytes, 0);
     int* rowptr = reinterpret_cast<int*>(host.data());
     int* col = rowptr + np + 1;
     float* coef = reinterpret_cast<float*>(col + nnz);
-    u64* gmask = reinterpret_cast<u64*>(host.data() + gmask_off);
+    unsigned* gmask = reinterpret_cast<unsigned*>(host.data() + gmask_off);
     float* gcoef = reinterpret_cast<float*>(host.data() + gcoef_off);
     size_t at = 0;
     for (int u = 0; u < L; ++u) {
@@ -71,7 +69,7 @@ static int upload_code(ngc_ctx* ctx) {
             for (int t = lc.rowptr[i]; t < lc.rowptr[i + 1]; ++t) {
                 col[at] = lc.col[t];
                 coef[at] = (float)lc.coef[t];
-                gmask[(size_t)u * ng + g] |= (u64)1 << lc.col[t];
+                gmask[(size_t)u * ng + g] |= 1u << (lc.col[t] / 4);
                 gcoef[(((size_t)u * ng + g) * kp + lc.col[t]) * 4 + r] = (float)lc.coef[t];
                 ++at;
             }
@@ -106,7 +104,7 @@ static code_view view_code(const ngc_ctx* ctx) {
     v.rowptr = (const int*)base;
     v.col = v.rowptr + np + 1;
     v.coef = (const float*)(v.col + ctx->code_nnz);
-    v.gmask = (const u64*)(base + ctx->code_gmask_off);
+    v.gmask = (const unsigned*)(base + ctx->code_gmask_off);
     v.gcoef = (const float*)(base + ctx->code_gcoef_off);
     v.nnz = (int)ctx->code_nnz;
     v.ng = ctx->code_ng;
@@ -140,26 +138,49 @@ __device__ __forceinline__ void stage_tile(VT* tile, const float* __restrict__ G
 
 // Messages of the four workers of one group under one layer for this lane's columns:
 //   m[r] = sum_j cf[j][r] * tile[j]   in ascending j, one fused multiply-add per term.
-// cf and umask are wave-uniform (scalar loads); four columns of B are taken per trip and a
-// trip whose columns lie outside the group's supports is skipped.
+// cf and cmask are wave-uniform (scalar loads); four columns of B are taken per trip, bit t of
+// cmask says whether columns 4t..4t+3 touch the group's supports at all (a trip that does not
+// is skipped).  The coefficients and tile rows of the next trip are requested before the
+// multiply-adds of the current one are issued.
+template <typename VT>
+__device__ __forceinline__ void load_trip(const VT* tile, int lane, const float* __restrict__ cf, int jc,
+                                          float (&w)[16], VT (&x)[4]) {
+#pragma unroll
+    for (int t = 0; t < 16; ++t) w[t] = cf[jc * 16 + t];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) x[t] = tile[(4 * jc + t) * 64 + lane];
+}
+
+template <typename VT>
+__device__ __forceinline__ void fma_trip(const float (&w)[16], const VT (&x)[4], VT (&m)[4]) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) m[r] = ngc_fma(w[t * 4 + r], x[t], m[r]);
+}
+
 template <typename VT>
 __device__ __forceinline__ void group_messages(const VT* tile, int lane, const float* __restrict__ cf,
-                                               u64 umask, int kp, VT (&m)[4]) {
+                                               unsigned cmask, VT (&m)[4]) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) m[r] = (VT)(0.0f);
-    for (int jc = 0; jc < kp / 4; ++jc) {
-        if (((umask >> (4 * jc)) & 0xFull) == 0) continue;
-        float w[16];
+    if (cmask == 0) return;
+    float w[16];
+    VT x[4];
+    load_trip<VT>(tile, lane, cf, __builtin_ctz(cmask), w, x);
+    cmask &= cmask - 1;
+    while (cmask != 0) {
+        float wn[16];
+        VT xn[4];
+        load_trip<VT>(tile, lane, cf, __builtin_ctz(cmask), wn, xn);
+        cmask &= cmask - 1;
+        fma_trip<VT>(w, x, m);
 #pragma unroll
-        for (int t = 0; t < 16; ++t) w[t] = cf[jc * 16 + t];
-        VT x[4];
+        for (int t = 0; t < 16; ++t) w[t] = wn[t];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) x[t] = tile[(4 * jc + t) * 64 + lane];
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) m[r] = ngc_fma(w[t * 4 + r], x[t], m[r]);
+        for (int t = 0; t < 4; ++t) x[t] = xn[t];
     }
+    fma_trip<VT>(w, x, m);
 }
 
 // ---------------------------------------------------------------------------
@@ -173,7 +194,7 @@ constexpr int ENC_WAVES = 8;
 template <typename VT, int V>
 __global__ __launch_bounds__(ENC_WAVES * 64) void encode_kernel(const float* __restrict__ G,
                                                                 float* __restrict__ C,
-                                                                const u64* __restrict__ gmask,
+                                                                const unsigned* __restrict__ gmask,
                                                                 const float* __restrict__ gcoef, int n, int k,
                                                                 int kp, int ng, int64_t d, int layer_begin,
                                                                 int layer_count) {
@@ -192,7 +213,7 @@ __global__ __launch_bounds__(ENC_WAVES * 64) void encode_kernel(const float* __r
         const int g = t / layer_count;
         const int ug = u * ng + g;
         VT m[4];
-        group_messages<VT>(tile, lane, gcoef + (size_t)ug * kp * 4, gmask[ug], kp, m);
+        group_messages<VT>(tile, lane, gcoef + (size_t)ug * kp * 4, gmask[ug], m);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int i = 4 * g + r;
@@ -356,7 +377,7 @@ template <typename VT, int V, bool SINGLE>
 __global__ __launch_bounds__(256) void coded_rounds_kernel(
     const float* __restrict__ G, int64_t g_stride, float* __restrict__ M, int64_t m_stride,
     float* __restrict__ ghat, const round_rec* __restrict__ recs, round_rec one,
-    const u64* __restrict__ gmask, const float* __restrict__ gcoef, int n, int k, int kp, int ng,
+    const unsigned* __restrict__ gmask, const float* __restrict__ gcoef, int n, int k, int kp, int ng,
     int64_t d, int ntiles, int rounds, int rounds_per_block) {
     extern __shared__ double lds_raw64[];
     double* xch = lds_raw64;                                   // [2][4][64*V]
@@ -389,7 +410,7 @@ __global__ __launch_bounds__(256) void coded_rounds_kernel(
             for (int g = wave; g < ng; g += 4) {
                 const int ug = layer * ng + g;
                 VT m[4];
-                group_messages<VT>(tile, lane, gcoef + (size_t)ug * kp * 4, gmask[ug], kp, m);
+                group_messages<VT>(tile, lane, gcoef + (size_t)ug * kp * 4, gmask[ug], m);
 #pragma unroll
                 for (int rr = 0; rr < 4; ++rr) {
                     const int i = 4 * g + rr;  // < NGC_MAX_N; a is zero beyond n
