@@ -837,6 +837,7 @@ def bench_pipeline(args, w, wl, ngc, torch, np, K, W, cpu_leg=True, probe=True, 
         out["cpu_baseline"] = cb
     ngc.ngc_destroy(ctx)
     del Xd, Yd, G, C, g, keep
+    gc.collect()
     torch.cuda.empty_cache()
     return out
 
@@ -881,11 +882,12 @@ def main():
         sys.exit(2)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    # With torch imported a full pass of the interpreter's cycle collector takes tens of
-    # milliseconds, as long as a thousand encode/decode rounds; the objects alive now are set
-    # aside so that a pass triggered inside a timed region only looks at what the loop made.
+    # With torch imported a pass of the interpreter's cycle collector takes milliseconds, as long
+    # as a thousand encode/decode rounds; the objects alive now are set aside and the collector
+    # is run between the legs instead of whenever an allocation count trips it inside a timed region.
     gc.collect()
     gc.freeze()
+    gc.disable()
     if args.mode == "latency":
         return bench_latency(args, ngc, torch, np)
     if args.mode == "lookup":

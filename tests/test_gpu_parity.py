@@ -1,12 +1,25 @@
 """Parity of the HIP path (through the C ABI) against the fp64 oracle.
 
 Bars: rel-L2 <= 1e-4 for floating point; layer, straggler handling and the
-support of the decode vector exact.  Where decoding is ill-conditioned
-(kappa = sum |a_i| ||c_i|| / ||g|| large, C5-like cases) the error must in
-addition stay inside the forward-error bound 4 * 2^-24 * kappa, and the share of
-rounds above 1e-4 is reported.
+support of the decode vector exact.  The decode kernel itself is held to 2e-7
+against the fp64 combination of the messages it read.  Against the exact sum of
+the partial gradients a decoded round may exceed 1e-4 only where the code itself
+magnifies the fp32 rounding of the messages (kappa = sum |a_i| ||c_i|| / ||g||
+large: a straggler count equal to the layer's tolerance leaves one decode vector
+and no choice): such a round must stay inside the forward-error bound
+4 * 2^-24 * kappa, the tests of the headline code (n = 32) assert plain 1e-4 on
+every round of its own straggler distribution, the n = 64 stress test asserts
+the share of rounds above 1e-4, and every figure goes to
+gpurun_out/parity_report.jsonl.
+
+Codes: by default the one the library builds (ngc_build_code, the configuration
+the benchmark times), read back through ngc_get_code and handed to the oracle,
+which first checks Def. 1 on sampled straggler sets; where a test names `kind`
+with oracle=True the oracle's own constructor supplies B through ngc_set_code.
 """
 import dataclasses
+import json
+import os
 
 import numpy as np
 import pytest
@@ -34,20 +47,55 @@ def rel(x, ref):
     return float(np.linalg.norm(x - ref) / max(np.linalg.norm(ref), 1e-300))
 
 
-class Pipeline:
-    """Device buffers + context for one workload; B comes from the oracle's constructor."""
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
-    def __init__(self, ngc, torch, w, Bs=None, kind=None, seed=0):
+
+def report(**kw):
+    """One line per parity figure, kept beside the test log."""
+    try:
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "parity_report.jsonl"), "a") as f:
+            f.write(json.dumps(kw) + "\n")
+    except OSError:
+        pass
+
+
+def def1_holds_on_samples(Bs, layers, seed=0, sets=6):
+    """Def. 1 in the oracle for a code that did not come from it: sampled straggler sets of the
+    design size of every layer decode with residual <= 1e-9, supports nested, B_0 = I."""
+    rng = np.random.default_rng(seed)
+    n = Bs[0].shape[0]
+    assert np.array_equal(Bs[0], np.eye(n))
+    for u, sigma in enumerate(layers):
+        if u:
+            assert np.all((Bs[u - 1] != 0) <= (Bs[u] != 0))                   # Def. 2
+        assert np.all(np.count_nonzero(Bs[u], axis=1) == sigma + 1)          # load (k/n)(sigma+1)
+        for _ in range(sets):
+            m = np.zeros(n, np.uint8)
+            m[rng.choice(n, size=sigma, replace=False)] = 1
+            assert coding.decode_vector(Bs[u], m)[1] <= 1e-9
+
+
+class Pipeline:
+    """Device buffers + context for one workload.  The code is the library's own
+    (ngc_build_code, seed 0) unless matrices or oracle=True are given."""
+
+    def __init__(self, ngc, torch, w, Bs=None, kind=None, seed=0, oracle=False):
         self.ngc, self.torch, self.w = ngc, torch, w
         self.dev = torch.device("cuda:0")
         stream = torch.cuda.current_stream().cuda_stream
         self.ctx = ngc.ngc_create(w.n, w.n, w.layers, w.d, stream)
-        if Bs is None:
-            kind = kind or ("cyclic" if w.code == wl.CODE_CYCLIC else "fracrep")
-            Bs = codes.nested_code(w.n, w.layers, kind, seed=seed, draws=2)
+        kind = kind or ("cyclic" if w.code == wl.CODE_CYCLIC else "fracrep")
+        if Bs is None and not oracle:
+            ngc.ngc_build_code(self.ctx, ngc.NGC_CODE_CYCLIC if kind == "cyclic" else ngc.NGC_CODE_FRACREP, seed)
+            Bs = [ngc.ngc_get_code(self.ctx, u) for u in range(len(w.layers))]
+            def1_holds_on_samples(Bs, w.layers)
+        else:
+            if Bs is None:
+                Bs = codes.nested_code(w.n, w.layers, kind, seed=seed, draws=2)
+            for u, B in enumerate(Bs):
+                ngc.ngc_set_code(self.ctx, u, B)
         self.Bs = Bs
-        for u, B in enumerate(Bs):
-            ngc.ngc_set_code(self.ctx, u, B)
         self.G = torch.empty((w.n, w.d), dtype=torch.float32, device=self.dev)
         self.C = torch.empty((len(w.layers), w.n, w.d), dtype=torch.float32, device=self.dev)
         self.g = torch.empty(w.d, dtype=torch.float32, device=self.dev)
@@ -76,8 +124,10 @@ class Pipeline:
         return u, a, r, self.g.cpu().numpy()
 
 
-def check_round(p, G_o, mask, C_gpu, strict=True):
-    """One mask: layer/support exact, decoded gradient vs oracle."""
+def check_round(p, G_o, mask, C_gpu, plain=False):
+    """One mask: layer/support exact, decode kernel against the fp64 combination of its own
+    input, decoded gradient against the oracle: within max(1e-4, 4 * 2^-24 * kappa), with
+    `plain` within 1e-4 whatever kappa is."""
     w = p.w
     u_o, a_o, g_o = coding.coded_gradient(p.Bs, w.layers, G_o, mask)
     u, a, r, g = p.decode(mask)
@@ -89,7 +139,7 @@ def check_round(p, G_o, mask, C_gpu, strict=True):
     assert rel(g, g_same) <= 2e-7
     err = rel(g, g_o)
     kappa = coding.conditioning(a_o, coding.encode(p.Bs[u_o], G_o), g_o)
-    assert err <= max(TOL if strict else 0.0, 4 * 2.0 ** -24 * kappa), (err, kappa)
+    assert err <= (TOL if plain else max(TOL, 4 * 2.0 ** -24 * kappa)), (err, kappa)
     return err, kappa
 
 
@@ -186,16 +236,19 @@ def test_logistic_saturated_margins(ngc, torch_dev):
 # --------------------------------------------------------------------------------------------
 # encode / decode on their own (no data): vector widths 4, 2, 1, column tails, both families
 # --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("from_oracle", [False, True])
 @pytest.mark.parametrize("n,layers,kind,d", [
     (4, (0, 1), "fracrep", 64), (16, (0, 1, 3, 7), "cyclic", 1024), (32, (0, 1, 3, 7, 15), "cyclic", 4096),
     (64, (0, 1, 3, 7, 15, 31), "cyclic", 16384), (64, (0, 1, 3, 7, 15, 31), "fracrep", 4096),
     (20, (0, 1, 4, 9), "cyclic", 1002), (20, (0, 1, 4, 9), "cyclic", 999), (7, (0, 2, 5), "cyclic", 100),
     (1, (0,), "cyclic", 5), (33, (0, 32), "cyclic", 68),
 ])
-def test_encode_and_decode_match_oracle(ngc, torch_dev, n, layers, kind, d):
+def test_encode_and_decode_match_oracle(ngc, torch_dev, n, layers, kind, d, from_oracle):
+    """Both directions: the library's code handed to the oracle, and the oracle's constructor's
+    code installed in the library."""
     w = wl.C5.scaled(n=n, d=d, layers=layers)
     G_h = wl.partial_gradients(w, seed=n + d)
-    p = Pipeline(ngc, torch_dev, w, kind=kind)
+    p = Pipeline(ngc, torch_dev, w, kind=kind, oracle=from_oracle)
     try:
         p.G.copy_(torch_dev.from_numpy(G_h))
         C = p.encode()
@@ -217,9 +270,9 @@ def test_encode_and_decode_match_oracle(ngc, torch_dev, n, layers, kind, d):
             s = int(rng.integers(0, layers[-1] + 1))
             m = np.zeros(n, np.uint8)
             m[rng.choice(n, size=s, replace=False)] = 1
-            err, kappa = check_round(p, G_h.astype(np.float64), m, C, strict=(n <= 32))
+            err, kappa = check_round(p, G_h.astype(np.float64), m, C)
             worst = max(worst, err)
-        print("n=%d d=%d %s worst decode rel-L2 %.2e" % (n, d, kind, worst))
+        report(test="encode_and_decode", n=n, d=d, kind=kind, worst_decode_rel_l2=worst)
     finally:
         p.close()
 
@@ -357,10 +410,11 @@ def test_c3_scaled_pipeline(ngc, torch_dev):
             assert rel(G[j], G_o[j]) <= TOL
         C = p.encode()
         assert rel(C, coding.encode_layers(p.Bs, G_o)) <= TOL
-        masks = wl.bernoulli_masks(w, 40, seed=1)
-        errs = [check_round(p, G_o, m, C)[0] for m in masks if m.sum() <= w.layers[-1]]
-        assert len(errs) >= 38
-        print("C3-scaled: worst decode rel-L2 %.2e over %d masks" % (max(errs), len(errs)))
+        masks = wl.bernoulli_masks(w, 200, seed=1)
+        errs = [check_round(p, G_o, m, C, plain=True)[0] for m in masks if m.sum() <= w.layers[-1]]
+        assert len(errs) >= 195
+        report(test="c3_scaled_pipeline", rounds=len(errs), worst_decode_rel_l2=max(errs),
+               median_decode_rel_l2=float(np.median(errs)))
     finally:
         p.close()
 
@@ -385,11 +439,14 @@ def test_c5_rounds(ngc, torch_dev):
                 with pytest.raises(ngc.NgcError):
                     ngc.ngc_select_decode_vec(p.ctx, m, w.n)
                 continue
-            errs.append(check_round(p, G64, m, C, strict=False)[0])
+            errs.append(check_round(p, G64, m, C)[0])
         errs = np.array(errs)
-        print("C5: %d rounds, median rel-L2 %.2e, worst %.2e, share above 1e-4: %.3f" %
-              (errs.size, np.median(errs), errs.max(), float(np.mean(errs > TOL))))
-        assert np.mean(errs > TOL) <= 0.05
+        report(test="c5_rounds", rounds=int(errs.size), median_decode_rel_l2=float(np.median(errs)),
+               worst_decode_rel_l2=float(errs.max()), share_above_1e_4=float(np.mean(errs > TOL)))
+        # a straggler count equal to a layer's tolerance leaves one decode vector; for a random
+        # real-valued code of this size a few per thousand of such sets magnify fp32 message
+        # rounding beyond 1e-4 (each of them inside the forward-error bound, checked above)
+        assert np.mean(errs > TOL) <= 0.01
     finally:
         p.close()
 
@@ -429,14 +486,16 @@ def test_c3_full_size_every_partition(ngc, torch_dev):
         C_o = coding.encode_layers(p.Bs, G_o)
         assert rel(C, C_o) <= TOL
         full = G_o.sum(axis=0)
-        masks = wl.bernoulli_masks(w, 20, seed=2)
+        masks = wl.bernoulli_masks(w, 60, seed=2)
+        worst = 0.0
         for m in masks:
             if m.sum() <= w.layers[-1]:
                 u, a, r, g = p.decode(m)
                 u_o, a_o, g_o = coding.coded_gradient(p.Bs, w.layers, G_o, m)
                 assert u == u_o and np.array_equal(a != 0, a_o != 0)
-                kappa = coding.conditioning(a_o, C_o[u_o], full)
-                assert rel(g, full) <= max(TOL, 4 * 2.0 ** -24 * kappa)
+                worst = max(worst, rel(g, full))
+                assert rel(g, full) <= TOL
+        report(test="c3_full_size", rounds=len(masks), worst_decode_rel_l2=worst)
     finally:
         p.close()
 

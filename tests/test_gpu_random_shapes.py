@@ -49,7 +49,7 @@ def test_random_configurations(ngc, torch_dev, seed):
             for _ in range(3):
                 m = np.zeros(w.n, np.uint8)
                 m[rng.choice(w.n, size=int(rng.integers(0, w.layers[-1] + 1)), replace=False)] = 1
-                check_round(p, G_o, m, C, strict=False)
+                check_round(p, G_o, m, C)
             # the fused iteration gives the bits of the stand-alone calls
             m = np.zeros(w.n, np.uint8)
             m[int(rng.integers(0, w.n))] = 1
