@@ -225,6 +225,104 @@ __global__ __launch_bounds__(WAVES * 64) void grad_stream_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// Single-pass partition gradient for narrow rows: d = 4*DQ with DQ = 1, 2, 4, .. 32 float4 per
+// row (4 to 128 features).  Rows are contiguous in memory, so one wave-wide 16-byte load
+// (1 KiB) fetches RPL = 64/DQ whole rows: lane l holds float4 number l % DQ of row l / DQ.
+// The dot product of a row is a sum over its DQ lanes (DPP steps inside a row of 16 lanes, one
+// cross-lane exchange for 32), after which every lane of the segment knows its row's slope and
+// adds slope * x into its own accumulator; the accumulators of the RPL segments are added once,
+// at the end, through LDS in segment order.  R loads form a group, the next group is in
+// flight while one is consumed; rows past the end re-read the last row with weight 0.  One
+// wave per block.
+// ---------------------------------------------------------------------------
+template <int DQ>
+__device__ __forceinline__ float segment_sum(float v) {
+    if (DQ >= 2) v = dpp_step<0xB1>(v);   // quad_perm [1,0,3,2]
+    if (DQ >= 4) v = dpp_step<0x4E>(v);   // quad_perm [2,3,0,1]
+    if (DQ >= 8) v = dpp_step<0x141>(v);  // row_half_mirror
+    if (DQ >= 16) v = dpp_step<0x140>(v); // row_mirror
+    if (DQ >= 32) v += __shfl_xor(v, 16);
+    return v;
+}
+
+template <int R>
+struct narrow_group {
+    v4f x[R];
+    float y[R];
+};
+
+template <int DQ, int R>
+__device__ __forceinline__ void load_narrow(narrow_group<R>& b, const v4f* __restrict__ xp,
+                                            const float* __restrict__ yp, int seg, int slot,
+                                            int64_t row, int64_t last_row) {
+    constexpr int RPL = 64 / DQ;
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+        int64_t r = row + u * RPL + seg;
+        r = r < last_row ? r : last_row;
+        b.x[u] = __builtin_nontemporal_load(xp + r * DQ + slot);
+        b.y[u] = yp[r];
+    }
+}
+
+template <int DQ, int R, int LOSS>
+__device__ __forceinline__ void consume_narrow(const narrow_group<R>& b, v4f& acc, const v4f th, int seg,
+                                               int64_t row, int64_t end_row) {
+    constexpr int RPL = 64 / DQ;
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+        const float z = segment_sum<DQ>(hsum(b.x[u] * th));
+        const float live = (row + u * RPL + seg < end_row) ? 1.0f : 0.0f;
+        const float res = loss_slope<LOSS>(z, b.y[u]) * live;
+        acc += res * b.x[u];
+    }
+}
+
+template <int DQ, int R, int LOSS>
+__global__ __launch_bounds__(64) void grad_narrow_kernel(const float* __restrict__ X, const float* __restrict__ y,
+                                                         const float* __restrict__ theta,
+                                                         float* __restrict__ partial, int64_t rows, int chunks,
+                                                         int64_t rows_per_chunk,
+                                                         const int* __restrict__ unit_part) {
+    constexpr int RPL = 64 / DQ;
+    __shared__ v4f red[64];
+    const int lane = threadIdx.x;
+    const int seg = lane / DQ, slot = lane % DQ;
+    const int unit = blockIdx.x / chunks;
+    const int j = unit_part ? unit_part[unit] : unit;
+    const int c = blockIdx.x % chunks;
+    const int64_t r0 = (int64_t)c * rows_per_chunk;
+    const int64_t r1 = rows < r0 + rows_per_chunk ? rows : r0 + rows_per_chunk;
+    const v4f* xp = reinterpret_cast<const v4f*>(X) + (int64_t)j * rows * DQ;
+    const float* yp = y + (int64_t)j * rows;
+    const v4f th = reinterpret_cast<const v4f*>(theta)[slot];
+    v4f acc = (v4f)(0.0f);
+    constexpr int GROUP = R * RPL;  // rows per group
+    const int64_t ngroups = r0 < r1 ? (r1 - r0 + GROUP - 1) / GROUP : 0;
+    if (ngroups > 0) {
+        const int64_t last = r1 - 1;
+        narrow_group<R> buf[2];
+        load_narrow<DQ, R>(buf[0], xp, yp, seg, slot, r0, last);
+        for (int64_t gb = 0; gb < ngroups; gb += 2) {
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const int64_t gi = gb + p;
+                load_narrow<DQ, R>(buf[(p + 1) % 2], xp, yp, seg, slot, r0 + (gi + 1) * GROUP, last);
+                consume_narrow<DQ, R, LOSS>(buf[p], acc, th, seg, r0 + gi * GROUP, r1);
+            }
+        }
+    }
+    red[lane] = acc;
+    __syncthreads();
+    if (lane < DQ) {
+        v4f s = red[lane];
+#pragma unroll
+        for (int g = 1; g < RPL; ++g) s += red[g * DQ + lane];
+        reinterpret_cast<v4f*>(partial)[(int64_t)blockIdx.x * DQ + lane] = s;
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Generic two-pass route for any d.  Pass 1: one wave per row forms the margin
 // and stores the residual.  Pass 2: one thread per column adds r*x over a run
 // of rows; partials are summed by K2.
@@ -489,8 +587,10 @@ static void launch_stream(ngc_ctx* ctx, int loss, const float* X, const float* y
 struct stream_shape {
     int nv, r, waves;
     bool ragged, scalar;
+    int narrow_dq = 0;  // > 0: rows of narrow_dq float4 take grad_narrow_kernel (several rows per load)
 };
 static stream_shape pick_stream_shape(int64_t d) {
+    if (d % 4 == 0 && d <= 128 && ((d / 4) & (d / 4 - 1)) == 0) return {1, 8, 1, false, false, (int)(d / 4)};
     if (d % 1024 == 0) {
         const int w = (int)(d / 1024);
         // narrow rows: one float4 per lane and many waves per block rather than one wave with
@@ -574,7 +674,8 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
         const int64_t block_slots = (int64_t)ctx->cu_count * per_cu;
         int64_t chunks = std::max<int64_t>(1, block_slots / k);
         int64_t rpc = (rows + chunks - 1) / chunks;
-        const int64_t quantum = 2 * sh.r;  // two row groups: one trip of the kernel's loop
+        // two row groups: one trip of the kernel's loop (a narrow-row group is r loads of 64/dq rows)
+        const int64_t quantum = sh.narrow_dq ? 2 * sh.r * (64 / sh.narrow_dq) : 2 * sh.r;
         rpc = ((rpc + quantum - 1) / quantum) * quantum;
         chunks = (rows + rpc - 1) / rpc;
         rc = get_ws(sizeof(float) * (size_t)k * chunks * d);
@@ -586,7 +687,23 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
     case W: launch_stream<NV, R, 2, W, RG>(NGC_STREAM_ARGS); break;
 #define NGC_STREAM_SCALAR(NV, R, W) \
     case W: launch_stream<NV, R, 2, W, true, float>(NGC_STREAM_ARGS); break;
-            if (sh.scalar) {
+            if (sh.narrow_dq) {
+                dim3 grid((unsigned)(k * chunks));
+#define NGC_NARROW_CASE(DQ)                                                                                          \
+    case DQ:                                                                                                         \
+        if (loss == NGC_LOSS_LSQ)                                                                                    \
+            hipLaunchKernelGGL((grad_narrow_kernel<DQ, 8, NGC_LOSS_LSQ>), grid, dim3(64), 0, ctx->stream, X_dev, y,  \
+                               theta_dev, ws, rows, (int)chunks, rpc, unit_part);                                    \
+        else                                                                                                         \
+            hipLaunchKernelGGL((grad_narrow_kernel<DQ, 8, NGC_LOSS_LOGISTIC>), grid, dim3(64), 0, ctx->stream, X_dev, \
+                               y, theta_dev, ws, rows, (int)chunks, rpc, unit_part);                                 \
+        break;
+                switch (sh.narrow_dq) {
+                    NGC_NARROW_CASE(1) NGC_NARROW_CASE(2) NGC_NARROW_CASE(4) NGC_NARROW_CASE(8)
+                    NGC_NARROW_CASE(16) NGC_NARROW_CASE(32)
+                }
+#undef NGC_NARROW_CASE
+            } else if (sh.scalar) {
                 if (sh.nv == 4) {
                     launch_stream<4, 16, 2, 1, true, float>(NGC_STREAM_ARGS);
                 } else if (sh.nv == 8) {

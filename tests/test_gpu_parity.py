@@ -193,6 +193,10 @@ GRAD_SHAPES = [
     (3000, 2, 11), (7000, 2, 6), (13000, 2, 4), (54, 3, 100), (1002, 3, 40), (2050, 2, 17),
     (4094, 2, 9), (5002, 2, 7), (8190, 2, 5), (8194, 2, 3), (20000, 2, 3), (16388, 2, 2),
     (1, 3, 40), (2, 2, 17), (5, 2, 33), (4, 2, 64), (16384, 1, 40),
+    # narrow rows of 1, 2, 4, .. 32 float4 (several rows per wave-wide load), with and without a
+    # ragged last group, and enough rows for several groups per block
+    (8, 3, 1000), (16, 2, 33), (32, 2, 50), (128, 3, 77), (64, 2, 5000), (128, 2, 3001), (4, 1, 70000),
+    (64, 64, 3),
 ]
 
 
