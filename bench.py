@@ -219,40 +219,54 @@ def bench_codec(args, w, wl, ngc, torch, np, rounds=None, cpu_leg=True):
     parity["def1_residual_max"] = def1_residual(np, Bs, w.layers)
     del M_sel, g_sel
 
+    side = not args.only_timed
     # ---- the same rounds with a G of its own per round (streamed from HBM) --------------------
-    Ks = min(K, 256)
-    Gs = torch.randn((Ks, n, d), dtype=torch.float32, device=dev)
-    ngc.ngc_coded_rounds(ctx, Gs, n * d, masks[:Ks], M, n * d, gh)
-    ngc.ngc_profile_read(ctx)
-    for _ in range(3):
+    Ks = min(K, 256) if side else 0
+    if side:
+        Gs = torch.randn((Ks, n, d), dtype=torch.float32, device=dev)
         ngc.ngc_coded_rounds(ctx, Gs, n * d, masks[:Ks], M, n * d, gh)
-    ls, ms_s = ngc.ngc_profile_read(ctx)["rounds"]
-    resp_s = float(np.count_nonzero(a_all[:Ks])) / Ks
-    stream_GBps = 4.0 * d * (n + resp_s + 1) * Ks * ls / (ms_s * 1e-3) / 1e9
-    del Gs
+        ngc.ngc_profile_read(ctx)
+        for _ in range(3):
+            ngc.ngc_coded_rounds(ctx, Gs, n * d, masks[:Ks], M, n * d, gh)
+        ls, ms_s = ngc.ngc_profile_read(ctx)["rounds"]
+        resp_s = float(np.count_nonzero(a_all[:Ks])) / Ks
+        stream_GBps = 4.0 * d * (n + resp_s + 1) * Ks * ls / (ms_s * 1e-3) / 1e9
+        del Gs
 
-    # ---- stand-alone kernels and the per-round loop (host in the loop) -------------------------
-    Kl = min(K, 300)
-    ngc.ngc_profile_enable(ctx, ["encode", "decode", "rounds"])
-    for t in range(Kl):
-        ngc.ngc_encode(ctx, G, -1, C)
-        ngc.ngc_decode(ctx, int(lay[t]), a_all[t], C, g)
-        ngc.ngc_encode_decode(ctx, G, int(lay[t]), a_all[t], M[0], g)
-    prof = ngc.ngc_profile_read(ctx)
+        # ---- stand-alone kernels and the per-round loop (host in the loop) ---------------------
+        Kl = min(K, 300)
+        ngc.ngc_profile_enable(ctx, ["encode", "decode", "rounds"])
+        for t in range(Kl):
+            ngc.ngc_encode(ctx, G, -1, C)
+            ngc.ngc_decode(ctx, int(lay[t]), a_all[t], C, g)
+            ngc.ngc_encode_decode(ctx, G, int(lay[t]), a_all[t], M[0], g)
+        prof = ngc.ngc_profile_read(ctx)
+        enc_ms = prof["encode"][1] / max(1, prof["encode"][0])
+        dec_ms = prof["decode"][1] / max(1, prof["decode"][0])
+        one_ms = prof["rounds"][1] / max(1, prof["rounds"][0])
+        torch.cuda.synchronize()
+        tl = time.perf_counter()
+        for t in range(Kl):
+            u, a, _ = ngc.ngc_select_decode_vec(ctx, masks[t], n)
+            ngc.ngc_encode_decode(ctx, G, u, a, M[0], g)
+        torch.cuda.synchronize()
+        loop_ms = (time.perf_counter() - tl) / Kl * 1e3
     ngc.ngc_profile_enable(ctx, False)
-    enc_ms = prof["encode"][1] / max(1, prof["encode"][0])
-    dec_ms = prof["decode"][1] / max(1, prof["decode"][0])
-    one_ms = prof["rounds"][1] / max(1, prof["rounds"][0])
-    torch.cuda.synchronize()
-    tl = time.perf_counter()
-    for t in range(Kl):
-        u, a, _ = ngc.ngc_select_decode_vec(ctx, masks[t], n)
-        ngc.ngc_encode_decode(ctx, G, u, a, M[0], g)
-    torch.cuda.synchronize()
-    loop_ms = (time.perf_counter() - tl) / Kl * 1e3
     enc_bytes = 4.0 * n * d * (1 + L)
     dec_bytes = 4.0 * d * (resp + 1)
 
+    stages = {"host_bookkeeping_ms_per_call": round(t_host * 1e3, 3),
+              "call_ms_repeats": [round(x * 1e3, 3) for x in walls],
+              "kernel_us_per_round": round(kern_ms / K * 1e3, 4),
+              "batched_GBps": round(achieved, 1)}
+    if side:
+        stages.update({
+            "batched_GBps_new_G_every_round": round(stream_GBps, 1),
+            "encode_all_layers_ms": round(enc_ms, 4), "encode_GBps": round(enc_bytes / (enc_ms * 1e-3) / 1e9, 1),
+            "decode_ms": round(dec_ms, 4), "decode_GBps": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
+            "fused_one_round_ms": round(one_ms, 4),
+            "fused_one_round_GBps": round(fused_bytes / (one_ms * 1e-3) / 1e9, 1),
+            "round_ms_host_in_loop": round(loop_ms, 4)})
     roofline = with_traffic(
         {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
          "frac": round(achieved / HBM_PEAK_GBS, 4), "algorithmic_bytes": fused_bytes * K,
@@ -271,16 +285,7 @@ def bench_codec(args, w, wl, ngc, torch, np, rounds=None, cpu_leg=True):
         "config": {"workload": w.name, "n": n, "d": d, "layers": list(w.layers),
                    "p_straggle": w.p_straggle, "mean_responders": resp, "rounds_per_call": K},
         "roofline": roofline,
-        "stages": {"host_bookkeeping_ms_per_call": round(t_host * 1e3, 3),
-                   "call_ms_repeats": [round(x * 1e3, 3) for x in walls],
-                   "kernel_us_per_round": round(kern_ms / K * 1e3, 4),
-                   "batched_GBps": round(achieved, 1),
-                   "batched_GBps_new_G_every_round": round(stream_GBps, 1),
-                   "encode_all_layers_ms": round(enc_ms, 4), "encode_GBps": round(enc_bytes / (enc_ms * 1e-3) / 1e9, 1),
-                   "decode_ms": round(dec_ms, 4), "decode_GBps": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
-                   "fused_one_round_ms": round(one_ms, 4),
-                   "fused_one_round_GBps": round(fused_bytes / (one_ms * 1e-3) / 1e9, 1),
-                   "round_ms_host_in_loop": round(loop_ms, 4)},
+        "stages": stages,
         "parity": parity,
     }
     if cpu_leg and not args.no_cpu_baseline:
@@ -776,7 +781,8 @@ def bench_pipeline(args, w, wl, ngc, torch, np, K, W, cpu_leg=True, probe=True, 
         ngc.ngc_profile_enable(ctx, False)
         del scratch
         ceiling = {"plain_read_GBps": round(Xd.numel() * 4 * n_read / (ms_read * 1e-3) / 1e9, 1),
-                   "plain_copy_GBps_read_plus_write": round(2 * nb * n_copy / (ms_copy * 1e-3) / 1e9, 1)}
+                   "plain_copy_GBps_read_plus_write": round(2 * nb * n_copy / (ms_copy * 1e-3) / 1e9, 1),
+                   "copy_bytes": nb}
     if ceiling and roofline.get("bound") == "hbm":
         # the same rate against what a plain read of the same buffer reaches on this machine
         roofline["frac_of_plain_read"] = round(roofline["achieved"] / ceiling["plain_read_GBps"], 4)
@@ -863,8 +869,14 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="headline workload only")
+    ap.add_argument("--only-timed", action="store_true",
+                    help="encode/decode stress: the timed batched launches only, none of the side measurements "
+                         "(so that a kernel trace holds one kind of launch per kernel)")
     ap.add_argument("--mode", default="pipeline", choices=["pipeline", "workers", "latency", "lookup"])
     ap.add_argument("--cpu-parts", type=int, default=32)
+    ap.add_argument("--rows", type=int, default=0,
+                    help="rows per partition instead of the workload's own (same distributions): a longer "
+                         "stream through the same kernel, named in config.workload")
     ap.add_argument("--parts-per-worker", type=int, default=1,
                     help="k = c n (Sec. II-C): the workload's partitions are shared out c to a worker")
     args = ap.parse_args()
@@ -892,8 +904,12 @@ def main():
         return bench_latency(args, ngc, torch, np)
     if args.mode == "lookup":
         return bench_lookup(args, wl, ngc, torch, np)
-    headline_only = args.workload is not None or args.no_others or args.parts_per_worker != 1 or args.mode != "pipeline"
+    headline_only = (args.workload is not None or args.no_others or args.parts_per_worker != 1 or
+                     args.mode != "pipeline" or args.rows > 0)
     w = wl.CONFIGS[args.workload or "C3"]
+    if args.rows > 0 and w.loss >= 0:
+        import dataclasses
+        w = dataclasses.replace(w, rows=args.rows, name="%s-rows%d" % (w.name, args.rows))
     if args.mode == "workers":
         if w.loss < 0:
             print("--mode workers needs a gradient workload (C1..C4)", file=sys.stderr)
