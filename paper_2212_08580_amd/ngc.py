@@ -17,7 +17,8 @@ import numpy as np
 import torch  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libngc.so")
+# NGC_LIB names another build of the same library (the host-sanitizer build of build.py)
+LIB_PATH = os.environ.get("NGC_LIB") or os.path.join(_HERE, "libngc.so")
 
 NGC_OK = 0
 NGC_ERR_INVALID = -1

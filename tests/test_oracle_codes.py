@@ -34,7 +34,13 @@ def test_cyclic_nested_code_satisfies_def1_and_def2(n, layers):
             if prev is not None:
                 assert prev[i] <= supp[i]                              # Def. 2 nesting
         prev = supp
-        # Def. 1: any n-sigma rows span an (n-sigma)-dim space containing 1
+        # Def. 1: any n-sigma rows span an (n-sigma)-dim space containing 1.  The rank is counted
+        # with an absolute threshold of 1e-9 on the singular values: the rows are solutions of
+        # linear systems, accurate to about 1e-13 relative to entries of order 1..100, so a
+        # singular value that should vanish comes out near 1e-12, while matrix_rank's default
+        # threshold (largest singular value x dimension x 2.2e-16, here about 1e-13) sits right
+        # at that noise level; the smallest singular value that should not vanish is above 1e-4
+        # for these sizes, far from either threshold (the pins pass with the default as well).
         for out in itertools.combinations(range(n), sigma):
             S = [i for i in range(n) if i not in out]
             assert np.linalg.matrix_rank(B[S], tol=1e-9) == n - sigma
