@@ -387,16 +387,22 @@ def bench_workers(args, w, wl, ngc, torch, np):
         flops = nested_tasks * w.rows * (2.0 * w.d_in * w.hidden * 2 + 2.0 * w.hidden * w.classes * 3)
         achieved = flops / (kern_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": 157.3, "unit": "TFLOP/s",
-                    "frac": round(achieved / 157.3, 4), "traffic": None, "algorithmic_flops": flops / K,
+                    "frac": round(achieved / 157.3, 4), "traffic": None, "traffic_source": None,
+                    "algorithmic_flops": flops / K,
                     "kernel": "mlp_gemm_kernel (whole MLP gradient call, one unit per worker task)",
                     "avg_ms": round(kern_ms / max(1, launches), 4), "launches": launches}
     else:
         nbytes = nested_tasks * w.rows * (4.0 * w.d + 4.0) + K * 4.0 * w.d
         achieved = nbytes / (kern_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                    "algorithmic_bytes": nbytes / K, "kernel": "grad_stream_kernel (one unit per worker task)",
-                    "avg_ms": round(kern_ms / max(1, launches), 4), "launches": launches}
+        roofline = with_traffic(
+            {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+             "frac": round(achieved / HBM_PEAK_GBS, 4),
+             "algorithmic_bytes": nbytes / K, "kernel": "grad_stream_kernel (one unit per worker task)",
+             "avg_ms": round(kern_ms / max(1, launches), 4), "launches": launches,
+             "note": "algorithmic bytes count every worker's own pass over each partition it computes; workers "
+                     "that read the same partition in one launch share the caches, so the HBM traffic (mean per "
+                     "launch over the same iterations) is lower than these bytes and `achieved` is not an HBM rate"},
+            "worker_execution_%s.txt" % w.name)
     out = {
         "metric": metric_name(w.n, w.d) + " (worker execution, useful samples/s)",
         "value": res["nested"]["useful_samples_per_s"], "unit": "samples/s", "n_gpus": 1, "steps": K,
@@ -410,12 +416,12 @@ def bench_workers(args, w, wl, ngc, torch, np):
                                           res["nested"]["ms_per_iteration"], 3),
         "roofline": roofline,
     }
+    Bs = oracle_code(ngc, ctx, L)        # the code the timed run used goes to the oracle's leg
     ngc.ngc_destroy(ctx)
     if keep is not None:
         # the oracle's worker execution of one iteration (the first timed straggler pattern):
         # every task of every worker recomputed in fp64, messages, termination rule, decoding
-        from oracle import codes, coding, workers as ow
-        Bs = codes.nested_code(w.n, w.layers, "cyclic" if w.code == wl.CODE_CYCLIC else "fracrep", seed=0, draws=2)
+        from oracle import coding, workers as ow
         Xh, Yh = keep
         alive = (masks[W] == 0).astype(np.int64)
         for t in range(1, T + 1):
