@@ -188,24 +188,22 @@ def bench_codec(args, w, wl, ngc, torch, np, rounds=None, cpu_leg=True):
         ngc.ngc_coded_rounds(ctx, G, 0, masks, M, n * d, gh)
     torch.cuda.synchronize()
     ngc.ngc_profile_enable(ctx, ["rounds"])
+    CALLS = 5                                               # the timed region: five calls of K rounds each
+    t_host, walls = 0.0, []
     t0 = time.perf_counter()
-    lay, a_all = ngc.ngc_coded_rounds(ctx, G, 0, masks, M, n * d, gh)
-    t_host = time.perf_counter() - t0
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    launches, kern_ms = ngc.ngc_profile_read(ctx)["rounds"]
-    resp = float(np.count_nonzero(a_all)) / K
-    fused_bytes = 4.0 * d * (n + resp + 1)                  # G read + responders' messages written + gradient
-    # a few more calls: spread of the kernel time, and of the call's wall time with the host part
-    walls = []
-    for _ in range(4):
-        torch.cuda.synchronize()
+    for _ in range(CALLS):
         tw = time.perf_counter()
-        ngc.ngc_coded_rounds(ctx, G, 0, masks, M, n * d, gh)
+        lay, a_all = ngc.ngc_coded_rounds(ctx, G, 0, masks, M, n * d, gh)
+        t_host += time.perf_counter() - tw
         torch.cuda.synchronize()
         walls.append(time.perf_counter() - tw)
+    elapsed = (time.perf_counter() - t0) / CALLS            # per call of K rounds
+    t_host /= CALLS
     per_call = ngc.ngc_profile_launches(ctx, "rounds")
-    ngc.ngc_profile_read(ctx)
+    launches, kern_ms = ngc.ngc_profile_read(ctx)["rounds"]
+    kern_ms /= max(1, launches)                             # average launch
+    resp = float(np.count_nonzero(a_all)) / K
+    fused_bytes = 4.0 * d * (n + resp + 1)                  # G read + responders' messages written + gradient
     achieved = fused_bytes * K / (kern_ms * 1e-3) / 1e9
     # parity of exactly these rounds against the oracle (the library-built code goes to the oracle),
     # on rounds spread over the run, taken before the buffers are used again below
@@ -271,7 +269,7 @@ def bench_codec(args, w, wl, ngc, torch, np, rounds=None, cpu_leg=True):
         {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
          "frac": round(achieved / HBM_PEAK_GBS, 4), "algorithmic_bytes": fused_bytes * K,
          "kernel": "coded_rounds_kernel (%d rounds per launch, one G for all rounds)" % K,
-         "avg_ms": round(kern_ms / max(1, launches), 4), "launches": launches,
+         "avg_ms": round(kern_ms, 4), "launches": launches,
          "median_ms": round(float(np.median(per_call)), 4) if per_call.size else None,
          "note": "algorithmic bytes per round = 4 n d (G) + 4 n_S d (messages written) + 4 d; with one G for all "
                  "rounds a block reads its tile of G once and keeps it in LDS, so the HBM traffic is mostly the "
@@ -280,10 +278,10 @@ def bench_codec(args, w, wl, ngc, torch, np, rounds=None, cpu_leg=True):
     out = {
         "metric": metric_name(n, d),
         "value": round(fused_bytes * K / elapsed / 1e9, 1), "unit": "GB/s", "n_gpus": 1,
-        "steps": K, "warmup": W, "ms_per_step": round(elapsed / K * 1e3, 5), "higher_is_better": True,
+        "steps": K * CALLS, "warmup": W, "ms_per_step": round(elapsed / K * 1e3, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "n": n, "d": d, "layers": list(w.layers),
-                   "p_straggle": w.p_straggle, "mean_responders": resp, "rounds_per_call": K},
+                   "p_straggle": w.p_straggle, "mean_responders": resp, "rounds_per_call": K, "calls": CALLS},
         "roofline": roofline,
         "stages": stages,
         "parity": parity,
@@ -718,14 +716,17 @@ def bench_pipeline(args, w, wl, ngc, torch, np, K, W, cpu_leg=True, probe=True, 
     else:
         grad_launches, grad_ms = prof["grad"]
         grad_avg_ms = grad_ms / max(1, grad_launches)
+        # rows of 4, 8, .. 128 features take the kernel that loads several rows at once
+        dq = w.d // 4
+        grad_kernel = "grad_narrow_kernel" if (w.d % 4 == 0 and w.d <= 128 and dq & (dq - 1) == 0) else "grad_stream_kernel"
         # algorithmic bytes per launch: X once + labels + theta + G  (4*d bytes per sample)
         grad_bytes = 4.0 * w.m * w.d + 4.0 * w.m + 4.0 * w.d + 4.0 * w.n * w.d
         achieved = grad_bytes / (grad_avg_ms * 1e-3) / 1e9
         roofline = with_traffic(
             {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
              "frac": round(achieved / HBM_PEAK_GBS, 4), "algorithmic_bytes": grad_bytes,
-             "kernel": "grad_stream_kernel", "avg_ms": round(grad_avg_ms, 4), "launches": grad_launches},
-            "grad_stream_%s.txt" % w.name)
+             "kernel": grad_kernel, "avg_ms": round(grad_avg_ms, 4), "launches": grad_launches},
+            "%s_%s.txt" % (grad_kernel[:-len("_kernel")], w.name))
     if per_launch.size:
         # the same launches one by one (HIP events of the timed region): spread of the kernel's time
         roofline["median_ms"] = round(float(np.median(per_launch)), 4)
