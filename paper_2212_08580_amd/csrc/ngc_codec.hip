@@ -136,6 +136,34 @@ __device__ __forceinline__ void stage_tile(VT* tile, const float* __restrict__ G
     }
 }
 
+// The same tile by way of registers, for a block of four waves and at most NGC_MAX_N rows: the
+// loads of a whole tile are issued (sixteen per thread) and land in LDS later, so that they can
+// be in flight while the block works on the tile that is in LDS now.
+template <typename VT>
+struct tile_regs {
+    VT v[NGC_MAX_N / 4];
+};
+
+template <typename VT>
+__device__ __forceinline__ void tile_fetch(tile_regs<VT>& t, const float* __restrict__ G, int k, int64_t d,
+                                           int64_t c, bool in, int wave) {
+#pragma unroll
+    for (int u = 0; u < NGC_MAX_N / 4; ++u) {
+        const int r = wave + 4 * u;
+        t.v[u] = (VT)(0.0f);
+        if (in && r < k) t.v[u] = *reinterpret_cast<const VT*>(G + (int64_t)r * d + c);
+    }
+}
+
+template <typename VT>
+__device__ __forceinline__ void tile_land(VT* tile, const tile_regs<VT>& t, int kp, int wave, int lane) {
+#pragma unroll
+    for (int u = 0; u < NGC_MAX_N / 4; ++u) {
+        const int r = wave + 4 * u;
+        if (r < kp) tile[r * 64 + lane] = t.v[u];
+    }
+}
+
 // Messages of the four workers of one group under one layer for this lane's columns:
 //   m[r] = sum_j cf[j][r] * tile[j]   in ascending j, one fused multiply-add per term.
 // cf and cmask are wave-uniform (scalar loads); four columns of B are taken per trip, bit t of
@@ -151,36 +179,58 @@ __device__ __forceinline__ void load_trip(const VT* tile, int lane, const float*
     for (int t = 0; t < 4; ++t) x[t] = tile[(4 * jc + t) * 64 + lane];
 }
 
-template <typename VT>
+// ROWS: bit r set = message r of the group is wanted (a straggler's message is not formed)
+template <typename VT, int ROWS>
 __device__ __forceinline__ void fma_trip(const float (&w)[16], const VT (&x)[4], VT (&m)[4]) {
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) m[r] = ngc_fma(w[t * 4 + r], x[t], m[r]);
+        for (int r = 0; r < 4; ++r)
+            if ((ROWS >> r) & 1) m[r] = ngc_fma(w[t * 4 + r], x[t], m[r]);
 }
 
-template <typename VT>
+// Two register sets take the trips in turn, so the loads of the next trip are in flight during
+// the multiply-adds of the current one without any copy between them.
+template <typename VT, int ROWS>
 __device__ __forceinline__ void group_messages(const VT* tile, int lane, const float* __restrict__ cf,
                                                unsigned cmask, VT (&m)[4]) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) m[r] = (VT)(0.0f);
     if (cmask == 0) return;
-    float w[16];
-    VT x[4];
-    load_trip<VT>(tile, lane, cf, __builtin_ctz(cmask), w, x);
+    float wa[16], wb[16];
+    VT xa[4], xb[4];
+    load_trip<VT>(tile, lane, cf, __builtin_ctz(cmask), wa, xa);
     cmask &= cmask - 1;
-    while (cmask != 0) {
-        float wn[16];
-        VT xn[4];
-        load_trip<VT>(tile, lane, cf, __builtin_ctz(cmask), wn, xn);
+    for (;;) {
+        if (cmask == 0) {
+            fma_trip<VT, ROWS>(wa, xa, m);
+            break;
+        }
+        load_trip<VT>(tile, lane, cf, __builtin_ctz(cmask), wb, xb);
         cmask &= cmask - 1;
-        fma_trip<VT>(w, x, m);
-#pragma unroll
-        for (int t = 0; t < 16; ++t) w[t] = wn[t];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) x[t] = xn[t];
+        fma_trip<VT, ROWS>(wa, xa, m);
+        if (cmask == 0) {
+            fma_trip<VT, ROWS>(wb, xb, m);
+            break;
+        }
+        load_trip<VT>(tile, lane, cf, __builtin_ctz(cmask), wa, xa);
+        cmask &= cmask - 1;
+        fma_trip<VT, ROWS>(wb, xb, m);
     }
-    fma_trip<VT>(w, x, m);
+}
+
+// The same with the wanted rows known only at run time (wave-uniform): one of sixteen variants.
+template <typename VT>
+__device__ __forceinline__ void group_messages_rows(const VT* tile, int lane, const float* __restrict__ cf,
+                                                    unsigned cmask, int rows, VT (&m)[4]) {
+    switch (rows) {
+#define NGC_ROWS_CASE(R) case R: group_messages<VT, R>(tile, lane, cf, cmask, m); break;
+        NGC_ROWS_CASE(1) NGC_ROWS_CASE(2) NGC_ROWS_CASE(3) NGC_ROWS_CASE(4) NGC_ROWS_CASE(5)
+        NGC_ROWS_CASE(6) NGC_ROWS_CASE(7) NGC_ROWS_CASE(8) NGC_ROWS_CASE(9) NGC_ROWS_CASE(10)
+        NGC_ROWS_CASE(11) NGC_ROWS_CASE(12) NGC_ROWS_CASE(13) NGC_ROWS_CASE(14) NGC_ROWS_CASE(15)
+#undef NGC_ROWS_CASE
+        default: break;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -213,7 +263,7 @@ __global__ __launch_bounds__(ENC_WAVES * 64) void encode_kernel(const float* __r
         const int g = t / layer_count;
         const int ug = u * ng + g;
         VT m[4];
-        group_messages<VT>(tile, lane, gcoef + (size_t)ug * kp * 4, gmask[ug], m);
+        group_messages<VT, 15>(tile, lane, gcoef + (size_t)ug * kp * 4, gmask[ug], m);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int i = 4 * g + r;
@@ -373,7 +423,9 @@ struct round_rec {
 };
 static_assert(sizeof(round_rec) == 576, "round record layout");
 
-template <typename VT, int V, bool SINGLE>
+enum { ROUNDS_SINGLE = 0, ROUNDS_ONE_G = 1, ROUNDS_G_PER_ROUND = 2 };
+
+template <typename VT, int V, int MODE>
 __global__ __launch_bounds__(256) void coded_rounds_kernel(
     const float* __restrict__ G, int64_t g_stride, float* __restrict__ M, int64_t m_stride,
     float* __restrict__ ghat, const round_rec* __restrict__ recs, round_rec one,
@@ -388,14 +440,23 @@ __global__ __launch_bounds__(256) void coded_rounds_kernel(
     const int chunk = (int)(blockIdx.x / (unsigned)ntiles);
     const int64_t c = ((int64_t)tile_id * 64 + lane) * V;
     const bool in = c < d;
+    constexpr bool SINGLE = MODE == ROUNDS_SINGLE;
     const int r0 = chunk * rounds_per_block;
     const int r1 = rounds < r0 + rounds_per_block ? rounds : r0 + rounds_per_block;
+    if (r0 >= r1) return;
+    // With a G per round the next round's tile is fetched into registers before this round's
+    // work starts and lands in LDS after it: its way from HBM is hidden behind the arithmetic.
+    tile_regs<VT> next;
+    if (MODE == ROUNDS_G_PER_ROUND) {
+        tile_fetch<VT>(next, G + (int64_t)r0 * g_stride, k, d, c, in, wave);
+        tile_land<VT>(tile, next, kp, wave, lane);
+    } else {
+        stage_tile<VT, 4>(tile, G, k, kp, d, c, in, wave, lane);
+    }
+    __syncthreads();
     for (int r = r0; r < r1; ++r) {
-        if (r == r0 || g_stride != 0) {
-            if (r != r0) __syncthreads();  // every wave is done with the previous round's tile
-            stage_tile<VT, 4>(tile, G + (int64_t)r * g_stride, k, kp, d, c, in, wave, lane);
-            __syncthreads();
-        }
+        if (MODE == ROUNDS_G_PER_ROUND && r + 1 < r1)
+            tile_fetch<VT>(next, G + (int64_t)(r + 1) * g_stride, k, d, c, in, wave);
         const int layer = SINGLE ? one.layer : recs[r].layer;
         double q[V];
 #pragma unroll
@@ -409,17 +470,24 @@ __global__ __launch_bounds__(256) void coded_rounds_kernel(
             float* Mr = M + (int64_t)r * m_stride + c;
             for (int g = wave; g < ng; g += 4) {
                 const int ug = layer * ng + g;
-                VT m[4];
-                group_messages<VT>(tile, lane, gcoef + (size_t)ug * kp * 4, gmask[ug], m);
+                double av[4];
+                int rows = 0;
 #pragma unroll
                 for (int rr = 0; rr < 4; ++rr) {
-                    const int i = 4 * g + rr;  // < NGC_MAX_N; a is zero beyond n
-                    const double a = SINGLE ? one.a[i] : recs[r].a[i];
-                    if (a != 0.0) {  // wave-uniform
-                        if (in) __builtin_nontemporal_store(m[rr], reinterpret_cast<VT*>(Mr + (int64_t)i * d));
+                    av[rr] = SINGLE ? one.a[4 * g + rr] : recs[r].a[4 * g + rr];  // index < NGC_MAX_N; zero beyond n
+                    rows |= (av[rr] != 0.0) << rr;
+                }
+                if (rows == 0) continue;  // wave-uniform: four stragglers in a row
+                VT m[4];
+                group_messages_rows<VT>(tile, lane, gcoef + (size_t)ug * kp * 4, gmask[ug], rows, m);
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    if (av[rr] != 0.0) {  // wave-uniform
+                        if (in)
+                            __builtin_nontemporal_store(m[rr], reinterpret_cast<VT*>(Mr + (int64_t)(4 * g + rr) * d));
 #pragma unroll
                         for (int v = 0; v < V; ++v)
-                            acc[rr][v] = __builtin_fma(a, (double)ngc_get(m[rr], v), acc[rr][v]);
+                            acc[rr][v] = __builtin_fma(av[rr], (double)ngc_get(m[rr], v), acc[rr][v]);
                     }
                 }
             }
@@ -437,6 +505,11 @@ __global__ __launch_bounds__(256) void coded_rounds_kernel(
                 ngc_set(out, v, (float)ngc_quad(x[(0 * V + v) * 64 + lane], x[(1 * V + v) * 64 + lane],
                                                 x[(2 * V + v) * 64 + lane], x[(3 * V + v) * 64 + lane]));
             *reinterpret_cast<VT*>(ghat + (int64_t)r * d + c) = out;
+        }
+        if (MODE == ROUNDS_G_PER_ROUND && r + 1 < r1) {
+            __syncthreads();  // every wave is done with this round's tile
+            tile_land<VT>(tile, next, kp, wave, lane);
+            __syncthreads();
         }
     }
 }
@@ -699,7 +772,7 @@ extern "C" int ngc_decode(ngc_ctx* ctx, int layer, const double* a_host, const f
 
 // ---- coded rounds ---------------------------------------------------------------------------
 // launch shape shared by the one-round and the many-round call
-template <bool SINGLE>
+template <int MODE>
 static int launch_rounds(ngc_ctx* ctx, const float* G_dev, int64_t g_stride, float* M_dev, int64_t m_stride,
                          float* g_dev, const round_rec* recs_dev, const round_rec& one, int rounds) {
     const code_view cv = view_code(ctx);
@@ -708,7 +781,7 @@ static int launch_rounds(ngc_ctx* ctx, const float* G_dev, int64_t g_stride, flo
     V = std::min(V, ngc_vec_width(d, g_dev, g_dev));
     if (g_stride % 4 || m_stride % 4) V = std::min(V, (g_stride % 2 || m_stride % 2) ? 1 : 2);
     // a single round has only its column tiles to fill the chip with: narrower tiles then
-    if (SINGLE)
+    if (MODE == ROUNDS_SINGLE)
         while (V > 1 && (d + 64 * V - 1) / (64 * V) < ctx->cu_count) V /= 2;
     const int64_t ntiles = (d + 64 * V - 1) / (64 * V);
     // runs of rounds per block: about eight blocks per CU in all, so that the tail of the launch is short
@@ -722,11 +795,11 @@ static int launch_rounds(ngc_ctx* ctx, const float* G_dev, int64_t g_stride, flo
     ngc_prof_scope ps(ctx, NGC_KERNEL_ROUNDS);
 #define NGC_ROUNDS_ARGS G_dev, g_stride, M_dev, m_stride, g_dev, recs_dev, one, cv.gmask, cv.gcoef, ctx->n, ctx->k, cv.kp, cv.ng, d, (int)ntiles, rounds, rpb
     if (V == 4)
-        hipLaunchKernelGGL((coded_rounds_kernel<v4f, 4, SINGLE>), grid, dim3(256), lds, ctx->stream, NGC_ROUNDS_ARGS);
+        hipLaunchKernelGGL((coded_rounds_kernel<v4f, 4, MODE>), grid, dim3(256), lds, ctx->stream, NGC_ROUNDS_ARGS);
     else if (V == 2)
-        hipLaunchKernelGGL((coded_rounds_kernel<v2f, 2, SINGLE>), grid, dim3(256), lds, ctx->stream, NGC_ROUNDS_ARGS);
+        hipLaunchKernelGGL((coded_rounds_kernel<v2f, 2, MODE>), grid, dim3(256), lds, ctx->stream, NGC_ROUNDS_ARGS);
     else
-        hipLaunchKernelGGL((coded_rounds_kernel<float, 1, SINGLE>), grid, dim3(256), lds, ctx->stream, NGC_ROUNDS_ARGS);
+        hipLaunchKernelGGL((coded_rounds_kernel<float, 1, MODE>), grid, dim3(256), lds, ctx->stream, NGC_ROUNDS_ARGS);
 #undef NGC_ROUNDS_ARGS
     NGC_HIP(ctx, hipGetLastError());
     return NGC_OK;
@@ -750,7 +823,7 @@ extern "C" int ngc_encode_decode(ngc_ctx* ctx, const float* G_dev, int layer, co
         one.a[i] = a_host[i];
     }
     one.layer = layer;
-    return launch_rounds<true>(ctx, G_dev, 0, M_dev, 0, g_dev, nullptr, one, 1);
+    return launch_rounds<ROUNDS_SINGLE>(ctx, G_dev, 0, M_dev, 0, g_dev, nullptr, one, 1);
 } catch (...) {
     return ngc_on_exception();
 }
@@ -845,8 +918,11 @@ extern "C" int ngc_coded_rounds(ngc_ctx* ctx, const float* G_dev, int64_t g_roun
     ctx->rounds_ev_set = true;
     round_rec none;
     std::memset(&none, 0, sizeof(none));
-    return launch_rounds<false>(ctx, G_dev, g_round_stride, M_dev, m_round_stride, g_dev,
-                                (const round_rec*)ctx->d_rounds, none, rounds);
+    if (g_round_stride != 0)
+        return launch_rounds<ROUNDS_G_PER_ROUND>(ctx, G_dev, g_round_stride, M_dev, m_round_stride, g_dev,
+                                                 (const round_rec*)ctx->d_rounds, none, rounds);
+    return launch_rounds<ROUNDS_ONE_G>(ctx, G_dev, 0, M_dev, m_round_stride, g_dev,
+                                       (const round_rec*)ctx->d_rounds, none, rounds);
 } catch (...) {
     return ngc_on_exception();
 }
