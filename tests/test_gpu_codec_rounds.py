@@ -8,21 +8,16 @@ messages (<= 2e-7: the kernel must use the rounded message, not the unrounded su
 against ngc_decode, and against the exact sum of the partial gradients within
 max(1e-4, 4 * 2^-24 * kappa).
 """
-import json
-import os
-
 import numpy as np
 import pytest
 
+from conftest import parity_report
 from oracle import codes, coding
 from paper_2212_08580_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
 TOL = 1e-4
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-REPORT = os.path.join(ROOT, "gpurun_out", "parity_report.jsonl")
 
 
 @pytest.fixture(scope="module")
@@ -198,10 +193,8 @@ def test_coded_rounds_c5_all_1000_rounds(ngc, torch_dev):
         # every round is inside the forward-error bound (run_rounds); those above 1e-4 are rounds whose
         # straggler count equals the layer's tolerance (one decode vector, no choice)
         assert float(np.mean(errs > TOL)) <= 0.01
-        with open(REPORT, "a") as f:
-            f.write(json.dumps({"test": "coded_rounds_c5", "rounds": int(errs.size),
-                                "median_decode_rel_l2": float(np.median(errs)), "worst_decode_rel_l2": float(errs.max()),
-                                "share_above_1e_4": float(np.mean(errs > TOL))}) + "\n")
+        parity_report(test="coded_rounds_c5", rounds=int(errs.size), median_decode_rel_l2=float(np.median(errs)),
+                      worst_decode_rel_l2=float(errs.max()), share_above_1e_4=float(np.mean(errs > TOL)))
     finally:
         ngc.ngc_destroy(ctx)
 
@@ -216,10 +209,8 @@ def test_coded_rounds_c3_masks(ngc, torch_dev):
     try:
         errs = run_rounds(ngc, torch_dev, ctx, w, Bs, G_h, masks, 0)
         assert errs.size >= 395 and errs.max() <= TOL                   # plain 1e-4 on every round
-        with open(REPORT, "a") as f:
-            f.write(json.dumps({"test": "coded_rounds_c3", "rounds": int(errs.size),
-                                "median_decode_rel_l2": float(np.median(errs)),
-                                "worst_decode_rel_l2": float(errs.max())}) + "\n")
+        parity_report(test="coded_rounds_c3", rounds=int(errs.size), median_decode_rel_l2=float(np.median(errs)),
+                      worst_decode_rel_l2=float(errs.max()))
     finally:
         ngc.ngc_destroy(ctx)
 

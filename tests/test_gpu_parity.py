@@ -9,8 +9,8 @@ large: a straggler count equal to the layer's tolerance leaves one decode vector
 and no choice): such a round must stay inside the forward-error bound
 4 * 2^-24 * kappa, the tests of the headline code (n = 32) assert plain 1e-4 on
 every round of its own straggler distribution, the n = 64 stress test asserts
-the share of rounds above 1e-4, and every figure goes to
-gpurun_out/parity_report.jsonl.
+the share of rounds above 1e-4, and every figure goes to the report file
+(conftest.parity_report).
 
 Codes: by default the one the library builds (ngc_build_code, the configuration
 the benchmark times), read back through ngc_get_code and handed to the oracle,
@@ -18,8 +18,6 @@ which first checks Def. 1 on sampled straggler sets; where a test names `kind`
 with oracle=True the oracle's own constructor supplies B through ngc_set_code.
 """
 import dataclasses
-import json
-import os
 
 import numpy as np
 import pytest
@@ -47,17 +45,10 @@ def rel(x, ref):
     return float(np.linalg.norm(x - ref) / max(np.linalg.norm(ref), 1e-300))
 
 
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-
-
 def report(**kw):
     """One line per parity figure, kept beside the test log."""
-    try:
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "parity_report.jsonl"), "a") as f:
-            f.write(json.dumps(kw) + "\n")
-    except OSError:
-        pass
+    from conftest import parity_report
+    parity_report(**kw)
 
 
 def def1_holds_on_samples(Bs, layers, seed=0, sets=6):
