@@ -755,12 +755,15 @@ def bench_pipeline(args, w, wl, ngc, torch, np, K, W, cpu_leg=True, probe=True, 
         ngc.ngc_coded_rounds(ctx, G, 0, bm, Mb, nw * w.d, gb)
         torch.cuda.synchronize()
         ngc.ngc_profile_enable(ctx, ["rounds"])
-        wall_b = []
+        wall_b, call_b = [], []
         for _ in range(3):
             tb = time.perf_counter()
             lay_b, a_b = ngc.ngc_coded_rounds(ctx, G, 0, bm, Mb, nw * w.d, gb)
+            call_b.append(time.perf_counter() - tb)
             torch.cuda.synchronize()
             wall_b.append(time.perf_counter() - tb)
+        log("%s: batched rounds, wall per call %s ms, of which inside the call %s ms" %
+            (w.name, [round(x * 1e3, 3) for x in wall_b], [round(x * 1e3, 3) for x in call_b]))
         wall_b = sorted(wall_b)[1]
         cnt_b, ms_b = ngc.ngc_profile_read(ctx)["rounds"]
         ms_b /= max(1, cnt_b)

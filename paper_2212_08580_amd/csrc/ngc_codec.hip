@@ -895,8 +895,12 @@ extern "C" int ngc_coded_rounds(ngc_ctx* ctx, const float* G_dev, int64_t g_roun
             rec.layer = layer;
         }
     };
+    // a solve costs about n^2 / 1500 microseconds; a thread is worth starting per quarter of a
+    // millisecond of such work (starting and joining one costs tens of microseconds, far more on a
+    // host whose cores are busy), so small jobs stay on the calling thread
     const unsigned hw = std::max(1u, std::thread::hardware_concurrency());
-    const int nthreads = (int)std::min<unsigned>(std::min(hw, 16u), (unsigned)std::max(1, rounds / 64));
+    const double work_us = (double)rounds * ctx->n * ctx->n / 1500.0;
+    const int nthreads = (int)std::min<double>(std::min(hw, 16u), std::max(1.0, work_us / 250.0));
     if (nthreads <= 1) {
         plan(0, rounds);
     } else {
