@@ -1,6 +1,7 @@
 """Whole path on randomly drawn (seeded) configurations: number of workers, layer set, code
 family, feature count (aligned, ragged, odd), rows per partition, loss.  Every step is
-compared with the oracle, and the fused iteration with the stand-alone calls bit for bit."""
+compared with the oracle, and the fused passes (whole iteration, encode + decode of one round,
+of several rounds in one launch) with the stand-alone calls bit for bit."""
 import numpy as np
 import pytest
 
@@ -63,5 +64,32 @@ def test_random_configurations(ngc, torch_dev, seed):
             ngc.ngc_sync(p.ctx)
             assert torch.equal(G2, p.G) and torch.equal(C2, p.C) and torch.equal(g2, p.g), tag
             assert torch.equal(th1, th2), tag
+            # encode + decode of that round in one pass over G, and of several rounds in one launch
+            # (some with one straggler too many): same bits as the stand-alone calls
+            M1 = torch.full((w.n, w.d), -3.0, dtype=torch.float32, device=p.dev)
+            g1 = torch.empty_like(p.g)
+            ngc.ngc_encode_decode(p.ctx, p.G, u, a, M1, g1)
+            ngc.ngc_sync(p.ctx)
+            resp = torch.from_numpy(np.flatnonzero(a != 0)).to(p.dev)
+            assert torch.equal(g1, p.g) and torch.equal(M1[resp], p.C[u][resp]), tag
+            R = 7
+            masks = np.zeros((R, w.n), np.uint8)
+            for r in range(R):
+                cnt = int(rng.integers(0, w.layers[-1] + 2))            # up to s_max + 1
+                masks[r, rng.choice(w.n, size=min(cnt, w.n), replace=False)] = 1
+            MR = torch.full((R, w.n, w.d), -3.0, dtype=torch.float32, device=p.dev)
+            gR = torch.full((R, w.d), -3.0, dtype=torch.float32, device=p.dev)
+            lay, aa = ngc.ngc_coded_rounds(p.ctx, p.G, 0, masks, MR, w.n * w.d, gR)
+            ngc.ngc_sync(p.ctx)
+            for r in range(R):
+                if masks[r].sum() > w.layers[-1]:
+                    assert lay[r] == -1 and bool((gR[r] == 0).all()) and bool((MR[r] == -3.0).all()), tag
+                    continue
+                u_o, a_o, g_o = coding.coded_gradient(p.Bs, w.layers, G_o, masks[r])
+                assert lay[r] == u_o and np.array_equal(aa[r] != 0, a_o != 0), tag
+                ngc.ngc_decode(p.ctx, int(lay[r]), aa[r], p.C, p.g)
+                ngc.ngc_sync(p.ctx)
+                resp = torch.from_numpy(np.flatnonzero(aa[r] != 0)).to(p.dev)
+                assert torch.equal(gR[r], p.g) and torch.equal(MR[r][resp], p.C[int(lay[r])][resp]), tag
         finally:
             p.close()
