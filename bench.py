@@ -199,9 +199,11 @@ def bench_codec(args, w, wl, ngc, torch, np, rounds=None, cpu_leg=True):
         walls.append(time.perf_counter() - tw)
     elapsed = (time.perf_counter() - t0) / CALLS            # per call of K rounds
     t_host /= CALLS
-    per_call = ngc.ngc_profile_launches(ctx, "rounds")
-    launches, kern_ms = ngc.ngc_profile_read(ctx)["rounds"]
-    kern_ms /= max(1, launches)                             # average launch
+    per_launch = ngc.ngc_profile_launches(ctx, "rounds")
+    launches, kern_total_ms = ngc.ngc_profile_read(ctx)["rounds"]
+    kern_ms = kern_total_ms / CALLS                         # kernel time of one call's K rounds
+    per_call_launches = max(1, launches // CALLS)           # a call goes in runs of 256 rounds, one launch each
+    launch_ms = kern_total_ms / max(1, launches)
     resp = float(np.count_nonzero(a_all)) / K
     fused_bytes = 4.0 * d * (n + resp + 1)                  # G read + responders' messages written + gradient
     achieved = fused_bytes * K / (kern_ms * 1e-3) / 1e9
@@ -267,10 +269,10 @@ def bench_codec(args, w, wl, ngc, torch, np, rounds=None, cpu_leg=True):
             "round_ms_host_in_loop": round(loop_ms, 4)})
     roofline = with_traffic(
         {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-         "frac": round(achieved / HBM_PEAK_GBS, 4), "algorithmic_bytes": fused_bytes * K,
-         "kernel": "coded_rounds_kernel (%d rounds per launch, one G for all rounds)" % K,
-         "avg_ms": round(kern_ms, 4), "launches": launches,
-         "median_ms": round(float(np.median(per_call)), 4) if per_call.size else None,
+         "frac": round(achieved / HBM_PEAK_GBS, 4), "algorithmic_bytes": fused_bytes * K / per_call_launches,
+         "kernel": "coded_rounds_kernel (%d rounds per call in %d launches, one G for all rounds)" % (K, per_call_launches),
+         "avg_ms": round(launch_ms, 4), "launches": launches,
+         "median_ms": round(float(np.median(per_launch)), 4) if per_launch.size else None,
          "note": "algorithmic bytes per round = 4 n d (G) + 4 n_S d (messages written) + 4 d; with one G for all "
                  "rounds a block reads its tile of G once and keeps it in LDS, so the HBM traffic is mostly the "
                  "messages (see traffic)"},

@@ -218,12 +218,14 @@ int ngc_encode_decode(ngc_ctx* ctx, const float* G_dev, int layer, const double*
                       float* M_dev, float* g_dev);
 
 /*
- * Many rounds of encode + decode in one launch.  masks_host: uint8 [rounds][n], one
+ * Many rounds of encode + decode per launch.  masks_host: uint8 [rounds][n], one
  * straggler mask per round (1 = straggler).  For every round r the main node's bookkeeping
  * (layer by the Observation after Def. 2, least-norm decode vector as in
- * ngc_select_decode_vec) is done on the host up front, the vectors go to the device as one
- * table, and one kernel then forms, for every round, the messages of that round's layer for
- * its responders and the recovered gradient, exactly as ngc_encode_decode does (same bits):
+ * ngc_select_decode_vec) is done on the host, the vectors go to the device as a table, and a
+ * kernel forms, for every round of its run, the messages of that round's layer for its
+ * responders and the recovered gradient, exactly as ngc_encode_decode does (same bits).  Up
+ * to 511 rounds are one run; more go in runs of 256, one launch each, the host solving for
+ * the next run while the device works on the current one:
  *   G of round r  = G_dev + r * g_round_stride   (float [k][d]; stride 0: one G for all rounds,
  *                                                 read from HBM once per block, else >= k*d)
  *   messages      -> M_dev + r * m_round_stride  (float [n][d]; stride >= n*d)
@@ -231,8 +233,9 @@ int ngc_encode_decode(ngc_ctx* ctx, const float* G_dev, int layer, const double*
  * layers_out (int [rounds], may be NULL) receives each round's layer, -1 for a round with
  * more stragglers than the largest tolerance: such a round writes a zero gradient and no
  * message and is not an error.  a_out (double [rounds][n], may be NULL) receives the decode
- * vectors.  NGC_ERR_SINGULAR if a round's residual is above tolerance (nothing is launched).
- * The host part runs on a few threads; the call returns when the kernel is enqueued.
+ * vectors.  NGC_ERR_SINGULAR if a round's residual is above tolerance: the run that holds the
+ * round and the runs after it are not launched (earlier runs are).  The host part uses a few
+ * threads when the solves are worth them; the call returns when the last kernel is enqueued.
  */
 int ngc_coded_rounds(ngc_ctx* ctx, const float* G_dev, int64_t g_round_stride, int rounds,
                      const uint8_t* masks_host, float* M_dev, int64_t m_round_stride, float* g_dev,

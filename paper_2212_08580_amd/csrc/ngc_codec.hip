@@ -16,7 +16,9 @@
 
 #include <algorithm>
 #include <cmath>
+#include <atomic>
 #include <cstring>
+#include <memory>
 #include <thread>
 #include <vector>
 
@@ -337,38 +339,68 @@ extern "C" int ngc_coded_rounds(ngc_ctx* ctx, const float* G_dev, int64_t g_roun
             rec.layer = layer;
         }
     };
-    // a solve costs about n^2 / 1500 microseconds; a thread is worth starting per quarter of a
-    // millisecond of such work (starting and joining one costs tens of microseconds, far more on a
-    // host whose cores are busy), so small jobs stay on the calling thread
+    // The rounds go to the device in runs of 256: while the kernel of one run works, the host
+    // solves for the next.  A solve costs about n^2 / 1500 microseconds; a thread is worth starting
+    // per quarter of a millisecond of such work over the whole call (starting and joining one costs
+    // tens of microseconds, far more on a host whose cores are busy), so small jobs stay on the
+    // calling thread.  Threads are started once; each takes its share of every run and counts
+    // itself done per run, the calling thread takes a share too, waits for the others, copies the
+    // run's records and launches.
+    const int run = rounds >= 512 ? 256 : rounds;
+    const int nruns = (rounds + run - 1) / run;
     const unsigned hw = std::max(1u, std::thread::hardware_concurrency());
     const double work_us = (double)rounds * ctx->n * ctx->n / 1500.0;
     const int nthreads = (int)std::min<double>(std::min(hw, 16u), std::max(1.0, work_us / 250.0));
-    if (nthreads <= 1) {
-        plan(0, rounds);
-    } else {
-        std::vector<std::thread> pool;
-        const int per = (rounds + nthreads - 1) / nthreads;
-        for (int t = 1; t < nthreads; ++t) pool.emplace_back(plan, std::min(rounds, t * per), std::min(rounds, (t + 1) * per));
-        plan(0, std::min(rounds, per));
-        for (auto& th : pool) th.join();
-    }
-    for (int r = 0; r < rounds; ++r) {
-        if (status[r] != NGC_OK)
-            return ngc_fail(ctx, status[r], status[r] == NGC_ERR_STATE ? "a chosen layer has no code yet"
-                                                                       : "decode residual above tolerance in round " + std::to_string(r));
-        if (layers_out) layers_out[r] = recs[r].layer;
-        if (a_out) std::memcpy(a_out + (size_t)r * n, recs[r].a, sizeof(double) * n);
-    }
-    NGC_HIP(ctx, hipMemcpyAsync(ctx->d_rounds, recs, sizeof(round_rec) * (size_t)rounds, hipMemcpyHostToDevice, ctx->stream));
-    NGC_HIP(ctx, hipEventRecord(ctx->rounds_ev, ctx->stream));
-    ctx->rounds_ev_set = true;
+    std::unique_ptr<std::atomic<int>[]> done(new std::atomic<int>[nruns]);
+    for (int c = 0; c < nruns; ++c) done[c].store(0);
+    auto share = [&](int tid) {
+        for (int c = 0; c < nruns; ++c) {
+            const int lo = c * run, hi = std::min(rounds, lo + run);
+            const int per = (hi - lo + nthreads - 1) / nthreads;
+            plan(std::min(hi, lo + tid * per), std::min(hi, lo + (tid + 1) * per));
+            done[c].fetch_add(1, std::memory_order_release);
+        }
+    };
+    std::vector<std::thread> pool;
+    for (int t = 1; t < nthreads; ++t) pool.emplace_back(share, t);
+    struct joiner {
+        std::vector<std::thread>& p;
+        ~joiner() {
+            for (auto& th : p)
+                if (th.joinable()) th.join();
+        }
+    } join_all{pool};
     round_rec none;
     std::memset(&none, 0, sizeof(none));
-    if (g_round_stride != 0)
-        return launch_rounds<ROUNDS_G_PER_ROUND>(ctx, G_dev, g_round_stride, M_dev, m_round_stride, g_dev,
-                                                 (const round_rec*)ctx->d_rounds, none, rounds);
-    return launch_rounds<ROUNDS_ONE_G>(ctx, G_dev, 0, M_dev, m_round_stride, g_dev,
-                                       (const round_rec*)ctx->d_rounds, none, rounds);
+    for (int c = 0; c < nruns; ++c) {
+        const int lo = c * run, hi = std::min(rounds, lo + run);
+        {
+            const int per = (hi - lo + nthreads - 1) / nthreads;
+            plan(lo, std::min(hi, lo + per));
+            done[c].fetch_add(1, std::memory_order_release);
+        }
+        while (done[c].load(std::memory_order_acquire) < nthreads) std::this_thread::yield();
+        for (int r = lo; r < hi; ++r) {
+            if (status[r] != NGC_OK)
+                return ngc_fail(ctx, status[r], status[r] == NGC_ERR_STATE ? "a chosen layer has no code yet"
+                                                                           : "decode residual above tolerance in round " + std::to_string(r));
+            if (layers_out) layers_out[r] = recs[r].layer;
+            if (a_out) std::memcpy(a_out + (size_t)r * n, recs[r].a, sizeof(double) * n);
+        }
+        round_rec* d_recs = (round_rec*)ctx->d_rounds + lo;
+        NGC_HIP(ctx, hipMemcpyAsync(d_recs, recs + lo, sizeof(round_rec) * (size_t)(hi - lo), hipMemcpyHostToDevice, ctx->stream));
+        NGC_HIP(ctx, hipEventRecord(ctx->rounds_ev, ctx->stream));
+        ctx->rounds_ev_set = true;
+        if (g_round_stride != 0)
+            rc = launch_rounds<ROUNDS_G_PER_ROUND>(ctx, G_dev + (int64_t)lo * g_round_stride, g_round_stride,
+                                                   M_dev + (int64_t)lo * m_round_stride, m_round_stride,
+                                                   g_dev + (int64_t)lo * d, d_recs, none, hi - lo);
+        else
+            rc = launch_rounds<ROUNDS_ONE_G>(ctx, G_dev, 0, M_dev + (int64_t)lo * m_round_stride, m_round_stride,
+                                             g_dev + (int64_t)lo * d, d_recs, none, hi - lo);
+        if (rc) return rc;
+    }
+    return NGC_OK;
 } catch (...) {
     return ngc_on_exception();
 }
