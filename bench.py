@@ -184,6 +184,10 @@ def bench_codec(args, w, wl, ngc, torch, np, rounds=None, cpu_leg=True):
     ngc.ngc_build_code(ctx, ngc.NGC_CODE_CYCLIC if w.code == wl.CODE_CYCLIC else ngc.NGC_CODE_FRACREP, 0)
 
     # ---- the timed region: all K rounds in one call (warm-up calls first) ---------------------
+    t_settle = time.perf_counter()                          # untimed: 100 ms of calls bring the card's clocks up
+    while time.perf_counter() - t_settle < 0.1:
+        ngc.ngc_coded_rounds(ctx, G, 0, masks, M, n * d, gh)
+        torch.cuda.synchronize()
     for _ in range(max(1, min(W, 3))):
         ngc.ngc_coded_rounds(ctx, G, 0, masks, M, n * d, gh)
     torch.cuda.synchronize()
@@ -673,6 +677,16 @@ def bench_pipeline(args, w, wl, ngc, torch, np, K, W, cpu_leg=True, probe=True, 
         ngc.ngc_update(ctx, thd, g, eta_over_m)
         return u, a
 
+    # Untimed: after an idle spell (the host just built and uploaded the data) the card needs some
+    # tens of milliseconds of work before its clocks are up; steps run until 100 ms have passed, theta is
+    # put back, then come the W warm-up steps.
+    th_start = thd.clone()
+    t_settle = time.perf_counter()
+    while time.perf_counter() - t_settle < 0.1:
+        for t in range(4):
+            step(t % (W + K))
+        torch.cuda.synchronize()
+    thd.copy_(th_start)
     for t in range(W):
         step(t)
     torch.cuda.synchronize()

@@ -293,6 +293,18 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(
 constexpr int TM = 112, TN = 128, TK = 8, LDA = TM, LDB = TN + 16;
 typedef float v4acc __attribute__((ext_vector_type(4)));
 
+// How a launch whose tile count is no multiple of the CU count is evened out (FAST only).
+// The tiles of one XCD's run (`per` of them, see xcd_tile) are `whole` tiles that are
+// computed as they are, a multiple of the XCD's CU count, and per - whole tiles that are cut
+// along K into `pieces` pieces each; a piece goes to a scratch tile and a second kernel adds
+// the pieces of a tile in piece order.  The launch is one-dimensional: block b works for XCD
+// b % 8 and is its item b / 8, whole tiles first, so the short items fill the gaps at the end.
+// pieces == 0: the plain three-dimensional launch, one block per tile.
+struct k_split {
+    int pieces, per, whole, gx, gy;
+    float* scratch;  // [8 * (per - whole) * pieces][TM][TN]
+};
+
 // 8-deep k tiles and one float4 of each operand per thread and stage keep the kernel
 // under 100 registers and 16 KiB of LDS, so five blocks fit a CU: 1280 slots for the
 // 1120 tiles of the 20 x 784 x 1024 backward product, which then run as one resident set
@@ -302,17 +314,37 @@ __global__ __launch_bounds__(256, 5) void mlp_gemm112_kernel(
     const float* __restrict__ A, const float* __restrict__ B, float* __restrict__ C, int M, int N,
     int K, int64_t lda, int64_t ldb, int64_t ldc, int64_t strideA, int64_t strideB,
     int64_t strideC, int a_vec_ok, int b_vec_ok, const int* __restrict__ a_batch,
-    const int* __restrict__ c_batch) {
+    const int* __restrict__ c_batch, const k_split split) {
     __shared__ float As[2][TK + 2][LDA];  // rows TK, TK+1: landing area for the 32 threads without an A element
     __shared__ float Bs[2][TK][LDB];
     const int t = threadIdx.x;
     const int lane = t & 63;
     const int wave = t >> 6;
     const int l16 = lane & 15, kq = lane >> 4;
-    const tile_id tile = xcd_tile();
+    tile_id tile;
+    int nk = (K + TK - 1) / TK;  // k tiles this block multiplies, starting at k tile kt0
+    int kt0 = 0;
+    float* piece_out = nullptr;
+    if (FAST && split.pieces > 0) {
+        const int xcd = blockIdx.x & 7, item = blockIdx.x >> 3;
+        int v = xcd * split.per + item;
+        if (item >= split.whole) {
+            const int p = item - split.whole, cut = p / split.pieces, piece = p % split.pieces;
+            v = xcd * split.per + split.whole + cut;
+            kt0 = (int)((int64_t)nk * piece / split.pieces);
+            nk = (int)((int64_t)nk * (piece + 1) / split.pieces) - kt0;
+            piece_out = split.scratch +
+                        ((int64_t)(xcd * (split.per - split.whole) + cut) * split.pieces + piece) * (TM * TN);
+        }
+        tile.x = v % split.gx;
+        tile.y = (v / split.gx) % split.gy;
+        tile.z = v / (split.gx * split.gy);
+    } else {
+        tile = xcd_tile();
+    }
     const int m0 = tile.y * TM, n0 = tile.x * TN;
-    A += (int64_t)(a_batch ? a_batch[tile.z] : tile.z) * strideA;
-    B += (int64_t)tile.z * strideB;
+    A += (int64_t)(a_batch ? a_batch[tile.z] : tile.z) * strideA + (int64_t)kt0 * TK * lda;
+    B += (int64_t)tile.z * strideB + (int64_t)kt0 * TK * ldb;
     C += (int64_t)(c_batch ? c_batch[tile.z] : tile.z) * strideC;
 
     v4acc acc[7][2];
@@ -384,7 +416,6 @@ __global__ __launch_bounds__(256, 5) void mlp_gemm112_kernel(
     // the launch is interior, 16-byte addressable and K a whole number of k tiles): loads
     // without guards and a steady-state loop without conditions, so that the wait before a
     // stage's LDS stores covers that stage's loads only.
-    const int nk = (K + TK - 1) / TK;
     v4f pa, pb, qa, qb;
     int kt = 0;
     if (FAST) {
@@ -437,6 +468,18 @@ __global__ __launch_bounds__(256, 5) void mlp_gemm112_kernel(
     }
 
     // result block: register r of lane l is element (row 4*(l/16) + r, column l % 16)
+    if (FAST) {   // every tile is interior; a piece of a tile goes to its scratch tile, rows of TN
+        float* out = piece_out ? piece_out : C + (int64_t)m0 * ldc + n0;
+        const int64_t ldo = piece_out ? TN : ldc;
+        out += (int64_t)(4 * kq) * ldo + wave * 32 + l16;
+#pragma unroll
+        for (int bn = 0; bn < 2; ++bn)
+#pragma unroll
+            for (int bm = 0; bm < 7; ++bm)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) out[(bm * 16 + r) * ldo + bn * 16] = acc[bm][bn][r];
+        return;
+    }
 #pragma unroll
     for (int bn = 0; bn < 2; ++bn) {
         const int gn = n0 + wave * 32 + bn * 16 + l16;
@@ -449,6 +492,40 @@ __global__ __launch_bounds__(256, 5) void mlp_gemm112_kernel(
                 if (gm < M) C[(int64_t)gm * ldc + gn] = acc[bm][bn][r];
             }
         }
+    }
+}
+
+// Second kernel of an evened-out launch: blocks (q, 0..6) add the pieces of cut tile q in
+// piece order and write the tile to its place in C; block (q, y) takes rows 16y..16y+15,
+// thread t four consecutive columns of rows 16y + t/32 and 16y + 8 + t/32.
+__global__ __launch_bounds__(256) void mlp_gemm112_join_kernel(float* __restrict__ C, int64_t ldc,
+                                                               int64_t strideC,
+                                                               const int* __restrict__ c_batch,
+                                                               const k_split split) {
+    const int cuts = split.per - split.whole;
+    const int xcd = blockIdx.x / cuts, cut = blockIdx.x % cuts;
+    const int v = xcd * split.per + split.whole + cut;
+    const int tx = v % split.gx, ty = (v / split.gx) % split.gy, tz = v / (split.gx * split.gy);
+    const float* src = split.scratch + (int64_t)blockIdx.x * split.pieces * (TM * TN);
+    float* dst = C + (int64_t)(c_batch ? c_batch[tz] : tz) * strideC + (int64_t)ty * TM * ldc + tx * TN;
+    const int t = threadIdx.x;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int row = blockIdx.y * 16 + h * 8 + (t >> 5), col = (t & 31) * 4;
+        const float* s = src + row * TN + col;
+        v4f acc = *reinterpret_cast<const v4f*>(s);
+        for (int p = 1; p < split.pieces; ++p) {
+            const v4f x = *reinterpret_cast<const v4f*>(s + (int64_t)p * (TM * TN));
+            acc.x += x.x;
+            acc.y += x.y;
+            acc.z += x.z;
+            acc.w += x.w;
+        }
+        float* o = dst + (int64_t)row * ldc + col;
+        o[0] = acc.x;
+        o[1] = acc.y;
+        o[2] = acc.z;
+        o[3] = acc.w;
     }
 }
 
@@ -832,7 +909,23 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
     chunks = (rows + rpc - 1) / rpc;
     const size_t h_floats = (((size_t)total * hid) + 63) / 64 * 64;
     const size_t z_floats = (((size_t)total * cls) + 63) / 64 * 64;
-    const size_t need = sizeof(float) * (h_floats + z_floats + (size_t)k * chunks * T);
+    // backward product in tiles of 112 rows: if its tile count leaves some CUs one tile short of
+    // the others, the last tiles of each XCD's run are cut along K (see k_split)
+    const int64_t gemm_tiles = (int64_t)((hid + TN - 1) / TN) * ((din + TM - 1) / TM) * k;
+    const int cus_per_xcd = ctx->cu_count / 8;
+    int64_t gemm_cuts = 0;  // cut tiles per XCD
+    int gemm_pieces = 8;    // pieces per cut tile: the fewest (4..16) that share out evenly over the XCD's CUs
+    if (cus_per_xcd > 0 && gemm_tiles % 8 == 0 && gemm_tiles / 8 < 16 * (int64_t)cus_per_xcd) {
+        gemm_cuts = (gemm_tiles / 8) % cus_per_xcd;
+        for (int p = 4; p <= 16; ++p)
+            if ((gemm_cuts * p) % cus_per_xcd == 0) {
+                gemm_pieces = p;
+                break;
+            }
+        if (rows / TK < 16 * gemm_pieces) gemm_cuts = 0;  // pieces of fewer than 16 k tiles are not worth their prologue
+    }
+    const size_t need = sizeof(float) * (h_floats + z_floats + (size_t)k * chunks * T +
+                                         (size_t)(8 * gemm_cuts * gemm_pieces) * TM * TN);
     if (need > ctx->d_ws_bytes) {
         if (ctx->d_ws) {
             NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
@@ -911,14 +1004,27 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
         if (pad112 < pad128) {
             dim3 grid((unsigned)((hid + TN - 1) / TN), (unsigned)((din + TM - 1) / TM), (unsigned)k);
             const bool all_fast = a_ok && b_ok && din % TM == 0 && hid % TN == 0 && rows % TK == 0;
-            if (all_fast)
+            k_split split = {0, 0, 0, (int)grid.x, (int)grid.y, nullptr};
+            if (all_fast && gemm_cuts > 0) {
+                split.pieces = gemm_pieces;
+                split.per = (int)(gemm_tiles / 8);
+                split.whole = split.per - (int)gemm_cuts;
+                split.scratch = partial + (size_t)k * chunks * T;
+                hipLaunchKernelGGL(mlp_gemm112_kernel<true>, dim3((unsigned)(8 * (split.whole + gemm_cuts * gemm_pieces))),
+                                   dim3(256), 0, ctx->stream, X, (const float*)H, G, din, hid, (int)rows,
+                                   (int64_t)din, (int64_t)hid, (int64_t)hid, rows * (int64_t)din,
+                                   rows * (int64_t)hid, d, a_ok, b_ok, unit_part, unit_row, split);
+                NGC_HIP(ctx, hipGetLastError());
+                hipLaunchKernelGGL(mlp_gemm112_join_kernel, dim3((unsigned)(8 * gemm_cuts), TM / 16), dim3(256), 0,
+                                   ctx->stream, G, (int64_t)hid, d, unit_row, split);
+            } else if (all_fast)
                 hipLaunchKernelGGL(mlp_gemm112_kernel<true>, grid, dim3(256), 0, ctx->stream, X, (const float*)H, G,
                                    din, hid, (int)rows, (int64_t)din, (int64_t)hid, (int64_t)hid,
-                                   rows * (int64_t)din, rows * (int64_t)hid, d, a_ok, b_ok, unit_part, unit_row);
+                                   rows * (int64_t)din, rows * (int64_t)hid, d, a_ok, b_ok, unit_part, unit_row, split);
             else
                 hipLaunchKernelGGL(mlp_gemm112_kernel<false>, grid, dim3(256), 0, ctx->stream, X, (const float*)H, G,
                                    din, hid, (int)rows, (int64_t)din, (int64_t)hid, (int64_t)hid,
-                                   rows * (int64_t)din, rows * (int64_t)hid, d, a_ok, b_ok, unit_part, unit_row);
+                                   rows * (int64_t)din, rows * (int64_t)hid, d, a_ok, b_ok, unit_part, unit_row, split);
         } else {
             dim3 grid((unsigned)((hid + BN - 1) / BN), (unsigned)((din + BM - 1) / BM), (unsigned)k);
             hipLaunchKernelGGL((mlp_gemm_kernel<true, EPI_STORE>), grid, dim3(256), 0, ctx->stream, X, (const float*)H, G,

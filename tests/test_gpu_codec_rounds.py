@@ -237,6 +237,69 @@ def test_coded_rounds_with_a_gradient_per_round_and_undecodable_rounds(ngc, torc
         ngc.ngc_destroy(ctx)
 
 
+@pytest.mark.parametrize("n,c,layers,d,rounds,g_pad,m_pad", [
+    (7, 3, (0, 2, 5), 257, 40, 7, 5),          # n not a multiple of 4, k = 3 n, odd d, unaligned strides
+    (13, 2, (0, 1, 4, 9), 1028, 130, 4, 4),    # 16-byte aligned strides with gaps
+    (62, 1, (0, 1, 4), 100, 33, 0, 8),         # one G for all rounds, gaps between the rounds' messages
+    (1, 1, (0,), 5, 3, 3, 1),                  # a single worker
+    (21, 3, (0, 20), 64, 600, 0, 0),           # k = 63, full tolerance, more rounds than one launch takes
+])
+def test_coded_rounds_with_padded_strides_and_several_partitions_per_worker(ngc, torch_dev, n, c, layers, d, rounds,
+                                                                            g_pad, m_pad):
+    """k = c n partitions (Sec. II-A), strides larger than one round's data: the gaps keep their
+    contents, every round equals the stand-alone calls bit for bit and the oracle's B G within
+    the message tolerance."""
+    torch = torch_dev
+    dev = torch.device("cuda:0")
+    k = n * c
+    rng = np.random.default_rng(1000 * n + d)
+    ctx = ngc.ngc_create(n, k, layers, d, torch.cuda.current_stream().cuda_stream)
+    try:
+        ngc.ngc_build_code(ctx, ngc.NGC_CODE_CYCLIC, 3)
+        Bs = [ngc.ngc_get_code(ctx, u) for u in range(len(layers))]
+        assert all(B.shape == (n, k) for B in Bs)
+        gs = k * d + g_pad if g_pad else 0
+        ms = n * d + m_pad
+        G = torch.from_numpy(rng.standard_normal((rounds - 1) * gs + k * d).astype(np.float32)).to(dev)
+        M = torch.full(((rounds - 1) * ms + n * d,), -7.0, dtype=torch.float32, device=dev)
+        gh = torch.full((rounds, d), -7.0, dtype=torch.float32, device=dev)
+        masks = random_masks(rng, n, layers[-1], rounds)
+        if layers[-1] + 1 <= n:
+            masks[rounds // 2] = 0
+            masks[rounds // 2, rng.choice(n, size=layers[-1] + 1, replace=False)] = 1
+        lay, a_all = ngc.ngc_coded_rounds(ctx, G, gs, masks, M, ms, gh)
+        ngc.ngc_sync(ctx)
+        C = torch.empty((len(layers), n, d), dtype=torch.float32, device=dev)
+        g_sep = torch.empty(d, dtype=torch.float32, device=dev)
+        for r in range(rounds):
+            Gr = G[r * gs: r * gs + k * d]
+            Mr = M[r * ms: r * ms + n * d].view(n, d)
+            if r + 1 < rounds and m_pad:
+                assert bool((M[r * ms + n * d: (r + 1) * ms] == -7.0).all()), r
+            if masks[r].sum() > layers[-1]:
+                assert lay[r] == -1 and bool((gh[r] == 0).all()) and bool((Mr == -7.0).all()), r
+                continue
+            u = coding.select_layer(layers, masks[r])
+            a_o, _ = coding.decode_vector(Bs[u], masks[r])
+            assert lay[r] == u and np.array_equal(a_all[r] != 0, a_o != 0), r
+            ngc.ngc_encode(ctx, Gr, u, C)
+            ngc.ngc_decode(ctx, u, a_all[r], C, g_sep)
+            ngc.ngc_sync(ctx)
+            resp = torch.from_numpy(np.flatnonzero(a_all[r] != 0)).to(dev)
+            out = torch.from_numpy(np.flatnonzero(a_all[r] == 0)).to(dev)
+            assert torch.equal(Mr[resp], C[u][resp]) and torch.equal(gh[r], g_sep), r
+            assert bool((Mr[out] == -7.0).all()), r
+            if r % 16 == 0:
+                G64 = Gr.cpu().numpy().astype(np.float64).reshape(k, d)
+                C_o = coding.encode(Bs[u], G64)
+                Mh = Mr.cpu().numpy()
+                for i in np.flatnonzero(a_all[r] != 0):
+                    assert rel(Mh[i], C_o[i]) <= 1e-6, (r, i)
+                assert rel(g_sep.cpu().numpy(), coding.decode(a_all[r], Mh)) <= 2e-7, r
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
 def test_coded_rounds_rejects_bad_arguments(ngc, torch_dev):
     torch = torch_dev
     dev = torch.device("cuda:0")

@@ -117,6 +117,9 @@ def check_blocks(w, X, Y, th, G, G_o):
     (1, 70, 300, 260, 7),        # both tile shapes ragged in every dimension
     (2, 45, 64, 2048, 10),       # hidden layer wider than one 1024-unit slice of the backward kernel
     (1, 33, 40, 1500, 4),        # ... and a ragged second slice
+    (4, 1024, 112, 256, 10),     # backward product: 8 tiles of 112 rows, every one cut along K into pieces
+    (5, 1032, 784, 1024, 10),    # ... 280 tiles: 32 whole and 3 cut per XCD, k tiles not a multiple of the pieces
+    (3, 1024, 112, 128, 4),      # ... 3 tiles: no multiple of 8, plain launch
 ])
 def test_mlp_partition_gradients_match_oracle(ngc, n, rows, d_in, hidden, classes):
     import torch
