@@ -719,7 +719,7 @@ def bench_pipeline(args, w, wl, ngc, torch, np, K, W, cpu_leg=True, probe=True, 
     # ---- roofline of the dominant kernel -------------------------------------------------------
     if is_mlp:
         # the two fp32 MFMA GEMMs (forward layer 1 and dW1) carry 98 % of the flops; timed here is
-        # the whole gradient call (GEMM, head pass, tail reduce, GEMM)
+        # the whole gradient call (GEMM, head pass, GEMM, closing sums)
         grad_launches, grad_ms = prof["mlp"]
         grad_avg_ms = grad_ms / max(1, grad_launches)
         flops = w.m * (2.0 * w.d_in * w.hidden * 2 + 2.0 * w.hidden * w.classes * 3)

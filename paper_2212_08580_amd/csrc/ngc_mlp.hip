@@ -2,13 +2,15 @@
 // relu(x W1 + b1) W2 + b2), the third loss of ngc_partition_grads: the partial
 // gradient g_j of Sec. II-C for each row block j, a plain sum over its rows.
 //
-// Three device steps, all partitions at once:
+// Device steps, all partitions at once:
 //   1. H = relu(X W1 + b1)                 fp32 MFMA GEMM, bias + ReLU in the epilogue
-//   2. per row: Z2 = H W2 + b2, P = softmax(Z2), dZ2 = P - onehot(label)   (one read of H);
+//   2. per row: Z2 = H W2 + b2, P = softmax(Z2), dZ2 = P - onehot(label);
 //      then dW2 += H^T dZ2, db2 += dZ2; dZ1 = (dZ2 W2^T) * [H > 0] written over H;
-//      db1 += dZ1                          (one read and one write of H, block partials)
+//      db1 += dZ1 (block partials).  One pass over H for a hidden layer of 1024 units
+//      (mlp_head1024_kernel), else a pass that reads H and one that reads and writes it
 //   3. dW1_j = X_j^T dZ1_j                 fp32 MFMA GEMM per partition, written into G
-// and a fixed-order sum of the block partials of step 2 into the tail of G.
+//   4. fixed-order sums: the block partials of step 2 into the tail of G, and the pieces of
+//      the tiles of step 3 that were cut along K
 //
 // MFMA tile: v_mfma_f32_32x32x2_f32.  A block of 4 waves computes a 128 x 128
 // tile of the output, each wave 64 x 64 as 2 x 2 MFMA blocks; operand tiles are
@@ -495,23 +497,22 @@ __global__ __launch_bounds__(256, 5) void mlp_gemm112_kernel(
     }
 }
 
-// Second kernel of an evened-out launch: blocks (q, 0..6) add the pieces of cut tile q in
-// piece order and write the tile to its place in C; block (q, y) takes rows 16y..16y+15,
-// thread t four consecutive columns of rows 16y + t/32 and 16y + 8 + t/32.
-__global__ __launch_bounds__(256) void mlp_gemm112_join_kernel(float* __restrict__ C, int64_t ldc,
-                                                               int64_t strideC,
-                                                               const int* __restrict__ c_batch,
-                                                               const k_split split) {
+// The pieces of cut tile q of an evened-out launch, added in piece order and written to the
+// tile's place in C; slab y (0..6) is rows 16y..16y+15, thread t takes four consecutive columns
+// of rows 16y + t/32 and 16y + 8 + t/32.
+__device__ __forceinline__ void join_tile(float* __restrict__ C, int64_t ldc, int64_t strideC,
+                                          const int* __restrict__ c_batch, const k_split& split, int q,
+                                          int y) {
     const int cuts = split.per - split.whole;
-    const int xcd = blockIdx.x / cuts, cut = blockIdx.x % cuts;
+    const int xcd = q / cuts, cut = q % cuts;
     const int v = xcd * split.per + split.whole + cut;
     const int tx = v % split.gx, ty = (v / split.gx) % split.gy, tz = v / (split.gx * split.gy);
-    const float* src = split.scratch + (int64_t)blockIdx.x * split.pieces * (TM * TN);
+    const float* src = split.scratch + (int64_t)q * split.pieces * (TM * TN);
     float* dst = C + (int64_t)(c_batch ? c_batch[tz] : tz) * strideC + (int64_t)ty * TM * ldc + tx * TN;
     const int t = threadIdx.x;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-        const int row = blockIdx.y * 16 + h * 8 + (t >> 5), col = (t & 31) * 4;
+        const int row = y * 16 + h * 8 + (t >> 5), col = (t & 31) * 4;
         const float* s = src + row * TN + col;
         v4f acc = *reinterpret_cast<const v4f*>(s);
         for (int p = 1; p < split.pieces; ++p) {
@@ -534,6 +535,12 @@ __device__ __forceinline__ float dpp_step(float v) {
     int iv = __builtin_bit_cast(int, v);
     int sh = __builtin_amdgcn_update_dpp(iv, iv, CTRL, 0xF, 0xF, false);
     return v + __builtin_bit_cast(float, sh);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_max(float v) {
+    int iv = __builtin_bit_cast(int, v);
+    int sh = __builtin_amdgcn_update_dpp(iv, iv, CTRL, 0xF, 0xF, false);
+    return fmaxf(v, __builtin_bit_cast(float, sh));
 }
 __device__ __forceinline__ float wave_sum(float v) {
     v = dpp_step<0xB1>(v);
@@ -831,14 +838,193 @@ __global__ __launch_bounds__(256) void mlp_back_kernel(
     }
 }
 
+// Steps 2a and 2b in one pass over H, for a hidden layer of exactly 1024 units and a class count
+// equal to NCP: H is read once and dZ1 written once, no dZ2 array in between.  A block of 8
+// waves owns a run of rows of one partition and takes them in trips of 8 rows; thread t owns
+// units 2t, 2t+1, wave w units 128w..128w+127.  Per trip:
+//   - the 8 rows go from registers into an LDS tile (row stride 1028 words: the eight rows a
+//     16-byte LDS read touches lie in eight different bank groups);
+//   - logits on the matrix cores (v_mfma_f32_16x16x4_f32, rows 8..15 of the 16-row block are
+//     not used): wave w multiplies its 128 units of the tile by its 128 rows of W2, which it
+//     holds in registers in operand layout for the whole kernel (lane l: class l % 16, unit
+//     16 s + 4 (l / 16) + e of step s, component e); the eight partial logits per (row, class)
+//     meet in LDS and are added in wave order;
+//   - softmax and dZ2 = P - onehot(label) by 16 lanes per row (waves 0 and 1), into LDS;
+//   - every thread reads the trip's dZ2 as LDS broadcasts and does what mlp_back_kernel does
+//     for its two units: dH = dZ2 W2^T, dZ1 = dH * [H > 0] over H, dW2 += h dZ2, db1 += dZ1,
+//     db2 += dZ2, in registers.
+// The next trip's rows are fetched into a second register set before the arithmetic of this one.
+// Block partial layout as in mlp_back_kernel.
+template <int NCP>
+__global__ __launch_bounds__(512, NCP <= 10 ? 4 : 2) void mlp_head1024_kernel(
+    float* __restrict__ H, const int* __restrict__ labels, const float* __restrict__ W2,
+    const float* __restrict__ b2, float* __restrict__ partial, int64_t rows, int chunks,
+    int64_t rows_per_chunk, const int* __restrict__ unit_part) {
+    constexpr int HID = 1024, TR = 8, LDH = HID + 4, NWV = 8;
+    __shared__ __attribute__((aligned(16))) float hs[TR][LDH];
+    __shared__ __attribute__((aligned(16))) float w2t[NCP][LDH];  // W2 transposed: [class][unit]
+    __shared__ float zp[NWV][TR][16];
+    __shared__ __attribute__((aligned(16))) float dzs[TR][16];
+    const int t = threadIdx.x;
+    const int lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int l16 = lane & 15, kq = lane >> 4;
+    const int j = blockIdx.x / chunks, c = blockIdx.x % chunks;
+    const int64_t r0 = (int64_t)c * rows_per_chunk;
+    const int64_t r1 = rows < r0 + rows_per_chunk ? rows : r0 + rows_per_chunk;
+    const int h0 = 2 * t;
+
+    float w2[2][NCP], dw2[2][NCP], db1[2] = {0.0f, 0.0f};
+    float db2 = 0.0f;  // threads 0..127: the sum of dZ2 over the rows (trip row t / 16, class t % 16) they handle
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+#pragma unroll
+        for (int q = 0; q < NCP; ++q) {
+            w2[e][q] = W2[(int64_t)(h0 + e) * NCP + q];
+            dw2[e][q] = 0.0f;
+        }
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+#pragma unroll
+        for (int q = 0; q < NCP; ++q) w2t[q][h0 + e] = w2[e][q];
+
+    float* Hp = H + ((int64_t)j * rows) * HID + h0;
+    const int* lab = labels + (int64_t)(unit_part ? unit_part[j] : j) * rows;
+    // rows past the end of the chunk are read from its last row and dropped
+    auto fetch = [&](int64_t rb, v2f (&hq)[TR]) {
+#pragma unroll
+        for (int u = 0; u < TR; ++u) {
+            const int64_t r = rb + u < r1 ? rb + u : r1 - 1;
+            hq[u] = *reinterpret_cast<const v2f*>(Hp + r * HID);
+        }
+    };
+    v2f hq[TR], nq[TR];
+    if (r0 < r1) fetch(r0, hq);
+    for (int64_t rb = r0; rb < r1; rb += TR) {
+#pragma unroll
+        for (int u = 0; u < TR; ++u) *reinterpret_cast<v2f*>(&hs[u][h0]) = hq[u];
+        __syncthreads();
+        if (rb + TR < r1) fetch(rb + TR, nq);
+        {   // partial logits of the wave's 128 units
+            // four accumulators, one per component, so that no product waits for the one before
+            // it; added in component order at the end
+            v4acc acc0 = (v4acc)(0.0f), acc1 = (v4acc)(0.0f), acc2 = (v4acc)(0.0f), acc3 = (v4acc)(0.0f);
+            // first operand: lane l feeds (row l % 16, unit 16 s + 4 (l / 16) + e), second operand
+            // (unit the same, class l % 16).  Rows 8..15 repeat rows 0..7 and classes >= NCP repeat
+            // lower ones: their results land in rows and columns of the block that nobody reads
+            const float* arow = &hs[l16 & (TR - 1)][wave * 128 + 4 * kq];
+            const float* brow = &w2t[l16 % NCP][wave * 128 + 4 * kq];
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                const v4f a4 = *reinterpret_cast<const v4f*>(arow + 16 * s);
+                const v4f b4 = *reinterpret_cast<const v4f*>(brow + 16 * s);
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.x, b4.x, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.y, b4.y, acc1, 0, 0, 0);
+                acc2 = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.z, b4.z, acc2, 0, 0, 0);
+                acc3 = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.w, b4.w, acc3, 0, 0, 0);
+            }
+            const v4acc acc = (acc0 + acc1) + (acc2 + acc3);
+            // result block: register r of lane l is (row 4 (l / 16) + r, class l % 16); rows 0..7 exist
+            if (kq < 2) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) zp[wave][4 * kq + r][l16] = acc[r];
+            }
+        }
+        __syncthreads();
+        if (t < TR * 16) {   // waves 0 and 1: 16 lanes per row
+            const int row = t >> 4, q = t & 15;
+            const int64_t r = rb + row < r1 ? rb + row : r1 - 1;
+            float z = -INFINITY;
+            if (q < NCP) {
+                z = zp[0][row][q];
+#pragma unroll
+                for (int w = 1; w < NWV; ++w) z += zp[w][row][q];
+                z += b2[q];
+            }
+            // maximum and sum over the 16 lanes of the row, every lane gets both (data-parallel
+            // moves within quads, half rows and rows; fixed order)
+            float mx = z;
+            mx = dpp_max<0xB1>(mx);
+            mx = dpp_max<0x4E>(mx);
+            mx = dpp_max<0x141>(mx);
+            mx = dpp_max<0x140>(mx);
+            const float ez = q < NCP ? expf(z - mx) : 0.0f;
+            float den = ez;
+            den = dpp_step<0xB1>(den);
+            den = dpp_step<0x4E>(den);
+            den = dpp_step<0x141>(den);
+            den = dpp_step<0x140>(den);
+            const float dz = q < NCP ? ez * (1.0f / den) - (q == lab[r] ? 1.0f : 0.0f) : 0.0f;
+            dzs[row][q] = dz;
+            if (rb + row < r1) db2 += dz;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < TR; ++u) {
+            if (rb + u < r1) {   // block-uniform
+                float dz[NCP];
+#pragma unroll
+                for (int q = 0; q < NCP; ++q) dz[q] = dzs[u][q];  // the same address in every lane
+                const float hv[2] = {hq[u].x, hq[u].y};
+                float dh[2] = {0.0f, 0.0f};
+#pragma unroll
+                for (int q = 0; q < NCP; ++q) {
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        dw2[e][q] += hv[e] * dz[q];
+                        dh[e] += dz[q] * w2[e][q];
+                    }
+                }
+                v2f out;
+                out.x = hv[0] > 0.0f ? dh[0] : 0.0f;  // ReLU'(0) = 0
+                out.y = hv[1] > 0.0f ? dh[1] : 0.0f;
+                db1[0] += out.x;
+                db1[1] += out.y;
+                *reinterpret_cast<v2f*>(Hp + (rb + u) * HID) = out;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < TR; ++u) hq[u] = nq[u];
+    }
+    const int64_t T = (int64_t)HID + (int64_t)HID * NCP + NCP;
+    float* P = partial + (int64_t)blockIdx.x * T;
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        P[h0 + e] = db1[e];
+#pragma unroll
+        for (int q = 0; q < NCP; ++q) P[HID + (int64_t)(h0 + e) * NCP + q] = dw2[e][q];
+    }
+    // db2: the eight row slots of a class are added in slot order
+    __syncthreads();
+    if (t < TR * 16) dzs[t >> 4][t & 15] = db2;
+    __syncthreads();
+    if (t < NCP) {
+        float acc = dzs[0][t];
+#pragma unroll
+        for (int u = 1; u < TR; ++u) acc += dzs[u][t];
+        P[HID + (int64_t)HID * NCP + t] = acc;
+    }
+}
+
+// The fixed-order sums that close a gradient call, one launch.  Blocks below join_blocks add
+// the pieces of the backward product's cut tiles (block b: tile b / 7, slab b % 7; none unless
+// the product was evened out).  The others sum the head's block partials: block b' = b -
+// join_blocks takes unit j = b' / tail_blocks and elements 256 (b' % tail_blocks)..+255:
 // out[row(j)*out_stride + t] = sum over chunks (in index order) of partial[(j*chunks + c)*T + t],
-// row(j) = unit_row[j], or j without a map
-__global__ __launch_bounds__(256) void mlp_tail_reduce_kernel(const float* __restrict__ partial,
-                                                              float* __restrict__ out, int64_t T,
-                                                              int chunks, int64_t out_stride,
-                                                              const int* __restrict__ unit_row) {
-    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int j = blockIdx.y;
+// row(j) = unit_row[j], or j without a map.
+__global__ __launch_bounds__(256) void mlp_sums_kernel(int join_blocks, float* __restrict__ C, int64_t ldc,
+                                                       int64_t strideC, const k_split split,
+                                                       const float* __restrict__ partial,
+                                                       float* __restrict__ out, int64_t T, int chunks,
+                                                       int tail_blocks, int64_t out_stride,
+                                                       const int* __restrict__ unit_row) {
+    if ((int)blockIdx.x < join_blocks) {
+        join_tile(C, ldc, strideC, unit_row, split, blockIdx.x / (TM / 16), blockIdx.x % (TM / 16));
+        return;
+    }
+    const int b = blockIdx.x - join_blocks;
+    const int j = b / tail_blocks;
+    const int64_t t = (int64_t)(b % tail_blocks) * 256 + threadIdx.x;
     if (t >= T) return;
     const float* p = partial + (int64_t)j * chunks * T + t;
     float acc = p[0];
@@ -902,7 +1088,9 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
     // workspace: H [total][hid] | dZ2 [total][cls] | block partials [k*chunks][T]
     // blocks of the backward head kernel: as many as are resident at once (its register count
     // allows 5, 3 or 2 blocks per CU for up to 4, 10 or 16 classes), so there is no second round
-    const int back_per_cu = cls <= 4 ? 5 : (cls <= 10 ? 3 : 2);
+    // (the one-pass head for 1024 hidden units: two blocks of 512 threads per CU, one at 16 classes)
+    const bool head_fused = hid == 1024 && (cls == 4 || cls == 10 || cls == 16);
+    const int back_per_cu = head_fused ? (cls == 16 ? 1 : 2) : (cls <= 4 ? 5 : (cls <= 10 ? 3 : 2));
     const int64_t slices = (hid + 1023) / 1024;  // the backward head kernel covers 1024 hidden units per block
     int64_t chunks = std::max<int64_t>(1, (int64_t)ctx->cu_count * back_per_cu / (k * slices));
     int64_t rpc = (rows + chunks - 1) / chunks;
@@ -983,7 +1171,18 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
     else                                                                                               \
         hipLaunchKernelGGL((mlp_back_kernel<NCP, false>), grid, dim3(256), 0, ctx->stream, H, (const float*)dZ2, \
                            W2, partial, hid, cls, rows, (int)chunks, rpc, hv);
-        if (cls <= 4) {
+        if (head_fused) {
+            dim3 fgrid((unsigned)(k * chunks));
+            if (cls == 4)
+                hipLaunchKernelGGL(mlp_head1024_kernel<4>, fgrid, dim3(512), 0, ctx->stream, H, labels, W2, b2, partial,
+                                   rows, (int)chunks, rpc, unit_part);
+            else if (cls == 10)
+                hipLaunchKernelGGL(mlp_head1024_kernel<10>, fgrid, dim3(512), 0, ctx->stream, H, labels, W2, b2, partial,
+                                   rows, (int)chunks, rpc, unit_part);
+            else
+                hipLaunchKernelGGL(mlp_head1024_kernel<16>, fgrid, dim3(512), 0, ctx->stream, H, labels, W2, b2, partial,
+                                   rows, (int)chunks, rpc, unit_part);
+        } else if (cls <= 4) {
             NGC_MLP_HEAD(4)
         } else if (cls <= 10) {
             NGC_MLP_HEAD(10)
@@ -992,11 +1191,9 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
         }
 #undef NGC_MLP_HEAD
         NGC_HIP(ctx, hipGetLastError());
-        dim3 rgrid((unsigned)((T + 255) / 256), (unsigned)k);
-        hipLaunchKernelGGL(mlp_tail_reduce_kernel, rgrid, dim3(256), 0, ctx->stream, (const float*)partial,
-                           G + (int64_t)din * hid, T, (int)chunks, d, unit_row);
-        NGC_HIP(ctx, hipGetLastError());
     }
+    int join_blocks = 0;
+    k_split split = {0, 0, 0, 0, 0, nullptr};
     {   // 3. dW1_j = X_j^T dZ1_j, one batch entry per partition, straight into G[j]
         const int a_ok = (int)(din % 4 == 0 && al(X, 16)), b_ok = (int)(hid % 4 == 0);
         // tiles of 112 rows when they pad the d_in rows less than tiles of 128 (784 = 7 * 112)
@@ -1004,7 +1201,8 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
         if (pad112 < pad128) {
             dim3 grid((unsigned)((hid + TN - 1) / TN), (unsigned)((din + TM - 1) / TM), (unsigned)k);
             const bool all_fast = a_ok && b_ok && din % TM == 0 && hid % TN == 0 && rows % TK == 0;
-            k_split split = {0, 0, 0, (int)grid.x, (int)grid.y, nullptr};
+            split.gx = (int)grid.x;
+            split.gy = (int)grid.y;
             if (all_fast && gemm_cuts > 0) {
                 split.pieces = gemm_pieces;
                 split.per = (int)(gemm_tiles / 8);
@@ -1014,9 +1212,7 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
                                    dim3(256), 0, ctx->stream, X, (const float*)H, G, din, hid, (int)rows,
                                    (int64_t)din, (int64_t)hid, (int64_t)hid, rows * (int64_t)din,
                                    rows * (int64_t)hid, d, a_ok, b_ok, unit_part, unit_row, split);
-                NGC_HIP(ctx, hipGetLastError());
-                hipLaunchKernelGGL(mlp_gemm112_join_kernel, dim3((unsigned)(8 * gemm_cuts), TM / 16), dim3(256), 0,
-                                   ctx->stream, G, (int64_t)hid, d, unit_row, split);
+                join_blocks = (int)(8 * gemm_cuts) * (TM / 16);
             } else if (all_fast)
                 hipLaunchKernelGGL(mlp_gemm112_kernel<true>, grid, dim3(256), 0, ctx->stream, X, (const float*)H, G,
                                    din, hid, (int)rows, (int64_t)din, (int64_t)hid, (int64_t)hid,
@@ -1032,6 +1228,13 @@ int ngc_mlp2_grads(ngc_ctx* ctx, const float* X, const int* labels, const float*
                                rows * (int64_t)din, rows * (int64_t)hid, d, a_ok, b_ok,
                                (int)(hid % 2 == 0 && d % 2 == 0 && al(G, 8)), unit_part, unit_row);
         }
+        NGC_HIP(ctx, hipGetLastError());
+    }
+    {   // 4. the sums that are left: pieces of cut tiles into G, the head's block partials into the tail of G
+        const int tail_blocks = (int)((T + 255) / 256);
+        hipLaunchKernelGGL(mlp_sums_kernel, dim3((unsigned)(join_blocks + tail_blocks * k)), dim3(256), 0, ctx->stream,
+                           join_blocks, G, (int64_t)hid, d, split, (const float*)partial, G + (int64_t)din * hid, T,
+                           (int)chunks, tail_blocks, d, unit_row);
         NGC_HIP(ctx, hipGetLastError());
     }
     return NGC_OK;

@@ -120,6 +120,9 @@ def check_blocks(w, X, Y, th, G, G_o):
     (4, 1024, 112, 256, 10),     # backward product: 8 tiles of 112 rows, every one cut along K into pieces
     (5, 1032, 784, 1024, 10),    # ... 280 tiles: 32 whole and 3 cut per XCD, k tiles not a multiple of the pieces
     (3, 1024, 112, 128, 4),      # ... 3 tiles: no multiple of 8, plain launch
+    (2, 50, 32, 1024, 4),        # 1024 hidden units: the head in one pass over H, 4 / 16 classes, ragged last trip
+    (1, 41, 16, 1024, 16),
+    (3, 8, 24, 1024, 10),        # ... exactly one trip of 8 rows per block
 ])
 def test_mlp_partition_gradients_match_oracle(ngc, n, rows, d_in, hidden, classes):
     import torch
