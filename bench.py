@@ -729,6 +729,8 @@ def bench_pipeline(args, w, wl, ngc, torch, np, K, W, cpu_leg=True, probe=True, 
                     "algorithmic_flops": flops,
                     "kernel": "mlp_gemm_kernel (whole MLP gradient call)", "avg_ms": round(grad_avg_ms, 4),
                     "launches": grad_launches}
+        if w.name == wl.C4.name:                      # the counters were taken at this workload's shape
+            with_traffic(roofline, "mlp_gemm_C4-mlp-n20.txt")
     else:
         grad_launches, grad_ms = prof["grad"]
         grad_avg_ms = grad_ms / max(1, grad_launches)
