@@ -29,7 +29,8 @@
 //   int   rowptr[L*n + 1] | int col[nnz] | float coef[nnz]      compressed rows, all layers
 //   u32   gmask[L*ng]                (64-byte aligned)  bit t: one of the columns 4t..4t+3 is in the
 //                                                       support of one of the workers 4g..4g+3
-//   float gcoef[L*ng][kp][4]         (64-byte aligned)  gcoef[(u*ng+g)*kp + j][r] = B^(u)[4g+r][j]
+//   float gcoef[L*ng][kp/4][4][4]    (64-byte aligned)  gcoef[u*ng+g][j/4][r][j%4] = B^(u)[4g+r][j]: per trip
+//                                                       of four columns, worker r's four coefficients together
 // ng = ceil(n/4) groups of four workers, kp = k rounded up to a multiple of 4; rows and
 // columns that do not exist hold zeros.
 // ---------------------------------------------------------------------------
@@ -72,7 +73,7 @@ static int upload_code(ngc_ctx* ctx) {
                 col[at] = lc.col[t];
                 coef[at] = (float)lc.coef[t];
                 gmask[(size_t)u * ng + g] |= 1u << (lc.col[t] / 4);
-                gcoef[(((size_t)u * ng + g) * kp + lc.col[t]) * 4 + r] = (float)lc.coef[t];
+                gcoef[((size_t)u * ng + g) * kp * 4 + (size_t)(lc.col[t] / 4) * 16 + r * 4 + lc.col[t] % 4] = (float)lc.coef[t];
                 ++at;
             }
         }

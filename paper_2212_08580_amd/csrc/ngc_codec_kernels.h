@@ -60,72 +60,72 @@ __device__ __forceinline__ void tile_land(VT* tile, const tile_regs<VT>& t, int 
 }
 
 // Messages of the four workers of one group under one layer for this lane's columns:
-//   m[r] = sum_j cf[j][r] * tile[j]   in ascending j, one fused multiply-add per term.
-// cf and cmask are wave-uniform (scalar loads); four columns of B are taken per trip, bit t of
+//   m[r] = sum_j B[4g+r][j] * tile[j]   in ascending j, one fused multiply-add per term,
+// on the matrix cores: v_mfma_f32_4x4x1_16B_f32 multiplies, in each of its sixteen blocks of
+// four lanes, a column of four values (lane 4b+r holds coefficient r) by a row of four values
+// (lane l holds its own tile element) and adds the 4 x 4 products to the accumulators, register
+// r of lane l <- coefficient r times the element of lane l: one product per output and
+// instruction, rounded once like a scalar fused multiply-add (checked bit for bit against fmaf,
+// denormals included), four workers' terms per instruction at twice the vector pipe's rate.
+// So lane l feeds coefficient l % 4 of the column, every lane gets all four messages, and the
+// order of additions is the canonical one.
+// cf holds the group's coefficients in trips of four columns, cf[jc*16 + r*4 + t] =
+// B[4g+r][4jc+t]: one 16-byte load per lane and trip (component t = column 4jc+t).  Bit t of
 // cmask says whether columns 4t..4t+3 touch the group's supports at all (a trip that does not
 // is skipped).  The coefficients and tile rows of the next trip are requested before the
 // multiply-adds of the current one are issued.
 template <typename VT>
 __device__ __forceinline__ void load_trip(const VT* tile, int lane, const float* __restrict__ cf, int jc,
-                                          float (&w)[16], VT (&x)[4]) {
-#pragma unroll
-    for (int t = 0; t < 16; ++t) w[t] = cf[jc * 16 + t];
+                                          v4f& w, VT (&x)[4]) {
+    w = *reinterpret_cast<const v4f*>(cf + jc * 16 + (lane & 3) * 4);
 #pragma unroll
     for (int t = 0; t < 4; ++t) x[t] = tile[(4 * jc + t) * 64 + lane];
 }
 
-// ROWS: bit r set = message r of the group is wanted (a straggler's message is not formed)
-template <typename VT, int ROWS>
-__device__ __forceinline__ void fma_trip(const float (&w)[16], const VT (&x)[4], VT (&m)[4]) {
+// acc[v]: the four messages' element v of this lane
+template <typename VT, int V>
+__device__ __forceinline__ void fma_trip(const v4f& w, const VT (&x)[4], v4f (&acc)[V]) {
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-            if ((ROWS >> r) & 1) m[r] = ngc_fma(w[t * 4 + r], x[t], m[r]);
+        for (int v = 0; v < V; ++v)
+            acc[v] = __builtin_amdgcn_mfma_f32_4x4x1f32(w[t], ngc_get(x[t], v), acc[v], 0, 0, 0);
 }
 
 // Two register sets take the trips in turn, so the loads of the next trip are in flight during
 // the multiply-adds of the current one without any copy between them.
-template <typename VT, int ROWS>
+template <typename VT, int V>
 __device__ __forceinline__ void group_messages(const VT* tile, int lane, const float* __restrict__ cf,
                                                unsigned cmask, VT (&m)[4]) {
+    v4f acc[V];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) m[r] = (VT)(0.0f);
-    if (cmask == 0) return;
-    float wa[16], wb[16];
-    VT xa[4], xb[4];
-    load_trip<VT>(tile, lane, cf, __builtin_ctz(cmask), wa, xa);
-    cmask &= cmask - 1;
-    for (;;) {
-        if (cmask == 0) {
-            fma_trip<VT, ROWS>(wa, xa, m);
-            break;
-        }
-        load_trip<VT>(tile, lane, cf, __builtin_ctz(cmask), wb, xb);
-        cmask &= cmask - 1;
-        fma_trip<VT, ROWS>(wa, xa, m);
-        if (cmask == 0) {
-            fma_trip<VT, ROWS>(wb, xb, m);
-            break;
-        }
+    for (int v = 0; v < V; ++v) acc[v] = (v4f)(0.0f);
+    if (cmask != 0) {
+        v4f wa, wb;
+        VT xa[4], xb[4];
         load_trip<VT>(tile, lane, cf, __builtin_ctz(cmask), wa, xa);
         cmask &= cmask - 1;
-        fma_trip<VT, ROWS>(wb, xb, m);
+        for (;;) {
+            if (cmask == 0) {
+                fma_trip<VT, V>(wa, xa, acc);
+                break;
+            }
+            load_trip<VT>(tile, lane, cf, __builtin_ctz(cmask), wb, xb);
+            cmask &= cmask - 1;
+            fma_trip<VT, V>(wa, xa, acc);
+            if (cmask == 0) {
+                fma_trip<VT, V>(wb, xb, acc);
+                break;
+            }
+            load_trip<VT>(tile, lane, cf, __builtin_ctz(cmask), wa, xa);
+            cmask &= cmask - 1;
+            fma_trip<VT, V>(wb, xb, acc);
+        }
     }
-}
-
-// The same with the wanted rows known only at run time (wave-uniform): one of sixteen variants.
-template <typename VT>
-__device__ __forceinline__ void group_messages_rows(const VT* tile, int lane, const float* __restrict__ cf,
-                                                    unsigned cmask, int rows, VT (&m)[4]) {
-    switch (rows) {
-#define NGC_ROWS_CASE(R) case R: group_messages<VT, R>(tile, lane, cf, cmask, m); break;
-        NGC_ROWS_CASE(1) NGC_ROWS_CASE(2) NGC_ROWS_CASE(3) NGC_ROWS_CASE(4) NGC_ROWS_CASE(5)
-        NGC_ROWS_CASE(6) NGC_ROWS_CASE(7) NGC_ROWS_CASE(8) NGC_ROWS_CASE(9) NGC_ROWS_CASE(10)
-        NGC_ROWS_CASE(11) NGC_ROWS_CASE(12) NGC_ROWS_CASE(13) NGC_ROWS_CASE(14) NGC_ROWS_CASE(15)
-#undef NGC_ROWS_CASE
-        default: break;
-    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int v = 0; v < V; ++v) ngc_set(m[r], v, acc[v][r]);
 }
 
 // ---------------------------------------------------------------------------
@@ -158,7 +158,7 @@ __global__ __launch_bounds__(ENC_WAVES * 64) void encode_kernel(const float* __r
         const int g = t / layer_count;
         const int ug = u * ng + g;
         VT m[4];
-        group_messages<VT, 15>(tile, lane, gcoef + (size_t)ug * kp * 4, gmask[ug], m);
+        group_messages<VT, V>(tile, lane, gcoef + (size_t)ug * kp * 4, gmask[ug], m);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int i = 4 * g + r;
@@ -366,15 +366,15 @@ __global__ __launch_bounds__(256) void coded_rounds_kernel(
             for (int g = wave; g < ng; g += 4) {
                 const int ug = layer * ng + g;
                 double av[4];
-                int rows = 0;
+                bool any = false;
 #pragma unroll
                 for (int rr = 0; rr < 4; ++rr) {
                     av[rr] = SINGLE ? one.a[4 * g + rr] : recs[r].a[4 * g + rr];  // index < NGC_MAX_N; zero beyond n
-                    rows |= (av[rr] != 0.0) << rr;
+                    any = any || av[rr] != 0.0;
                 }
-                if (rows == 0) continue;  // wave-uniform: four stragglers in a row
+                if (!any) continue;  // wave-uniform: four stragglers in a row
                 VT m[4];
-                group_messages_rows<VT>(tile, lane, gcoef + (size_t)ug * kp * 4, gmask[ug], rows, m);
+                group_messages<VT, V>(tile, lane, gcoef + (size_t)ug * kp * 4, gmask[ug], m);
 #pragma unroll
                 for (int rr = 0; rr < 4; ++rr) {
                     if (av[rr] != 0.0) {  // wave-uniform

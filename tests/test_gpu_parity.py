@@ -762,6 +762,51 @@ def test_fused_iteration_equals_separate_calls(ngc, torch_dev, base, n, c, rows,
         ngc.ngc_destroy(ctx)
 
 
+def test_messages_of_subnormal_gradients(ngc, torch_dev):
+    """Partial gradients below the smallest normal fp32 number: the stand-alone encode forms its
+    messages on the matrix cores, the tail of ngc_iteration with scalar fused multiply-adds; both
+    must keep subnormal terms (no flush to zero), give the same bits, and match the oracle to the
+    spacing of subnormal numbers."""
+    torch = torch_dev
+    dev = torch.device("cuda:0")
+    n, rows, d, layers = 8, 6, 256, (0, 1, 3)
+    w = wl.C3.scaled(rows=rows, d=d, n=n, layers=layers)
+    X, Y = wl.dataset(w, seed=3, threads=1)
+    X = (X.astype(np.float64) * 1e-40).astype(np.float32)           # subnormal features
+    assert np.all(np.abs(X) < 1.1754944e-38) and np.count_nonzero(X) > X.size // 2
+    th = wl.theta(w, seed=1)
+    Bs = codes.nested_code(n, layers, "cyclic", seed=0, draws=2)
+    ctx = ngc.ngc_create(n, n, layers, d, torch.cuda.current_stream().cuda_stream)
+    try:
+        for u, B in enumerate(Bs):
+            ngc.ngc_set_code(ctx, u, B)
+        Xd, Yd = torch.from_numpy(X).to(dev), torch.from_numpy(Y).to(dev)
+        L = len(layers)
+        thd = torch.from_numpy(th).to(dev)
+        G0 = torch.empty((n, d), dtype=torch.float32, device=dev)
+        C0 = torch.empty((L, n, d), dtype=torch.float32, device=dev)
+        G1, C1 = torch.empty_like(G0), torch.empty_like(C0)
+        g1 = torch.empty(d, dtype=torch.float32, device=dev)
+        ngc.ngc_partition_grads(ctx, w.loss, Xd, Yd, thd, rows, G0)
+        ngc.ngc_encode(ctx, G0, -1, C0)
+        ngc.ngc_iteration(ctx, w.loss, Xd, Yd, thd, rows, np.zeros(n, np.uint8), 0.0, G1, C1, g1, n)
+        ngc.ngc_sync(ctx)
+        assert torch.equal(G0, G1) and torch.equal(C0, C1)
+        G, C = G0.cpu().numpy(), C0.cpu().numpy()
+        tiny = 1.1754944e-38
+        assert np.count_nonzero((np.abs(G) > 0) & (np.abs(G) < tiny)) > G.size // 2
+        assert np.count_nonzero((np.abs(C[L - 1]) > 0) & (np.abs(C[L - 1]) < tiny)) > C[L - 1].size // 2
+        G_o = gradients.partial_gradients(w.loss, X, Y, th)
+        ulp = 2.0 ** -149                                            # spacing of subnormal fp32
+        assert np.max(np.abs(G - G_o)) <= 4 * rows * ulp
+        for u in range(L):
+            C_o = coding.encode(Bs[u], G.astype(np.float64))         # from the GPU's G: the encode alone
+            bound = (np.abs(Bs[u]) @ np.ones(n)).max() * (layers[u] + 2) * ulp
+            assert np.max(np.abs(C[u] - C_o)) <= bound
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
 # --------------------------------------------------------------------------------------------
 # C2 at full size: logistic regression, n = 16, 16 x 8192 rows, d = 1024, layers 0,1,3,7,
 # 200 descent iterations with Bernoulli(0.2) stragglers, through ngc_iteration
