@@ -224,8 +224,10 @@ int ngc_encode_decode(ngc_ctx* ctx, const float* G_dev, int layer, const double*
  * ngc_select_decode_vec) is done on the host, the vectors go to the device as a table, and a
  * kernel forms, for every round of its run, the messages of that round's layer for its
  * responders and the recovered gradient, exactly as ngc_encode_decode does (same bits).  Up
- * to 511 rounds are one run; more go in runs of 256, one launch each, the host solving for
- * the next run while the device works on the current one:
+ * to 255 rounds are one run; more go as a first run of 64 (so that the device starts early)
+ * and runs of 256 after it, one launch each, the host solving for the next run while the
+ * device works on the current one; a run's table travels on a stream of the library's own
+ * and its kernel, on the context's stream, waits for it:
  *   G of round r  = G_dev + r * g_round_stride   (float [k][d]; stride 0: one G for all rounds,
  *                                                 read from HBM once per block, else >= k*d)
  *   messages      -> M_dev + r * m_round_stride  (float [n][d]; stride >= n*d)
@@ -235,7 +237,8 @@ int ngc_encode_decode(ngc_ctx* ctx, const float* G_dev, int layer, const double*
  * message and is not an error.  a_out (double [rounds][n], may be NULL) receives the decode
  * vectors.  NGC_ERR_SINGULAR if a round's residual is above tolerance: the run that holds the
  * round and the runs after it are not launched (earlier runs are).  The host part uses a few
- * threads when the solves are worth them; the call returns when the last kernel is enqueued.
+ * threads, kept by the context between calls, when the solves are worth them; the call
+ * returns when the last kernel is enqueued.  Not for use under stream capture.
  */
 int ngc_coded_rounds(ngc_ctx* ctx, const float* G_dev, int64_t g_round_stride, int rounds,
                      const uint8_t* masks_host, float* M_dev, int64_t m_round_stride, float* g_dev,

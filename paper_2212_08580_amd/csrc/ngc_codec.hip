@@ -276,7 +276,9 @@ extern "C" int ngc_encode_decode(ngc_ctx* ctx, const float* G_dev, int layer, co
 // room for `count` round records in the device table and its pinned staging copy
 static int ensure_rounds(ngc_ctx* ctx, size_t count) {
     if (!ctx->rounds_ev) NGC_HIP(ctx, hipEventCreateWithFlags(&ctx->rounds_ev, hipEventDisableTiming));
+    if (!ctx->rounds_copy_stream) NGC_HIP(ctx, hipStreamCreateWithFlags(&ctx->rounds_copy_stream, hipStreamNonBlocking));
     if (count <= ctx->rounds_cap) return NGC_OK;
+    NGC_HIP(ctx, hipStreamSynchronize(ctx->rounds_copy_stream));
     NGC_HIP(ctx, hipStreamSynchronize(ctx->stream));
     if (ctx->d_rounds) NGC_HIP(ctx, hipFree(ctx->d_rounds));
     if (ctx->h_rounds) NGC_HIP(ctx, hipHostFree(ctx->h_rounds));
@@ -323,6 +325,7 @@ extern "C" int ngc_coded_rounds(ngc_ctx* ctx, const float* G_dev, int64_t g_roun
     // main-node bookkeeping of every round up front (Observation after Def. 2; Def. 1): layer and
     // least-norm decode vector per mask, shared out over a few host threads
     std::vector<int> status((size_t)rounds, NGC_OK);
+    std::atomic<bool> failed(false);
     auto plan = [&](int lo, int hi) {
         for (int r = lo; r < hi; ++r) {
             round_rec& rec = recs[r];
@@ -340,47 +343,67 @@ extern "C" int ngc_coded_rounds(ngc_ctx* ctx, const float* G_dev, int64_t g_roun
             rec.layer = layer;
         }
     };
-    // The rounds go to the device in runs of 256: while the kernel of one run works, the host
-    // solves for the next.  A solve costs about n^2 / 1500 microseconds; a thread is worth starting
-    // per quarter of a millisecond of such work over the whole call (starting and joining one costs
-    // tens of microseconds, far more on a host whose cores are busy), so small jobs stay on the
-    // calling thread.  Threads are started once; each takes its share of every run and counts
-    // itself done per run, the calling thread takes a share too, waits for the others, copies the
-    // run's records and launches.
-    const int run = rounds >= 512 ? 256 : rounds;
-    const int nruns = (rounds + run - 1) / run;
+    // The rounds go to the device in runs: a first short one of 64, so that the device starts
+    // early, then runs of 256; while the kernel of one run works, the host solves for the next.
+    // A round's bookkeeping costs about 0.3 + n^2 / 1500 microseconds; a pool thread (kept by the context, asleep
+    // between calls) is worth waking per 40 microseconds of such work over the whole call, so
+    // small jobs stay on the calling thread.  Each thread takes its share of every run and
+    // counts itself done per run; the calling thread takes a share too, waits for the others,
+    // copies the run's records and launches.
+    std::vector<int> bounds{0};
+    if (rounds >= 256) bounds.push_back(64);
+    while (bounds.back() < rounds) bounds.push_back(std::min(rounds, bounds.back() + 256));
+    const int nruns = (int)bounds.size() - 1;
     const unsigned hw = std::max(1u, std::thread::hardware_concurrency());
-    const double work_us = (double)rounds * ctx->n * ctx->n / 1500.0;
-    const int nthreads = (int)std::min<double>(std::min(hw, 16u), std::max(1.0, work_us / 250.0));
+    const double work_us = (double)rounds * (0.3 + ctx->n * ctx->n / 1500.0);
+    const int nthreads = (int)std::min<double>(std::min(hw, 16u), std::max(1.0, work_us / 40.0));
     std::unique_ptr<std::atomic<int>[]> done(new std::atomic<int>[nruns]);
     for (int c = 0; c < nruns; ++c) done[c].store(0);
-    auto share = [&](int tid) {
-        for (int c = 0; c < nruns; ++c) {
-            const int lo = c * run, hi = std::min(rounds, lo + run);
-            const int per = (hi - lo + nthreads - 1) / nthreads;
-            plan(std::min(hi, lo + tid * per), std::min(hi, lo + (tid + 1) * per));
-            done[c].fetch_add(1, std::memory_order_release);
-        }
+    auto share_of_run = [&](int c, int tid) {
+        const int lo = bounds[c], hi = bounds[c + 1];
+        const int per = (hi - lo + nthreads - 1) / nthreads;
+        plan(std::min(hi, lo + tid * per), std::min(hi, lo + (tid + 1) * per));
+        done[c].fetch_add(1, std::memory_order_release);
     };
-    std::vector<std::thread> pool;
-    for (int t = 1; t < nthreads; ++t) pool.emplace_back(share, t);
-    struct joiner {
-        std::vector<std::thread>& p;
-        ~joiner() {
-            for (auto& th : p)
-                if (th.joinable()) th.join();
+    // the pool's threads are waited for on every way out: they work on this call's arrays
+    struct pool_guard {
+        ngc_host_pool* p = nullptr;
+        ~pool_guard() {
+            if (p) p->wait();
         }
-    } join_all{pool};
+    } guard;
+    if (nthreads > 1) {
+        if (!ctx->pool) ctx->pool.reset(new ngc_host_pool);
+        ctx->pool->start(nthreads - 1, [&](int tid) {
+            int c = 0;
+            try {
+                for (; c < nruns; ++c) share_of_run(c, tid);
+            } catch (...) {
+                // out of memory inside a solve: its rounds stay unplanned, the call fails; the
+                // runs this thread has not counted itself done for are counted now
+                failed.store(true);
+                for (; c < nruns; ++c) done[c].fetch_add(1, std::memory_order_release);
+            }
+        });
+        guard.p = ctx->pool.get();
+    }
+    // Records are copied on the library's own stream: it first waits for what the caller's
+    // stream holds now (kernels of an earlier call may still read the table), then a run's copy
+    // can overlap the kernel of the run before it; the kernel waits for its run's copy.
+    while ((int)ctx->rounds_run_ev.size() < nruns + 1) {
+        hipEvent_t e = nullptr;
+        NGC_HIP(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        ctx->rounds_run_ev.push_back(e);
+    }
+    NGC_HIP(ctx, hipEventRecord(ctx->rounds_run_ev[nruns], ctx->stream));
+    NGC_HIP(ctx, hipStreamWaitEvent(ctx->rounds_copy_stream, ctx->rounds_run_ev[nruns], 0));
     round_rec none;
     std::memset(&none, 0, sizeof(none));
     for (int c = 0; c < nruns; ++c) {
-        const int lo = c * run, hi = std::min(rounds, lo + run);
-        {
-            const int per = (hi - lo + nthreads - 1) / nthreads;
-            plan(lo, std::min(hi, lo + per));
-            done[c].fetch_add(1, std::memory_order_release);
-        }
+        const int lo = bounds[c], hi = bounds[c + 1];
+        share_of_run(c, 0);
         while (done[c].load(std::memory_order_acquire) < nthreads) std::this_thread::yield();
+        if (failed.load()) return ngc_fail(ctx, NGC_ERR_NOMEM, "out of host memory while planning the rounds");
         for (int r = lo; r < hi; ++r) {
             if (status[r] != NGC_OK)
                 return ngc_fail(ctx, status[r], status[r] == NGC_ERR_STATE ? "a chosen layer has no code yet"
@@ -389,9 +412,11 @@ extern "C" int ngc_coded_rounds(ngc_ctx* ctx, const float* G_dev, int64_t g_roun
             if (a_out) std::memcpy(a_out + (size_t)r * n, recs[r].a, sizeof(double) * n);
         }
         round_rec* d_recs = (round_rec*)ctx->d_rounds + lo;
-        NGC_HIP(ctx, hipMemcpyAsync(d_recs, recs + lo, sizeof(round_rec) * (size_t)(hi - lo), hipMemcpyHostToDevice, ctx->stream));
-        NGC_HIP(ctx, hipEventRecord(ctx->rounds_ev, ctx->stream));
+        NGC_HIP(ctx, hipMemcpyAsync(d_recs, recs + lo, sizeof(round_rec) * (size_t)(hi - lo), hipMemcpyHostToDevice, ctx->rounds_copy_stream));
+        NGC_HIP(ctx, hipEventRecord(ctx->rounds_run_ev[c], ctx->rounds_copy_stream));
+        NGC_HIP(ctx, hipEventRecord(ctx->rounds_ev, ctx->rounds_copy_stream));  // the staging copy is free after this
         ctx->rounds_ev_set = true;
+        NGC_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->rounds_run_ev[c], 0));
         if (g_round_stride != 0)
             rc = launch_rounds<ROUNDS_G_PER_ROUND>(ctx, G_dev + (int64_t)lo * g_round_stride, g_round_stride,
                                                    M_dev + (int64_t)lo * m_round_stride, m_round_stride,

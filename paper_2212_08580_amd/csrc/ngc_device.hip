@@ -55,6 +55,13 @@ void ngc_dev_release(ngc_ctx* ctx) {
     if (ctx->d_rounds) (void)hipFree(ctx->d_rounds);
     if (ctx->h_rounds) (void)hipHostFree(ctx->h_rounds);
     if (ctx->rounds_ev) (void)hipEventDestroy(ctx->rounds_ev);
+    if (ctx->rounds_copy_stream) {
+        (void)hipStreamSynchronize(ctx->rounds_copy_stream);
+        (void)hipStreamDestroy(ctx->rounds_copy_stream);
+    }
+    ctx->rounds_copy_stream = nullptr;
+    for (auto e : ctx->rounds_run_ev) (void)hipEventDestroy(e);
+    ctx->rounds_run_ev.clear();
     ctx->d_rounds = ctx->h_rounds = nullptr;
     ctx->rounds_ev = nullptr;
     ctx->rounds_ev_set = false;

@@ -5,10 +5,12 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <memory>
 #include <string>
 #include <vector>
 
 #include "../../include/ngc.h"
+#include "ngc_host_pool.h"
 
 constexpr int NGC_MAX_N = 64;
 constexpr int NGC_MAX_PROFILE = 4096;
@@ -70,6 +72,11 @@ struct ngc_ctx {
     size_t rounds_cap = 0;           // records both hold
     hipEvent_t rounds_ev = nullptr;
     bool rounds_ev_set = false;
+    // the records travel on a stream of the library's own (default priority), so that a run's
+    // copy overlaps the kernel of the run before it; one event per run orders kernel after copy
+    hipStream_t rounds_copy_stream = nullptr;
+    std::vector<hipEvent_t> rounds_run_ev;
+    std::unique_ptr<ngc_host_pool> pool;  // host threads for the bookkeeping of many rounds, created on first need
     float* d_ws = nullptr;           // workspace: block partials / residuals / MLP activations
     size_t d_ws_bytes = 0;
     // worker mode: unit -> partition / output-row maps, two copies used in turn so that a call
