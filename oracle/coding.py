@@ -16,6 +16,15 @@ Readings:
 * The layer used is the smallest tolerance s_u >= number of stragglers (the
   Observation after Def. 2); more stragglers than s_max cannot be decoded
   (Theorem 1 sums failures only up to s_max).
+* Guarded layer choice (an option, off unless asked for): every component code
+  with s_v >= number of stragglers recovers the gradient (Def. 1), and when all
+  responders hold all their layers' messages the main node is free to take a
+  larger one.  With exactly s_u stragglers the layer-u decode vector is the only
+  one there is and can be huge for a real-valued code; the guard then moves up
+  to the first layer whose estimated amplification of message rounding,
+  kappa_hat = sum_i |a_i| ||b_i||_2 / sqrt(k)  (what `conditioning` gives for
+  partial gradients with independent entries of equal variance), is within a
+  limit, and to the layer of smallest kappa_hat if none is.
 """
 import numpy as np
 
@@ -73,6 +82,28 @@ def conditioning(a, C, g):
     messages (relative size eps each) shows up in the decoded vector."""
     C = np.asarray(C, np.float64)
     return float(np.abs(a) @ np.linalg.norm(C, axis=1) / max(np.linalg.norm(g), 1e-300))
+
+
+def amplification(B, a):
+    """kappa_hat = sum_i |a_i| ||b_i||_2 / sqrt(k) for the decode vector a of the code B."""
+    B = np.asarray(B, np.float64)
+    return float(np.abs(np.asarray(a, np.float64)) @ np.linalg.norm(B, axis=1) / np.sqrt(B.shape[1]))
+
+
+def select_guarded(Bs, layers, mask, kappa_limit):
+    """(u, a): the smallest layer u with s_u >= #stragglers whose decode vector has
+    kappa_hat <= kappa_limit; the layer of smallest kappa_hat (the lowest of them on a tie)
+    if no layer meets the limit.  kappa_limit = inf is the plain rule of `select_layer`."""
+    u0 = select_layer(layers, mask)
+    best = None
+    for u in range(u0, len(layers)):
+        a, _ = decode_vector(Bs[u], mask)
+        kh = amplification(Bs[u], a)
+        if kh <= kappa_limit:
+            return u, a
+        if best is None or kh < best[0]:
+            best = (kh, u, a)
+    return best[1], best[2]
 
 
 def coded_gradient(Bs, layers, G, mask, message_dtype=np.float64):

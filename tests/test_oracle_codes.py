@@ -281,3 +281,82 @@ def test_zero_padded_rows_do_not_change_the_gradient():
     assert np.allclose(og.lsq_gradient(Xp, yp, th), og.lsq_gradient(X, y, th), rtol=1e-14)
     ypm = np.concatenate([np.sign(y), np.ones(2)])
     assert np.allclose(og.logistic_gradient(Xp, ypm, th), og.logistic_gradient(X, np.sign(y), th), rtol=1e-14)
+
+
+# ---- guarded layer choice (an option on top of the Observation after Def. 2) ---------------
+def _kappa_hat_by_hand(B, mask):
+    """kappa_hat of the least-norm decode vector, written out with library routines only."""
+    S = np.flatnonzero(mask == 0)
+    aS = np.linalg.lstsq(B[S].T, np.ones(B.shape[1]), rcond=None)[0]
+    return float(np.abs(aS) @ np.sqrt((B[S] ** 2).sum(axis=1)) / np.sqrt(B.shape[1])), S, aS
+
+
+def test_guarded_choice_fracrep_closed_form():
+    # n = 4, layers (0, 1), block code 1100/1100/0011/0011, worker 0 straggles: the layer-1
+    # vector is (0, 1, 1/2, 1/2), every row has norm sqrt 2, k = 4:
+    # kappa_hat = (1 + 1/2 + 1/2) sqrt 2 / 2 = sqrt 2
+    Bs = codes.nested_code(4, [0, 1], "fracrep")
+    m = np.array([1, 0, 0, 0], np.uint8)
+    a, _ = coding.decode_vector(Bs[1], m)
+    assert np.isclose(coding.amplification(Bs[1], a), np.sqrt(2.0), atol=1e-12)
+    # no stragglers, layer 0 = identity: a = 1, rows of norm 1: kappa_hat = 4 / 2
+    assert np.isclose(coding.amplification(Bs[0], np.ones(4)), 2.0, atol=1e-12)
+    # a limit nobody meets: the layer of smallest kappa_hat among the sufficient ones;
+    # without stragglers layer 1 gives a = 1/2 each, kappa_hat = 4 (1/2) sqrt 2 / 2 = sqrt 2 < 2
+    u, a = coding.select_guarded(Bs, [0, 1], np.zeros(4, np.uint8), 0.1)
+    assert u == 1 and np.allclose(a, 0.5)
+    u, a = coding.select_guarded(Bs, [0, 1], np.zeros(4, np.uint8), 2.0)      # layer 0 meets the limit
+    assert u == 0 and np.allclose(a, 1.0)
+    with pytest.raises(coding.Undecodable):
+        coding.select_guarded(Bs, [0, 1], np.array([1, 1, 0, 0], np.uint8), 1e9)
+
+
+def test_guarded_choice_without_a_limit_is_the_plain_rule():
+    layers = [0, 1, 3]
+    Bs = codes.nested_code(8, layers, "cyclic", seed=2, draws=2)
+    for m in _masks(8, 3):
+        u, a = coding.select_guarded(Bs, layers, m, np.inf)
+        assert u == coding.select_layer(layers, m)
+        assert np.array_equal(a, coding.decode_vector(Bs[u], m)[0])
+
+
+@pytest.mark.parametrize("limit", [0.5, 1.5, 3.0, 10.0])
+def test_guarded_choice_rule_by_brute_force(limit):
+    """Every mask of a small nested code: the result decodes (Def. 1), lies at or above the
+    smallest sufficient layer, and is the first layer within the limit, else the best one."""
+    layers = [0, 1, 2, 4]
+    n = 7
+    Bs = codes.nested_code(n, layers, "cyclic", seed=5, draws=2)
+    moved = 0
+    for m in _masks(n, 4):
+        u, a = coding.select_guarded(Bs, layers, m, limit)
+        u0 = min(v for v, s in enumerate(layers) if s >= int(m.sum()))
+        assert u >= u0
+        assert np.all(a[m == 1] == 0.0) and np.allclose(a @ Bs[u], 1.0, atol=1e-9)
+        kh = [_kappa_hat_by_hand(Bs[v], m)[0] for v in range(u0, len(layers))]
+        within = [v for v, x in zip(range(u0, len(layers)), kh) if x <= limit]
+        want = within[0] if within else u0 + int(np.argmin(kh))
+        assert u == want
+        _, S, aS = _kappa_hat_by_hand(Bs[u], m)
+        assert np.allclose(a[S], aS, atol=1e-9)
+        moved += u != u0
+    assert limit >= 10.0 or moved > 0          # tight limits do move rounds up
+
+
+def test_guarded_choice_tames_the_tail_of_a_random_code():
+    """n = 16, sigma = 7, exactly 7 stragglers: the worst sets of a random real-valued code
+    amplify rounding by orders of magnitude more than the same sets one layer up."""
+    layers = [0, 1, 3, 7, 11]
+    Bs = codes.nested_code(16, layers, "cyclic", seed=0, draws=2)
+    rng = np.random.default_rng(1)
+    plain, guarded = [], []
+    for _ in range(300):
+        m = np.zeros(16, np.uint8)
+        m[rng.choice(16, size=7, replace=False)] = 1
+        a0, _ = coding.decode_vector(Bs[3], m)
+        plain.append(coding.amplification(Bs[3], a0))
+        u, a = coding.select_guarded(Bs, layers, m, 50.0)
+        guarded.append(coding.amplification(Bs[u], a))
+        assert np.allclose(a @ Bs[u], 1.0, atol=1e-8)
+    assert max(plain) > 20 * max(guarded)
+    assert max(guarded) <= 50.0

@@ -90,6 +90,46 @@ def test_layer_choice_and_decode_mistakes_are_caught(monkeypatch):
     assert fails(pins_codes.test_fracrep_worked_case_matches_golden)
 
 
+def test_guarded_choice_mistakes_are_caught(monkeypatch):
+    good_amp = coding.amplification
+    # row norms left out of the estimate
+    monkeypatch.setattr(coding, "amplification", lambda B, a: float(np.abs(a).sum() / np.sqrt(np.asarray(B).shape[1])))
+    assert fails(pins_codes.test_guarded_choice_fracrep_closed_form)
+    monkeypatch.undo()
+    # divided by k instead of its root
+    monkeypatch.setattr(coding, "amplification", lambda B, a: good_amp(B, a) / np.sqrt(np.asarray(B).shape[1]))
+    assert fails(pins_codes.test_guarded_choice_fracrep_closed_form)
+    monkeypatch.undo()
+
+    def always_best(Bs, layers, mask, limit):                  # ignores the limit: always the best layer
+        u0 = coding.select_layer(layers, mask)
+        cand = [(good_amp(Bs[u], coding.decode_vector(Bs[u], mask)[0]), u) for u in range(u0, len(layers))]
+        u = min(cand)[1]
+        return u, coding.decode_vector(Bs[u], mask)[0]
+    monkeypatch.setattr(coding, "select_guarded", always_best)
+    assert fails(pins_codes.test_guarded_choice_without_a_limit_is_the_plain_rule)
+    monkeypatch.undo()
+
+    def never_moves(Bs, layers, mask, limit):
+        u = coding.select_layer(layers, mask)
+        return u, coding.decode_vector(Bs[u], mask)[0]
+    monkeypatch.setattr(coding, "select_guarded", never_moves)
+    assert fails(pins_codes.test_guarded_choice_rule_by_brute_force, 1.5)
+    assert fails(pins_codes.test_guarded_choice_tames_the_tail_of_a_random_code)
+    monkeypatch.undo()
+
+    def last_within(Bs, layers, mask, limit):                  # the highest layer within the limit, not the first
+        u0 = coding.select_layer(layers, mask)
+        pick = None
+        for u in range(u0, len(layers)):
+            a = coding.decode_vector(Bs[u], mask)[0]
+            if good_amp(Bs[u], a) <= limit:
+                pick = (u, a)
+        return pick if pick else never_moves(Bs, layers, mask, limit)
+    monkeypatch.setattr(coding, "select_guarded", last_within)
+    assert fails(pins_codes.test_guarded_choice_rule_by_brute_force, 3.0)
+
+
 def test_worker_rule_mistakes_are_caught(monkeypatch):
     good = workers.terminate
 
