@@ -222,6 +222,26 @@ def bench_codec(args, w, wl, ngc, torch, np, rounds=None, cpu_leg=True):
     parity["code"] = "ngc_build_code(seed 0), read back with ngc_get_code and handed to the oracle"
     parity["def1_residual_max"] = def1_residual(np, Bs, w.layers)
     del M_sel, g_sel
+    # every round's recovered gradient against the exact sum of the partial gradients (fp64, host),
+    # with the paper's layer rule (what was timed) and once more with the guarded layer choice
+    full = G64.sum(axis=0)
+
+    def all_round_errors(layers_chosen):
+        gh_h = gh.cpu().numpy().astype(np.float64)
+        e = np.linalg.norm(gh_h - full, axis=1) / np.linalg.norm(full)
+        return e[layers_chosen >= 0]
+    e_plain = all_round_errors(lay)
+    parity["all_rounds"] = {"rounds": int(e_plain.size), "decoded_rel_l2_max": float(e_plain.max()),
+                            "share_within_1e-4": float(np.mean(e_plain <= 1e-4))}
+    if not args.only_timed:
+        ngc.ngc_set_decode_guard(ctx, 1000.0)
+        lay_g, _ = ngc.ngc_coded_rounds(ctx, G, 0, masks, M, n * d, gh)
+        torch.cuda.synchronize()
+        ngc.ngc_set_decode_guard(ctx, 0.0)
+        e_guard = all_round_errors(lay_g)
+        parity["all_rounds_guarded_choice"] = {
+            "kappa_limit": 1000.0, "rounds": int(e_guard.size), "rounds_moved_up": int(np.count_nonzero(lay_g != lay)),
+            "decoded_rel_l2_max": float(e_guard.max()), "share_within_1e-4": float(np.mean(e_guard <= 1e-4))}
 
     side = not args.only_timed
     # ---- the same rounds with a G of its own per round (streamed from HBM) --------------------

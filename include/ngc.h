@@ -188,6 +188,25 @@ int ngc_select_decode_vec(const ngc_ctx* ctx, const uint8_t* straggler_mask, int
                           double* a_out, double* residual_out);
 
 /*
+ * Guarded layer choice (an option; off by default, and then the rule above holds as stated).
+ * Every component code with s[v] >= number of stragglers recovers the gradient (Def. 1), and a
+ * main node whose responders hold the messages of all their layers may take a larger one.
+ * With exactly s[u] stragglers the layer-u decode vector is the only one there is, and for a
+ * real-valued code it can be large enough to lift the rounding of fp32 messages above a
+ * tolerance.  With a limit set, ngc_select_decode_vec, ngc_coded_rounds and ngc_iteration
+ * estimate that amplification for the vector they find,
+ *   kappa_hat = sum_i |a_i| ||b_i||_2 / sqrt(k)
+ * (the factor for partial gradients with independent entries of equal variance; the decoded
+ * gradient is then off by about 0.1 * 2^-24 * kappa_hat in relative 2-norm, 4 * 2^-24 *
+ * kappa_hat at most), and if it exceeds the limit move up to the first layer whose estimate is
+ * within it, or to the layer of smallest estimate if none is (the lowest of them on a tie).
+ * kappa_limit > 0 sets the limit; 0 or +infinity switches the guard off; negative or NaN is
+ * NGC_ERR_INVALID.  Not applied by ngc_select_decode_vec_first, ngc_select_from_progress
+ * (workers there have not computed the larger layers) or ngc_decode_lookup.
+ */
+int ngc_set_decode_guard(ngc_ctx* ctx, double kappa_limit);
+
+/*
  * Same bookkeeping with the decode vector supported on the n - s[u]
  * responders of lowest index only (a literal row of the decoding matrix of
  * Def. 1).

@@ -61,6 +61,12 @@ static void install_layer(ngc_ctx* ctx, int layer, const double* B) {
     lc.A_stale = true;
     lc.B.assign(B, B + (size_t)ctx->n * ctx->k);
     compress_layer(lc, ctx->n, ctx->k);
+    lc.row_norm.assign(ctx->n, 0.0);
+    for (int i = 0; i < ctx->n; ++i) {
+        double q = 0.0;
+        for (int j = 0; j < ctx->k; ++j) q += B[(size_t)i * ctx->k + j] * B[(size_t)i * ctx->k + j];
+        lc.row_norm[i] = std::sqrt(q);
+    }
     lc.a0.assign(ctx->n, 0.0);
     lc.N.assign((size_t)ctx->n * ctx->n, 0.0);
     double full_resid = 1.0;
@@ -437,6 +443,35 @@ int ngc_select_core(const ngc_ctx* ctx, const uint8_t* mask, int* layer_out, dou
     ngc_layer_decode_vec(ctx, u, rows, ns, a_out, &resid);
     if (residual_out) *residual_out = resid;
     if (!(resid <= 1e-6)) return NGC_ERR_SINGULAR;
+    // Guarded choice (off unless a limit is set): every component code with s_v >= #stragglers
+    // recovers the gradient (Def. 1); if the estimated amplification of message rounding at the
+    // smallest such layer exceeds the limit, the first layer above it within the limit is
+    // taken, else the layer of smallest estimate (the lowest on a tie).
+    if (!first_only && ctx->guard_limit > 0.0) {
+        auto kappa_hat = [&](int v, const double* a) {
+            double q = 0.0;
+            for (int i = 0; i < n; ++i) q += std::fabs(a[i]) * ctx->code[v].row_norm[i];
+            return q / std::sqrt((double)ctx->k);
+        };
+        double best = kappa_hat(u, a_out);
+        if (best > ctx->guard_limit) {
+            for (int v = u + 1; v < ctx->L; ++v) {
+                if (!ctx->code[v].set) return NGC_ERR_STATE;
+                double av[NGC_MAX_N] = {0.0};
+                double rv = 0.0;
+                ngc_layer_decode_vec(ctx, v, rows, ns, av, &rv);
+                if (!(rv <= 1e-6)) continue;  // this layer cannot decode the set numerically: not a candidate
+                const double kv = kappa_hat(v, av);
+                if (kv < best) {
+                    best = kv;
+                    *layer_out = v;
+                    for (int i = 0; i < n; ++i) a_out[i] = av[i];
+                    if (residual_out) *residual_out = rv;
+                }
+                if (kv <= ctx->guard_limit) break;
+            }
+        }
+    }
     return NGC_OK;
 }
 
@@ -451,6 +486,15 @@ static int select_impl(const ngc_ctx* ctx, const uint8_t* mask, int* layer_out, 
         case NGC_ERR_STATE: return ngc_fail(ctx, rc, "chosen layer has no code yet");
         default: return ngc_fail(ctx, rc, "decode residual above tolerance");
     }
+}
+
+extern "C" int ngc_set_decode_guard(ngc_ctx* ctx, double kappa_limit) try {
+    if (!ctx) return NGC_ERR_INVALID;
+    if (!(kappa_limit >= 0.0)) return ngc_fail(ctx, NGC_ERR_INVALID, "the limit must be positive, or 0 to switch the guard off");
+    ctx->guard_limit = std::isfinite(kappa_limit) ? kappa_limit : 0.0;  // no limit: the plain rule
+    return NGC_OK;
+} catch (...) {
+    return ngc_on_exception();
 }
 
 extern "C" int ngc_select_decode_vec(const ngc_ctx* ctx, const uint8_t* straggler_mask, int* layer_out,

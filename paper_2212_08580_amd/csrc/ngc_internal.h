@@ -29,6 +29,7 @@ struct ngc_layer_code {
     std::vector<int> rowptr;    // n + 1
     std::vector<int> col;
     std::vector<double> coef;
+    std::vector<double> row_norm;  // ||b_i||_2, n entries (guarded layer choice)
     // full-response factor for decode-vector selection (ngc_solve.cpp): least-norm a0 with
     // a0^T B = 1^T and an orthonormal basis N (n x q, row-major) of {v : v^T B = 0};
     // null_ok is false when B has no exact full-response solution
@@ -51,6 +52,7 @@ struct ngc_ctx {
     std::vector<int> s;
     hipStream_t stream = nullptr;
     std::vector<ngc_layer_code> code;
+    double guard_limit = 0.0;  // guarded layer choice: limit on kappa_hat, 0 = off (ngc_set_decode_guard)
 
     // MLP shape (NGC_LOSS_MLP2)
     int mlp_din = 0, mlp_hidden = 0, mlp_classes = 0;

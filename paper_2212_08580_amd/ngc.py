@@ -36,7 +36,7 @@ NGC_KERNEL_COUNT = len(NGC_KERNEL_NAMES)
 EXPORTS = (
     "ngc_create", "ngc_destroy", "ngc_set_code", "ngc_get_code", "ngc_get_shape", "ngc_build_code",
     "ngc_set_mlp2_shape", "ngc_partition_grads", "ngc_partition_grads_static", "ngc_encode", "ngc_select_decode_vec",
-    "ngc_select_decode_vec_first", "ngc_decode", "ngc_encode_decode", "ngc_coded_rounds", "ngc_update",
+    "ngc_select_decode_vec_first", "ngc_set_decode_guard", "ngc_decode", "ngc_encode_decode", "ngc_coded_rounds", "ngc_update",
     "ngc_iteration", "ngc_tail_lds_bytes", "ngc_sync",
     "ngc_worker_task_count", "ngc_worker_schedule", "ngc_worker_grads", "ngc_worker_encode",
     "ngc_select_from_progress", "ngc_build_decoding_table", "ngc_decoding_row_index",
@@ -63,6 +63,7 @@ _lib.ngc_build_code.argtypes = [_vp, _i, _u64]
 _lib.ngc_get_shape.argtypes = [_vp, ctypes.POINTER(_i), ctypes.POINTER(_i), ctypes.POINTER(_i),
                                ctypes.POINTER(_i64), ctypes.POINTER(_i)]
 _lib.ngc_set_mlp2_shape.argtypes = [_vp, _i, _i, _i]
+_lib.ngc_set_decode_guard.argtypes = [_vp, _dbl]
 _lib.ngc_partition_grads.argtypes = [_vp, _i, _vp, _vp, _vp, _i64, _vp]
 _lib.ngc_partition_grads_static.argtypes = _lib.ngc_partition_grads.argtypes
 _lib.ngc_encode.argtypes = [_vp, _vp, _i, _vp]
@@ -245,6 +246,11 @@ def _select(fn, ctx, mask, n):
 def ngc_select_decode_vec(ctx, mask, n):
     """-> (layer, a [n] fp64, residual)."""
     return _select(_lib.ngc_select_decode_vec, ctx, mask, n)
+
+
+def ngc_set_decode_guard(ctx, kappa_limit):
+    """Guarded layer choice: limit on the estimated amplification of message rounding; 0 = off."""
+    _check(_lib.ngc_set_decode_guard(ctx, float(kappa_limit)), ctx)
 
 
 def ngc_select_decode_vec_first(ctx, mask, n):

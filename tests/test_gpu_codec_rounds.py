@@ -65,10 +65,14 @@ def random_masks(rng, n, smax, rounds):
     return masks
 
 
-def oracle_round(Bs, layers, G64, mask):
-    """layer, decode vector, fp32-rounded messages of the layer, their fp64 combination, kappa."""
-    u = coding.select_layer(layers, mask)
-    a, _ = coding.decode_vector(Bs[u], mask)
+def oracle_round(Bs, layers, G64, mask, guard=None):
+    """layer, decode vector, fp32-rounded messages of the layer, their fp64 combination, kappa;
+    guard: limit of the guarded layer choice, None for the plain rule."""
+    if guard is None:
+        u = coding.select_layer(layers, mask)
+        a, _ = coding.decode_vector(Bs[u], mask)
+    else:
+        u, a = coding.select_guarded(Bs, layers, mask, guard)
     C = coding.encode(Bs[u], G64)
     C32 = C.astype(np.float32)
     g = coding.decode(a, C32)
@@ -125,9 +129,10 @@ def test_one_round_fused_equals_encode_then_decode(ngc, torch_dev, n, c, layers,
         ngc.ngc_destroy(ctx)
 
 
-def run_rounds(ngc, torch, ctx, w, Bs, G_h, masks, g_stride, check_messages_every=1, oracle_every=1):
+def run_rounds(ngc, torch, ctx, w, Bs, G_h, masks, g_stride, check_messages_every=1, oracle_every=1, guard=None):
     """ngc_coded_rounds over `masks`, checked round by round.  G_h: [k, d] (g_stride 0) or
-    [rounds, k, d].  Returns the decode errors against the exact gradient sum."""
+    [rounds, k, d].  guard: the limit set with ngc_set_decode_guard, if any.  Returns the decode
+    errors against the exact gradient sum."""
     dev = torch.device("cuda:0")
     n, d, layers = w.n, w.d, w.layers
     rounds = masks.shape[0]
@@ -150,7 +155,7 @@ def run_rounds(ngc, torch, ctx, w, Bs, G_h, masks, g_stride, check_messages_ever
             assert bool((gh[r] == 0.0).all()) and bool((M[r] == -7.0).all())
             continue
         u, a = int(lay[r]), a_all[r]
-        assert u == coding.select_layer(layers, mask)
+        assert u >= coding.select_layer(layers, mask) and (guard is not None or u == coding.select_layer(layers, mask))
         assert np.all(a[mask == 1] == 0)
         resp = np.flatnonzero(a != 0)
         ridx = torch.from_numpy(resp).to(dev)
@@ -167,7 +172,7 @@ def run_rounds(ngc, torch, ctx, w, Bs, G_h, masks, g_stride, check_messages_ever
                 assert bool((M[r][torch.from_numpy(out).to(dev)] == -7.0).all())
         if r % oracle_every == 0:
             G64 = Gr.astype(np.float64)
-            u_o, a_o, C_o, C32_o, g_o, kappa = oracle_round(Bs, layers, G64, mask)
+            u_o, a_o, C_o, C32_o, g_o, kappa = oracle_round(Bs, layers, G64, mask, guard)
             assert u == u_o and np.array_equal(a != 0, a_o != 0)
             Mh = M[r].cpu().numpy()
             worst_msg = max(worst_msg, max(rel(Mh[i], C_o[i]) for i in resp))
@@ -195,6 +200,29 @@ def test_coded_rounds_c5_all_1000_rounds(ngc, torch_dev):
         assert float(np.mean(errs > TOL)) <= 0.01
         parity_report(test="coded_rounds_c5", rounds=int(errs.size), median_decode_rel_l2=float(np.median(errs)),
                       worst_decode_rel_l2=float(errs.max()), share_above_1e_4=float(np.mean(errs > TOL)))
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
+def test_coded_rounds_c5_guarded_layer_choice(ngc, torch_dev):
+    """The same 1000 rounds with the guarded layer choice (limit 1000 on the estimated
+    amplification): the rounds whose only decode vector is huge move one layer up, layers and
+    supports are the oracle's guarded ones, and every round is within plain 1e-4."""
+    w = wl.C5
+    G_h = wl.partial_gradients(w, 0)
+    masks = wl.binomial_count_masks(w, 1000, seed=0)
+    ctx, Bs = library_code(ngc, torch_dev, w.n, w.layers, w.d)
+    try:
+        ngc.ngc_set_decode_guard(ctx, 1000.0)
+        errs = run_rounds(ngc, torch_dev, ctx, w, Bs, G_h, masks, 0, check_messages_every=10, guard=1000.0)
+        assert errs.size >= 990 and errs.max() <= TOL
+        moved = sum(coding.select_guarded(Bs, w.layers, m, 1000.0)[0] != coding.select_layer(w.layers, m)
+                    for m in masks if m.sum() <= w.layers[-1])
+        assert 0 < moved <= 0.1 * errs.size
+        parity_report(test="coded_rounds_c5_guarded", rounds=int(errs.size), kappa_limit=1000.0, rounds_moved_up=int(moved),
+                      median_decode_rel_l2=float(np.median(errs)), worst_decode_rel_l2=float(errs.max()),
+                      share_above_1e_4=float(np.mean(errs > TOL)))
+        ngc.ngc_set_decode_guard(ctx, 0.0)
     finally:
         ngc.ngc_destroy(ctx)
 

@@ -216,6 +216,51 @@ def test_select_agrees_with_oracle_on_random_masks(ngc, n, layers, kind):
         ngc.ngc_destroy(ctx)
 
 
+@pytest.mark.parametrize("n,layers,kind,limits", [
+    (16, [0, 1, 3, 7], "cyclic", (2.0, 10.0, 100.0)), (32, [0, 1, 3, 7, 15], "cyclic", (20.0, 300.0)),
+    (64, [0, 1, 3, 7, 15, 31], "cyclic", (100.0, 1000.0)), (8, [0, 1, 3, 7], "fracrep", (0.5, 1.5, 4.0)),
+    (12, [0, 1, 2, 3, 4, 5], "cyclic", (1.0, 5.0, 30.0))])
+def test_guarded_choice_agrees_with_oracle(ngc, n, layers, kind, limits):
+    """ngc_set_decode_guard: the layer and the vector of the guarded rule are the oracle's for
+    masks that stress it (as many stragglers as a layer tolerates) and for random ones; with
+    the guard off the plain rule is back; the first-responders variant is never guarded."""
+    Bs = codes.nested_code(n, layers, kind, seed=0, draws=2)
+    ctx = ngc.ngc_create(n, n, layers, 4)
+    try:
+        for u, B in enumerate(Bs):
+            ngc.ngc_set_code(ctx, u, B)
+        rng = np.random.default_rng(3 * n)
+        masks = []
+        for t in range(80):
+            s = layers[1 + t % (len(layers) - 1)] if t % 2 else int(rng.integers(0, layers[-1] + 1))
+            m = np.zeros(n, np.uint8)
+            m[rng.choice(n, size=s, replace=False)] = 1
+            masks.append(m)
+        moved = 0
+        for limit in limits:
+            ngc.ngc_set_decode_guard(ctx, limit)
+            for m in masks:
+                u_o, a_o = coding.select_guarded(Bs, layers, m, limit)
+                u, a, r = ngc.ngc_select_decode_vec(ctx, m, n)
+                assert u == u_o
+                assert np.array_equal(a != 0, a_o != 0) and np.all(a[m == 1] == 0) and r < 1e-8
+                assert np.abs(a - a_o).max() <= 1e-7 * max(1.0, np.abs(a_o).max())
+                moved += u != coding.select_layer(layers, m)
+                u1, _, _ = ngc.ngc_select_decode_vec_first(ctx, m, n)
+                assert u1 == coding.select_layer(layers, m)
+        assert moved > 0
+        for off in (0.0, float("inf")):
+            ngc.ngc_set_decode_guard(ctx, off)
+            for m in masks[:20]:
+                assert ngc.ngc_select_decode_vec(ctx, m, n)[0] == coding.select_layer(layers, m)
+        for bad in (-1.0, float("nan")):
+            with pytest.raises(ngc.NgcError) as e:
+                ngc.ngc_set_decode_guard(ctx, bad)
+            assert e.value.code == ngc.NGC_ERR_INVALID
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
 def test_select_reports_singular_for_a_matrix_that_is_no_gradient_code(ngc):
     n = 6
     ctx = ngc.ngc_create(n, n, [0, 2], 4)
