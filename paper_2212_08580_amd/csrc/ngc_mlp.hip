@@ -510,23 +510,32 @@ __device__ __forceinline__ void join_tile(float* __restrict__ C, int64_t ldc, in
     const float* src = split.scratch + (int64_t)q * split.pieces * (TM * TN);
     float* dst = C + (int64_t)(c_batch ? c_batch[tz] : tz) * strideC + (int64_t)ty * TM * ldc + tx * TN;
     const int t = threadIdx.x;
+    // both rows' pieces are asked for before any is added, eight pieces per row at a time: the
+    // kernel is short and bound by how many loads it has in flight
+    const int col = (t & 31) * 4;
+    const int row[2] = {y * 16 + (t >> 5), y * 16 + 8 + (t >> 5)};
+    v4f acc[2];
+    for (int p0 = 0; p0 < split.pieces; p0 += 8) {  // block-uniform trip count
+        v4f x[2][8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                if (p0 + u < split.pieces)
+                    x[h][u] = *reinterpret_cast<const v4f*>(src + (int64_t)(p0 + u) * (TM * TN) + row[h] * TN + col);
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                if (p0 + u < split.pieces) acc[h] = (p0 + u == 0) ? x[h][u] : acc[h] + x[h][u];
+    }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-        const int row = y * 16 + h * 8 + (t >> 5), col = (t & 31) * 4;
-        const float* s = src + row * TN + col;
-        v4f acc = *reinterpret_cast<const v4f*>(s);
-        for (int p = 1; p < split.pieces; ++p) {
-            const v4f x = *reinterpret_cast<const v4f*>(s + (int64_t)p * (TM * TN));
-            acc.x += x.x;
-            acc.y += x.y;
-            acc.z += x.z;
-            acc.w += x.w;
-        }
-        float* o = dst + (int64_t)row * ldc + col;
-        o[0] = acc.x;
-        o[1] = acc.y;
-        o[2] = acc.z;
-        o[3] = acc.w;
+        float* o = dst + (int64_t)row[h] * ldc + col;
+        o[0] = acc[h].x;
+        o[1] = acc[h].y;
+        o[2] = acc[h].z;
+        o[3] = acc[h].w;
     }
 }
 
@@ -1027,16 +1036,16 @@ __global__ __launch_bounds__(256) void mlp_sums_kernel(int join_blocks, float* _
     const int64_t t = (int64_t)(b % tail_blocks) * 256 + threadIdx.x;
     if (t >= T) return;
     const float* p = partial + (int64_t)j * chunks * T + t;
-    float acc = p[0];
-    int c = 1;
-    for (; c + 8 <= chunks; c += 8) {  // eight loads in flight, added in index order
-        float a[8];
+    float acc = 0.0f;
+    for (int c0 = 0; c0 < chunks; c0 += 32) {  // up to thirty-two loads in flight, added in index order
+        float a[32];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) a[u] = p[(int64_t)(c + u) * T];
+        for (int u = 0; u < 32; ++u)
+            if (c0 + u < chunks) a[u] = p[(int64_t)(c0 + u) * T];  // block-uniform condition
 #pragma unroll
-        for (int u = 0; u < 8; ++u) acc += a[u];
+        for (int u = 0; u < 32; ++u)
+            if (c0 + u < chunks) acc = (c0 + u == 0) ? a[u] : acc + a[u];
     }
-    for (; c < chunks; ++c) acc += p[(int64_t)c * T];
     out[(int64_t)(unit_row ? unit_row[j] : j) * out_stride + t] = acc;
 }
 
