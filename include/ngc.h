@@ -137,7 +137,7 @@ int ngc_set_mlp2_shape(ngc_ctx* ctx, int d_in, int hidden, int classes);
  * X_dev: float [k][rows_per_part][d_in] row-major (d_in = d for the first two
  * losses), 16-byte aligned.  theta_dev: float [d].  G_dev: float [k][d], fully
  * overwritten.  Each row of X is read from HBM exactly once for every
- * d <= 16384 that is a multiple of 4 and every d <= 8192 that is not (fastest
+ * d <= 32768 that is a multiple of 4 and every d <= 8192 that is not (fastest
  * when d is 256, 512, 768 or a multiple of 1024); larger d take a two-pass
  * route that reads X twice.
  * Accumulation is fp32 with a fixed summation order (bit-reproducible).
@@ -155,9 +155,10 @@ int ngc_partition_grads(ngc_ctx* ctx, int loss, const float* X_dev, const void* 
  * event (its launches are not recorded by ngc_profile_*).  The very first call on a device
  * looks up the array's address there; make that call outside a capture.
  *   Limits: NGC_LOSS_LSQ and NGC_LOSS_LOGISTIC only (the perceptron's activations do not
- *   fit), and shapes whose block partials fit the array: every single-pass shape
- *   (d <= 16384) does; beyond that 4 * k * (d + rows_per_part) bytes plus 0.5 MiB must
- *   stay below 20 MiB.  Anything else returns NGC_ERR_INVALID and launches nothing.
+ *   fit), and shapes whose block partials fit the array: every single-pass shape with
+ *   d <= 16384 does, wider single-pass rows (one block per compute unit, 4 d bytes each)
+ *   up to d = 20480 on a GPU of 256 compute units; for the two-pass shapes
+ *   4 * k * (d + rows_per_part) bytes plus 0.5 MiB must stay below 20 MiB.  Anything else returns NGC_ERR_INVALID and launches nothing.
  *   All calls on one GPU share the one array, whichever context they use: calls that
  *   overlap in time on one GPU (two streams, two host threads) race on it.  Nothing in it
  *   has to start at zero (every partial is written before it is read), so it is not cleared.

@@ -160,23 +160,23 @@ extern "C" int ngc_sync(ngc_ctx* ctx) try {
 
 
 // ---- partition gradients --------------------------------------------------
-template <int NV, int R, int NBUF, int WAVES, bool RAGGED, typename VT = v4f>
+template <int NV, int R, int NBUF, int WAVES, bool RAGGED, typename VT = v4f, bool TH_LDS = false>
 static void launch_stream(ngc_ctx* ctx, int loss, const float* X, const float* y,
                           const float* theta, float* partial, int k, int64_t rows, int chunks,
                           int64_t rpc, const int* unit_part, int dq) {
     dim3 grid((unsigned)(k * chunks));
     if (loss == NGC_LOSS_LSQ)
-        hipLaunchKernelGGL((grad_stream_kernel<NV, R, NBUF, WAVES, NGC_LOSS_LSQ, RAGGED, VT>), grid,
+        hipLaunchKernelGGL((grad_stream_kernel<NV, R, NBUF, WAVES, NGC_LOSS_LSQ, RAGGED, VT, TH_LDS>), grid,
                            dim3(WAVES * 64), 0, ctx->stream, X, y, theta, partial, rows, chunks, rpc,
                            unit_part, dq);
     else
-        hipLaunchKernelGGL((grad_stream_kernel<NV, R, NBUF, WAVES, NGC_LOSS_LOGISTIC, RAGGED, VT>), grid,
+        hipLaunchKernelGGL((grad_stream_kernel<NV, R, NBUF, WAVES, NGC_LOSS_LOGISTIC, RAGGED, VT, TH_LDS>), grid,
                            dim3(WAVES * 64), 0, ctx->stream, X, y, theta, partial, rows, chunks, rpc,
                            unit_part, dq);
 }
 
 // Shape of the single-pass kernel for a given d, or waves = 0 if d has none
-// (above 16384, or above 8192 and not a multiple of 4).  A block offers
+// (above 32768, or above 8192 and not a multiple of 4).  A block offers
 // nv*waves*64 slots per row, each a float4, or a float (`scalar`) when d is not
 // a multiple of 4 and rows are therefore not 16-byte aligned; `ragged` when
 // the row has fewer elements than the block has slots.
@@ -199,6 +199,8 @@ static stream_shape pick_stream_shape(int64_t d) {
     if (d == 256) return {1, 16, 1, false, false};
     if (d == 512) return {2, 8, 1, false, false};
     if (d == 768) return {3, 5, 1, false, false};
+    // wide rows: ten to sixteen waves of eight float4 per lane and row, theta in LDS (the shapes with more than eight waves)
+    if (d > 16384 && d <= 32768 && d % 4 == 0) return {8, 1, 2 * (int)((d / 4 + 1023) / 1024), true, false};
     if (d < 1 || d > 16384) return {0, 0, 0, false, false};
     if (d % 4 != 0) {
         if (d <= 256) return {4, 16, 1, true, true};
@@ -347,6 +349,10 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
                 switch (sh.waves) {
                     NGC_STREAM_CASE(8, 2, 5, true) NGC_STREAM_CASE(8, 2, 6, true)
                     NGC_STREAM_CASE(8, 2, 7, true) NGC_STREAM_CASE(8, 2, 8, true)
+                    case 10: launch_stream<8, 1, 2, 10, true, v4f, true>(NGC_STREAM_ARGS); break;
+                    case 12: launch_stream<8, 1, 2, 12, true, v4f, true>(NGC_STREAM_ARGS); break;
+                    case 14: launch_stream<8, 1, 2, 14, true, v4f, true>(NGC_STREAM_ARGS); break;
+                    case 16: launch_stream<8, 1, 2, 16, true, v4f, true>(NGC_STREAM_ARGS); break;
                 }
             } else if (sh.nv == 1) {
                 launch_stream<1, 16, 2, 1, true>(NGC_STREAM_ARGS);
@@ -383,7 +389,11 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
     }
     // generic two-pass route
     const int64_t total_rows = (int64_t)k * rows;
-    const int64_t col_blocks = (d + 255) / 256;
+    // float4 elements when rows and theta are 16-byte addressable (the partials always are: the
+    // workspace is 256-byte aligned and the residuals before them take a multiple of 64 floats)
+    const bool vec = d % 4 == 0 && ((reinterpret_cast<uintptr_t>(X_dev) | reinterpret_cast<uintptr_t>(theta_dev)) & 15) == 0;
+    const int64_t dv = vec ? d / 4 : d;
+    const int64_t col_blocks = (dv + 255) / 256;
     int64_t chunks = std::max<int64_t>(1, std::min<int64_t>(rows, (wave_slots / 4 + k * col_blocks - 1) / (k * col_blocks)));
     chunks = std::min<int64_t>(chunks, 65535);
     int64_t rpc = (rows + chunks - 1) / chunks;
@@ -396,16 +406,23 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
     {
         ngc_prof_scope ps(ctx, NGC_KERNEL_GRAD);
         const int64_t blocks = std::min<int64_t>((total_rows + 3) / 4, (int64_t)ctx->cu_count * 8);
-        if (loss == NGC_LOSS_LSQ)
-            hipLaunchKernelGGL((resid_kernel<NGC_LOSS_LSQ>), dim3((unsigned)blocks), dim3(256), 0, ctx->stream,
-                               X_dev, y, theta_dev, resid, total_rows, d, rows, unit_part);
-        else
-            hipLaunchKernelGGL((resid_kernel<NGC_LOSS_LOGISTIC>), dim3((unsigned)blocks), dim3(256), 0,
-                               ctx->stream, X_dev, y, theta_dev, resid, total_rows, d, rows, unit_part);
+#define NGC_RESID(LOSS_ID, VEC)                                                                                  \
+    hipLaunchKernelGGL((resid_kernel<LOSS_ID, VEC>), dim3((unsigned)blocks), dim3(256), 0, ctx->stream, X_dev, y, \
+                       theta_dev, resid, total_rows, d, rows, unit_part)
+        if (loss == NGC_LOSS_LSQ) {
+            if (vec) NGC_RESID(NGC_LOSS_LSQ, true); else NGC_RESID(NGC_LOSS_LSQ, false);
+        } else {
+            if (vec) NGC_RESID(NGC_LOSS_LOGISTIC, true); else NGC_RESID(NGC_LOSS_LOGISTIC, false);
+        }
+#undef NGC_RESID
         NGC_HIP(ctx, hipGetLastError());
         dim3 grid((unsigned)col_blocks, (unsigned)chunks, (unsigned)k);
-        hipLaunchKernelGGL(xtr_kernel, grid, dim3(256), 0, ctx->stream, X_dev, resid, partial, rows, d,
-                           (int)chunks, rpc, unit_part);
+        if (vec)
+            hipLaunchKernelGGL(xtr_kernel<true>, grid, dim3(256), 0, ctx->stream, X_dev, resid, partial, rows, d,
+                               (int)chunks, rpc, unit_part);
+        else
+            hipLaunchKernelGGL(xtr_kernel<false>, grid, dim3(256), 0, ctx->stream, X_dev, resid, partial, rows, d,
+                               (int)chunks, rpc, unit_part);
     }
     NGC_HIP(ctx, hipGetLastError());
     if (defer) {

@@ -5,6 +5,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "ngc_dev_common.h"
 
 // ---------------------------------------------------------------------------
@@ -90,17 +92,30 @@ __device__ __forceinline__ void load_group(row_group<NV, R, VT>& b, const char* 
 __device__ __forceinline__ float hsum(float q) { return q; }
 __device__ __forceinline__ float hsum(v4f q) { return (q.x + q.y) + (q.z + q.w); }
 
-template <int NV, int R, int WAVES, int LOSS, typename VT>
+// th_l (TH_LDS): the lane's theta elements in LDS, element i at th_l[i * 64], instead of th.
+template <int NV, int R, int WAVES, int LOSS, typename VT, bool TH_LDS = false>
 __device__ __forceinline__ void consume_group(const row_group<NV, R, VT>& b, VT (&acc)[NV],
-                                              const VT (&th)[NV], float* ex, int wave,
-                                              int lane, int64_t row, int64_t end_row) {
+                                              const VT (&th)[TH_LDS ? 1 : NV], const VT* th_l, float* ex,
+                                              int wave, int lane, int64_t row, int64_t end_row) {
     float dot[R];
+    if (TH_LDS) {
+        VT q[R];
 #pragma unroll
-    for (int rr = 0; rr < R; ++rr) {
-        VT q = b.x[rr][0] * th[0];
+        for (int i = 0; i < NV; ++i) {
+            const VT t = th_l[i * 64];
 #pragma unroll
-        for (int i = 1; i < NV; ++i) q += b.x[rr][i] * th[i];
-        dot[rr] = wave_sum(hsum(q));
+            for (int rr = 0; rr < R; ++rr) q[rr] = i == 0 ? b.x[rr][0] * t : q[rr] + b.x[rr][i] * t;
+        }
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) dot[rr] = wave_sum(hsum(q[rr]));
+    } else {
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) {
+            VT q = b.x[rr][0] * th[0];
+#pragma unroll
+            for (int i = 1; i < NV; ++i) q += b.x[rr][i] * th[i];
+            dot[rr] = wave_sum(hsum(q));
+        }
     }
     if (WAVES > 1) {
         // ex[rr*WAVES + w]: every lane of wave w stores the same value
@@ -145,7 +160,10 @@ __device__ __forceinline__ void consume_group(const row_group<NV, R, VT>& b, VT 
     }
 }
 
-template <int NV, int R, int NBUF, int WAVES, int LOSS, bool RAGGED, typename VT>
+// TH_LDS: theta sits in LDS (one copy per block, each wave reads its own slice once per row
+// group) instead of in registers; a wave with eight float4 per lane and row then stays within
+// 128 registers, sixteen such waves form a block, and rows of up to 32768 features take one pass.
+template <int NV, int R, int NBUF, int WAVES, int LOSS, bool RAGGED, typename VT, bool TH_LDS = false>
 __global__ __launch_bounds__(WAVES * 64) void grad_stream_kernel(
     const float* __restrict__ X, const float* __restrict__ y, const float* __restrict__ theta,
     float* __restrict__ partial, int64_t rows, int chunks, int64_t rows_per_chunk,
@@ -174,14 +192,23 @@ __global__ __launch_bounds__(WAVES * 64) void grad_stream_kernel(
     const uint32_t last_off = (uint32_t)(dv - 1) * (uint32_t)sizeof(VT);
     const int64_t pitch = dv * (int64_t)sizeof(VT);
 
-    VT th[NV], acc[NV];
+    __shared__ VT th_s[TH_LDS ? SLOTS : 1];
+    VT th[TH_LDS ? 1 : NV], acc[NV];
+    // the lane's elements of theta; with TH_LDS a wave writes and later reads only its own
+    // slice, so no barrier is needed between the two
+    const VT* th_l = th_s + (TH_LDS ? wave * 64 * NV + lane : 0);
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const int slot = wave * 64 * NV + i * 64 + lane;
+        VT t;
         if (RAGGED)
-            th[i] = slot < dq ? reinterpret_cast<const VT*>(theta)[slot] : (VT)(0.0f);
+            t = slot < dq ? reinterpret_cast<const VT*>(theta)[slot] : (VT)(0.0f);
         else
-            th[i] = reinterpret_cast<const VT*>(theta)[slot];
+            t = reinterpret_cast<const VT*>(theta)[slot];
+        if (TH_LDS)
+            th_s[slot] = t;
+        else
+            th[i] = t;
         acc[i] = (VT)(0.0f);
     }
 
@@ -203,7 +230,7 @@ __global__ __launch_bounds__(WAVES * 64) void grad_stream_kernel(
                 const int64_t gi = gb + p;
                 load_group<NV, R, SLOTS, RAGGED, VT>(buf[(p + NBUF - 1) % NBUF], xbase, yp, lane_off,
                                                      last_off, pitch, lane, r0 + (gi + NBUF - 1) * R, last);
-                consume_group<NV, R, WAVES, LOSS, VT>(buf[p], acc, th, ex_s[gi & 1], wave, lane, r0 + gi * R, r1);
+                consume_group<NV, R, WAVES, LOSS, VT, TH_LDS>(buf[p], acc, th, th_l, ex_s[gi & 1], wave, lane, r0 + gi * R, r1);
             }
         }
     }
@@ -315,47 +342,79 @@ __global__ __launch_bounds__(64) void grad_narrow_kernel(const float* __restrict
 
 // ---------------------------------------------------------------------------
 // Generic two-pass route for any d.  Pass 1: one wave per row forms the margin
-// and stores the residual.  Pass 2: one thread per column adds r*x over a run
-// of rows; partials are summed by K2.
+// and stores the residual.  Pass 2: a thread adds r*x over a run of rows for its
+// columns; partials are summed by K2.  VEC (d a multiple of 4, X 16-byte
+// aligned): elements are float4.  Both passes keep eight loads per lane in flight;
+// a column's terms are added in row order whatever the width.
 // ---------------------------------------------------------------------------
-template <int LOSS>
+template <int LOSS, bool VEC>
 __global__ __launch_bounds__(256) void resid_kernel(const float* __restrict__ X,
                                                     const float* __restrict__ y,
                                                     const float* __restrict__ theta,
                                                     float* __restrict__ resid, int64_t total_rows,
                                                     int64_t d, int64_t rows,
                                                     const int* __restrict__ unit_part) {
+    using VT = typename std::conditional<VEC, v4f, float>::type;
     const int lane = threadIdx.x & 63;
     const int64_t wave0 = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t nwaves = (int64_t)gridDim.x * 4;
+    const int64_t dv = VEC ? d / 4 : d;
+    const VT* tv = reinterpret_cast<const VT*>(theta);
     for (int64_t r = wave0; r < total_rows; r += nwaves) {
         // row r of the unit list is row (r % rows) of partition unit_part[r / rows]
         const int64_t src = unit_part ? (int64_t)unit_part[r / rows] * rows + r % rows : r;
-        const float* xr = X + src * d;
-        float dot = 0.0f;
-        for (int64_t c = lane; c < d; c += 64) dot += xr[c] * theta[c];
-        float z = wave_sum(dot);
+        const VT* xr = reinterpret_cast<const VT*>(X + src * d);
+        // eight partial sums per lane (element c goes to sum (c / 64) % 8), added in order at the end
+        VT q[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) q[u] = (VT)(0.0f);
+        int64_t base = 0;
+        for (; base + 8 * 64 <= dv; base += 8 * 64) {  // wave-uniform
+            VT x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) x[u] = __builtin_nontemporal_load(xr + base + u * 64 + lane);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) q[u] += x[u] * tv[base + u * 64 + lane];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int64_t c = base + u * 64 + lane;
+            if (c < dv) q[u] += xr[c] * tv[c];
+        }
+        const VT s = ((q[0] + q[1]) + (q[2] + q[3])) + ((q[4] + q[5]) + (q[6] + q[7]));
+        const float z = wave_sum(hsum(s));
         if (lane == 0) resid[r] = loss_slope<LOSS>(z, y[src]);
     }
 }
 
+template <bool VEC>
 __global__ __launch_bounds__(256) void xtr_kernel(const float* __restrict__ X,
                                                   const float* __restrict__ resid,
                                                   float* __restrict__ partial, int64_t rows,
                                                   int64_t d, int chunks, int64_t rows_per_chunk,
                                                   const int* __restrict__ unit_part) {
+    using VT = typename std::conditional<VEC, v4f, float>::type;
+    const int64_t dv = VEC ? d / 4 : d;
     const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int chunk = blockIdx.y;
     const int j = blockIdx.z;  // unit
-    if (c >= d) return;
+    if (c >= dv) return;
     const int64_t r0 = (int64_t)chunk * rows_per_chunk;
     const int64_t r1 = rows < r0 + rows_per_chunk ? rows : r0 + rows_per_chunk;
     const int part = unit_part ? unit_part[j] : j;
-    const float* xp = X + ((int64_t)part * rows) * d + c;
+    const VT* xp = reinterpret_cast<const VT*>(X + ((int64_t)part * rows) * d) + c;
     const float* rp = resid + (int64_t)j * rows;
-    float acc = 0.0f;
-    for (int64_t r = r0; r < r1; ++r) acc += rp[r] * xp[r * d];
-    partial[((int64_t)j * chunks + chunk) * d + c] = acc;
+    VT acc = (VT)(0.0f);
+    int64_t r = r0;
+    for (; r + 8 <= r1; r += 8) {
+        VT x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = __builtin_nontemporal_load(xp + (r + u) * dv);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += rp[r + u] * x[u];
+    }
+    for (; r < r1; ++r) acc += rp[r] * xp[r * dv];
+    reinterpret_cast<VT*>(partial)[((int64_t)j * chunks + chunk) * dv + c] = acc;
 }
 
 // K2: G[j][:] = sum over chunks of partial[j][chunk][:], chunks added in index order.

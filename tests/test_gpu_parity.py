@@ -179,10 +179,13 @@ GRAD_SHAPES = [
     (64, 4, 256), (200, 3, 50), (77, 2, 19), (1000, 2, 33), (4100, 2, 10), (5120, 2, 9),
     (4096, 2, 1), (1024, 1, 3), (4096, 64, 9),
     # rows shorter than the block's slots (d a multiple of 4) and rows that are not 16-byte
-    # aligned (d not a multiple of 4), one case per kernel shape family; the last three take
-    # the two-pass route (no single-pass shape)
+    # aligned (d not a multiple of 4), one case per kernel shape family
     (3000, 2, 11), (7000, 2, 6), (13000, 2, 4), (54, 3, 100), (1002, 3, 40), (2050, 2, 17),
-    (4094, 2, 9), (5002, 2, 7), (8190, 2, 5), (8194, 2, 3), (20000, 2, 3), (16388, 2, 2),
+    (4094, 2, 9), (5002, 2, 7), (8190, 2, 5),
+    # wide rows, 16388 to 32768 features in float4: theta in LDS, ten to sixteen waves per block
+    (20000, 2, 3), (16388, 2, 2), (24580, 2, 4), (28672, 1, 7), (32768, 2, 5), (32768, 3, 1),
+    # no single-pass shape: the two-pass route
+    (8194, 2, 3), (32772, 2, 2), (40000, 2, 3), (20002, 1, 4),
     (1, 3, 40), (2, 2, 17), (5, 2, 33), (4, 2, 64), (16384, 1, 40),
     # narrow rows of 1, 2, 4, .. 32 float4 (several rows per wave-wide load), with and without a
     # ragged last group, and enough rows for several groups per block
