@@ -203,6 +203,9 @@ static stream_shape pick_stream_shape(int64_t d) {
     if (d > 16384 && d <= 32768 && d % 4 == 0) return {8, 1, 2 * (int)((d / 4 + 1023) / 1024), true, false};
     if (d < 1 || d > 16384) return {0, 0, 0, false, false};
     if (d % 4 != 0) {
+        if (d <= 64) return {1, 16, 1, true, true};   // as few idle lanes as the row length allows
+        if (d <= 128) return {2, 16, 1, true, true};
+        if (d <= 192) return {3, 16, 1, true, true};
         if (d <= 256) return {4, 16, 1, true, true};
         if (d <= 4096) return {8, 8, (int)((d + 511) / 512), true, true};
         if (d <= 8192) return {16, 3, (int)((d + 1023) / 1024), true, true};
@@ -268,7 +271,7 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
         // rows of at most 128 features fill no more than half of a wave's lanes: twice the
         // blocks keep as many bytes in flight (measured: 3.1 -> 3.6 TB/s at 64 features,
         // 4.3 -> 5.0 at 100, 5.5 -> 6.1 at 128; wider rows lose 2 % with more than 8)
-        const int per_cu = (sh.waves == 1 && !sh.scalar && d <= 128) ? 16 : std::max(1, 8 / sh.waves);
+        const int per_cu = (sh.waves == 1 && d <= 128) ? 16 : std::max(1, 8 / sh.waves);
         const int64_t block_slots = (int64_t)ctx->cu_count * per_cu;
         int64_t chunks = std::max<int64_t>(1, block_slots / k);
         int64_t rpc = (rows + chunks - 1) / chunks;
@@ -302,7 +305,13 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
                 }
 #undef NGC_NARROW_CASE
             } else if (sh.scalar) {
-                if (sh.nv == 4) {
+                if (sh.nv == 1) {
+                    launch_stream<1, 16, 2, 1, true, float>(NGC_STREAM_ARGS);
+                } else if (sh.nv == 2) {
+                    launch_stream<2, 16, 2, 1, true, float>(NGC_STREAM_ARGS);
+                } else if (sh.nv == 3) {
+                    launch_stream<3, 16, 2, 1, true, float>(NGC_STREAM_ARGS);
+                } else if (sh.nv == 4) {
                     launch_stream<4, 16, 2, 1, true, float>(NGC_STREAM_ARGS);
                 } else if (sh.nv == 8) {
                     switch (sh.waves) {

@@ -181,7 +181,7 @@ GRAD_SHAPES = [
     # rows shorter than the block's slots (d a multiple of 4) and rows that are not 16-byte
     # aligned (d not a multiple of 4), one case per kernel shape family
     (3000, 2, 11), (7000, 2, 6), (13000, 2, 4), (54, 3, 100), (1002, 3, 40), (2050, 2, 17),
-    (4094, 2, 9), (5002, 2, 7), (8190, 2, 5),
+    (4094, 2, 9), (5002, 2, 7), (8190, 2, 5), (30, 2, 70), (123, 2, 41), (130, 3, 35), (191, 2, 18), (250, 2, 9),
     # wide rows, 16388 to 32768 features in float4: theta in LDS, ten to sixteen waves per block
     (20000, 2, 3), (16388, 2, 2), (24580, 2, 4), (28672, 1, 7), (32768, 2, 5), (32768, 3, 1),
     # no single-pass shape: the two-pass route
