@@ -349,10 +349,38 @@ __global__ __launch_bounds__(256) void coded_rounds_kernel(
         stage_tile<VT, 4>(tile, G, k, kp, d, c, in, wave, lane);
     }
     __syncthreads();
+    // A round's record (layer, the decode weights of the wave's workers, the trip masks of its
+    // groups) is wave-uniform and comes through scalar loads.  They are asked for a round ahead,
+    // all at once: the layer and the sixteen weights at the start of the round before, the trip
+    // masks (which need the layer) at its end, so that a group's work does not begin by waiting
+    // for two loads in a row.  Wave w owns groups w, w+4, w+8, w+12 (GW = 4 at most).
+    constexpr int GW = NGC_MAX_N / 16;
+    auto load_rec = [&](int r, int& layer, double (&a)[GW][4]) {
+        layer = SINGLE ? one.layer : recs[r].layer;
+#pragma unroll
+        for (int gi = 0; gi < GW; ++gi)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int i = 4 * (wave + 4 * gi) + rr;  // < NGC_MAX_N; the vector is zero beyond n
+                a[gi][rr] = SINGLE ? one.a[i] : recs[r].a[i];
+            }
+    };
+    auto load_masks = [&](int layer, unsigned (&gm)[GW]) {
+#pragma unroll
+        for (int gi = 0; gi < GW; ++gi) {
+            const int g = wave + 4 * gi;
+            gm[gi] = (layer >= 0 && g < ng) ? gmask[layer * ng + g] : 0u;
+        }
+    };
+    int layer, layer_n = -1;
+    double aw[GW][4], aw_n[GW][4];
+    unsigned gm[GW], gm_n[GW];
+    load_rec(r0, layer, aw);
+    load_masks(layer, gm);
     for (int r = r0; r < r1; ++r) {
         if (MODE == ROUNDS_G_PER_ROUND && r + 1 < r1)
             tile_fetch<VT>(next, G + (int64_t)(r + 1) * g_stride, k, d, c, in, wave);
-        const int layer = SINGLE ? one.layer : recs[r].layer;
+        if (r + 1 < r1) load_rec(r + 1, layer_n, aw_n);
         double q[V];
 #pragma unroll
         for (int v = 0; v < V; ++v) q[v] = 0.0;
@@ -363,32 +391,30 @@ __global__ __launch_bounds__(256) void coded_rounds_kernel(
 #pragma unroll
                 for (int v = 0; v < V; ++v) acc[rr][v] = 0.0;
             float* Mr = M + (int64_t)r * m_stride + c;
-            for (int g = wave; g < ng; g += 4) {
-                const int ug = layer * ng + g;
-                double av[4];
-                bool any = false;
 #pragma unroll
-                for (int rr = 0; rr < 4; ++rr) {
-                    av[rr] = SINGLE ? one.a[4 * g + rr] : recs[r].a[4 * g + rr];  // index < NGC_MAX_N; zero beyond n
-                    any = any || av[rr] != 0.0;
-                }
-                if (!any) continue;  // wave-uniform: four stragglers in a row
-                VT m[4];
-                group_messages<VT, V>(tile, lane, gcoef + (size_t)ug * kp * 4, gmask[ug], m);
+            for (int gi = 0; gi < GW; ++gi) {
+                const int g = wave + 4 * gi;
+                const double(&av)[4] = aw[gi];
+                const bool any = av[0] != 0.0 || av[1] != 0.0 || av[2] != 0.0 || av[3] != 0.0;
+                if (g < ng && any) {  // wave-uniform; not taken for four stragglers in a row
+                    VT m[4];
+                    group_messages<VT, V>(tile, lane, gcoef + (size_t)(layer * ng + g) * kp * 4, gm[gi], m);
 #pragma unroll
-                for (int rr = 0; rr < 4; ++rr) {
-                    if (av[rr] != 0.0) {  // wave-uniform
-                        if (in)
-                            __builtin_nontemporal_store(m[rr], reinterpret_cast<VT*>(Mr + (int64_t)(4 * g + rr) * d));
+                    for (int rr = 0; rr < 4; ++rr) {
+                        if (av[rr] != 0.0) {  // wave-uniform
+                            if (in)
+                                __builtin_nontemporal_store(m[rr], reinterpret_cast<VT*>(Mr + (int64_t)(4 * g + rr) * d));
 #pragma unroll
-                        for (int v = 0; v < V; ++v)
-                            acc[rr][v] = __builtin_fma(av[rr], (double)ngc_get(m[rr], v), acc[rr][v]);
+                            for (int v = 0; v < V; ++v)
+                                acc[rr][v] = __builtin_fma(av[rr], (double)ngc_get(m[rr], v), acc[rr][v]);
+                        }
                     }
                 }
             }
 #pragma unroll
             for (int v = 0; v < V; ++v) q[v] = ngc_quad(acc[0][v], acc[1][v], acc[2][v], acc[3][v]);
         }
+        if (r + 1 < r1) load_masks(layer_n, gm_n);
         double* x = xch + (size_t)(r & 1) * 4 * 64 * V;
 #pragma unroll
         for (int v = 0; v < V; ++v) x[(wave * V + v) * 64 + lane] = q[v];
@@ -405,6 +431,13 @@ __global__ __launch_bounds__(256) void coded_rounds_kernel(
             __syncthreads();  // every wave is done with this round's tile
             tile_land<VT>(tile, next, kp, wave, lane);
             __syncthreads();
+        }
+        layer = layer_n;
+#pragma unroll
+        for (int gi = 0; gi < GW; ++gi) {
+            gm[gi] = gm_n[gi];
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) aw[gi][rr] = aw_n[gi][rr];
         }
     }
 }
