@@ -46,7 +46,7 @@ __device__ __forceinline__ void tile_fetch(tile_regs<VT>& t, const float* __rest
     for (int u = 0; u < NGC_MAX_N / 4; ++u) {
         const int r = wave + 4 * u;
         t.v[u] = (VT)(0.0f);
-        if (in && r < k) t.v[u] = *reinterpret_cast<const VT*>(G + (int64_t)r * d + c);
+        if (in && r < k) t.v[u] = __builtin_nontemporal_load(reinterpret_cast<const VT*>(G + (int64_t)r * d + c));  // read once: keep it out of the caches' way
     }
 }
 

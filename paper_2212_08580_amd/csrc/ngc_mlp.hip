@@ -907,13 +907,29 @@ __global__ __launch_bounds__(512, NCP <= 10 ? 4 : 2) void mlp_head1024_kernel(
             hq[u] = *reinterpret_cast<const v2f*>(Hp + r * HID);
         }
     };
+    // the softmax lanes (threads 0..127: trip row t / 16, class t % 16) hold their class's bias for the
+    // whole kernel and ask for a trip's label together with its rows, a trip ahead: the softmax step
+    // keeps all eight waves waiting and must not begin with a trip to memory
+    const int srow = t >> 4, sq = t & 15;
+    const float b2q = (t < TR * 16 && sq < NCP) ? b2[sq] : 0.0f;
+    auto fetch_label = [&](int64_t rb) {
+        const int64_t r = rb + srow < r1 ? rb + srow : r1 - 1;
+        return t < TR * 16 ? lab[r] : 0;
+    };
     v2f hq[TR], nq[TR];
-    if (r0 < r1) fetch(r0, hq);
+    int label = 0, label_n = 0;
+    if (r0 < r1) {
+        fetch(r0, hq);
+        label = fetch_label(r0);
+    }
     for (int64_t rb = r0; rb < r1; rb += TR) {
 #pragma unroll
         for (int u = 0; u < TR; ++u) *reinterpret_cast<v2f*>(&hs[u][h0]) = hq[u];
         __syncthreads();
-        if (rb + TR < r1) fetch(rb + TR, nq);
+        if (rb + TR < r1) {
+            fetch(rb + TR, nq);
+            label_n = fetch_label(rb + TR);
+        }
         {   // partial logits of the wave's 128 units
             // four accumulators, one per component, so that no product waits for the one before
             // it; added in component order at the end
@@ -941,14 +957,13 @@ __global__ __launch_bounds__(512, NCP <= 10 ? 4 : 2) void mlp_head1024_kernel(
         }
         __syncthreads();
         if (t < TR * 16) {   // waves 0 and 1: 16 lanes per row
-            const int row = t >> 4, q = t & 15;
-            const int64_t r = rb + row < r1 ? rb + row : r1 - 1;
+            const int row = srow, q = sq;
             float z = -INFINITY;
             if (q < NCP) {
                 z = zp[0][row][q];
 #pragma unroll
                 for (int w = 1; w < NWV; ++w) z += zp[w][row][q];
-                z += b2[q];
+                z += b2q;
             }
             // maximum and sum over the 16 lanes of the row, every lane gets both (data-parallel
             // moves within quads, half rows and rows; fixed order)
@@ -963,7 +978,7 @@ __global__ __launch_bounds__(512, NCP <= 10 ? 4 : 2) void mlp_head1024_kernel(
             den = dpp_step<0x4E>(den);
             den = dpp_step<0x141>(den);
             den = dpp_step<0x140>(den);
-            const float dz = q < NCP ? ez * (1.0f / den) - (q == lab[r] ? 1.0f : 0.0f) : 0.0f;
+            const float dz = q < NCP ? ez * (1.0f / den) - (q == label ? 1.0f : 0.0f) : 0.0f;
             dzs[row][q] = dz;
             if (rb + row < r1) db2 += dz;
         }
@@ -994,6 +1009,7 @@ __global__ __launch_bounds__(512, NCP <= 10 ? 4 : 2) void mlp_head1024_kernel(
         }
 #pragma unroll
         for (int u = 0; u < TR; ++u) hq[u] = nq[u];
+        label = label_n;
     }
     const int64_t T = (int64_t)HID + (int64_t)HID * NCP + NCP;
     float* P = partial + (int64_t)blockIdx.x * T;
