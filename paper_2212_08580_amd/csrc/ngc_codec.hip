@@ -475,14 +475,18 @@ int ngc_launch_tail(ngc_ctx* ctx, const float* partial, int chunks, int layer, c
     const size_t lds = tail_lds_bytes(n, k, L, cv.nnz, V, tables);
     if (lds > (size_t)ctx->lds_limit) return ngc_fail(ctx, NGC_ERR_INVALID, "tiles do not fit the LDS of a block");
     const int64_t gx = (d + 16 * V - 1) / (16 * V);
+    // The launch is short and bound by its chain of dependent steps, not by bytes: as many groups of
+    // sixteen lanes as there are (layer, worker) messages to form, up to 64, shorten the chain.
+    const int groups = (std::min(64, std::max(16, L * n)) + 3) / 4 * 4;  // whole waves
+    const int threads = 16 * groups;
     ngc_prof_scope ps(ctx, NGC_KERNEL_TAIL);
 #define NGC_TAIL_ARGS partial, chunks, G_dev, C_dev, cv.rowptr, cv.col, cv.coef, cv.nnz, n, k, L, d, layer, args, g_dev, theta_dev, (float)scale
 #define NGC_TAIL_LAUNCH(VT, VV)                                                                                          \
     do {                                                                                                                 \
         if (tables)                                                                                                      \
-            hipLaunchKernelGGL((iteration_tail_kernel<VT, VV, true>), dim3((unsigned)gx), dim3(256), lds, ctx->stream, NGC_TAIL_ARGS); \
+            hipLaunchKernelGGL((iteration_tail_kernel<VT, VV, true>), dim3((unsigned)gx), dim3(threads), lds, ctx->stream, NGC_TAIL_ARGS); \
         else                                                                                                             \
-            hipLaunchKernelGGL((iteration_tail_kernel<VT, VV, false>), dim3((unsigned)gx), dim3(256), lds, ctx->stream, NGC_TAIL_ARGS); \
+            hipLaunchKernelGGL((iteration_tail_kernel<VT, VV, false>), dim3((unsigned)gx), dim3(threads), lds, ctx->stream, NGC_TAIL_ARGS); \
     } while (0)
     if (V == 4)
         NGC_TAIL_LAUNCH(v4f, 4);

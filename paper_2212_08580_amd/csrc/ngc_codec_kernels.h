@@ -446,12 +446,12 @@ __global__ __launch_bounds__(256) void coded_rounds_kernel(
 // Fused tail of one iteration for a tile of 16*V columns: sum of the gradient kernel's block
 // partials (-> G), messages of every layer (-> C), decode with the given vector (-> g) and the
 // descent update of theta, all from LDS, each step in the canonical order of the stand-alone
-// kernels (same bits).  Threads: 16 groups of 16 lanes; a lane owns V columns.  TAB_LDS: the
+// kernels (same bits).  Threads: groups of 16 lanes; a lane owns V columns.  TAB_LDS: the
 // compressed code tables are copied to LDS once per block; otherwise (tables too large for
 // the LDS a block may have) they are read from global memory.
 // ---------------------------------------------------------------------------
 template <typename VT, int V, bool TAB_LDS>
-__global__ __launch_bounds__(256) void iteration_tail_kernel(
+__global__ __launch_bounds__(1024) void iteration_tail_kernel(
     const float* __restrict__ partial, int chunks, float* __restrict__ G, float* __restrict__ C,
     const int* __restrict__ rowptr, const int* __restrict__ col, const float* __restrict__ coef,
     int nnz, int n, int k, int L, int64_t d, int layer, decode_args args, float* __restrict__ g,
@@ -467,19 +467,22 @@ __global__ __launch_bounds__(256) void iteration_tail_kernel(
     const int* rp_s = TAB_LDS ? rp_l : rowptr;
     const int* col_s = TAB_LDS ? col_l : col;
     const float* coef_s = TAB_LDS ? coef_l : coef;
+    // blockDim.x / 16 groups of 16 lanes (16 to 64 of them) share out the partitions of step 1 and the
+    // messages of step 2; the decode keeps to the first sixteen, one per partial sum
     const int lane16 = threadIdx.x & 15;
     const int slot = threadIdx.x >> 4;
+    const int nslot = (int)blockDim.x >> 4;
     const int64_t c = ((int64_t)blockIdx.x * 16 + lane16) * V;
     const bool in = c < d;
     if (TAB_LDS) {
-        for (int t = threadIdx.x; t <= L * n; t += 256) rp_l[t] = rowptr[t];
-        for (int t = threadIdx.x; t < nnz; t += 256) {
+        for (int t = threadIdx.x; t <= L * n; t += (int)blockDim.x) rp_l[t] = rowptr[t];
+        for (int t = threadIdx.x; t < nnz; t += (int)blockDim.x) {
             col_l[t] = col[t];
             coef_l[t] = coef[t];
         }
     }
     // 1. G tile = sum of block partials, chunks added in index order (sixteen loads in flight)
-    for (int j = slot; j < k; j += 16) {
+    for (int j = slot; j < k; j += nslot) {
         VT acc = (VT)(0.0f);
         if (in) {
             const float* p = partial + (int64_t)j * chunks * d + c;
@@ -508,7 +511,7 @@ __global__ __launch_bounds__(256) void iteration_tail_kernel(
     __syncthreads();
     // 2. messages of every (layer, worker) pair; those of the decode layer are kept in LDS
     const int np = L * n;
-    for (int p = slot; p < np; p += 16) {
+    for (int p = slot; p < np; p += nslot) {
         const int b = rp_s[p], e = rp_s[p + 1];
         VT m = (VT)(0.0f);
         int t = b;
@@ -532,16 +535,18 @@ __global__ __launch_bounds__(256) void iteration_tail_kernel(
     double acc[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) acc[v] = 0.0;
-    for (int i = slot; i < n; i += 16) {
-        const double a = args.a[i];
-        if (a != 0.0) {
-            const VT m = msg[i * 16 + lane16];
+    if (slot < 16) {
+        for (int i = slot; i < n; i += 16) {
+            const double a = args.a[i];
+            if (a != 0.0) {
+                const VT m = msg[i * 16 + lane16];
 #pragma unroll
-            for (int v = 0; v < V; ++v) acc[v] = __builtin_fma(a, (double)ngc_get(m, v), acc[v]);
+                for (int v = 0; v < V; ++v) acc[v] = __builtin_fma(a, (double)ngc_get(m, v), acc[v]);
+            }
         }
-    }
 #pragma unroll
-    for (int v = 0; v < V; ++v) part[slot * PW + lane16 * V + v] = acc[v];
+        for (int v = 0; v < V; ++v) part[slot * PW + lane16 * V + v] = acc[v];
+    }
     __syncthreads();
     const int q = threadIdx.x;
     if (q < 16 * V) {
