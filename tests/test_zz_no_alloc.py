@@ -46,7 +46,9 @@ def test_static_scratch_entry_point_two_calls_in_a_row(ngc):
     torch.cuda.set_device(0)
     # first call: the headline shape shrunk in rows only (n = 32, d = 4096, ragged row count);
     # second call: a smaller problem (fewer partitions, shorter unaligned rows, other loss)
-    cases = [(wl.C3.scaled(rows=203, name="static-1"), 11, None),
+    # before them: rows wider than 16384 features (theta in LDS), still one pass and within the scratch
+    cases = [(wl.C3.scaled(rows=9, d=20000, n=2, layers=(0,), name="static-0"), 10, None),
+             (wl.C3.scaled(rows=203, name="static-1"), 11, None),
              (wl.C2.scaled(rows=50, d=1002, n=3, layers=(0,), name="static-2"), 12, 2.0 / np.sqrt(1002))]
     for w, seed, scale in cases:
         print("static entry point: n=%d rows=%d d=%d loss=%d" % (w.n, w.rows, w.d, w.loss), flush=True)
