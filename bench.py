@@ -757,6 +757,8 @@ def bench_pipeline(args, w, wl, ngc, torch, np, K, W, cpu_leg=True, probe=True, 
         # rows of 4, 8, .. 128 features take the kernel that loads several rows at once
         dq = w.d // 4
         grad_kernel = "grad_narrow_kernel" if (w.d % 4 == 0 and w.d <= 128 and dq & (dq - 1) == 0) else "grad_stream_kernel"
+        if w.d > 32768 or (w.d % 4 != 0 and w.d > 8192):   # no single-pass shape: X is read twice
+            grad_kernel = "resid_kernel + xtr_kernel (two passes over X)"
         # algorithmic bytes per launch: X once + labels + theta + G  (4*d bytes per sample)
         grad_bytes = 4.0 * w.m * w.d + 4.0 * w.m + 4.0 * w.d + 4.0 * w.n * w.d
         achieved = grad_bytes / (grad_avg_ms * 1e-3) / 1e9
@@ -925,6 +927,9 @@ def main():
     ap.add_argument("--rows", type=int, default=0,
                     help="rows per partition instead of the workload's own (same distributions): a longer "
                          "stream through the same kernel, named in config.workload")
+    ap.add_argument("--features", type=int, default=0,
+                    help="features per row instead of the workload's own (regression workloads; same "
+                         "distributions): other shapes of the gradient kernel, named in config.workload")
     ap.add_argument("--parts-per-worker", type=int, default=1,
                     help="k = c n (Sec. II-C): the workload's partitions are shared out c to a worker")
     args = ap.parse_args()
@@ -953,11 +958,16 @@ def main():
     if args.mode == "lookup":
         return bench_lookup(args, wl, ngc, torch, np)
     headline_only = (args.workload is not None or args.no_others or args.parts_per_worker != 1 or
-                     args.mode != "pipeline" or args.rows > 0)
+                     args.mode != "pipeline" or args.rows > 0 or args.features > 0)
     w = wl.CONFIGS[args.workload or "C3"]
     if args.rows > 0 and w.loss >= 0:
         import dataclasses
         w = dataclasses.replace(w, rows=args.rows, name="%s-rows%d" % (w.name, args.rows))
+    if args.features > 0:
+        if w.loss not in (wl.LOSS_LSQ, wl.LOSS_LOGISTIC):
+            print("--features needs a regression workload (C1..C3)", file=sys.stderr)
+            sys.exit(2)
+        w = w.scaled(d=args.features, name="%s-d%d" % (w.name, args.features))
     if args.mode == "workers":
         if w.loss < 0:
             print("--mode workers needs a gradient workload (C1..C4)", file=sys.stderr)
