@@ -183,10 +183,15 @@ static void launch_stream(ngc_ctx* ctx, int loss, const float* X, const float* y
 struct stream_shape {
     int nv, r, waves;
     bool ragged, scalar;
-    int narrow_dq = 0;  // > 0: rows of narrow_dq float4 take grad_narrow_kernel (several rows per load)
+    int narrow_dq = 0;  // > 0: rows of narrow_dq elements take a kernel that loads several rows at once
+    bool narrow_any = false;  // narrow_dq is no power of two, or counts single floats (scalar): grad_narrow_any_kernel
 };
 static stream_shape pick_stream_shape(int64_t d) {
     if (d % 4 == 0 && d <= 128 && ((d / 4) & (d / 4 - 1)) == 0) return {1, 8, 1, false, false, (int)(d / 4)};
+    // other short rows: two or more whole rows per wave-wide load
+    // (up to 60 features in float4 and 21 in single floats; beyond that one row per load is as fast or faster)
+    if (d % 4 == 0 && d <= 64) return {1, 8, 1, false, false, (int)(d / 4), true};
+    if (d % 4 != 0 && d <= 21) return {1, 8, 1, false, true, (int)d, true};
     if (d % 1024 == 0) {
         const int w = (int)(d / 1024);
         // narrow rows: one float4 per lane and many waves per block rather than one wave with
@@ -288,7 +293,18 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
     case W: launch_stream<NV, R, 2, W, RG>(NGC_STREAM_ARGS); break;
 #define NGC_STREAM_SCALAR(NV, R, W) \
     case W: launch_stream<NV, R, 2, W, true, float>(NGC_STREAM_ARGS); break;
-            if (sh.narrow_dq) {
+            if (sh.narrow_any) {
+                dim3 grid((unsigned)(k * chunks));
+#define NGC_NARROW_ANY(VT, RR, LOSS_ID)                                                                            \
+    hipLaunchKernelGGL((grad_narrow_any_kernel<VT, RR, LOSS_ID>), grid, dim3(64), 0, ctx->stream, X_dev, y, theta_dev, \
+                       ws, rows, (int)chunks, rpc, unit_part, sh.narrow_dq)
+                if (sh.scalar) {  // (sixteen loads per group instead of eight: a third slower)
+                    if (loss == NGC_LOSS_LSQ) NGC_NARROW_ANY(float, 8, NGC_LOSS_LSQ); else NGC_NARROW_ANY(float, 8, NGC_LOSS_LOGISTIC);
+                } else {
+                    if (loss == NGC_LOSS_LSQ) NGC_NARROW_ANY(v4f, 8, NGC_LOSS_LSQ); else NGC_NARROW_ANY(v4f, 8, NGC_LOSS_LOGISTIC);
+                }
+#undef NGC_NARROW_ANY
+            } else if (sh.narrow_dq) {
                 dim3 grid((unsigned)(k * chunks));
 #define NGC_NARROW_CASE(DQ)                                                                                          \
     case DQ:                                                                                                         \

@@ -341,6 +341,99 @@ __global__ __launch_bounds__(64) void grad_narrow_kernel(const float* __restrict
 }
 
 // ---------------------------------------------------------------------------
+// The same for any short row: dq elements per row (float4 when the rows are 16-byte aligned,
+// dq <= 32; single floats otherwise, dq <= 32), known at run time.  A wave-wide load fetches
+// rpl = 64 / dq whole rows (the lanes past rpl * dq idle: they re-read valid data against a
+// zero of theta and a weight of 0); lane l holds element l % dq of row l / dq.  A row's dot
+// product is a sum over dq consecutive lanes, folded in halves through the cross-lane shuffle
+// (the part past the largest power of two below dq first, then 16, 8, .. 1: a fixed order) and
+// handed back to every lane of the segment from its first lane.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float segment_sum_any(float v, int slot, int seg_base, int dq) {
+    int len = dq;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        if (off < len) {  // wave-uniform
+            const float t = __shfl_down(v, off, 64);
+            if (slot + off < len) v += t;
+            len = off;
+        }
+    }
+    return __shfl(v, seg_base, 64);
+}
+
+template <typename VT, int R>
+struct narrow_any_group {
+    VT x[R];
+    float y[R];
+};
+
+template <typename VT, int R>
+__device__ __forceinline__ void load_narrow_any(narrow_any_group<VT, R>& b, const VT* __restrict__ xp,
+                                                const float* __restrict__ yp, int seg, int slot, int dq, int rpl,
+                                                int64_t row, int64_t last_row) {
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+        int64_t r = row + u * rpl + seg;
+        r = r < last_row ? r : last_row;
+        b.x[u] = __builtin_nontemporal_load(xp + r * dq + slot);
+        b.y[u] = yp[r];
+    }
+}
+
+template <typename VT, int R, int LOSS>
+__global__ __launch_bounds__(64) void grad_narrow_any_kernel(const float* __restrict__ X, const float* __restrict__ y,
+                                                             const float* __restrict__ theta,
+                                                             float* __restrict__ partial, int64_t rows, int chunks,
+                                                             int64_t rows_per_chunk,
+                                                             const int* __restrict__ unit_part, int dq) {
+    __shared__ VT red[64];
+    const int lane = threadIdx.x;
+    const int rpl = 64 / dq;
+    // lanes past the last whole row form a segment of their own (seg == rpl) that counts for nothing
+    const int seg = lane / dq, slot = lane - seg * dq;
+    const bool act = seg < rpl;
+    const int unit = blockIdx.x / chunks;
+    const int j = unit_part ? unit_part[unit] : unit;
+    const int c = blockIdx.x % chunks;
+    const int64_t r0 = (int64_t)c * rows_per_chunk;
+    const int64_t r1 = rows < r0 + rows_per_chunk ? rows : r0 + rows_per_chunk;
+    const VT* xp = reinterpret_cast<const VT*>(X) + (int64_t)j * rows * dq;
+    const float* yp = y + (int64_t)j * rows;
+    const VT th = act ? reinterpret_cast<const VT*>(theta)[slot] : (VT)(0.0f);
+    VT acc = (VT)(0.0f);
+    const int group = R * rpl;  // rows per group
+    const int64_t ngroups = r0 < r1 ? (r1 - r0 + group - 1) / group : 0;
+    if (ngroups > 0) {
+        const int64_t last = r1 - 1;
+        narrow_any_group<VT, R> buf[2];
+        load_narrow_any<VT, R>(buf[0], xp, yp, seg, slot, dq, rpl, r0, last);
+        for (int64_t gb = 0; gb < ngroups; gb += 2) {
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const int64_t gi = gb + p;
+                load_narrow_any<VT, R>(buf[(p + 1) % 2], xp, yp, seg, slot, dq, rpl, r0 + (gi + 1) * group, last);
+                const int64_t row = r0 + gi * group;
+#pragma unroll
+                for (int u = 0; u < R; ++u) {
+                    const float z = segment_sum_any(hsum(buf[p].x[u] * th), slot, seg * dq, dq);
+                    const float live = (act && row + u * rpl + seg < r1) ? 1.0f : 0.0f;
+                    const float res = loss_slope<LOSS>(z, buf[p].y[u]) * live;
+                    acc += res * buf[p].x[u];
+                }
+            }
+        }
+    }
+    red[lane] = acc;
+    __syncthreads();
+    if (lane < dq) {
+        VT s = red[lane];
+        for (int g = 1; g < rpl; ++g) s += red[g * dq + lane];
+        reinterpret_cast<VT*>(partial)[(int64_t)blockIdx.x * dq + lane] = s;
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Generic two-pass route for any d.  Pass 1: one wave per row forms the margin
 // and stores the residual.  Pass 2: a thread adds r*x over a run of rows for its
 // columns; partials are summed by K2.  VEC (d a multiple of 4, X 16-byte

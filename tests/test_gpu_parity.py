@@ -191,6 +191,10 @@ GRAD_SHAPES = [
     # ragged last group, and enough rows for several groups per block
     (8, 3, 1000), (16, 2, 33), (32, 2, 50), (128, 3, 77), (64, 2, 5000), (128, 2, 3001), (4, 1, 70000),
     (64, 64, 3),
+    # short rows whose element count is no power of two, in float4 (d a multiple of 4) or single floats (up to 32
+    # features): two or more whole rows per wave-wide load, idle lanes past the last whole row
+    (12, 3, 1000), (20, 2, 333), (24, 2, 70), (40, 3, 129), (48, 2, 50), (68, 2, 40), (96, 2, 77), (100, 2, 64),
+    (124, 2, 33), (3, 2, 500), (6, 2, 100), (10, 3, 64), (17, 2, 90), (31, 2, 50), (21, 1, 4000),
 ]
 
 
