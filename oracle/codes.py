@@ -76,12 +76,17 @@ def fracrep_code(n, sigma):
 
 
 def min_norm_decode_vector(B, responders):
-    """a with a_S^T B_S = 1^T of least 2-norm, zero outside S (Def. 1, last two bullets)."""
+    """a with a_S^T B_S = 1^T of least 2-norm, zero outside S (Def. 1, last two bullets).
+
+    The rows of a component code span n - sigma dimensions (Def. 1, second bullet), fewer than
+    there are responders whenever more than n - sigma respond; singular values below 1e-10 of
+    the largest are the rounding of the construction (for sigma = n - 1 every row is the
+    all-ones vector up to 1e-14), not part of the code, and are cut."""
     n = B.shape[0]
     S = np.asarray(responders, dtype=int)
     a = np.zeros(n)
     if S.size:
-        sol = np.linalg.lstsq(B[S].T, np.ones(B.shape[1]), rcond=None)[0]
+        sol = np.linalg.lstsq(B[S].T, np.ones(B.shape[1]), rcond=1e-10)[0]
         a[S] = sol
     return a
 

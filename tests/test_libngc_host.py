@@ -261,6 +261,27 @@ def test_guarded_choice_agrees_with_oracle(ngc, n, layers, kind, limits):
         ngc.ngc_destroy(ctx)
 
 
+def test_select_on_the_full_replication_layer(ngc):
+    """sigma = n - 1 (every row the all-ones vector up to the rounding of its construction): the
+    least-norm vector over r responders is 1/r each, from the oracle's code and the library's own."""
+    n, layers = 6, [0, 5]
+    for built in (False, True):
+        ctx = ngc.ngc_create(n, n, layers, 4)
+        try:
+            if built:
+                ngc.ngc_build_code(ctx, ngc.NGC_CODE_CYCLIC, 3)
+            else:
+                ngc.ngc_set_code(ctx, 1, codes.nested_code(n, layers, "cyclic", seed=149, draws=2)[1])
+            for bits in range(1, 2 ** n - 1):
+                m = np.array([(bits >> i) & 1 for i in range(n)], np.uint8)
+                u, a, resid = ngc.ngc_select_decode_vec(ctx, m, n)
+                r = n - int(m.sum())
+                assert u == 1 and resid < 1e-9
+                assert np.allclose(a, np.where(m == 0, 1.0 / r, 0.0), atol=1e-9)
+        finally:
+            ngc.ngc_destroy(ctx)
+
+
 def test_select_reports_singular_for_a_matrix_that_is_no_gradient_code(ngc):
     n = 6
     ctx = ngc.ngc_create(n, n, [0, 2], 4)

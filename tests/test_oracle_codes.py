@@ -360,3 +360,17 @@ def test_guarded_choice_tames_the_tail_of_a_random_code():
         assert np.allclose(a @ Bs[u], 1.0, atol=1e-8)
     assert max(plain) > 20 * max(guarded)
     assert max(guarded) <= 50.0
+
+
+def test_full_replication_layer_gives_equal_weights():
+    """sigma = n - 1: the rows of the component code span one dimension (Def. 1, second bullet:
+    rank n - sigma = 1) and contain 1, so every row is the all-ones vector and the least-norm
+    decode vector over r responders is 1/r on each of them, however the construction rounds."""
+    for seed in (0, 149):
+        B = codes.nested_code(6, [0, 5], "cyclic", seed=seed, draws=2)[1]
+        assert np.allclose(B, 1.0, atol=1e-12)
+        for m in _masks(6, 5):
+            a, resid = coding.decode_vector(B, m)
+            r = 6 - int(m.sum())
+            assert resid < 1e-12
+            assert np.allclose(a, np.where(m == 0, 1.0 / r, 0.0), atol=1e-12)
