@@ -261,6 +261,31 @@ def test_guarded_choice_agrees_with_oracle(ngc, n, layers, kind, limits):
         ngc.ngc_destroy(ctx)
 
 
+def test_guarded_choice_with_several_partitions_per_worker(ngc):
+    """k = c n: the estimate is taken over the k columns of the expanded code on both sides."""
+    n, c, layers = 8, 2, [0, 1, 3, 5]
+    Bs = codes.expand_partitions(codes.nested_code(n, layers, "cyclic", seed=4, draws=2), c)
+    ctx = ngc.ngc_create(n, n * c, layers, 4)
+    try:
+        for u, B in enumerate(Bs):
+            ngc.ngc_set_code(ctx, u, B)
+        rng = np.random.default_rng(11)
+        moved = 0
+        for limit in (1.5, 4.0, 20.0):
+            ngc.ngc_set_decode_guard(ctx, limit)
+            for _ in range(60):
+                m = np.zeros(n, np.uint8)
+                m[rng.choice(n, size=int(rng.integers(0, layers[-1] + 1)), replace=False)] = 1
+                u_o, a_o = coding.select_guarded(Bs, layers, m, limit)
+                u, a, r = ngc.ngc_select_decode_vec(ctx, m, n)
+                assert u == u_o and r < 1e-8
+                assert np.abs(a - a_o).max() <= 1e-7 * max(1.0, np.abs(a_o).max())
+                moved += u != coding.select_layer(layers, m)
+        assert moved > 0
+    finally:
+        ngc.ngc_destroy(ctx)
+
+
 def test_select_on_the_full_replication_layer(ngc):
     """sigma = n - 1 (every row the all-ones vector up to the rounding of its construction): the
     least-norm vector over r responders is 1/r each, from the oracle's code and the library's own."""
