@@ -261,6 +261,11 @@ def test_coded_rounds_with_a_gradient_per_round_and_undecodable_rounds(ngc, torc
     try:
         run_rounds(ngc, torch_dev, ctx, w, Bs, G_h, masks, n * d)
         run_rounds(ngc, torch_dev, ctx, w, Bs, G_h[0], masks[:5], 0)        # fewer rounds afterwards
+        # the guarded layer choice on the same rounds, then the plain rule again
+        ngc.ngc_set_decode_guard(ctx, 50.0)
+        run_rounds(ngc, torch_dev, ctx, w, Bs, G_h, masks, n * d, guard=50.0)
+        ngc.ngc_set_decode_guard(ctx, 0.0)
+        run_rounds(ngc, torch_dev, ctx, w, Bs, G_h[:7], masks[:7], n * d)
     finally:
         ngc.ngc_destroy(ctx)
 
