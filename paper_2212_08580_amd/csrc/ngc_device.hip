@@ -17,6 +17,7 @@
 #include "ngc_dev_common.h"
 
 #include "ngc_grad_kernels.h"
+#include "ngc_grad_flat.h"
 
 // ===========================================================================
 // host-side launchers
@@ -185,9 +186,18 @@ struct stream_shape {
     bool ragged, scalar;
     int narrow_dq = 0;  // > 0: rows of narrow_dq elements take a kernel that loads several rows at once
     bool narrow_any = false;  // narrow_dq is no power of two, or counts single floats (scalar): grad_narrow_any_kernel
+    int flat_dmax = 0;        // > 0: grad_flat_kernel<flat_dmax> (short rows read as one flat stretch of float4)
 };
-static stream_shape pick_stream_shape(int64_t d) {
+// allow_flat: X holds at least one whole float4
+static stream_shape pick_stream_shape(int64_t d, bool allow_flat) {
     if (d % 4 == 0 && d <= 128 && ((d / 4) & (d / 4 - 1)) == 0) return {1, 8, 1, false, false, (int)(d / 4)};
+    // short rows that are not 16-byte addressable one by one, and those multiples of four that the
+    // kernel below serves less well (20 features and more; not 48: its LDS reads would collide
+    // sixteen-way): read as one flat stretch, 64 * (64 / dmax) whole rows per trip and wave
+    if (allow_flat && d < 64 && (d % 4 != 0 || (d >= 20 && d % 16 != 0))) {
+        const int dmax = d < 2 ? 2 : 8 * (int)(d / 8 + 1);  // (4 for d = 3: 6.3 -> 5.8 TB/s)
+        return {1, 1, 1, false, true, 0, false, dmax};
+    }
     // other short rows: two or more whole rows per wave-wide load
     // (up to 60 features in float4 and 21 in single floats; beyond that one row per load is as fast or faster)
     if (d % 4 == 0 && d <= 64) return {1, 8, 1, false, false, (int)(d / 4), true};
@@ -267,7 +277,8 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
     const float* y = (const float*)y_dev;
     const int64_t wave_slots = (int64_t)ctx->cu_count * 8;  // 2 waves per SIMD
 
-    const stream_shape sh = pick_stream_shape(d);
+    const int64_t x_floats = (int64_t)ctx->k * rows * d;
+    const stream_shape sh = pick_stream_shape(d, x_floats >= 4);
     if (sh.waves) {
         // enough blocks to give every SIMD two waves, split evenly over the partitions
         // a CU holds 8 such waves (2 per SIMD at up to 256 registers), so it takes
@@ -276,12 +287,13 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
         // rows of at most 128 features fill no more than half of a wave's lanes: twice the
         // blocks keep as many bytes in flight (measured: 3.1 -> 3.6 TB/s at 64 features,
         // 4.3 -> 5.0 at 100, 5.5 -> 6.1 at 128; wider rows lose 2 % with more than 8)
-        const int per_cu = (sh.waves == 1 && d <= 128) ? 16 : std::max(1, 8 / sh.waves);
+        // (the flat kernel's blocks are four waves with 16 KiB of LDS each: two per CU)
+        const int per_cu = sh.flat_dmax ? 2 : (sh.waves == 1 && d <= 128) ? 16 : std::max(1, 8 / sh.waves);
         const int64_t block_slots = (int64_t)ctx->cu_count * per_cu;
         int64_t chunks = std::max<int64_t>(1, block_slots / k);
         int64_t rpc = (rows + chunks - 1) / chunks;
         // two row groups: one trip of the kernel's loop (a narrow-row group is r loads of 64/dq rows)
-        const int64_t quantum = sh.narrow_dq ? 2 * sh.r * (64 / sh.narrow_dq) : 2 * sh.r;
+        const int64_t quantum = sh.flat_dmax ? 4 * 64 * (64 / sh.flat_dmax) : sh.narrow_dq ? 2 * sh.r * (64 / sh.narrow_dq) : 2 * sh.r;
         rpc = ((rpc + quantum - 1) / quantum) * quantum;
         chunks = (rows + rpc - 1) / rpc;
         rc = get_ws(sizeof(float) * (size_t)k * chunks * d);
@@ -293,7 +305,23 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
     case W: launch_stream<NV, R, 2, W, RG>(NGC_STREAM_ARGS); break;
 #define NGC_STREAM_SCALAR(NV, R, W) \
     case W: launch_stream<NV, R, 2, W, true, float>(NGC_STREAM_ARGS); break;
-            if (sh.narrow_any) {
+            if (sh.flat_dmax) {
+                dim3 grid((unsigned)(k * chunks));
+#define NGC_FLAT_CASE(DMAX)                                                                                         \
+    case DMAX:                                                                                                      \
+        if (loss == NGC_LOSS_LSQ)                                                                                   \
+            hipLaunchKernelGGL((grad_flat_kernel<DMAX, NGC_LOSS_LSQ>), grid, dim3(256), 0, ctx->stream, X_dev, y,   \
+                               theta_dev, ws, rows, (int)chunks, rpc, unit_part, (int)d, x_floats);                 \
+        else                                                                                                        \
+            hipLaunchKernelGGL((grad_flat_kernel<DMAX, NGC_LOSS_LOGISTIC>), grid, dim3(256), 0, ctx->stream, X_dev, \
+                               y, theta_dev, ws, rows, (int)chunks, rpc, unit_part, (int)d, x_floats);              \
+        break;
+                switch (sh.flat_dmax) {
+                    NGC_FLAT_CASE(2) NGC_FLAT_CASE(8) NGC_FLAT_CASE(16) NGC_FLAT_CASE(24) NGC_FLAT_CASE(32)
+                    NGC_FLAT_CASE(40) NGC_FLAT_CASE(48) NGC_FLAT_CASE(56) NGC_FLAT_CASE(64)
+                }
+#undef NGC_FLAT_CASE
+            } else if (sh.narrow_any) {
                 dim3 grid((unsigned)(k * chunks));
 #define NGC_NARROW_ANY(VT, RR, LOSS_ID)                                                                            \
     hipLaunchKernelGGL((grad_narrow_any_kernel<VT, RR, LOSS_ID>), grid, dim3(64), 0, ctx->stream, X_dev, y, theta_dev, \
@@ -402,7 +430,15 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
             ngc_prof_scope ps(ctx, NGC_KERNEL_REDUCE);
             const int64_t dv = sh.scalar ? d : d / 4;
             dim3 grid((unsigned)((dv + 255) / 256), (unsigned)k);
-            if (sh.scalar)
+            if (chunks >= 64) {  // short rows: many partials per partition, few columns
+                dim3 grid64((unsigned)((dv + 63) / 64), (unsigned)k);
+                if (sh.scalar)
+                    hipLaunchKernelGGL((reduce_partials_deep_kernel<float>), grid64, dim3(64), 0, ctx->stream,
+                                       (const float*)ws, G_dev, dv, (int)chunks, unit_row);
+                else
+                    hipLaunchKernelGGL((reduce_partials_deep_kernel<v4f>), grid64, dim3(64), 0, ctx->stream,
+                                       (const v4f*)ws, (v4f*)G_dev, dv, (int)chunks, unit_row);
+            } else if (sh.scalar)
                 hipLaunchKernelGGL((reduce_partials_kernel<float>), grid, dim3(256), 0, ctx->stream,
                                    (const float*)ws, G_dev, dv, (int)chunks, unit_row);
             else

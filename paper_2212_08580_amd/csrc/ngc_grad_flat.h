@@ -1,0 +1,177 @@
+// Partition gradients (least squares / logistic) for rows of fewer than 64 features, of any
+// length: written for those whose length is no multiple of four.  Such rows are not 16-byte
+// addressable one by one, but a run of them is one contiguous stretch of X, and that stretch
+// is: the kernel reads it as it lies, in whole float4 from the 16-byte granule the run starts
+// in, 1 KiB per wave and instruction, and sorts out rows afterwards.  The stretch of one trip
+// (64*R rows) goes through LDS unchanged; there lane l picks up rows l, l+64, ... whole, one
+// element per LDS read, so a row's margin x.theta and its update acc += r*x stay inside one
+// lane and nothing crosses lanes until the block's final sum.  (The lanes' reads are d words
+// apart: no bank conflict for odd d; up to eight-way conflicts, d = 8 * odd, cost nothing
+// measurable, the sixteen-way ones of d = 16 and 48 cost a third and d = 32 two thirds, which is
+// why the launcher keeps those on the kernels that load whole rows.)
+// theta is wave-uniform (scalar registers), the d accumulators of a lane sit in registers, the
+// next trip's float4 are in flight while this one is worked on.
+//
+// A block of four waves owns a run of rows of one partition and each wave a quarter of it
+// (a quarter of the block partials that one-wave blocks would leave to be summed); the trips of
+// a wave's run all start at the same offset (0..3 floats) inside their granule.  Loads
+// never leave X: vector indices are clamped to the last whole float4 of X.  If X ends inside a
+// granule (its float count is no multiple of four) the rows that reach into that granule (one
+// row; up to three if d = 1) cannot be read that way; a block leaves them out of its trips and
+// one lane per such row adds it at the end from single loads.
+// Rows past the end of the run re-read the run's last row with weight 0.
+// One partial per block, summed in block order by the reduction kernel.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "ngc_dev_common.h"
+#include "ngc_grad_kernels.h"
+
+// DMAX: 2 or a multiple of 8, above d; R = 64 / DMAX rows per lane and trip.
+template <int DMAX, int LOSS>
+__global__ __launch_bounds__(256) void grad_flat_kernel(const float* __restrict__ X, const float* __restrict__ y,
+                                                       const float* __restrict__ theta, float* __restrict__ partial,
+                                                       int64_t rows, int chunks, int64_t rows_per_chunk,
+                                                       const int* __restrict__ unit_part, int d, int64_t x_floats) {
+    constexpr int R = 64 / DMAX;
+    constexpr int TRIP_ROWS = 64 * R;
+    constexpr int NL = (R * DMAX + 3) / 4;  // float4 per lane that cover a trip wherever it starts (d < DMAX)
+    __shared__ v4f stage_all[4][NL * 64];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    v4f* stage = stage_all[wave];
+    float* flat = reinterpret_cast<float*>(stage);
+    const int unit = blockIdx.x / chunks;
+    const int j = unit_part ? unit_part[unit] : unit;
+    const int c0 = blockIdx.x % chunks;
+    // the block's run in four quarters, one per wave (rows_per_chunk is a multiple of 4)
+    const int64_t quarter = rows_per_chunk >> 2;
+    int64_t r0 = (int64_t)c0 * rows_per_chunk + wave * quarter;
+    if (r0 > rows) r0 = rows;
+    const int64_t r_end = rows < r0 + quarter ? rows : r0 + quarter;
+    // rows r1 .. r_end - 1 of the run reach into the granule X ends in (at most three rows, and
+    // only in the blocks at the very end of X)
+    int64_t r1 = r_end;
+    if (x_floats & 3) {
+        const int64_t first = (x_floats & ~(int64_t)3) / d - (int64_t)j * rows;  // first such row of this partition
+        if (first < r1) r1 = first > r0 ? first : r0;
+    }
+    const float* yp = y + (int64_t)j * rows;
+    const int64_t f0 = ((int64_t)j * rows + r0) * d;  // first float of the run
+    const int shift = (int)(f0 & 3);
+    const v4f* xv = reinterpret_cast<const v4f*>(X) + (f0 >> 2) + lane;
+    const int64_t vroom = x_floats / 4 - 1 - (f0 >> 2) - lane;  // highest vector offset this lane may load
+    const int trip_vecs = 16 * R * d;                            // TRIP_ROWS * d / 4
+    const int nl = (trip_vecs + (shift != 0) + 63) / 64;         // <= NL
+    float th[DMAX], acc[DMAX];
+#pragma unroll
+    for (int c = 0; c < DMAX; ++c) {
+        th[c] = c < d ? theta[c] : 0.0f;
+        acc[c] = 0.0f;
+    }
+    const int64_t ntrips = r0 < r1 ? (r1 - r0 + TRIP_ROWS - 1) / TRIP_ROWS : 0;
+    if (ntrips > 0) {
+        const int64_t last = r1 - 1;
+        v4f s[NL];
+        float yn[R];
+        auto fetch = [&](int64_t t) {
+            const int64_t vb = t * trip_vecs;
+#pragma unroll
+            for (int u = 0; u < NL; ++u) {
+                if (u < nl) {  // wave-uniform
+                    int64_t v = vb + u * 64;
+                    v = v < vroom ? v : vroom;
+                    s[u] = __builtin_nontemporal_load(xv + v);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < R; ++i) {
+                int64_t r = r0 + t * TRIP_ROWS + lane + 64 * i;
+                r = r < last ? r : last;
+                yn[i] = yp[r];
+            }
+        };
+        fetch(0);
+        for (int64_t t = 0; t < ntrips; ++t) {
+#pragma unroll
+            for (int u = 0; u < NL; ++u)
+                if (u < nl) stage[u * 64 + lane] = s[u];
+            float yc[R];
+#pragma unroll
+            for (int i = 0; i < R; ++i) yc[i] = yn[i];
+            fetch(t + 1);  // past the run's end: clamped re-reads, never used
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            const int64_t left = r1 - (r0 + t * TRIP_ROWS);  // live rows from this trip's start on, >= 1
+            const int lim = (int)(left < TRIP_ROWS ? left : TRIP_ROWS) - 1;
+#pragma unroll
+            for (int i = 0; i < R; ++i) {
+                const int rit = lane + 64 * i;
+                const int rr = rit < lim ? rit : lim;
+                const float* xr = flat + shift + rr * d;
+                float x[DMAX];
+#pragma unroll
+                for (int c = 0; c < DMAX; ++c) x[c] = c < d ? xr[c] : 0.0f;
+                float z = 0.0f;
+#pragma unroll
+                for (int c = 0; c < DMAX; ++c) z = __builtin_fmaf(x[c], th[c], z);
+                const float res = loss_slope<LOSS>(z, yc[i]) * (rit <= lim ? 1.0f : 0.0f);
+#pragma unroll
+                for (int c = 0; c < DMAX; ++c) acc[c] = __builtin_fmaf(res, x[c], acc[c]);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+    if (lane < r_end - r1) {
+        const int64_t r = r1 + lane;
+        const float* xr = X + ((int64_t)j * rows + r) * d;
+        float z = 0.0f;
+        for (int c = 0; c < d; ++c) z = __builtin_fmaf(xr[c], theta[c], z);
+        const float res = loss_slope<LOSS>(z, yp[r]);
+#pragma unroll
+        for (int c = 0; c < DMAX; ++c)
+            if (c < d) acc[c] = __builtin_fmaf(res, xr[c], acc[c]);
+    }
+    // block sum: column c of every lane of every wave, added in wave and lane order by thread c
+    // (stride 65 words: d * 65 floats fit a wave's staging area, and the readers' banks differ)
+    static_assert((DMAX - 1) * 65 <= NL * 64 * 4, "block sum area");
+#pragma unroll
+    for (int c = 0; c < DMAX; ++c)
+        if (c < d) flat[c * 65 + lane] = acc[c];
+    __syncthreads();
+    if (threadIdx.x < d) {
+        float sum = 0.0f;
+        for (int w = 0; w < 4; ++w) {
+            const float* fw = reinterpret_cast<const float*>(stage_all[w]) + threadIdx.x * 65;
+            for (int l = 0; l < 64; ++l) sum += fw[l];
+        }
+        partial[(int64_t)blockIdx.x * d + threadIdx.x] = sum;
+    }
+}
+
+// G[j][:] = sum over chunks of partial[j][chunk][:], chunks added in index order, for launches
+// that leave many block partials per partition (short rows: hundreds to a thousand): the same
+// sum, term by term, as reduce_partials_kernel, with sixteen loads of a thread in flight instead
+// of four (a thread's additions wait for memory, not for each other).
+template <typename VT>
+__global__ __launch_bounds__(64) void reduce_partials_deep_kernel(const VT* __restrict__ partial, VT* __restrict__ G,
+                                                                  int64_t dv, int chunks,
+                                                                  const int* __restrict__ unit_row) {
+    const int64_t c = (int64_t)blockIdx.x * 64 + threadIdx.x;
+    const int j = blockIdx.y;
+    if (c >= dv) return;
+    const VT* p = partial + (int64_t)j * chunks * dv + c;
+    VT acc = p[0];
+    int t = 1;
+    for (; t + 16 <= chunks; t += 16) {
+        VT a[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) a[u] = p[(int64_t)(t + u) * dv];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) acc += a[u];
+    }
+    for (; t < chunks; ++t) acc += p[(int64_t)t * dv];
+    G[(int64_t)(unit_row ? unit_row[j] : j) * dv + c] = acc;
+}
