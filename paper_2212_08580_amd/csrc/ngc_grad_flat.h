@@ -15,7 +15,8 @@
 // A block of four waves owns a run of rows of one partition and each wave a quarter of it
 // (a quarter of the block partials that one-wave blocks would leave to be summed); the trips of
 // a wave's run all start at the same offset (0..3 floats) inside their granule.  Loads
-// never leave X: vector indices are clamped to the last whole float4 of X.  If X ends inside a
+// never leave the run: vector indices are clamped to the last float4 of the trip and of the
+// run (so no byte is fetched twice either), which is a whole float4 of X.  If X ends inside a
 // granule (its float count is no multiple of four) the rows that reach into that granule (one
 // row; up to three if d = 1) cannot be read that way; a block leaves them out of its trips and
 // one lane per such row adds it at the end from single loads.
@@ -60,10 +61,13 @@ __global__ __launch_bounds__(256) void grad_flat_kernel(const float* __restrict_
     const float* yp = y + (int64_t)j * rows;
     const int64_t f0 = ((int64_t)j * rows + r0) * d;  // first float of the run
     const int shift = (int)(f0 & 3);
-    const v4f* xv = reinterpret_cast<const v4f*>(X) + (f0 >> 2) + lane;
-    const int64_t vroom = x_floats / 4 - 1 - (f0 >> 2) - lane;  // highest vector offset this lane may load
-    const int trip_vecs = 16 * R * d;                            // TRIP_ROWS * d / 4
-    const int nl = (trip_vecs + (shift != 0) + 63) / 64;         // <= NL
+    const v4f* xv = reinterpret_cast<const v4f*>(X) + (f0 >> 2);
+    const int trip_vecs = 16 * R * d;                     // TRIP_ROWS * d / 4
+    const int trip_last = trip_vecs - (shift == 0);       // last float4 of a trip, counted from its first
+    const int nl = trip_last / 64 + 1;                    // <= NL
+    // last float4 the run needs, counted from its first: the one that holds the last float of
+    // row r1 - 1, a whole float4 of X.  Lanes past the end of a trip or of the run re-read those.
+    const int64_t run_last = ((((int64_t)j * rows + r1) * d - 1) >> 2) - (f0 >> 2);
     float th[DMAX], acc[DMAX];
 #pragma unroll
     for (int c = 0; c < DMAX; ++c) {
@@ -76,13 +80,17 @@ __global__ __launch_bounds__(256) void grad_flat_kernel(const float* __restrict_
         v4f s[NL];
         float yn[R];
         auto fetch = [&](int64_t t) {
-            const int64_t vb = t * trip_vecs;
+            // wave-uniform base and room, a 32-bit offset per lane
+            int64_t vb = t * trip_vecs;
+            vb = vb < run_last ? vb : run_last;
+            const int64_t room64 = run_last - vb;
+            const int room = room64 < trip_last ? (int)room64 : trip_last;
+            const v4f* tb = xv + vb;
 #pragma unroll
             for (int u = 0; u < NL; ++u) {
                 if (u < nl) {  // wave-uniform
-                    int64_t v = vb + u * 64;
-                    v = v < vroom ? v : vroom;
-                    s[u] = __builtin_nontemporal_load(xv + v);
+                    const int rel = u * 64 + lane;
+                    s[u] = __builtin_nontemporal_load(tb + (rel < room ? rel : room));
                 }
             }
 #pragma unroll
