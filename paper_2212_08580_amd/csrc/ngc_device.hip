@@ -186,7 +186,8 @@ struct stream_shape {
     bool ragged, scalar;
     int narrow_dq = 0;  // > 0: rows of narrow_dq elements take a kernel that loads several rows at once
     bool narrow_any = false;  // narrow_dq is no power of two, or counts single floats (scalar): grad_narrow_any_kernel
-    int flat_dmax = 0;        // > 0: grad_flat_kernel<flat_dmax> (short rows read as one flat stretch of float4)
+    int flat_dmax = 0;        // > 0: grad_flat_kernel<flat_dmax, flat_lanes> (rows read as one flat stretch of float4)
+    int flat_lanes = 1;       // lanes that share a row
 };
 // allow_flat: X holds at least one whole float4
 static stream_shape pick_stream_shape(int64_t d, bool allow_flat) {
@@ -198,8 +199,16 @@ static stream_shape pick_stream_shape(int64_t d, bool allow_flat) {
         const int dmax = d < 2 ? 2 : 8 * (int)(d / 8 + 1);  // (4 for d = 3: 6.3 -> 5.8 TB/s)
         return {1, 1, 1, false, true, 0, false, dmax};
     }
-    // other short rows: two or more whole rows per wave-wide load
-    // (up to 60 features in float4 and 21 in single floats; beyond that one row per load is as fast or faster)
+    // the same, four or eight lanes to a row, for rows of 65 to 248 features that are no multiple
+    // of 4 and for the multiples of 4 up to 132 (from 144 on the kernel with one float4 per lane
+    // and row is as fast: 6.7-6.85 TB/s)
+    if (allow_flat && d > 64 && d <= 248 && (d % 4 != 0 || d <= 132)) {
+        const int lanes = d <= 124 ? 4 : 8;
+        const int h = (int)((d + lanes - 1) / lanes);  // 16 .. 31
+        return {1, 1, 1, false, true, 0, false, 8 * (h / 8 + 1), lanes};
+    }
+    // what is left of the short rows (12 and 48 features in float4; single floats only when X holds
+    // fewer than four floats): two or more whole rows per wave-wide load
     if (d % 4 == 0 && d <= 64) return {1, 8, 1, false, false, (int)(d / 4), true};
     if (d % 4 != 0 && d <= 21) return {1, 8, 1, false, true, (int)d, true};
     if (d % 1024 == 0) {
@@ -218,10 +227,7 @@ static stream_shape pick_stream_shape(int64_t d, bool allow_flat) {
     if (d > 16384 && d <= 32768 && d % 4 == 0) return {8, 1, 2 * (int)((d / 4 + 1023) / 1024), true, false};
     if (d < 1 || d > 16384) return {0, 0, 0, false, false};
     if (d % 4 != 0) {
-        if (d <= 64) return {1, 16, 1, true, true};   // as few idle lanes as the row length allows
-        if (d <= 128) return {2, 16, 1, true, true};
-        if (d <= 192) return {3, 16, 1, true, true};
-        if (d <= 256) return {4, 16, 1, true, true};
+        if (d <= 256) return {4, 16, 1, true, true};  // 249 .. 255 (shorter rows are read as a flat stretch)
         if (d <= 4096) return {8, 8, (int)((d + 511) / 512), true, true};
         if (d <= 8192) return {16, 3, (int)((d + 1023) / 1024), true, true};
         return {0, 0, 0, false, false};
@@ -293,7 +299,7 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
         int64_t chunks = std::max<int64_t>(1, block_slots / k);
         int64_t rpc = (rows + chunks - 1) / chunks;
         // two row groups: one trip of the kernel's loop (a narrow-row group is r loads of 64/dq rows)
-        const int64_t quantum = sh.flat_dmax ? 4 * 64 * (64 / sh.flat_dmax) : sh.narrow_dq ? 2 * sh.r * (64 / sh.narrow_dq) : 2 * sh.r;
+        const int64_t quantum = sh.flat_dmax ? 4 * (64 / sh.flat_lanes) * (64 / sh.flat_dmax) : sh.narrow_dq ? 2 * sh.r * (64 / sh.narrow_dq) : 2 * sh.r;
         rpc = ((rpc + quantum - 1) / quantum) * quantum;
         chunks = (rows + rpc - 1) / rpc;
         rc = get_ws(sizeof(float) * (size_t)k * chunks * d);
@@ -307,18 +313,20 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
     case W: launch_stream<NV, R, 2, W, true, float>(NGC_STREAM_ARGS); break;
             if (sh.flat_dmax) {
                 dim3 grid((unsigned)(k * chunks));
-#define NGC_FLAT_CASE(DMAX)                                                                                         \
-    case DMAX:                                                                                                      \
+#define NGC_FLAT_CASE(DMAX, LANES)                                                                                  \
+    case DMAX * 16 + LANES:                                                                                         \
         if (loss == NGC_LOSS_LSQ)                                                                                   \
-            hipLaunchKernelGGL((grad_flat_kernel<DMAX, NGC_LOSS_LSQ>), grid, dim3(256), 0, ctx->stream, X_dev, y,   \
-                               theta_dev, ws, rows, (int)chunks, rpc, unit_part, (int)d, x_floats);                 \
+            hipLaunchKernelGGL((grad_flat_kernel<DMAX, LANES, NGC_LOSS_LSQ>), grid, dim3(256), 0, ctx->stream,      \
+                               X_dev, y, theta_dev, ws, rows, (int)chunks, rpc, unit_part, (int)d, x_floats);       \
         else                                                                                                        \
-            hipLaunchKernelGGL((grad_flat_kernel<DMAX, NGC_LOSS_LOGISTIC>), grid, dim3(256), 0, ctx->stream, X_dev, \
-                               y, theta_dev, ws, rows, (int)chunks, rpc, unit_part, (int)d, x_floats);              \
+            hipLaunchKernelGGL((grad_flat_kernel<DMAX, LANES, NGC_LOSS_LOGISTIC>), grid, dim3(256), 0, ctx->stream, \
+                               X_dev, y, theta_dev, ws, rows, (int)chunks, rpc, unit_part, (int)d, x_floats);       \
         break;
-                switch (sh.flat_dmax) {
-                    NGC_FLAT_CASE(2) NGC_FLAT_CASE(8) NGC_FLAT_CASE(16) NGC_FLAT_CASE(24) NGC_FLAT_CASE(32)
-                    NGC_FLAT_CASE(40) NGC_FLAT_CASE(48) NGC_FLAT_CASE(56) NGC_FLAT_CASE(64)
+                switch (sh.flat_dmax * 16 + sh.flat_lanes) {
+                    NGC_FLAT_CASE(2, 1) NGC_FLAT_CASE(8, 1) NGC_FLAT_CASE(16, 1) NGC_FLAT_CASE(24, 1)
+                    NGC_FLAT_CASE(32, 1) NGC_FLAT_CASE(40, 1) NGC_FLAT_CASE(48, 1) NGC_FLAT_CASE(56, 1)
+                    NGC_FLAT_CASE(64, 1) NGC_FLAT_CASE(24, 4) NGC_FLAT_CASE(32, 4) NGC_FLAT_CASE(24, 8)
+                    NGC_FLAT_CASE(32, 8)
                 }
 #undef NGC_FLAT_CASE
             } else if (sh.narrow_any) {
@@ -349,13 +357,7 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
                 }
 #undef NGC_NARROW_CASE
             } else if (sh.scalar) {
-                if (sh.nv == 1) {
-                    launch_stream<1, 16, 2, 1, true, float>(NGC_STREAM_ARGS);
-                } else if (sh.nv == 2) {
-                    launch_stream<2, 16, 2, 1, true, float>(NGC_STREAM_ARGS);
-                } else if (sh.nv == 3) {
-                    launch_stream<3, 16, 2, 1, true, float>(NGC_STREAM_ARGS);
-                } else if (sh.nv == 4) {
+                if (sh.nv == 4) {
                     launch_stream<4, 16, 2, 1, true, float>(NGC_STREAM_ARGS);
                 } else if (sh.nv == 8) {
                     switch (sh.waves) {

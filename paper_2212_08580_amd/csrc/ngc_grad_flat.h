@@ -1,15 +1,16 @@
-// Partition gradients (least squares / logistic) for rows of fewer than 64 features, of any
-// length: written for those whose length is no multiple of four.  Such rows are not 16-byte
+// Partition gradients (least squares / logistic) for short rows (up to some 250 features) of
+// any length: written for those whose length is no multiple of four.  Such rows are not 16-byte
 // addressable one by one, but a run of them is one contiguous stretch of X, and that stretch
 // is: the kernel reads it as it lies, in whole float4 from the 16-byte granule the run starts
 // in, 1 KiB per wave and instruction, and sorts out rows afterwards.  The stretch of one trip
-// (64*R rows) goes through LDS unchanged; there lane l picks up rows l, l+64, ... whole, one
-// element per LDS read, so a row's margin x.theta and its update acc += r*x stay inside one
-// lane and nothing crosses lanes until the block's final sum.  (The lanes' reads are d words
+// goes through LDS unchanged; there (rows of fewer than 64 features) lane l picks up rows l,
+// l+64, ... whole, one element per LDS read, so a row's margin x.theta and its update
+// acc += r*x stay inside one lane and nothing crosses lanes until the block's final sum; longer
+// rows are shared by four or eight lanes, see below.  (The lanes' reads are d words
 // apart: no bank conflict for odd d; up to eight-way conflicts, d = 8 * odd, cost nothing
 // measurable, the sixteen-way ones of d = 16 and 48 cost a third and d = 32 two thirds, which is
 // why the launcher keeps those on the kernels that load whole rows.)
-// theta is wave-uniform (scalar registers), the d accumulators of a lane sit in registers, the
+// theta is wave-uniform then (scalar registers), the accumulators of a lane sit in registers, the
 // next trip's float4 are in flight while this one is worked on.
 //
 // A block of four waves owns a run of rows of one partition and each wave a quarter of it
@@ -29,15 +30,22 @@
 #include "ngc_dev_common.h"
 #include "ngc_grad_kernels.h"
 
-// DMAX: 2 or a multiple of 8, above d; R = 64 / DMAX rows per lane and trip.
-template <int DMAX, int LOSS>
+// L lanes share a row (L = 1 for d < 64; 4 or 8 for longer rows): lane l works on row l / L of a
+// pass and owns the h = ceil(d / L) columns from (l % L) * h on; the L partial margins meet
+// through cross-lane exchanges in a fixed order.  DMAX: 2 or a multiple of 8, above h.
+// A trip is R = 64 / DMAX passes of 64 / L rows.
+template <int DMAX, int L, int LOSS>
 __global__ __launch_bounds__(256) void grad_flat_kernel(const float* __restrict__ X, const float* __restrict__ y,
                                                        const float* __restrict__ theta, float* __restrict__ partial,
                                                        int64_t rows, int chunks, int64_t rows_per_chunk,
                                                        const int* __restrict__ unit_part, int d, int64_t x_floats) {
     constexpr int R = 64 / DMAX;
-    constexpr int TRIP_ROWS = 64 * R;
-    constexpr int NL = (R * DMAX + 3) / 4;  // float4 per lane that cover a trip wherever it starts (d < DMAX)
+    constexpr int PASS_ROWS = 64 / L;
+    constexpr int TRIP_ROWS = PASS_ROWS * R;
+    constexpr int NL = (R * DMAX + 3) / 4;  // float4 per lane that cover a trip wherever it starts (h < DMAX)
+    static_assert(TRIP_ROWS % 4 == 0, "a trip is a whole number of float4");
+    // an LDS read of column DMAX - 1 of the last part of a trip's last row stays inside the staging area
+    static_assert(L == 1 || 64 * R > L + DMAX + 2, "staging area");
     __shared__ v4f stage_all[4][NL * 64];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -62,16 +70,21 @@ __global__ __launch_bounds__(256) void grad_flat_kernel(const float* __restrict_
     const int64_t f0 = ((int64_t)j * rows + r0) * d;  // first float of the run
     const int shift = (int)(f0 & 3);
     const v4f* xv = reinterpret_cast<const v4f*>(X) + (f0 >> 2);
-    const int trip_vecs = 16 * R * d;                     // TRIP_ROWS * d / 4
+    const int trip_vecs = (TRIP_ROWS / 4) * d;
     const int trip_last = trip_vecs - (shift == 0);       // last float4 of a trip, counted from its first
     const int nl = trip_last / 64 + 1;                    // <= NL
     // last float4 the run needs, counted from its first: the one that holds the last float of
     // row r1 - 1, a whole float4 of X.  Lanes past the end of a trip or of the run re-read those.
     const int64_t run_last = ((((int64_t)j * rows + r1) * d - 1) >> 2) - (f0 >> 2);
+    // this lane's row within a pass and its columns cbase .. cbase + hc - 1
+    const int prow = lane / L;
+    const int h = (d + L - 1) / L;
+    const int cbase = (lane % L) * h;
+    const int hc = d - cbase < h ? (d - cbase > 0 ? d - cbase : 0) : h;
     float th[DMAX], acc[DMAX];
 #pragma unroll
     for (int c = 0; c < DMAX; ++c) {
-        th[c] = c < d ? theta[c] : 0.0f;
+        th[c] = c < hc ? theta[cbase + c] : 0.0f;
         acc[c] = 0.0f;
     }
     const int64_t ntrips = r0 < r1 ? (r1 - r0 + TRIP_ROWS - 1) / TRIP_ROWS : 0;
@@ -95,7 +108,7 @@ __global__ __launch_bounds__(256) void grad_flat_kernel(const float* __restrict_
             }
 #pragma unroll
             for (int i = 0; i < R; ++i) {
-                int64_t r = r0 + t * TRIP_ROWS + lane + 64 * i;
+                int64_t r = r0 + t * TRIP_ROWS + prow + PASS_ROWS * i;
                 r = r < last ? r : last;
                 yn[i] = yp[r];
             }
@@ -115,15 +128,17 @@ __global__ __launch_bounds__(256) void grad_flat_kernel(const float* __restrict_
             const int lim = (int)(left < TRIP_ROWS ? left : TRIP_ROWS) - 1;
 #pragma unroll
             for (int i = 0; i < R; ++i) {
-                const int rit = lane + 64 * i;
+                const int rit = prow + PASS_ROWS * i;
                 const int rr = rit < lim ? rit : lim;
-                const float* xr = flat + shift + rr * d;
+                const float* xr = flat + shift + rr * d + cbase;
                 float x[DMAX];
 #pragma unroll
-                for (int c = 0; c < DMAX; ++c) x[c] = c < d ? xr[c] : 0.0f;
+                for (int c = 0; c < DMAX; ++c) x[c] = c < hc ? xr[c] : 0.0f;
                 float z = 0.0f;
 #pragma unroll
                 for (int c = 0; c < DMAX; ++c) z = __builtin_fmaf(x[c], th[c], z);
+#pragma unroll
+                for (int m = 1; m < L; m <<= 1) z += __shfl_xor(z, m, 64);
                 const float res = loss_slope<LOSS>(z, yc[i]) * (rit <= lim ? 1.0f : 0.0f);
 #pragma unroll
                 for (int c = 0; c < DMAX; ++c) acc[c] = __builtin_fmaf(res, x[c], acc[c]);
@@ -132,28 +147,30 @@ __global__ __launch_bounds__(256) void grad_flat_kernel(const float* __restrict_
             __builtin_amdgcn_wave_barrier();
         }
     }
-    if (lane < r_end - r1) {
-        const int64_t r = r1 + lane;
+    if (prow < r_end - r1) {
+        const int64_t r = r1 + prow;
         const float* xr = X + ((int64_t)j * rows + r) * d;
         float z = 0.0f;
         for (int c = 0; c < d; ++c) z = __builtin_fmaf(xr[c], theta[c], z);
         const float res = loss_slope<LOSS>(z, yp[r]);
 #pragma unroll
         for (int c = 0; c < DMAX; ++c)
-            if (c < d) acc[c] = __builtin_fmaf(res, xr[c], acc[c]);
+            if (c < hc) acc[c] = __builtin_fmaf(res, xr[cbase + c], acc[c]);
     }
-    // block sum: column c of every lane of every wave, added in wave and lane order by thread c
-    // (stride 65 words: d * 65 floats fit a wave's staging area, and the readers' banks differ)
+    // block sum: a column's accumulators (one per wave and row of a pass), added in wave and
+    // lane order by one thread per column (stride 65 words: h * 65 floats fit a wave's staging
+    // area, and the readers' banks differ)
     static_assert((DMAX - 1) * 65 <= NL * 64 * 4, "block sum area");
 #pragma unroll
     for (int c = 0; c < DMAX; ++c)
-        if (c < d) flat[c * 65 + lane] = acc[c];
+        if (c < h) flat[c * 65 + lane] = acc[c];
     __syncthreads();
-    if (threadIdx.x < d) {
+    if ((int)threadIdx.x < d) {
+        const int part = threadIdx.x / h, c = threadIdx.x - part * h;
         float sum = 0.0f;
         for (int w = 0; w < 4; ++w) {
-            const float* fw = reinterpret_cast<const float*>(stage_all[w]) + threadIdx.x * 65;
-            for (int l = 0; l < 64; ++l) sum += fw[l];
+            const float* fw = reinterpret_cast<const float*>(stage_all[w]) + c * 65 + part;
+            for (int g = 0; g < PASS_ROWS; ++g) sum += fw[g * L];
         }
         partial[(int64_t)blockIdx.x * d + threadIdx.x] = sum;
     }

@@ -201,6 +201,9 @@ GRAD_SHAPES = [
     (7, 3, 1001), (13, 2, 333), (23, 3, 71), (29, 2, 4097), (33, 2, 515), (39, 1, 77), (47, 3, 301), (55, 2, 129),
     (63, 3, 1001), (57, 1, 5), (63, 2, 20000), (3, 1, 70001), (1, 1, 3), (2, 1, 1), (1, 5, 1), (9, 1, 1), (61, 1, 1),
     (1, 17, 54), (1, 7, 1), (1, 2, 3), (1, 3, 513), (2, 3, 171), (3, 5, 1),   # several rows in X's last granule
+    # rows of 65 to 248 features that are no multiple of 4: the same kernel with four or eight lanes to a row
+    (65, 3, 1000), (91, 2, 300), (93, 2, 129), (125, 2, 77), (185, 1, 50), (247, 3, 333), (249, 2, 20), (101, 1, 1),
+    (67, 5, 3), (199, 2, 5000), (127, 1, 9000), (72, 2, 130), (88, 3, 33), (112, 1, 400), (132, 2, 65),
     # the multiples of four that take the same kernel
     (20, 3, 777), (28, 2, 130), (36, 2, 65), (44, 1, 300), (52, 2, 64), (56, 3, 100), (60, 2, 4100),
 ]
