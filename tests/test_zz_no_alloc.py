@@ -49,7 +49,10 @@ def test_static_scratch_entry_point_two_calls_in_a_row(ngc):
     # before them: rows wider than 16384 features (theta in LDS), still one pass and within the scratch
     cases = [(wl.C3.scaled(rows=9, d=20000, n=2, layers=(0,), name="static-0"), 10, None),
              (wl.C3.scaled(rows=203, name="static-1"), 11, None),
-             (wl.C2.scaled(rows=50, d=1002, n=3, layers=(0,), name="static-2"), 12, 2.0 / np.sqrt(1002))]
+             (wl.C2.scaled(rows=50, d=1002, n=3, layers=(0,), name="static-2"), 12, 2.0 / np.sqrt(1002)),
+             # short rows read as one flat stretch: one lane per row, then eight lanes per row; X ends inside a float4
+             (wl.C3.scaled(rows=3001, d=54, n=3, layers=(0,), name="static-3"), 13, None),
+             (wl.C2.scaled(rows=77, d=199, n=1, layers=(0,), name="static-4"), 14, 2.0 / np.sqrt(199))]
     for w, seed, scale in cases:
         print("static entry point: n=%d rows=%d d=%d loss=%d" % (w.n, w.rows, w.d, w.loss), flush=True)
         ctx, (Xd, Yd, thd), G_static, G_alloc, X, Y, th = run_both(ngc, torch, w, seed, scale)
