@@ -193,9 +193,9 @@ struct stream_shape {
 static stream_shape pick_stream_shape(int64_t d, bool allow_flat) {
     if (d % 4 == 0 && d <= 128 && ((d / 4) & (d / 4 - 1)) == 0) return {1, 8, 1, false, false, (int)(d / 4)};
     // short rows that are not 16-byte addressable one by one, and those multiples of four that the
-    // kernel below serves less well (20 features and more; not 48: its LDS reads would collide
-    // sixteen-way): read as one flat stretch, 64 * (64 / dmax) whole rows per trip and wave
-    if (allow_flat && d < 64 && (d % 4 != 0 || (d >= 20 && d % 16 != 0))) {
+    // kernel below serves less well (20 features and more; 48 with padded rows in LDS, or its reads
+    // would collide sixteen-way): read as one flat stretch, 64 * (64 / dmax) whole rows per trip and wave
+    if (allow_flat && d < 64 && (d % 4 != 0 || d >= 20)) {
         const int dmax = d < 2 ? 2 : 8 * (int)(d / 8 + 1);  // (4 for d = 3: 6.3 -> 5.8 TB/s)
         return {1, 1, 1, false, true, 0, false, dmax};
     }
@@ -322,6 +322,18 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
             hipLaunchKernelGGL((grad_flat_kernel<DMAX, LANES, NGC_LOSS_LOGISTIC>), grid, dim3(256), 0, ctx->stream, \
                                X_dev, y, theta_dev, ws, rows, (int)chunks, rpc, unit_part, (int)d, x_floats);       \
         break;
+#define NGC_FLAT_PAD_CASE(DMAX)                                                                                      \
+    case DMAX:                                                                                                       \
+        if (loss == NGC_LOSS_LSQ)                                                                                    \
+            hipLaunchKernelGGL((grad_flat_kernel<DMAX, 1, NGC_LOSS_LSQ, true>), grid, dim3(256), 0, ctx->stream,     \
+                               X_dev, y, theta_dev, ws, rows, (int)chunks, rpc, unit_part, (int)d, x_floats);        \
+        else                                                                                                         \
+            hipLaunchKernelGGL((grad_flat_kernel<DMAX, 1, NGC_LOSS_LOGISTIC, true>), grid, dim3(256), 0, ctx->stream, \
+                               X_dev, y, theta_dev, ws, rows, (int)chunks, rpc, unit_part, (int)d, x_floats);        \
+        break;
+                if (d == 48) {  // padded rows in LDS (for 24, 40 and 56 features they change nothing measurable)
+                    switch (sh.flat_dmax) { NGC_FLAT_PAD_CASE(56) }
+                } else
                 switch (sh.flat_dmax * 16 + sh.flat_lanes) {
                     NGC_FLAT_CASE(2, 1) NGC_FLAT_CASE(8, 1) NGC_FLAT_CASE(16, 1) NGC_FLAT_CASE(24, 1)
                     NGC_FLAT_CASE(32, 1) NGC_FLAT_CASE(40, 1) NGC_FLAT_CASE(48, 1) NGC_FLAT_CASE(56, 1)
@@ -329,6 +341,7 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
                     NGC_FLAT_CASE(32, 8)
                 }
 #undef NGC_FLAT_CASE
+#undef NGC_FLAT_PAD_CASE
             } else if (sh.narrow_any) {
                 dim3 grid((unsigned)(k * chunks));
 #define NGC_NARROW_ANY(VT, RR, LOSS_ID)                                                                            \

@@ -8,8 +8,8 @@
 // acc += r*x stay inside one lane and nothing crosses lanes until the block's final sum; longer
 // rows are shared by four or eight lanes, see below.  (The lanes' reads are d words
 // apart: no bank conflict for odd d; up to eight-way conflicts, d = 8 * odd, cost nothing
-// measurable, the sixteen-way ones of d = 16 and 48 cost a third and d = 32 two thirds, which is
-// why the launcher keeps those on the kernels that load whole rows.)
+// measurable, the sixteen-way ones of d = 16 and 48 cost a third and d = 32 two thirds: 48 takes
+// the padded layout below, 16 and 32 the kernels that load whole rows.)
 // theta is wave-uniform then (scalar registers), the accumulators of a lane sit in registers, the
 // next trip's float4 are in flight while this one is worked on.
 //
@@ -34,7 +34,10 @@
 // pass and owns the h = ceil(d / L) columns from (l % L) * h on; the L partial margins meet
 // through cross-lane exchanges in a fixed order.  DMAX: 2 or a multiple of 8, above h.
 // A trip is R = 64 / DMAX passes of 64 / L rows.
-template <int DMAX, int L, int LOSS>
+// PAD (L = 1, d a multiple of 8): a row takes d + 4 words of LDS, its float4 land one slot
+// further per row before them, and the lanes' reads are d + 4 words apart instead of d: for
+// d = 48 that turns sixteen-way bank conflicts into four-way ones (5.3 -> 6.2 TB/s).
+template <int DMAX, int L, int LOSS, bool PAD = false>
 __global__ __launch_bounds__(256) void grad_flat_kernel(const float* __restrict__ X, const float* __restrict__ y,
                                                        const float* __restrict__ theta, float* __restrict__ partial,
                                                        int64_t rows, int chunks, int64_t rows_per_chunk,
@@ -46,6 +49,7 @@ __global__ __launch_bounds__(256) void grad_flat_kernel(const float* __restrict_
     static_assert(TRIP_ROWS % 4 == 0, "a trip is a whole number of float4");
     // an LDS read of column DMAX - 1 of the last part of a trip's last row stays inside the staging area
     static_assert(L == 1 || 64 * R > L + DMAX + 2, "staging area");
+    static_assert(!PAD || (L == 1 && DMAX >= 16), "padded rows: d + 4 <= DMAX - 4, so a trip still fits");
     __shared__ v4f stage_all[4][NL * 64];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -92,6 +96,14 @@ __global__ __launch_bounds__(256) void grad_flat_kernel(const float* __restrict_
         const int64_t last = r1 - 1;
         v4f s[NL];
         float yn[R];
+        // LDS slot of this lane's u-th float4 of a trip (the same in every trip)
+        int slot[NL];
+#pragma unroll
+        for (int u = 0; u < NL; ++u) {
+            const int v = u * 64 + lane;
+            slot[u] = PAD ? v + v / (d >> 2) : v;
+        }
+        const int pitch = PAD ? d + 4 : d;
         auto fetch = [&](int64_t t) {
             // wave-uniform base and room, a 32-bit offset per lane
             int64_t vb = t * trip_vecs;
@@ -117,7 +129,7 @@ __global__ __launch_bounds__(256) void grad_flat_kernel(const float* __restrict_
         for (int64_t t = 0; t < ntrips; ++t) {
 #pragma unroll
             for (int u = 0; u < NL; ++u)
-                if (u < nl) stage[u * 64 + lane] = s[u];
+                if (u < nl) stage[slot[u]] = s[u];
             float yc[R];
 #pragma unroll
             for (int i = 0; i < R; ++i) yc[i] = yn[i];
@@ -130,7 +142,7 @@ __global__ __launch_bounds__(256) void grad_flat_kernel(const float* __restrict_
             for (int i = 0; i < R; ++i) {
                 const int rit = prow + PASS_ROWS * i;
                 const int rr = rit < lim ? rit : lim;
-                const float* xr = flat + shift + rr * d + cbase;
+                const float* xr = flat + shift + rr * pitch + cbase;
                 float x[DMAX];
 #pragma unroll
                 for (int c = 0; c < DMAX; ++c) x[c] = c < hc ? xr[c] : 0.0f;
