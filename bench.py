@@ -758,7 +758,7 @@ def bench_pipeline(args, w, wl, ngc, torch, np, K, W, cpu_leg=True, probe=True, 
         dq = w.d // 4
         grad_kernel = "grad_narrow_kernel" if (w.d % 4 == 0 and w.d <= 128 and dq & (dq - 1) == 0) else "grad_stream_kernel"
         # other rows of fewer than 64 features (all that are no multiple of 4) are read as one flat stretch
-        if (w.d < 64 and (w.d % 4 != 0 or (w.d >= 20 and w.d != 32))) or \
+        if (w.d < 64 and (w.d % 4 != 0 or dq & (dq - 1) != 0)) or \
                 (64 < w.d <= 248 and w.d != 128 and (w.d % 4 != 0 or w.d <= 132)):
             grad_kernel = "grad_flat_kernel"
         if w.d > 32768 or (w.d % 4 != 0 and w.d > 8192):   # no single-pass shape: X is read twice

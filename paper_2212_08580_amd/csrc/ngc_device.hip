@@ -185,17 +185,17 @@ struct stream_shape {
     int nv, r, waves;
     bool ragged, scalar;
     int narrow_dq = 0;  // > 0: rows of narrow_dq elements take a kernel that loads several rows at once
-    bool narrow_any = false;  // narrow_dq is no power of two, or counts single floats (scalar): grad_narrow_any_kernel
+    bool narrow_any = false;  // narrow_dq counts single floats (scalar): grad_narrow_any_kernel
     int flat_dmax = 0;        // > 0: grad_flat_kernel<flat_dmax, flat_lanes> (rows read as one flat stretch of float4)
     int flat_lanes = 1;       // lanes that share a row
 };
 // allow_flat: X holds at least one whole float4
 static stream_shape pick_stream_shape(int64_t d, bool allow_flat) {
     if (d % 4 == 0 && d <= 128 && ((d / 4) & (d / 4 - 1)) == 0) return {1, 8, 1, false, false, (int)(d / 4)};
-    // short rows that are not 16-byte addressable one by one, and those multiples of four that the
-    // kernel below serves less well (20 features and more; 48 with padded rows in LDS, or its reads
-    // would collide sixteen-way): read as one flat stretch, 64 * (64 / dmax) whole rows per trip and wave
-    if (allow_flat && d < 64 && (d % 4 != 0 || d >= 20)) {
+    // every other row of fewer than 64 features, 16-byte addressable or not: read as one flat stretch,
+    // 64 * (64 / dmax) whole rows per trip and wave (48 features with padded rows in LDS, or its
+    // reads would collide sixteen-way)
+    if (allow_flat && d < 64) {
         const int dmax = d < 2 ? 2 : 8 * (int)(d / 8 + 1);  // (4 for d = 3: 6.3 -> 5.8 TB/s)
         return {1, 1, 1, false, true, 0, false, dmax};
     }
@@ -207,9 +207,7 @@ static stream_shape pick_stream_shape(int64_t d, bool allow_flat) {
         const int h = (int)((d + lanes - 1) / lanes);  // 16 .. 31
         return {1, 1, 1, false, true, 0, false, 8 * (h / 8 + 1), lanes};
     }
-    // what is left of the short rows (12 and 48 features in float4; single floats only when X holds
-    // fewer than four floats): two or more whole rows per wave-wide load
-    if (d % 4 == 0 && d <= 64) return {1, 8, 1, false, false, (int)(d / 4), true};
+    // an X of fewer than four floats (at most three features): two or more whole rows per wave-wide load
     if (d % 4 != 0 && d <= 21) return {1, 8, 1, false, true, (int)d, true};
     if (d % 1024 == 0) {
         const int w = (int)(d / 1024);
@@ -347,11 +345,7 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
 #define NGC_NARROW_ANY(VT, RR, LOSS_ID)                                                                            \
     hipLaunchKernelGGL((grad_narrow_any_kernel<VT, RR, LOSS_ID>), grid, dim3(64), 0, ctx->stream, X_dev, y, theta_dev, \
                        ws, rows, (int)chunks, rpc, unit_part, sh.narrow_dq)
-                if (sh.scalar) {  // (sixteen loads per group instead of eight: a third slower)
-                    if (loss == NGC_LOSS_LSQ) NGC_NARROW_ANY(float, 8, NGC_LOSS_LSQ); else NGC_NARROW_ANY(float, 8, NGC_LOSS_LOGISTIC);
-                } else {
-                    if (loss == NGC_LOSS_LSQ) NGC_NARROW_ANY(v4f, 8, NGC_LOSS_LSQ); else NGC_NARROW_ANY(v4f, 8, NGC_LOSS_LOGISTIC);
-                }
+                if (loss == NGC_LOSS_LSQ) NGC_NARROW_ANY(float, 8, NGC_LOSS_LSQ); else NGC_NARROW_ANY(float, 8, NGC_LOSS_LOGISTIC);
 #undef NGC_NARROW_ANY
             } else if (sh.narrow_dq) {
                 dim3 grid((unsigned)(k * chunks));
