@@ -191,13 +191,12 @@ GRAD_SHAPES = [
     # ragged last group, and enough rows for several groups per block
     (8, 3, 1000), (16, 2, 33), (32, 2, 50), (128, 3, 77), (64, 2, 5000), (128, 2, 3001), (4, 1, 70000),
     (64, 64, 3),
-    # short rows whose element count is no power of two, in float4 (d a multiple of 4) or single floats (up to 32
-    # features): two or more whole rows per wave-wide load, idle lanes past the last whole row
+    # short rows whose float4 count is no power of two, or that are no multiple of 4 at all
     (12, 3, 1000), (20, 2, 333), (24, 2, 70), (40, 3, 129), (48, 2, 50), (68, 2, 40), (96, 2, 77), (100, 2, 64),
     (124, 2, 33), (3, 2, 500), (6, 2, 100), (10, 3, 64), (17, 2, 90), (31, 2, 50), (21, 1, 4000),
-    # short rows that are not 16-byte addressable (d < 64, no multiple of 4), read as one flat stretch: every
-    # register-width variant, partitions that start inside a 16-byte granule, X ending inside one (the last row
-    # is then added from single loads), several trips per block, several blocks per partition, a lone row
+    # short rows read as one flat stretch of float4 and sorted into rows in LDS (here d < 64, no multiple of 4):
+    # every register-width variant, partitions that start inside a 16-byte granule, X ending inside one (its
+    # last rows are then added from single loads), several trips per block, several blocks per partition, a lone row
     (7, 3, 1001), (13, 2, 333), (23, 3, 71), (29, 2, 4097), (33, 2, 515), (39, 1, 77), (47, 3, 301), (55, 2, 129),
     (63, 3, 1001), (57, 1, 5), (63, 2, 20000), (3, 1, 70001), (1, 1, 3), (2, 1, 1), (1, 5, 1), (9, 1, 1), (61, 1, 1),
     (1, 17, 54), (1, 7, 1), (1, 2, 3), (1, 3, 513), (2, 3, 171), (3, 5, 1),   # several rows in X's last granule
