@@ -93,3 +93,30 @@ def test_random_configurations(ngc, torch_dev, seed):
                 assert torch.equal(gR[r], p.g) and torch.equal(MR[r][resp], p.C[int(lay[r])][resp]), tag
         finally:
             p.close()
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_short_rows(ngc, torch_dev, seed):
+    """Partition gradients for rows of 1 to 255 features over row counts from one row to several
+    blocks of several trips per partition (the kernels that pack several rows into a wave-wide
+    load, or read a run of rows as one flat stretch): against the oracle, twice for the same bits."""
+    rng = np.random.default_rng(2000 + seed)
+    for it in range(25):
+        d = int(rng.integers(1, 256))
+        n = int(rng.integers(1, 7))
+        rows = int(np.exp(rng.uniform(0.0, np.log(60000.0))))
+        base = wl.C3 if rng.random() < 0.5 else wl.C2
+        w = base.scaled(rows=rows, d=d, n=n, layers=(0,), name="short")
+        tag = (seed, it, d, n, rows, w.loss)
+        X, Y = wl.dataset(w, seed=it, threads=1)
+        th = wl.theta(w, seed=it + 1, scale=None if w.loss == wl.LOSS_LSQ else 2.0 / np.sqrt(d))
+        p = Pipeline(ngc, torch_dev, w, Bs=[np.eye(n)])
+        try:
+            G = p.grads(X, Y, th)
+            G_o = gradients.partial_gradients(w.loss, X, Y, th)
+            assert np.all(np.isfinite(G)), tag
+            for j in range(n):
+                assert rel(G[j], G_o[j]) <= 1e-4, (tag, j, rel(G[j], G_o[j]))
+            assert np.array_equal(G, p.grads(X, Y, th)), tag
+        finally:
+            p.close()
