@@ -761,7 +761,7 @@ def bench_pipeline(args, w, wl, ngc, torch, np, K, W, cpu_leg=True, probe=True, 
         if (w.d < 64 and (w.d % 4 != 0 or dq & (dq - 1) != 0)) or \
                 (64 < w.d <= 248 and w.d != 128 and (w.d % 4 != 0 or w.d <= 132)):
             grad_kernel = "grad_flat_kernel"
-        if w.d > 32768 or (w.d % 4 != 0 and w.d > 8192):   # no single-pass shape: X is read twice
+        if w.d > 32768 or (w.d % 4 != 0 and w.d > 16384):   # no single-pass shape: X is read twice
             grad_kernel = "resid_kernel + xtr_kernel (two passes over X)"
         # algorithmic bytes per launch: X once + labels + theta + G  (4*d bytes per sample)
         grad_bytes = 4.0 * w.m * w.d + 4.0 * w.m + 4.0 * w.d + 4.0 * w.n * w.d

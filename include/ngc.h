@@ -137,7 +137,7 @@ int ngc_set_mlp2_shape(ngc_ctx* ctx, int d_in, int hidden, int classes);
  * X_dev: float [k][rows_per_part][d_in] row-major (d_in = d for the first two
  * losses), 16-byte aligned.  theta_dev: float [d].  G_dev: float [k][d], fully
  * overwritten.  Each row of X is read from HBM exactly once for every
- * d <= 32768 that is a multiple of 4 and every d <= 8192 that is not (fastest
+ * d <= 32768 that is a multiple of 4 and every d <= 16384 that is not (fastest
  * when d is 256, 512, 768 or a multiple of 1024); larger d take a two-pass
  * route that reads X twice.
  * Accumulation is fp32 with a fixed summation order (bit-reproducible).

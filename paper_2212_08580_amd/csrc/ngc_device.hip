@@ -177,7 +177,7 @@ static void launch_stream(ngc_ctx* ctx, int loss, const float* X, const float* y
 }
 
 // Shape of the single-pass kernel for a given d, or waves = 0 if d has none
-// (above 32768, or above 8192 and not a multiple of 4).  A block offers
+// (above 32768, or above 16384 and not a multiple of 4).  A block offers
 // nv*waves*64 slots per row, each a float4, or a float (`scalar`) when d is not
 // a multiple of 4 and rows are therefore not 16-byte aligned; `ragged` when
 // the row has fewer elements than the block has slots.
@@ -228,7 +228,9 @@ static stream_shape pick_stream_shape(int64_t d, bool allow_flat) {
         if (d <= 256) return {4, 16, 1, true, true};  // 249 .. 255 (shorter rows are read as a flat stretch)
         if (d <= 4096) return {8, 8, (int)((d + 511) / 512), true, true};
         if (d <= 8192) return {16, 3, (int)((d + 1023) / 1024), true, true};
-        return {0, 0, 0, false, false};
+        // up to 16384: ten, twelve or sixteen waves, theta in LDS, one row per group (fourteen waves
+        // spill a dozen registers and are slower than sixteen with idle slots: 5.2 against 5.5 TB/s)
+        return {16, 1, d <= 10240 ? 10 : d <= 12288 ? 12 : 16, true, true};
     }
     const int dq = (int)(d / 4);
     if (dq <= 64) return {1, 16, 1, true, false};
@@ -376,6 +378,9 @@ static int grads_impl(ngc_ctx* ctx, int loss, const float* X_dev, const void* y_
                     switch (sh.waves) {
                         NGC_STREAM_SCALAR(16, 3, 5) NGC_STREAM_SCALAR(16, 3, 6)
                         NGC_STREAM_SCALAR(16, 3, 7) NGC_STREAM_SCALAR(16, 3, 8)
+                        case 10: launch_stream<16, 1, 2, 10, true, float, true>(NGC_STREAM_ARGS); break;
+                        case 12: launch_stream<16, 1, 2, 12, true, float, true>(NGC_STREAM_ARGS); break;
+                        case 16: launch_stream<16, 1, 2, 16, true, float, true>(NGC_STREAM_ARGS); break;
                     }
                 }
             } else if (!sh.ragged) {

@@ -184,8 +184,10 @@ GRAD_SHAPES = [
     (4094, 2, 9), (5002, 2, 7), (8190, 2, 5), (30, 2, 70), (123, 2, 41), (130, 3, 35), (191, 2, 18), (250, 2, 9),
     # wide rows, 16388 to 32768 features in float4: theta in LDS, ten to sixteen waves per block
     (20000, 2, 3), (16388, 2, 2), (24580, 2, 4), (28672, 1, 7), (32768, 2, 5), (32768, 3, 1),
+    # rows of 8193 to 16384 features that are no multiple of 4: sixteen waves of sixteen floats per lane and row
+    (8194, 2, 3), (12001, 2, 5), (16383, 3, 4), (9999, 1, 33),
     # no single-pass shape: the two-pass route
-    (8194, 2, 3), (32772, 2, 2), (40000, 2, 3), (20002, 1, 4),
+    (32772, 2, 2), (40000, 2, 3), (20002, 1, 4),
     (1, 3, 40), (2, 2, 17), (5, 2, 33), (4, 2, 64), (16384, 1, 40),
     # narrow rows of 1, 2, 4, .. 32 float4 (several rows per wave-wide load), with and without a
     # ragged last group, and enough rows for several groups per block
